@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of libsdrop's hot path on one MI355X.
+
+A step is one pass of the whole hot path of arxiv 2411.01238 (Section 3.1 eq. (1)-(3),
+Section 3.2) over one batch: draw the block mask, forward GEMM, dX GEMM, dW GEMM.
+The workload is the 4096^3 bf16 square case with 128x128 blocks; the headline value is
+the effective TFLOP/s (flops of kept blocks only: 3 * 2 * nnz * BM * BK * N per step)
+at p = 0.5, and the same is reported for the whole sweep of p together with the
+speed-up over this library's own dense run (p = 0, all blocks kept, same kernels).
+
+Prints one JSON line.  One GPU only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_DENSE_TFLOPS = 2500.0     # MI355X published dense bf16/fp16 MFMA peak
+HEADLINE_P = 0.5
+
+
+def _sets(w, n_sets, torch):
+    """n_sets independent copies of the inputs and outputs, resident in HBM."""
+    from paper_2411_01238_amd.workloads import make_inputs
+    X, W, dY = make_inputs(w)
+    sets = []
+    for _ in range(n_sets):
+        s = {"X": X.cuda(), "W": W.cuda(), "dY": dY.cuda()}
+        s["Y"] = torch.empty((w.M, w.N), dtype=X.dtype, device="cuda")
+        s["dX"] = torch.empty((w.M, w.K), dtype=X.dtype, device="cuda")
+        s["dW"] = torch.empty((w.K, w.N), dtype=X.dtype, device="cuda")
+        sets.append(s)
+    return sets
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="square4096")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (the hot path is a single-GPU kernel path); "
+                 "run with --gpus 1")
+
+    import torch
+    from paper_2411_01238_amd import sdrop
+    from paper_2411_01238_amd.workloads import WORKLOADS
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    sdrop.lib()   # fails loudly if the HIP library is not built
+    w = WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # three buffer sets (576 MiB at 4096^3) rotate so that a step's operands are not left in
+    # the 256 MiB Infinity Cache by the step before; a single-set (warm) figure is given too
+    sets = _sets(w, 3, torch)
+    mask = sdrop.Mask(w.M, w.K, w.BM, w.BK, HEADLINE_P)
+
+    def step(s, p, seed, events=None):
+        if events is not None:
+            events[0].record()
+        sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, seed, 0, out=mask)
+        if events is not None:
+            events[1].record()
+        sdrop.sdrop_fwd(s["X"], s["W"], mask, out=s["Y"])
+        if events is not None:
+            events[2].record()
+        sdrop.sdrop_bwd_dx(s["dY"], s["W"], mask, out=s["dX"])
+        if events is not None:
+            events[3].record()
+        sdrop.sdrop_bwd_dw(s["X"], s["dY"], mask, out=s["dW"])
+        if events is not None:
+            events[4].record()
+
+    def nnz_of(p, seed):
+        sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, seed, 0, out=mask)
+        torch.cuda.synchronize()
+        return mask.nnz()
+
+    def timed(p, steps, warmup, n_sets, seed=w.mask_seed):
+        for i in range(warmup):
+            step(sets[i % n_sets], p, seed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(sets[i % n_sets], p, seed)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3     # ms per step
+
+    def per_kernel(p, steps, n_sets, seed=w.mask_seed):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+        for i in range(steps):
+            step(sets[i % n_sets], p, seed, evs[i])
+        torch.cuda.synchronize()
+        names = ("mask", "fwd", "dx", "dw")
+        return {n: sum(e[k].elapsed_time(e[k + 1]) for e in evs) / steps for k, n in enumerate(names)}
+
+    flops_per_block = 3 * 2.0 * w.BM * w.BK * w.N
+
+    # ---- headline: p = 0.5, rotating buffer sets ----
+    nnz = nnz_of(HEADLINE_P, w.mask_seed)
+    ms = timed(HEADLINE_P, args.steps, args.warmup, 3)
+    value = nnz * flops_per_block / (ms * 1e-3) / 1e12
+    ms_warm = timed(HEADLINE_P, args.steps, args.warmup, 1)
+    kern = per_kernel(HEADLINE_P, args.steps, 3)
+
+    # ---- sweep over p (fewer steps each), speed-up against the library's own dense run ----
+    sweep = {}
+    if not args.no_sweep:
+        k_sweep = max(10, args.steps // 2)
+        ms_dense = timed(0.0, k_sweep, 3, 3)
+        for p in w.ps:
+            n_p = nnz_of(p, w.mask_seed)
+            ms_p = ms if p == HEADLINE_P else (ms_dense if p == 0.0 else timed(p, k_sweep, 3, 3))
+            sweep["%.1f" % p] = {
+                "ms_per_step": round(ms_p, 5), "kept_fraction": round(n_p / (w.MB * w.KB), 5),
+                "eff_tflops": round(n_p * flops_per_block / (ms_p * 1e-3) / 1e12, 3),
+                "speedup_vs_own_dense": round(ms_dense / ms_p, 4),
+                "ideal_speedup": round(w.MB * w.KB / max(n_p, 1), 4),
+            }
+
+    # ---- roofline of the dominant kernel (largest average duration among the three GEMMs) ----
+    dom = max(("fwd", "dx", "dw"), key=lambda n: kern[n])
+    flops_launch = 2.0 * nnz * w.BM * w.BK * w.N       # algorithmic flops of one GEMM launch
+    achieved = flops_launch / (kern[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "sdrop_" + {"fwd": "fwd", "dx": "bwd_dx", "dw": "bwd_dw"}[dom],
+                "achieved": round(achieved, 3), "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_DENSE_TFLOPS, 5), "traffic": None,
+                "avg_launch_ms": {k: round(v, 5) for k, v in kern.items()}}
+
+    out = {
+        "metric": "effective TFLOP/s fwd+bwd (kept blocks) & speedup vs dense GEMM at p in {0.1,0.3,0.5}",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: M=K=N=%d %s, block %dx%d, p=%.1f (mask + fwd + dX + dW per step), "
+                               "%s outputs, 3 rotating buffer sets" % (w.name, w.M, w.dtype, w.BM, w.BK, HEADLINE_P, w.dtype),
+                   "kept_blocks": nnz, "blocks": w.MB * w.KB},
+        "frac_of_bf16_peak": round(value / PEAK_BF16_DENSE_TFLOPS, 5),
+        "ms_per_step_warm_single_set": round(ms_warm, 5),
+        "sweep": sweep,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, HEADLINE_P)
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, p, rows=None):
+    """The float64 oracle, as it stands, on the first `rows` rows of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import sdrop_oracle as orc
+    from paper_2411_01238_amd.workloads import make_inputs
+    rows = w.M if rows is None else rows
+    X, W, dY = make_inputs(w, M=rows)
+    keep = orc.mask(rows // w.BM, w.KB, p, w.mask_seed, 0)
+    Xd, Wd, dYd = (t.to(torch.float64).numpy() for t in (X, W, dY))
+    t0 = time.perf_counter()
+    orc.fwd(Xd, Wd, keep, w.BM, w.BK, p)
+    orc.bwd_dx(dYd, Wd, keep, w.BM, w.BK, p)
+    orc.bwd_dw(Xd, dYd, keep, w.BM, w.BK, p)
+    dt = time.perf_counter() - t0
+    flops = 3 * 2.0 * int(keep.sum()) * w.BM * w.BK * w.N
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": "first %d rows of X and dY (M=%d of %d), full K and N, same mask rule, p=%.1f; "
+                      "float64 fwd + dX + dW once, %.1f s" % (rows, rows, w.M, p, dt)}
+
+
+if __name__ == "__main__":
+    main()

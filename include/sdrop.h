@@ -1,0 +1,173 @@
+/*
+ * sdrop.h -- C ABI of libsdrop: SparseDrop's block-structured dropout fused
+ * into the following matrix multiply, as hand-written HIP kernels for gfx950.
+ *
+ * The operations are those of arxiv 2411.01238, Section 3.1 eq. (1)-(3), with
+ * the block mask of Section 3.2:
+ *
+ *     m'  : one Bernoulli(1-p) keep flag per BM x BK block of X   (Section 3.2)
+ *     Y   = s (X . m') W                                          (eq. 1)
+ *     dX  = s (dY W^T) . m'                                       (eq. 2)
+ *     dW  = s (X . m')^T dY                                       (eq. 3)
+ *     s   = 1/(1-p)   (s = 0 when p = 1: everything is dropped)
+ *
+ * with X[M,K], W[K,N], Y[M,N], dY[M,N], dX[M,K], dW[K,N], no bias.
+ *
+ * Conventions shared by every entry point
+ *   - All matrix and mask pointers are DEVICE pointers (HBM).  Matrices are dense
+ *     row-major and contiguous (leading dimension = number of columns) and
+ *     16-byte aligned.  The caller owns every buffer and the stream; the
+ *     library allocates nothing, frees nothing and keeps no pointer after a
+ *     call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it and return; no call synchronises with the
+ *     host or copies to the host.
+ *   - Block sizes must divide the shape (Section 2.2, footnote): BM | M and
+ *     BK | K, with BM, BK in {64, 128}.  N must be a multiple of 8.
+ *   - Inputs are fp16 or bf16 (SDROP_F16 / SDROP_BF16); products are
+ *     accumulated in fp32 on the matrix cores; the scale s is applied to the
+ *     fp32 accumulator; the result is rounded to nearest-even once, to
+ *     `out_dtype` (the input type, or SDROP_F32 for unrounded fp32 output).
+ *   - Outputs are completely overwritten.  Dropped blocks of dX are written as
+ *     +0 by the library (Section 3.2 assumes a zero-initialised output; here no
+ *     such precondition exists).  Dropped blocks of X are never read, so their
+ *     contents (NaN included) cannot reach Y or dW.
+ *   - Return value: SDROP_OK or an error code.  Argument errors are detected on
+ *     the host before anything is enqueued and leave every buffer untouched.
+ */
+#ifndef SDROP_H
+#define SDROP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SDROP_OK = 0,
+    SDROP_EINVAL = 1,      /* null pointer, p outside [0,1] or NaN, bad enum value */
+    SDROP_ESHAPE = 2,      /* non-positive size, BM does not divide M, BK does not divide K,
+                              unsupported block size, N not a multiple of 8 */
+    SDROP_EDTYPE = 3,      /* unsupported dtype / out_dtype combination */
+    SDROP_EALIGN = 4,      /* a pointer is not 16-byte aligned */
+    SDROP_EWORKSPACE = 5,  /* mask buffer or workspace smaller than required */
+    SDROP_EHIP = 6         /* the HIP runtime refused a launch; see sdrop_last_hip_error() */
+};
+
+enum { SDROP_F16 = 0, SDROP_BF16 = 1, SDROP_F32 = 2 /* out_dtype only */ };
+
+enum { SDROP_OP_FWD = 0, SDROP_OP_BWD_DX = 1, SDROP_OP_BWD_DW = 2 };
+
+/* Text for an error code (static storage). */
+const char *sdrop_strerror(int code);
+
+/* The hipError_t (as int) of the last SDROP_EHIP on the calling thread, else 0. */
+int sdrop_last_hip_error(void);
+
+/*
+ * Layout of a mask object in device memory.  A mask object is one caller-owned
+ * buffer of `total_bytes`; all offsets are in bytes from its start.  With
+ * MB = M/BM, KB = K/BK and nnz = number of kept blocks:
+ *
+ *   header   at 0 (256 bytes): int64 M, K; int32 BM, BK, MB, KB, words_per_row, nnz; ...
+ *            (nnz is the int32 at byte offset SDROP_MASK_NNZ_OFFSET)
+ *   bits     uint64[MB][words_per_row]: block (i,j) is bit j%64 of word j/64 of
+ *            row i, 1 = kept, unused high bits zero (the 64-bit packing of Section 3.4)
+ *   row_ptr  int32[MB+1], col_idx int32[nnz (room for MB*KB)]: kept block columns of
+ *            each block row, ascending (what eq. 1 walks)
+ *   blk_row  int32[nnz (room for MB*KB)]: block row of the t-th kept block in the same
+ *            order as col_idx, i.e. (blk_row[t], col_idx[t]) lists the kept
+ *            blocks row-major (what eq. 2 computes)
+ *   col_ptr  int32[KB+1], row_idx int32[nnz (room for MB*KB)]: kept block rows of each
+ *            block column, ascending (what eq. 3 walks)
+ *   row_order int32[MB], col_order int32[KB]: block rows / columns sorted by
+ *            descending kept count (ties in unspecified order); used to
+ *            schedule heavy tiles first
+ */
+typedef struct sdrop_mask_layout {
+    size_t total_bytes;
+    size_t off_bits, off_row_ptr, off_col_idx, off_blk_row;
+    size_t off_col_ptr, off_row_idx, off_row_order, off_col_order;
+    int64_t MB, KB, words_per_row;
+} sdrop_mask_layout_t;
+
+#define SDROP_MASK_NNZ_OFFSET 36
+
+/* Fills *out for a mask over X[M,K] in BM x BK blocks.  SDROP_ESHAPE on a bad shape. */
+int sdrop_mask_layout(int64_t M, int64_t K, int BM, int BK, sdrop_mask_layout_t *out);
+
+/* total_bytes of the layout above, or 0 on a bad shape. */
+size_t sdrop_mask_bytes(int64_t M, int64_t K, int BM, int BK);
+
+/*
+ * Draws the block mask m' of Section 3.2 on the device and builds every index
+ * list above from it in the same launch.
+ *
+ * The paper does not fix a generator.  This library uses Philox4x32-10 with
+ * counter (b lo32, b hi32, rng_stream lo32, rng_stream hi32), where b = i*KB + j
+ * is the block number, key (seed lo32, seed hi32), and keeps block (i,j) iff
+ * output word 0 >= floor(p * 2^32).  The mask is a pure function of
+ * (seed, rng_stream, MB, KB, p): the backward calls of a step reuse the object
+ * written by the forward's call, or regenerate it.
+ *
+ *   mask        device buffer of at least sdrop_mask_bytes(...) bytes, 16-byte aligned
+ *   p           dropout probability in [0,1]
+ *   seed, rng_stream   generator key and stream (e.g. layer or step number)
+ */
+int sdrop_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
+               double p, uint64_t seed, uint64_t rng_stream, void *stream);
+
+/*
+ * Same object, but the keep bits are given instead of drawn: `bits` is a device
+ * array uint64[MB][words_per_row] in the packing described above (unused high
+ * bits are ignored).  For callers that bring their own block mask, and for
+ * tests that need a particular pattern (for example all blocks dropped).
+ */
+int sdrop_mask_from_bits(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
+                         const uint64_t *bits, void *stream);
+
+/* Bytes of device workspace an operation needs for these arguments (may be 0). */
+size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, int BK,
+                             int dtype, int out_dtype);
+
+/*
+ * eq. (1): Y[M,N] = s (X . m') W.  For each block row only the kept K-blocks
+ * are walked; dropped blocks of X and the matching row blocks of W are not read
+ * (Section 3.2, structured dsd_matmul).
+ *
+ *   X[M,K], W[K,N]  inputs of type `dtype`;  Y[M,N] output of type `out_dtype`
+ *   mask            object written by sdrop_mask / sdrop_mask_from_bits with the same
+ *                   (M, K, BM, BK); a kernel that finds a different header writes nothing
+ *   p               the dropout probability the scale s is derived from
+ *   ws, ws_bytes    device workspace of at least sdrop_workspace_bytes(SDROP_OP_FWD, ...)
+ *                   bytes (ws may be NULL when that is 0)
+ */
+int sdrop_fwd(const void *X, const void *W, const void *mask, void *Y,
+              int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+              int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * eq. (2): dX[M,K] = s (dY W^T) . m'.  Only kept output blocks are computed
+ * (Section 3.2, sdd_matmul); dropped blocks are filled with +0.
+ *   dY[M,N], W[K,N] inputs;  dX[M,K] output.  Other arguments as for sdrop_fwd.
+ */
+int sdrop_bwd_dx(const void *dY, const void *W, const void *mask, void *dX,
+                 int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                 int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * eq. (3): dW[K,N] = s (X . m')^T dY.  For each block column of X only the kept
+ * row blocks are walked (Section 3.3: a GEMM of size (K,N,M) whose reduction
+ * runs over M in steps of the mask's row block).
+ *   X[M,K], dY[M,N] inputs;  dW[K,N] output.  Other arguments as for sdrop_fwd.
+ */
+int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
+                 int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                 int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDROP_H */

@@ -1,0 +1,61 @@
+// Internal declarations shared by the translation units of libsdrop.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "sdrop.h"
+
+namespace sdrop {
+
+// First 256 bytes of a mask object (device memory).  nnz sits at byte 36.
+struct MaskHeader {
+    int64_t M, K;            // 0, 8
+    int32_t BM, BK;          // 16, 20
+    int32_t MB, KB;          // 24, 28
+    int32_t words_per_row;   // 32
+    int32_t nnz;             // 36
+    uint32_t magic;          // 40
+    int32_t max_row_cnt;     // 44
+    int32_t max_col_cnt;     // 48
+    int32_t pad_[51];
+};
+static_assert(sizeof(MaskHeader) == 256, "mask header is 256 bytes");
+static_assert(offsetof(MaskHeader, nnz) == SDROP_MASK_NNZ_OFFSET, "nnz offset is part of the ABI");
+
+constexpr uint32_t kMaskMagic = 0x5344524Fu;  // "SDRO"
+
+// Device-side view of a mask object.
+struct MaskView {
+    const MaskHeader *hdr;
+    const uint64_t *bits;
+    const int32_t *row_ptr, *col_idx, *blk_row;
+    const int32_t *col_ptr, *row_idx, *row_order, *col_order;
+};
+
+inline MaskView make_view(const void *mask, const sdrop_mask_layout_t &L)
+{
+    const char *b = static_cast<const char *>(mask);
+    MaskView v;
+    v.hdr = reinterpret_cast<const MaskHeader *>(b);
+    v.bits = reinterpret_cast<const uint64_t *>(b + L.off_bits);
+    v.row_ptr = reinterpret_cast<const int32_t *>(b + L.off_row_ptr);
+    v.col_idx = reinterpret_cast<const int32_t *>(b + L.off_col_idx);
+    v.blk_row = reinterpret_cast<const int32_t *>(b + L.off_blk_row);
+    v.col_ptr = reinterpret_cast<const int32_t *>(b + L.off_col_ptr);
+    v.row_idx = reinterpret_cast<const int32_t *>(b + L.off_row_idx);
+    v.row_order = reinterpret_cast<const int32_t *>(b + L.off_row_order);
+    v.col_order = reinterpret_cast<const int32_t *>(b + L.off_col_order);
+    return v;
+}
+
+// Host-side argument checks shared by the GEMM entry points.
+int check_gemm_args(const void *a, const void *b, const void *mask, void *out,
+                    int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                    int dtype, int out_dtype);
+
+// Records a HIP failure for sdrop_last_hip_error() and returns SDROP_EHIP, or SDROP_OK.
+int hip_status(hipError_t e);
+
+inline bool block_size_ok(int b) { return b == 64 || b == 128; }
+
+}  // namespace sdrop

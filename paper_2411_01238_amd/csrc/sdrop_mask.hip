@@ -1,0 +1,307 @@
+// Block-mask draw and index-list compaction for SparseDrop (arxiv 2411.01238,
+// Sections 3.2 and 3.4), plus the small host-side pieces of the C ABI that are
+// not GEMMs (layout, error text).
+//
+// One launch of one 1024-thread workgroup does everything: the mask of the
+// largest workload here has 16384 blocks, so the job is latency, not
+// throughput, and a single workgroup needs no cross-workgroup scan.  A wavefront
+// owns a block row (lane <-> block column): its 64-lane ballot IS the packed
+// 64-bit mask word of Section 3.4, and popcount(ballot & lanes-below) is the
+// position of a kept block inside its row's list.  Row totals are turned into
+// row_ptr by a workgroup prefix scan.  The column lists (what eq. 3 walks) are
+// built the same way with lane <-> block row, reading the bits just written.
+#include "sdrop_internal.h"
+#include <math.h>
+
+namespace sdrop {
+
+static thread_local int g_last_hip_error = 0;
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return SDROP_OK;
+    g_last_hip_error = static_cast<int>(e);
+    return SDROP_EHIP;
+}
+
+namespace {
+
+constexpr int kMaskThreads = 1024;
+constexpr int kMaskWaves = kMaskThreads / 64;
+constexpr int kMaxBins = 4096;   // histogram bins of the descending-count sort
+
+struct MaskParams {
+    MaskHeader *hdr;
+    uint64_t *bits;
+    int32_t *row_ptr, *col_idx, *blk_row, *col_ptr, *row_idx, *row_order, *col_order;
+    const uint64_t *given_bits;      // non-null: take the bits from here instead of drawing
+    int64_t M, K;
+    int32_t BM, BK, MB, KB, wpr;
+    uint32_t key0, key1, ctr2, ctr3; // seed and rng_stream split in 32-bit words
+    uint64_t threshold;              // floor(p * 2^32)
+};
+
+// Philox4x32-10 (Salmon et al., SC'11); returns output word 0.
+__device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t MUL0 = 0xD2511F53u, MUL1 = 0xCD9E8D57u;
+    constexpr uint32_t BUMP0 = 0x9E3779B9u, BUMP1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(MUL0, c0), lo0 = MUL0 * c0;
+        const uint32_t hi1 = __umulhi(MUL1, c2), lo1 = MUL1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += BUMP0; k1 += BUMP1;   // the bump after the last round is unused
+    }
+    return c0;
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+__device__ __forceinline__ uint64_t lanes_below()
+{
+    return (uint64_t(1) << lane_id()) - 1;
+}
+
+// In-place inclusive prefix sum of a[0..n) by the whole workgroup.  `a` may be in
+// LDS or in global memory written earlier by this same workgroup.
+__device__ void block_inclusive_scan(int32_t *a, int n, int32_t *wave_tot /* LDS[kMaskWaves+1] */)
+{
+    int carry = 0;
+    for (int base = 0; base < n; base += kMaskThreads) {
+        const int idx = base + threadIdx.x;
+        int v = (idx < n) ? a[idx] : 0;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(v, d, 64);
+            if (lane_id() >= d) v += up;
+        }
+        if (lane_id() == 63) wave_tot[wave_id()] = v;
+        __syncthreads();
+        int before = 0, total = 0;
+        for (int w = 0; w < kMaskWaves; ++w) {
+            const int t = wave_tot[w];
+            if (w < wave_id()) before += t;
+            total += t;
+        }
+        if (idx < n) a[idx] = v + before + carry;
+        carry += total;
+        __syncthreads();
+    }
+}
+
+// order[] := indices 0..n-1 sorted by descending cnt(i) = ptr[i+1]-ptr[i] (counting
+// sort; ties land in unspecified order).  max_cnt is the upper bound of cnt.
+__device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t *order,
+                                 int32_t *bins /* LDS[kMaxBins+1] */, int32_t *wave_tot)
+{
+    const int nb = (max_cnt < kMaxBins ? max_cnt : kMaxBins) + 1;
+    for (int b = threadIdx.x; b < nb; b += kMaskThreads) bins[b] = 0;
+    __syncthreads();
+    auto bin_of = [&](int cnt) {
+        const int b = (max_cnt <= kMaxBins) ? cnt : int((int64_t)cnt * kMaxBins / max_cnt);
+        return nb - 1 - b;             // bin 0 holds the largest counts
+    };
+    for (int i = threadIdx.x; i < n; i += kMaskThreads) atomicAdd(&bins[bin_of(ptr[i + 1] - ptr[i])], 1);
+    __syncthreads();
+    block_inclusive_scan(bins, nb, wave_tot);
+    // bins[b] is now the END of bin b; claim slots from the end backwards
+    for (int i = threadIdx.x; i < n; i += kMaskThreads) {
+        const int pos = atomicSub(&bins[bin_of(ptr[i + 1] - ptr[i])], 1) - 1;
+        order[pos] = i;
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
+{
+    __shared__ int32_t wave_tot[kMaskWaves + 1];
+    __shared__ int32_t bins[kMaxBins + 1];
+    const int lane = lane_id(), wave = wave_id();
+
+    // -- rows: draw (or fetch) the keep bits, store packed words, count per row --
+    for (int i = wave; i < P.MB; i += kMaskWaves) {
+        int cnt = 0;
+        for (int w = 0; w < P.wpr; ++w) {
+            const int j = w * 64 + lane;
+            bool keep = false;
+            if (j < P.KB) {
+                if (P.given_bits) {
+                    keep = (P.given_bits[(int64_t)i * P.wpr + w] >> lane) & 1;
+                } else {
+                    const uint64_t b = (uint64_t)i * (uint64_t)P.KB + (uint64_t)j;
+                    const uint32_t r = philox_word0((uint32_t)b, (uint32_t)(b >> 32), P.ctr2, P.ctr3,
+                                                    P.key0, P.key1);
+                    keep = (uint64_t)r >= P.threshold;
+                }
+            }
+            const uint64_t word = __ballot(keep);
+            if (lane == 0) P.bits[(int64_t)i * P.wpr + w] = word;
+            cnt += __popcll(word);
+        }
+        if (lane == 0) P.row_ptr[i + 1] = cnt;
+    }
+    if (threadIdx.x == 0) P.row_ptr[0] = 0;
+    __syncthreads();
+    block_inclusive_scan(P.row_ptr + 1, P.MB, wave_tot);
+
+    // -- rows again: scatter kept columns to their slots --
+    for (int i = wave; i < P.MB; i += kMaskWaves) {
+        int pos = P.row_ptr[i];
+        for (int w = 0; w < P.wpr; ++w) {
+            const uint64_t word = P.bits[(int64_t)i * P.wpr + w];
+            if ((word >> lane) & 1) {
+                const int at = pos + __popcll(word & lanes_below());
+                P.col_idx[at] = w * 64 + lane;
+                P.blk_row[at] = i;
+            }
+            pos += __popcll(word);
+        }
+    }
+
+    // -- columns: lane <-> block row --
+    for (int j = wave; j < P.KB; j += kMaskWaves) {
+        int cnt = 0;
+        for (int i0 = 0; i0 < P.MB; i0 += 64) {
+            const int i = i0 + lane;
+            const bool keep = (i < P.MB) && ((P.bits[(int64_t)i * P.wpr + (j >> 6)] >> (j & 63)) & 1);
+            cnt += __popcll(__ballot(keep));
+        }
+        if (lane == 0) P.col_ptr[j + 1] = cnt;
+    }
+    if (threadIdx.x == 0) P.col_ptr[0] = 0;
+    __syncthreads();
+    block_inclusive_scan(P.col_ptr + 1, P.KB, wave_tot);
+    for (int j = wave; j < P.KB; j += kMaskWaves) {
+        int pos = P.col_ptr[j];
+        for (int i0 = 0; i0 < P.MB; i0 += 64) {
+            const int i = i0 + lane;
+            const bool keep = (i < P.MB) && ((P.bits[(int64_t)i * P.wpr + (j >> 6)] >> (j & 63)) & 1);
+            const uint64_t word = __ballot(keep);
+            if (keep) P.row_idx[pos + __popcll(word & lanes_below())] = i;
+            pos += __popcll(word);
+        }
+    }
+
+    // -- schedules: heavy rows / columns first --
+    descending_order(P.row_ptr, P.MB, P.KB, P.row_order, bins, wave_tot);
+    descending_order(P.col_ptr, P.KB, P.MB, P.col_order, bins, wave_tot);
+
+    if (threadIdx.x == 0) {
+        MaskHeader h = {};
+        h.M = P.M; h.K = P.K; h.BM = P.BM; h.BK = P.BK; h.MB = P.MB; h.KB = P.KB;
+        h.words_per_row = P.wpr;
+        h.nnz = P.row_ptr[P.MB];
+        h.magic = kMaskMagic;
+        h.max_row_cnt = P.MB > 0 ? P.row_ptr[P.row_order[0] + 1] - P.row_ptr[P.row_order[0]] : 0;
+        h.max_col_cnt = P.KB > 0 ? P.col_ptr[P.col_order[0] + 1] - P.col_ptr[P.col_order[0]] : 0;
+        *P.hdr = h;
+    }
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
+                double p, uint64_t seed, uint64_t rng_stream, const uint64_t *given_bits,
+                void *stream)
+{
+    if (!mask) return SDROP_EINVAL;
+    if (!(p >= 0.0 && p <= 1.0)) return SDROP_EINVAL;
+    sdrop_mask_layout_t L;
+    const int rc = sdrop_mask_layout(M, K, BM, BK, &L);
+    if (rc != SDROP_OK) return rc;
+    if (reinterpret_cast<uintptr_t>(mask) % 16) return SDROP_EALIGN;
+    if (given_bits && reinterpret_cast<uintptr_t>(given_bits) % 8) return SDROP_EALIGN;
+    if (mask_bytes < L.total_bytes) return SDROP_EWORKSPACE;
+
+    char *b = static_cast<char *>(mask);
+    MaskParams P;
+    P.hdr = reinterpret_cast<MaskHeader *>(b);
+    P.bits = reinterpret_cast<uint64_t *>(b + L.off_bits);
+    P.row_ptr = reinterpret_cast<int32_t *>(b + L.off_row_ptr);
+    P.col_idx = reinterpret_cast<int32_t *>(b + L.off_col_idx);
+    P.blk_row = reinterpret_cast<int32_t *>(b + L.off_blk_row);
+    P.col_ptr = reinterpret_cast<int32_t *>(b + L.off_col_ptr);
+    P.row_idx = reinterpret_cast<int32_t *>(b + L.off_row_idx);
+    P.row_order = reinterpret_cast<int32_t *>(b + L.off_row_order);
+    P.col_order = reinterpret_cast<int32_t *>(b + L.off_col_order);
+    P.given_bits = given_bits;
+    P.M = M; P.K = K; P.BM = BM; P.BK = BK;
+    P.MB = static_cast<int32_t>(L.MB); P.KB = static_cast<int32_t>(L.KB);
+    P.wpr = static_cast<int32_t>(L.words_per_row);
+    P.key0 = static_cast<uint32_t>(seed); P.key1 = static_cast<uint32_t>(seed >> 32);
+    P.ctr2 = static_cast<uint32_t>(rng_stream); P.ctr3 = static_cast<uint32_t>(rng_stream >> 32);
+    P.threshold = static_cast<uint64_t>(floor(p * 4294967296.0));
+    hipLaunchKernelGGL(mask_kernel, dim3(1), dim3(kMaskThreads), 0, static_cast<hipStream_t>(stream), P);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+}  // namespace sdrop
+
+extern "C" {
+
+const char *sdrop_strerror(int code)
+{
+    switch (code) {
+    case SDROP_OK: return "ok";
+    case SDROP_EINVAL: return "invalid argument (null pointer, p outside [0,1], bad enum)";
+    case SDROP_ESHAPE: return "bad shape (sizes must be positive, BM|M, BK|K, BM,BK in {64,128}, 8|N)";
+    case SDROP_EDTYPE: return "unsupported dtype / out_dtype";
+    case SDROP_EALIGN: return "pointer not 16-byte aligned";
+    case SDROP_EWORKSPACE: return "mask buffer or workspace too small";
+    case SDROP_EHIP: return "HIP runtime error (see sdrop_last_hip_error)";
+    default: return "unknown sdrop error code";
+    }
+}
+
+int sdrop_last_hip_error(void) { return sdrop::g_last_hip_error; }
+
+int sdrop_mask_layout(int64_t M, int64_t K, int BM, int BK, sdrop_mask_layout_t *out)
+{
+    if (!out) return SDROP_EINVAL;
+    if (M <= 0 || K <= 0 || !sdrop::block_size_ok(BM) || !sdrop::block_size_ok(BK)) return SDROP_ESHAPE;
+    if (M % BM || K % BK) return SDROP_ESHAPE;
+    const int64_t MB = M / BM, KB = K / BK;
+    // the index lists are int32 and one workgroup builds them
+    if (MB > (1 << 20) || KB > (1 << 20) || MB * KB > (int64_t(1) << 26)) return SDROP_ESHAPE;
+    const int64_t wpr = (KB + 63) / 64;
+    const size_t nblk = static_cast<size_t>(MB * KB);
+    size_t off = sizeof(sdrop::MaskHeader);
+    out->off_bits = off;      off = sdrop::align_up(off + sizeof(uint64_t) * MB * wpr, 256);
+    out->off_row_ptr = off;   off = sdrop::align_up(off + 4 * (MB + 1), 256);
+    out->off_col_idx = off;   off = sdrop::align_up(off + 4 * nblk, 256);
+    out->off_blk_row = off;   off = sdrop::align_up(off + 4 * nblk, 256);
+    out->off_col_ptr = off;   off = sdrop::align_up(off + 4 * (KB + 1), 256);
+    out->off_row_idx = off;   off = sdrop::align_up(off + 4 * nblk, 256);
+    out->off_row_order = off; off = sdrop::align_up(off + 4 * MB, 256);
+    out->off_col_order = off; off = sdrop::align_up(off + 4 * KB, 256);
+    out->total_bytes = off;
+    out->MB = MB; out->KB = KB; out->words_per_row = wpr;
+    return SDROP_OK;
+}
+
+size_t sdrop_mask_bytes(int64_t M, int64_t K, int BM, int BK)
+{
+    sdrop_mask_layout_t L;
+    return sdrop_mask_layout(M, K, BM, BK, &L) == SDROP_OK ? L.total_bytes : 0;
+}
+
+int sdrop_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
+               double p, uint64_t seed, uint64_t rng_stream, void *stream)
+{
+    return sdrop::launch_mask(mask, mask_bytes, M, K, BM, BK, p, seed, rng_stream, nullptr, stream);
+}
+
+int sdrop_mask_from_bits(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
+                         const uint64_t *bits, void *stream)
+{
+    if (!bits) return SDROP_EINVAL;
+    return sdrop::launch_mask(mask, mask_bytes, M, K, BM, BK, 0.0, 0, 0, bits, stream);
+}
+
+}  // extern "C"

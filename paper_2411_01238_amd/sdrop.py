@@ -1,0 +1,219 @@
+"""Thin ctypes binding over libsdrop.so (the C ABI declared in include/sdrop.h).
+
+Argument marshalling only: every function below passes device pointers of torch
+tensors, sizes and the current HIP stream straight to the C entry point of the
+same name.  There is no CPU fallback: if the library is not built, or a call is
+made without a GPU tensor, it raises.
+
+The operations are those of arxiv 2411.01238, Section 3.1 eq. (1)-(3) with the
+block mask of Section 3.2; see the header for the full contract.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsdrop.so")
+
+OK, EINVAL, ESHAPE, EDTYPE, EALIGN, EWORKSPACE, EHIP = range(7)
+F16, BF16, F32 = 0, 1, 2
+OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
+MASK_NNZ_OFFSET = 36
+
+EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_mask_layout", "sdrop_mask_bytes",
+           "sdrop_mask", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
+           "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw")
+
+_DTYPES = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
+
+
+class SdropError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__("%s failed: %s (code %d)" % (what, strerror(code), code))
+
+
+class MaskLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in
+                ("total_bytes", "off_bits", "off_row_ptr", "off_col_idx", "off_blk_row",
+                 "off_col_ptr", "off_row_idx", "off_row_order", "off_col_order")] + \
+               [(n, ctypes.c_int64) for n in ("MB", "KB", "words_per_row")]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libsdrop.so; raises if it has not been built (python -m paper_2411_01238_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libsdrop.so is not built: run `python -m paper_2411_01238_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, u64, dbl, vp, ci, sz = (ctypes.c_int64, ctypes.c_uint64, ctypes.c_double,
+                                     ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t)
+        L.sdrop_strerror.argtypes = [ci]
+        L.sdrop_strerror.restype = ctypes.c_char_p
+        L.sdrop_last_hip_error.argtypes = []
+        L.sdrop_last_hip_error.restype = ci
+        L.sdrop_mask_layout.argtypes = [i64, i64, ci, ci, ctypes.POINTER(MaskLayout)]
+        L.sdrop_mask_layout.restype = ci
+        L.sdrop_mask_bytes.argtypes = [i64, i64, ci, ci]
+        L.sdrop_mask_bytes.restype = sz
+        L.sdrop_mask.argtypes = [vp, sz, i64, i64, ci, ci, dbl, u64, u64, vp]
+        L.sdrop_mask.restype = ci
+        L.sdrop_mask_from_bits.argtypes = [vp, sz, i64, i64, ci, ci, vp, vp]
+        L.sdrop_mask_from_bits.restype = ci
+        L.sdrop_workspace_bytes.argtypes = [ci, i64, i64, i64, ci, ci, ci, ci]
+        L.sdrop_workspace_bytes.restype = sz
+        for name in ("sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw"):
+            f = getattr(L, name)
+            f.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
+            f.restype = ci
+        _lib = L
+    return _lib
+
+
+def strerror(code):
+    return lib().sdrop_strerror(int(code)).decode()
+
+
+def _check(code, what):
+    if code != OK:
+        raise SdropError(code, what)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous GPU tensor" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def mask_layout(M, K, BM, BK):
+    out = MaskLayout()
+    _check(lib().sdrop_mask_layout(M, K, BM, BK, ctypes.byref(out)), "sdrop_mask_layout")
+    return out
+
+
+def mask_bytes(M, K, BM, BK):
+    return int(lib().sdrop_mask_bytes(M, K, BM, BK))
+
+
+class Mask:
+    """A mask object in device memory (a caller-owned uint8 tensor) plus its shape."""
+
+    def __init__(self, M, K, BM, BK, p, device="cuda"):
+        self.M, self.K, self.BM, self.BK, self.p = M, K, BM, BK, float(p)
+        self.layout = mask_layout(M, K, BM, BK)
+        self.buf = torch.empty(self.layout.total_bytes, dtype=torch.uint8, device=device)
+
+    @property
+    def MB(self):
+        return int(self.layout.MB)
+
+    @property
+    def KB(self):
+        return int(self.layout.KB)
+
+    # views for tests and diagnostics (each .cpu() call synchronises)
+    def _i32(self, off, n):
+        return self.buf[off:off + 4 * n].view(torch.int32)
+
+    def nnz(self):
+        return int(self.buf[MASK_NNZ_OFFSET:MASK_NNZ_OFFSET + 4].view(torch.int32).item())
+
+    def bits(self):
+        L = self.layout
+        n = self.MB * int(L.words_per_row)
+        return self.buf[L.off_bits:L.off_bits + 8 * n].view(torch.int64).reshape(self.MB, -1)
+
+    def lists(self):
+        L = self.layout
+        nnz = self.nnz()
+        return {
+            "row_ptr": self._i32(L.off_row_ptr, self.MB + 1),
+            "col_idx": self._i32(L.off_col_idx, nnz),
+            "blk_row": self._i32(L.off_blk_row, nnz),
+            "col_ptr": self._i32(L.off_col_ptr, self.KB + 1),
+            "row_idx": self._i32(L.off_row_idx, nnz),
+            "row_order": self._i32(L.off_row_order, self.MB),
+            "col_order": self._i32(L.off_col_order, self.KB),
+        }
+
+
+def sdrop_mask(M, K, BM, BK, p, seed, rng_stream=0, out=None):
+    """Draws the block mask of Section 3.2 on the device; returns a Mask."""
+    m = out if out is not None else Mask(M, K, BM, BK, p)
+    m.p = float(p)
+    _check(lib().sdrop_mask(_dev(m.buf, "mask"), m.buf.numel(), M, K, BM, BK, float(p),
+                            int(seed), int(rng_stream), _stream()), "sdrop_mask")
+    return m
+
+
+def sdrop_mask_from_bits(M, K, BM, BK, p, bits, out=None):
+    """Mask object from given keep bits: int64/uint64 GPU tensor [MB, words_per_row]."""
+    m = out if out is not None else Mask(M, K, BM, BK, p)
+    m.p = float(p)
+    _check(lib().sdrop_mask_from_bits(_dev(m.buf, "mask"), m.buf.numel(), M, K, BM, BK,
+                                      _dev(bits, "bits"), _stream()), "sdrop_mask_from_bits")
+    return m
+
+
+def workspace_bytes(op, M, K, N, BM, BK, dtype, out_dtype):
+    return int(lib().sdrop_workspace_bytes(op, M, K, N, BM, BK, _DTYPES[dtype], _DTYPES[out_dtype]))
+
+
+def _gemm(name, op, a, b, mask, out_shape, M, K, N, out_dtype, out, ws):
+    dtype = a.dtype
+    if b.dtype != dtype:
+        raise ValueError("operands must have the same dtype")
+    out_dtype = dtype if out_dtype is None else out_dtype
+    if out is None:
+        out = torch.empty(out_shape, dtype=out_dtype, device=a.device)
+    elif tuple(out.shape) != tuple(out_shape) or out.dtype != out_dtype:
+        raise ValueError("out has the wrong shape or dtype")
+    if dtype not in (torch.float16, torch.bfloat16) or out_dtype not in _DTYPES:
+        raise SdropError(EDTYPE, name)
+    need = workspace_bytes(op, M, K, N, mask.BM, mask.BK, dtype, out_dtype)
+    if ws is None and need:
+        ws = torch.empty(need, dtype=torch.uint8, device=a.device)
+    ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
+    ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    rc = getattr(lib(), name)(_dev(a, "a"), _dev(b, "b"), _dev(mask.buf, "mask"), _dev(out, "out"),
+                              M, K, N, mask.BM, mask.BK, mask.p, _DTYPES[dtype], _DTYPES[out_dtype],
+                              ws_ptr, ws_bytes, _stream())
+    _check(rc, name)
+    return out
+
+
+def sdrop_fwd(X, W, mask, out_dtype=None, out=None, ws=None):
+    """eq. (1): Y = s (X . m') W."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_fwd")
+    return _gemm("sdrop_fwd", OP_FWD, X, W, mask, (M, N), M, K, N, out_dtype, out, ws)
+
+
+def sdrop_bwd_dx(dY, W, mask, out_dtype=None, out=None, ws=None):
+    """eq. (2): dX = s (dY W^T) . m'."""
+    M, N = dY.shape
+    K, N2 = W.shape
+    if N2 != N or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_bwd_dx")
+    return _gemm("sdrop_bwd_dx", OP_BWD_DX, dY, W, mask, (M, K), M, K, N, out_dtype, out, ws)
+
+
+def sdrop_bwd_dw(X, dY, mask, out_dtype=None, out=None, ws=None):
+    """eq. (3): dW = s (X . m')^T dY."""
+    M, K = X.shape
+    M2, N = dY.shape
+    if M2 != M or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_bwd_dw")
+    return _gemm("sdrop_bwd_dw", OP_BWD_DW, X, dY, mask, (K, N), M, K, N, out_dtype, out, ws)

@@ -1,0 +1,62 @@
+"""Helpers shared by the GPU parity tests (no method arithmetic here)."""
+import numpy as np
+import torch
+
+# tolerance of the parity gate: relative Frobenius error and max-abs error relative
+# to the largest reference magnitude, for fp32-accumulated results
+REL_FRO = 1e-3
+MAX_ABS = 5e-3
+
+
+def f64(t):
+    """Exact widening of a 16-bit (or fp32) torch tensor to a float64 numpy array."""
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def errors(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    fro = np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got - ref)
+    mx = np.max(np.abs(ref)) if ref.size else 0.0
+    mabs = (np.max(np.abs(got - ref)) / mx if mx > 0 else np.max(np.abs(got - ref))) if ref.size else 0.0
+    return fro, mabs
+
+
+def assert_close(got, ref, what, rel_fro=REL_FRO, max_abs=MAX_ABS):
+    assert np.all(np.isfinite(got)), what + ": non-finite output"
+    fro, mabs = errors(got, ref)
+    assert fro <= rel_fro, "%s: relative Frobenius error %.3e > %.1e" % (what, fro, rel_fro)
+    assert mabs <= max_abs, "%s: max-abs error %.3e of max|ref| > %.1e" % (what, mabs, max_abs)
+    return fro, mabs
+
+
+def bf16_round(a64):
+    """Round-to-nearest-even of float64 values to bf16, returned as float64."""
+    return torch.from_numpy(np.asarray(a64, dtype=np.float64)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def assert_bf16_rounding_of(got16, ref, what, acc_tol=2e-5):
+    """A bf16 output must be the rounding of an accurate fp32 result: each entry within half a
+    bf16 ulp of the reference (2^-8 relative, 8 significand bits) plus the fp32 accumulation
+    allowance acc_tol * max|ref| (a length-K fp32 sum of exact 16-bit products errs by about
+    sqrt(K) * 2^-24 of its partial sums: 4e-6 at K = 4096; the allowance is 5x that)."""
+    got16 = np.asarray(got16, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    mx = np.max(np.abs(ref)) if ref.size else 0.0
+    bound = np.abs(ref) * (2.0 ** -8) * (1 + 2.0 ** -7) + acc_tol * mx
+    bad = np.abs(got16 - ref) > bound
+    assert not bad.any(), "%s: %d entries further than half a bf16 ulp + %.0e*max from the oracle" % (
+        what, int(bad.sum()), acc_tol)
+
+
+def lists_from_keep(keep):
+    """The index lists a mask object must hold, derived from keep flags with numpy."""
+    keep = np.asarray(keep, dtype=np.uint8)
+    MB, KB = keep.shape
+    row_ptr = np.concatenate([[0], np.cumsum(keep.sum(axis=1))]).astype(np.int32)
+    rows, cols = np.nonzero(keep)                      # row-major order
+    col_ptr = np.concatenate([[0], np.cumsum(keep.sum(axis=0))]).astype(np.int32)
+    crows, ccols = np.nonzero(keep.T)                  # column-major order: (col, row)
+    return {"row_ptr": row_ptr, "col_idx": cols.astype(np.int32), "blk_row": rows.astype(np.int32),
+            "col_ptr": col_ptr, "row_idx": ccols.astype(np.int32)}

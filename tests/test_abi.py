@@ -1,0 +1,91 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares,
+and its host-side argument checks answer before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2411_01238_amd import sdrop
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sdrop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sdrop_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = sdrop.lib()
+    names = _declared()
+    assert set(names) == set(sdrop.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_strerror_and_codes():
+    assert sdrop.strerror(sdrop.OK) == "ok"
+    for c in range(1, 7):
+        assert len(sdrop.strerror(c)) > 3
+    assert "unknown" in sdrop.strerror(99)
+
+
+def test_mask_layout_regions_do_not_overlap():
+    for (M, K, BM, BK) in ((256, 256, 64, 64), (4096, 4096, 128, 128), (65536, 4096, 128, 128),
+                           (16384, 3072, 128, 64), (64, 64 * 130, 64, 64)):
+        L = sdrop.mask_layout(M, K, BM, BK)
+        MB, KB = M // BM, K // BK
+        assert (L.MB, L.KB, L.words_per_row) == (MB, KB, (KB + 63) // 64)
+        regions = [(0, 256), (L.off_bits, 8 * MB * L.words_per_row), (L.off_row_ptr, 4 * (MB + 1)),
+                   (L.off_col_idx, 4 * MB * KB), (L.off_blk_row, 4 * MB * KB), (L.off_col_ptr, 4 * (KB + 1)),
+                   (L.off_row_idx, 4 * MB * KB), (L.off_row_order, 4 * MB), (L.off_col_order, 4 * KB)]
+        end = 0
+        for off, size in regions:
+            assert off >= end and off % 16 == 0
+            end = off + size
+        assert L.total_bytes >= end
+        assert sdrop.mask_bytes(M, K, BM, BK) == L.total_bytes
+
+
+def test_bad_shapes_have_no_layout():
+    assert sdrop.mask_bytes(100, 256, 64, 64) == 0        # BM does not divide M
+    assert sdrop.mask_bytes(256, 256, 48, 64) == 0        # unsupported block
+    assert sdrop.mask_bytes(0, 256, 64, 64) == 0
+    with pytest.raises(sdrop.SdropError) as e:
+        sdrop.mask_layout(256, 200, 64, 64)
+    assert e.value.code == sdrop.ESHAPE
+
+
+def test_host_side_argument_errors_return_before_any_launch():
+    L = sdrop.lib()
+    buf = ctypes.create_string_buffer(1 << 16)   # host memory: never dereferenced by these calls
+    addr = (ctypes.addressof(buf) + 15) // 16 * 16
+    p = ctypes.c_void_p(addr)
+    null = ctypes.c_void_p(0)
+    assert L.sdrop_mask(null, 1 << 16, 256, 256, 64, 64, 0.5, 0, 0, null) == sdrop.EINVAL
+    assert L.sdrop_mask(p, 1 << 16, 256, 256, 64, 64, 1.5, 0, 0, null) == sdrop.EINVAL
+    assert L.sdrop_mask(p, 1 << 16, 256, 256, 64, 64, float("nan"), 0, 0, null) == sdrop.EINVAL
+    assert L.sdrop_mask(p, 1 << 16, 250, 256, 64, 64, 0.5, 0, 0, null) == sdrop.ESHAPE
+    assert L.sdrop_mask(p, 16, 256, 256, 64, 64, 0.5, 0, 0, null) == sdrop.EWORKSPACE
+    assert L.sdrop_mask(ctypes.c_void_p(addr + 4), 1 << 16, 256, 256, 64, 64, 0.5, 0, 0, null) == sdrop.EALIGN
+    assert L.sdrop_mask_from_bits(p, 1 << 16, 256, 256, 64, 64, null, null) == sdrop.EINVAL
+    for name in ("sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw"):
+        f = getattr(L, name)
+        ok = (p, p, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)
+
+        def call(**kw):
+            a = list(ok)
+            for k, v in kw.items():
+                a[int(k[1:])] = v
+            return f(*a)
+        assert call(a0=null) == sdrop.EINVAL
+        assert call(a3=null) == sdrop.EINVAL
+        assert call(a9=-0.1) == sdrop.EINVAL
+        assert call(a4=255) == sdrop.ESHAPE
+        assert call(a6=250) == sdrop.ESHAPE           # N not a multiple of 8
+        assert call(a7=32) == sdrop.ESHAPE
+        assert call(a10=sdrop.F32) == sdrop.EDTYPE
+        assert call(a11=sdrop.BF16) == sdrop.EDTYPE   # out_dtype must be the input type or fp32
+        assert call(a1=ctypes.c_void_p(addr + 8)) == sdrop.EALIGN

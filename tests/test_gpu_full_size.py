@@ -1,0 +1,86 @@
+"""GPU parity at the full workload sizes, in the launch configuration the benchmark times.
+
+The oracle cannot form whole products of these sizes in seconds, so it evaluates the same
+definitions (arxiv 2411.01238 eq. (1)-(3)) at sampled output positions, spread over every
+kind of position: kept and dropped blocks, first/last rows and columns of tiles.  Properties
+that hold at any size are checked on the whole output: dropped blocks of dX are +0, kept
+blocks are not, the bf16 output is the rounding of the fp32 output.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdrop_oracle as orc
+from paper_2411_01238_amd import sdrop
+from paper_2411_01238_amd.workloads import WORKLOADS, make_inputs
+from _util import f64, assert_close, assert_bf16_rounding_of
+
+pytestmark = pytest.mark.gpu
+
+
+def _positions(rng, R, C, n, tr, tc):
+    """n positions in an R x C matrix: random ones plus tile corners (tile tr x tc)."""
+    r = rng.integers(0, R, n)
+    c = rng.integers(0, C, n)
+    edge_r = np.array([0, tr - 1, tr, R - 1, R - tr, R // 2])
+    edge_c = np.array([0, tc - 1, tc, C - 1, C - tc, C // 2])
+    er, ec = np.meshgrid(edge_r % R, edge_c % C)
+    return np.concatenate([r, er.reshape(-1)]), np.concatenate([c, ec.reshape(-1)])
+
+
+def _sampled_parity(w, p, layer=0, n=400, n_dw=96):
+    tag = "%s p=%.1f layer %d" % (w.name, p, layer)
+    print("full-size case", tag, flush=True)
+    X, W, dY = make_inputs(w, layer=layer)
+    m = sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, w.mask_seed, layer)
+    keep = orc.mask(w.MB, w.KB, p, w.mask_seed, layer)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    rng = np.random.default_rng(1234)
+    Xd, Wd, dYd = f64(X), f64(W), f64(dY)
+    is_bf16 = X.dtype == torch.bfloat16
+
+    def gather(t, r, c):
+        return t[torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()].cpu().to(torch.float64).numpy()
+
+    def check(name, fn, oracle_at, a, b, R, C, tr, tc, count):
+        r, c = _positions(rng, R, C, count, tr, tc)
+        ref = oracle_at(a, b, keep, w.BM, w.BK, p, r, c)
+        o32 = fn(out_dtype=torch.float32)
+        o16 = fn(out_dtype=None)
+        torch.cuda.synchronize()
+        assert torch.isfinite(o32).all().item(), tag + " " + name
+        # tolerances are relative to the whole result; sampled entries stand in for it
+        assert_close(gather(o32, r, c), ref, "%s %s fp32 out (sampled)" % (tag, name))
+        if is_bf16:
+            assert torch.equal(o16, o32.to(torch.bfloat16)), "%s %s bf16 != RNE(fp32 out)" % (tag, name)
+            assert_bf16_rounding_of(gather(o16, r, c), ref, "%s %s bf16 out (sampled)" % (tag, name))
+        else:
+            assert_close(gather(o16, r, c), ref, "%s %s fp16 out (sampled)" % (tag, name))
+        return o32, o16
+
+    check("Y", lambda **k: sdrop.sdrop_fwd(Xg, Wg, m, **k), orc.fwd_at, Xd, Wd, w.M, w.N, w.BM, 256, n)
+    dX32, dX16 = check("dX", lambda **k: sdrop.sdrop_bwd_dx(dYg, Wg, m, **k), orc.bwd_dx_at, dYd, Wd,
+                       w.M, w.K, w.BM, w.BK, n)
+    check("dW", lambda **k: sdrop.sdrop_bwd_dw(Xg, dYg, m, **k), orc.bwd_dw_at, Xd, dYd, w.K, w.N, w.BK, 256, n_dw)
+
+    # whole-output property: per block, dX is all +0 exactly where the block is dropped
+    keep_t = torch.from_numpy(keep.astype(bool)).cuda()
+    for dX in (dX32, dX16):
+        blocks = dX.view(w.MB, w.BM, w.KB, w.BK)
+        nz = (blocks != 0).any(dim=3).any(dim=1)
+        assert torch.equal(nz, keep_t), tag + ": dX block support differs from the mask"
+        neg0 = torch.signbit(blocks).any(dim=3).any(dim=1) & ~keep_t
+        assert not neg0.any().item()
+
+
+CASES = [(w.name, p) for w in WORKLOADS.values() if w.name != "tiny" for p in w.ps]
+
+
+@pytest.mark.parametrize("name,p", CASES)
+def test_full_size_sampled(name, p):
+    _sampled_parity(WORKLOADS[name], p)
+
+
+def test_mlp_other_layers_use_their_own_stream():
+    w = WORKLOADS["mlp"]
+    _sampled_parity(w, 0.5, layer=3, n=200, n_dw=48)

@@ -1,0 +1,164 @@
+"""GPU parity of the three products (arxiv 2411.01238 Section 3.1 eq. (1)-(3)) against the
+float64 CPU oracle, through the C ABI.
+
+Bar: relative Frobenius error <= 1e-3 and max-abs error <= 5e-3 * max|ref| for the
+fp32-accumulated result (out_dtype fp32) and for fp16 outputs.  A bf16-stored output
+cannot meet 1e-3 against an unrounded reference (rounding to 8 mantissa bits alone
+costs about 1.7e-3), so bf16 outputs are held to: bit-equal to the round-to-nearest-even
+of the library's own fp32 output, and each entry within half a bf16 ulp (plus the fp32
+accumulation allowance) of the oracle value.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdrop_oracle as orc
+from paper_2411_01238_amd import sdrop
+from paper_2411_01238_amd.workloads import WORKLOADS, make_inputs, make_custom
+from _util import f64, assert_close, assert_bf16_rounding_of
+
+pytestmark = pytest.mark.gpu
+
+
+def _expand(keep, BM, BK):
+    return np.repeat(np.repeat(keep.astype(bool), BM, axis=0), BK, axis=1)
+
+
+def _run_all(X, W, dY, m, out_dtype):
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    Y = sdrop.sdrop_fwd(Xg, Wg, m, out_dtype=out_dtype)
+    dX = sdrop.sdrop_bwd_dx(dYg, Wg, m, out_dtype=out_dtype)
+    dW = sdrop.sdrop_bwd_dw(Xg, dYg, m, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    return Y, dX, dW
+
+
+def _check_16bit_outputs(outs16, outs32, refs, dtype, tag):
+    for name, o16, o32, ref in zip(("Y", "dX", "dW"), outs16, outs32, refs):
+        if dtype == torch.float16:
+            assert_close(f64(o16), ref, "%s %s fp16 out" % (tag, name))
+        else:
+            assert torch.equal(o16, o32.to(torch.bfloat16)), "%s %s: bf16 output is not RNE of the fp32 output" % (tag, name)
+            assert_bf16_rounding_of(f64(o16), ref, "%s %s bf16 out" % (tag, name))
+
+
+def _full_parity(X, W, dY, BM, BK, p, seed, stream, tag, keep=None):
+    M, K = X.shape
+    if keep is None:
+        m = sdrop.sdrop_mask(M, K, BM, BK, p, seed, stream)
+        keep = orc.mask(M // BM, K // BK, p, seed, stream)
+    else:
+        bits = torch.from_numpy(orc.pack_bits(keep).view(np.int64)).cuda()
+        m = sdrop.sdrop_mask_from_bits(M, K, BM, BK, p, bits)
+    Xd, Wd, dYd = f64(X), f64(W), f64(dY)
+    refs = (orc.fwd(Xd, Wd, keep, BM, BK, p), orc.bwd_dx(dYd, Wd, keep, BM, BK, p),
+            orc.bwd_dw(Xd, dYd, keep, BM, BK, p))
+    outs32 = _run_all(X, W, dY, m, torch.float32)
+    for name, o, ref in zip(("Y", "dX", "dW"), outs32, refs):
+        assert_close(f64(o), ref, "%s %s fp32 out" % (tag, name))
+    outs16 = _run_all(X, W, dY, m, None)
+    _check_16bit_outputs(outs16, outs32, refs, X.dtype, tag)
+    # dropped blocks of dX are +0 exactly, in both output types
+    dropped = ~_expand(keep, BM, BK)
+    for o in (outs32[1], outs16[1]):
+        d = f64(o)
+        assert np.all(d[dropped] == 0.0) and not np.any(np.signbit(d[dropped])), tag + " dX dropped blocks"
+    return keep
+
+
+def test_tiny_workload():
+    w = WORKLOADS["tiny"]
+    X, W, dY = make_inputs(w)
+    print("gemm tiny", flush=True)
+    keep = _full_parity(X, W, dY, w.BM, w.BK, 0.5, w.mask_seed, 0, "tiny")
+    assert int(keep.sum()) == 10
+
+
+@pytest.mark.parametrize("M,K,N,BM,BK,dtype,p,seed", [
+    (512, 768, 328, 128, 128, "bf16", 0.3, 1),    # two N tiles, ragged tail of 72
+    (512, 768, 328, 128, 128, "f16", 0.5, 2),
+    (384, 512, 264, 64, 64, "f16", 0.5, 3),       # ragged tail of 8
+    (384, 512, 520, 64, 128, "bf16", 0.4, 4),     # three N tiles
+    (640, 320, 72, 128, 64, "bf16", 0.2, 5),      # N smaller than any tile
+    (256, 384, 512, 64, 64, "bf16", 0.7, 6),
+    (256, 256, 8, 128, 128, "f16", 0.5, 7),       # smallest legal N
+])
+def test_mid_sizes_every_element(M, K, N, BM, BK, dtype, p, seed):
+    print("gemm mid", M, K, N, BM, BK, dtype, p, seed, flush=True)
+    X, W, dY = make_custom(M, K, N, dtype, seed=seed)
+    _full_parity(X, W, dY, BM, BK, p, seed, 0, "mid(%d,%d,%d,%dx%d,%s)" % (M, K, N, BM, BK, dtype))
+
+
+def test_p0_is_plain_gemm_and_p1_is_zero():
+    X, W, dY = make_custom(256, 384, 136, "bf16", seed=11)
+    print("gemm p0/p1", flush=True)
+    keep = _full_parity(X, W, dY, 128, 128, 0.0, 0, 0, "p=0")
+    assert keep.all()
+    m = sdrop.sdrop_mask(256, 384, 128, 128, 1.0, 0, 0)
+    for o in _run_all(X, W, dY, m, torch.float32) + _run_all(X, W, dY, m, None):
+        assert torch.count_nonzero(o).item() == 0 and not torch.signbit(o).any().item()
+
+
+def test_explicit_masks_all_dropped_rows_and_columns():
+    X, W, dY = make_custom(384, 384, 136, "f16", seed=12)
+    print("gemm explicit masks", flush=True)
+    BM = BK = 64
+    keep = np.ones((6, 6), dtype=np.uint8)
+    keep[2, :] = 0          # an empty block row: Y rows 128..191 are zero
+    keep[:, 4] = 0          # an empty block column: dW rows 256..319 are zero
+    keep[0, 1] = 0
+    _full_parity(X, W, dY, BM, BK, 0.25, 0, 0, "explicit", keep=keep)
+    _full_parity(X, W, dY, BM, BK, 0.5, 0, 0, "all-dropped", keep=np.zeros((6, 6), dtype=np.uint8))
+    one = np.zeros((6, 6), dtype=np.uint8)
+    one[5, 0] = 1
+    _full_parity(X, W, dY, BM, BK, 0.5, 0, 0, "one-block", keep=one)
+
+
+def test_dropped_blocks_are_never_read():
+    # NaN planted in the dropped blocks of X must not reach Y or dW (Section 3.2)
+    X, W, dY = make_custom(512, 512, 264, "bf16", seed=13)
+    print("gemm nan poison", flush=True)
+    BM = BK = 128
+    p = 0.5
+    m = sdrop.sdrop_mask(512, 512, BM, BK, p, 3, 0)
+    keep = orc.mask(4, 4, p, 3, 0)
+    assert 0 < keep.sum() < 16
+    Xp = X.clone()
+    Xp[torch.from_numpy(~_expand(keep, BM, BK))] = float("nan")
+    Y0, _, dW0 = _run_all(X, W, dY, m, torch.float32)
+    Y1, _, dW1 = _run_all(Xp, W, dY, m, torch.float32)
+    assert torch.equal(Y0, Y1) and torch.equal(dW0, dW1)
+
+
+def test_results_are_bitwise_reproducible():
+    X, W, dY = make_custom(512, 512, 264, "f16", seed=14)
+    m = sdrop.sdrop_mask(512, 512, 64, 64, 0.3, 1, 0)
+    a = _run_all(X, W, dY, m, torch.float32)
+    b = _run_all(X, W, dY, m, torch.float32)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_mask_for_another_problem_writes_nothing():
+    X, W, dY = make_custom(256, 256, 64, "f16", seed=15)
+    m = sdrop.sdrop_mask(256, 256, 64, 64, 0.5, 0, 0)
+    wrong = sdrop.sdrop_mask(256, 256, 128, 128, 0.5, 0, 0)
+    wrong.BM = wrong.BK = 64            # lie to the binding; the device header still says 128
+    wrong.buf = torch.cat([wrong.buf, torch.zeros(m.buf.numel(), dtype=torch.uint8, device="cuda")])
+    out = torch.full((256, 64), 7.0, dtype=torch.float16, device="cuda")
+    sdrop.sdrop_fwd(X.cuda(), W.cuda(), wrong, out=out)
+    torch.cuda.synchronize()
+    assert torch.all(out == 7.0)
+
+
+def test_binding_reports_errors():
+    X, W, dY = make_custom(256, 256, 64, "f16", seed=16)
+    m = sdrop.sdrop_mask(256, 256, 64, 64, 0.5, 0, 0)
+    with pytest.raises(sdrop.SdropError) as e:
+        sdrop.sdrop_fwd(X.cuda(), W.cuda()[:, :60].contiguous(), m)      # N = 60
+    assert e.value.code == sdrop.ESHAPE
+    with pytest.raises(sdrop.SdropError):
+        sdrop.sdrop_fwd(X.cuda()[:128].contiguous(), W.cuda(), m)         # mask is for M = 256
+    with pytest.raises(sdrop.SdropError) as e:
+        sdrop.sdrop_fwd(X.cuda().float(), W.cuda().float(), m)
+    assert e.value.code == sdrop.EDTYPE

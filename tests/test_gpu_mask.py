@@ -1,0 +1,88 @@
+"""GPU parity: the device mask (Section 3.2 of arxiv 2411.01238, this build's Philox rule)
+must equal the CPU oracle's bit for bit, and every index list must describe that same set."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdrop_oracle as orc
+from paper_2411_01238_amd import sdrop
+from paper_2411_01238_amd.workloads import WORKLOADS
+from _util import lists_from_keep
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_mask(m, keep):
+    MB, KB = keep.shape
+    torch.cuda.synchronize()
+    assert m.nnz() == int(keep.sum())
+    got_bits = m.bits().cpu().numpy().view(np.uint64)
+    assert np.array_equal(got_bits, orc.pack_bits(keep))
+    got = {k: v.cpu().numpy() for k, v in m.lists().items()}
+    want = lists_from_keep(keep)
+    for k in ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx"):
+        assert np.array_equal(got[k], want[k]), k
+    # the schedules are permutations sorted by descending kept count (ties: any order)
+    rc, cc = keep.sum(axis=1).astype(np.int64), keep.sum(axis=0).astype(np.int64)
+    assert sorted(got["row_order"].tolist()) == list(range(MB))
+    assert sorted(got["col_order"].tolist()) == list(range(KB))
+    assert np.all(np.diff(rc[got["row_order"]]) <= 0)
+    assert np.all(np.diff(cc[got["col_order"]]) <= 0)
+
+
+CASES = []
+for w in WORKLOADS.values():
+    for p in w.ps:
+        for layer in range(w.layers):
+            CASES.append((w.name, p, layer))
+
+
+@pytest.mark.parametrize("name,p,layer", CASES)
+def test_mask_matches_oracle_on_every_workload(name, p, layer):
+    w = WORKLOADS[name]
+    print("mask case", name, p, layer, flush=True)
+    m = sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, w.mask_seed, layer)
+    _check_mask(m, orc.mask(w.MB, w.KB, p, w.mask_seed, layer))
+
+
+@pytest.mark.parametrize("M,K,BM,BK,p,seed,stream", [
+    (64, 64, 64, 64, 0.5, 1, 0),                 # a single block
+    (64, 64, 64, 64, 1.0, 1, 0),
+    (128 * 3, 64 * 70, 128, 64, 0.4, 5, 9),      # KB = 70: two mask words per row
+    (64 * 1100, 128 * 3, 64, 128, 0.6, 2**40 + 7, 2**33 + 1),   # MB > 1024: several scan chunks; 64-bit seed/stream
+    (128 * 5, 128 * 64, 128, 128, 0.0, 3, 3),    # exactly one full word, all kept
+    (128 * 5, 128 * 65, 128, 128, 2.0 ** -32, 0, 0),
+    (64 * 200, 64 * 130, 64, 64, 0.9, 4, 4),     # sparse, three words per row
+])
+def test_mask_edge_shapes(M, K, BM, BK, p, seed, stream):
+    print("mask edge", M, K, BM, BK, p, seed, stream, flush=True)
+    m = sdrop.sdrop_mask(M, K, BM, BK, p, seed, stream)
+    _check_mask(m, orc.mask(M // BM, K // BK, p, seed, stream))
+
+
+def test_mask_is_reproducible_and_reusable():
+    a = sdrop.sdrop_mask(4096, 4096, 128, 128, 0.5, 0, 0)
+    b = sdrop.sdrop_mask(4096, 4096, 128, 128, 0.5, 0, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(a.bits(), b.bits())
+    for k in ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx"):
+        assert torch.equal(a.lists()[k], b.lists()[k])
+    # a buffer that held another mask is fully rewritten
+    sdrop.sdrop_mask(4096, 4096, 128, 128, 0.1, 7, 1, out=a)
+    _check_mask(a, orc.mask(32, 32, 0.1, 7, 1))
+
+
+def test_mask_from_bits():
+    rng = np.random.default_rng(0)
+    for (MB, KB, BM, BK) in ((4, 4, 64, 64), (9, 70, 128, 64), (33, 5, 64, 128)):
+        keep = (rng.random((MB, KB)) < 0.5).astype(np.uint8)
+        words = orc.pack_bits(keep)
+        # junk in the unused high bits must be ignored
+        if KB % 64:
+            words[:, -1] |= np.uint64(0xFFFFFFFFFFFFFFFF) << np.uint64(KB % 64)
+        bits = torch.from_numpy(words.view(np.int64)).cuda()
+        m = sdrop.sdrop_mask_from_bits(MB * BM, KB * BK, BM, BK, 0.5, bits)
+        _check_mask(m, keep)
+    none = torch.zeros((4, 1), dtype=torch.int64, device="cuda")
+    m = sdrop.sdrop_mask_from_bits(256, 256, 64, 64, 0.5, none)
+    _check_mask(m, np.zeros((4, 4), dtype=np.uint8))
