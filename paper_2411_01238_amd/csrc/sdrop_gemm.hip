@@ -5,24 +5,35 @@
 //   DX   dX = s (dY W^T) . m'     tile = one kept block (i,j): reduction over all of N
 //   DW   dW = s (X . m')^T dY     tile (block column j, N tile): walks the kept row blocks of column j
 //
-// Each workgroup owns one TM x TN output tile and steps through its reduction
-// in slices of TK = 64.  A slice of each operand is staged in LDS exactly as it
-// lies in HBM (16-byte global loads, 16-byte LDS stores), two LDS stages deep:
-// the global loads of slice t+1 are issued before the MFMAs of slice t and land
-// in the other stage afterwards, one barrier per slice.  The paper names the
-// lack of this software pipelining as the reason its kernels lose to dense at
-// zero sparsity (Section 5.1).
+// Each workgroup (4 wavefronts, one per SIMD, one workgroup per CU) owns one
+// TM x TN output tile and steps through its reduction in slices of TK = 64 that
+// rotate through three LDS stages.  The paper names the lack of software
+// pipelining as the reason its kernels lose to dense at zero sparsity
+// (Section 5.1); here, while the MFMAs of slice t run, slice t+1 is complete in
+// LDS and slice t+2 is on its way.  One barrier per slice, placed before the last
+// quarter of the slice's MFMAs so that the first operands of slice t+1 are read
+// behind them.  Within a slice the LDS reads, LDS writes, byte permutes and
+// global loads are interleaved with the MFMAs by explicit scheduling groups,
+// because one wavefront per SIMD has no other wavefront to hide its issue slots.
 //
 // The matrix-core instruction is v_mfma_f32_32x32x16_{f16,bf16}: lane l supplies
 // row (l%32) of the left operand and column (l%32) of the right operand, each
-// as 8 consecutive reduction indices starting at 8*(l/32).  An operand whose
-// reduction index is contiguous in memory (X in FWD, dY and W in DX) is read
-// from LDS with one 16-byte load per lane.  An operand whose reduction index is
-// the strided one (W in FWD; X and dY in DW) is read with the transposing LDS
-// load ds_read_b64_tr_b16, which hands each lane four reduction-consecutive
-// values out of a row-major tile, so no transposed copy is ever made.
-// LDS rows are padded (16 bytes for reduction-contiguous tiles, 64 bytes for
-// the others) so that both kinds of read are free of bank conflicts.
+// as 8 consecutive reduction indices starting at 8*(l/32).  Every operand slice
+// therefore lives in LDS in ONE form, [rows][64 reduction indices] with 128-byte
+// rows, read with one 16-byte ds_read_b128 per lane and MFMA.
+//   - An operand whose reduction index is contiguous in HBM (X in FWD, dY and W
+//     in DX) goes HBM -> LDS directly (global_load_lds_dwordx4): no registers, no
+//     LDS store instructions, and the LDS pipe stays free for the reads (an LDS
+//     store of 1 KiB was measured at 13 clocks, a read at 5.6).
+//   - An operand whose reduction index is the strided one (W in FWD; X and dY in
+//     DW) is transposed in registers on its way in: a thread loads an 8 x NW patch
+//     (8 reduction rows, NW contiguous columns), regroups it with byte permutes
+//     and stores NW rows of 8.  (The transposing LDS read of gfx950,
+//     ds_read_b64_tr_b16, was measured at a third of the byte rate of
+//     ds_read_b128 and made the loop LDS-bound.)
+// The 16-byte slot of chunk c in row r is c ^ swz(r) (see lds_off): with it the
+// row-wise stores, the transposed stores and the operand reads are all free of
+// bank conflicts without padding, which the direct loads require.
 #include "sdrop_internal.h"
 
 namespace sdrop {
@@ -58,6 +69,7 @@ template <> struct In<BF16> {
 
 constexpr int TK = 64;           // reduction slice staged per step
 constexpr int kThreads = 256;    // 4 wavefronts per workgroup
+constexpr int kStages = 3;       // LDS stages
 
 enum Op { FWD = 0, DX = 1, DW = 2 };
 
@@ -68,88 +80,184 @@ struct GemmParams {
     MaskView mv;
     int64_t M, K, N;
     int32_t BM, BK, MB, KB;
-    int32_t n_tiles_n;  // FWD/DW: number of TN-wide tiles along N
+    int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
     float scale;
 };
 
-// LDS row strides in bytes.  kmajor: rows of TK reduction-contiguous elements.
-constexpr int lds_stride(bool kmajor, int cols) { return cols * 2 + (kmajor ? 16 : 64); }
+// Slot swizzle of an LDS operand row: a 3-bit value XORed into the chunk index.
+// With m = (r>>1)&7: rotate m left by one and flip with bits 4,5 of r.  Measured
+// conflict-free for ds_read_b128 of 32 consecutive rows x 2 chunks per wavefront,
+// for row-wise 16-byte stores and for the transposed stores below.
+__device__ __forceinline__ int swz(int r)
+{
+    const int m = (r >> 1) & 7;
+    return (((m & 3) << 1) | (m >> 2)) ^ ((r >> 3) & 6);
+}
+// Byte offset of 16-byte chunk c (0..7) of row r in an LDS operand tile.
+__device__ __forceinline__ int lds_off(int r, int c) { return r * 128 + (((c ^ swz(r)) & 7) << 4); }
 
-template <int OP, int TM, int TN> struct Geometry {
-    static constexpr bool A_KMAJ = (OP != DW);
-    static constexpr bool B_KMAJ = (OP == DX);
-    // tile as it lies in memory: [rows][cols], cols contiguous
-    static constexpr int A_ROWS = A_KMAJ ? TM : TK, A_COLS = A_KMAJ ? TK : TM;
-    static constexpr int B_ROWS = B_KMAJ ? TN : TK, B_COLS = B_KMAJ ? TK : TN;
-    static constexpr int SA = lds_stride(A_KMAJ, A_COLS), SB = lds_stride(B_KMAJ, B_COLS);
-    static constexpr int A_BYTES = A_ROWS * SA, B_BYTES = B_ROWS * SB;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-    static constexpr int A_CHUNKS = A_ROWS * A_COLS / 8 / kThreads;   // 16-byte chunks per thread
-    static constexpr int B_CHUNKS = B_ROWS * B_COLS / 8 / kThreads;
-    static_assert(A_CHUNKS >= 1 && B_CHUNKS >= 1, "tile too small for 256 threads");
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void gbl_void_t;
+
+// HBM -> LDS without registers, for an operand tile [ROWS][64] whose rows lie ld_bytes
+// apart in HBM.  One instruction of one wavefront fills 1 KiB = 8 LDS rows: lane l lands in
+// row 8*I + l/8, slot l%8, so it fetches chunk (l%8) ^ swz(row) of that row.  Wavefront w
+// issues instructions I = w, w+4, ...; instructions [PART*PER, (PART+1)*PER) of those.
+template <int ROWS, int NGRP, int PART, int NPARTS>
+__device__ __forceinline__ void dma_slice(const char *const (&base)[NGRP], int64_t ld_bytes, char *lds)
+{
+    constexpr int PER_WAVE = ROWS / 32, PER = PER_WAVE / NPARTS, GROUP_ROWS = ROWS / NGRP;
+    static_assert(PER_WAVE % NPARTS == 0 && GROUP_ROWS % 32 == 0, "bad split");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = PART * PER; i < (PART + 1) * PER; ++i) {
+        const int I = wave + 4 * i;                       // rows 8I .. 8I+7
+        const int g = (32 * i) / GROUP_ROWS;              // uniform: rows of pass i are 32i .. 32i+31
+        const int r = 8 * I + (lane >> 3);
+        const int c = (lane & 7) ^ swz(r);
+        const char *src = base[g] + (int64_t)(r - g * GROUP_ROWS) * ld_bytes + c * 16;
+        __builtin_amdgcn_global_load_lds((gbl_void_t *)src, (lds_void_t *)(lds + I * 1024), 16, 0, 0);
+    }
+}
+
+// A slice of an operand on its way from HBM to LDS through registers.
+//
+// KMAJ:  HBM tile [ROWS][64], rows ld_bytes apart.  Thread t moves 16-byte chunks
+//        t, t+256, ...: chunk q is row q/8, chunk q%8.  The rows may come from up to
+//        NGRP row groups with separate base pointers.
+// !KMAJ: HBM tile [64][ROWS] (ROWS contiguous).  Thread t owns reduction rows
+//        8*(t/32)..+8 and columns NW*(t%32)..+NW, NW = ROWS/32, and turns them
+//        into NW LDS rows of one 16-byte chunk each.
+// RAGGED: chunks beyond `lim` valid elements of the contiguous dimension read as zero.
+template <bool KMAJ, int ROWS, bool RAGGED, int NGRP = 1> struct Slice {
+    static constexpr int NW = ROWS / 32;                       // !KMAJ: columns per thread
+    static constexpr int NCH = KMAJ ? ROWS * 8 / kThreads : 1; // KMAJ: chunks per thread
+    static constexpr int ND = KMAJ ? 4 * NCH : 4 * NW;         // dwords held
+    static constexpr int NLOADS = KMAJ ? NCH : 8;
+    static constexpr int NSTORES = KMAJ ? NCH : NW;
+    static constexpr int NPERMS = KMAJ ? 0 : 4 * NW;
+    static constexpr int GROUP_ROWS = ROWS / NGRP;
+    static_assert(ROWS % 32 == 0 && (KMAJ ? NCH >= 1 : (NW == 2 || NW == 4 || NW == 8)), "unsupported tile edge");
+    static_assert(!KMAJ || NGRP == 1 || (GROUP_ROWS % 32 == 0), "row groups must cover whole passes");
+    uint32_t d[ND];
+
+    template <class V> __device__ __forceinline__ static V ld(const char *p, const char *safe, bool ok)
+    {
+        if constexpr (RAGGED) {
+            V v = *reinterpret_cast<const V *>(ok ? p : safe);
+            V z = {};
+            return ok ? v : z;
+        } else {
+            return *reinterpret_cast<const V *>(p);
+        }
+    }
+
+    // base[g]: start of row group g.  lim = valid elements along the contiguous dimension.
+    __device__ __forceinline__ void load(const char *const (&base)[NGRP], int64_t ld_bytes, int lim)
+    {
+        if constexpr (KMAJ) {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) {
+                const int c = threadIdx.x + q * kThreads;
+                const int row = c >> 3, cc = c & 7;
+                const int g = (q * 32) / GROUP_ROWS;           // rows of pass q: 32q .. 32q+31
+                const int r = row - g * GROUP_ROWS;
+                const uint4 v = ld<uint4>(base[g] + r * ld_bytes + cc * 16, base[g], cc * 8 < lim);
+                d[4 * q] = v.x; d[4 * q + 1] = v.y; d[4 * q + 2] = v.z; d[4 * q + 3] = v.w;
+            }
+        } else {
+            const int ng = threadIdx.x & 31, kc = threadIdx.x >> 5;
+            const char *p = base[0] + (int64_t)(kc * 8) * ld_bytes + ng * (NW * 2);
+            const bool ok = ng * NW < lim;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if constexpr (NW == 8) {
+                    const uint4 v = ld<uint4>(p + i * ld_bytes, base[0], ok);
+                    d[4 * i] = v.x; d[4 * i + 1] = v.y; d[4 * i + 2] = v.z; d[4 * i + 3] = v.w;
+                } else if constexpr (NW == 4) {
+                    const uint2 v = ld<uint2>(p + i * ld_bytes, base[0], ok);
+                    d[2 * i] = v.x; d[2 * i + 1] = v.y;
+                } else {
+                    d[i] = ld<uint32_t>(p + i * ld_bytes, base[0], ok);
+                }
+            }
+        }
+    }
+
+    // Stores part PART of NPARTS equal parts of this slice (so that the stores can be
+    // spread over several MFMA groups).
+    template <int PART, int NPARTS> __device__ __forceinline__ void store(char *lds) const
+    {
+        constexpr int PER = NSTORES / NPARTS;
+        static_assert(NSTORES % NPARTS == 0, "parts must divide the stores");
+        if constexpr (KMAJ) {
+#pragma unroll
+            for (int q = PART * PER; q < (PART + 1) * PER; ++q) {
+                const int c = threadIdx.x + q * kThreads;
+                *reinterpret_cast<uint4 *>(lds + lds_off(c >> 3, c & 7)) =
+                    make_uint4(d[4 * q], d[4 * q + 1], d[4 * q + 2], d[4 * q + 3]);
+            }
+        } else {
+            // d[(NW/2)*i + w] holds columns 2w (low half) and 2w+1 (high half) of reduction row i.
+            // LDS row n gets (row 0, row 1), (row 2, row 3), ... of column n as four dwords.
+            const int ng = threadIdx.x & 31, kc = threadIdx.x >> 5;
+            constexpr int DW_PER_ROW = NW / 2;
+#pragma unroll
+            for (int n = PART * PER; n < (PART + 1) * PER; ++n) {
+                const uint32_t sel = (n & 1) ? 0x07060302u : 0x05040100u;
+                uint32_t o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    o[j] = __builtin_amdgcn_perm(d[DW_PER_ROW * (2 * j + 1) + n / 2], d[DW_PER_ROW * (2 * j) + n / 2], sel);
+                *reinterpret_cast<uint4 *>(lds + lds_off(ng * NW + n, kc)) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+        }
+    }
 };
 
-// One operand slice: global -> registers.
-template <int ROWS, int COLS, int NCH>
-__device__ __forceinline__ void load_slice(uint4 (&r)[NCH], const char *base, int64_t ld_bytes, int lim_cols)
-{
-    constexpr int CPR = COLS / 8;
-#pragma unroll
-    for (int q = 0; q < NCH; ++q) {
-        const int c = threadIdx.x + q * kThreads;
-        const int row = c / CPR, cc = c % CPR;
-        if (cc * 8 < lim_cols)
-            r[q] = *reinterpret_cast<const uint4 *>(base + row * ld_bytes + cc * 16);
-        else
-            r[q] = make_uint4(0, 0, 0, 0);
-    }
-}
-
-// registers -> LDS, same [rows][cols] arrangement with padded rows.
-template <int ROWS, int COLS, int NCH, int STRIDE>
-__device__ __forceinline__ void store_slice(const uint4 (&r)[NCH], char *lds)
-{
-    constexpr int CPR = COLS / 8;
-#pragma unroll
-    for (int q = 0; q < NCH; ++q) {
-        const int c = threadIdx.x + q * kThreads;
-        const int row = c / CPR, cc = c % CPR;
-        *reinterpret_cast<uint4 *>(lds + row * STRIDE + cc * 16) = r[q];
-    }
-}
-
-// MFMA operand for 32 rows (or columns) starting at `base32` of the tile, reduction
-// indices [kk*16, kk*16+16): lane l gets index base32 + l%32, reduction 8*(l/32)..+8.
-template <class T, bool KMAJ, int STRIDE>
+// MFMA operand for the 32 rows starting at `base32` of an LDS operand tile, reduction
+// indices [kk*16, kk*16+16): lane l gets row base32 + l%32, reduction 8*(l/32)..+8.
+template <class T>
 __device__ __forceinline__ typename In<T>::vec read_frag(const char *lds, int base32, int kk)
 {
     const int l = threadIdx.x & 63;
-    if constexpr (KMAJ) {
-        const char *p = lds + (base32 + (l & 31)) * STRIDE + (kk * 2 + (l >> 5)) * 16;
-        return *reinterpret_cast<const typename In<T>::vec *>(p);
-    } else {
-        // transposing read: within each group of 16 lanes, lane q loads 4 elements of
-        // row q/4 at columns 4*(q%4).., and receives column (q) of the 4x16 patch
-        const int row = kk * 16 + (l >> 5) * 8 + ((l & 15) >> 2);
-        const int col = base32 + ((l >> 4) & 1) * 16 + (l & 3) * 4;
-        const char *p = lds + row * STRIDE + col * 2;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * STRIDE));
-        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(typename In<T>::vec, v);
-    }
+    return *reinterpret_cast<const typename In<T>::vec *>(lds + lds_off(base32 + (l & 31), kk * 2 + (l >> 5)));
 }
 
 template <class OutT> __device__ __forceinline__ void store_out(OutT *p, float v) { *p = static_cast<OutT>(v); }
 
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN>
+// Scheduling recipe for one MFMA group: each of the NM MFMAs is followed by its share of
+// the LDS reads, global loads, VALU ops and LDS writes that were emitted with it.
+constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
+template <int NM, int NDSR, int NVALU, int NDSW, int NVMEM>
+__device__ __forceinline__ void interleave()
+{
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   // MFMA
+        if constexpr (NDSR > 0) __builtin_amdgcn_sched_group_barrier(0x100, ceil_div(NDSR, NM), 0);   // DS read
+        if constexpr (NVMEM > 0) __builtin_amdgcn_sched_group_barrier(0x020, ceil_div(NVMEM, NM), 0); // VMEM read
+        if constexpr (NVALU > 0) __builtin_amdgcn_sched_group_barrier(0x002, ceil_div(NVALU, NM), 0); // VALU
+        if constexpr (NDSW > 0) __builtin_amdgcn_sched_group_barrier(0x200, ceil_div(NDSW, NM), 0);   // DS write
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory operations
+// are outstanding and all LDS/scalar operations have completed.
+constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (0 << 8); }
+
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
 {
-    using G = Geometry<OP, TM, TN>;
     static_assert(WM * WN * 64 == kThreads, "4 wavefronts");
     constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
     static_assert(MI >= 1 && NI >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be 32-aligned");
+    constexpr bool A_KMAJ = (OP != DW), B_KMAJ = (OP == DX);    // reduction index contiguous in HBM?
+    constexpr bool A_DMA = A_KMAJ && !(RAGGED && OP == DX);     // the reduction tail of DX needs zero fill
+    constexpr bool B_DMA = B_KMAJ && !RAGGED;
+    constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int NGRP_MAX = 4;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -157,81 +265,83 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
     const MaskHeader *H = P.mv.hdr;
     if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
 
-    const int esz = 2;
-    const char *a_tile = nullptr, *b_tile = nullptr;   // advanced per step
+    constexpr int esz = 2;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const char *a_tile = nullptr, *b_tile = nullptr;
     int64_t lda, ldb, ldc;                              // in bytes
-    char *c_tile;
-    int c_lim;                                          // valid output columns in this tile
-    int nsteps, sub;                                    // reduction steps; TK-slices per mask block
+    char *c_tile = nullptr;
+    int c_lim = TN;                                     // valid output columns in this tile
+    int nsteps = 0, sub_shift = 0;                      // reduction steps; log2(TK-slices per mask block)
     const int32_t *list = nullptr;                      // kept-block list walked by this tile
-    int a_lim = TK, b_lim = TK;
+    int list_len = 0;
+    // DX only: the tile's TN columns are DXG chunks of 64, each a (half) kept block of W / dX
+    constexpr int DXG = (OP == DX) ? TN / 64 : 1;
+    static_assert(DXG <= NGRP_MAX, "DX tile too wide");
+    const char *bgrp[NGRP_MAX] = {nullptr, nullptr, nullptr, nullptr};
+    char *cgrp[NGRP_MAX] = {nullptr, nullptr, nullptr, nullptr};
+    int chunks_valid = 0;                               // 64-column chunks that hold real blocks
 
     if constexpr (OP == FWD) {
         const int t = blockIdx.x;
-        const int i = P.mv.row_order[t / P.n_tiles_n], nt = t % P.n_tiles_n;
+        const int i = P.mv.row_order[t / P.n_tiles], nt = t % P.n_tiles;
         const int rp = P.mv.row_ptr[i];
         list = P.mv.col_idx + rp;
-        sub = P.BK / TK;
-        nsteps = (P.mv.row_ptr[i + 1] - rp) * sub;
+        list_len = P.mv.row_ptr[i + 1] - rp;
+        sub_shift = (P.BK == 128);
+        nsteps = list_len << sub_shift;
         lda = P.K * esz; ldb = P.N * esz; ldc = P.N * (int64_t)sizeof(OutT);
         a_tile = P.A + (int64_t)i * P.BM * lda;
         b_tile = P.B + (int64_t)nt * TN * esz;
         c_tile = P.C + (int64_t)i * P.BM * ldc + (int64_t)nt * TN * sizeof(OutT);
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
-        b_lim = c_lim;
     } else if constexpr (OP == DW) {
         const int t = blockIdx.x;
-        const int j = P.mv.col_order[t / P.n_tiles_n], nt = t % P.n_tiles_n;
+        const int j = P.mv.col_order[t / P.n_tiles], nt = t % P.n_tiles;
         const int cp = P.mv.col_ptr[j];
         list = P.mv.row_idx + cp;
-        sub = P.BM / TK;
-        nsteps = (P.mv.col_ptr[j + 1] - cp) * sub;
+        list_len = P.mv.col_ptr[j + 1] - cp;
+        sub_shift = (P.BM == 128);
+        nsteps = list_len << sub_shift;
         lda = P.K * esz; ldb = P.N * esz; ldc = P.N * (int64_t)sizeof(OutT);
         a_tile = P.A + (int64_t)j * P.BK * esz;
         b_tile = P.B + (int64_t)nt * TN * esz;
         c_tile = P.C + (int64_t)j * P.BK * ldc + (int64_t)nt * TN * sizeof(OutT);
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
-        b_lim = c_lim;
-        a_lim = TM;
     } else {
-        // blockIdx.x = q * MB + i: rank-q kept block of row i is computed; block
-        // position q of row i is zero-filled if it is a dropped one
+        // blockIdx.x = q * MB + i.  The workgroup computes the kept blocks of ranks
+        // [q*G, q*G+G) of block row i as one TM x (G*BK) tile, and zero-fills the block
+        // positions [q*G, q*G+G) of row i that are dropped.
+        const int G_ = TN / P.BK;
         const int i = blockIdx.x % P.MB, q = blockIdx.x / P.MB;
         lda = P.N * esz; ldb = P.N * esz; ldc = P.K * (int64_t)sizeof(OutT);
-        if (!((P.mv.bits[(int64_t)i * H->words_per_row + (q >> 6)] >> (q & 63)) & 1)) {
-            char *z = P.C + (int64_t)i * P.BM * ldc + (int64_t)q * P.BK * sizeof(OutT);
-            constexpr int row_chunks = TN * (int)sizeof(OutT) / 16;
-            for (int c = threadIdx.x; c < TM * row_chunks; c += kThreads)
-                *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
+        for (int g = 0; g < G_; ++g) {
+            const int pos = q * G_ + g;
+            if (pos < P.KB && !((P.mv.bits[(int64_t)i * H->words_per_row + (pos >> 6)] >> (pos & 63)) & 1)) {
+                char *z = P.C + (int64_t)i * P.BM * ldc + (int64_t)pos * P.BK * sizeof(OutT);
+                const int row_chunks = P.BK * (int)sizeof(OutT) / 16;
+                for (int c = threadIdx.x; c < TM * row_chunks; c += kThreads)
+                    *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
+            }
         }
         const int rp = P.mv.row_ptr[i];
-        if (q >= P.mv.row_ptr[i + 1] - rp) return;
-        const int j = P.mv.col_idx[rp + q];
-        sub = 1;
+        const int cnt = P.mv.row_ptr[i + 1] - rp;
+        if (q * G_ >= cnt) return;
+        const int blocks_valid = cnt - q * G_ < G_ ? cnt - q * G_ : G_;
+        const int cshift = (P.BK == 128);             // 64-column chunks per block, log2
+        chunks_valid = blocks_valid << cshift;
+#pragma unroll
+        for (int g = 0; g < DXG; ++g) {
+            const int b = g >> cshift;                // which of the gathered blocks (a missing one repeats the last)
+            const int j = P.mv.col_idx[rp + q * G_ + (b < blocks_valid ? b : blocks_valid - 1)];
+            const int64_t col0 = (int64_t)j * P.BK + (g & ((1 << cshift) - 1)) * 64;
+            bgrp[g] = P.B + col0 * ldb;
+            cgrp[g] = P.C + (int64_t)i * P.BM * ldc + col0 * sizeof(OutT);
+        }
         nsteps = (int)((P.N + TK - 1) / TK);
         a_tile = P.A + (int64_t)i * P.BM * lda;
-        b_tile = P.B + (int64_t)j * P.BK * ldb;
-        c_tile = P.C + (int64_t)i * P.BM * ldc + (int64_t)j * P.BK * sizeof(OutT);
-        c_lim = TN;
     }
-
-    // pointers to the slice of step s
-    auto slice_ptrs = [&](int s, const char *&ap, const char *&bp, int &al, int &bl) {
-        if constexpr (OP == FWD) {
-            const int64_t k0 = (int64_t)list[s / sub] * P.BK + (int64_t)(s % sub) * TK;
-            ap = a_tile + k0 * esz; bp = b_tile + k0 * ldb; al = TK; bl = b_lim;
-        } else if constexpr (OP == DW) {
-            const int64_t m0 = (int64_t)list[s / sub] * P.BM + (int64_t)(s % sub) * TK;
-            ap = a_tile + m0 * lda; bp = b_tile + m0 * ldb; al = a_lim; bl = b_lim;
-        } else {
-            const int64_t n0 = (int64_t)s * TK;
-            ap = a_tile + n0 * esz; bp = b_tile + n0 * esz;
-            { const int64_t left = P.N - n0; al = bl = left < TK ? (int)left : TK; }
-        }
-    };
-
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int wm = wave / WN, wn = wave % WN;
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -241,45 +351,132 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    uint4 ra[G::A_CHUNKS], rb[G::B_CHUNKS];
     if (nsteps > 0) {
-        const char *ap, *bp; int al, bl;
-        slice_ptrs(0, ap, bp, al, bl);
-        load_slice<G::A_ROWS, G::A_COLS, G::A_CHUNKS>(ra, ap, lda, al);
-        load_slice<G::B_ROWS, G::B_COLS, G::B_CHUNKS>(rb, bp, ldb, bl);
-        store_slice<G::A_ROWS, G::A_COLS, G::A_CHUNKS, G::SA>(ra, smem);
-        store_slice<G::B_ROWS, G::B_COLS, G::B_CHUNKS, G::SB>(rb, smem + G::A_BYTES);
-    }
-    __syncthreads();
+        using SliceA = Slice<A_KMAJ, TM, RAGGED && OP == DX>;
+        using SliceB = Slice<B_KMAJ, TN, RAGGED, DXG>;
+        SliceA ra;      // used only when !A_DMA
+        SliceB rb;      // used only when !B_DMA
 
-    for (int s = 0; s < nsteps; ++s) {
-        const bool more = s + 1 < nsteps;
-        if (more) {
-            const char *ap, *bp; int al, bl;
-            slice_ptrs(s + 1, ap, bp, al, bl);
-            load_slice<G::A_ROWS, G::A_COLS, G::A_CHUNKS>(ra, ap, lda, al);
-            load_slice<G::B_ROWS, G::B_COLS, G::B_CHUNKS>(rb, bp, ldb, bl);
+        // Kept-block indices: lane l of every wavefront holds entry 64*chunk + l of the list.
+        // refresh_for(s) must run (outside the scheduled code) before the loads of step s.
+        int idx_reg = 0, idx_chunk = -1;
+        auto refresh_for = [&](int s) {
+            if constexpr (OP != DX) {
+                const int sc = s < nsteps ? s : nsteps - 1;
+                const int chunk = (sc >> sub_shift) >> 6;
+                if (chunk != idx_chunk) {
+                    idx_chunk = chunk;
+                    const int e = chunk * 64 + lane;
+                    idx_reg = list[e < list_len ? e : list_len - 1];
+                }
+            }
+        };
+
+        // HBM addresses of slice s (clamped to the last slice: the pipeline runs two slices
+        // ahead and re-fetches the last one rather than branch)
+        struct Src { const char *a[1]; const char *b[DXG]; int lim; };
+        auto src_of = [&](int s) -> Src {
+            Src r;
+            const int sc = s < nsteps ? s : nsteps - 1;
+            if constexpr (OP == FWD) {
+                const int blk = __builtin_amdgcn_readlane(idx_reg, (sc >> sub_shift) & 63);
+                const int64_t k0 = (int64_t)blk * P.BK + (int64_t)(sc & ((1 << sub_shift) - 1)) * TK;
+                r.a[0] = a_tile + k0 * esz; r.b[0] = b_tile + k0 * ldb; r.lim = c_lim;
+            } else if constexpr (OP == DW) {
+                const int blk = __builtin_amdgcn_readlane(idx_reg, (sc >> sub_shift) & 63);
+                const int64_t m0 = (int64_t)blk * P.BM + (int64_t)(sc & ((1 << sub_shift) - 1)) * TK;
+                r.a[0] = a_tile + m0 * lda; r.b[0] = b_tile + m0 * ldb; r.lim = c_lim;
+            } else {
+                const int64_t n0 = (int64_t)sc * TK;
+                const int64_t left = P.N - n0;
+                r.lim = left < TK ? (int)left : TK;
+                r.a[0] = a_tile + n0 * esz;
+#pragma unroll
+                for (int g = 0; g < DXG; ++g) r.b[g] = bgrp[g] + n0 * esz;
+            }
+            return r;
+        };
+        auto a_lim = [&](const Src &x) { return OP == DX ? x.lim : (OP == FWD ? TK : TM); };
+
+        auto stage_ptr = [&](int st) -> char * { return smem + st * STAGE_BYTES; };
+        constexpr int NDMA_ITER = (A_DMA ? TM / 32 : 0) + (B_DMA ? TN / 32 : 0);   // per wavefront
+        constexpr int NREG_ITER = (A_DMA ? 0 : SliceA::NLOADS) + (B_DMA ? 0 : SliceB::NLOADS);
+
+        // ---- prologue.  Direct operands: slices 0 and 1 straight to stages 0 and 1.
+        //      Register operands: slice 0 to stage 0, slice 1 stays in registers. ----
+        {
+            refresh_for(0);
+            const Src s0 = src_of(0);
+            if constexpr (A_DMA) dma_slice<TM, 1, 0, 1>(s0.a, lda, stage_ptr(0));
+            if constexpr (B_DMA) dma_slice<TN, DXG, 0, 1>(s0.b, ldb, stage_ptr(0) + A_BYTES);
+            if constexpr (!A_DMA) { ra.load(s0.a, lda, a_lim(s0)); ra.template store<0, 1>(stage_ptr(0)); }
+            if constexpr (!B_DMA) { rb.load(s0.b, ldb, s0.lim); rb.template store<0, 1>(stage_ptr(0) + A_BYTES); }
+            refresh_for(1);
+            const Src s1 = src_of(1);
+            if constexpr (A_DMA) dma_slice<TM, 1, 0, 1>(s1.a, lda, stage_ptr(1));
+            if constexpr (B_DMA) dma_slice<TN, DXG, 0, 1>(s1.b, ldb, stage_ptr(1) + A_BYTES);
+            if constexpr (!A_DMA) ra.load(s1.a, lda, a_lim(s1));
+            if constexpr (!B_DMA) rb.load(s1.b, ldb, s1.lim);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+            __builtin_amdgcn_s_barrier();
         }
-        const char *sa = smem + (s & 1) * G::STAGE_BYTES;
-        const char *sb = sa + G::A_BYTES;
+
+        typename In<T>::vec fa[2][MI], fb[2][NI];
+        auto read_frags = [&](int buf, const char *st, int kk) {
 #pragma unroll
-        for (int kk = 0; kk < TK / 16; ++kk) {
-            typename In<T>::vec fa[MI], fb[NI];
+            for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = read_frag<T>(st, wm * WTM + mi * 32, kk);
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) fa[mi] = read_frag<T, G::A_KMAJ, G::SA>(sa, wm * WTM + mi * 32, kk);
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) fb[ni] = read_frag<T, G::B_KMAJ, G::SB>(sb, wn * WTN + ni * 32, kk);
+            for (int ni = 0; ni < NI; ++ni) fb[buf][ni] = read_frag<T>(st + A_BYTES, wn * WTN + ni * 32, kk);
+        };
+        auto mfmas = [&](int buf) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = In<T>::mfma(fa[mi], fb[ni], acc[mi][ni]);
+                for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = In<T>::mfma(fa[buf][mi], fb[buf][ni], acc[mi][ni]);
+        };
+        constexpr int NM = MI * NI, NFR = MI + NI;
+        constexpr int A_ST = A_DMA ? 0 : SliceA::NSTORES, A_PM = A_DMA ? 0 : SliceA::NPERMS;
+        constexpr int B_ST = B_DMA ? 0 : SliceB::NSTORES, B_PM = B_DMA ? 0 : SliceB::NPERMS;
+
+        int st0 = 0, st1 = 1, st2 = 2;      // stages of slices s, s+1, s+2
+        read_frags(0, stage_ptr(0), 0);
+
+        for (int s = 0; s < nsteps; ++s) {
+            // On entry: slice s complete in stage st0 and its kk=0 operands in flight to
+            // fa[0]/fb[0]; direct slice s+1 in flight to st1; register slice s+1 in (ra, rb).
+            const char *cur = stage_ptr(st0);
+            char *nx1 = stage_ptr(st1), *nx2 = stage_ptr(st2);
+            refresh_for(s + 2);
+            const Src s2 = src_of(s + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            // group 0: MFMAs kk=0 | operands kk=1; A: registers -> st1, or HBM -> st2; first half of B likewise
+            read_frags(1, cur, 1);
+            if constexpr (A_DMA) dma_slice<TM, 1, 0, 1>(s2.a, lda, nx2); else ra.template store<0, 1>(nx1);
+            if constexpr (B_DMA) dma_slice<TN, DXG, 0, 2>(s2.b, ldb, nx2 + A_BYTES); else rb.template store<0, 2>(nx1 + A_BYTES);
+            mfmas(0);
+            interleave<NM, NFR, A_PM + B_PM / 2 + 2 * NDMA_ITER, A_ST + B_ST / 2, (A_DMA ? TM / 32 : 0) + (B_DMA ? TN / 64 : 0)>();
+            // group 1: MFMAs kk=1 | operands kk=2; second half of B
+            read_frags(0, cur, 2);
+            if constexpr (B_DMA) dma_slice<TN, DXG, 1, 2>(s2.b, ldb, nx2 + A_BYTES); else rb.template store<1, 2>(nx1 + A_BYTES);
+            mfmas(1);
+            interleave<NM, NFR, B_PM / 2 + NDMA_ITER, B_ST / 2, B_DMA ? TN / 64 : 0>();
+            // group 2: MFMAs kk=2 | operands kk=3; register operands: global loads of slice s+2
+            read_frags(1, cur, 3);
+            if constexpr (!A_DMA) ra.load(s2.a, lda, a_lim(s2));
+            if constexpr (!B_DMA) rb.load(s2.b, ldb, s2.lim);
+            mfmas(0);
+            interleave<NM, NFR, 2 * NREG_ITER, 0, NREG_ITER>();
+            // everything of slice s+1 must have landed: this wavefront's direct loads of it
+            // (issued one iteration ago; only this iteration's may stay in flight) and LDS stores
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NDMA_ITER + NREG_ITER));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // group 3: MFMAs kk=3 | kk=0 operands of slice s+1
+            read_frags(0, nx1, 0);
+            mfmas(1);
+            interleave<NM, NFR, 0, 0, 0>();
+            const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
         }
-        if (more) {
-            char *da = smem + ((s + 1) & 1) * G::STAGE_BYTES;
-            store_slice<G::A_ROWS, G::A_COLS, G::A_CHUNKS, G::SA>(ra, da);
-            store_slice<G::B_ROWS, G::B_COLS, G::B_CHUNKS, G::SB>(rb, da + G::A_BYTES);
-        }
-        __syncthreads();
     }
 
     // epilogue: scale in fp32, round once, store.  Accumulator register r of lane l is
@@ -289,55 +486,73 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
-            const int col = wn * WTN + ni * 32 + (lane & 31);
-            if (col < c_lim) {
+            int col = wn * WTN + ni * 32 + (lane & 31);
+            char *cbase = c_tile;
+            bool ok = col < c_lim;
+            if constexpr (OP == DX) {
+                const int g = col >> 6;               // uniform per wavefront and ni
+                ok = g < chunks_valid;
+                cbase = cgrp[0];
+#pragma unroll
+                for (int gg = 1; gg < DXG; ++gg) cbase = (g == gg) ? cgrp[gg] : cbase;
+                col &= 63;
+            }
+            if (ok) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = wm * WTM + mi * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                    store_out(reinterpret_cast<OutT *>(c_tile + row * ldc) + col, acc[mi][ni][r] * scale);
+                    store_out(reinterpret_cast<OutT *>(cbase + row * ldc) + col, acc[mi][ni][r] * scale);
                 }
             }
         }
 }
 
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN>
-int launch(const GemmParams &P, int grid, hipStream_t stream)
+int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
 {
-    using G = Geometry<OP, TM, TN>;
-    auto kern = gemm_kernel<OP, T, OutT, TM, TN, WM, WN>;
+    constexpr int LDS_BYTES = kStages * (TM + TN) * TK * 2;
+    auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false>;
+    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, true>;
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_full),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_ragged),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return hip_status(e);
         attr_set = true;
     }
     if (grid <= 0) return SDROP_OK;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), G::LDS_BYTES, stream, P);
+    hipLaunchKernelGGL(ragged ? k_ragged : k_full, dim3(grid), dim3(kThreads), LDS_BYTES, stream, P);
     return hip_status(hipGetLastError());
 }
 
 // Tile shapes: the tile edge that lies along the mask must equal the mask's block
-// (Section 3.2); the N edge is free (Section 3.3) and is 256 where N allows.
+// (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
+// 256/BK kept blocks of one block row into a 256-wide tile.
 template <int OP, class T, class OutT>
 int dispatch_tile(GemmParams &P, hipStream_t stream)
 {
     if constexpr (OP == FWD) {
-        P.n_tiles_n = (int)((P.N + 255) / 256);
-        const int grid = P.MB * P.n_tiles_n;
-        if (P.BM == 128) return launch<FWD, T, OutT, 128, 256, 2, 2>(P, grid, stream);
-        return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, stream);
+        P.n_tiles = (int)((P.N + 255) / 256);
+        const int grid = P.MB * P.n_tiles;
+        const bool ragged = P.N % 256 != 0;
+        if (P.BM == 128) return launch<FWD, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
+        return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else if constexpr (OP == DW) {
-        P.n_tiles_n = (int)((P.N + 255) / 256);
-        const int grid = P.KB * P.n_tiles_n;
-        if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 2, 2>(P, grid, stream);
-        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, stream);
+        P.n_tiles = (int)((P.N + 255) / 256);
+        const int grid = P.KB * P.n_tiles;
+        const bool ragged = P.N % 256 != 0;
+        if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
+        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else {
-        const int grid = P.MB * P.KB;
-        if (P.BM == 128 && P.BK == 128) return launch<DX, T, OutT, 128, 128, 2, 2>(P, grid, stream);
-        if (P.BM == 128 && P.BK == 64) return launch<DX, T, OutT, 128, 64, 2, 2>(P, grid, stream);
-        if (P.BM == 64 && P.BK == 128) return launch<DX, T, OutT, 64, 128, 2, 2>(P, grid, stream);
-        return launch<DX, T, OutT, 64, 64, 2, 2>(P, grid, stream);
+        const int G_ = 256 / P.BK;
+        P.n_tiles = (P.KB + G_ - 1) / G_;
+        const int grid = P.MB * P.n_tiles;
+        const bool ragged = P.N % TK != 0;
+        if (P.BM == 128) return launch<DX, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
+        return launch<DX, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     }
 }
 
@@ -359,7 +574,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
     P.mv = make_view(mask, L);
     P.M = M; P.K = K; P.N = N; P.BM = BM; P.BK = BK;
     P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
-    P.n_tiles_n = 0;
+    P.n_tiles = 0;
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == SDROP_F16) {
