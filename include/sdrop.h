@@ -23,7 +23,8 @@
  *     Calls only enqueue work on it and return; no call synchronises with the
  *     host or copies to the host.
  *   - Block sizes must divide the shape (Section 2.2, footnote): BM | M and
- *     BK | K, with BM, BK in {64, 128}.  N must be a multiple of 8.
+ *     BK | K, with BM, BK in {64, 128}.  N must be a multiple of 8.  M <= 2^30,
+ *     K <= 2^24, N <= 2^24.
  *   - Inputs are fp16 or bf16 (SDROP_F16 / SDROP_BF16); products are
  *     accumulated in fp32 on the matrix cores; the scale s is applied to the
  *     fp32 accumulator; the result is rounded to nearest-even once, to

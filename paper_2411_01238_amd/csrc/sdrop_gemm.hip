@@ -35,6 +35,8 @@
 // row-wise stores, the transposed stores and the operand reads are all free of
 // bank conflicts without padding, which the direct loads require.
 #include "sdrop_internal.h"
+#include <type_traits>
+#include <utility>
 
 namespace sdrop {
 namespace {
@@ -67,6 +69,17 @@ template <> struct In<BF16> {
     }
 };
 
+// Compile-time loop: f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N-1>{}).
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 constexpr int TK = 64;           // reduction slice staged per step
 constexpr int kThreads = 256;    // 4 wavefronts per workgroup
 constexpr int kStages = 3;       // LDS stages
@@ -82,6 +95,7 @@ struct GemmParams {
     int32_t BM, BK, MB, KB;
     int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
     float scale;
+    double p;           // host only: dropout probability, for choosing tile shapes
 };
 
 // Slot swizzle of an LDS operand row: a 3-bit value XORed into the chunk index.
@@ -96,29 +110,83 @@ __device__ __forceinline__ int swz(int r)
 // Byte offset of 16-byte chunk c (0..7) of row r in an LDS operand tile.
 __device__ __forceinline__ int lds_off(int r, int c) { return r * 128 + (((c ^ swz(r)) & 7) << 4); }
 
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void gbl_void_t;
+// One global_load_lds_dwordx4: every lane moves 16 bytes from sbase + voff (uniform 64-bit base
+// plus 32-bit lane offset) to LDS byte address lds_base + 16*lane.  Written as inline assembly on
+// purpose: the compiler then does not know that LDS is written behind its back, and does not make
+// every later LDS read wait for ALL outstanding vector-memory operations (which is what it does
+// for the builtin form as soon as a transposing LDS read is involved, serialising the pipeline).
+// The price is that completion is tracked by hand: explicit s_waitcnt vmcnt(n) before the barrier
+// that publishes a slice.
+__device__ __forceinline__ void dma16(const char *sbase, uint32_t voff, const char *lds)
+{
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)lds;
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "{m0}"(lds_base));
+}
 
 // HBM -> LDS without registers, for an operand tile [ROWS][64] whose rows lie ld_bytes
-// apart in HBM.  One instruction of one wavefront fills 1 KiB = 8 LDS rows: lane l lands in
-// row 8*I + l/8, slot l%8, so it fetches chunk (l%8) ^ swz(row) of that row.  Wavefront w
-// issues instructions I = w, w+4, ...; instructions [PART*PER, (PART+1)*PER) of those.
-template <int ROWS, int NGRP, int PART, int NPARTS>
-__device__ __forceinline__ void dma_slice(const char *const (&base)[NGRP], int64_t ld_bytes, char *lds)
-{
-    constexpr int PER_WAVE = ROWS / 32, PER = PER_WAVE / NPARTS, GROUP_ROWS = ROWS / NGRP;
-    static_assert(PER_WAVE % NPARTS == 0 && GROUP_ROWS % 32 == 0, "bad split");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int i = PART * PER; i < (PART + 1) * PER; ++i) {
-        const int I = wave + 4 * i;                       // rows 8I .. 8I+7
-        const int g = (32 * i) / GROUP_ROWS;              // uniform: rows of pass i are 32i .. 32i+31
-        const int r = 8 * I + (lane >> 3);
-        const int c = (lane & 7) ^ swz(r);
-        const char *src = base[g] + (int64_t)(r - g * GROUP_ROWS) * ld_bytes + c * 16;
-        __builtin_amdgcn_global_load_lds((gbl_void_t *)src, (lds_void_t *)(lds + I * 1024), 16, 0, 0);
+// apart in HBM (reduction index contiguous).  One instruction of one wavefront fills
+// 1 KiB = 8 LDS rows: lane l lands in row 8*I + l/8, slot l%8, so it fetches chunk
+// (l%8) ^ swz(row) of that row.  Wavefront w issues instructions I = w + 4*i, i = 0 ..
+// ROWS/32 - 1.  Row of this lane in pass i is r = 32*i + r0; adding 32*i only flips bit 2 of
+// swz(r) for odd i, so two lane offsets (even / odd pass) serve every pass and the rest of
+// the address is uniform.
+template <int ROWS, int NGRP> struct DmaK {
+    static constexpr int PER_WAVE = ROWS / 32, GROUP_ROWS = ROWS / NGRP;
+    static_assert(GROUP_ROWS % 32 == 0, "row groups must cover whole passes");
+    uint32_t voff_even, voff_odd;
+    int wave;
+    __device__ __forceinline__ void init(int64_t ld_bytes)
+    {
+        const int lane = threadIdx.x & 63;
+        wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int r0 = 8 * wave + (lane >> 3);
+        const uint32_t row_off = (uint32_t)r0 * (uint32_t)ld_bytes;
+        voff_even = row_off + (((lane & 7) ^ swz(r0)) << 4);
+        voff_odd = row_off + (((lane & 7) ^ swz(r0) ^ 4) << 4);
     }
+    // pass i of this wavefront
+    __device__ __forceinline__ void issue(const char *const (&base)[NGRP], int64_t ld_bytes, char *lds, int i) const
+    {
+        const int g = (32 * i) / GROUP_ROWS;              // uniform: rows of pass i are 32i .. 32i+31
+        const char *sbase = base[g] + (int64_t)(32 * i - g * GROUP_ROWS) * ld_bytes;
+        dma16(sbase, (i & 1) ? voff_odd : voff_even, lds + (wave + 4 * i) * 1024);
+    }
+};
+
+// Slot swizzle of an LDS tile kept as it lies in HBM when the reduction index is the strided
+// one: [64 reduction rows][ROWS contiguous].  The transposing read of one 16-lane group
+// touches 4 consecutive rows x 32 bytes; XORing the 64-byte slot index with (row & 3) (with
+// (row>>1)&1 for 128-byte rows) keeps those rows on different banks.
+template <int ROWS> __device__ __forceinline__ int swz_t(int k)
+{
+    return ROWS >= 128 ? ((k & 3) << 2) : (((k >> 1) & 1) << 2);
 }
+
+// HBM -> LDS without registers for an operand tile [64][ROWS] (ROWS contiguous, rows ld_bytes
+// apart).  One instruction fills 1 KiB = 1024/(2*ROWS) tile rows; lane l lands at byte 16*l of
+// it and fetches the chunk whose swizzled slot that is.  Row k = RPI*I + kl with I = w + 4*i:
+// k & 3 (or (k>>1)&1) does not depend on i, so one lane offset serves every pass.
+template <int ROWS> struct DmaT {
+    static constexpr int ROW_BYTES = 2 * ROWS, RPI = 1024 / ROW_BYTES;       // rows per instruction
+    static constexpr int PER_WAVE = ROWS / 32;
+    static_assert(ROWS == 64 || ROWS == 128 || ROWS == 256, "unsupported tile edge");
+    uint32_t voff;
+    int wave;
+    __device__ __forceinline__ void init(int64_t ld_bytes)
+    {
+        const int lane = threadIdx.x & 63;
+        wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int kl = (lane * 16) / ROW_BYTES;              // row within the instruction
+        const int cpos = ((lane * 16) % ROW_BYTES) >> 4;     // 16-byte slot within the row
+        const int k0 = RPI * wave + kl;
+        voff = (uint32_t)kl * (uint32_t)ld_bytes + ((cpos ^ swz_t<ROWS>(k0)) << 4);
+    }
+    __device__ __forceinline__ void issue(const char *const (&base)[1], int64_t ld_bytes, char *lds, int i) const
+    {
+        const int I = wave + 4 * i;
+        dma16(base[0] + (int64_t)(RPI * I) * ld_bytes, voff, lds + I * 1024);
+    }
+};
 
 // A slice of an operand on its way from HBM to LDS through registers.
 //
@@ -144,7 +212,7 @@ template <bool KMAJ, int ROWS, bool RAGGED, int NGRP = 1> struct Slice {
     template <class V> __device__ __forceinline__ static V ld(const char *p, const char *safe, bool ok)
     {
         if constexpr (RAGGED) {
-            V v = *reinterpret_cast<const V *>(ok ? p : safe);
+            V v = *reinterpret_cast<const V *>(ok ? p : safe);   // `safe` is the (valid) start of the row
             V z = {};
             return ok ? v : z;
         } else {
@@ -152,33 +220,37 @@ template <bool KMAJ, int ROWS, bool RAGGED, int NGRP = 1> struct Slice {
         }
     }
 
-    // base[g]: start of row group g.  lim = valid elements along the contiguous dimension.
+    // base[g]: start of row group g (uniform).  lim = valid elements along the contiguous
+    // dimension.  Addresses are a uniform 64-bit base plus one 32-bit lane offset, so that the
+    // loads take the scalar-base form and no 64-bit lane addresses are kept in registers.
     __device__ __forceinline__ void load(const char *const (&base)[NGRP], int64_t ld_bytes, int lim)
     {
         if constexpr (KMAJ) {
+            const int cc = threadIdx.x & 7;
+            const uint32_t voff = (uint32_t)(threadIdx.x >> 3) * (uint32_t)ld_bytes + cc * 16;
+            const bool ok = cc * 8 < lim;
 #pragma unroll
             for (int q = 0; q < NCH; ++q) {
-                const int c = threadIdx.x + q * kThreads;
-                const int row = c >> 3, cc = c & 7;
                 const int g = (q * 32) / GROUP_ROWS;           // rows of pass q: 32q .. 32q+31
-                const int r = row - g * GROUP_ROWS;
-                const uint4 v = ld<uint4>(base[g] + r * ld_bytes + cc * 16, base[g], cc * 8 < lim);
+                const char *sbase = base[g] + (int64_t)(32 * q - g * GROUP_ROWS) * ld_bytes;
+                const uint4 v = ld<uint4>(sbase + voff, sbase, ok);
                 d[4 * q] = v.x; d[4 * q + 1] = v.y; d[4 * q + 2] = v.z; d[4 * q + 3] = v.w;
             }
         } else {
             const int ng = threadIdx.x & 31, kc = threadIdx.x >> 5;
-            const char *p = base[0] + (int64_t)(kc * 8) * ld_bytes + ng * (NW * 2);
+            const uint32_t voff = (uint32_t)(kc * 8) * (uint32_t)ld_bytes + ng * (NW * 2);
             const bool ok = ng * NW < lim;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
+                const char *sbase = base[0] + (int64_t)i * ld_bytes;
                 if constexpr (NW == 8) {
-                    const uint4 v = ld<uint4>(p + i * ld_bytes, base[0], ok);
+                    const uint4 v = ld<uint4>(sbase + voff, sbase, ok);
                     d[4 * i] = v.x; d[4 * i + 1] = v.y; d[4 * i + 2] = v.z; d[4 * i + 3] = v.w;
                 } else if constexpr (NW == 4) {
-                    const uint2 v = ld<uint2>(p + i * ld_bytes, base[0], ok);
+                    const uint2 v = ld<uint2>(sbase + voff, sbase, ok);
                     d[2 * i] = v.x; d[2 * i + 1] = v.y;
                 } else {
-                    d[i] = ld<uint32_t>(p + i * ld_bytes, base[0], ok);
+                    d[i] = ld<uint32_t>(sbase + voff, sbase, ok);
                 }
             }
         }
@@ -215,13 +287,27 @@ template <bool KMAJ, int ROWS, bool RAGGED, int NGRP = 1> struct Slice {
     }
 };
 
-// MFMA operand for the 32 rows starting at `base32` of an LDS operand tile, reduction
-// indices [kk*16, kk*16+16): lane l gets row base32 + l%32, reduction 8*(l/32)..+8.
-template <class T>
+// MFMA operand for the 32 rows (or columns) starting at `base32` of an LDS operand tile,
+// reduction indices [kk*16, kk*16+16): lane l gets index base32 + l%32, reduction 8*(l/32)..+8.
+// TR = false: tile [rows][64], one ds_read_b128.  TR = true: tile [64][ROWS] as in HBM, two
+// transposing reads (ds_read_b64_tr_b16): within a group of 16 lanes, lane q loads 4 elements
+// of row q/4 at columns 4*(q%4).. and receives column q of that 4 x 16 patch.
+template <class T, bool TR, int ROWS>
 __device__ __forceinline__ typename In<T>::vec read_frag(const char *lds, int base32, int kk)
 {
     const int l = threadIdx.x & 63;
-    return *reinterpret_cast<const typename In<T>::vec *>(lds + lds_off(base32 + (l & 31), kk * 2 + (l >> 5)));
+    if constexpr (!TR) {
+        return *reinterpret_cast<const typename In<T>::vec *>(lds + lds_off(base32 + (l & 31), kk * 2 + (l >> 5)));
+    } else {
+        constexpr int ROW_BYTES = 2 * ROWS;
+        const int k = kk * 16 + (l >> 5) * 8 + ((l & 15) >> 2);
+        const int col = base32 + ((l >> 4) & 1) * 16 + (l & 3) * 4;
+        const char *p = lds + k * ROW_BYTES + ((((col >> 3) ^ swz_t<ROWS>(k))) << 4) + ((col * 2) & 15);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * ROW_BYTES));
+        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(typename In<T>::vec, v);
+    }
 }
 
 template <class OutT> __device__ __forceinline__ void store_out(OutT *p, float v) { *p = static_cast<OutT>(v); }
@@ -254,8 +340,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
     constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
     static_assert(MI >= 1 && NI >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be 32-aligned");
     constexpr bool A_KMAJ = (OP != DW), B_KMAJ = (OP == DX);    // reduction index contiguous in HBM?
-    constexpr bool A_DMA = A_KMAJ && !(RAGGED && OP == DX);     // the reduction tail of DX needs zero fill
-    constexpr bool B_DMA = B_KMAJ && !RAGGED;
+    // Operands go HBM -> LDS directly unless a ragged edge needs zero fill (the reduction tail
+    // of DX, the N tail of W / dY in FWD / DW); those go through registers.
+    constexpr bool A_DMA = !(RAGGED && OP == DX);
+    constexpr bool B_DMA = !RAGGED;
+    // A directly loaded operand whose reduction index is strided in HBM stays in that form in
+    // LDS and is read with transposing reads.
+    constexpr bool A_TR = A_DMA && !A_KMAJ, B_TR = B_DMA && !B_KMAJ;
     constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int NGRP_MAX = 4;
 
@@ -357,64 +448,91 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
         SliceA ra;      // used only when !A_DMA
         SliceB rb;      // used only when !B_DMA
 
-        // Kept-block indices: lane l of every wavefront holds entry 64*chunk + l of the list.
-        // refresh_for(s) must run (outside the scheduled code) before the loads of step s.
-        int idx_reg = 0, idx_chunk = -1;
-        auto refresh_for = [&](int s) {
+        // Kept-block indices: lane l holds entries 64*ch + l (idx_a) and 64*(ch+1) + l (idx_b)
+        // of the list, so that positions up to 64 apart can be looked up.
+        int idx_a = 0, idx_b = 0, idx_ch = 0;
+        auto list_at = [&](int e) __attribute__((always_inline)) { return list[e < list_len ? e : list_len - 1]; };
+        if constexpr (OP != DX) { idx_a = list_at(lane); idx_b = list_at(64 + lane); }
+        // make the list position of step s available; runs outside the scheduled code
+        auto refresh_for = [&](int s) __attribute__((always_inline)) {
             if constexpr (OP != DX) {
                 const int sc = s < nsteps ? s : nsteps - 1;
-                const int chunk = (sc >> sub_shift) >> 6;
-                if (chunk != idx_chunk) {
-                    idx_chunk = chunk;
-                    const int e = chunk * 64 + lane;
-                    idx_reg = list[e < list_len ? e : list_len - 1];
+                if (((sc >> sub_shift) >> 6) > idx_ch + 1) {
+                    ++idx_ch;
+                    idx_a = idx_b;
+                    idx_b = list_at((idx_ch + 1) * 64 + lane);
                 }
             }
         };
+        auto block_at = [&](int pos) __attribute__((always_inline)) -> int {         // pos is uniform
+            const int va = __builtin_amdgcn_readlane(idx_a, pos & 63);
+            const int vb = __builtin_amdgcn_readlane(idx_b, pos & 63);
+            return (pos >> 6) == idx_ch ? va : vb;
+        };
 
-        // HBM addresses of slice s (clamped to the last slice: the pipeline runs two slices
-        // ahead and re-fetches the last one rather than branch)
-        struct Src { const char *a[1]; const char *b[DXG]; int lim; };
-        auto src_of = [&](int s) -> Src {
-            Src r;
+        // Position of slice s along the reduction, in elements (clamped to the last slice: the
+        // pipeline runs ahead of the loop and re-fetches the last slice rather than branch)
+        auto offset_of = [&](int s) __attribute__((always_inline)) -> int64_t {
             const int sc = s < nsteps ? s : nsteps - 1;
             if constexpr (OP == FWD) {
-                const int blk = __builtin_amdgcn_readlane(idx_reg, (sc >> sub_shift) & 63);
-                const int64_t k0 = (int64_t)blk * P.BK + (int64_t)(sc & ((1 << sub_shift) - 1)) * TK;
-                r.a[0] = a_tile + k0 * esz; r.b[0] = b_tile + k0 * ldb; r.lim = c_lim;
+                return (int64_t)block_at(sc >> sub_shift) * P.BK + (int64_t)(sc & ((1 << sub_shift) - 1)) * TK;
             } else if constexpr (OP == DW) {
-                const int blk = __builtin_amdgcn_readlane(idx_reg, (sc >> sub_shift) & 63);
-                const int64_t m0 = (int64_t)blk * P.BM + (int64_t)(sc & ((1 << sub_shift) - 1)) * TK;
-                r.a[0] = a_tile + m0 * lda; r.b[0] = b_tile + m0 * ldb; r.lim = c_lim;
+                return (int64_t)block_at(sc >> sub_shift) * P.BM + (int64_t)(sc & ((1 << sub_shift) - 1)) * TK;
             } else {
-                const int64_t n0 = (int64_t)sc * TK;
-                const int64_t left = P.N - n0;
+                return (int64_t)sc * TK;
+            }
+        };
+        // HBM addresses of the slice at reduction position `off`
+        struct Src { const char *a[1]; const char *b[DXG]; int lim; };
+        auto src_at = [&](int64_t off) __attribute__((always_inline)) -> Src {
+            Src r;
+            if constexpr (OP == FWD) {
+                r.a[0] = a_tile + off * esz; r.b[0] = b_tile + off * ldb; r.lim = c_lim;
+            } else if constexpr (OP == DW) {
+                r.a[0] = a_tile + off * lda; r.b[0] = b_tile + off * ldb; r.lim = c_lim;
+            } else {
+                const int64_t left = P.N - off;
                 r.lim = left < TK ? (int)left : TK;
-                r.a[0] = a_tile + n0 * esz;
+                r.a[0] = a_tile + off * esz;
 #pragma unroll
-                for (int g = 0; g < DXG; ++g) r.b[g] = bgrp[g] + n0 * esz;
+                for (int g = 0; g < DXG; ++g) r.b[g] = bgrp[g] + off * esz;
             }
             return r;
         };
-        auto a_lim = [&](const Src &x) { return OP == DX ? x.lim : (OP == FWD ? TK : TM); };
+        auto src_of = [&](int s) __attribute__((always_inline)) -> Src { return src_at(offset_of(s)); };
+        auto a_lim = [&](const Src &x) __attribute__((always_inline)) { return OP == DX ? x.lim : (OP == FWD ? TK : TM); };
 
-        auto stage_ptr = [&](int st) -> char * { return smem + st * STAGE_BYTES; };
-        constexpr int NDMA_ITER = (A_DMA ? TM / 32 : 0) + (B_DMA ? TN / 32 : 0);   // per wavefront
+        // direct-load engines (lane offsets computed once)
+        using DmaA = typename std::conditional<A_KMAJ, DmaK<TM, 1>, DmaT<TM>>::type;
+        using DmaB = typename std::conditional<B_KMAJ, DmaK<TN, DXG>, DmaT<TN>>::type;
+        DmaA da;
+        DmaB db;
+        if constexpr (A_DMA) da.init(lda);
+        if constexpr (B_DMA) db.init(ldb);
+        constexpr int NDMA_A = A_DMA ? TM / 32 : 0, NDMA_B = B_DMA ? TN / 32 : 0;     // per wavefront and slice
+        constexpr int NDMA_ITER = NDMA_A + NDMA_B;
+        // direct-load instruction j of a slice (A's first, then B's) into stage st
+        auto dma_one = [&](const Src &x, char *st, int j) __attribute__((always_inline)) {
+            if (j < NDMA_A) { if constexpr (A_DMA) da.issue(x.a, lda, st, j); }
+            else { if constexpr (B_DMA) db.issue(x.b, ldb, st + A_BYTES, j - NDMA_A); }
+        };
+        auto dma_range = [&](const Src &x, char *st, int j0, int j1) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = j0; j < j1; ++j) dma_one(x, st, j);
+        };
+
+        auto stage_ptr = [&](int st) __attribute__((always_inline)) -> char * { return smem + st * STAGE_BYTES; };
         constexpr int NREG_ITER = (A_DMA ? 0 : SliceA::NLOADS) + (B_DMA ? 0 : SliceB::NLOADS);
 
         // ---- prologue.  Direct operands: slices 0 and 1 straight to stages 0 and 1.
         //      Register operands: slice 0 to stage 0, slice 1 stays in registers. ----
         {
-            refresh_for(0);
             const Src s0 = src_of(0);
-            if constexpr (A_DMA) dma_slice<TM, 1, 0, 1>(s0.a, lda, stage_ptr(0));
-            if constexpr (B_DMA) dma_slice<TN, DXG, 0, 1>(s0.b, ldb, stage_ptr(0) + A_BYTES);
+            dma_range(s0, stage_ptr(0), 0, NDMA_ITER);
             if constexpr (!A_DMA) { ra.load(s0.a, lda, a_lim(s0)); ra.template store<0, 1>(stage_ptr(0)); }
             if constexpr (!B_DMA) { rb.load(s0.b, ldb, s0.lim); rb.template store<0, 1>(stage_ptr(0) + A_BYTES); }
-            refresh_for(1);
             const Src s1 = src_of(1);
-            if constexpr (A_DMA) dma_slice<TM, 1, 0, 1>(s1.a, lda, stage_ptr(1));
-            if constexpr (B_DMA) dma_slice<TN, DXG, 0, 1>(s1.b, ldb, stage_ptr(1) + A_BYTES);
+            dma_range(s1, stage_ptr(1), 0, NDMA_ITER);
             if constexpr (!A_DMA) ra.load(s1.a, lda, a_lim(s1));
             if constexpr (!B_DMA) rb.load(s1.b, ldb, s1.lim);
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
@@ -422,60 +540,112 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
         }
 
         typename In<T>::vec fa[2][MI], fb[2][NI];
-        auto read_frags = [&](int buf, const char *st, int kk) {
+        auto read_frags = [&](int buf, const char *st, int kk) __attribute__((always_inline)) {
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = read_frag<T>(st, wm * WTM + mi * 32, kk);
+            for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = read_frag<T, A_TR, TM>(st, wm * WTM + mi * 32, kk);
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) fb[buf][ni] = read_frag<T>(st + A_BYTES, wn * WTN + ni * 32, kk);
+            for (int ni = 0; ni < NI; ++ni) fb[buf][ni] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + ni * 32, kk);
         };
-        auto mfmas = [&](int buf) {
+        auto mfmas = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = In<T>::mfma(fa[buf][mi], fb[buf][ni], acc[mi][ni]);
         };
-        constexpr int NM = MI * NI, NFR = MI + NI;
-        constexpr int A_ST = A_DMA ? 0 : SliceA::NSTORES, A_PM = A_DMA ? 0 : SliceA::NPERMS;
-        constexpr int B_ST = B_DMA ? 0 : SliceB::NSTORES, B_PM = B_DMA ? 0 : SliceB::NPERMS;
+        constexpr int NM = MI * NI, NOPS = MI + NI;
+        constexpr int NFR = MI * (A_TR ? 2 : 1) + NI * (B_TR ? 2 : 1);              // LDS reads per operand set
 
         int st0 = 0, st1 = 1, st2 = 2;      // stages of slices s, s+1, s+2
         read_frags(0, stage_ptr(0), 0);
 
-        for (int s = 0; s < nsteps; ++s) {
-            // On entry: slice s complete in stage st0 and its kk=0 operands in flight to
-            // fa[0]/fb[0]; direct slice s+1 in flight to st1; register slice s+1 in (ra, rb).
-            const char *cur = stage_ptr(st0);
-            char *nx1 = stage_ptr(st1), *nx2 = stage_ptr(st2);
-            refresh_for(s + 2);
-            const Src s2 = src_of(s + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            // group 0: MFMAs kk=0 | operands kk=1; A: registers -> st1, or HBM -> st2; first half of B likewise
-            read_frags(1, cur, 1);
-            if constexpr (A_DMA) dma_slice<TM, 1, 0, 1>(s2.a, lda, nx2); else ra.template store<0, 1>(nx1);
-            if constexpr (B_DMA) dma_slice<TN, DXG, 0, 2>(s2.b, ldb, nx2 + A_BYTES); else rb.template store<0, 2>(nx1 + A_BYTES);
-            mfmas(0);
-            interleave<NM, NFR, A_PM + B_PM / 2 + 2 * NDMA_ITER, A_ST + B_ST / 2, (A_DMA ? TM / 32 : 0) + (B_DMA ? TN / 64 : 0)>();
-            // group 1: MFMAs kk=1 | operands kk=2; second half of B
-            read_frags(0, cur, 2);
-            if constexpr (B_DMA) dma_slice<TN, DXG, 1, 2>(s2.b, ldb, nx2 + A_BYTES); else rb.template store<1, 2>(nx1 + A_BYTES);
-            mfmas(1);
-            interleave<NM, NFR, B_PM / 2 + NDMA_ITER, B_ST / 2, B_DMA ? TN / 64 : 0>();
-            // group 2: MFMAs kk=2 | operands kk=3; register operands: global loads of slice s+2
-            read_frags(1, cur, 3);
-            if constexpr (!A_DMA) ra.load(s2.a, lda, a_lim(s2));
-            if constexpr (!B_DMA) rb.load(s2.b, ldb, s2.lim);
-            mfmas(0);
-            interleave<NM, NFR, 2 * NREG_ITER, 0, NREG_ITER>();
-            // everything of slice s+1 must have landed: this wavefront's direct loads of it
-            // (issued one iteration ago; only this iteration's may stay in flight) and LDS stores
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NDMA_ITER + NREG_ITER));
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            // group 3: MFMAs kk=3 | kk=0 operands of slice s+1
-            read_frags(0, nx1, 0);
-            mfmas(1);
-            interleave<NM, NFR, 0, 0, 0>();
-            const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+        if constexpr (A_DMA && B_DMA) {
+            // Every instruction has its place: MFMA c of a group is followed by its share of the
+            // group's operand reads and of the slice's direct loads, and nothing moves across
+            // the fence after it.  The direct loads of slice s+2 are spread over groups 0..2.
+            // All indices are compile-time so that operands and accumulators stay in registers.
+            int64_t nxt_off = offset_of(2);
+            for (int s = 0; s < nsteps; ++s) {
+                const char *cur = stage_ptr(st0);
+                const char *nx1 = stage_ptr(st1);
+                char *nx2 = stage_ptr(st2);
+                const Src s2 = src_at(nxt_off);
+                refresh_for(s + 3);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<4>([&](auto gi) __attribute__((always_inline)) {
+                    constexpr int g = decltype(gi)::value;
+                    if constexpr (g == 3) {
+                        // slice s+1 must have landed everywhere: this wavefront's direct loads of it
+                        // were issued one iteration ago; only this iteration's may stay in flight
+                        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NDMA_ITER));
+                        __builtin_amdgcn_s_barrier();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    static_for<NM>([&](auto ci) __attribute__((always_inline)) {
+                        constexpr int c = decltype(ci)::value;
+                        constexpr int mi = c / NI, ni = c % NI, cb = g & 1, nb = (g + 1) & 1;
+                        acc[mi][ni] = In<T>::mfma(fa[cb][mi], fb[cb][ni], acc[mi][ni]);
+                        // operands for the next group: kk = g+1 of this slice, or kk = 0 of slice s+1
+                        constexpr int r0 = c * NOPS / NM, r1 = (c + 1) * NOPS / NM;
+                        static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
+                            constexpr int r = r0 + decltype(ri)::value;
+                            const char *st = g < 3 ? cur : nx1;
+                            constexpr int kk = g < 3 ? g + 1 : 0;
+                            if constexpr (r < MI) fa[nb][r] = read_frag<T, A_TR, TM>(st, wm * WTM + r * 32, kk);
+                            else fb[nb][r - MI] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + (r - MI) * 32, kk);
+                        });
+                        if constexpr (g < 3) {
+                            constexpr int gc = g * NM + c;
+                            constexpr int j0 = gc * NDMA_ITER / (3 * NM), j1 = (gc + 1) * NDMA_ITER / (3 * NM);
+                            static_for<j1 - j0>([&](auto ji) __attribute__((always_inline)) {
+                                constexpr int j = j0 + decltype(ji)::value;
+                                if constexpr (j < NDMA_A) da.issue(s2.a, lda, nx2, j);
+                                else db.issue(s2.b, ldb, nx2 + A_BYTES, j - NDMA_A);
+                            });
+                        } else if constexpr (c == 0) {
+                            nxt_off = offset_of(s + 3);   // list lookup for the next iteration
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                });
+                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+            }
+        } else {
+            constexpr int A_ST = A_DMA ? 0 : SliceA::NSTORES, A_PM = A_DMA ? 0 : SliceA::NPERMS;
+            constexpr int B_ST = B_DMA ? 0 : SliceB::NSTORES, B_PM = B_DMA ? 0 : SliceB::NPERMS;
+            for (int s = 0; s < nsteps; ++s) {
+                // On entry: slice s complete in stage st0 and its kk=0 operands in flight to
+                // fa[0]/fb[0]; direct slice s+1 in flight to st1; register slice s+1 in (ra, rb).
+                const char *cur = stage_ptr(st0);
+                char *nx1 = stage_ptr(st1), *nx2 = stage_ptr(st2);
+                refresh_for(s + 2);
+                const Src s2 = src_of(s + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                // group 0: MFMAs kk=0 | operands kk=1; A: registers -> st1, or HBM -> st2; first half of B -> st1
+                read_frags(1, cur, 1);
+                if constexpr (A_DMA) dma_range(s2, nx2, 0, NDMA_A); else ra.template store<0, 1>(nx1);
+                rb.template store<0, 2>(nx1 + A_BYTES);
+                mfmas(0);
+                interleave<NM, NFR, A_PM + B_PM / 2 + 2 * NDMA_ITER, A_ST + B_ST / 2, 0>();
+                // group 1: MFMAs kk=1 | operands kk=2; second half of B
+                read_frags(0, cur, 2);
+                rb.template store<1, 2>(nx1 + A_BYTES);
+                mfmas(1);
+                interleave<NM, NFR, B_PM / 2, B_ST / 2, 0>();
+                // group 2: MFMAs kk=2 | operands kk=3; register operands: global loads of slice s+2
+                read_frags(1, cur, 3);
+                if constexpr (!A_DMA) ra.load(s2.a, lda, a_lim(s2));
+                rb.load(s2.b, ldb, s2.lim);
+                mfmas(0);
+                interleave<NM, NFR, 2 * NREG_ITER, 0, NREG_ITER>();
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NDMA_ITER + NREG_ITER));
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                // group 3: MFMAs kk=3 | kk=0 operands of slice s+1
+                read_frags(0, nx1, 0);
+                mfmas(1);
+                interleave<NM, NFR, 0, 0, 0>();
+                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+            }
         }
     }
 
@@ -528,6 +698,20 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+int cu_count()
+{
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
 // Tile shapes: the tile edge that lies along the mask must equal the mask's block
 // (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
 // 256/BK kept blocks of one block row into a 256-wide tile.
@@ -538,21 +722,37 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         P.n_tiles = (int)((P.N + 255) / 256);
         const int grid = P.MB * P.n_tiles;
         const bool ragged = P.N % 256 != 0;
-        if (P.BM == 128) return launch<FWD, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
+        if (P.BM == 128) return launch<FWD, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
         return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else if constexpr (OP == DW) {
         P.n_tiles = (int)((P.N + 255) / 256);
         const int grid = P.KB * P.n_tiles;
         const bool ragged = P.N % 256 != 0;
-        if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
+        if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
         return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else {
-        const int G_ = 256 / P.BK;
+        // Every kept block costs the same, so the launch runs in ceil(tiles / CUs) rounds of
+        // equal tiles.  A 256-wide tile moves a quarter less data per flop than two 128-wide
+        // ones (about 2/3 of the time of the wide tile each); take whichever shape is expected
+        // to finish first for the expected number of kept blocks, (1-p) MB KB.
+        const double kept = (1.0 - P.p) * (double)P.MB * (double)P.KB;
+        const int ncu = cu_count();
+        auto rounds = [&](int tn) {
+            const int g = tn / P.BK;
+            const double tiles = kept / g + (g > 1 ? 0.5 * P.MB : 0.0);   // a partly filled group per block row
+            return (double)((int64_t)((tiles + ncu - 1) / ncu));
+        };
+        const int TNsel = (rounds(128) * (2.0 / 3.0) < rounds(256)) ? 128 : 256;
+        const int G_ = TNsel / P.BK;
         P.n_tiles = (P.KB + G_ - 1) / G_;
         const int grid = P.MB * P.n_tiles;
         const bool ragged = P.N % TK != 0;
-        if (P.BM == 128) return launch<DX, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
-        return launch<DX, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
+        if (TNsel == 256) {
+            if (P.BM == 128) return launch<DX, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
+            return launch<DX, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
+        }
+        if (P.BM == 128) return launch<DX, T, OutT, 128, 128, 2, 2>(P, grid, ragged, stream);
+        return launch<DX, T, OutT, 64, 128, 1, 4>(P, grid, ragged, stream);
     }
 }
 
@@ -576,6 +776,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
     P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
     P.n_tiles = 0;
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
+    P.p = p;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == SDROP_F16) {
         if (out_dtype == SDROP_F32) return dispatch_tile<OP, F16, float>(P, st);
@@ -598,7 +799,8 @@ int check_gemm_args(const void *a, const void *b, const void *mask, void *out,
     sdrop_mask_layout_t L;
     const int rc = sdrop_mask_layout(M, K, BM, BK, &L);
     if (rc != SDROP_OK) return rc;
-    if (M > (int64_t(1) << 30) || K > (int64_t(1) << 30) || N > (int64_t(1) << 30)) return SDROP_ESHAPE;
+    // lane offsets inside a slice are 32-bit: up to 64 rows of K or N 16-bit elements
+    if (M > (int64_t(1) << 30) || K > (int64_t(1) << 24) || N > (int64_t(1) << 24)) return SDROP_ESHAPE;
     if (dtype != SDROP_F16 && dtype != SDROP_BF16) return SDROP_EDTYPE;
     if (out_dtype != dtype && out_dtype != SDROP_F32) return SDROP_EDTYPE;
     const uintptr_t bits = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) |

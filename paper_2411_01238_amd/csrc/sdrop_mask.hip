@@ -97,8 +97,10 @@ __device__ void block_inclusive_scan(int32_t *a, int n, int32_t *wave_tot /* LDS
 // order[] := indices 0..n-1 sorted by descending cnt(i) = ptr[i+1]-ptr[i] (counting
 // sort; ties land in unspecified order).  max_cnt is the upper bound of cnt.
 __device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t *order,
-                                 int32_t *bins /* LDS[kMaxBins+1] */, int32_t *wave_tot)
+                                 int32_t *bins /* LDS[kMaxBins+1] */, int32_t *wave_tot,
+                                 int32_t *largest /* LDS: receives the largest count */)
 {
+    if (threadIdx.x == 0) *largest = 0;
     const int nb = (max_cnt < kMaxBins ? max_cnt : kMaxBins) + 1;
     for (int b = threadIdx.x; b < nb; b += kMaskThreads) bins[b] = 0;
     __syncthreads();
@@ -106,7 +108,11 @@ __device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t
         const int b = (max_cnt <= kMaxBins) ? cnt : int((int64_t)cnt * kMaxBins / max_cnt);
         return nb - 1 - b;             // bin 0 holds the largest counts
     };
-    for (int i = threadIdx.x; i < n; i += kMaskThreads) atomicAdd(&bins[bin_of(ptr[i + 1] - ptr[i])], 1);
+    for (int i = threadIdx.x; i < n; i += kMaskThreads) {
+        const int cnt = ptr[i + 1] - ptr[i];
+        atomicAdd(&bins[bin_of(cnt)], 1);
+        atomicMax(largest, cnt);
+    }
     __syncthreads();
     block_inclusive_scan(bins, nb, wave_tot);
     // bins[b] is now the END of bin b; claim slots from the end backwards
@@ -117,11 +123,25 @@ __device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t
     __syncthreads();
 }
 
+// Limits of the variant that keeps the bits and both pointer arrays in LDS between phases.
+constexpr int kLdsWords = 2048;   // MB * words_per_row
+constexpr int kLdsPtrs = 2048;    // MB, KB
+
+// IN_LDS: bits, row_ptr and col_ptr live in LDS while the lists are built and are copied
+// out once, so that no phase waits on a round trip to HBM.  Otherwise (large block grids)
+// the same phases run on the global arrays.
+template <bool IN_LDS>
 __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
 {
     __shared__ int32_t wave_tot[kMaskWaves + 1];
     __shared__ int32_t bins[kMaxBins + 1];
+    __shared__ uint64_t s_bits[IN_LDS ? kLdsWords : 1];
+    __shared__ int32_t s_row_ptr[IN_LDS ? kLdsPtrs + 1 : 1];
+    __shared__ int32_t s_col_ptr[IN_LDS ? kLdsPtrs + 1 : 1];
     const int lane = lane_id(), wave = wave_id();
+    uint64_t *const bits = IN_LDS ? s_bits : P.bits;
+    int32_t *const row_ptr = IN_LDS ? s_row_ptr : P.row_ptr;
+    int32_t *const col_ptr = IN_LDS ? s_col_ptr : P.col_ptr;
 
     // -- rows: draw (or fetch) the keep bits, store packed words, count per row --
     for (int i = wave; i < P.MB; i += kMaskWaves) {
@@ -140,20 +160,25 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
                 }
             }
             const uint64_t word = __ballot(keep);
-            if (lane == 0) P.bits[(int64_t)i * P.wpr + w] = word;
+            if (lane == 0) {
+                bits[(int64_t)i * P.wpr + w] = word;
+                if (IN_LDS) P.bits[(int64_t)i * P.wpr + w] = word;
+            }
             cnt += __popcll(word);
         }
-        if (lane == 0) P.row_ptr[i + 1] = cnt;
+        if (lane == 0) row_ptr[i + 1] = cnt;
     }
-    if (threadIdx.x == 0) P.row_ptr[0] = 0;
+    if (threadIdx.x == 0) row_ptr[0] = 0;
     __syncthreads();
-    block_inclusive_scan(P.row_ptr + 1, P.MB, wave_tot);
+    block_inclusive_scan(row_ptr + 1, P.MB, wave_tot);
+    if (IN_LDS)
+        for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = row_ptr[i];
 
     // -- rows again: scatter kept columns to their slots --
     for (int i = wave; i < P.MB; i += kMaskWaves) {
-        int pos = P.row_ptr[i];
+        int pos = row_ptr[i];
         for (int w = 0; w < P.wpr; ++w) {
-            const uint64_t word = P.bits[(int64_t)i * P.wpr + w];
+            const uint64_t word = bits[(int64_t)i * P.wpr + w];
             if ((word >> lane) & 1) {
                 const int at = pos + __popcll(word & lanes_below());
                 P.col_idx[at] = w * 64 + lane;
@@ -168,19 +193,21 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
         int cnt = 0;
         for (int i0 = 0; i0 < P.MB; i0 += 64) {
             const int i = i0 + lane;
-            const bool keep = (i < P.MB) && ((P.bits[(int64_t)i * P.wpr + (j >> 6)] >> (j & 63)) & 1);
+            const bool keep = (i < P.MB) && ((bits[(int64_t)i * P.wpr + (j >> 6)] >> (j & 63)) & 1);
             cnt += __popcll(__ballot(keep));
         }
-        if (lane == 0) P.col_ptr[j + 1] = cnt;
+        if (lane == 0) col_ptr[j + 1] = cnt;
     }
-    if (threadIdx.x == 0) P.col_ptr[0] = 0;
+    if (threadIdx.x == 0) col_ptr[0] = 0;
     __syncthreads();
-    block_inclusive_scan(P.col_ptr + 1, P.KB, wave_tot);
+    block_inclusive_scan(col_ptr + 1, P.KB, wave_tot);
+    if (IN_LDS)
+        for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = col_ptr[j];
     for (int j = wave; j < P.KB; j += kMaskWaves) {
-        int pos = P.col_ptr[j];
+        int pos = col_ptr[j];
         for (int i0 = 0; i0 < P.MB; i0 += 64) {
             const int i = i0 + lane;
-            const bool keep = (i < P.MB) && ((P.bits[(int64_t)i * P.wpr + (j >> 6)] >> (j & 63)) & 1);
+            const bool keep = (i < P.MB) && ((bits[(int64_t)i * P.wpr + (j >> 6)] >> (j & 63)) & 1);
             const uint64_t word = __ballot(keep);
             if (keep) P.row_idx[pos + __popcll(word & lanes_below())] = i;
             pos += __popcll(word);
@@ -188,17 +215,18 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     }
 
     // -- schedules: heavy rows / columns first --
-    descending_order(P.row_ptr, P.MB, P.KB, P.row_order, bins, wave_tot);
-    descending_order(P.col_ptr, P.KB, P.MB, P.col_order, bins, wave_tot);
+    __shared__ int32_t s_first[2];
+    descending_order(row_ptr, P.MB, P.KB, P.row_order, bins, wave_tot, &s_first[0]);
+    descending_order(col_ptr, P.KB, P.MB, P.col_order, bins, wave_tot, &s_first[1]);
 
     if (threadIdx.x == 0) {
         MaskHeader h = {};
         h.M = P.M; h.K = P.K; h.BM = P.BM; h.BK = P.BK; h.MB = P.MB; h.KB = P.KB;
         h.words_per_row = P.wpr;
-        h.nnz = P.row_ptr[P.MB];
+        h.nnz = row_ptr[P.MB];
         h.magic = kMaskMagic;
-        h.max_row_cnt = P.MB > 0 ? P.row_ptr[P.row_order[0] + 1] - P.row_ptr[P.row_order[0]] : 0;
-        h.max_col_cnt = P.KB > 0 ? P.col_ptr[P.col_order[0] + 1] - P.col_ptr[P.col_order[0]] : 0;
+        h.max_row_cnt = s_first[0];
+        h.max_col_cnt = s_first[1];
         *P.hdr = h;
     }
 }
@@ -236,7 +264,11 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     P.key0 = static_cast<uint32_t>(seed); P.key1 = static_cast<uint32_t>(seed >> 32);
     P.ctr2 = static_cast<uint32_t>(rng_stream); P.ctr3 = static_cast<uint32_t>(rng_stream >> 32);
     P.threshold = static_cast<uint64_t>(floor(p * 4294967296.0));
-    hipLaunchKernelGGL(mask_kernel, dim3(1), dim3(kMaskThreads), 0, static_cast<hipStream_t>(stream), P);
+    const bool in_lds = L.MB * L.words_per_row <= kLdsWords && L.MB <= kLdsPtrs && L.KB <= kLdsPtrs;
+    if (in_lds)
+        hipLaunchKernelGGL(mask_kernel<true>, dim3(1), dim3(kMaskThreads), 0, static_cast<hipStream_t>(stream), P);
+    else
+        hipLaunchKernelGGL(mask_kernel<false>, dim3(1), dim3(kMaskThreads), 0, static_cast<hipStream_t>(stream), P);
     return hip_status(hipGetLastError());
 }
 
