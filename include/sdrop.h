@@ -129,7 +129,13 @@ int sdrop_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int 
 int sdrop_mask_from_bits(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
                          const uint64_t *bits, void *stream);
 
-/* Bytes of device workspace an operation needs for these arguments (may be 0). */
+/*
+ * Bytes of device workspace an operation needs for these arguments (may be 0).  Only
+ * sdrop_bwd_dw uses one: when K/BK * ceil(N/256) output tiles are too few to fill the chip,
+ * the reduction over M is cut into `splits` parts that write fp32 planes [splits][K][N] to
+ * the workspace, summed in a fixed order by a second pass.  A function of the shape and of
+ * the device's CU count only.
+ */
 size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, int BK,
                              int dtype, int out_dtype);
 

@@ -94,6 +94,7 @@ struct GemmParams {
     int64_t M, K, N;
     int32_t BM, BK, MB, KB;
     int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
+    int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)
     float scale;
     double p;           // host only: dropout probability, for choosing tile shapes
 };
@@ -388,17 +389,23 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
         c_tile = P.C + (int64_t)i * P.BM * ldc + (int64_t)nt * TN * sizeof(OutT);
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
     } else if constexpr (OP == DW) {
+        // blockIdx.x = (rank of block column j in the schedule, N tile, part of the list)
         const int t = blockIdx.x;
-        const int j = P.mv.col_order[t / P.n_tiles], nt = t % P.n_tiles;
+        const int per_col = P.n_tiles * P.splits;
+        const int j = P.mv.col_order[t / per_col];
+        const int nt = (t % per_col) / P.splits, part = t % P.splits;
         const int cp = P.mv.col_ptr[j];
-        list = P.mv.row_idx + cp;
-        list_len = P.mv.col_ptr[j + 1] - cp;
+        const int cnt = P.mv.col_ptr[j + 1] - cp;
+        const int lo = (int)((int64_t)cnt * part / P.splits), hi = (int)((int64_t)cnt * (part + 1) / P.splits);
+        list = P.mv.row_idx + cp + lo;
+        list_len = hi - lo;
         sub_shift = (P.BM == 128);
         nsteps = list_len << sub_shift;
         lda = P.K * esz; ldb = P.N * esz; ldc = P.N * (int64_t)sizeof(OutT);
         a_tile = P.A + (int64_t)j * P.BK * esz;
         b_tile = P.B + (int64_t)nt * TN * esz;
-        c_tile = P.C + (int64_t)j * P.BK * ldc + (int64_t)nt * TN * sizeof(OutT);
+        // with a split list, part `part` writes its own K x N plane of partial sums
+        c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)j * P.BK * ldc + (int64_t)nt * TN * sizeof(OutT);
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
     } else {
         // blockIdx.x = q * MB + i.  The workgroup computes the kept blocks of ranks
@@ -698,6 +705,40 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// out[e] = scale * sum_c part[c][e], rounded once (the second pass of a split DW)
+template <class OutT>
+__global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, OutT *out, int64_t n, int splits, float scale)
+{
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= n) return;
+    float4 acc = *reinterpret_cast<const float4 *>(part + e);
+    for (int c = 1; c < splits; ++c) {
+        const float4 v = *reinterpret_cast<const float4 *>(part + (int64_t)c * n + e);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    out[e] = static_cast<OutT>(acc.x * scale); out[e + 1] = static_cast<OutT>(acc.y * scale);
+    out[e + 2] = static_cast<OutT>(acc.z * scale); out[e + 3] = static_cast<OutT>(acc.w * scale);
+}
+
+int cu_count();
+
+// Parts the reduction of DW is cut into.  DW has only KB * ceil(N/256) output tiles; when
+// that is fewer than the chip has CUs, each block column's kept-row list is cut into parts
+// computed by different workgroups into fp32 planes that a second pass sums in a fixed
+// order (deterministic, unlike atomics).  A pure function of the shape (not of p), so that
+// the workspace size can be asked for without the mask.
+int dw_splits(int64_t M, int64_t N, int BM, int BK, int64_t K)
+{
+    const int64_t tiles = (K / BK) * ((N + 255) / 256);
+    const int64_t ncu = cu_count();
+    if (tiles >= ncu) return 1;
+    int64_t s = (2 * ncu + tiles - 1) / tiles;            // aim at two waves of workgroups
+    const int64_t max_by_len = (M / BM) / 4;              // keep at least ~4 row blocks per part
+    if (s > max_by_len) s = max_by_len;
+    if (s > 16) s = 16;
+    return s < 1 ? 1 : (int)s;
+}
+
 int cu_count()
 {
     static int n = 0;
@@ -726,23 +767,24 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else if constexpr (OP == DW) {
         P.n_tiles = (int)((P.N + 255) / 256);
-        const int grid = P.KB * P.n_tiles;
+        const int grid = P.KB * P.n_tiles * P.splits;
         const bool ragged = P.N % 256 != 0;
         if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
         return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else {
         // Every kept block costs the same, so the launch runs in ceil(tiles / CUs) rounds of
         // equal tiles.  A 256-wide tile moves a quarter less data per flop than two 128-wide
-        // ones (about 2/3 of the time of the wide tile each); take whichever shape is expected
+        // ones (a 128-wide tile was measured at 0.6 of the time of a wide one); take whichever shape is expected
         // to finish first for the expected number of kept blocks, (1-p) MB KB.
         const double kept = (1.0 - P.p) * (double)P.MB * (double)P.KB;
         const int ncu = cu_count();
         auto rounds = [&](int tn) {
             const int g = tn / P.BK;
-            const double tiles = kept / g + (g > 1 ? 0.5 * P.MB : 0.0);   // a partly filled group per block row
+            // groups of g kept blocks per block row; a random row leaves (g-1)/2g of a group unfilled
+            const double tiles = kept / g + (P.p > 0.0 ? P.MB * (g - 1) / (2.0 * g) : 0.0);
             return (double)((int64_t)((tiles + ncu - 1) / ncu));
         };
-        const int TNsel = (rounds(128) * (2.0 / 3.0) < rounds(256)) ? 128 : 256;
+        const int TNsel = (rounds(128) * 0.6 < rounds(256)) ? 128 : 256;
         const int G_ = TNsel / P.BK;
         P.n_tiles = (P.KB + G_ - 1) / G_;
         const int grid = P.MB * P.n_tiles;
@@ -763,8 +805,8 @@ int run(const void *a, const void *b, const void *mask, void *out,
 {
     const int rc = check_gemm_args(a, b, mask, out, M, K, N, BM, BK, p, dtype, out_dtype);
     if (rc != SDROP_OK) return rc;
-    if (ws_bytes < sdrop_workspace_bytes(OP, M, K, N, BM, BK, dtype, out_dtype)) return SDROP_EWORKSPACE;
-    (void)ws;
+    const size_t ws_need = sdrop_workspace_bytes(OP, M, K, N, BM, BK, dtype, out_dtype);
+    if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
     sdrop_mask_layout_t L;
     sdrop_mask_layout(M, K, BM, BK, &L);
     GemmParams P;
@@ -775,9 +817,31 @@ int run(const void *a, const void *b, const void *mask, void *out,
     P.M = M; P.K = K; P.N = N; P.BM = BM; P.BK = BK;
     P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
     P.n_tiles = 0;
+    P.splits = 1;
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
     P.p = p;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if constexpr (OP == DW) {
+        P.splits = dw_splits(M, N, BM, BK, K);
+        if (P.splits > 1) {
+            // first pass: unscaled fp32 partial planes into the workspace; second pass: sum, scale, round
+            const float scale = P.scale;
+            P.C = static_cast<char *>(ws);
+            P.scale = 1.0f;
+            const int rc1 = (dtype == SDROP_F16) ? dispatch_tile<OP, F16, float>(P, st) : dispatch_tile<OP, BF16, float>(P, st);
+            if (rc1 != SDROP_OK) return rc1;
+            const int64_t n = K * N;
+            const unsigned grid = (unsigned)((n / 4 + 255) / 256);
+            const float *part = static_cast<const float *>(ws);
+            if (out_dtype == SDROP_F32)
+                hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, P.splits, scale);
+            else if (dtype == SDROP_F16)
+                hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, P.splits, scale);
+            else
+                hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, P.splits, scale);
+            return hip_status(hipGetLastError());
+        }
+    }
     if (dtype == SDROP_F16) {
         if (out_dtype == SDROP_F32) return dispatch_tile<OP, F16, float>(P, st);
         return dispatch_tile<OP, F16, _Float16>(P, st);
@@ -816,8 +880,11 @@ extern "C" {
 size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, int BK,
                              int dtype, int out_dtype)
 {
-    (void)op; (void)M; (void)K; (void)N; (void)BM; (void)BK; (void)dtype; (void)out_dtype;
-    return 0;
+    (void)dtype; (void)out_dtype;
+    if (op != SDROP_OP_BWD_DW) return 0;
+    if (M <= 0 || K <= 0 || N <= 0 || !sdrop::block_size_ok(BM) || !sdrop::block_size_ok(BK) || M % BM || K % BK) return 0;
+    const int splits = sdrop::dw_splits(M, N, BM, BK, K);
+    return splits > 1 ? (size_t)splits * (size_t)K * (size_t)N * sizeof(float) : 0;
 }
 
 int sdrop_fwd(const void *X, const void *W, const void *mask, void *Y,

@@ -2,14 +2,15 @@
 // Sections 3.2 and 3.4), plus the small host-side pieces of the C ABI that are
 // not GEMMs (layout, error text).
 //
-// One launch of one 1024-thread workgroup does everything: the mask of the
-// largest workload here has 16384 blocks, so the job is latency, not
-// throughput, and a single workgroup needs no cross-workgroup scan.  A wavefront
-// owns a block row (lane <-> block column): its 64-lane ballot IS the packed
-// 64-bit mask word of Section 3.4, and popcount(ballot & lanes-below) is the
-// position of a kept block inside its row's list.  Row totals are turned into
-// row_ptr by a workgroup prefix scan.  The column lists (what eq. 3 walks) are
-// built the same way with lane <-> block row, reading the bits just written.
+// Two launches.  (1) The draw: one wavefront per 64 blocks of a block row (lane <-> block
+// column), spread over the whole chip because ten Philox rounds per block are integer-multiply
+// bound; the 64-lane ballot of the keep decisions IS the packed 64-bit mask word of
+// Section 3.4.  (2) The lists: one 1024-thread workgroup turns the words into every index
+// list.  The largest mask here has 16384 blocks, so this part is latency, not throughput,
+// and a single workgroup needs no cross-workgroup scan: a wavefront owns a block row,
+// popcount(word & lanes-below) is the position of a kept block inside its row's list, row
+// totals become row_ptr by a workgroup prefix scan, and the column lists (what eq. 3 walks)
+// are built the same way with lane <-> block row.
 #include "sdrop_internal.h"
 #include <math.h>
 
@@ -123,6 +124,25 @@ __device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t
     __syncthreads();
 }
 
+// The draw: wavefront gid handles word gid of the packed mask (row gid / wpr, word gid % wpr).
+__global__ __launch_bounds__(256) void mask_draw_kernel(MaskParams P)
+{
+    const int lane = lane_id();
+    const int64_t gid = (int64_t)blockIdx.x * 4 + wave_id();
+    if (gid >= (int64_t)P.MB * P.wpr) return;
+    const int64_t i = gid / P.wpr;
+    const int w = (int)(gid % P.wpr);
+    const int j = w * 64 + lane;
+    bool keep = false;
+    if (j < P.KB) {
+        const uint64_t b = (uint64_t)i * (uint64_t)P.KB + (uint64_t)j;
+        const uint32_t r = philox_word0((uint32_t)b, (uint32_t)(b >> 32), P.ctr2, P.ctr3, P.key0, P.key1);
+        keep = (uint64_t)r >= P.threshold;
+    }
+    const uint64_t word = __ballot(keep);
+    if (lane == 0) P.bits[gid] = word;
+}
+
 // Limits of the variant that keeps the bits and both pointer arrays in LDS between phases.
 constexpr int kLdsWords = 2048;   // MB * words_per_row
 constexpr int kLdsPtrs = 2048;    // MB, KB
@@ -143,30 +163,22 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     int32_t *const row_ptr = IN_LDS ? s_row_ptr : P.row_ptr;
     int32_t *const col_ptr = IN_LDS ? s_col_ptr : P.col_ptr;
 
-    // -- rows: draw (or fetch) the keep bits, store packed words, count per row --
-    for (int i = wave; i < P.MB; i += kMaskWaves) {
+    // -- rows: fetch the packed words (drawn by mask_draw_kernel, or given by the caller with
+    //    possibly dirty padding bits), count per row --
+    const uint64_t *src_bits = P.given_bits ? P.given_bits : P.bits;
+    for (int64_t g = threadIdx.x; g < (int64_t)P.MB * P.wpr; g += kMaskThreads) {
+        const int w = (int)(g % P.wpr);
+        const int valid = P.KB - w * 64;                 // columns covered by this word
+        uint64_t word = src_bits[g];
+        if (valid < 64) word &= (uint64_t(1) << valid) - 1;
+        if (IN_LDS) bits[g] = word;
+        if (IN_LDS || P.given_bits) P.bits[g] = word;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
         int cnt = 0;
-        for (int w = 0; w < P.wpr; ++w) {
-            const int j = w * 64 + lane;
-            bool keep = false;
-            if (j < P.KB) {
-                if (P.given_bits) {
-                    keep = (P.given_bits[(int64_t)i * P.wpr + w] >> lane) & 1;
-                } else {
-                    const uint64_t b = (uint64_t)i * (uint64_t)P.KB + (uint64_t)j;
-                    const uint32_t r = philox_word0((uint32_t)b, (uint32_t)(b >> 32), P.ctr2, P.ctr3,
-                                                    P.key0, P.key1);
-                    keep = (uint64_t)r >= P.threshold;
-                }
-            }
-            const uint64_t word = __ballot(keep);
-            if (lane == 0) {
-                bits[(int64_t)i * P.wpr + w] = word;
-                if (IN_LDS) P.bits[(int64_t)i * P.wpr + w] = word;
-            }
-            cnt += __popcll(word);
-        }
-        if (lane == 0) row_ptr[i + 1] = cnt;
+        for (int w = 0; w < P.wpr; ++w) cnt += __popcll(bits[(int64_t)i * P.wpr + w]);
+        row_ptr[i + 1] = cnt;
     }
     if (threadIdx.x == 0) row_ptr[0] = 0;
     __syncthreads();
@@ -264,11 +276,18 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     P.key0 = static_cast<uint32_t>(seed); P.key1 = static_cast<uint32_t>(seed >> 32);
     P.ctr2 = static_cast<uint32_t>(rng_stream); P.ctr3 = static_cast<uint32_t>(rng_stream >> 32);
     P.threshold = static_cast<uint64_t>(floor(p * 4294967296.0));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!given_bits) {
+        const int64_t words = L.MB * L.words_per_row;
+        hipLaunchKernelGGL(mask_draw_kernel, dim3((unsigned)((words + 3) / 4)), dim3(256), 0, st, P);
+        const int rc2 = hip_status(hipGetLastError());
+        if (rc2 != SDROP_OK) return rc2;
+    }
     const bool in_lds = L.MB * L.words_per_row <= kLdsWords && L.MB <= kLdsPtrs && L.KB <= kLdsPtrs;
     if (in_lds)
-        hipLaunchKernelGGL(mask_kernel<true>, dim3(1), dim3(kMaskThreads), 0, static_cast<hipStream_t>(stream), P);
+        hipLaunchKernelGGL(mask_kernel<true>, dim3(1), dim3(kMaskThreads), 0, st, P);
     else
-        hipLaunchKernelGGL(mask_kernel<false>, dim3(1), dim3(kMaskThreads), 0, static_cast<hipStream_t>(stream), P);
+        hipLaunchKernelGGL(mask_kernel<false>, dim3(1), dim3(kMaskThreads), 0, st, P);
     return hip_status(hipGetLastError());
 }
 

@@ -82,6 +82,8 @@ def test_tiny_workload():
     (640, 320, 72, 128, 64, "bf16", 0.2, 5),      # N smaller than any tile
     (256, 384, 512, 64, 64, "bf16", 0.7, 6),
     (256, 256, 8, 128, 128, "f16", 0.5, 7),       # smallest legal N
+    (2048, 256, 264, 64, 64, "bf16", 0.5, 8),     # few dW tiles, long columns: dW runs as split parts + reduce
+    (1536, 256, 512, 128, 128, "f16", 0.3, 9),    # the same with 128-blocks and no ragged edge
 ])
 def test_mid_sizes_every_element(M, K, N, BM, BK, dtype, p, seed):
     print("gemm mid", M, K, N, BM, BK, dtype, p, seed, flush=True)
