@@ -65,6 +65,9 @@ def main():
     # the 256 MiB Infinity Cache by the step before; a single-set (warm) figure is given too
     sets = _sets(w, 3, torch)
     mask = sdrop.Mask(w.M, w.K, w.BM, w.BK, HEADLINE_P)
+    td = w.torch_dtype
+    ws_need = sdrop.workspace_bytes(sdrop.OP_BWD_DW, w.M, w.K, w.N, w.BM, w.BK, td, td)
+    ws = torch.empty(max(ws_need, 16), dtype=torch.uint8, device="cuda")
 
     def step(s, p, seed, events=None):
         if events is not None:
@@ -78,7 +81,7 @@ def main():
         sdrop.sdrop_bwd_dx(s["dY"], s["W"], mask, out=s["dX"])
         if events is not None:
             events[3].record()
-        sdrop.sdrop_bwd_dw(s["X"], s["dY"], mask, out=s["dW"])
+        sdrop.sdrop_bwd_dw(s["X"], s["dY"], mask, out=s["dW"], ws=ws)
         if events is not None:
             events[4].record()
 

@@ -165,8 +165,16 @@ def sdrop_mask_from_bits(M, K, BM, BK, p, bits, out=None):
     return m
 
 
+_ws_cache = {}
+
+
 def workspace_bytes(op, M, K, N, BM, BK, dtype, out_dtype):
-    return int(lib().sdrop_workspace_bytes(op, M, K, N, BM, BK, _DTYPES[dtype], _DTYPES[out_dtype]))
+    key = (op, M, K, N, BM, BK, dtype, out_dtype)
+    v = _ws_cache.get(key)
+    if v is None:
+        v = int(lib().sdrop_workspace_bytes(op, M, K, N, BM, BK, _DTYPES[dtype], _DTYPES[out_dtype]))
+        _ws_cache[key] = v
+    return v
 
 
 def _gemm(name, op, a, b, mask, out_shape, M, K, N, out_dtype, out, ws):
