@@ -36,6 +36,7 @@
 // bank conflicts without padding, which the direct loads require.
 #include "sdrop_internal.h"
 #include <type_traits>
+#include <cstdlib>
 #include <utility>
 
 namespace sdrop {
@@ -82,7 +83,10 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
 
 constexpr int TK = 64;           // reduction slice staged per step
 constexpr int kThreads = 256;    // 4 wavefronts per workgroup
-constexpr int kStages = 3;       // LDS stages
+// LDS stages: three for tiles of 128 rows (one workgroup per CU; the deeper prefetch measured
+// faster than two co-resident workgroups with two stages: 93 vs 120 us for dX at 4096^3, p=0.5);
+// two for tiles of 64 rows, so that two or three workgroups share a CU (measured faster there).
+constexpr int stages_for(int tm, int tn) { return (void)tn, tm <= 64 ? 2 : 3; }
 
 enum Op { FWD = 0, DX = 1, DW = 2 };
 
@@ -95,6 +99,7 @@ struct GemmParams {
     int32_t BM, BK, MB, KB;
     int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
     int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)
+    int32_t map_mode;   // experiment: workgroup -> tile mapping
     float scale;
     double p;           // host only: dropout probability, for choosing tile shapes
 };
@@ -349,6 +354,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
     // LDS and is read with transposing reads.
     constexpr bool A_TR = A_DMA && !A_KMAJ, B_TR = B_DMA && !B_KMAJ;
     constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int STAGES = stages_for(TM, TN);
+    constexpr int AHEAD = STAGES - 1;          // a direct load issued in iteration s brings slice s + AHEAD
     constexpr int NGRP_MAX = 4;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -377,7 +384,18 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
 
     if constexpr (OP == FWD) {
         const int t = blockIdx.x;
-        const int i = P.mv.row_order[t / P.n_tiles], nt = t % P.n_tiles;
+        int rank = t / P.n_tiles, nt = t % P.n_tiles;
+        if (P.map_mode == 1) {            // XCD x owns row ranks x, x+8, ... and all their N tiles
+            const int x = t & 7, u = t >> 3;
+            rank = (u / P.n_tiles) * 8 + x; nt = u % P.n_tiles;
+        } else if (P.map_mode == 2) {     // XCD x = (row parity, group of n_tiles/4 N tiles)
+            const int x = t & 7, u = t >> 3, per = P.n_tiles / 4;
+            rank = (u / per) * 2 + (x >> 2); nt = (x & 3) * per + u % per;
+        } else if (P.map_mode == 3) {     // XCD x = (row rank mod 4, half of the N tiles)
+            const int x = t & 7, u = t >> 3, per = P.n_tiles / 2;
+            rank = (u / per) * 4 + (x >> 1); nt = (x & 1) * per + u % per;
+        }
+        const int i = P.mv.row_order[rank];
         const int rp = P.mv.row_ptr[i];
         list = P.mv.col_idx + rp;
         list_len = P.mv.row_ptr[i + 1] - rp;
@@ -532,14 +550,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
         constexpr int NREG_ITER = (A_DMA ? 0 : SliceA::NLOADS) + (B_DMA ? 0 : SliceB::NLOADS);
 
         // ---- prologue.  Direct operands: slices 0 and 1 straight to stages 0 and 1.
-        //      Register operands: slice 0 to stage 0, slice 1 stays in registers. ----
+        //      (with two stages only slice 0).  Register operands: slice 0 to stage 0, slice 1
+        //      stays in registers. ----
         {
             const Src s0 = src_of(0);
             dma_range(s0, stage_ptr(0), 0, NDMA_ITER);
             if constexpr (!A_DMA) { ra.load(s0.a, lda, a_lim(s0)); ra.template store<0, 1>(stage_ptr(0)); }
             if constexpr (!B_DMA) { rb.load(s0.b, ldb, s0.lim); rb.template store<0, 1>(stage_ptr(0) + A_BYTES); }
             const Src s1 = src_of(1);
-            dma_range(s1, stage_ptr(1), 0, NDMA_ITER);
+            if constexpr (STAGES == 3) dma_range(s1, stage_ptr(1), 0, NDMA_ITER);
             if constexpr (!A_DMA) ra.load(s1.a, lda, a_lim(s1));
             if constexpr (!B_DMA) rb.load(s1.b, ldb, s1.lim);
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
@@ -570,35 +589,42 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
             // group's operand reads and of the slice's direct loads, and nothing moves across
             // the fence after it.  The direct loads of slice s+2 are spread over groups 0..2.
             // All indices are compile-time so that operands and accumulators stay in registers.
-            int64_t nxt_off = offset_of(2);
+            int64_t nxt_off = offset_of(AHEAD);
             for (int s = 0; s < nsteps; ++s) {
                 const char *cur = stage_ptr(st0);
                 const char *nx1 = stage_ptr(st1);
-                char *nx2 = stage_ptr(st2);
-                const Src s2 = src_at(nxt_off);
-                refresh_for(s + 3);
+                char *nx2 = stage_ptr(STAGES == 3 ? st2 : st1);      // where this iteration's direct loads land
+                const Src s2 = src_at(nxt_off);                       // slice s + AHEAD
+                refresh_for(s + AHEAD + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<4>([&](auto gi) __attribute__((always_inline)) {
                     constexpr int g = decltype(gi)::value;
-                    if constexpr (g == 3) {
-                        // slice s+1 must have landed everywhere: this wavefront's direct loads of it
-                        // were issued one iteration ago; only this iteration's may stay in flight
-                        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NDMA_ITER));
-                        __builtin_amdgcn_s_barrier();
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+                    // In the last group the first NB MFMAs go out before the barrier (they need only
+                    // operands already read), so that the matrix pipe has work while the wavefronts
+                    // meet; the operand reads of slice s+1 follow the barrier.
+                    constexpr int NB = (g == 3 && NM >= 4) ? 2 : 0;
                     static_for<NM>([&](auto ci) __attribute__((always_inline)) {
                         constexpr int c = decltype(ci)::value;
                         constexpr int mi = c / NI, ni = c % NI, cb = g & 1, nb = (g + 1) & 1;
+                        if constexpr (g == 3 && c == NB) {
+                            // slice s+1 must have landed everywhere: this wavefront's direct loads of it
+                            // were issued one iteration ago (only this iteration's may stay in flight),
+                            // and every wavefront must be done reading slice s before its stage is reused
+                            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(STAGES == 3 ? NDMA_ITER : 0));
+                            __builtin_amdgcn_s_barrier();
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
                         acc[mi][ni] = In<T>::mfma(fa[cb][mi], fb[cb][ni], acc[mi][ni]);
-                        // operands for the next group: kk = g+1 of this slice, or kk = 0 of slice s+1
-                        constexpr int r0 = c * NOPS / NM, r1 = (c + 1) * NOPS / NM;
+                        // operands for the next group (kk = g+1 of this slice, or kk = 0 of slice s+1),
+                        // B's first: MFMA c needs A[c / NI] and B[c % NI]
+                        constexpr int r0 = c < NB ? 0 : (c - NB) * NOPS / (NM - NB);
+                        constexpr int r1 = c < NB ? 0 : (c - NB + 1) * NOPS / (NM - NB);
                         static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
                             constexpr int r = r0 + decltype(ri)::value;
                             const char *st = g < 3 ? cur : nx1;
                             constexpr int kk = g < 3 ? g + 1 : 0;
-                            if constexpr (r < MI) fa[nb][r] = read_frag<T, A_TR, TM>(st, wm * WTM + r * 32, kk);
-                            else fb[nb][r - MI] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + (r - MI) * 32, kk);
+                            if constexpr (r < NI) fb[nb][r] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + r * 32, kk);
+                            else fa[nb][r - NI] = read_frag<T, A_TR, TM>(st, wm * WTM + (r - NI) * 32, kk);
                         });
                         if constexpr (g < 3) {
                             constexpr int gc = g * NM + c;
@@ -609,12 +635,12 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
                                 else db.issue(s2.b, ldb, nx2 + A_BYTES, j - NDMA_A);
                             });
                         } else if constexpr (c == 0) {
-                            nxt_off = offset_of(s + 3);   // list lookup for the next iteration
+                            nxt_off = offset_of(s + 1 + AHEAD);   // list lookup for the next iteration
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     });
                 });
-                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+                const int t0 = st0; st0 = st1; st1 = (STAGES == 3 ? st2 : t0); st2 = t0;
             }
         } else {
             constexpr int A_ST = A_DMA ? 0 : SliceA::NSTORES, A_PM = A_DMA ? 0 : SliceA::NPERMS;
@@ -623,13 +649,14 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
                 // On entry: slice s complete in stage st0 and its kk=0 operands in flight to
                 // fa[0]/fb[0]; direct slice s+1 in flight to st1; register slice s+1 in (ra, rb).
                 const char *cur = stage_ptr(st0);
-                char *nx1 = stage_ptr(st1), *nx2 = stage_ptr(st2);
+                char *nx1 = stage_ptr(st1), *nx2 = stage_ptr(STAGES == 3 ? st2 : st1);
                 refresh_for(s + 2);
-                const Src s2 = src_of(s + 2);
+                const Src s2 = src_of(s + 2);            // register operands: slice s+2
+                const Src sd = src_of(s + AHEAD);        // direct operand: slice s + AHEAD -> nx2
                 __builtin_amdgcn_sched_barrier(0);
                 // group 0: MFMAs kk=0 | operands kk=1; A: registers -> st1, or HBM -> st2; first half of B -> st1
                 read_frags(1, cur, 1);
-                if constexpr (A_DMA) dma_range(s2, nx2, 0, NDMA_A); else ra.template store<0, 1>(nx1);
+                if constexpr (A_DMA) dma_range(sd, nx2, 0, NDMA_A); else ra.template store<0, 1>(nx1);
                 rb.template store<0, 2>(nx1 + A_BYTES);
                 mfmas(0);
                 interleave<NM, NFR, A_PM + B_PM / 2 + 2 * NDMA_ITER, A_ST + B_ST / 2, 0>();
@@ -644,14 +671,14 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
                 rb.load(s2.b, ldb, s2.lim);
                 mfmas(0);
                 interleave<NM, NFR, 2 * NREG_ITER, 0, NREG_ITER>();
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NDMA_ITER + NREG_ITER));
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((STAGES == 3 ? NDMA_ITER : 0) + NREG_ITER));
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
                 // group 3: MFMAs kk=3 | kk=0 operands of slice s+1
                 read_frags(0, nx1, 0);
                 mfmas(1);
                 interleave<NM, NFR, 0, 0, 0>();
-                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+                const int t0 = st0; st0 = st1; st1 = (STAGES == 3 ? st2 : t0); st2 = t0;
             }
         }
     }
@@ -687,7 +714,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN>
 int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
 {
-    constexpr int LDS_BYTES = kStages * (TM + TN) * TK * 2;
+    constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
     auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false>;
     auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, true>;
     static bool attr_set = false;   // per instantiation
@@ -818,6 +845,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
     P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
     P.n_tiles = 0;
     P.splits = 1;
+    { const char *e = getenv("SDROP_MAP"); P.map_mode = e ? atoi(e) : 0; }
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
     P.p = p;
     hipStream_t st = static_cast<hipStream_t>(stream);
