@@ -36,7 +36,6 @@
 // bank conflicts without padding, which the direct loads require.
 #include "sdrop_internal.h"
 #include <type_traits>
-#include <cstdlib>
 #include <utility>
 
 namespace sdrop {
@@ -99,7 +98,6 @@ struct GemmParams {
     int32_t BM, BK, MB, KB;
     int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
     int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)
-    int32_t map_mode;   // experiment: workgroup -> tile mapping
     float scale;
     double p;           // host only: dropout probability, for choosing tile shapes
 };
@@ -384,17 +382,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
 
     if constexpr (OP == FWD) {
         const int t = blockIdx.x;
-        int rank = t / P.n_tiles, nt = t % P.n_tiles;
-        if (P.map_mode == 1) {            // XCD x owns row ranks x, x+8, ... and all their N tiles
-            const int x = t & 7, u = t >> 3;
-            rank = (u / P.n_tiles) * 8 + x; nt = u % P.n_tiles;
-        } else if (P.map_mode == 2) {     // XCD x = (row parity, group of n_tiles/4 N tiles)
-            const int x = t & 7, u = t >> 3, per = P.n_tiles / 4;
-            rank = (u / per) * 2 + (x >> 2); nt = (x & 3) * per + u % per;
-        } else if (P.map_mode == 3) {     // XCD x = (row rank mod 4, half of the N tiles)
-            const int x = t & 7, u = t >> 3, per = P.n_tiles / 2;
-            rank = (u / per) * 4 + (x >> 1); nt = (x & 1) * per + u % per;
-        }
+        const int rank = t / P.n_tiles, nt = t % P.n_tiles;
         const int i = P.mv.row_order[rank];
         const int rp = P.mv.row_ptr[i];
         list = P.mv.col_idx + rp;
@@ -845,7 +833,6 @@ int run(const void *a, const void *b, const void *mask, void *out,
     P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
     P.n_tiles = 0;
     P.splits = 1;
-    { const char *e = getenv("SDROP_MAP"); P.map_mode = e ? atoi(e) : 0; }
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
     P.p = p;
     hipStream_t st = static_cast<hipStream_t>(stream);

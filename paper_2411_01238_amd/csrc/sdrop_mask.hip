@@ -144,6 +144,11 @@ __global__ __launch_bounds__(256) void mask_draw_kernel(MaskParams P)
 }
 
 // Limits of the variant that keeps the bits and both pointer arrays in LDS between phases.
+#ifdef SDROP_MASK_TIMING
+#define MASK_TICK(n) do { if (threadIdx.x == 0) ticks[n] = clock64(); } while (0)
+#else
+#define MASK_TICK(n) do { } while (0)
+#endif
 constexpr int kLdsWords = 2048;   // MB * words_per_row
 constexpr int kLdsPtrs = 2048;    // MB, KB
 
@@ -162,6 +167,10 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     uint64_t *const bits = IN_LDS ? s_bits : P.bits;
     int32_t *const row_ptr = IN_LDS ? s_row_ptr : P.row_ptr;
     int32_t *const col_ptr = IN_LDS ? s_col_ptr : P.col_ptr;
+#ifdef SDROP_MASK_TIMING
+    long long ticks[12] = {0};
+#endif
+    MASK_TICK(0);
 
     // -- rows: fetch the packed words (drawn by mask_draw_kernel, or given by the caller with
     //    possibly dirty padding bits), count per row --
@@ -175,6 +184,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
         if (IN_LDS || P.given_bits) P.bits[g] = word;
     }
     __syncthreads();
+    MASK_TICK(1);
     for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
         int cnt = 0;
         for (int w = 0; w < P.wpr; ++w) cnt += __popcll(bits[(int64_t)i * P.wpr + w]);
@@ -183,6 +193,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     if (threadIdx.x == 0) row_ptr[0] = 0;
     __syncthreads();
     block_inclusive_scan(row_ptr + 1, P.MB, wave_tot);
+    MASK_TICK(2);
     if (IN_LDS)
         for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = row_ptr[i];
 
@@ -200,6 +211,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
         }
     }
 
+    MASK_TICK(3);
     // -- columns: lane <-> block row --
     for (int j = wave; j < P.KB; j += kMaskWaves) {
         int cnt = 0;
@@ -212,7 +224,9 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     }
     if (threadIdx.x == 0) col_ptr[0] = 0;
     __syncthreads();
+    MASK_TICK(4);
     block_inclusive_scan(col_ptr + 1, P.KB, wave_tot);
+    MASK_TICK(5);
     if (IN_LDS)
         for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = col_ptr[j];
     for (int j = wave; j < P.KB; j += kMaskWaves) {
@@ -227,9 +241,12 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     }
 
     // -- schedules: heavy rows / columns first --
+    MASK_TICK(6);
     __shared__ int32_t s_first[2];
     descending_order(row_ptr, P.MB, P.KB, P.row_order, bins, wave_tot, &s_first[0]);
+    MASK_TICK(7);
     descending_order(col_ptr, P.KB, P.MB, P.col_order, bins, wave_tot, &s_first[1]);
+    MASK_TICK(8);
 
     if (threadIdx.x == 0) {
         MaskHeader h = {};
@@ -239,6 +256,140 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
         h.magic = kMaskMagic;
         h.max_row_cnt = s_first[0];
         h.max_col_cnt = s_first[1];
+#ifdef SDROP_MASK_TIMING
+        for (int n = 0; n < 9; ++n) h.pad_[2 + n] = (int32_t)(ticks[n] - ticks[0]);
+#endif
+        *P.hdr = h;
+    }
+}
+
+// ---- lists for small block grids (MB, KB <= 1024, at most 2048 mask words) ----
+// Same result as mask_kernel, built for latency: three barriers instead of a dozen.  Scans run
+// in one wavefront each (registers + shuffles), the schedules are rank sorts (rank = number of
+// entries with a larger count, ties by index: deterministic), and for very small grids the
+// draw itself is done here, which saves a launch.
+constexpr int kSmallN = 1024;
+
+// ptr[0..n] := exclusive prefix sums of cnt[0..n), by one wavefront (all 64 lanes call it).
+__device__ __forceinline__ void wave_scan(const int32_t *cnt, int32_t *ptr, int n)
+{
+    const int lane = lane_id();
+    const int per = (n + 63) / 64;
+    const int lo = lane * per, hi = (lo + per < n) ? lo + per : n;
+    int sum = 0;
+    for (int i = lo; i < hi; ++i) sum += cnt[i];
+    int incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    int run = incl - sum;
+    for (int i = lo; i < hi; ++i) { ptr[i] = run; run += cnt[i]; }
+    if (lane == 63) ptr[n] = incl;
+}
+
+template <bool DRAW>
+__global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
+{
+    __shared__ uint64_t s_bits[kLdsWords];
+    __shared__ int32_t s_rcnt[kSmallN], s_ccnt[kSmallN];
+    __shared__ int32_t s_row_ptr[kSmallN + 1], s_col_ptr[kSmallN + 1];
+    __shared__ int32_t s_max[2];
+    const int lane = lane_id(), wave = wave_id();
+    const int nwords = P.MB * P.wpr;
+
+    // -- phase 0: the packed words into LDS (drawn here, drawn by mask_draw_kernel, or given) --
+    for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) s_ccnt[j] = 0;
+    if (threadIdx.x < 2) s_max[threadIdx.x] = 0;
+    if constexpr (DRAW) {
+        for (int g = wave; g < nwords; g += kMaskWaves) {
+            const int i = g / P.wpr, w = g % P.wpr, j = w * 64 + lane;
+            bool keep = false;
+            if (j < P.KB) {
+                const uint64_t b = (uint64_t)i * (uint64_t)P.KB + (uint64_t)j;
+                const uint32_t r = philox_word0((uint32_t)b, (uint32_t)(b >> 32), P.ctr2, P.ctr3, P.key0, P.key1);
+                keep = (uint64_t)r >= P.threshold;
+            }
+            const uint64_t word = __ballot(keep);
+            if (lane == 0) { s_bits[g] = word; P.bits[g] = word; }
+        }
+    } else {
+        const uint64_t *src_bits = P.given_bits ? P.given_bits : P.bits;
+        for (int g = threadIdx.x; g < nwords; g += kMaskThreads) {
+            const int valid = P.KB - (g % P.wpr) * 64;       // columns covered by this word
+            uint64_t word = src_bits[g];
+            if (valid < 64) word &= (uint64_t(1) << valid) - 1;
+            s_bits[g] = word;
+            P.bits[g] = word;
+        }
+    }
+    __syncthreads();
+
+    // -- phase 1: kept counts per block row and per block column --
+    for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
+        int cnt = 0;
+        for (int w = 0; w < P.wpr; ++w) cnt += __popcll(s_bits[i * P.wpr + w]);
+        s_rcnt[i] = cnt;
+        atomicMax(&s_max[0], cnt);
+    }
+    for (int e = threadIdx.x; e < P.MB * P.KB; e += kMaskThreads) {
+        const int i = e / P.KB, j = e % P.KB;
+        if ((s_bits[i * P.wpr + (j >> 6)] >> (j & 63)) & 1) atomicAdd(&s_ccnt[j], 1);
+    }
+    __syncthreads();
+
+    // -- phase 2: pointers (one wavefront each) and schedules (everybody) --
+    if (wave == 0) wave_scan(s_rcnt, s_row_ptr, P.MB);
+    if (wave == 1) wave_scan(s_ccnt, s_col_ptr, P.KB);
+    for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
+        const int c = s_rcnt[i];
+        int rank = 0;
+        for (int o = 0; o < P.MB; ++o) { const int co = s_rcnt[o]; rank += (co > c) || (co == c && o < i); }
+        P.row_order[rank] = i;
+    }
+    for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) {
+        const int c = s_ccnt[j];
+        atomicMax(&s_max[1], c);
+        int rank = 0;
+        for (int o = 0; o < P.KB; ++o) { const int co = s_ccnt[o]; rank += (co > c) || (co == c && o < j); }
+        P.col_order[rank] = j;
+    }
+    __syncthreads();
+
+    // -- phase 3: the lists --
+    for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
+    for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = s_col_ptr[j];
+    for (int i = wave; i < P.MB; i += kMaskWaves) {
+        int pos = s_row_ptr[i];
+        for (int w = 0; w < P.wpr; ++w) {
+            const uint64_t word = s_bits[i * P.wpr + w];
+            if ((word >> lane) & 1) {
+                const int at = pos + __popcll(word & lanes_below());
+                P.col_idx[at] = w * 64 + lane;
+                P.blk_row[at] = i;
+            }
+            pos += __popcll(word);
+        }
+    }
+    for (int j = wave; j < P.KB; j += kMaskWaves) {
+        int pos = s_col_ptr[j];
+        for (int i0 = 0; i0 < P.MB; i0 += 64) {
+            const int i = i0 + lane;
+            const bool keep = (i < P.MB) && ((s_bits[i * P.wpr + (j >> 6)] >> (j & 63)) & 1);
+            const uint64_t word = __ballot(keep);
+            if (keep) P.row_idx[pos + __popcll(word & lanes_below())] = i;
+            pos += __popcll(word);
+        }
+    }
+    if (threadIdx.x == 0) {
+        MaskHeader h = {};
+        h.M = P.M; h.K = P.K; h.BM = P.BM; h.BK = P.BK; h.MB = P.MB; h.KB = P.KB;
+        h.words_per_row = P.wpr;
+        h.nnz = s_row_ptr[P.MB];
+        h.magic = kMaskMagic;
+        h.max_row_cnt = s_max[0];
+        h.max_col_cnt = s_max[1];
         *P.hdr = h;
     }
 }
@@ -277,11 +428,18 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     P.ctr2 = static_cast<uint32_t>(rng_stream); P.ctr3 = static_cast<uint32_t>(rng_stream >> 32);
     P.threshold = static_cast<uint64_t>(floor(p * 4294967296.0));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (!given_bits) {
-        const int64_t words = L.MB * L.words_per_row;
+    const int64_t words = L.MB * L.words_per_row;
+    const bool small = L.MB <= kSmallN && L.KB <= kSmallN && words <= kLdsWords;
+    const bool fused_draw = small && !given_bits && words <= 64;     // a launch costs more than 4 draws per wavefront
+    if (!given_bits && !fused_draw) {
         hipLaunchKernelGGL(mask_draw_kernel, dim3((unsigned)((words + 3) / 4)), dim3(256), 0, st, P);
         const int rc2 = hip_status(hipGetLastError());
         if (rc2 != SDROP_OK) return rc2;
+    }
+    if (small) {
+        if (fused_draw) hipLaunchKernelGGL(mask_small_kernel<true>, dim3(1), dim3(kMaskThreads), 0, st, P);
+        else hipLaunchKernelGGL(mask_small_kernel<false>, dim3(1), dim3(kMaskThreads), 0, st, P);
+        return hip_status(hipGetLastError());
     }
     const bool in_lds = L.MB * L.words_per_row <= kLdsWords && L.MB <= kLdsPtrs && L.KB <= kLdsPtrs;
     if (in_lds)

@@ -53,6 +53,9 @@ def test_mask_matches_oracle_on_every_workload(name, p, layer):
     (128 * 5, 128 * 64, 128, 128, 0.0, 3, 3),    # exactly one full word, all kept
     (128 * 5, 128 * 65, 128, 128, 2.0 ** -32, 0, 0),
     (64 * 200, 64 * 130, 64, 64, 0.9, 4, 4),     # sparse, three words per row
+    (64 * 2100, 64 * 2, 64, 64, 0.5, 6, 1),      # MB > 2048: the list builder that works in global memory
+    (128 * 3, 64 * 2100, 128, 64, 0.25, 7, 2),   # KB > 2048: 33 words per row
+    (128 * 64, 128 * 1, 128, 128, 0.5, 8, 0),    # a single block column
 ])
 def test_mask_edge_shapes(M, K, BM, BK, p, seed, stream):
     print("mask edge", M, K, BM, BK, p, seed, stream, flush=True)
