@@ -20,6 +20,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_DENSE_TFLOPS = 2500.0     # MI355X published dense bf16/fp16 MFMA peak
+# Bytes per launch that crossed L2 -> fabric, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a known 1 GiB
+# copy (profiles/bench_square4096_p0.5_hbm_traffic.md), workload square4096 at p = 0.5
+MEASURED_TRAFFIC_BYTES = {"square4096": {"fwd": 235.2e6, "dx": 411.3e6, "dw": 239.2e6}}
 HEADLINE_P = 0.5
 
 
@@ -45,6 +48,8 @@ def main():
     ap.add_argument("--workload", default="square4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy, as the known-size reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (the hot path is a single-GPU kernel path); "
@@ -110,6 +115,15 @@ def main():
 
     flops_per_block = 3 * 2.0 * w.BM * w.BK * w.N
 
+    if args.calibrate_copy:
+        # reads 1 GiB and writes 1 GiB: what FETCH_SIZE / WRITE_SIZE report for it gives the scale factor
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- headline: p = 0.5, rotating buffer sets ----
     nnz = nnz_of(HEADLINE_P, w.mask_seed)
     ms = timed(HEADLINE_P, args.steps, args.warmup, 3)
@@ -138,7 +152,8 @@ def main():
     achieved = flops_launch / (kern[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "sdrop_" + {"fwd": "fwd", "dx": "bwd_dx", "dw": "bwd_dw"}[dom],
                 "achieved": round(achieved, 3), "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_DENSE_TFLOPS, 5), "traffic": None,
+                "frac": round(achieved / PEAK_BF16_DENSE_TFLOPS, 5),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
                 "avg_launch_ms": {k: round(v, 5) for k, v in kern.items()}}
 
     out = {
