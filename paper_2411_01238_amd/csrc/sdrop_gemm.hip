@@ -130,13 +130,13 @@ __device__ __forceinline__ void dma16(const char *sbase, uint32_t voff, const ch
 // HBM -> LDS without registers, for an operand tile [ROWS][64] whose rows lie ld_bytes
 // apart in HBM (reduction index contiguous).  One instruction of one wavefront fills
 // 1 KiB = 8 LDS rows: lane l lands in row 8*I + l/8, slot l%8, so it fetches chunk
-// (l%8) ^ swz(row) of that row.  Wavefront w issues instructions I = w + 4*i, i = 0 ..
-// ROWS/32 - 1.  Row of this lane in pass i is r = 32*i + r0; adding 32*i only flips bit 2 of
-// swz(r) for odd i, so two lane offsets (even / odd pass) serve every pass and the rest of
-// the address is uniform.
-template <int ROWS, int NGRP> struct DmaK {
-    static constexpr int PER_WAVE = ROWS / 32, GROUP_ROWS = ROWS / NGRP;
-    static_assert(GROUP_ROWS % 32 == 0, "row groups must cover whole passes");
+// (l%8) ^ swz(row) of that row.  Wavefront w of NW issues instructions I = w + NW*i.  Row of
+// this lane in pass i is r = 8*NW*i + r0; of the pass offset swz(r) sees only bit 5, so two
+// lane offsets serve every pass and the rest of the address is uniform.
+template <int ROWS, int NGRP, int NW> struct DmaK {
+    static constexpr int PASS_ROWS = 8 * NW;              // rows filled by one pass of the NW wavefronts
+    static constexpr int PER_WAVE = ROWS / PASS_ROWS, GROUP_ROWS = ROWS / NGRP;
+    static_assert(GROUP_ROWS % PASS_ROWS == 0 && ROWS % PASS_ROWS == 0, "row groups must cover whole passes");
     uint32_t voff_even, voff_odd;
     int wave;
     __device__ __forceinline__ void init(int64_t ld_bytes)
@@ -151,9 +151,10 @@ template <int ROWS, int NGRP> struct DmaK {
     // pass i of this wavefront
     __device__ __forceinline__ void issue(const char *const (&base)[NGRP], int64_t ld_bytes, char *lds, int i) const
     {
-        const int g = (32 * i) / GROUP_ROWS;              // uniform: rows of pass i are 32i .. 32i+31
-        const char *sbase = base[g] + (int64_t)(32 * i - g * GROUP_ROWS) * ld_bytes;
-        dma16(sbase, (i & 1) ? voff_odd : voff_even, lds + (wave + 4 * i) * 1024);
+        const int g = (PASS_ROWS * i) / GROUP_ROWS;       // uniform: pass i covers rows PASS_ROWS*i ..
+        const char *sbase = base[g] + (int64_t)(PASS_ROWS * i - g * GROUP_ROWS) * ld_bytes;
+        // bit 5 of the row (the only bit of a pass offset that swz() sees) picks the lane offset
+        dma16(sbase, ((PASS_ROWS * i) & 32) ? voff_odd : voff_even, lds + (wave + NW * i) * 1024);
     }
 };
 
@@ -168,11 +169,12 @@ template <int ROWS> __device__ __forceinline__ int swz_t(int k)
 
 // HBM -> LDS without registers for an operand tile [64][ROWS] (ROWS contiguous, rows ld_bytes
 // apart).  One instruction fills 1 KiB = 1024/(2*ROWS) tile rows; lane l lands at byte 16*l of
-// it and fetches the chunk whose swizzled slot that is.  Row k = RPI*I + kl with I = w + 4*i:
+// it and fetches the chunk whose swizzled slot that is.  Row k = RPI*I + kl with I = w + NW*i:
 // k & 3 (or (k>>1)&1) does not depend on i, so one lane offset serves every pass.
-template <int ROWS> struct DmaT {
+template <int ROWS, int NW> struct DmaT {
     static constexpr int ROW_BYTES = 2 * ROWS, RPI = 1024 / ROW_BYTES;       // rows per instruction
-    static constexpr int PER_WAVE = ROWS / 32;
+    static constexpr int PER_WAVE = ROWS / (8 * NW);
+    static_assert(ROWS % (8 * NW) == 0, "every wavefront issues whole instructions");
     static_assert(ROWS == 64 || ROWS == 128 || ROWS == 256, "unsupported tile edge");
     uint32_t voff;
     int wave;
@@ -187,7 +189,7 @@ template <int ROWS> struct DmaT {
     }
     __device__ __forceinline__ void issue(const char *const (&base)[1], int64_t ld_bytes, char *lds, int i) const
     {
-        const int I = wave + 4 * i;
+        const int I = wave + NW * i;
         dma16(base[0] + (int64_t)(RPI * I) * ld_bytes, voff, lds + I * 1024);
     }
 };
@@ -338,9 +340,10 @@ __device__ __forceinline__ void interleave()
 constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (0 << 8); }
 
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
+__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
 {
-    static_assert(WM * WN * 64 == kThreads, "4 wavefronts");
+    constexpr int NW = WM * WN, NT = NW * 64;           // wavefronts, threads
+    static_assert(NW == 4 || (NW == 8 && !RAGGED), "4 wavefronts (8 only without the register path)");
     constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
     static_assert(MI >= 1 && NI >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be 32-aligned");
     constexpr bool A_KMAJ = (OP != DW), B_KMAJ = (OP == DX);    // reduction index contiguous in HBM?
@@ -425,7 +428,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
             if (pos < P.KB && !((P.mv.bits[(int64_t)i * H->words_per_row + (pos >> 6)] >> (pos & 63)) & 1)) {
                 char *z = P.C + (int64_t)i * P.BM * ldc + (int64_t)pos * P.BK * sizeof(OutT);
                 const int row_chunks = P.BK * (int)sizeof(OutT) / 16;
-                for (int c = threadIdx.x; c < TM * row_chunks; c += kThreads)
+                for (int c = threadIdx.x; c < TM * row_chunks; c += NT)
                     *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
             }
         }
@@ -516,13 +519,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
         auto a_lim = [&](const Src &x) __attribute__((always_inline)) { return OP == DX ? x.lim : (OP == FWD ? TK : TM); };
 
         // direct-load engines (lane offsets computed once)
-        using DmaA = typename std::conditional<A_KMAJ, DmaK<TM, 1>, DmaT<TM>>::type;
-        using DmaB = typename std::conditional<B_KMAJ, DmaK<TN, DXG>, DmaT<TN>>::type;
+        using DmaA = typename std::conditional<A_KMAJ, DmaK<TM, 1, NW>, DmaT<TM, NW>>::type;
+        using DmaB = typename std::conditional<B_KMAJ, DmaK<TN, DXG, NW>, DmaT<TN, NW>>::type;
         DmaA da;
         DmaB db;
         if constexpr (A_DMA) da.init(lda);
         if constexpr (B_DMA) db.init(ldb);
-        constexpr int NDMA_A = A_DMA ? TM / 32 : 0, NDMA_B = B_DMA ? TN / 32 : 0;     // per wavefront and slice
+        constexpr int NDMA_A = A_DMA ? TM / (8 * NW) : 0, NDMA_B = B_DMA ? TN / (8 * NW) : 0;   // per wavefront and slice
         constexpr int NDMA_ITER = NDMA_A + NDMA_B;
         // direct-load instruction j of a slice (A's first, then B's) into stage st
         auto dma_one = [&](const Src &x, char *st, int j) __attribute__((always_inline)) {
@@ -699,12 +702,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams P)
         }
 }
 
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN>
+// WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
 int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
 {
     constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
     auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false>;
-    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, true>;
+    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WMR, WNR, true>;
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_full),
@@ -716,7 +720,8 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
         attr_set = true;
     }
     if (grid <= 0) return SDROP_OK;
-    hipLaunchKernelGGL(ragged ? k_ragged : k_full, dim3(grid), dim3(kThreads), LDS_BYTES, stream, P);
+    if (ragged) hipLaunchKernelGGL(k_ragged, dim3(grid), dim3(WMR * WNR * 64), LDS_BYTES, stream, P);
+    else hipLaunchKernelGGL(k_full, dim3(grid), dim3(WM * WN * 64), LDS_BYTES, stream, P);
     return hip_status(hipGetLastError());
 }
 
