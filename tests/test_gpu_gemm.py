@@ -84,6 +84,10 @@ def test_tiny_workload():
     (256, 256, 8, 128, 128, "f16", 0.5, 7),       # smallest legal N
     (2048, 256, 264, 64, 64, "bf16", 0.5, 8),     # few dW tiles, long columns: dW runs as split parts + reduce
     (1536, 256, 512, 128, 128, "f16", 0.3, 9),    # the same with 128-blocks and no ragged edge
+    (128, 64 * 200, 256, 64, 64, "f16", 0.2, 10), # 200 block columns: fwd walks a kept list longer than 128 entries
+    (64 * 300, 128, 256, 64, 64, "bf16", 0.1, 11),  # 300 block rows: dW walks long column lists (and splits them)
+    (128 * 150, 128, 264, 128, 128, "bf16", 0.0, 12),  # the same, all kept, 128-blocks, ragged N
+    (256, 128 * 140, 256, 128, 128, "bf16", 0.05, 13),  # fwd: 140 block columns with two slices each
 ])
 def test_mid_sizes_every_element(M, K, N, BM, BK, dtype, p, seed):
     print("gemm mid", M, K, N, BM, BK, dtype, p, seed, flush=True)
