@@ -5,35 +5,44 @@
 //   DX   dX = s (dY W^T) . m'     tile = one kept block (i,j): reduction over all of N
 //   DW   dW = s (X . m')^T dY     tile (block column j, N tile): walks the kept row blocks of column j
 //
-// Each workgroup (4 wavefronts, one per SIMD, one workgroup per CU) owns one
-// TM x TN output tile and steps through its reduction in slices of TK = 64 that
-// rotate through three LDS stages.  The paper names the lack of software
-// pipelining as the reason its kernels lose to dense at zero sparsity
-// (Section 5.1); here, while the MFMAs of slice t run, slice t+1 is complete in
-// LDS and slice t+2 is on its way.  One barrier per slice, placed before the last
-// quarter of the slice's MFMAs so that the first operands of slice t+1 are read
-// behind them.  Within a slice the LDS reads, LDS writes, byte permutes and
-// global loads are interleaved with the MFMAs by explicit scheduling groups,
-// because one wavefront per SIMD has no other wavefront to hide its issue slots.
+// Each workgroup owns one TM x TN output tile and steps through its reduction in slices of
+// TK = 64 that rotate through LDS stages (three for 128-row tiles, one workgroup per CU; two for
+// 64-row tiles, several workgroups per CU).  The paper names the lack of software pipelining as
+// the reason its kernels lose to dense at zero sparsity (Section 5.1); here, while the MFMAs of
+// slice t run, slice t+1 is complete in LDS and slice t+2 is on its way.  One barrier per slice,
+// placed after the first MFMAs of the slice's last quarter so that the matrix pipe has work
+// while the wavefronts meet.  Inside a slice every instruction has a fixed place (compile-time
+// loops and scheduling fences), because one computing wavefront per SIMD has no other wavefront
+// to hide its issue slots.
 //
-// The matrix-core instruction is v_mfma_f32_32x32x16_{f16,bf16}: lane l supplies
-// row (l%32) of the left operand and column (l%32) of the right operand, each
-// as 8 consecutive reduction indices starting at 8*(l/32).  Every operand slice
-// therefore lives in LDS in ONE form, [rows][64 reduction indices] with 128-byte
-// rows, read with one 16-byte ds_read_b128 per lane and MFMA.
-//   - An operand whose reduction index is contiguous in HBM (X in FWD, dY and W
-//     in DX) goes HBM -> LDS directly (global_load_lds_dwordx4): no registers, no
-//     LDS store instructions, and the LDS pipe stays free for the reads (an LDS
-//     store of 1 KiB was measured at 13 clocks, a read at 5.6).
-//   - An operand whose reduction index is the strided one (W in FWD; X and dY in
-//     DW) is transposed in registers on its way in: a thread loads an 8 x NW patch
-//     (8 reduction rows, NW contiguous columns), regroups it with byte permutes
-//     and stores NW rows of 8.  (The transposing LDS read of gfx950,
-//     ds_read_b64_tr_b16, was measured at a third of the byte rate of
-//     ds_read_b128 and made the loop LDS-bound.)
-// The 16-byte slot of chunk c in row r is c ^ swz(r) (see lds_off): with it the
-// row-wise stores, the transposed stores and the operand reads are all free of
-// bank conflicts without padding, which the direct loads require.
+// For 128-row tiles the workgroup has eight wavefronts: four compute (one per SIMD), four only
+// issue loads (again one per SIMD).  A load instruction that the memory pipeline holds up then
+// stalls a wavefront that has nothing else to do, not the one feeding the matrix pipe
+// (measured: 134 -> 119 us for the dense 4096^3 forward).
+//
+// The matrix-core instruction is v_mfma_f32_32x32x16_{f16,bf16}: lane l supplies row (l%32) of
+// one operand and column (l%32) of the other, each as 8 consecutive reduction indices starting
+// at 8*(l/32).
+//   - Every operand goes HBM -> LDS directly (global_load_lds_dwordx4): no registers, no LDS
+//     store instructions, and the LDS pipe stays free for the reads (an LDS store of 1 KiB was
+//     measured at 13 clocks, a read at 5.6).
+//   - An operand whose reduction index is contiguous in HBM (X in FWD, dY and W in DX) lies in
+//     LDS as [rows][64 reduction indices] with 128-byte rows and is read with one 16-byte
+//     ds_read_b128 per lane and MFMA.  The 16-byte slot of chunk c in row r is c ^ swz(r) (see
+//     lds_off): the direct loads forbid padding, and with this swizzle the reads are free of
+//     bank conflicts.
+//   - An operand whose reduction index is the strided one (W in FWD; X and dY in DW) stays in
+//     LDS as it lies in HBM, [64 reduction rows][columns], and is read with the transposing
+//     read of gfx950 (two ds_read_b64_tr_b16 per operand).
+//   - Only a ragged edge (N not a multiple of the tile in FWD / DW, N not a multiple of 64 in
+//     DX) sends the affected operand through registers, which zero-fill the tail and, for the
+//     strided operand, transpose 8 x NW patches with byte permutes on the way.
+// The MFMAs are issued with the operands swapped (B's columns as the instruction's rows), so
+// that an accumulator register quad holds four consecutive output columns for the epilogue.
+//
+// On this chip the loop is limited by power, not by issue slots: the shader clock, read in the
+// loop, is ~2.0 GHz with the MFMAs alone, ~1.55 GHz once the operand reads from LDS are added
+// and ~1.4 GHz with the loads as well, at 84 % MFMA duty (1214 clocks per slice against 1024).
 #include "sdrop_internal.h"
 #include <type_traits>
 #include <utility>
@@ -89,6 +98,18 @@ constexpr int stages_for(int tm, int tn) { return (void)tn, tm <= 64 ? 2 : 3; }
 
 enum Op { FWD = 0, DX = 1, DW = 2 };
 
+// A value that is the same in every lane, told to the compiler (it then lives in a scalar register
+// and everything derived from it is scalar arithmetic).
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+
+#ifdef SDROP_GEMM_TIMING   // development aid: per-workgroup phase timestamps
+__device__ long long g_ticks[16384 * 16];
+#define GEMM_TICK(n) do { if (threadIdx.x == 0 && blockIdx.x < 16384) { g_ticks[blockIdx.x * 16 + (n)] = wall_clock64(); g_ticks[blockIdx.x * 16 + 8 + (n)] = clock64(); } } while (0)
+#else
+#define GEMM_TICK(n) do { } while (0)
+#endif
+
 struct GemmParams {
     const char *A;      // FWD: X   DX: dY  DW: X
     const char *B;      // FWD: W   DX: W   DW: dY
@@ -139,10 +160,10 @@ template <int ROWS, int NGRP, int NW> struct DmaK {
     static_assert(GROUP_ROWS % PASS_ROWS == 0 && ROWS % PASS_ROWS == 0, "row groups must cover whole passes");
     uint32_t voff_even, voff_odd;
     int wave;
-    __device__ __forceinline__ void init(int64_t ld_bytes)
+    __device__ __forceinline__ void init(int64_t ld_bytes, int w)
     {
         const int lane = threadIdx.x & 63;
-        wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        wave = w;
         const int r0 = 8 * wave + (lane >> 3);
         const uint32_t row_off = (uint32_t)r0 * (uint32_t)ld_bytes;
         voff_even = row_off + (((lane & 7) ^ swz(r0)) << 4);
@@ -178,10 +199,10 @@ template <int ROWS, int NW> struct DmaT {
     static_assert(ROWS == 64 || ROWS == 128 || ROWS == 256, "unsupported tile edge");
     uint32_t voff;
     int wave;
-    __device__ __forceinline__ void init(int64_t ld_bytes)
+    __device__ __forceinline__ void init(int64_t ld_bytes, int w)
     {
         const int lane = threadIdx.x & 63;
-        wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        wave = w;
         const int kl = (lane * 16) / ROW_BYTES;              // row within the instruction
         const int cpos = ((lane * 16) % ROW_BYTES) >> 4;     // 16-byte slot within the row
         const int k0 = RPI * wave + kl;
@@ -316,8 +337,6 @@ __device__ __forceinline__ typename In<T>::vec read_frag(const char *lds, int ba
     }
 }
 
-template <class OutT> __device__ __forceinline__ void store_out(OutT *p, float v) { *p = static_cast<OutT>(v); }
-
 // Scheduling recipe for one MFMA group: each of the NM MFMAs is followed by its share of
 // the LDS reads, global loads, VALU ops and LDS writes that were emitted with it.
 constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -339,11 +358,14 @@ __device__ __forceinline__ void interleave()
 // are outstanding and all LDS/scalar operations have completed.
 constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (0 << 8); }
 
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
+// SPEC: the workgroup has NW more wavefronts (one more per SIMD) that do nothing but issue the
+// direct loads, so that a load instruction held up by the memory pipeline never holds up MFMAs.
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED, bool SPEC>
+__global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(GemmParams P)
 {
-    constexpr int NW = WM * WN, NT = NW * 64;           // wavefronts, threads
+    constexpr int NW = WM * WN, NT = NW * 64 * (SPEC ? 2 : 1);   // computing wavefronts; threads
     static_assert(NW == 4 || (NW == 8 && !RAGGED), "4 wavefronts (8 only without the register path)");
+    static_assert(!(SPEC && RAGGED), "loader wavefronts exist only where every operand is loaded directly");
     constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
     static_assert(MI >= 1 && NI >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be 32-aligned");
     constexpr bool A_KMAJ = (OP != DW), B_KMAJ = (OP == DX);    // reduction index contiguous in HBM?
@@ -361,12 +383,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
+    GEMM_TICK(0);
     // a kernel handed a mask built for another problem writes nothing
     const MaskHeader *H = P.mv.hdr;
     if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
 
     constexpr int esz = 2;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = SPEC && wave_all >= NW;          // uniform over the wavefront
+    const int wave = loader ? wave_all - NW : wave_all;  // index among the wavefronts of the same role
     const int wm = wave / WN, wn = wave % WN;
 
     const char *a_tile = nullptr, *b_tile = nullptr;
@@ -386,10 +412,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
     if constexpr (OP == FWD) {
         const int t = blockIdx.x;
         const int rank = t / P.n_tiles, nt = t % P.n_tiles;
-        const int i = P.mv.row_order[rank];
-        const int rp = P.mv.row_ptr[i];
+        const int i = uni(P.mv.row_order[rank]);
+        const int rp = uni(P.mv.row_ptr[i]);
         list = P.mv.col_idx + rp;
-        list_len = P.mv.row_ptr[i + 1] - rp;
+        list_len = uni(P.mv.row_ptr[i + 1]) - rp;
         sub_shift = (P.BK == 128);
         nsteps = list_len << sub_shift;
         lda = P.K * esz; ldb = P.N * esz; ldc = P.N * (int64_t)sizeof(OutT);
@@ -401,10 +427,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
         // blockIdx.x = (rank of block column j in the schedule, N tile, part of the list)
         const int t = blockIdx.x;
         const int per_col = P.n_tiles * P.splits;
-        const int j = P.mv.col_order[t / per_col];
+        const int j = uni(P.mv.col_order[t / per_col]);
         const int nt = (t % per_col) / P.splits, part = t % P.splits;
-        const int cp = P.mv.col_ptr[j];
-        const int cnt = P.mv.col_ptr[j + 1] - cp;
+        const int cp = uni(P.mv.col_ptr[j]);
+        const int cnt = uni(P.mv.col_ptr[j + 1]) - cp;
         const int lo = (int)((int64_t)cnt * part / P.splits), hi = (int)((int64_t)cnt * (part + 1) / P.splits);
         list = P.mv.row_idx + cp + lo;
         list_len = hi - lo;
@@ -423,26 +449,43 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
         const int G_ = TN / P.BK;
         const int i = blockIdx.x % P.MB, q = blockIdx.x / P.MB;
         lda = P.N * esz; ldb = P.N * esz; ldc = P.K * (int64_t)sizeof(OutT);
+        // every index is fetched before the zero fill below: a load that follows a store cannot
+        // be proven unaliased and would lose its scalar form
+        const int rp = uni(P.mv.row_ptr[i]);
+        const int cnt = uni(P.mv.row_ptr[i + 1]) - rp;
+        const int blocks_valid = cnt - q * G_ < G_ ? cnt - q * G_ : G_;   // <= 0: nothing to compute
+        const int cshift = (P.BK == 128);             // 64-column chunks per block, log2
+        chunks_valid = blocks_valid << cshift;
+        int jg[NGRP_MAX] = {0, 0, 0, 0};
+        if (blocks_valid > 0) {
+#pragma unroll
+            for (int g = 0; g < DXG; ++g) {
+                const int b = g >> cshift;            // which of the gathered blocks (a missing one repeats the last)
+                jg[g] = uni(P.mv.col_idx[rp + q * G_ + (b < blocks_valid ? b : blocks_valid - 1)]);
+            }
+        }
+        uint64_t keep_word[2];                        // the bits of positions [q*G_, q*G_ + G_) lie in at most two words
+        const int pos0 = q * G_;
+        {
+            const uint64_t *row_bits = P.mv.bits + (int64_t)i * H->words_per_row;
+            const int w0 = pos0 >> 6, w1 = (pos0 + G_ - 1) >> 6, wmax = (P.KB - 1) >> 6;
+            keep_word[0] = row_bits[w0 < wmax ? w0 : wmax];
+            keep_word[1] = row_bits[w1 < wmax ? w1 : wmax];
+        }
         for (int g = 0; g < G_; ++g) {
-            const int pos = q * G_ + g;
-            if (pos < P.KB && !((P.mv.bits[(int64_t)i * H->words_per_row + (pos >> 6)] >> (pos & 63)) & 1)) {
+            const int pos = pos0 + g;
+            const uint64_t word = keep_word[(pos >> 6) != (pos0 >> 6)];
+            if (pos < P.KB && !((word >> (pos & 63)) & 1)) {
                 char *z = P.C + (int64_t)i * P.BM * ldc + (int64_t)pos * P.BK * sizeof(OutT);
                 const int row_chunks = P.BK * (int)sizeof(OutT) / 16;
                 for (int c = threadIdx.x; c < TM * row_chunks; c += NT)
                     *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
             }
         }
-        const int rp = P.mv.row_ptr[i];
-        const int cnt = P.mv.row_ptr[i + 1] - rp;
-        if (q * G_ >= cnt) return;
-        const int blocks_valid = cnt - q * G_ < G_ ? cnt - q * G_ : G_;
-        const int cshift = (P.BK == 128);             // 64-column chunks per block, log2
-        chunks_valid = blocks_valid << cshift;
+        if (blocks_valid <= 0) return;
 #pragma unroll
         for (int g = 0; g < DXG; ++g) {
-            const int b = g >> cshift;                // which of the gathered blocks (a missing one repeats the last)
-            const int j = P.mv.col_idx[rp + q * G_ + (b < blocks_valid ? b : blocks_valid - 1)];
-            const int64_t col0 = (int64_t)j * P.BK + (g & ((1 << cshift) - 1)) * 64;
+            const int64_t col0 = (int64_t)jg[g] * P.BK + (g & ((1 << cshift) - 1)) * 64;
             bgrp[g] = P.B + col0 * ldb;
             cgrp[g] = P.C + (int64_t)i * P.BM * ldc + col0 * sizeof(OutT);
         }
@@ -458,6 +501,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
+    GEMM_TICK(1);
     if (nsteps > 0) {
         using SliceA = Slice<A_KMAJ, TM, RAGGED && OP == DX>;
         using SliceB = Slice<B_KMAJ, TN, RAGGED, DXG>;
@@ -523,8 +567,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
         using DmaB = typename std::conditional<B_KMAJ, DmaK<TN, DXG, NW>, DmaT<TN, NW>>::type;
         DmaA da;
         DmaB db;
-        if constexpr (A_DMA) da.init(lda);
-        if constexpr (B_DMA) db.init(ldb);
+        if constexpr (A_DMA) da.init(lda, wave);
+        if constexpr (B_DMA) db.init(ldb, wave);
         constexpr int NDMA_A = A_DMA ? TM / (8 * NW) : 0, NDMA_B = B_DMA ? TN / (8 * NW) : 0;   // per wavefront and slice
         constexpr int NDMA_ITER = NDMA_A + NDMA_B;
         // direct-load instruction j of a slice (A's first, then B's) into stage st
@@ -545,11 +589,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
         //      stays in registers. ----
         {
             const Src s0 = src_of(0);
-            dma_range(s0, stage_ptr(0), 0, NDMA_ITER);
+            if (!SPEC || loader) dma_range(s0, stage_ptr(0), 0, NDMA_ITER);
             if constexpr (!A_DMA) { ra.load(s0.a, lda, a_lim(s0)); ra.template store<0, 1>(stage_ptr(0)); }
             if constexpr (!B_DMA) { rb.load(s0.b, ldb, s0.lim); rb.template store<0, 1>(stage_ptr(0) + A_BYTES); }
             const Src s1 = src_of(1);
-            if constexpr (STAGES == 3) dma_range(s1, stage_ptr(1), 0, NDMA_ITER);
+            if constexpr (STAGES == 3) { if (!SPEC || loader) dma_range(s1, stage_ptr(1), 0, NDMA_ITER); }
             if constexpr (!A_DMA) ra.load(s1.a, lda, a_lim(s1));
             if constexpr (!B_DMA) rb.load(s1.b, ldb, s1.lim);
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
@@ -567,26 +611,47 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = In<T>::mfma(fa[buf][mi], fb[buf][ni], acc[mi][ni]);
+                for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = In<T>::mfma(fb[buf][ni], fa[buf][mi], acc[mi][ni]);
         };
         constexpr int NM = MI * NI, NOPS = MI + NI;
+        // operand reads requested per MFMA in the fine-grained loop (at least what fits the group)
+        constexpr int RPM_MIN = ceil_div(NOPS, NM >= 4 ? NM - 2 : NM), RPM = 2 > RPM_MIN ? 2 : RPM_MIN;
+        static_assert((NM >= 4 ? NM - 2 : NM) * RPM >= NOPS, "every operand of the next group must be requested within the group");
         constexpr int NFR = MI * (A_TR ? 2 : 1) + NI * (B_TR ? 2 : 1);              // LDS reads per operand set
 
         int st0 = 0, st1 = 1, st2 = 2;      // stages of slices s, s+1, s+2
-        read_frags(0, stage_ptr(0), 0);
+        GEMM_TICK(2);
+        if (!loader) read_frags(0, stage_ptr(0), 0);
 
-        if constexpr (A_DMA && B_DMA) {
+        if (loader) {
+            // A loader wavefront: per slice, all of this wavefront's direct loads of slice
+            // s + AHEAD, then wait until its loads of slice s + 1 have landed and meet the others.
+            if constexpr (SPEC) {
+                int64_t nxt_off = offset_of(AHEAD);
+                for (int s = 0; s < nsteps; ++s) {
+                    char *nx2 = stage_ptr(STAGES == 3 ? st2 : st1);
+                    const Src s2 = src_at(nxt_off);
+                    refresh_for(s + AHEAD + 1);
+                    dma_range(s2, nx2, 0, NDMA_ITER);
+                    nxt_off = offset_of(s + 1 + AHEAD);
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(STAGES == 3 ? NDMA_ITER : 0));
+                    __builtin_amdgcn_s_barrier();
+                    const int t0 = st0; st0 = st1; st1 = (STAGES == 3 ? st2 : t0); st2 = t0;
+                }
+            }
+        } else if constexpr (A_DMA && B_DMA) {
+            constexpr bool WITH_DMA = !SPEC;     // otherwise the loader wavefronts issue them
             // Every instruction has its place: MFMA c of a group is followed by its share of the
             // group's operand reads and of the slice's direct loads, and nothing moves across
             // the fence after it.  The direct loads of slice s+2 are spread over groups 0..2.
             // All indices are compile-time so that operands and accumulators stay in registers.
-            int64_t nxt_off = offset_of(AHEAD);
+            int64_t nxt_off = WITH_DMA ? offset_of(AHEAD) : 0;
             for (int s = 0; s < nsteps; ++s) {
                 const char *cur = stage_ptr(st0);
                 const char *nx1 = stage_ptr(st1);
                 char *nx2 = stage_ptr(STAGES == 3 ? st2 : st1);      // where this iteration's direct loads land
-                const Src s2 = src_at(nxt_off);                       // slice s + AHEAD
-                refresh_for(s + AHEAD + 1);
+                const Src s2 = src_at(WITH_DMA ? nxt_off : 0);        // slice s + AHEAD
+                if constexpr (WITH_DMA) refresh_for(s + AHEAD + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<4>([&](auto gi) __attribute__((always_inline)) {
                     constexpr int g = decltype(gi)::value;
@@ -601,23 +666,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
                             // slice s+1 must have landed everywhere: this wavefront's direct loads of it
                             // were issued one iteration ago (only this iteration's may stay in flight),
                             // and every wavefront must be done reading slice s before its stage is reused
-                            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(STAGES == 3 ? NDMA_ITER : 0));
+                            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(!WITH_DMA ? 63 : (STAGES == 3 ? NDMA_ITER : 0)));
                             __builtin_amdgcn_s_barrier();
                             __builtin_amdgcn_sched_barrier(0);
                         }
-                        acc[mi][ni] = In<T>::mfma(fa[cb][mi], fb[cb][ni], acc[mi][ni]);
-                        // operands for the next group (kk = g+1 of this slice, or kk = 0 of slice s+1),
-                        // B's first: MFMA c needs A[c / NI] and B[c % NI]
-                        constexpr int r0 = c < NB ? 0 : (c - NB) * NOPS / (NM - NB);
-                        constexpr int r1 = c < NB ? 0 : (c - NB + 1) * NOPS / (NM - NB);
+                        acc[mi][ni] = In<T>::mfma(fb[cb][ni], fa[cb][mi], acc[mi][ni]);
+                        // operands for the next group (kk = g+1 of this slice, or kk = 0 of slice s+1) go to the
+                        // other register set, so they are requested as early as the group allows, RPM per
+                        // MFMA, in the order the next group's MFMAs (A index major) first use them:
+                        // A0, B0 .. B(NI-1), A1 .. A(MI-1)
+                        constexpr int r0 = c < NB ? 0 : (c - NB) * RPM < NOPS ? (c - NB) * RPM : NOPS;
+                        constexpr int r1 = c < NB ? 0 : (c - NB + 1) * RPM < NOPS ? (c - NB + 1) * RPM : NOPS;
                         static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
                             constexpr int r = r0 + decltype(ri)::value;
                             const char *st = g < 3 ? cur : nx1;
                             constexpr int kk = g < 3 ? g + 1 : 0;
-                            if constexpr (r < NI) fb[nb][r] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + r * 32, kk);
+                            if constexpr (r == 0) fa[nb][0] = read_frag<T, A_TR, TM>(st, wm * WTM, kk);
+                            else if constexpr (r <= NI) fb[nb][r - 1] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + (r - 1) * 32, kk);
                             else fa[nb][r - NI] = read_frag<T, A_TR, TM>(st, wm * WTM + (r - NI) * 32, kk);
                         });
-                        if constexpr (g < 3) {
+                        if constexpr (g < 3 && WITH_DMA) {
                             constexpr int gc = g * NM + c;
                             constexpr int j0 = gc * NDMA_ITER / (3 * NM), j1 = (gc + 1) * NDMA_ITER / (3 * NM);
                             static_for<j1 - j0>([&](auto ji) __attribute__((always_inline)) {
@@ -625,7 +693,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
                                 if constexpr (j < NDMA_A) da.issue(s2.a, lda, nx2, j);
                                 else db.issue(s2.b, ldb, nx2 + A_BYTES, j - NDMA_A);
                             });
-                        } else if constexpr (c == 0) {
+                        } else if constexpr (g == 3 && c == 0 && WITH_DMA) {
                             nxt_off = offset_of(s + 1 + AHEAD);   // list lookup for the next iteration
                         }
                         __builtin_amdgcn_sched_barrier(0);
@@ -674,32 +742,62 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(GemmParams P)
         }
     }
 
-    // epilogue: scale in fp32, round once, store.  Accumulator register r of lane l is
-    // row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 patch.
-    const float scale = P.scale;
+    // epilogue: scale in fp32, round once, and store whole rows.  The MFMAs were issued with
+    // the operands swapped (B's columns as the instruction's rows), so accumulator register r of
+    // lane l is row l%32, column 8*(r/4) + 4*(l/32) + r%4 of its 32x32 patch: each register quad
+    // is four consecutive columns.  A wavefront parks its WTM x WTN sub-tile in its own piece of
+    // LDS (rows padded by one quad against bank conflicts) and writes it out 16 bytes per lane,
+    // so that a store instruction covers full 128-byte lines instead of 32 scattered pieces.
+    GEMM_TICK(3);
+    {
+        constexpr int ESZ = (int)sizeof(OutT);
+        constexpr int ROWB = WTN * ESZ, RS = ROWB + 4 * ESZ, REGION = WTM * RS;
+        static_assert(NW * REGION <= stages_for(TM, TN) * STAGE_BYTES, "epilogue staging must fit in the operand stages");
+        // operand stages are dead: no direct load may still be landing, no wavefront still reading
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+        __builtin_amdgcn_s_barrier();
+        if (loader) return;
+        char *reg = smem + wave * REGION;
+        const float scale = P.scale;
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            int col = wn * WTN + ni * 32 + (lane & 31);
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = mi * 32 + (lane & 31), col = ni * 32 + q * 8 + (lane >> 5) * 4;
+                    const float v0 = acc[mi][ni][4 * q] * scale, v1 = acc[mi][ni][4 * q + 1] * scale;
+                    const float v2 = acc[mi][ni][4 * q + 2] * scale, v3 = acc[mi][ni][4 * q + 3] * scale;
+                    char *dst = reg + row * RS + col * ESZ;
+                    if constexpr (ESZ == 4) {
+                        *reinterpret_cast<float4 *>(dst) = make_float4(v0, v1, v2, v3);
+                    } else {
+                        typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
+                        const out4 o = {static_cast<OutT>(v0), static_cast<OutT>(v1), static_cast<OutT>(v2), static_cast<OutT>(v3)};
+                        *reinterpret_cast<out4 *>(dst) = o;
+                    }
+                }
+        constexpr int CH = ROWB / 16, RPI = 64 / CH;         // 16-byte pieces per row; rows per store instruction
+        static_assert(CH <= 64 && 64 % CH == 0 && WTM % RPI == 0, "sub-tile rows must tile a wavefront");
+#pragma unroll
+        for (int it = 0; it < WTM / RPI; ++it) {
+            const int row = it * RPI + lane / CH, ch = lane % CH;
+            const uint4 v = *reinterpret_cast<const uint4 *>(reg + row * RS + ch * 16);
+            int col = wn * WTN + ch * (16 / ESZ);               // column within the tile
             char *cbase = c_tile;
-            bool ok = col < c_lim;
+            bool ok = col < c_lim;                             // c_lim is a multiple of 8
             if constexpr (OP == DX) {
-                const int g = col >> 6;               // uniform per wavefront and ni
+                const int g = col >> 6;
                 ok = g < chunks_valid;
                 cbase = cgrp[0];
 #pragma unroll
                 for (int gg = 1; gg < DXG; ++gg) cbase = (g == gg) ? cgrp[gg] : cbase;
                 col &= 63;
             }
-            if (ok) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = wm * WTM + mi * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                    store_out(reinterpret_cast<OutT *>(cbase + row * ldc) + col, acc[mi][ni][r] * scale);
-                }
-            }
+            if (ok) *reinterpret_cast<uint4 *>(cbase + (int64_t)(wm * WTM + row) * ldc + col * ESZ) = v;
         }
+        GEMM_TICK(4);
+    }
 }
 
 // WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
@@ -707,8 +805,9 @@ template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR =
 int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
 {
     constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
-    auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false>;
-    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WMR, WNR, true>;
+    constexpr bool SPEC = TM >= 128;     // loader wavefronts for the one-workgroup-per-CU tiles
+    auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false, SPEC>;
+    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WMR, WNR, true, false>;
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_full),
@@ -721,7 +820,7 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
     }
     if (grid <= 0) return SDROP_OK;
     if (ragged) hipLaunchKernelGGL(k_ragged, dim3(grid), dim3(WMR * WNR * 64), LDS_BYTES, stream, P);
-    else hipLaunchKernelGGL(k_full, dim3(grid), dim3(WM * WN * 64), LDS_BYTES, stream, P);
+    else hipLaunchKernelGGL(k_full, dim3(grid), dim3(WM * WN * 64 * (SPEC ? 2 : 1)), LDS_BYTES, stream, P);
     return hip_status(hipGetLastError());
 }
 
@@ -894,6 +993,13 @@ int check_gemm_args(const void *a, const void *b, const void *mask, void *out,
 }
 
 }  // namespace sdrop
+
+#ifdef SDROP_GEMM_TIMING
+extern "C" int sdrop_debug_ticks(long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(sdrop::g_ticks), sizeof(long long) * n);
+}
+#endif
 
 extern "C" {
 
