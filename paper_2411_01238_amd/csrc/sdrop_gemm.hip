@@ -44,6 +44,7 @@
 // loop, is ~2.0 GHz with the MFMAs alone, ~1.55 GHz once the operand reads from LDS are added
 // and ~1.4 GHz with the loads as well, at 84 % MFMA duty (1214 clocks per slice against 1024).
 #include "sdrop_internal.h"
+#include <stdlib.h>
 #include <type_traits>
 #include <utility>
 
@@ -106,8 +107,10 @@ __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlan
 #ifdef SDROP_GEMM_TIMING   // development aid: per-workgroup phase timestamps
 __device__ long long g_ticks[16384 * 16];
 #define GEMM_TICK(n) do { if (threadIdx.x == 0 && blockIdx.x < 16384) { g_ticks[blockIdx.x * 16 + (n)] = wall_clock64(); g_ticks[blockIdx.x * 16 + 8 + (n)] = clock64(); } } while (0)
+#define GEMM_TICKW(n) do { if (threadIdx.x == 0 && blockIdx.x < 16384 && (n) < 16) g_ticks[blockIdx.x * 16 + (n)] = wall_clock64(); } while (0)
 #else
 #define GEMM_TICK(n) do { } while (0)
+#define GEMM_TICKW(n) do { } while (0)
 #endif
 
 struct GemmParams {
@@ -119,6 +122,7 @@ struct GemmParams {
     int32_t BM, BK, MB, KB;
     int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
     int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)
+    int32_t total_tiles; // persistent kernels: tiles of the whole launch
     float scale;
     double p;           // host only: dropout probability, for choosing tile shapes
 };
@@ -800,7 +804,328 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
     }
 }
 
+// s_waitcnt immediate that waits only for vector-memory operations (at most `vm` outstanding).
+constexpr int waitcnt_vm_only(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// FWD and DW for 128-row tiles without ragged edges, as a persistent kernel: one workgroup per
+// CU walks a fixed sequence of tiles, and the slices of consecutive tiles form ONE stream
+// through the three LDS stages.  The four loader wavefronts run two slices ahead of the four
+// computing wavefronts across tile boundaries, so the first operands of the next tile arrive
+// while the current tile is still being multiplied and stored; what the per-tile launch pays
+// for every tile (index look-ups, the latency of the first loads: about 4 us, against 25 us of
+// MFMAs per tile at 4096^3 with half the blocks kept) is paid once per workgroup.
+//
+// Tile sequence of workgroup w of G: tiles are numbered in the mask's schedule order (heaviest
+// block rows / columns first), and round k takes tile k*G + w (k even) or k*G + G-1-w (k odd),
+// so a workgroup that drew a heavy tile in one round draws a light one in the next.
+//
+// Synchronisation: slice g of the workgroup's stream lives in stage g % 3.  Barrier g is passed
+// by the computing wavefronts when they have read all of slice g, and by the loaders when their
+// part of slice g+1 has landed; the loaders issue slice g+2 (into the stage of slice g-1) after
+// barrier g-1.  One more barrier, before the first slice, publishes slice 0.  Both roles derive
+// the number of slices from the same mask lists, so they execute the same number of barriers.
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
+{
+    static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
+    constexpr int NW = WM * WN;
+    static_assert(NW == 4, "one computing and one loading wavefront per SIMD");
+    constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
+    constexpr bool A_KMAJ = (OP == FWD), A_TR = !A_KMAJ, B_TR = true;
+    constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int STAGES = 3, AHEAD = 2;
+    constexpr int ESZ = (int)sizeof(OutT);
+    constexpr int STAGING = 32 * 128;           // per computing wavefront: 32 rows of 128 bytes
+    constexpr int NIP = 128 / (32 * ESZ);       // 32-column accumulator blocks per 128-byte row
+    static_assert(NI % NIP == 0, "a wavefront's columns must fill whole 128-byte rows");
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *const staging = smem + STAGES * STAGE_BYTES;
+
+    const MaskHeader *H = P.mv.hdr;
+    if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = wave_all >= NW;
+    const int wave = loader ? wave_all - NW : wave_all;
+    const int wm = wave / WN, wn = wave % WN;
+    const int G = gridDim.x, w = blockIdx.x;
+    const int total = P.total_tiles;
+    const int BLK = (OP == FWD) ? P.BK : P.BM;            // extent of a mask block along the reduction
+    const int sub_shift = (BLK == 128), sub_mask = (1 << sub_shift) - 1;
+    const int64_t lda = P.K * 2, ldb = P.N * 2, ldc = P.N * (int64_t)ESZ;
+    const int32_t *const order = (OP == FWD) ? P.mv.row_order : P.mv.col_order;
+    const int32_t *const ptr = (OP == FWD) ? P.mv.row_ptr : P.mv.col_ptr;
+    const int32_t *const lists = (OP == FWD) ? P.mv.col_idx : P.mv.row_idx;
+    const int per_line = P.n_tiles * P.splits;            // tiles per block row / column
+
+    // tile number of round k (may be >= total: the sequence has ended)
+    auto tile_of = [&](int k) __attribute__((always_inline)) -> int { return k * G + ((k & 1) ? G - 1 - w : w); };
+    // position in the schedule order; clamped so that look-ahead beyond the end stays in bounds
+    auto rank_of = [&](int t) __attribute__((always_inline)) -> int { return (t < total ? t : total - 1) / per_line; };
+    // the part of a kept list of `cnt` entries that tile t reduces: [lo, lo + len)
+    auto part_of = [&](int t, int cnt, int &lo) __attribute__((always_inline)) -> int {
+        if (P.splits == 1) { lo = 0; return cnt; }
+        const int part = t % P.splits;
+        lo = (int)((int64_t)cnt * part / P.splits);
+        return (int)((int64_t)cnt * (part + 1) / P.splits) - lo;
+    };
+    auto stage_ptr = [&](int st) __attribute__((always_inline)) -> char * { return smem + st * STAGE_BYTES; };
+
+    if (loader) {
+        // ---------------- loaders: the stream of slices ----------------
+        using DmaA = typename std::conditional<A_KMAJ, DmaK<TM, 1, NW>, DmaT<TM, NW>>::type;
+        using DmaB = DmaT<TN, NW>;
+        DmaA da;
+        DmaB db;
+        da.init(lda, wave);
+        db.init(ldb, wave);
+        constexpr int NDMA_A = TM / (8 * NW), NDMA_B = TN / (8 * NW), NDMA = NDMA_A + NDMA_B;
+
+        // Look-ups run three tiles ahead of the tile being issued, one level of indirection per
+        // tile, so that no load waits for the one before it: order[] of tile k+3, the list bounds
+        // of tile k+2, the first two list entries of tile k+1.
+        // The mask lists do not change while the kernel runs: read through the constant address
+        // space they keep the scalar load form also after a barrier (which otherwise counts as a
+        // possible write to anything in global memory).
+        typedef const __attribute__((address_space(4))) int32_t *const_i32;
+        const const_i32 k_order = (const_i32)(uintptr_t)order, k_ptr = (const_i32)(uintptr_t)ptr;
+        const const_i32 k_lists = (const_i32)(uintptr_t)lists;
+        struct Meta { int t, ord, start, len, e0, e1; };
+        auto level1 = [&](int k) __attribute__((always_inline)) -> Meta {
+            Meta m;
+            m.t = tile_of(k);
+            m.ord = k_order[rank_of(m.t)];
+            m.start = m.len = m.e0 = m.e1 = 0;
+            return m;
+        };
+        auto level2 = [&](Meta &m) __attribute__((always_inline)) {
+            const int p0 = k_ptr[m.ord], cnt = k_ptr[m.ord + 1] - p0;
+            int lo;
+            m.len = part_of(m.t < total ? m.t : total - 1, cnt, lo);
+            m.start = p0 + lo;
+        };
+        auto entry = [&](const Meta &m, int e) __attribute__((always_inline)) -> int {
+            const int ec = e < m.len ? e : m.len - 1;
+            return k_lists[ec < 0 ? 0 : m.start + ec];
+        };
+        auto level3 = [&](Meta &m) __attribute__((always_inline)) { m.e0 = entry(m, 0); m.e1 = entry(m, 1); };
+
+        Meta cur, n1, n2, n3;
+        n1 = level1(0); level2(n1); level3(n1);
+        n2 = level1(1); level2(n2);
+        n3 = level1(2);
+        int k = -1;                      // round of the tile being issued
+        int s = 0, nsteps = 0;           // next slice of that tile; its number of slices
+        int e_cur = 0, e_nxt = 0;        // list entries of slice s and of the block after it
+        const char *a_tile = nullptr, *b_tile = nullptr;
+        bool ended = false;
+
+        // issues the next slice of the stream into stage `st`; false when the stream has ended
+        auto issue_next = [&](int st) __attribute__((always_inline)) -> bool {
+            while (s == nsteps) {
+                if (ended) return false;
+                ++k;
+                cur = n1;
+                if (cur.t >= total) { ended = true; return false; }
+                n1 = n2; level3(n1);
+                n2 = n3; level2(n2);
+                n3 = level1(k + 3);
+                s = 0;
+                nsteps = cur.len << sub_shift;
+                e_cur = cur.e0; e_nxt = cur.e1;
+                const int line = cur.t % per_line;
+                const int nt = line / P.splits;
+                if constexpr (OP == FWD) a_tile = P.A + (int64_t)cur.ord * P.BM * lda;
+                else a_tile = P.A + (int64_t)cur.ord * P.BK * 2;
+                b_tile = P.B + (int64_t)nt * TN * 2;
+            }
+            const int64_t off = (int64_t)e_cur * BLK + (int64_t)(s & sub_mask) * TK;
+            const char *const sa[1] = {a_tile + off * (OP == FWD ? 2 : lda)};
+            const char *const sb[1] = {b_tile + off * ldb};
+            char *stp = stage_ptr(st);
+#pragma unroll
+            for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+#pragma unroll
+            for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+            ++s;
+            if ((s & sub_mask) == 0) {
+                e_cur = e_nxt;
+                e_nxt = entry(cur, (s >> sub_shift) + 1);
+            }
+            return true;
+        };
+
+        int issued = 0, st_issue = 0;
+        for (int i = 0; i < AHEAD; ++i)
+            if (issue_next(st_issue)) { ++issued; st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1; }
+        if (issued == 0) return;         // no slice at all: the computing wavefronts meet no barrier either
+        if (issued == AHEAD) __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+        __builtin_amdgcn_s_barrier();    // slice 0 is in place
+        for (int g = 0; g < issued; ++g) {
+            const bool more = issue_next(st_issue);
+            if (more) {
+                ++issued;
+                st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1;
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));      // all but the slice just issued: g+1 is in
+            } else {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+            }
+            __builtin_amdgcn_s_barrier();
+        }
+        return;
+    }
+
+    // ---------------- computing wavefronts ----------------
+    // Look-ups two tiles ahead (order[] of tile k+2, list bounds of tile k+1), as vector loads:
+    // they are waited for with the vector-memory counter, which the main loop never waits on.
+    struct CMeta { int t, ord, len; };
+    auto c_level1 = [&](int k) __attribute__((always_inline)) -> CMeta {
+        CMeta m;
+        m.t = tile_of(k);
+        m.ord = order[rank_of(m.t)];
+        m.len = 0;
+        return m;
+    };
+    auto c_level2 = [&](CMeta &m) __attribute__((always_inline)) {
+        const int o = uni(m.ord);
+        const int cnt = ptr[o + 1] - ptr[o];
+        int lo;
+        m.len = part_of(m.t < total ? m.t : total - 1, cnt, lo);
+    };
+    CMeta cur, n1, n2;
+    cur = c_level1(0); c_level2(cur);
+    n1 = c_level1(1);
+    n2 = c_level1(2);
+
+    typename In<T>::vec fa[2][MI], fb[2][NI];
+    f32x16 acc[MI][NI];
+    constexpr int NM = MI * NI, NOPS = MI + NI;
+    constexpr int RPM_MIN = ceil_div(NOPS, NM >= 4 ? NM - 2 : NM), RPM = 2 > RPM_MIN ? 2 : RPM_MIN;
+    int st0 = 0, st1 = 1, st2 = 2;       // stages of the stream's slices g, g+1, g+2
+    bool started = false;
+    const float scale = P.scale;
+    char *const reg = staging + wave * STAGING;
+
+    for (int k = 0;; ++k) {
+        if (cur.t >= total) break;
+        const int t = cur.t, ord = uni(cur.ord), nsteps = uni(cur.len) << sub_shift;
+        GEMM_TICKW(k * 4);
+        // look-ups for the tiles after this one (n1.ord was requested a whole tile ago)
+        c_level2(n1);
+        CMeta n3 = c_level1(k + 3);
+
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+        if (nsteps > 0 && !started) {
+            started = true;
+            __builtin_amdgcn_s_barrier();                     // slice 0 is in place
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) fa[0][mi] = read_frag<T, A_TR, TM>(stage_ptr(0), wm * WTM + mi * 32, 0);
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) fb[0][ni] = read_frag<T, B_TR, TN>(stage_ptr(0) + A_BYTES, wn * WTN + ni * 32, 0);
+        }
+        for (int s = 0; s < nsteps; ++s) {
+            const char *cur_st = stage_ptr(st0);
+            const char *nx1 = stage_ptr(st1);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<4>([&](auto gi) __attribute__((always_inline)) {
+                constexpr int g = decltype(gi)::value;
+                constexpr int NB = (g == 3 && NM >= 4) ? 2 : 0;   // MFMAs of the last group that precede the barrier
+                static_for<NM>([&](auto ci) __attribute__((always_inline)) {
+                    constexpr int c = decltype(ci)::value;
+                    constexpr int mi = c / NI, ni = c % NI, cb = g & 1, nb = (g + 1) & 1;
+                    if constexpr (g == 3 && c == NB) {
+                        // every wavefront is done reading this slice; the next one has landed
+                        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
+                        __builtin_amdgcn_s_barrier();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    acc[mi][ni] = In<T>::mfma(fb[cb][ni], fa[cb][mi], acc[mi][ni]);
+                    constexpr int r0 = c < NB ? 0 : (c - NB) * RPM < NOPS ? (c - NB) * RPM : NOPS;
+                    constexpr int r1 = c < NB ? 0 : (c - NB + 1) * RPM < NOPS ? (c - NB + 1) * RPM : NOPS;
+                    static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
+                        constexpr int r = r0 + decltype(ri)::value;
+                        const char *st = g < 3 ? cur_st : nx1;
+                        constexpr int kk = g < 3 ? g + 1 : 0;
+                        if constexpr (r == 0) fa[nb][0] = read_frag<T, A_TR, TM>(st, wm * WTM, kk);
+                        else if constexpr (r <= NI) fb[nb][r - 1] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + (r - 1) * 32, kk);
+                        else fa[nb][r - NI] = read_frag<T, A_TR, TM>(st, wm * WTM + (r - NI) * 32, kk);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            });
+            const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+            if (s == 0) GEMM_TICKW(k * 4 + 1);
+        }
+        GEMM_TICKW(k * 4 + 2);
+
+        // epilogue: scale in fp32, round once, park 32 rows x 128 bytes at a time in this
+        // wavefront's own piece of LDS and write them out as whole 128-byte lines.  The MFMAs took
+        // the operands swapped, so accumulator register 4q+e of lane l is row l%32, column
+        // 8q + 4(l/32) + e of its 32x32 block.  8-byte slot u of row r lies at slot u ^ (r & 15): the
+        // 8-byte writes of 32 rows then spread over all banks, and a 16-byte read finds its two
+        // halves in one 16-byte piece, exchanged when r is odd.
+        {
+            const int line = t % per_line;
+            const int nt = line / P.splits, part = line % P.splits;
+            char *c_tile;
+            if constexpr (OP == FWD) c_tile = P.C + (int64_t)ord * P.BM * ldc + (int64_t)nt * TN * ESZ;
+            else c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)ord * P.BK * ldc + (int64_t)nt * TN * ESZ;
+            c_tile += (int64_t)(wm * WTM) * ldc + (int64_t)(wn * WTN) * ESZ;
+            const int wrow = lane & 31, whalf = lane >> 5;
+            const int rrow = lane >> 3, rch = lane & 7;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int nj = 0; nj < NI / NIP; ++nj) {
+#pragma unroll
+                    for (int nl = 0; nl < NIP; ++nl)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x16 &a = acc[mi][nj * NIP + nl];
+                            const float v0 = a[4 * q] * scale, v1 = a[4 * q + 1] * scale;
+                            const float v2 = a[4 * q + 2] * scale, v3 = a[4 * q + 3] * scale;
+                            if constexpr (ESZ == 4) {
+                                // 16 bytes per lane: 16-byte slot 2q + half, exchanged as a whole with (row & 7)
+                                const int slot = (2 * q + whalf) ^ (wrow & 7);
+                                *reinterpret_cast<float4 *>(reg + wrow * 128 + slot * 16) = make_float4(v0, v1, v2, v3);
+                            } else {
+                                typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
+                                const out4 o = {static_cast<OutT>(v0), static_cast<OutT>(v1), static_cast<OutT>(v2), static_cast<OutT>(v3)};
+                                const int slot8 = (nl * 8 + 2 * q + whalf) ^ (wrow & 15);
+                                *reinterpret_cast<out4 *>(reg + wrow * 128 + slot8 * 8) = o;
+                            }
+                        }
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int row = it * 8 + rrow;
+                        uint4 v;
+                        if constexpr (ESZ == 4) {
+                            v = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
+                        } else {
+                            const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
+                            v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
+                        }
+                        *reinterpret_cast<uint4 *>(c_tile + (int64_t)(mi * 32 + row) * ldc + (nj * 128) + rch * 16) = v;
+                    }
+                }
+        }
+        GEMM_TICKW(k * 4 + 3);
+        cur = n1; n1 = n2; n2 = n3;
+    }
+}
+
 // WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
+int cu_count();
+
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
 int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
 {
@@ -819,6 +1144,32 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
         attr_set = true;
     }
     if (grid <= 0) return SDROP_OK;
+    if constexpr (SPEC && OP != DX) {
+        if (!ragged) {
+            // persistent form: three operand stages plus 4 KiB of output staging per computing wavefront
+            constexpr int P_LDS = 3 * (TM + TN) * TK * 2 + WM * WN * 4096;
+            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN>;
+            static int pers_ok = -1;    // per instantiation: does the device grant that much LDS?
+            if (pers_ok < 0) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_pers),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+                pers_ok = (e == hipSuccess);
+                if (!pers_ok) (void)hipGetLastError();
+            }
+#ifdef SDROP_GEMM_TIMING
+            const bool pers_off = getenv("SDROP_NO_PERSIST") != nullptr;
+#else
+            const bool pers_off = false;
+#endif
+            if (pers_ok && !pers_off) {
+                GemmParams Q = P;
+                Q.total_tiles = grid;
+                const int ncu = cu_count();
+                hipLaunchKernelGGL(k_pers, dim3(grid < ncu ? grid : ncu), dim3(WM * WN * 128), P_LDS, stream, Q);
+                return hip_status(hipGetLastError());
+            }
+        }
+    }
     if (ragged) hipLaunchKernelGGL(k_ragged, dim3(grid), dim3(WMR * WNR * 64), LDS_BYTES, stream, P);
     else hipLaunchKernelGGL(k_full, dim3(grid), dim3(WM * WN * 64 * (SPEC ? 2 : 1)), LDS_BYTES, stream, P);
     return hip_status(hipGetLastError());
@@ -838,8 +1189,6 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, Ou
     out[e] = static_cast<OutT>(acc.x * scale); out[e + 1] = static_cast<OutT>(acc.y * scale);
     out[e + 2] = static_cast<OutT>(acc.z * scale); out[e + 3] = static_cast<OutT>(acc.w * scale);
 }
-
-int cu_count();
 
 // Parts the reduction of DW is cut into.  DW has only KB * ceil(N/256) output tiles; when
 // that is fewer than the chip has CUs, each block column's kept-row list is cut into parts
@@ -937,6 +1286,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
     P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
     P.n_tiles = 0;
     P.splits = 1;
+    P.total_tiles = 0;
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
     P.p = p;
     hipStream_t st = static_cast<hipStream_t>(stream);
