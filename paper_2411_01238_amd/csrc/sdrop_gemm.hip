@@ -447,45 +447,74 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)j * P.BK * ldc + (int64_t)nt * TN * sizeof(OutT);
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
     } else {
-        // blockIdx.x = q * MB + i.  The workgroup computes the kept blocks of ranks
-        // [q*G, q*G+G) of block row i as one TM x (G*BK) tile, and zero-fills the block
-        // positions [q*G, q*G+G) of row i that are dropped.
-        const int G_ = TN / P.BK;
-        const int i = blockIdx.x % P.MB, q = blockIdx.x / P.MB;
+        const int G_ = TN / P.BK;                     // kept blocks gathered into one tile
         lda = P.N * esz; ldb = P.N * esz; ldc = P.K * (int64_t)sizeof(OutT);
-        // every index is fetched before the zero fill below: a load that follows a store cannot
-        // be proven unaliased and would lose its scalar form
-        const int rp = uni(P.mv.row_ptr[i]);
-        const int cnt = uni(P.mv.row_ptr[i + 1]) - rp;
-        const int blocks_valid = cnt - q * G_ < G_ ? cnt - q * G_ : G_;   // <= 0: nothing to compute
         const int cshift = (P.BK == 128);             // 64-column chunks per block, log2
-        chunks_valid = blocks_valid << cshift;
+        const int row_chunks = P.BK * (int)sizeof(OutT) / 16;
+        auto zero_block = [&](int zi, int zj) __attribute__((always_inline)) {
+            char *z = P.C + (int64_t)zi * P.BM * ldc + (int64_t)zj * P.BK * sizeof(OutT);
+            for (int c = threadIdx.x; c < TM * row_chunks; c += NT)
+                *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
+        };
+        int i, blocks_valid;                          // block row; kept blocks in this tile (<= 0: nothing to compute)
         int jg[NGRP_MAX] = {0, 0, 0, 0};
-        if (blocks_valid > 0) {
+        // In both forms every index is fetched before the zero fill: a load that follows a store
+        // cannot be proven unaliased and would lose its scalar form.
+        if (G_ == 1) {
+            // One kept block per tile.  Two duties per workgroup.  (1) Zero fill: block position
+            // blockIdx.x, if it is dropped.  (2) Compute: kept block e of the row-major list, where the
+            // hardware's round-robin placement of workgroups on the 8 XCDs is undone: workgroup b runs
+            // on XCD b % 8 and takes e = (b % 8) * ceil(nnz / 8) + b / 8.  Every XCD so gets the same
+            // number of tiles (its CUs run one workgroup each, so a single extra tile on one XCD
+            // costs a whole round: 3 instead of 2 at 4096^3 with half the blocks kept) and a
+            // contiguous run of block rows, whose dY tiles stay in its L2.
+            const int b = blockIdx.x;
+            const int nnz = H->nnz;
+            const int per_xcd = (nnz + 7) >> 3;
+            const int e = (b & 7) * per_xcd + (b >> 3);
+            const bool computes = (b >> 3) < per_xcd && e < nnz;
+            const int ec = computes ? e : 0;          // blk_row / col_idx have room for at least one entry
+            i = uni(P.mv.blk_row[ec]);
+            jg[0] = uni(P.mv.col_idx[ec]);
 #pragma unroll
-            for (int g = 0; g < DXG; ++g) {
-                const int b = g >> cshift;            // which of the gathered blocks (a missing one repeats the last)
-                jg[g] = uni(P.mv.col_idx[rp + q * G_ + (b < blocks_valid ? b : blocks_valid - 1)]);
+            for (int g = 1; g < DXG; ++g) jg[g] = jg[0];
+            const int total = P.MB * P.KB;
+            const int zb = b < total ? b : total - 1;
+            const int zi = zb / P.KB, zj = zb % P.KB;
+            const uint64_t zword = P.mv.bits[(int64_t)zi * H->words_per_row + (zj >> 6)];
+            if (b < total && !((zword >> (zj & 63)) & 1)) zero_block(zi, zj);
+            blocks_valid = computes ? 1 : 0;
+        } else {
+            // blockIdx.x = q * MB + i.  The workgroup computes the kept blocks of ranks
+            // [q*G, q*G+G) of block row i as one TM x (G*BK) tile, and zero-fills the block
+            // positions [q*G, q*G+G) of row i that are dropped.
+            i = blockIdx.x % P.MB;
+            const int q = blockIdx.x / P.MB;
+            const int rp = uni(P.mv.row_ptr[i]);
+            const int cnt = uni(P.mv.row_ptr[i + 1]) - rp;
+            blocks_valid = cnt - q * G_ < G_ ? cnt - q * G_ : G_;
+            if (blocks_valid > 0) {
+#pragma unroll
+                for (int g = 0; g < DXG; ++g) {
+                    const int bb = g >> cshift;       // which of the gathered blocks (a missing one repeats the last)
+                    jg[g] = uni(P.mv.col_idx[rp + q * G_ + (bb < blocks_valid ? bb : blocks_valid - 1)]);
+                }
+            }
+            uint64_t keep_word[2];                    // the bits of positions [q*G_, q*G_ + G_) lie in at most two words
+            const int pos0 = q * G_;
+            {
+                const uint64_t *row_bits = P.mv.bits + (int64_t)i * H->words_per_row;
+                const int w0 = pos0 >> 6, w1 = (pos0 + G_ - 1) >> 6, wmax = (P.KB - 1) >> 6;
+                keep_word[0] = row_bits[w0 < wmax ? w0 : wmax];
+                keep_word[1] = row_bits[w1 < wmax ? w1 : wmax];
+            }
+            for (int g = 0; g < G_; ++g) {
+                const int pos = pos0 + g;
+                const uint64_t word = keep_word[(pos >> 6) != (pos0 >> 6)];
+                if (pos < P.KB && !((word >> (pos & 63)) & 1)) zero_block(i, pos);
             }
         }
-        uint64_t keep_word[2];                        // the bits of positions [q*G_, q*G_ + G_) lie in at most two words
-        const int pos0 = q * G_;
-        {
-            const uint64_t *row_bits = P.mv.bits + (int64_t)i * H->words_per_row;
-            const int w0 = pos0 >> 6, w1 = (pos0 + G_ - 1) >> 6, wmax = (P.KB - 1) >> 6;
-            keep_word[0] = row_bits[w0 < wmax ? w0 : wmax];
-            keep_word[1] = row_bits[w1 < wmax ? w1 : wmax];
-        }
-        for (int g = 0; g < G_; ++g) {
-            const int pos = pos0 + g;
-            const uint64_t word = keep_word[(pos >> 6) != (pos0 >> 6)];
-            if (pos < P.KB && !((word >> (pos & 63)) & 1)) {
-                char *z = P.C + (int64_t)i * P.BM * ldc + (int64_t)pos * P.BK * sizeof(OutT);
-                const int row_chunks = P.BK * (int)sizeof(OutT) / 16;
-                for (int c = threadIdx.x; c < TM * row_chunks; c += NT)
-                    *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
-            }
-        }
+        chunks_valid = blocks_valid << cshift;
         if (blocks_valid <= 0) return;
 #pragma unroll
         for (int g = 0; g < DXG; ++g) {
@@ -1255,7 +1284,8 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         const int TNsel = (rounds(128) * 0.6 < rounds(256)) ? 128 : 256;
         const int G_ = TNsel / P.BK;
         P.n_tiles = (P.KB + G_ - 1) / G_;
-        const int grid = P.MB * P.n_tiles;
+        // one kept block per tile: a workgroup per block position, rounded up to whole sets of 8 XCDs
+        const int grid = G_ == 1 ? (P.MB * P.KB + 7) / 8 * 8 : P.MB * P.n_tiles;
         const bool ragged = P.N % TK != 0;
         if (TNsel == 256) {
             if (P.BM == 128) return launch<DX, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
