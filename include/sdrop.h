@@ -86,11 +86,18 @@ int sdrop_last_hip_error(void);
  *   row_order int32[MB], col_order int32[KB]: block rows / columns sorted by
  *            descending kept count (ties in unspecified order); used to
  *            schedule heavy tiles first
+ *   loc_row, loc_col  int32[nnz (room for MB*KB)] each: the kept blocks once more, as
+ *            (loc_row[t], loc_col[t]), sorted by (i / 8, j, i % 8): groups of 8 block rows
+ *            in order, inside a group column by column.  Blocks that are neighbours in
+ *            this list share block rows AND block columns, which is the order eq. 2
+ *            computes them in (tiles that run at the same time then share operand
+ *            tiles in cache)
  */
 typedef struct sdrop_mask_layout {
     size_t total_bytes;
     size_t off_bits, off_row_ptr, off_col_idx, off_blk_row;
     size_t off_col_ptr, off_row_idx, off_row_order, off_col_order;
+    size_t off_loc_row, off_loc_col;
     int64_t MB, KB, words_per_row;
 } sdrop_mask_layout_t;
 

@@ -30,6 +30,7 @@ struct MaskView {
     const uint64_t *bits;
     const int32_t *row_ptr, *col_idx, *blk_row;
     const int32_t *col_ptr, *row_idx, *row_order, *col_order;
+    const int32_t *loc_row, *loc_col;
 };
 
 inline MaskView make_view(const void *mask, const sdrop_mask_layout_t &L)
@@ -45,6 +46,8 @@ inline MaskView make_view(const void *mask, const sdrop_mask_layout_t &L)
     v.row_idx = reinterpret_cast<const int32_t *>(b + L.off_row_idx);
     v.row_order = reinterpret_cast<const int32_t *>(b + L.off_row_order);
     v.col_order = reinterpret_cast<const int32_t *>(b + L.off_col_order);
+    v.loc_row = reinterpret_cast<const int32_t *>(b + L.off_loc_row);
+    v.loc_col = reinterpret_cast<const int32_t *>(b + L.off_loc_col);
     return v;
 }
 

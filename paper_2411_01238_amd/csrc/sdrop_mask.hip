@@ -34,7 +34,7 @@ constexpr int kMaxBins = 4096;   // histogram bins of the descending-count sort
 struct MaskParams {
     MaskHeader *hdr;
     uint64_t *bits;
-    int32_t *row_ptr, *col_idx, *blk_row, *col_ptr, *row_idx, *row_order, *col_order;
+    int32_t *row_ptr, *col_idx, *blk_row, *col_ptr, *row_idx, *row_order, *col_order, *loc_row, *loc_col;
     const uint64_t *given_bits;      // non-null: take the bits from here instead of drawing
     int64_t M, K;
     int32_t BM, BK, MB, KB, wpr;
@@ -124,6 +124,38 @@ __device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t
     __syncthreads();
 }
 
+// The kept blocks sorted by (i / 8, j, i % 8): a wavefront takes a group of 8 block rows, lane <->
+// block column.  The group's blocks fill the same range of the list as in row-major order,
+// [row_ptr[8g], row_ptr[8g + 8)); inside it a block's place is the number of kept blocks of the
+// group in earlier columns (a prefix sum over the lanes) plus those above it in its own column.
+// `bits` and `row_ptr` may be in LDS or in global memory written earlier by this workgroup.
+__device__ void local_order(const uint64_t *bits, const int32_t *row_ptr, const MaskParams &P)
+{
+    const int lane = lane_id();
+    for (int i0 = wave_id() * 8; i0 < P.MB; i0 += kMaskWaves * 8) {
+        const int nr = P.MB - i0 < 8 ? P.MB - i0 : 8;
+        int pos = row_ptr[i0];
+        for (int w = 0; w < P.wpr; ++w) {
+            int mine = 0, cnt = 0;                   // bit r: block (i0 + r, 64 w + lane) is kept
+            for (int r = 0; r < nr; ++r) {
+                const int bit = (int)((bits[(int64_t)(i0 + r) * P.wpr + w] >> lane) & 1);
+                mine |= bit << r;
+                cnt += bit;
+            }
+            int incl = cnt;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += up;
+            }
+            int at = pos + incl - cnt;
+            for (int r = 0; r < nr; ++r)
+                if ((mine >> r) & 1) { P.loc_row[at] = i0 + r; P.loc_col[at] = w * 64 + lane; ++at; }
+            pos += __shfl(incl, 63, 64);
+        }
+    }
+}
+
 // The draw: wavefront gid handles word gid of the packed mask (row gid / wpr, word gid % wpr).
 __global__ __launch_bounds__(256) void mask_draw_kernel(MaskParams P)
 {
@@ -210,6 +242,8 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
             pos += __popcll(word);
         }
     }
+
+    local_order(bits, row_ptr, P);
 
     MASK_TICK(3);
     // -- columns: lane <-> block row --
@@ -372,6 +406,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
             pos += __popcll(word);
         }
     }
+    local_order(s_bits, s_row_ptr, P);
     for (int j = wave; j < P.KB; j += kMaskWaves) {
         int pos = s_col_ptr[j];
         for (int i0 = 0; i0 < P.MB; i0 += 64) {
@@ -420,6 +455,8 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     P.row_idx = reinterpret_cast<int32_t *>(b + L.off_row_idx);
     P.row_order = reinterpret_cast<int32_t *>(b + L.off_row_order);
     P.col_order = reinterpret_cast<int32_t *>(b + L.off_col_order);
+    P.loc_row = reinterpret_cast<int32_t *>(b + L.off_loc_row);
+    P.loc_col = reinterpret_cast<int32_t *>(b + L.off_loc_col);
     P.given_bits = given_bits;
     P.M = M; P.K = K; P.BM = BM; P.BK = BK;
     P.MB = static_cast<int32_t>(L.MB); P.KB = static_cast<int32_t>(L.KB);
@@ -489,6 +526,8 @@ int sdrop_mask_layout(int64_t M, int64_t K, int BM, int BK, sdrop_mask_layout_t 
     out->off_row_idx = off;   off = sdrop::align_up(off + 4 * nblk, 256);
     out->off_row_order = off; off = sdrop::align_up(off + 4 * MB, 256);
     out->off_col_order = off; off = sdrop::align_up(off + 4 * KB, 256);
+    out->off_loc_row = off;   off = sdrop::align_up(off + 4 * nblk, 256);
+    out->off_loc_col = off;   off = sdrop::align_up(off + 4 * nblk, 256);
     out->total_bytes = off;
     out->MB = MB; out->KB = KB; out->words_per_row = wpr;
     return SDROP_OK;

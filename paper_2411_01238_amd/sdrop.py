@@ -37,7 +37,7 @@ class SdropError(RuntimeError):
 class MaskLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
                 ("total_bytes", "off_bits", "off_row_ptr", "off_col_idx", "off_blk_row",
-                 "off_col_ptr", "off_row_idx", "off_row_order", "off_col_order")] + \
+                 "off_col_ptr", "off_row_idx", "off_row_order", "off_col_order", "off_loc_row", "off_loc_col")] + \
                [(n, ctypes.c_int64) for n in ("MB", "KB", "words_per_row")]
 
 
@@ -144,6 +144,8 @@ class Mask:
             "row_idx": self._i32(L.off_row_idx, nnz),
             "row_order": self._i32(L.off_row_order, self.MB),
             "col_order": self._i32(L.off_col_order, self.KB),
+            "loc_row": self._i32(L.off_loc_row, nnz),
+            "loc_col": self._i32(L.off_loc_col, nnz),
         }
 
 

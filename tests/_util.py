@@ -58,5 +58,8 @@ def lists_from_keep(keep):
     rows, cols = np.nonzero(keep)                      # row-major order
     col_ptr = np.concatenate([[0], np.cumsum(keep.sum(axis=0))]).astype(np.int32)
     crows, ccols = np.nonzero(keep.T)                  # column-major order: (col, row)
+    # the same blocks sorted by (row // 8, column, row % 8)
+    o = np.lexsort((rows % 8, cols, rows // 8))
     return {"row_ptr": row_ptr, "col_idx": cols.astype(np.int32), "blk_row": rows.astype(np.int32),
-            "col_ptr": col_ptr, "row_idx": ccols.astype(np.int32)}
+            "col_ptr": col_ptr, "row_idx": ccols.astype(np.int32),
+            "loc_row": rows[o].astype(np.int32), "loc_col": cols[o].astype(np.int32)}

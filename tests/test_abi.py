@@ -40,7 +40,8 @@ def test_mask_layout_regions_do_not_overlap():
         assert (L.MB, L.KB, L.words_per_row) == (MB, KB, (KB + 63) // 64)
         regions = [(0, 256), (L.off_bits, 8 * MB * L.words_per_row), (L.off_row_ptr, 4 * (MB + 1)),
                    (L.off_col_idx, 4 * MB * KB), (L.off_blk_row, 4 * MB * KB), (L.off_col_ptr, 4 * (KB + 1)),
-                   (L.off_row_idx, 4 * MB * KB), (L.off_row_order, 4 * MB), (L.off_col_order, 4 * KB)]
+                   (L.off_row_idx, 4 * MB * KB), (L.off_row_order, 4 * MB), (L.off_col_order, 4 * KB),
+                   (L.off_loc_row, 4 * MB * KB), (L.off_loc_col, 4 * MB * KB)]
         end = 0
         for off, size in regions:
             assert off >= end and off % 16 == 0

@@ -20,7 +20,7 @@ def _check_mask(m, keep):
     assert np.array_equal(got_bits, orc.pack_bits(keep))
     got = {k: v.cpu().numpy() for k, v in m.lists().items()}
     want = lists_from_keep(keep)
-    for k in ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx"):
+    for k in ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx", "loc_row", "loc_col"):
         assert np.array_equal(got[k], want[k]), k
     # the schedules are permutations sorted by descending kept count (ties: any order)
     rc, cc = keep.sum(axis=1).astype(np.int64), keep.sum(axis=0).astype(np.int64)
@@ -68,7 +68,7 @@ def test_mask_is_reproducible_and_reusable():
     b = sdrop.sdrop_mask(4096, 4096, 128, 128, 0.5, 0, 0)
     torch.cuda.synchronize()
     assert torch.equal(a.bits(), b.bits())
-    for k in ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx"):
+    for k in ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx", "loc_row", "loc_col"):
         assert torch.equal(a.lists()[k], b.lists()[k])
     # a buffer that held another mask is fully rewritten
     sdrop.sdrop_mask(4096, 4096, 128, 128, 0.1, 7, 1, out=a)
