@@ -61,6 +61,17 @@ enum { SDROP_F16 = 0, SDROP_BF16 = 1, SDROP_F32 = 2 /* out_dtype only */ };
 
 enum { SDROP_OP_FWD = 0, SDROP_OP_BWD_DX = 1, SDROP_OP_BWD_DW = 2 };
 
+/*
+ * Host-side tuning knobs (process-wide; not thread-safe against concurrent GEMM calls).  They change
+ * which kernel a call uses, never its result.
+ *   SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU  sdrop_bwd_dx with tiles of several kept blocks uses its
+ *       persistent kernel when it expects at least this many tiles per CU (default 16; 0 = whenever
+ *       the shape allows it)
+ * Returns SDROP_EINVAL for an unknown knob or a negative value.
+ */
+enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0 };
+int sdrop_set_tuning(int knob, int value);
+
 /* Text for an error code (static storage). */
 const char *sdrop_strerror(int code);
 

@@ -836,6 +836,127 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
     }
 }
 
+// The computing side of a persistent kernel: one wavefront's accumulators and operand registers,
+// the MFMA schedule of one slice, and the epilogue.
+template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int WN> struct Compute {
+    static constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
+    static constexpr int A_BYTES = TM * TK * 2;
+    static constexpr int NM = MI * NI, NOPS = MI + NI;
+    // operand reads requested per MFMA (at least what fits the group)
+    static constexpr int RPM_MIN = ceil_div(NOPS, NM >= 4 ? NM - 2 : NM), RPM = 2 > RPM_MIN ? 2 : RPM_MIN;
+    static constexpr int ESZ = (int)sizeof(OutT);
+    static constexpr int STAGING = 32 * 128;         // output staging per wavefront: 32 rows of 128 bytes
+    static constexpr int NIP = 128 / (32 * ESZ);     // 32-column accumulator blocks per 128-byte row
+    static constexpr int NJ = NI / NIP;              // 128-byte column groups of the wavefront's sub-tile
+    static_assert(NI % NIP == 0, "a wavefront's columns must fill whole 128-byte rows");
+
+    typename In<T>::vec fa[2][MI], fb[2][NI];
+    f32x16 acc[MI][NI];
+    int wm, wn;
+
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+    }
+    // operands of the first quarter of the slice in stage `st`
+    __device__ __forceinline__ void first(const char *st)
+    {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) fa[0][mi] = read_frag<T, A_TR, TM>(st, wm * WTM + mi * 32, 0);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) fb[0][ni] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + ni * 32, 0);
+    }
+    // One slice: 4 quarters of NM MFMAs.  On entry the first quarter's operands are in flight to
+    // register set 0; each MFMA is followed by up to RPM operand reads for the next quarter, in the
+    // order that quarter's MFMAs (A index major) first use them: A0, B0 .. B(NI-1), A1 .. A(MI-1).
+    // After the first MFMAs of the last quarter comes the slice's barrier (every wavefront is done
+    // reading `cur`; the slice in `nx1` has landed), then the first operands of `nx1`.
+    __device__ __forceinline__ void slice(const char *cur, const char *nx1)
+    {
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<4>([&](auto gi) __attribute__((always_inline)) {
+            constexpr int g = decltype(gi)::value;
+            constexpr int NB = (g == 3 && NM >= 4) ? 2 : 0;   // MFMAs of the last quarter that precede the barrier
+            static_for<NM>([&](auto ci) __attribute__((always_inline)) {
+                constexpr int c = decltype(ci)::value;
+                constexpr int mi = c / NI, ni = c % NI, cb = g & 1, nb = (g + 1) & 1;
+                if constexpr (g == 3 && c == NB) {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
+                    __builtin_amdgcn_s_barrier();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[mi][ni] = In<T>::mfma(fb[cb][ni], fa[cb][mi], acc[mi][ni]);
+                constexpr int r0 = c < NB ? 0 : (c - NB) * RPM < NOPS ? (c - NB) * RPM : NOPS;
+                constexpr int r1 = c < NB ? 0 : (c - NB + 1) * RPM < NOPS ? (c - NB + 1) * RPM : NOPS;
+                static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
+                    constexpr int r = r0 + decltype(ri)::value;
+                    const char *st = g < 3 ? cur : nx1;
+                    constexpr int kk = g < 3 ? g + 1 : 0;
+                    if constexpr (r == 0) fa[nb][0] = read_frag<T, A_TR, TM>(st, wm * WTM, kk);
+                    else if constexpr (r <= NI) fb[nb][r - 1] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + (r - 1) * 32, kk);
+                    else fa[nb][r - NI] = read_frag<T, A_TR, TM>(st, wm * WTM + (r - NI) * 32, kk);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    }
+    // Epilogue: scale in fp32, round once, park 32 rows x 128 bytes at a time in this wavefront's
+    // own piece of LDS (`reg`) and write them out as whole 128-byte lines.  The MFMAs took the
+    // operands swapped, so accumulator register 4q+e of lane l is row l%32, column 8q + 4(l/32) + e
+    // of its 32x32 block.  8-byte slot u of row r lies at slot u ^ (r & 15): the 8-byte writes of 32
+    // rows then spread over all banks, and a 16-byte read finds its two halves in one 16-byte
+    // piece, exchanged when r is odd.  dst(mi, nj) is the address of row 0 of the 32 x 128-byte
+    // piece (mi, nj) of the wavefront's sub-tile, or null if that piece is not to be written.
+    template <class F> __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, F &&dst)
+    {
+        const int lane = threadIdx.x & 63;
+        const int wrow = lane & 31, whalf = lane >> 5;
+        const int rrow = lane >> 3, rch = lane & 7;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int nj = 0; nj < NJ; ++nj) {
+                char *const out = dst(mi, nj);
+                if (!out) continue;                        // uniform
+#pragma unroll
+                for (int nl = 0; nl < NIP; ++nl)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16 &a = acc[mi][nj * NIP + nl];
+                        const float v0 = a[4 * q] * scale, v1 = a[4 * q + 1] * scale;
+                        const float v2 = a[4 * q + 2] * scale, v3 = a[4 * q + 3] * scale;
+                        if constexpr (ESZ == 4) {
+                            // 16 bytes per lane: 16-byte slot 2q + half, exchanged as a whole with (row & 7)
+                            const int slot = (2 * q + whalf) ^ (wrow & 7);
+                            *reinterpret_cast<float4 *>(reg + wrow * 128 + slot * 16) = make_float4(v0, v1, v2, v3);
+                        } else {
+                            typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
+                            const out4 o = {static_cast<OutT>(v0), static_cast<OutT>(v1), static_cast<OutT>(v2), static_cast<OutT>(v3)};
+                            const int slot8 = (nl * 8 + 2 * q + whalf) ^ (wrow & 15);
+                            *reinterpret_cast<out4 *>(reg + wrow * 128 + slot8 * 8) = o;
+                        }
+                    }
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = it * 8 + rrow;
+                    uint4 v;
+                    if constexpr (ESZ == 4) {
+                        v = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
+                    } else {
+                        const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
+                        v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
+                    }
+                    *reinterpret_cast<uint4 *>(out + (int64_t)row * ldc + rch * 16) = v;
+                }
+            }
+    }
+};
+
 // s_waitcnt immediate that waits only for vector-memory operations (at most `vm` outstanding).
 constexpr int waitcnt_vm_only(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (15 << 8); }
 
@@ -868,8 +989,6 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
     constexpr int STAGES = 3, AHEAD = 2;
     constexpr int ESZ = (int)sizeof(OutT);
     constexpr int STAGING = 32 * 128;           // per computing wavefront: 32 rows of 128 bytes
-    constexpr int NIP = 128 / (32 * ESZ);       // 32-column accumulator blocks per 128-byte row
-    static_assert(NI % NIP == 0, "a wavefront's columns must fill whole 128-byte rows");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char *const staging = smem + STAGES * STAGE_BYTES;
@@ -1032,10 +1151,8 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
     n1 = c_level1(1);
     n2 = c_level1(2);
 
-    typename In<T>::vec fa[2][MI], fb[2][NI];
-    f32x16 acc[MI][NI];
-    constexpr int NM = MI * NI, NOPS = MI + NI;
-    constexpr int RPM_MIN = ceil_div(NOPS, NM >= 4 ? NM - 2 : NM), RPM = 2 > RPM_MIN ? 2 : RPM_MIN;
+    Compute<T, OutT, A_TR, B_TR, TM, TN, WM, WN> cw;
+    cw.wm = wm; cw.wn = wn;
     int st0 = 0, st1 = 1, st2 = 2;       // stages of the stream's slices g, g+1, g+2
     bool started = false;
     const float scale = P.scale;
@@ -1049,62 +1166,18 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
         c_level2(n1);
         CMeta n3 = c_level1(k + 3);
 
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
+        cw.zero();
         if (nsteps > 0 && !started) {
             started = true;
             __builtin_amdgcn_s_barrier();                     // slice 0 is in place
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) fa[0][mi] = read_frag<T, A_TR, TM>(stage_ptr(0), wm * WTM + mi * 32, 0);
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) fb[0][ni] = read_frag<T, B_TR, TN>(stage_ptr(0) + A_BYTES, wn * WTN + ni * 32, 0);
+            cw.first(stage_ptr(0));
         }
         for (int s = 0; s < nsteps; ++s) {
-            const char *cur_st = stage_ptr(st0);
-            const char *nx1 = stage_ptr(st1);
-            __builtin_amdgcn_sched_barrier(0);
-            static_for<4>([&](auto gi) __attribute__((always_inline)) {
-                constexpr int g = decltype(gi)::value;
-                constexpr int NB = (g == 3 && NM >= 4) ? 2 : 0;   // MFMAs of the last group that precede the barrier
-                static_for<NM>([&](auto ci) __attribute__((always_inline)) {
-                    constexpr int c = decltype(ci)::value;
-                    constexpr int mi = c / NI, ni = c % NI, cb = g & 1, nb = (g + 1) & 1;
-                    if constexpr (g == 3 && c == NB) {
-                        // every wavefront is done reading this slice; the next one has landed
-                        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
-                        __builtin_amdgcn_s_barrier();
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    acc[mi][ni] = In<T>::mfma(fb[cb][ni], fa[cb][mi], acc[mi][ni]);
-                    constexpr int r0 = c < NB ? 0 : (c - NB) * RPM < NOPS ? (c - NB) * RPM : NOPS;
-                    constexpr int r1 = c < NB ? 0 : (c - NB + 1) * RPM < NOPS ? (c - NB + 1) * RPM : NOPS;
-                    static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
-                        constexpr int r = r0 + decltype(ri)::value;
-                        const char *st = g < 3 ? cur_st : nx1;
-                        constexpr int kk = g < 3 ? g + 1 : 0;
-                        if constexpr (r == 0) fa[nb][0] = read_frag<T, A_TR, TM>(st, wm * WTM, kk);
-                        else if constexpr (r <= NI) fb[nb][r - 1] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + (r - 1) * 32, kk);
-                        else fa[nb][r - NI] = read_frag<T, A_TR, TM>(st, wm * WTM + (r - NI) * 32, kk);
-                    });
-                    __builtin_amdgcn_sched_barrier(0);
-                });
-            });
+            cw.slice(stage_ptr(st0), stage_ptr(st1));
             const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
             if (s == 0) GEMM_TICKW(k * 4 + 1);
         }
         GEMM_TICKW(k * 4 + 2);
-
-        // epilogue: scale in fp32, round once, park 32 rows x 128 bytes at a time in this
-        // wavefront's own piece of LDS and write them out as whole 128-byte lines.  The MFMAs took
-        // the operands swapped, so accumulator register 4q+e of lane l is row l%32, column
-        // 8q + 4(l/32) + e of its 32x32 block.  8-byte slot u of row r lies at slot u ^ (r & 15): the
-        // 8-byte writes of 32 rows then spread over all banks, and a 16-byte read finds its two
-        // halves in one 16-byte piece, exchanged when r is odd.
         {
             const int line = t % per_line;
             const int nt = line / P.splits, part = line % P.splits;
@@ -1112,46 +1185,281 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
             if constexpr (OP == FWD) c_tile = P.C + (int64_t)ord * P.BM * ldc + (int64_t)nt * TN * ESZ;
             else c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)ord * P.BK * ldc + (int64_t)nt * TN * ESZ;
             c_tile += (int64_t)(wm * WTM) * ldc + (int64_t)(wn * WTN) * ESZ;
-            const int wrow = lane & 31, whalf = lane >> 5;
-            const int rrow = lane >> 3, rch = lane & 7;
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int nj = 0; nj < NI / NIP; ++nj) {
-#pragma unroll
-                    for (int nl = 0; nl < NIP; ++nl)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const f32x16 &a = acc[mi][nj * NIP + nl];
-                            const float v0 = a[4 * q] * scale, v1 = a[4 * q + 1] * scale;
-                            const float v2 = a[4 * q + 2] * scale, v3 = a[4 * q + 3] * scale;
-                            if constexpr (ESZ == 4) {
-                                // 16 bytes per lane: 16-byte slot 2q + half, exchanged as a whole with (row & 7)
-                                const int slot = (2 * q + whalf) ^ (wrow & 7);
-                                *reinterpret_cast<float4 *>(reg + wrow * 128 + slot * 16) = make_float4(v0, v1, v2, v3);
-                            } else {
-                                typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
-                                const out4 o = {static_cast<OutT>(v0), static_cast<OutT>(v1), static_cast<OutT>(v2), static_cast<OutT>(v3)};
-                                const int slot8 = (nl * 8 + 2 * q + whalf) ^ (wrow & 15);
-                                *reinterpret_cast<out4 *>(reg + wrow * 128 + slot8 * 8) = o;
-                            }
-                        }
-#pragma unroll
-                    for (int it = 0; it < 4; ++it) {
-                        const int row = it * 8 + rrow;
-                        uint4 v;
-                        if constexpr (ESZ == 4) {
-                            v = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
-                        } else {
-                            const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
-                            v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
-                        }
-                        *reinterpret_cast<uint4 *>(c_tile + (int64_t)(mi * 32 + row) * ldc + (nj * 128) + rch * 16) = v;
-                    }
-                }
+            cw.store(reg, scale, ldc, [&](int mi, int nj) __attribute__((always_inline)) -> char * {
+                return c_tile + (int64_t)(mi * 32) * ldc + nj * 128;
+            });
         }
         GEMM_TICKW(k * 4 + 3);
         cur = n1; n1 = n2; n2 = n3;
+    }
+}
+
+// a[i] for a uniform index i in 0..3, as selects (keeps everything in scalar registers)
+__device__ __forceinline__ int sel4(const int (&a)[4], int i)
+{
+    return i == 0 ? a[0] : i == 1 ? a[1] : i == 2 ? a[2] : a[3];
+}
+
+// dX for 128-row tiles without a ragged reduction tail, as a persistent kernel (same stream of
+// slices, stages and barrier protocol as gemm_persistent_kernel; every tile reduces over all of N,
+// so every tile has the same number of slices).
+//
+// Work units are groups of G = TN / BK consecutive entries of a kept-block list: the locally
+// ordered one for G = 1, the row-major one for G > 1 (consecutive entries then share the block
+// row).  A group whose entries lie in one block row is one tile; where the row changes inside a
+// group it is cut into one tile per run of equal rows.  The groups are dealt out in equal
+// contiguous chunks to the XCDs (workgroup w runs on XCD w mod 8) and round-robin inside a
+// chunk, so that the tiles an XCD has in flight at one time are neighbours in the list.
+// Both roles read the same list entries and derive the same tiles from them.
+//
+// Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; the computing
+// wavefronts test a batch of them per tile (bits fetched before the tile's slices, used after
+// its stores) and finish what is left after their last tile.
+template <class T, class OutT, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
+{
+    constexpr int NW = WM * WN;
+    static_assert(NW == 4 && TM == 128, "one computing and one loading wavefront per SIMD, 128-row tiles");
+    constexpr int WTM = TM / WM, WTN = TN / WN;
+    constexpr int DXG = TN / 64;                      // 64-column chunks of a tile
+    static_assert(DXG <= 4, "tile too wide");
+    constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int STAGES = 3, AHEAD = 2;
+    constexpr int ESZ = (int)sizeof(OutT);
+    constexpr int STAGING = 32 * 128;
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *const staging = smem + STAGES * STAGE_BYTES;
+
+    const MaskHeader *H = P.mv.hdr;
+    if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = wave_all >= NW;
+    const int wave = loader ? wave_all - NW : wave_all;
+    const int wm = wave / WN, wn = wave % WN;
+    const int G = gridDim.x, w = blockIdx.x;
+    const int GB = TN / P.BK;                          // kept blocks per group: 1, 2 or 4
+    const int cshift = (P.BK == 128), cmask = (1 << cshift) - 1;   // 64-column chunks per block
+    const int nnz = H->nnz;
+    const int ngroups = (nnz + GB - 1) / GB;
+    const int nsteps = (int)(P.N / TK);
+    const int64_t lda = P.N * 2, ldb = P.N * 2, ldc = P.K * (int64_t)ESZ;
+    const int32_t *const rows = GB == 1 ? P.mv.loc_row : P.mv.blk_row;
+    const int32_t *const cols = GB == 1 ? P.mv.loc_col : P.mv.col_idx;
+    // this workgroup's groups: chunk x of the list, local indices r, r + wx, r + 2 wx, ...
+    const int nx = G < 8 ? G : 8;
+    const int x = w % nx, r = w / nx;
+    const int wx = (G - x + nx - 1) / nx;              // workgroups that share chunk x
+    const int per_chunk = (ngroups + nx - 1) / nx;
+    // group of round k, or -1 when the workgroup has no more
+    auto group_of = [&](int k) __attribute__((always_inline)) -> int {
+        const int lr = r + k * wx;
+        const int u = x * per_chunk + lr;
+        return (lr < per_chunk && u < ngroups) ? u : -1;
+    };
+    auto stage_ptr = [&](int st) __attribute__((always_inline)) -> char * { return smem + st * STAGE_BYTES; };
+    struct Group { int u, n; int r[4], c[4]; };        // list entries [u GB, u GB + n)
+
+    if (loader) {
+        DmaK<TM, 1, NW> da;
+        DmaK<TN, DXG, NW> db;
+        da.init(lda, wave);
+        db.init(ldb, wave);
+        constexpr int NDMA_A = TM / (8 * NW), NDMA_B = TN / (8 * NW), NDMA = NDMA_A + NDMA_B;
+        typedef const __attribute__((address_space(4))) int32_t *const_i32;   // see gemm_persistent_kernel
+        const const_i32 k_rows = (const_i32)(uintptr_t)rows, k_cols = (const_i32)(uintptr_t)cols;
+        auto load_group = [&](int k) __attribute__((always_inline)) -> Group {
+            Group g;
+            g.u = group_of(k);
+            const int e0 = (g.u < 0 ? 0 : g.u) * GB;
+            g.n = g.u < 0 ? 0 : (nnz - e0 < GB ? nnz - e0 : GB);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int e = e0 + (b < g.n ? b : 0);   // always a valid entry (the lists hold at least one slot)
+                g.r[b] = k_rows[e < nnz ? e : 0];
+                g.c[b] = k_cols[e < nnz ? e : 0];
+            }
+            return g;
+        };
+        Group cur, nxt;
+        cur.u = -1; cur.n = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) cur.r[b] = cur.c[b] = 0;
+        nxt = load_group(0);
+        int k = -1, a = 0;                              // round of `cur`; next unused entry of `cur`
+        int s = nsteps;                                 // next slice of the tile being issued
+        const char *a_tile = nullptr;
+        const char *bgrp[DXG];
+#pragma unroll
+        for (int g = 0; g < DXG; ++g) bgrp[g] = nullptr;
+        bool ended = false;
+
+        auto issue_next = [&](int st) __attribute__((always_inline)) -> bool {
+            if (s == nsteps) {
+                if (ended) return false;
+                if (a >= cur.n) {
+                    ++k;
+                    cur = nxt;
+                    if (cur.u < 0) { ended = true; return false; }
+                    nxt = load_group(k + 1);
+                    a = 0;
+                }
+                const int row = sel4(cur.r, a);
+                int nb = 1;
+                while (a + nb < cur.n && sel4(cur.r, a + nb) == row) ++nb;
+                a_tile = P.A + (int64_t)row * P.BM * lda;
+#pragma unroll
+                for (int g = 0; g < DXG; ++g) {
+                    const int bb = g >> cshift;         // a missing block repeats the last one
+                    const int col = sel4(cur.c, a + (bb < nb ? bb : nb - 1));
+                    bgrp[g] = P.B + ((int64_t)col * P.BK + (g & cmask) * 64) * ldb;
+                }
+                a += nb;
+                s = 0;
+            }
+            const int64_t off = (int64_t)s * TK * 2;
+            const char *const sa[1] = {a_tile + off};
+            const char *sb[DXG];
+#pragma unroll
+            for (int g = 0; g < DXG; ++g) sb[g] = bgrp[g] + off;
+            char *stp = stage_ptr(st);
+#pragma unroll
+            for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+#pragma unroll
+            for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+            ++s;
+            return true;
+        };
+
+        int issued = 0, st_issue = 0;
+        for (int i = 0; i < AHEAD; ++i)
+            if (issue_next(st_issue)) { ++issued; st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1; }
+        if (issued == 0) return;
+        if (issued == AHEAD) __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+        __builtin_amdgcn_s_barrier();
+        for (int g = 0; g < issued; ++g) {
+            const bool more = issue_next(st_issue);
+            if (more) {
+                ++issued;
+                st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1;
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+            } else {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+            }
+            __builtin_amdgcn_s_barrier();
+        }
+        return;
+    }
+
+    // ---------------- computing wavefronts ----------------
+    auto c_load_group = [&](int k) __attribute__((always_inline)) -> Group {
+        Group g;
+        g.u = group_of(k);
+        const int e0 = (g.u < 0 ? 0 : g.u) * GB;
+        g.n = g.u < 0 ? 0 : (nnz - e0 < GB ? nnz - e0 : GB);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int e = e0 + (b < g.n ? b : 0);
+            g.r[b] = rows[e < nnz ? e : 0];
+            g.c[b] = cols[e < nnz ? e : 0];
+        }
+        return g;
+    };
+    // zero fill: this workgroup's positions are w + G z, z in [0, nz)
+    const int total_pos = P.MB * P.KB;
+    const int nz = w < total_pos ? (total_pos - w + G - 1) / G : 0;
+    int my_groups = 0;
+    {
+        const int first = x * per_chunk;
+        const int avail = ngroups - first < per_chunk ? ngroups - first : per_chunk;   // groups in chunk x
+        my_groups = avail > r ? (avail - r + wx - 1) / wx : 0;
+    }
+    int quota = my_groups > 0 ? (nz + my_groups - 1) / my_groups : 0;
+    if (quota > 64) quota = 64;
+    int z_done = 0;
+    const int row_chunks = P.BK * ESZ / 16;
+    // lane l: is position z0 + l (l < cnt) of this workgroup dropped?  (word fetched here, tested later)
+    auto fetch_bits = [&](int z0, int cnt, int &bitpos) __attribute__((always_inline)) -> uint64_t {
+        const int z = z0 + (lane < cnt ? lane : 0);
+        const int pz = w + G * z;
+        const int pc = pz < total_pos ? pz : 0;
+        const int zi = pc / P.KB, zj = pc % P.KB;
+        bitpos = zj & 63;
+        return P.mv.bits[(int64_t)zi * H->words_per_row + (zj >> 6)];
+    };
+    auto fill_batch = [&](int z0, int cnt, uint64_t word, int bitpos) __attribute__((always_inline)) {
+        const bool dropped = lane < cnt && (w + G * (z0 + lane)) < total_pos && !((word >> bitpos) & 1);
+        uint64_t todo = __ballot(dropped);
+        while (todo) {
+            const int l = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int pz = w + G * (z0 + l);
+            const int zi = pz / P.KB, zj = pz % P.KB;
+            char *z = P.C + (int64_t)zi * P.BM * ldc + (int64_t)zj * P.BK * ESZ;
+            for (int c = threadIdx.x; c < TM * row_chunks; c += NW * 64)
+                *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    Compute<T, OutT, false, false, TM, TN, WM, WN> cw;
+    cw.wm = wm; cw.wn = wn;
+    int st0 = 0, st1 = 1, st2 = 2;
+    bool started = false;
+    const float scale = P.scale;
+    char *const reg = staging + wave * STAGING;
+
+    Group nxt = c_load_group(0);
+    for (int k = 0; nxt.u >= 0; ++k) {
+        int gr[4], gc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) { gr[b] = uni(nxt.r[b]); gc[b] = uni(nxt.c[b]); }
+        const int gn = nxt.n;
+        nxt = c_load_group(k + 1);                      // requested a whole group ahead of its use
+        int a = 0;
+        while (a < gn) {
+            const int row = sel4(gr, a);
+            int nb = 1;
+            while (a + nb < gn && sel4(gr, a + nb) == row) ++nb;
+            const int chunks_valid = nb << cshift;
+            // bits of the next batch of this workgroup's positions
+            const int zc = nz - z_done < quota ? nz - z_done : quota;
+            int bitpos = 0;
+            uint64_t zword = 0;
+            if (zc > 0) zword = fetch_bits(z_done, zc, bitpos);
+
+            cw.zero();
+            if (!started) {
+                started = true;
+                __builtin_amdgcn_s_barrier();           // slice 0 is in place
+                cw.first(stage_ptr(0));
+            }
+            for (int s = 0; s < nsteps; ++s) {
+                cw.slice(stage_ptr(st0), stage_ptr(st1));
+                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+            }
+            char *const c_rows = P.C + ((int64_t)row * P.BM + wm * WTM) * ldc;
+            cw.store(reg, scale, ldc, [&](int mi, int nj) __attribute__((always_inline)) -> char * {
+                const int col_t = wn * WTN + nj * (128 / ESZ);         // first column of the piece, in the tile
+                const int g = col_t >> 6;
+                if (g >= chunks_valid) return nullptr;
+                const int col = sel4(gc, a + (g >> cshift));
+                const int64_t col0 = (int64_t)col * P.BK + (g & cmask) * 64 + (col_t & 63);
+                return c_rows + (int64_t)(mi * 32) * ldc + col0 * ESZ;
+            });
+            if (zc > 0) { fill_batch(z_done, zc, zword, bitpos); z_done += zc; }
+            a += nb;
+        }
+    }
+    // what is left of the zero fill (all of it for a workgroup without tiles)
+    while (z_done < nz) {
+        const int zc = nz - z_done < 64 ? nz - z_done : 64;
+        int bitpos = 0;
+        const uint64_t zword = fetch_bits(z_done, zc, bitpos);
+        fill_batch(z_done, zc, zword, bitpos);
+        z_done += zc;
     }
 }
 
@@ -1207,6 +1515,28 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
+template <class T, class OutT, int TN>
+int launch_dx_persistent(const GemmParams &P, hipStream_t stream)
+{
+    constexpr int P_LDS = 3 * (128 + TN) * TK * 2 + 4 * 4096;
+    auto k = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+#ifdef SDROP_GEMM_TIMING
+    if (getenv("SDROP_NO_PERSIST")) return -1;
+#endif
+    if (!ok) return -1;
+    const int64_t positions = (int64_t)P.MB * P.KB;
+    const int ncu = cu_count();
+    hipLaunchKernelGGL(k, dim3((unsigned)(positions < ncu ? positions : ncu)), dim3(512), P_LDS, stream, P);
+    return hip_status(hipGetLastError());
+}
+
 // out[e] = scale * sum_c part[c][e], rounded once (the second pass of a split DW)
 template <class OutT>
 __global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, OutT *out, int64_t n, int splits, float scale)
@@ -1253,6 +1583,9 @@ int cu_count()
     return n;
 }
 
+// groups of kept blocks per CU from which dX tiles of several blocks use the persistent kernel
+int g_dx_persistent_groups_per_cu = 16;
+
 // Tile shapes: the tile edge that lies along the mask must equal the mask's block
 // (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
 // 256/BK kept blocks of one block row into a 256-wide tile.
@@ -1290,6 +1623,14 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         // one kept block per tile: a workgroup per block position, rounded up to whole sets of 8 XCDs
         const int grid = G_ == 1 ? (P.MB * P.KB + 7) / 8 * 8 : P.MB * P.n_tiles;
         const bool ragged = P.N % TK != 0;
+        // The persistent kernel deals out groups of G_ list entries and cuts a group where the block
+        // row changes inside it; with few groups per workgroup one such extra tile is a whole round
+        // (4096^3, a tenth dropped: 147 us against 111 us), so it is used for single-block tiles
+        // (no cuts) and where a workgroup gets many groups (65536 x 4096 x 1024: 485 against 515 us).
+        if (P.BM == 128 && !ragged && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu)) {
+            const int rc = TNsel == 256 ? launch_dx_persistent<T, OutT, 256>(P, stream) : launch_dx_persistent<T, OutT, 128>(P, stream);
+            if (rc != -1) return rc;      // -1: the device does not grant the LDS; use the per-tile kernels
+        }
         if (TNsel == 256) {
             if (P.BM == 128) return launch<DX, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
             return launch<DX, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
@@ -1385,6 +1726,15 @@ extern "C" int sdrop_debug_ticks(long long *host, int n)
 #endif
 
 extern "C" {
+
+int sdrop_set_tuning(int knob, int value)
+{
+    if (knob == SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU && value >= 0) {
+        sdrop::g_dx_persistent_groups_per_cu = value;
+        return SDROP_OK;
+    }
+    return SDROP_EINVAL;
+}
 
 size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, int BK,
                              int dtype, int out_dtype)

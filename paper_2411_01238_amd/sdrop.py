@@ -21,7 +21,7 @@ F16, BF16, F32 = 0, 1, 2
 OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
 MASK_NNZ_OFFSET = 36
 
-EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_mask_layout", "sdrop_mask_bytes",
+EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
            "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw")
 
@@ -58,6 +58,8 @@ def lib():
         L.sdrop_strerror.restype = ctypes.c_char_p
         L.sdrop_last_hip_error.argtypes = []
         L.sdrop_last_hip_error.restype = ci
+        L.sdrop_set_tuning.argtypes = [ci, ci]
+        L.sdrop_set_tuning.restype = ci
         L.sdrop_mask_layout.argtypes = [i64, i64, ci, ci, ctypes.POINTER(MaskLayout)]
         L.sdrop_mask_layout.restype = ci
         L.sdrop_mask_bytes.argtypes = [i64, i64, ci, ci]
@@ -74,6 +76,13 @@ def lib():
             f.restype = ci
         _lib = L
     return _lib
+
+
+TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0
+
+
+def set_tuning(knob, value):
+    _check(lib().sdrop_set_tuning(int(knob), int(value)), "sdrop_set_tuning")
 
 
 def strerror(code):

@@ -32,6 +32,13 @@ def test_strerror_and_codes():
     assert "unknown" in sdrop.strerror(99)
 
 
+def test_tuning_knobs_reject_bad_arguments():
+    L = sdrop.lib()
+    assert L.sdrop_set_tuning(99, 1) == sdrop.EINVAL
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, -1) == sdrop.EINVAL
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16) == sdrop.OK
+
+
 def test_mask_layout_regions_do_not_overlap():
     for (M, K, BM, BK) in ((256, 256, 64, 64), (4096, 4096, 128, 128), (65536, 4096, 128, 128),
                            (16384, 3072, 128, 64), (64, 64 * 130, 64, 64)):

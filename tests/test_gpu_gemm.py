@@ -88,6 +88,13 @@ def test_tiny_workload():
     (64 * 300, 128, 256, 64, 64, "bf16", 0.1, 11),  # 300 block rows: dW walks long column lists (and splits them)
     (128 * 150, 128, 264, 128, 128, "bf16", 0.0, 12),  # the same, all kept, 128-blocks, ragged N
     (256, 128 * 140, 256, 128, 128, "bf16", 0.05, 13),  # fwd: 140 block columns with two slices each
+    # dX as a persistent kernel (128-row blocks, N a multiple of 64)
+    (1024, 1024, 256, 128, 64, "bf16", 0.3, 14),  # groups of two 64-column blocks, cut where the block row changes
+    (2048, 512, 128, 128, 128, "f16", 0.9, 15),   # mostly zero fill: more workgroups than kept blocks
+    (128, 128, 64, 128, 128, "bf16", 0.0, 16),    # a single block, a single slice
+    (4096, 4096, 64, 128, 128, "bf16", 0.1, 17),  # 256-wide tiles of two kept blocks, one slice per tile
+    (4096, 2048, 64, 128, 64, "f16", 0.1, 18),    # 256-wide tiles of four kept 64-column blocks
+    (512, 4096, 192, 128, 128, "f16", 0.5, 19),   # three slices per tile, 4 x 32 blocks
 ])
 def test_mid_sizes_every_element(M, K, N, BM, BK, dtype, p, seed):
     print("gemm mid", M, K, N, BM, BK, dtype, p, seed, flush=True)
@@ -105,13 +112,42 @@ def test_p0_is_plain_gemm_and_p1_is_zero():
         assert torch.count_nonzero(o).item() == 0 and not torch.signbit(o).any().item()
 
 
-def test_explicit_masks_all_dropped_rows_and_columns():
-    X, W, dY = make_custom(384, 384, 136, "f16", seed=12)
-    print("gemm explicit masks", flush=True)
-    BM = BK = 64
+@pytest.mark.parametrize("M,K,N,BM,BK,dtype,p,seed", [
+    (1024, 1024, 256, 128, 64, "bf16", 0.3, 14),  # groups of two 64-column blocks, cut where the block row changes
+    (4096, 4096, 64, 128, 128, "bf16", 0.1, 17),  # groups of two 128-column blocks
+    (4096, 2048, 64, 128, 64, "f16", 0.1, 18),    # groups of four 64-column blocks
+    (384, 2048, 128, 128, 64, "bf16", 0.6, 20),   # groups of two, rows with few kept blocks: many cuts, zero fill
+])
+def test_dx_persistent_kernel_with_several_blocks_per_tile(M, K, N, BM, BK, dtype, p, seed):
+    # by default this kernel is chosen only for launches with many tiles per CU; here it is forced
+    print("gemm dx persistent groups", M, K, N, BM, BK, dtype, p, seed, flush=True)
+    X, W, dY = make_custom(M, K, N, dtype, seed=seed)
+    sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 0)
+    try:
+        _full_parity(X, W, dY, BM, BK, p, seed, 0, "dx-persistent(%d,%d,%d,%dx%d,%s)" % (M, K, N, BM, BK, dtype))
+    finally:
+        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16)
+
+
+def test_p1_and_p0_without_ragged_edges():
+    # the persistent kernels: everything dropped (zero fill only, no tile at all) and everything kept
+    X, W, dY = make_custom(512, 512, 128, "bf16", seed=21)
+    print("gemm p0/p1 persistent", flush=True)
+    keep = _full_parity(X, W, dY, 128, 128, 0.0, 0, 0, "p=0 persistent")
+    assert keep.all()
+    m = sdrop.sdrop_mask(512, 512, 128, 128, 1.0, 0, 0)
+    for o in _run_all(X, W, dY, m, torch.float32) + _run_all(X, W, dY, m, None):
+        assert torch.count_nonzero(o).item() == 0 and not torch.signbit(o).any().item()
+
+
+@pytest.mark.parametrize("B,N", [(64, 136), (128, 128)])    # per-tile kernels with a ragged edge; persistent kernels
+def test_explicit_masks_all_dropped_rows_and_columns(B, N):
+    X, W, dY = make_custom(6 * B, 6 * B, N, "f16", seed=12)
+    print("gemm explicit masks", B, N, flush=True)
+    BM = BK = B
     keep = np.ones((6, 6), dtype=np.uint8)
-    keep[2, :] = 0          # an empty block row: Y rows 128..191 are zero
-    keep[:, 4] = 0          # an empty block column: dW rows 256..319 are zero
+    keep[2, :] = 0          # an empty block row: those rows of Y are zero
+    keep[:, 4] = 0          # an empty block column: those rows of dW are zero
     keep[0, 1] = 0
     _full_parity(X, W, dY, BM, BK, 0.25, 0, 0, "explicit", keep=keep)
     _full_parity(X, W, dY, BM, BK, 0.5, 0, 0, "all-dropped", keep=np.zeros((6, 6), dtype=np.uint8))
