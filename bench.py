@@ -146,6 +146,41 @@ def main():
                 "ideal_speedup": round(w.MB * w.KB / max(n_p, 1), 4),
             }
 
+    # ---- how linear is t(p) in the kept fraction f?  least squares t = a + b f over the sweep ----
+    linearity = None
+    if len(sweep) >= 3:
+        fs = [v["kept_fraction"] for v in sweep.values()]
+        ts = [v["ms_per_step"] for v in sweep.values()]
+        n = len(fs)
+        mf, mt = sum(fs) / n, sum(ts) / n
+        b = sum((f - mf) * (t - mt) for f, t in zip(fs, ts)) / sum((f - mf) ** 2 for f in fs)
+        a = mt - b * mf
+        ss_res = sum((t - (a + b * f)) ** 2 for f, t in zip(fs, ts))
+        ss_tot = sum((t - mt) ** 2 for t in ts)
+        linearity = {"fit": "ms_per_step = a + b * kept_fraction", "a_ms": round(a, 5), "b_ms": round(b, 5),
+                     "a_over_t_dense": round(a / sweep["0.0"]["ms_per_step"], 4) if "0.0" in sweep else None,
+                     "r2": round(1.0 - ss_res / ss_tot, 5)}
+
+    # ---- context only: the vendor's dense GEMMs (torch.matmul) on the same shapes and layouts ----
+    vendor = None
+    if not args.no_sweep:
+        s0 = sets[0]
+        def _t(fn, iters=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / iters
+        vendor = {"fwd_X@W": round(_t(lambda: torch.matmul(s0["X"], s0["W"], out=s0["Y"])), 5),
+                  "dx_dY@W.T": round(_t(lambda: torch.matmul(s0["dY"], s0["W"].t(), out=s0["dX"])), 5),
+                  "dw_X.T@dY": round(_t(lambda: torch.matmul(s0["X"].t(), s0["dY"], out=s0["dW"])), 5)}
+        vendor["sum_ms"] = round(sum(vendor.values()), 5)
+
     # ---- roofline of the dominant kernel (largest average duration among the three GEMMs) ----
     dom = max(("fwd", "dx", "dw"), key=lambda n: kern[n])
     flops_launch = 2.0 * nnz * w.BM * w.BK * w.N       # algorithmic flops of one GEMM launch
@@ -167,6 +202,8 @@ def main():
         "frac_of_bf16_peak": round(value / PEAK_BF16_DENSE_TFLOPS, 5),
         "ms_per_step_warm_single_set": round(ms_warm, 5),
         "sweep": sweep,
+        "linearity": linearity,
+        "vendor_dense_gemm_ms_single_set": vendor,
         "roofline": roofline,
     }
 

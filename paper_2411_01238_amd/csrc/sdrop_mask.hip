@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void mask_draw_kernel(MaskParams P)
 
 // Limits of the variant that keeps the bits and both pointer arrays in LDS between phases.
 #ifdef SDROP_MASK_TIMING
-#define MASK_TICK(n) do { if (threadIdx.x == 0) ticks[n] = clock64(); } while (0)
+#define MASK_TICK(n) do { if (threadIdx.x == 0) ticks[n] = wall_clock64(); } while (0)
 #else
 #define MASK_TICK(n) do { } while (0)
 #endif
@@ -327,14 +327,23 @@ template <bool DRAW>
 __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
 {
     __shared__ uint64_t s_bits[kLdsWords];
-    __shared__ int32_t s_rcnt[kSmallN], s_ccnt[kSmallN];
+    __shared__ __attribute__((aligned(16))) int32_t s_rcnt[kSmallN], s_ccnt[kSmallN];
+    __shared__ __attribute__((aligned(16))) int32_t s_rkey[kSmallN], s_ckey[kSmallN];   // sort keys, see phase 2
     __shared__ int32_t s_row_ptr[kSmallN + 1], s_col_ptr[kSmallN + 1];
     __shared__ int32_t s_max[2];
     const int lane = lane_id(), wave = wave_id();
     const int nwords = P.MB * P.wpr;
+#ifdef SDROP_MASK_TIMING
+    long long ticks[12] = {0};
+#endif
+    MASK_TICK(0);
 
     // -- phase 0: the packed words into LDS (drawn here, drawn by mask_draw_kernel, or given) --
-    for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) s_ccnt[j] = 0;
+    for (int j = threadIdx.x; j < kSmallN; j += kMaskThreads) {
+        if (j < P.KB) s_ccnt[j] = 0;
+        else s_ckey[j] = -1;                 // keys past the end never outrank anything (the rank loops read quads)
+        if (j >= P.MB) s_rkey[j] = -1;
+    }
     if (threadIdx.x < 2) s_max[threadIdx.x] = 0;
     if constexpr (DRAW) {
         for (int g = wave; g < nwords; g += kMaskWaves) {
@@ -359,37 +368,59 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         }
     }
     __syncthreads();
+    MASK_TICK(1);
 
     // -- phase 1: kept counts per block row and per block column --
     for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
         int cnt = 0;
         for (int w = 0; w < P.wpr; ++w) cnt += __popcll(s_bits[i * P.wpr + w]);
         s_rcnt[i] = cnt;
-        atomicMax(&s_max[0], cnt);
+        s_rkey[i] = cnt * kSmallN + (kSmallN - 1 - i);
     }
-    for (int e = threadIdx.x; e < P.MB * P.KB; e += kMaskThreads) {
-        const int i = e / P.KB, j = e % P.KB;
-        if ((s_bits[i * P.wpr + (j >> 6)] >> (j & 63)) & 1) atomicAdd(&s_ccnt[j], 1);
+    // columns: lane <-> block column of a word; every wavefront sums its share of the rows, then one
+    // atomic per lane and wavefront
+    for (int w = 0; w < P.wpr; ++w) {
+        int c = 0;
+        for (int i = wave; i < P.MB; i += kMaskWaves) c += (int)((s_bits[i * P.wpr + w] >> lane) & 1);
+        if (w * 64 + lane < P.KB && c) atomicAdd(&s_ccnt[w * 64 + lane], c);
     }
     __syncthreads();
+    MASK_TICK(2);
 
-    // -- phase 2: pointers (one wavefront each) and schedules (everybody) --
-    if (wave == 0) wave_scan(s_rcnt, s_row_ptr, P.MB);
-    if (wave == 1) wave_scan(s_ccnt, s_col_ptr, P.KB);
-    for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
-        const int c = s_rcnt[i];
+    // -- phase 2: pointers (one wavefront each) and schedules.  rank = number of entries with a larger
+    //    count, ties by index: with the key count * 1024 + (1023 - index) that is the number of larger
+    //    keys, one compare and one add per entry.  Rows are ranked by the lower half of the workgroup
+    //    and columns by the upper half at the same time; the keys are read four at a time --
+    for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) s_ckey[j] = s_ccnt[j] * kSmallN + (kSmallN - 1 - j);
+    __syncthreads();
+    if (wave == kMaskWaves - 1) wave_scan(s_rcnt, s_row_ptr, P.MB);
+    if (wave == kMaskWaves - 2) wave_scan(s_ccnt, s_col_ptr, P.KB);
+    auto rank_of = [](const int32_t *key, int n, int mine) {
         int rank = 0;
-        for (int o = 0; o < P.MB; ++o) { const int co = s_rcnt[o]; rank += (co > c) || (co == c && o < i); }
-        P.row_order[rank] = i;
-    }
-    for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) {
-        const int c = s_ccnt[j];
-        atomicMax(&s_max[1], c);
-        int rank = 0;
-        for (int o = 0; o < P.KB; ++o) { const int co = s_ccnt[o]; rank += (co > c) || (co == c && o < j); }
-        P.col_order[rank] = j;
+        const int4 *q = reinterpret_cast<const int4 *>(key);
+#pragma unroll 4
+        for (int o = 0; o < (n + 3) / 4; ++o) {
+            const int4 v = q[o];
+            rank += (v.x > mine) + (v.y > mine) + (v.z > mine) + (v.w > mine);
+        }
+        return rank;
+    };
+    constexpr int kHalf = kMaskThreads / 2;
+    if (threadIdx.x < kHalf) {
+        for (int i = threadIdx.x; i < P.MB; i += kHalf) {
+            const int rank = rank_of(s_rkey, P.MB, s_rkey[i]);
+            P.row_order[rank] = i;
+            if (rank == 0) s_max[0] = s_rcnt[i];
+        }
+    } else {
+        for (int j = threadIdx.x - kHalf; j < P.KB; j += kHalf) {
+            const int rank = rank_of(s_ckey, P.KB, s_ckey[j]);
+            P.col_order[rank] = j;
+            if (rank == 0) s_max[1] = s_ccnt[j];
+        }
     }
     __syncthreads();
+    MASK_TICK(3);
 
     // -- phase 3: the lists --
     for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
@@ -406,7 +437,9 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
             pos += __popcll(word);
         }
     }
+    MASK_TICK(4);
     local_order(s_bits, s_row_ptr, P);
+    MASK_TICK(5);
     for (int j = wave; j < P.KB; j += kMaskWaves) {
         int pos = s_col_ptr[j];
         for (int i0 = 0; i0 < P.MB; i0 += 64) {
@@ -425,6 +458,10 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         h.magic = kMaskMagic;
         h.max_row_cnt = s_max[0];
         h.max_col_cnt = s_max[1];
+#ifdef SDROP_MASK_TIMING
+        ticks[6] = wall_clock64();
+        for (int n = 0; n < 9; ++n) h.pad_[2 + n] = (int32_t)(ticks[n] - ticks[0]);
+#endif
         *P.hdr = h;
     }
 }
