@@ -1467,7 +1467,7 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
 int cu_count();
 
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
-int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
+int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok = true)
 {
     constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
     constexpr bool SPEC = TM >= 128;     // loader wavefronts for the one-workgroup-per-CU tiles
@@ -1484,8 +1484,8 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream)
         attr_set = true;
     }
     if (grid <= 0) return SDROP_OK;
-    if constexpr (SPEC && OP != DX) {
-        if (!ragged) {
+    if constexpr (OP != DX) {
+        if (!ragged && persistent_ok) {
             // persistent form: three operand stages plus 4 KiB of output staging per computing wavefront
             constexpr int P_LDS = 3 * (TM + TN) * TK * 2 + WM * WN * 4096;
             auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN>;
@@ -1603,7 +1603,12 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         const int grid = P.KB * P.n_tiles * P.splits;
         const bool ragged = P.N % 256 != 0;
         if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
-        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
+        // 64-row tiles: the persistent kernel runs one workgroup per CU, whose epilogue nothing
+        // overlaps; with short kept lists (a few slices per tile) three co-resident workgroups of the
+        // per-tile kernel do better (8192 x 1024 x 1024, 64 x 64 blocks, half kept, 16 parts:
+        // 26.5 against 29.5 us; 16384 x 3072 x 768, a tenth dropped, 4 parts: 121 against 101 us)
+        const double slices = (1.0 - P.p) * P.MB / P.splits * (P.BM / 64);
+        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream, slices >= 16.0);
     } else {
         // Every kept block costs the same, so the launch runs in ceil(tiles / CUs) rounds of
         // equal tiles.  A 256-wide tile moves a quarter less data per flop than two 128-wide
