@@ -108,6 +108,17 @@ def mask(MB, KB, p, seed, stream):
     return mask_rows(0, MB, KB, p, seed, stream)
 
 
+def mask_split(MB, KB, split_m, split_k, p, seed, stream):
+    """Block splitting (Section 3.3): the logical mask has (MB/split_m) x (KB/split_k) blocks; the
+    retiled mask keep[MB, KB] repeats each logical entry split_m times along M and split_k times
+    along K.  (The section's text and its figure caption disagree on which of the two factors goes
+    with which axis; this follows the text's formula, new block = (Mblk/p, Kblk/q).)"""
+    if split_m < 1 or split_k < 1 or MB % split_m or KB % split_k:
+        raise ValueError("mask_split: the split factors must divide the block grid")
+    logical = mask(MB // split_m, KB // split_k, p, seed, stream)
+    return np.repeat(np.repeat(logical, split_m, axis=0), split_k, axis=1)
+
+
 def pack_bits(keep):
     keep = np.ascontiguousarray(keep, dtype=np.uint8)
     MB, KB = keep.shape

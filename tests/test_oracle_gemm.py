@@ -185,3 +185,22 @@ def test_bad_shapes_are_rejected():
         orc.fwd(X, W, keep, BM + 1, BK, p)
     with pytest.raises(ValueError):
         orc.fwd(X, W, keep, BM, BK, 1.5)
+
+
+def test_retiled_mask_gives_the_products_of_the_logical_mask():
+    # Section 3.3: block splitting changes the tiling, not the result.  Logical blocks of 4 x 6
+    # elements; forward with K-blocks halved, dW with M-blocks halved (the section's two uses), and both.
+    MBL, KBL, LBM, LBK, N, p, seed = 3, 2, 4, 6, 5, 0.5, 6
+    M, K = MBL * LBM, KBL * LBK
+    X, W, dY = _rand((M, K), 1), _rand((K, N), 2), _rand((M, N), 3)
+    logical = orc.mask(MBL, KBL, p, seed, 0)
+    assert 0 < logical.sum() < logical.size
+    ref = (orc.fwd(X, W, logical, LBM, LBK, p), orc.bwd_dx(dY, W, logical, LBM, LBK, p),
+           orc.bwd_dw(X, dY, logical, LBM, LBK, p))
+    for sm, sk in ((1, 2), (2, 1), (2, 3)):
+        keep = orc.mask_split(MBL * sm, KBL * sk, sm, sk, p, seed, 0)
+        BM, BK = LBM // sm, LBK // sk
+        got = (orc.fwd(X, W, keep, BM, BK, p), orc.bwd_dx(dY, W, keep, BM, BK, p), orc.bwd_dw(X, dY, keep, BM, BK, p))
+        for g, r in zip(got, ref):
+            # the same elements are kept; only the grouping of the sums may differ
+            assert np.allclose(g, r, rtol=1e-13, atol=1e-13), (sm, sk)

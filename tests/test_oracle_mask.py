@@ -157,3 +157,39 @@ def test_tiny_workload_fixture():
     assert [int(v) for v in keep.reshape(-1)] == [int(x) for x in vals["keep"]]
     assert [int(v) for v in orc.pack_bits(keep).reshape(-1)] == [int(x, 16) for x in vals["packed"]]
     assert int(keep.sum()) == 10
+
+
+def _elementwise(keep, BM, BK):
+    return np.repeat(np.repeat(keep, BM, axis=0), BK, axis=1)
+
+
+def test_block_splitting_keeps_the_semantics_of_the_logical_mask():
+    # Section 3.3, Figure 3: a logical mask with 2x2-element blocks, the same mask retiled to 2x1- or
+    # 1x2-element blocks ("operates on" half blocks), and to 1x1, mask exactly the same elements
+    seed, stream, p = 9, 4, 0.5
+    logical = orc.mask(3, 5, p, seed, stream)
+    assert 0 < logical.sum() < 15
+    want = _elementwise(logical, 2, 2)
+    for sm, sk in ((1, 1), (2, 1), (1, 2), (2, 2)):
+        split = orc.mask_split(3 * sm, 5 * sk, sm, sk, p, seed, stream)
+        assert split.shape == (3 * sm, 5 * sk)
+        assert np.array_equal(_elementwise(split, 2 // sm, 2 // sk), want), (sm, sk)
+    assert np.array_equal(orc.mask_split(3, 5, 1, 1, p, seed, stream), logical)
+
+
+def test_block_splitting_entry_by_entry_and_axes():
+    # entry (i, j) of the retiled mask is the keep decision of logical block (i // split_m, j // split_k),
+    # numbered row-major over the LOGICAL grid; a non-square case tells the two axes apart
+    seed, stream, p, sm, sk = 3, 1, 0.4, 3, 2
+    MBL, KBL = 4, 7
+    split = orc.mask_split(MBL * sm, KBL * sk, sm, sk, p, seed, stream)
+    thr = orc.threshold(p)
+    for i in range(MBL * sm):
+        for j in range(KBL * sk):
+            b = (i // sm) * KBL + (j // sk)
+            assert split[i, j] == (1 if orc.block_word(seed, stream, b) >= thr else 0)
+    # rows repeat in runs of split_m, columns in runs of split_k
+    assert all(np.array_equal(split[i], split[i - i % sm]) for i in range(MBL * sm))
+    assert all(np.array_equal(split[:, j], split[:, j - j % sk]) for j in range(KBL * sk))
+    with pytest.raises(ValueError):
+        orc.mask_split(7, 8, 2, 2, p, seed, stream)
