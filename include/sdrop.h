@@ -139,6 +139,22 @@ int sdrop_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int 
                double p, uint64_t seed, uint64_t rng_stream, void *stream);
 
 /*
+ * Block splitting (Section 3.3): the mask object of a LOGICAL mask whose blocks are
+ * (split_m * BM) x (split_k * BK), retiled to BM x BK blocks: one Bernoulli(1-p) draw per logical
+ * block, numbered b = I * (KB / split_k) + J over the logical grid, repeated split_m times along M
+ * and split_k times along K.  Objects made with different (BM, BK, split_m, split_k) but the same
+ * products split_m * BM and split_k * BK, p, seed and rng_stream mask exactly the same elements, so
+ * the forward pass and the two backward passes of one layer may each use the block size that
+ * suits their GEMM.  split_m = split_k = 1 is sdrop_mask.  (The section's text and its figure
+ * caption disagree on which factor goes with which axis; this follows the text's formula.)
+ * SDROP_ESHAPE if split_m does not divide M/BM or split_k does not divide K/BK, SDROP_EINVAL if
+ * a factor is < 1.
+ */
+int sdrop_mask_split(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
+                     int split_m, int split_k, double p, uint64_t seed, uint64_t rng_stream,
+                     void *stream);
+
+/*
  * Same object, but the keep bits are given instead of drawn: `bits` is a device
  * array uint64[MB][words_per_row] in the packing described above (unused high
  * bits are ignored).  For callers that bring their own block mask, and for

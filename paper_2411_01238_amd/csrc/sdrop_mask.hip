@@ -38,6 +38,7 @@ struct MaskParams {
     const uint64_t *given_bits;      // non-null: take the bits from here instead of drawing
     int64_t M, K;
     int32_t BM, BK, MB, KB, wpr;
+    int32_t split_m, split_k, KBL;   // block splitting: logical block = split_m x split_k blocks; logical columns
     uint32_t key0, key1, ctr2, ctr3; // seed and rng_stream split in 32-bit words
     uint64_t threshold;              // floor(p * 2^32)
 };
@@ -58,6 +59,14 @@ __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint3
         k0 += BUMP0; k1 += BUMP1;   // the bump after the last round is unused
     }
     return c0;
+}
+
+// Number of the logical block that decides block (i, j): with block splitting (Section 3.3) the
+// logical grid is (MB / split_m) x KBL and every logical entry is repeated split_m times along M
+// and split_k times along K; without it this is i * KB + j.
+__device__ __forceinline__ uint64_t logical_block(const MaskParams &P, int64_t i, int j)
+{
+    return (uint64_t)(i / P.split_m) * (uint64_t)P.KBL + (uint64_t)(j / P.split_k);
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
@@ -167,7 +176,7 @@ __global__ __launch_bounds__(256) void mask_draw_kernel(MaskParams P)
     const int j = w * 64 + lane;
     bool keep = false;
     if (j < P.KB) {
-        const uint64_t b = (uint64_t)i * (uint64_t)P.KB + (uint64_t)j;
+        const uint64_t b = logical_block(P, i, j);
         const uint32_t r = philox_word0((uint32_t)b, (uint32_t)(b >> 32), P.ctr2, P.ctr3, P.key0, P.key1);
         keep = (uint64_t)r >= P.threshold;
     }
@@ -350,7 +359,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
             const int i = g / P.wpr, w = g % P.wpr, j = w * 64 + lane;
             bool keep = false;
             if (j < P.KB) {
-                const uint64_t b = (uint64_t)i * (uint64_t)P.KB + (uint64_t)j;
+                const uint64_t b = logical_block(P, i, j);
                 const uint32_t r = philox_word0((uint32_t)b, (uint32_t)(b >> 32), P.ctr2, P.ctr3, P.key0, P.key1);
                 keep = (uint64_t)r >= P.threshold;
             }
@@ -470,16 +479,18 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
                 double p, uint64_t seed, uint64_t rng_stream, const uint64_t *given_bits,
-                void *stream)
+                void *stream, int split_m = 1, int split_k = 1)
 {
     if (!mask) return SDROP_EINVAL;
     if (!(p >= 0.0 && p <= 1.0)) return SDROP_EINVAL;
+    if (split_m < 1 || split_k < 1) return SDROP_EINVAL;
     sdrop_mask_layout_t L;
     const int rc = sdrop_mask_layout(M, K, BM, BK, &L);
     if (rc != SDROP_OK) return rc;
     if (reinterpret_cast<uintptr_t>(mask) % 16) return SDROP_EALIGN;
     if (given_bits && reinterpret_cast<uintptr_t>(given_bits) % 8) return SDROP_EALIGN;
     if (mask_bytes < L.total_bytes) return SDROP_EWORKSPACE;
+    if (L.MB % split_m || L.KB % split_k) return SDROP_ESHAPE;
 
     char *b = static_cast<char *>(mask);
     MaskParams P;
@@ -498,6 +509,7 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     P.M = M; P.K = K; P.BM = BM; P.BK = BK;
     P.MB = static_cast<int32_t>(L.MB); P.KB = static_cast<int32_t>(L.KB);
     P.wpr = static_cast<int32_t>(L.words_per_row);
+    P.split_m = split_m; P.split_k = split_k; P.KBL = P.KB / split_k;
     P.key0 = static_cast<uint32_t>(seed); P.key1 = static_cast<uint32_t>(seed >> 32);
     P.ctr2 = static_cast<uint32_t>(rng_stream); P.ctr3 = static_cast<uint32_t>(rng_stream >> 32);
     P.threshold = static_cast<uint64_t>(floor(p * 4294967296.0));
@@ -580,6 +592,12 @@ int sdrop_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int 
                double p, uint64_t seed, uint64_t rng_stream, void *stream)
 {
     return sdrop::launch_mask(mask, mask_bytes, M, K, BM, BK, p, seed, rng_stream, nullptr, stream);
+}
+
+int sdrop_mask_split(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,
+                     int split_m, int split_k, double p, uint64_t seed, uint64_t rng_stream, void *stream)
+{
+    return sdrop::launch_mask(mask, mask_bytes, M, K, BM, BK, p, seed, rng_stream, nullptr, stream, split_m, split_k);
 }
 
 int sdrop_mask_from_bits(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int BK,

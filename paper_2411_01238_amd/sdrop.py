@@ -22,7 +22,7 @@ OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
 MASK_NNZ_OFFSET = 36
 
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
-           "sdrop_mask", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
+           "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
            "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw")
 
 _DTYPES = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
@@ -66,6 +66,8 @@ def lib():
         L.sdrop_mask_bytes.restype = sz
         L.sdrop_mask.argtypes = [vp, sz, i64, i64, ci, ci, dbl, u64, u64, vp]
         L.sdrop_mask.restype = ci
+        L.sdrop_mask_split.argtypes = [vp, sz, i64, i64, ci, ci, ci, ci, dbl, u64, u64, vp]
+        L.sdrop_mask_split.restype = ci
         L.sdrop_mask_from_bits.argtypes = [vp, sz, i64, i64, ci, ci, vp, vp]
         L.sdrop_mask_from_bits.restype = ci
         L.sdrop_workspace_bytes.argtypes = [ci, i64, i64, i64, ci, ci, ci, ci]
@@ -164,6 +166,15 @@ def sdrop_mask(M, K, BM, BK, p, seed, rng_stream=0, out=None):
     m.p = float(p)
     _check(lib().sdrop_mask(_dev(m.buf, "mask"), m.buf.numel(), M, K, BM, BK, float(p),
                             int(seed), int(rng_stream), _stream()), "sdrop_mask")
+    return m
+
+
+def sdrop_mask_split(M, K, BM, BK, split_m, split_k, p, seed, rng_stream=0, out=None):
+    """Block splitting (Section 3.3): logical blocks of (split_m BM) x (split_k BK), retiled to BM x BK."""
+    m = out if out is not None else Mask(M, K, BM, BK, p)
+    m.p = float(p)
+    _check(lib().sdrop_mask_split(_dev(m.buf, "mask"), m.buf.numel(), M, K, BM, BK, int(split_m), int(split_k),
+                                  float(p), int(seed), int(rng_stream), _stream()), "sdrop_mask_split")
     return m
 
 

@@ -79,6 +79,9 @@ def test_host_side_argument_errors_return_before_any_launch():
     assert L.sdrop_mask(p, 16, 256, 256, 64, 64, 0.5, 0, 0, null) == sdrop.EWORKSPACE
     assert L.sdrop_mask(ctypes.c_void_p(addr + 4), 1 << 16, 256, 256, 64, 64, 0.5, 0, 0, null) == sdrop.EALIGN
     assert L.sdrop_mask_from_bits(p, 1 << 16, 256, 256, 64, 64, null, null) == sdrop.EINVAL
+    assert L.sdrop_mask_split(p, 1 << 16, 256, 256, 64, 64, 0, 1, 0.5, 0, 0, null) == sdrop.EINVAL
+    assert L.sdrop_mask_split(p, 1 << 16, 256, 256, 64, 64, 3, 1, 0.5, 0, 0, null) == sdrop.ESHAPE   # 4 block rows
+    assert L.sdrop_mask_split(p, 1 << 16, 256, 256, 64, 64, 2, 8, 0.5, 0, 0, null) == sdrop.ESHAPE
     for name in ("sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw"):
         f = getattr(L, name)
         ok = (p, p, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)

@@ -129,6 +129,28 @@ def test_dx_persistent_kernel_with_several_blocks_per_tile(M, K, N, BM, BK, dtyp
         sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16)
 
 
+def test_retilings_of_one_logical_mask_give_the_same_products():
+    # Section 3.3: logical blocks of 128 x 128, used as such, with the K-blocks halved (the section's
+    # forward pass), with the M-blocks halved (its dW), and quartered; each against the oracle on
+    # its own tiling, whose three results agree with each other on the CPU already
+    M, K, N, p, seed = 1024, 768, 256, 0.4, 31
+    X, W, dY = make_custom(M, K, N, "bf16", seed=seed)
+    print("gemm retiled masks", flush=True)
+    Xd, Wd, dYd = f64(X), f64(W), f64(dY)
+    logical = orc.mask(M // 128, K // 128, p, seed, 0)
+    ref = (orc.fwd(Xd, Wd, logical, 128, 128, p), orc.bwd_dx(dYd, Wd, logical, 128, 128, p),
+           orc.bwd_dw(Xd, dYd, logical, 128, 128, p))
+    for BM, BK in ((128, 128), (128, 64), (64, 128), (64, 64)):
+        sm, sk = 128 // BM, 128 // BK
+        m = sdrop.sdrop_mask_split(M, K, BM, BK, sm, sk, p, seed, 0)
+        keep = orc.mask_split(M // BM, K // BK, sm, sk, p, seed, 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(m.bits().cpu().numpy().view(np.uint64), orc.pack_bits(keep))
+        outs = _run_all(X, W, dY, m, torch.float32)
+        for name, o, r in zip(("Y", "dX", "dW"), outs, ref):
+            assert_close(f64(o), r, "retiled %dx%d %s" % (BM, BK, name))
+
+
 def test_p1_and_p0_without_ragged_edges():
     # the persistent kernels: everything dropped (zero fill only, no tile at all) and everything kept
     X, W, dY = make_custom(512, 512, 128, "bf16", seed=21)

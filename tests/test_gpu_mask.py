@@ -63,6 +63,19 @@ def test_mask_edge_shapes(M, K, BM, BK, p, seed, stream):
     _check_mask(m, orc.mask(M // BM, K // BK, p, seed, stream))
 
 
+@pytest.mark.parametrize("M,K,BM,BK,sm,sk,p,seed,stream", [
+    (512, 512, 64, 64, 2, 2, 0.5, 1, 0),               # 8 x 8 blocks from a 4 x 4 logical mask (bits drawn by the list kernel)
+    (128 * 32, 128 * 32, 128, 128, 2, 1, 0.5, 0, 3),   # logical 256 x 128
+    (64 * 96, 64 * 140, 64, 64, 3, 2, 0.3, 5, 1),      # three words per row; factors that are not powers of two
+    (64 * 2100, 64 * 4, 64, 64, 2, 4, 0.6, 2, 2),      # more than 2048 block rows: the list builder in global memory
+    (128 * 6, 64 * 10, 128, 64, 1, 2, 0.4, 8, 0),      # the forward pass's use in Section 3.3: K-blocks halved
+])
+def test_block_splitting_matches_oracle(M, K, BM, BK, sm, sk, p, seed, stream):
+    print("mask split", M, K, BM, BK, sm, sk, p, seed, stream, flush=True)
+    m = sdrop.sdrop_mask_split(M, K, BM, BK, sm, sk, p, seed, stream)
+    _check_mask(m, orc.mask_split(M // BM, K // BK, sm, sk, p, seed, stream))
+
+
 def test_mask_is_reproducible_and_reusable():
     a = sdrop.sdrop_mask(4096, 4096, 128, 128, 0.5, 0, 0)
     b = sdrop.sdrop_mask(4096, 4096, 128, 128, 0.5, 0, 0)
