@@ -44,6 +44,7 @@
 // loop, is ~2.0 GHz with the MFMAs alone, ~1.55 GHz once the operand reads from LDS are added
 // and ~1.4 GHz with the loads as well, at 84 % MFMA duty (1214 clocks per slice against 1024).
 #include "sdrop_internal.h"
+#include <limits.h>
 #include <stdlib.h>
 #include <type_traits>
 #include <utility>
@@ -1656,6 +1657,11 @@ int run(const void *a, const void *b, const void *mask, void *out,
     if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
     sdrop_mask_layout_t L;
     sdrop_mask_layout(M, K, BM, BK, &L);
+    {
+        // tile numbers are 32-bit (no operand that fits the device's memory comes near this)
+        const int64_t n_tiles = (N + 255) / 256, lines = L.MB > L.KB ? L.MB : L.KB;
+        if (lines * n_tiles * 16 > INT32_MAX) return SDROP_ESHAPE;
+    }
     GemmParams P;
     P.A = static_cast<const char *>(a);
     P.B = static_cast<const char *>(b);
