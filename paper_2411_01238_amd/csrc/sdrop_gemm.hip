@@ -1558,16 +1558,32 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, Ou
 // computed by different workgroups into fp32 planes that a second pass sums in a fixed
 // order (deterministic, unlike atomics).  A pure function of the shape (not of p), so that
 // the workspace size can be asked for without the mask.
+//
+// The number of parts minimises a small cost model, in units of one reduction slice: the launch
+// runs ceil(tiles * parts / CUs) rounds of part-tiles, each costing its share of the list (taken
+// at full length, M/64 slices) plus a fixed 10 for set-up and epilogue, and the summing pass reads
+// parts * K * N floats (about 0.86e6 floats per slice time).  Measured against "always two rounds":
+// 2048^3 with 128-blocks 37 -> 28 us, the 8192 x 1024 x 1024 layer 26 -> 23 us.  Only powers of
+// two are tried (3 or 5 parts measured up to 1.5x slower than 2 or 4 on the same shapes).
 int dw_splits(int64_t M, int64_t N, int BM, int BK, int64_t K)
 {
     const int64_t tiles = (K / BK) * ((N + 255) / 256);
     const int64_t ncu = cu_count();
     if (tiles >= ncu) return 1;
-    int64_t s = (2 * ncu + tiles - 1) / tiles;            // aim at two waves of workgroups
-    const int64_t max_by_len = (M / BM) / 4;              // keep at least ~4 row blocks per part
-    if (s > max_by_len) s = max_by_len;
-    if (s > 16) s = 16;
-    return s < 1 ? 1 : (int)s;
+#ifdef SDROP_GEMM_TIMING
+    if (getenv("SDROP_DW_SPLITS")) return atoi(getenv("SDROP_DW_SPLITS"));
+#endif
+    int64_t max_parts = (M / BM) / 4;                      // keep at least ~4 row blocks per part
+    if (max_parts > 16) max_parts = 16;
+    const double len = (double)(M / 64), sum_cost = (double)K * (double)N / 0.86e6;
+    int best = 1;
+    double best_cost = 0.0;
+    for (int64_t parts = 1; parts <= max_parts || parts == 1; parts *= 2) {   // powers of two: odd counts measured far worse
+        const double rounds = (double)((tiles * parts + ncu - 1) / ncu);
+        const double cost = rounds * (len / parts + 10.0) + (parts > 1 ? parts * sum_cost : 0.0);
+        if (parts == 1 || cost < best_cost) { best = (int)parts; best_cost = cost; }
+    }
+    return best;
 }
 
 int cu_count()
