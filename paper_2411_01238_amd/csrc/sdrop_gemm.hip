@@ -2,8 +2,14 @@
 // eq. (1)-(3), Section 3.2) as one MFMA main loop with three instantiations.
 //
 //   FWD  Y  = s (X . m') W        tile (block row i, N tile): walks the kept K-blocks of row i
-//   DX   dX = s (dY W^T) . m'     tile = one kept block (i,j): reduction over all of N
+//   DX   dX = s (dY W^T) . m'     tile = 1, 2 or 4 kept blocks of one block row: reduction over all of N
 //   DW   dW = s (X . m')^T dY     tile (block column j, N tile): walks the kept row blocks of column j
+//
+// Two kernel forms share that loop.  gemm_kernel: one launch per tile (ragged edges, and the shapes
+// where several co-resident workgroups or the hardware's dynamic dispatch do better).
+// gemm_persistent_kernel / gemm_persistent_dx_kernel: one workgroup per CU walks a sequence of
+// tiles as one stream of slices, so that the next tile's operands arrive while the current one is
+// still multiplied and stored; the host picks between them per call (dispatch_tile).
 //
 // Each workgroup owns one TM x TN output tile and steps through its reduction in slices of
 // TK = 64 that rotate through LDS stages (three for 128-row tiles, one workgroup per CU; two for
