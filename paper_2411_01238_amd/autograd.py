@@ -1,0 +1,63 @@
+"""torch.autograd wrapper over the binding: SparseDrop in front of a linear layer as one op.
+
+Section 3.1 of arxiv 2411.01238: forward eq. (1), backward eq. (2) and (3), the block mask of
+Section 3.2 drawn once per call and shared by the three products.  Everything runs in libsdrop's
+kernels; this file only wires them into autograd (no arithmetic of its own besides the bias add
+and the seed bookkeeping).
+"""
+import torch
+
+from . import sdrop
+
+
+class _SparseDropMatmul(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, w, p, BM, BK, seed, rng_stream):
+        m = sdrop.sdrop_mask(x.shape[0], x.shape[1], BM, BK, p, seed, rng_stream)
+        y = sdrop.sdrop_fwd(x, w, m)
+        ctx.save_for_backward(x, w)
+        ctx.mask = m
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        x, w = ctx.saved_tensors
+        dy = dy.contiguous()
+        dx = sdrop.sdrop_bwd_dx(dy, w, ctx.mask) if ctx.needs_input_grad[0] else None
+        dw = sdrop.sdrop_bwd_dw(x, dy, ctx.mask) if ctx.needs_input_grad[1] else None
+        return dx, dw, None, None, None, None, None
+
+
+def sparsedrop_matmul(x, w, p, BM=128, BK=128, seed=0, rng_stream=0):
+    """y = (x . m') w / (1 - p) with a fresh block mask m' (Bernoulli(1-p) per BM x BK block of x).
+
+    x [M, K] and w [K, N] are contiguous fp16 / bf16 GPU tensors; M % BM == 0, K % BK == 0, N % 8 == 0.
+    """
+    return _SparseDropMatmul.apply(x, w, float(p), int(BM), int(BK), int(seed), int(rng_stream))
+
+
+class SparseDropLinear(torch.nn.Module):
+    """Dropout(p) followed by Linear(K -> N), with the dropout block-structured and fused into the
+    layer's three GEMMs (the layer substitution of Section 4).  The weight is stored [K, N] as in
+    Section 3.1.  In eval mode nothing is dropped (p = 0: all blocks kept, scale 1)."""
+
+    def __init__(self, in_features, out_features, p=0.5, BM=128, BK=128, bias=True, seed=0,
+                 dtype=torch.bfloat16, device="cuda"):
+        super().__init__()
+        self.p, self.BM, self.BK, self.seed = float(p), int(BM), int(BK), int(seed)
+        w = torch.empty(in_features, out_features, dtype=torch.float32)
+        torch.nn.init.kaiming_uniform_(w.t(), a=5 ** 0.5)
+        self.weight = torch.nn.Parameter(w.to(dtype=dtype, device=device))
+        self.bias = torch.nn.Parameter(torch.zeros(out_features, dtype=dtype, device=device)) if bias else None
+        self.calls = 0          # the mask's rng_stream: a new mask every forward call
+
+    def forward(self, x):
+        lead = x.shape[:-1]
+        x2 = x.reshape(-1, x.shape[-1]).contiguous()
+        p = self.p if self.training else 0.0
+        y = sparsedrop_matmul(x2, self.weight, p, self.BM, self.BK, self.seed, self.calls)
+        if self.training:
+            self.calls += 1
+        if self.bias is not None:
+            y = y + self.bias
+        return y.reshape(*lead, y.shape[-1])
