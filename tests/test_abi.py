@@ -100,3 +100,22 @@ def test_host_side_argument_errors_return_before_any_launch():
         assert call(a10=sdrop.F32) == sdrop.EDTYPE
         assert call(a11=sdrop.BF16) == sdrop.EDTYPE   # out_dtype must be the input type or fp32
         assert call(a1=ctypes.c_void_p(addr + 8)) == sdrop.EALIGN
+
+
+def test_workspace_size_is_a_whole_number_of_fp32_planes():
+    # only dW asks for a workspace: `parts` fp32 planes of K x N, parts a power of two up to 16, none
+    # when K/BK * ceil(N/256) output tiles already fill the chip (256 CUs assumed without a device)
+    L = sdrop.lib()
+    for (M, K, N, BM, BK) in ((4096, 4096, 4096, 128, 128), (65536, 4096, 1024, 128, 128), (8192, 1024, 1024, 64, 64),
+                              (16384, 3072, 768, 128, 64), (2048, 256, 264, 64, 64), (256, 256, 8, 128, 128)):
+        for op in (sdrop.OP_FWD, sdrop.OP_BWD_DX):
+            assert L.sdrop_workspace_bytes(op, M, K, N, BM, BK, sdrop.BF16, sdrop.BF16) == 0
+        b = L.sdrop_workspace_bytes(sdrop.OP_BWD_DW, M, K, N, BM, BK, sdrop.BF16, sdrop.BF16)
+        assert b % (K * N * 4) == 0
+        parts = b // (K * N * 4)
+        tiles = (K // BK) * ((N + 255) // 256)
+        assert parts in (0, 2, 4, 8, 16)
+        if tiles >= 304:
+            assert parts == 0
+        assert parts <= max((M // BM) // 4, 1) or parts == 0
+    assert L.sdrop_workspace_bytes(sdrop.OP_BWD_DW, 100, 256, 256, 64, 64, sdrop.BF16, sdrop.BF16) == 0   # bad shape
