@@ -84,3 +84,40 @@ def test_full_size_sampled(name, p):
 def test_mlp_other_layers_use_their_own_stream():
     w = WORKLOADS["mlp"]
     _sampled_parity(w, 0.5, layer=3, n=200, n_dw=48)
+
+
+def test_mlp_four_layers_chained():
+    # the 4-layer MLP as a chain: layer l+1 reads the 16-bit Y of layer l, the backward pass feeds dX of
+    # layer l+1 to layer l as its dY (no activation in between).  Each product is checked against the
+    # oracle on exactly the 16-bit operands the device used, so errors do not accumulate in the check.
+    w = WORKLOADS["mlp"]
+    p = 0.5
+    print("full-size case mlp chain", flush=True)
+    rng = np.random.default_rng(99)
+    X0, _, dY_last = make_inputs(w, layer=0)
+    Ws = [make_inputs(w, layer=l)[1].cuda() for l in range(w.layers)]
+    masks = [sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, w.mask_seed, l) for l in range(w.layers)]
+    keeps = [orc.mask(w.MB, w.KB, p, w.mask_seed, l) for l in range(w.layers)]
+    acts = [X0.cuda()]
+    for l in range(w.layers):
+        acts.append(sdrop.sdrop_fwd(acts[l], Ws[l], masks[l]))
+    grads = [None] * (w.layers + 1)
+    grads[w.layers] = dY_last.cuda()
+    dWs = [None] * w.layers
+    for l in reversed(range(w.layers)):
+        dWs[l] = sdrop.sdrop_bwd_dw(acts[l], grads[l + 1], masks[l])
+        grads[l] = sdrop.sdrop_bwd_dx(grads[l + 1], Ws[l], masks[l])
+    torch.cuda.synchronize()
+
+    def gather(t, r, c):
+        return t[torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()].cpu().to(torch.float64).numpy()
+
+    for l in range(w.layers):
+        Xd, Wd, dYd = f64(acts[l].cpu()), f64(Ws[l].cpu()), f64(grads[l + 1].cpu())
+        assert np.isfinite(Xd).all() and np.isfinite(dYd).all()
+        r, c = _positions(rng, w.M, w.N, 150, w.BM, 256)
+        assert_close(gather(acts[l + 1], r, c), orc.fwd_at(Xd, Wd, keeps[l], w.BM, w.BK, p, r, c), "chain layer %d Y" % l)
+        r, c = _positions(rng, w.M, w.K, 150, w.BM, w.BK)
+        assert_close(gather(grads[l], r, c), orc.bwd_dx_at(dYd, Wd, keeps[l], w.BM, w.BK, p, r, c), "chain layer %d dX" % l)
+        r, c = _positions(rng, w.K, w.N, 48, w.BK, 256)
+        assert_close(gather(dWs[l], r, c), orc.bwd_dw_at(Xd, dYd, keeps[l], w.BM, w.BK, p, r, c), "chain layer %d dW" % l)
