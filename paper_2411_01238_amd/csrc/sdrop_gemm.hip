@@ -134,6 +134,17 @@ struct GemmParams {
     double p;           // host only: dropout probability, for choosing tile shapes
 };
 
+// 16 bytes of output, as a non-temporal store.  Outputs are written once and not read again by the
+// kernel that writes them; stored this way they neither displace operand tiles from the L2s and
+// the Infinity Cache nor wait there, dirty, for the write-back at the end of the kernel (4096^3,
+// half the blocks kept, operands outside the Infinity Cache: 224 -> 208 us per step).
+__device__ __forceinline__ void store_out(char *p, uint4 v)
+{
+    typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+    const u32x4 w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(p));
+}
+
 // Slot swizzle of an LDS operand row: a 3-bit value XORed into the chunk index.
 // With m = (r>>1)&7: rotate m left by one and flip with bits 4,5 of r.  Measured
 // conflict-free for ds_read_b128 of 32 consecutive rows x 2 chunks per wavefront,
@@ -461,7 +472,7 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         auto zero_block = [&](int zi, int zj) __attribute__((always_inline)) {
             char *z = P.C + (int64_t)zi * P.BM * ldc + (int64_t)zj * P.BK * sizeof(OutT);
             for (int c = threadIdx.x; c < TM * row_chunks; c += NT)
-                *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
+                store_out(z + (c / row_chunks) * ldc + (c % row_chunks) * 16, make_uint4(0, 0, 0, 0));
         };
         int i, blocks_valid;                          // block row; kept blocks in this tile (<= 0: nothing to compute)
         int jg[NGRP_MAX] = {0, 0, 0, 0};
@@ -837,7 +848,7 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
                 for (int gg = 1; gg < DXG; ++gg) cbase = (g == gg) ? cgrp[gg] : cbase;
                 col &= 63;
             }
-            if (ok) *reinterpret_cast<uint4 *>(cbase + (int64_t)(wm * WTM + row) * ldc + col * ESZ) = v;
+            if (ok) store_out(cbase + (int64_t)(wm * WTM + row) * ldc + col * ESZ, v);
         }
         GEMM_TICK(4);
     }
@@ -958,7 +969,7 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                         const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
                         v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
                     }
-                    *reinterpret_cast<uint4 *>(out + (int64_t)row * ldc + rch * 16) = v;
+                    store_out(out + (int64_t)row * ldc + rch * 16, v);
                 }
             }
     }
@@ -1407,7 +1418,7 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
             const int zi = pz / P.KB, zj = pz % P.KB;
             char *z = P.C + (int64_t)zi * P.BM * ldc + (int64_t)zj * P.BK * ESZ;
             for (int c = threadIdx.x; c < TM * row_chunks; c += NW * 64)
-                *reinterpret_cast<uint4 *>(z + (c / row_chunks) * ldc + (c % row_chunks) * 16) = make_uint4(0, 0, 0, 0);
+                store_out(z + (c / row_chunks) * ldc + (c % row_chunks) * 16, make_uint4(0, 0, 0, 0));
         }
     };
 
