@@ -22,7 +22,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_DENSE_TFLOPS = 2500.0     # MI355X published dense bf16/fp16 MFMA peak
 # Bytes per launch that crossed L2 -> fabric, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a known 1 GiB
 # copy (profiles/bench_square4096_p0.5_hbm_traffic.md), workload square4096 at p = 0.5
-MEASURED_TRAFFIC_BYTES = {"square4096": {"fwd": 236.0e6, "dx": 317.7e6, "dw": 239.8e6}}
+MEASURED_TRAFFIC_BYTES = {"square4096": {"fwd": 235.7e6, "dx": 316.9e6, "dw": 238.6e6}}
 HEADLINE_P = 0.5
 
 
