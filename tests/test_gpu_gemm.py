@@ -226,3 +226,32 @@ def test_binding_reports_errors():
     with pytest.raises(sdrop.SdropError) as e:
         sdrop.sdrop_fwd(X.cuda().float(), W.cuda().float(), m)
     assert e.value.code == sdrop.EDTYPE
+
+
+def _patterns(MB, KB):
+    full_row = np.zeros((MB, KB), dtype=np.uint8); full_row[MB // 2, :] = 1
+    full_col = np.zeros((MB, KB), dtype=np.uint8); full_col[:, KB - 1] = 1
+    checker = ((np.add.outer(np.arange(MB), np.arange(KB)) % 2) == 0).astype(np.uint8)
+    lower = (np.subtract.outer(np.arange(MB), np.arange(KB)) >= 0).astype(np.uint8)
+    last = np.zeros((MB, KB), dtype=np.uint8); last[MB - 1, KB - 1] = 1
+    all_but_one = np.ones((MB, KB), dtype=np.uint8); all_but_one[0, 0] = 0
+    return {"one full block row": full_row, "one full block column": full_col, "checkerboard": checker,
+            "lower triangle": lower, "only the last block": last, "all but the first block": all_but_one}
+
+
+@pytest.mark.parametrize("force_groups", [False, True])
+def test_structured_masks_on_a_grid_larger_than_the_chip(force_groups):
+    # 24 x 20 blocks of 128 x 128: more block positions than CUs, so the persistent kernels run several
+    # tiles per workgroup, with kept lists that are as unbalanced as they get (an empty row next to a
+    # full one, a single column, a triangle).  Once with the default choice of dX kernel, once with
+    # tiles of several blocks forced onto the persistent kernel.
+    MB, KB, B, N = 24, 20, 128, 256
+    X, W, dY = make_custom(MB * B, KB * B, N, "bf16", seed=41)
+    sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 0 if force_groups else 16)
+    try:
+        for name, keep in _patterns(MB, KB).items():
+            print("gemm structured mask:", name, force_groups, flush=True)
+            p = 1.0 - float(keep.mean())              # the scale that goes with this kept fraction; any p would do
+            _full_parity(X, W, dY, B, B, p, 0, 0, name, keep=keep)
+    finally:
+        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16)
