@@ -204,6 +204,7 @@ def main():
                    "kept_blocks": nnz, "blocks": w.MB * w.KB},
         "frac_of_bf16_peak": round(value / PEAK_BF16_DENSE_TFLOPS, 5),
         "ms_per_step_warm_single_set": round(ms_warm, 5),
+        "untimed_settle_steps_before_warmup": 150,
         "sweep": sweep,
         "linearity": linearity,
         "vendor_dense_gemm_ms_single_set": vendor,
