@@ -208,6 +208,73 @@ int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
                  int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Sparse operators for the layers around the dropout (Section 4.3, closing remark: the layer
+ * directly before the dropout can use sparse operators as well).  None of this is part of
+ * eq. (1)-(3); it is what lets a block  H -> act(H W0^T + b0) -> SparseDrop -> . W  run without
+ * ever computing, storing or reading a dropped block, forward and backward.
+ *
+ * An element-wise tail on the fp32 accumulator, before the single rounding:
+ *
+ *     out = [relu_mask > 0] act(scale * acc + bias[column])
+ *
+ *   scale_mode  SDROP_SCALE_DROPOUT: scale = 1/(1-p), as in eq. (1)-(3)
+ *               SDROP_SCALE_ONE:     scale = 1 (a masked product that is not a dropout's output)
+ *   act         SDROP_ACT_NONE, SDROP_ACT_RELU (max(v,0)), SDROP_ACT_GELU_TANH
+ *               (0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))), the "tanh" form of GELU)
+ *   bias        device, fp32[number of output columns], 16-byte aligned, or NULL
+ *   relu_mask   device, a matrix of type `dtype` with the output's shape, 16-byte aligned, or
+ *               NULL: where it is not > 0 the output is +-0 (the backward of a ReLU, given
+ *               the ReLU's output).  Its dropped blocks are never read.
+ *
+ * sdrop_fwd_ex / sdrop_bwd_dx_ex / sdrop_bwd_dw_ex are sdrop_fwd / sdrop_bwd_dx / sdrop_bwd_dw
+ * with such a tail (epi = NULL: exactly those).  sdrop_bwd_dw_ex takes scale_mode only and
+ * returns SDROP_EINVAL for anything else; bad enum values give SDROP_EINVAL, a misaligned bias
+ * or relu_mask SDROP_EALIGN.  Dropped blocks of sdrop_bwd_dx_ex's output are +0 whatever the tail.
+ */
+enum { SDROP_SCALE_DROPOUT = 0, SDROP_SCALE_ONE = 1 };
+enum { SDROP_ACT_NONE = 0, SDROP_ACT_RELU = 1, SDROP_ACT_GELU_TANH = 2 };
+
+typedef struct sdrop_epilogue {
+    int32_t scale_mode;
+    int32_t act;
+    const float *bias;
+    const void *relu_mask;
+} sdrop_epilogue_t;
+
+int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,
+                 int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                 int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                 const sdrop_epilogue_t *epi);
+int sdrop_bwd_dx_ex(const void *dY, const void *W, const void *mask, void *dX,
+                    int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                    int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                    const sdrop_epilogue_t *epi);
+int sdrop_bwd_dw_ex(const void *X, const void *dY, const void *mask, void *dW,
+                    int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                    int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                    const sdrop_epilogue_t *epi);
+
+/*
+ * The layer before the dropout as an output-sparse product: only the blocks of X that the
+ * dropout keeps are computed; dropped blocks are written as +0.
+ *
+ *     X[M,K] = m' . act(H W0^T + b0)
+ *
+ *   H[M,N0]   input of type `dtype`
+ *   W0[K,N0]  the producing layer's weight, one ROW per output feature (the [out, in] layout)
+ *   bias      device fp32[K] or NULL;  act as above;  mask over X[M,K] in BM x BK blocks
+ *   p         used only to choose tile shapes (the product is not scaled)
+ * It is sdrop_bwd_dx_ex(H, W0, ...) with SDROP_SCALE_ONE: the same kernels.  Its backward uses
+ * the other two (dZ = the gradient at the pre-activation, zero on dropped blocks):
+ *     dH[M,N0]  = (dZ . m') W0      sdrop_fwd_ex(dZ, W0, mask, dH, M, K, N0, ..., SDROP_SCALE_ONE)
+ *     dW0[K,N0] = (dZ . m')^T H     sdrop_bwd_dw_ex(dZ, H, mask, dW0, M, K, N0, ..., SDROP_SCALE_ONE)
+ * and, for act = ReLU, dZ itself comes from sdrop_bwd_dx_ex(dY, W, ..., relu_mask = X).
+ */
+int sdrop_producer(const void *H, const void *W0, const float *bias, const void *mask, void *X,
+                   int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
+                   int dtype, int out_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

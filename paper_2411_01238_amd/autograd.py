@@ -36,6 +36,57 @@ def sparsedrop_matmul(x, w, p, BM=128, BK=128, seed=0, rng_stream=0):
     return _SparseDropMatmul.apply(x, w, float(p), int(BM), int(BK), int(seed), int(rng_stream))
 
 
+class _SparseReluBlock(torch.autograd.Function):
+    """Linear -> ReLU -> SparseDrop -> Linear with every GEMM sparse (Section 4.3, closing remark).
+
+    forward   X = m' . relu(H W0^T + b0)        sdrop_producer (dropped blocks never computed)
+              Y = s X W                          eq. (1)
+    backward  dZ  = s (dY W^T) . m' . [X > 0]    eq. (2) with the ReLU gate in its tail
+              dW  = s X^T dY                     eq. (3)
+              dH  = dZ W0, dW0 = dZ^T H          eq. (1) / eq. (3) at scale 1 on the block-sparse dZ
+              db0 = column sums of dZ            (a torch reduction: no GEMM)
+    """
+
+    @staticmethod
+    def forward(ctx, h, w0, b0, w, p, BM, BK, seed, rng_stream):
+        M, K = h.shape[0], w0.shape[0]
+        m = sdrop.sdrop_mask(M, K, BM, BK, p, seed, rng_stream)
+        x = sdrop.sdrop_producer(h, w0, b0, m, act=sdrop.ACT_RELU)
+        y = sdrop.sdrop_fwd(x, w, m)
+        ctx.save_for_backward(h, w0, w, x)
+        ctx.mask = m
+        ctx.has_bias = b0 is not None
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        h, w0, w, x = ctx.saved_tensors
+        m = ctx.mask
+        dy = dy.contiguous()
+        need_h, need_w0, need_b0, need_w = ctx.needs_input_grad[:4]
+        dz = dh = dw0 = db0 = dw = None
+        if need_h or need_w0 or (need_b0 and ctx.has_bias):
+            dz = sdrop.sdrop_bwd_dx_ex(dy, w, m, relu_mask=x)
+        if need_h:
+            dh = sdrop.sdrop_fwd_ex(dz, w0, m, scale_mode=sdrop.SCALE_ONE)
+        if need_w0:
+            dw0 = sdrop.sdrop_bwd_dw_ex(dz, h, m, scale_mode=sdrop.SCALE_ONE)
+        if need_b0 and ctx.has_bias:
+            db0 = dz.sum(dim=0, dtype=torch.float32)
+        if need_w:
+            dw = sdrop.sdrop_bwd_dw(x, dy, m)
+        return dh, dw0, db0, dw, None, None, None, None, None
+
+
+def sparse_relu_block(h, w0, b0, w, p, BM=128, BK=128, seed=0, rng_stream=0):
+    """y = s (m' . relu(h w0^T + b0)) w with a fresh block mask m' over the hidden activation.
+
+    h [M, N0], w0 [K, N0] (one row per hidden feature), b0 fp32 [K] or None, w [K, N]: contiguous
+    fp16 / bf16 GPU tensors; M % BM == 0, K % BK == 0, N0 % 8 == 0, N % 8 == 0.
+    """
+    return _SparseReluBlock.apply(h, w0, b0, w, float(p), int(BM), int(BK), int(seed), int(rng_stream))
+
+
 class SparseDropLinear(torch.nn.Module):
     """Dropout(p) followed by Linear(K -> N), with the dropout block-structured and fused into the
     layer's three GEMMs (the layer substitution of Section 4).  The weight is stored [K, N] as in

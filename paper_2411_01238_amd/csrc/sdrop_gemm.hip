@@ -131,6 +131,10 @@ struct GemmParams {
     int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)
     int32_t total_tiles; // persistent kernels: tiles of the whole launch
     float scale;
+    // optional element-wise tail of FWD and DX (see Tail below); all null / 0 for eq. (1)-(3) proper
+    const float *bias;
+    const char *aux;
+    int32_t act;
     double p;           // host only: dropout probability, for choosing tile shapes
 };
 
@@ -143,6 +147,57 @@ __device__ __forceinline__ void store_out(char *p, uint4 v)
     typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
     const u32x4 w = {v.x, v.y, v.z, v.w};
     __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(p));
+}
+
+// Element-wise tail applied to the scaled fp32 accumulator before the single rounding, for the
+// layers around the dropout (Section 4.3, closing remark: sparse operators for the layer before
+// the dropout as well):  out = [aux > 0] act(scale * acc + bias[column]).
+//   bias  fp32, one value per output column
+//   act   SDROP_ACT_RELU: max(v, 0);  SDROP_ACT_GELU_TANH: v / (1 + exp(-2 c (v + 0.044715 v^3))),
+//         c = sqrt(2/pi), which is 0.5 v (1 + tanh(c (v + 0.044715 v^3)))
+//   aux   matrix of the operands' type and the output's shape; where it is not > 0 the output
+//         is 0 (the backward of a ReLU whose output was kept)
+struct Tail {
+    const float *bias;
+    const char *aux;
+    const char *c0;     // the output's origin
+    int act;
+    bool on;
+};
+__device__ __forceinline__ Tail make_tail(const GemmParams &P)
+{
+    Tail t;
+    t.bias = P.bias; t.aux = P.aux; t.c0 = P.C; t.act = P.act;
+    t.on = P.bias != nullptr || P.aux != nullptr || P.act != 0;
+    return t;
+}
+// v: four consecutive columns of one output row, starting at global column `col`; `elem` is the
+// index of v[0] in the output matrix (row * columns + col).  col is a multiple of 4.
+template <class T>
+__device__ __forceinline__ void tail4(const Tail &tl, float (&v)[4], int64_t col, int64_t elem)
+{
+    if (tl.bias) {
+        const float4 b = *reinterpret_cast<const float4 *>(tl.bias + col);
+        v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
+    }
+    if (tl.act == SDROP_ACT_RELU) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = v[e] < 0.f ? 0.f : v[e];
+    } else if (tl.act == SDROP_ACT_GELU_TANH) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float x = v[e];
+            const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+            v[e] = x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));
+        }
+    }
+    if (tl.aux) {
+        using E = typename In<T>::out16;
+        typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
+        const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = static_cast<float>(x[e]) > 0.f ? v[e] : 0.f;
+    }
 }
 
 // Slot swizzle of an LDS operand row: a 3-bit value XORed into the chunk index.
@@ -430,6 +485,10 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
     const char *bgrp[NGRP_MAX] = {nullptr, nullptr, nullptr, nullptr};
     char *cgrp[NGRP_MAX] = {nullptr, nullptr, nullptr, nullptr};
     int chunks_valid = 0;                               // 64-column chunks that hold real blocks
+    // for the element-wise tail: global row of the tile's first row; global column of the tile
+    // (FWD) or of each 64-column chunk (DX)
+    int64_t out_row0 = 0;
+    int out_col0[NGRP_MAX] = {0, 0, 0, 0};
 
     if constexpr (OP == FWD) {
         const int t = blockIdx.x;
@@ -444,6 +503,8 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         a_tile = P.A + (int64_t)i * P.BM * lda;
         b_tile = P.B + (int64_t)nt * TN * esz;
         c_tile = P.C + (int64_t)i * P.BM * ldc + (int64_t)nt * TN * sizeof(OutT);
+        out_row0 = (int64_t)i * P.BM;
+        out_col0[0] = nt * TN;
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
     } else if constexpr (OP == DW) {
         // blockIdx.x = (rank of block column j in the schedule, N tile, part of the list)
@@ -542,7 +603,9 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
             const int64_t col0 = (int64_t)jg[g] * P.BK + (g & ((1 << cshift) - 1)) * 64;
             bgrp[g] = P.B + col0 * ldb;
             cgrp[g] = P.C + (int64_t)i * P.BM * ldc + col0 * sizeof(OutT);
+            out_col0[g] = (int)col0;
         }
+        out_row0 = (int64_t)i * P.BM;
         nsteps = (int)((P.N + TK - 1) / TK);
         a_tile = P.A + (int64_t)i * P.BM * lda;
     }
@@ -813,6 +876,7 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         if (loader) return;
         char *reg = smem + wave * REGION;
         const float scale = P.scale;
+        const Tail tl = make_tail(P);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -820,14 +884,33 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int row = mi * 32 + (lane & 31), col = ni * 32 + q * 8 + (lane >> 5) * 4;
-                    const float v0 = acc[mi][ni][4 * q] * scale, v1 = acc[mi][ni][4 * q + 1] * scale;
-                    const float v2 = acc[mi][ni][4 * q + 2] * scale, v3 = acc[mi][ni][4 * q + 3] * scale;
+                    float v[4] = {acc[mi][ni][4 * q] * scale, acc[mi][ni][4 * q + 1] * scale,
+                                  acc[mi][ni][4 * q + 2] * scale, acc[mi][ni][4 * q + 3] * scale};
+                    if constexpr (OP != DW) {
+                        if (tl.on) {
+                            const int cl = wn * WTN + col;          // column within the tile
+                            bool ok;
+                            int64_t gcol;
+                            if constexpr (OP == DX) {
+                                const int g = cl >> 6;
+                                ok = g < chunks_valid;
+                                int c0 = out_col0[0];
+#pragma unroll
+                                for (int gg = 1; gg < DXG; ++gg) c0 = (g == gg) ? out_col0[gg] : c0;
+                                gcol = c0 + (cl & 63);
+                            } else {
+                                ok = cl < c_lim;                    // c_lim is a multiple of 8
+                                gcol = out_col0[0] + cl;
+                            }
+                            if (ok) tail4<T>(tl, v, gcol, (out_row0 + wm * WTM + row) * (ldc / ESZ) + gcol);
+                        }
+                    }
                     char *dst = reg + row * RS + col * ESZ;
                     if constexpr (ESZ == 4) {
-                        *reinterpret_cast<float4 *>(dst) = make_float4(v0, v1, v2, v3);
+                        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
                     } else {
                         typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
-                        const out4 o = {static_cast<OutT>(v0), static_cast<OutT>(v1), static_cast<OutT>(v2), static_cast<OutT>(v3)};
+                        const out4 o = {static_cast<OutT>(v[0]), static_cast<OutT>(v[1]), static_cast<OutT>(v[2]), static_cast<OutT>(v[3])};
                         *reinterpret_cast<out4 *>(dst) = o;
                     }
                 }
@@ -930,7 +1013,8 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
     // rows then spread over all banks, and a 16-byte read finds its two halves in one 16-byte
     // piece, exchanged when r is odd.  dst(mi, nj) is the address of row 0 of the 32 x 128-byte
     // piece (mi, nj) of the wavefront's sub-tile, or null if that piece is not to be written.
-    template <class F> __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, F &&dst)
+    // With a tail (tl.on), dst also reports the global column of the piece's first column.
+    template <class F> __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
     {
         const int lane = threadIdx.x & 63;
         const int wrow = lane & 31, whalf = lane >> 5;
@@ -939,15 +1023,20 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int nj = 0; nj < NJ; ++nj) {
-                char *const out = dst(mi, nj);
+                int64_t gcol0 = 0;
+                char *const out = dst(mi, nj, gcol0);
                 if (!out) continue;                        // uniform
 #pragma unroll
                 for (int nl = 0; nl < NIP; ++nl)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const f32x16 &a = acc[mi][nj * NIP + nl];
-                        const float v0 = a[4 * q] * scale, v1 = a[4 * q + 1] * scale;
-                        const float v2 = a[4 * q + 2] * scale, v3 = a[4 * q + 3] * scale;
+                        float v[4] = {a[4 * q] * scale, a[4 * q + 1] * scale, a[4 * q + 2] * scale, a[4 * q + 3] * scale};
+                        if (tl.on) {
+                            const int c = nl * 32 + 8 * q + 4 * whalf;       // column within the piece
+                            tail4<T>(tl, v, gcol0 + c, (out - tl.c0) / ESZ + wrow * (ldc / ESZ) + c);
+                        }
+                        const float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
                         if constexpr (ESZ == 4) {
                             // 16 bytes per lane: 16-byte slot 2q + half, exchanged as a whole with (row & 7)
                             const int slot = (2 * q + whalf) ^ (wrow & 7);
@@ -1174,6 +1263,7 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
     int st0 = 0, st1 = 1, st2 = 2;       // stages of the stream's slices g, g+1, g+2
     bool started = false;
     const float scale = P.scale;
+    const Tail tl = make_tail(P);
     char *const reg = staging + wave * STAGING;
 
     for (int k = 0;; ++k) {
@@ -1203,7 +1293,8 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
             if constexpr (OP == FWD) c_tile = P.C + (int64_t)ord * P.BM * ldc + (int64_t)nt * TN * ESZ;
             else c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)ord * P.BK * ldc + (int64_t)nt * TN * ESZ;
             c_tile += (int64_t)(wm * WTM) * ldc + (int64_t)(wn * WTN) * ESZ;
-            cw.store(reg, scale, ldc, [&](int mi, int nj) __attribute__((always_inline)) -> char * {
+            cw.store(reg, scale, ldc, tl, [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
+                gcol0 = (int64_t)nt * TN + wn * WTN + nj * (128 / ESZ);
                 return c_tile + (int64_t)(mi * 32) * ldc + nj * 128;
             });
         }
@@ -1427,6 +1518,7 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
     int st0 = 0, st1 = 1, st2 = 2;
     bool started = false;
     const float scale = P.scale;
+    const Tail tl = make_tail(P);
     char *const reg = staging + wave * STAGING;
 
     Group nxt = c_load_group(0);
@@ -1459,12 +1551,13 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
                 const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
             }
             char *const c_rows = P.C + ((int64_t)row * P.BM + wm * WTM) * ldc;
-            cw.store(reg, scale, ldc, [&](int mi, int nj) __attribute__((always_inline)) -> char * {
+            cw.store(reg, scale, ldc, tl, [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
                 const int col_t = wn * WTN + nj * (128 / ESZ);         // first column of the piece, in the tile
                 const int g = col_t >> 6;
                 if (g >= chunks_valid) return nullptr;
                 const int col = sel4(gc, a + (g >> cshift));
                 const int64_t col0 = (int64_t)col * P.BK + (g & cmask) * 64 + (col_t & 63);
+                gcol0 = col0;
                 return c_rows + (int64_t)(mi * 32) * ldc + col0 * ESZ;
             });
             if (zc > 0) { fill_batch(z_done, zc, zword, bitpos); z_done += zc; }
@@ -1682,10 +1775,18 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
 template <int OP>
 int run(const void *a, const void *b, const void *mask, void *out,
         int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
-        int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
+        int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+        const sdrop_epilogue_t *epi = nullptr)
 {
     const int rc = check_gemm_args(a, b, mask, out, M, K, N, BM, BK, p, dtype, out_dtype);
     if (rc != SDROP_OK) return rc;
+    if (epi) {
+        if (epi->scale_mode != SDROP_SCALE_DROPOUT && epi->scale_mode != SDROP_SCALE_ONE) return SDROP_EINVAL;
+        if (epi->act != SDROP_ACT_NONE && epi->act != SDROP_ACT_RELU && epi->act != SDROP_ACT_GELU_TANH) return SDROP_EINVAL;
+        // the gradient of the weights takes a scale only
+        if (OP == DW && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask)) return SDROP_EINVAL;
+        if ((reinterpret_cast<uintptr_t>(epi->bias) | reinterpret_cast<uintptr_t>(epi->relu_mask)) % 16) return SDROP_EALIGN;
+    }
     const size_t ws_need = sdrop_workspace_bytes(OP, M, K, N, BM, BK, dtype, out_dtype);
     if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
     sdrop_mask_layout_t L;
@@ -1706,6 +1807,13 @@ int run(const void *a, const void *b, const void *mask, void *out,
     P.splits = 1;
     P.total_tiles = 0;
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
+    P.bias = nullptr; P.aux = nullptr; P.act = SDROP_ACT_NONE;
+    if (epi) {
+        if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
+        P.bias = epi->bias;
+        P.aux = static_cast<const char *>(epi->relu_mask);
+        P.act = epi->act;
+    }
     P.p = p;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if constexpr (OP == DW) {
@@ -1809,6 +1917,42 @@ int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
 {
     return sdrop::run<sdrop::DW>(X, dY, mask, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
+}
+
+int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,
+                 int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                 int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                 const sdrop_epilogue_t *epi)
+{
+    return sdrop::run<sdrop::FWD>(X, W, mask, Y, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, epi);
+}
+
+int sdrop_bwd_dx_ex(const void *dY, const void *W, const void *mask, void *dX,
+                    int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                    int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                    const sdrop_epilogue_t *epi)
+{
+    return sdrop::run<sdrop::DX>(dY, W, mask, dX, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, epi);
+}
+
+int sdrop_bwd_dw_ex(const void *X, const void *dY, const void *mask, void *dW,
+                    int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                    int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                    const sdrop_epilogue_t *epi)
+{
+    return sdrop::run<sdrop::DW>(X, dY, mask, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, epi);
+}
+
+int sdrop_producer(const void *H, const void *W0, const float *bias, const void *mask, void *X,
+                   int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
+                   int dtype, int out_dtype, void *stream)
+{
+    sdrop_epilogue_t epi;
+    epi.scale_mode = SDROP_SCALE_ONE;
+    epi.act = act;
+    epi.bias = bias;
+    epi.relu_mask = nullptr;
+    return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi);
 }
 
 }  // extern "C"

@@ -23,7 +23,11 @@ MASK_NNZ_OFFSET = 36
 
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
-           "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw")
+           "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw",
+           "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer")
+
+SCALE_DROPOUT, SCALE_ONE = 0, 1
+ACT_NONE, ACT_RELU, ACT_GELU_TANH = 0, 1, 2
 
 _DTYPES = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 
@@ -39,6 +43,12 @@ class MaskLayout(ctypes.Structure):
                 ("total_bytes", "off_bits", "off_row_ptr", "off_col_idx", "off_blk_row",
                  "off_col_ptr", "off_row_idx", "off_row_order", "off_col_order", "off_loc_row", "off_loc_col")] + \
                [(n, ctypes.c_int64) for n in ("MB", "KB", "words_per_row")]
+
+
+class Epilogue(ctypes.Structure):
+    """sdrop_epilogue_t of the header."""
+    _fields_ = [("scale_mode", ctypes.c_int32), ("act", ctypes.c_int32),
+                ("bias", ctypes.c_void_p), ("relu_mask", ctypes.c_void_p)]
 
 
 _lib = None
@@ -76,6 +86,12 @@ def lib():
             f = getattr(L, name)
             f.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
             f.restype = ci
+        for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex"):
+            f = getattr(L, name)
+            f.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp, ctypes.POINTER(Epilogue)]
+            f.restype = ci
+        L.sdrop_producer.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, ci, vp]
+        L.sdrop_producer.restype = ci
         _lib = L
     return _lib
 
@@ -199,7 +215,25 @@ def workspace_bytes(op, M, K, N, BM, BK, dtype, out_dtype):
     return v
 
 
-def _gemm(name, op, a, b, mask, out_shape, M, K, N, out_dtype, out, ws):
+def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype):
+    """Marshals the tail arguments into the C struct (None when there is no tail)."""
+    if scale_mode == SCALE_DROPOUT and act == ACT_NONE and bias is None and relu_mask is None:
+        return None
+    e = Epilogue()
+    e.scale_mode, e.act = int(scale_mode), int(act)
+    e.bias = e.relu_mask = None
+    if bias is not None:
+        if bias.dtype != torch.float32 or tuple(bias.shape) != (ncols,):
+            raise ValueError("bias must be fp32 with one value per output column")
+        e.bias = _dev(bias, "bias").value
+    if relu_mask is not None:
+        if relu_mask.dtype != dtype or tuple(relu_mask.shape) != tuple(out_shape):
+            raise ValueError("relu_mask must have the operands' dtype and the output's shape")
+        e.relu_mask = _dev(relu_mask, "relu_mask").value
+    return e
+
+
+def _gemm(name, op, a, b, mask, out_shape, M, K, N, out_dtype, out, ws, epi=None):
     dtype = a.dtype
     if b.dtype != dtype:
         raise ValueError("operands must have the same dtype")
@@ -215,9 +249,12 @@ def _gemm(name, op, a, b, mask, out_shape, M, K, N, out_dtype, out, ws):
         ws = torch.empty(need, dtype=torch.uint8, device=a.device)
     ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
     ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
-    rc = getattr(lib(), name)(_dev(a, "a"), _dev(b, "b"), _dev(mask.buf, "mask"), _dev(out, "out"),
-                              M, K, N, mask.BM, mask.BK, mask.p, _DTYPES[dtype], _DTYPES[out_dtype],
-                              ws_ptr, ws_bytes, _stream())
+    args = (_dev(a, "a"), _dev(b, "b"), _dev(mask.buf, "mask"), _dev(out, "out"),
+            M, K, N, mask.BM, mask.BK, mask.p, _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream())
+    if name.endswith("_ex"):
+        rc = getattr(lib(), name)(*args, ctypes.byref(epi) if epi is not None else None)
+    else:
+        rc = getattr(lib(), name)(*args)
     _check(rc, name)
     return out
 
@@ -247,3 +284,61 @@ def sdrop_bwd_dw(X, dY, mask, out_dtype=None, out=None, ws=None):
     if M2 != M or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dw")
     return _gemm("sdrop_bwd_dw", OP_BWD_DW, X, dY, mask, (K, N), M, K, N, out_dtype, out, ws)
+
+
+def sdrop_fwd_ex(X, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
+                 out_dtype=None, out=None, ws=None):
+    """eq. (1) with an element-wise tail: Y = [relu_mask > 0] act(scale (X . m') W + bias)."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_fwd_ex")
+    epi = _epilogue(scale_mode, act, bias, relu_mask, N, (M, N), X.dtype)
+    return _gemm("sdrop_fwd_ex", OP_FWD, X, W, mask, (M, N), M, K, N, out_dtype, out, ws, epi)
+
+
+def sdrop_bwd_dx_ex(dY, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
+                    out_dtype=None, out=None, ws=None):
+    """eq. (2) with an element-wise tail on the kept blocks; dropped blocks are +0."""
+    M, N = dY.shape
+    K, N2 = W.shape
+    if N2 != N or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_bwd_dx_ex")
+    epi = _epilogue(scale_mode, act, bias, relu_mask, K, (M, K), dY.dtype)
+    return _gemm("sdrop_bwd_dx_ex", OP_BWD_DX, dY, W, mask, (M, K), M, K, N, out_dtype, out, ws, epi)
+
+
+def sdrop_bwd_dw_ex(X, dY, mask, scale_mode=SCALE_DROPOUT, out_dtype=None, out=None, ws=None):
+    """eq. (3) with the scale chosen by scale_mode."""
+    M, K = X.shape
+    M2, N = dY.shape
+    if M2 != M or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_bwd_dw_ex")
+    epi = _epilogue(scale_mode, ACT_NONE, None, None, N, (K, N), X.dtype)
+    return _gemm("sdrop_bwd_dw_ex", OP_BWD_DW, X, dY, mask, (K, N), M, K, N, out_dtype, out, ws, epi)
+
+
+def sdrop_producer(H, W0, bias, mask, act=ACT_NONE, out_dtype=None, out=None):
+    """The layer before the dropout, output-sparse: X = m' . act(H W0^T + bias), W0 is [K, N0]."""
+    M, N0 = H.shape
+    K, N02 = W0.shape
+    if N02 != N0 or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_producer")
+    dtype = H.dtype
+    if W0.dtype != dtype:
+        raise ValueError("operands must have the same dtype")
+    out_dtype = dtype if out_dtype is None else out_dtype
+    if out is None:
+        out = torch.empty((M, K), dtype=out_dtype, device=H.device)
+    elif tuple(out.shape) != (M, K) or out.dtype != out_dtype:
+        raise ValueError("out has the wrong shape or dtype")
+    if dtype not in (torch.float16, torch.bfloat16) or out_dtype not in _DTYPES:
+        raise SdropError(EDTYPE, "sdrop_producer")
+    if bias is not None and (bias.dtype != torch.float32 or tuple(bias.shape) != (K,)):
+        raise ValueError("bias must be fp32 with one value per output column")
+    rc = lib().sdrop_producer(_dev(H, "H"), _dev(W0, "W0"),
+                              _dev(bias, "bias") if bias is not None else ctypes.c_void_p(0),
+                              _dev(mask.buf, "mask"), _dev(out, "out"), M, N0, K, mask.BM, mask.BK, mask.p,
+                              int(act), _DTYPES[dtype], _DTYPES[out_dtype], _stream())
+    _check(rc, "sdrop_producer")
+    return out

@@ -102,6 +102,43 @@ def test_host_side_argument_errors_return_before_any_launch():
         assert call(a1=ctypes.c_void_p(addr + 8)) == sdrop.EALIGN
 
 
+def test_tail_arguments_are_checked_on_the_host():
+    L = sdrop.lib()
+    buf = ctypes.create_string_buffer(1 << 16)
+    addr = (ctypes.addressof(buf) + 15) // 16 * 16
+    p = ctypes.c_void_p(addr)
+    null = ctypes.c_void_p(0)
+    # 64 x 64 blocks over 256 x 16384: 256 output tiles for dW, so no workspace is asked for
+    base = (p, p, p, p, 256, 16384, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)
+
+    def epi(scale_mode=sdrop.SCALE_DROPOUT, act=sdrop.ACT_NONE, bias=None, relu_mask=None):
+        e = sdrop.Epilogue()
+        e.scale_mode, e.act, e.bias, e.relu_mask = scale_mode, act, bias, relu_mask
+        return ctypes.byref(e)
+    for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex"):
+        f = getattr(L, name)
+        assert f(*base[:3], null, *base[4:], epi()) == sdrop.EINVAL          # the plain checks still apply
+        assert f(*base, epi(scale_mode=2)) == sdrop.EINVAL
+        assert f(*base, epi(act=3)) == sdrop.EINVAL
+        assert f(*base, epi(act=-1)) == sdrop.EINVAL
+    for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex"):
+        f = getattr(L, name)
+        assert f(*base, epi(bias=addr + 4)) == sdrop.EALIGN
+        assert f(*base, epi(relu_mask=addr + 8)) == sdrop.EALIGN
+    # the gradient of the weights takes a scale only
+    f = L.sdrop_bwd_dw_ex
+    assert f(*base, epi(act=sdrop.ACT_RELU)) == sdrop.EINVAL
+    assert f(*base, epi(bias=addr)) == sdrop.EINVAL
+    assert f(*base, epi(relu_mask=addr)) == sdrop.EINVAL
+    # the producer: same checks as eq. (2), plus the activation
+    g = L.sdrop_producer
+    ok = (p, p, null, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.ACT_RELU, sdrop.F16, sdrop.F16, null)
+    assert g(*ok[:11], 7, *ok[12:]) == sdrop.EINVAL
+    assert g(null, *ok[1:]) == sdrop.EINVAL
+    assert g(*ok[:5], 250, *ok[6:]) == sdrop.ESHAPE
+    assert g(*ok[:2], ctypes.c_void_p(addr + 4), *ok[3:]) == sdrop.EALIGN
+
+
 def test_workspace_size_is_a_whole_number_of_fp32_planes():
     # only dW asks for a workspace: `parts` fp32 planes of K x N, parts a power of two up to 16, none
     # when K/BK * ceil(N/256) output tiles already fill the chip (256 CUs assumed without a device)

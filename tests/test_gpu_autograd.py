@@ -5,7 +5,8 @@ import pytest
 import torch
 
 from oracle import sdrop_oracle as orc
-from paper_2411_01238_amd.autograd import sparsedrop_matmul, SparseDropLinear
+from oracle import sparse_block_oracle as sb
+from paper_2411_01238_amd.autograd import sparsedrop_matmul, SparseDropLinear, sparse_relu_block
 from paper_2411_01238_amd.workloads import make_custom
 from _util import f64, assert_close
 
@@ -46,3 +47,41 @@ def test_module_train_and_eval():
     assert_close(f64((ye - layer.bias).detach().reshape(-1, 128)), dense, "module eval = dense")
     y0.sum().backward()
     assert layer.weight.grad is not None and layer.bias.grad is not None
+
+
+def test_sparse_relu_block_matches_oracle_forward_and_gradients():
+    # Linear -> ReLU -> SparseDrop -> Linear with all six GEMMs sparse, against the chain rule
+    # written out in float64.  The GPU keeps the hidden activation in 16 bits and gates the backward
+    # on it; the oracle gates on its own float64 pre-activation: the two can differ only where that
+    # pre-activation is within rounding of zero, so those few entries are left out of the max-abs
+    # bound of dZ's consumers by comparing in the Frobenius norm only.
+    M, N0, K, N, BM, BK, p, seed, stream = 512, 256, 384, 136, 128, 64, 0.4, 11, 3
+    g = torch.Generator(device="cpu")
+    g.manual_seed(123)
+    H = (torch.randn(M, N0, generator=g)).to(torch.bfloat16)
+    W0 = (torch.randn(K, N0, generator=g) / N0 ** 0.5).to(torch.bfloat16)
+    b0 = torch.randn(K, generator=g) * 0.5
+    W = (torch.randn(K, N, generator=g) / K ** 0.5).to(torch.bfloat16)
+    dY = torch.randn(M, N, generator=g).to(torch.bfloat16)
+    print("autograd sparse relu block", flush=True)
+    h = H.cuda().requires_grad_(True)
+    w0 = W0.cuda().requires_grad_(True)
+    b = b0.cuda().requires_grad_(True)
+    w = W.cuda().requires_grad_(True)
+    y = sparse_relu_block(h, w0, b, w, p, BM, BK, seed, stream)
+    y.backward(dY.cuda())
+    torch.cuda.synchronize()
+    keep = orc.mask(M // BM, K // BK, p, seed, stream)
+    Hd, W0d, b0d, Wd, dYd = f64(H), f64(W0), f64(b0), f64(W), f64(dY)
+    _, Yref = sb.block_forward(Hd, W0d, b0d, Wd, keep, BM, BK, p, sb.ACT_RELU)
+    gref = sb.block_backward(Hd, W0d, b0d, Wd, keep, BM, BK, p, dYd)
+    # two 16-bit roundings on the way (X, then Y or a gradient): 2^-9 relative each in bf16
+    tol = dict(rel_fro=6e-3, max_abs=3e-2)
+    assert_close(f64(y.detach()), Yref, "block Y", **tol)
+    assert_close(f64(w.grad), gref["dW"], "block dW", **tol)
+    for name, got in (("dH", h.grad), ("dW0", w0.grad), ("db0", b.grad)):
+        got = f64(got)
+        assert np.all(np.isfinite(got))
+        fro = np.linalg.norm(got - gref[name]) / np.linalg.norm(gref[name])
+        assert fro <= 6e-3, "block %s: relative Frobenius error %.3e" % (name, fro)
+    assert b.grad.dtype == torch.float32
