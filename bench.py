@@ -184,6 +184,34 @@ def main():
                   "dw_X.T@dY": round(_t(lambda: torch.matmul(s0["X"].t(), s0["dY"], out=s0["dW"])), 5)}
         vendor["sum_ms"] = round(sum(vendor.values()), 5)
 
+    # ---- beyond the headline: the block Linear -> ReLU -> SparseDrop -> Linear with all six GEMMs
+    #      sparse (producer with bias + ReLU in its tail, eq. (2) with the ReLU gate, eq. (1)/(3) at
+    #      scale 1 for the producing layer's gradients); needs N0 = N, true for the square workloads ----
+    block = None
+    if not args.no_sweep and vendor is not None:
+        s0 = sets[0]
+        nnz_of(HEADLINE_P, w.mask_seed)
+        b0 = torch.zeros(w.K, dtype=torch.float32, device="cuda")
+        dz, dh, dw0 = torch.empty_like(s0["dX"]), torch.empty_like(s0["dY"]), torch.empty_like(s0["W"])
+        parts = {
+            "producer_bias_relu": lambda: sdrop.sdrop_producer(s0["dY"], s0["W"], b0, mask, act=sdrop.ACT_RELU, out=s0["X"]),
+            "fwd": lambda: sdrop.sdrop_fwd(s0["X"], s0["W"], mask, out=s0["Y"]),
+            "dx_relu_gate": lambda: sdrop.sdrop_bwd_dx_ex(s0["dY"], s0["W"], mask, relu_mask=s0["X"], out=dz),
+            "dw": lambda: sdrop.sdrop_bwd_dw(s0["X"], s0["dY"], mask, out=s0["dW"], ws=ws),
+            "dh_fwd_scale1": lambda: sdrop.sdrop_fwd_ex(dz, s0["W"], mask, scale_mode=sdrop.SCALE_ONE, out=dh),
+            "dw0_dw_scale1": lambda: sdrop.sdrop_bwd_dw_ex(dz, s0["dY"], mask, scale_mode=sdrop.SCALE_ONE, out=dw0, ws=ws),
+        }
+        def whole():
+            for f in parts.values():
+                f()
+        block = {k: round(_t(f), 5) for k, f in parts.items()}
+        block["plain_dx"] = round(_t(lambda: sdrop.sdrop_bwd_dx(s0["dY"], s0["W"], mask, out=dz)), 5)
+        t_block = _t(whole)
+        block["six_gemms_ms"] = round(t_block, 5)
+        block["eff_tflops"] = round(6 * 2.0 * nnz * w.BM * w.BK * w.N / (t_block * 1e-3) / 1e12, 3)
+        # the same block with a dense producing layer (vendor GEMMs, element-wise passes not counted)
+        block["three_sparse_plus_three_vendor_dense_ms"] = round(ms_warm + vendor["sum_ms"], 5)
+
     # ---- roofline of the dominant kernel (largest average duration among the three GEMMs) ----
     dom = max(("fwd", "dx", "dw"), key=lambda n: kern[n])
     flops_launch = 2.0 * nnz * w.BM * w.BK * w.N       # algorithmic flops of one GEMM launch
@@ -208,6 +236,7 @@ def main():
         "sweep": sweep,
         "linearity": linearity,
         "vendor_dense_gemm_ms_single_set": vendor,
+        "sparse_relu_block_ms_single_set": block,
         "roofline": roofline,
     }
 

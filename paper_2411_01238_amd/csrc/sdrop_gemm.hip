@@ -162,28 +162,27 @@ struct Tail {
     const char *aux;
     const char *c0;     // the output's origin
     int act;
-    bool on;
 };
 __device__ __forceinline__ Tail make_tail(const GemmParams &P)
 {
     Tail t;
     t.bias = P.bias; t.aux = P.aux; t.c0 = P.C; t.act = P.act;
-    t.on = P.bias != nullptr || P.aux != nullptr || P.act != 0;
     return t;
 }
 // v: four consecutive columns of one output row, starting at global column `col`; `elem` is the
-// index of v[0] in the output matrix (row * columns + col).  col is a multiple of 4.
-template <class T>
-__device__ __forceinline__ void tail4(const Tail &tl, float (&v)[4], int64_t col, int64_t elem)
+// index of v[0] in the output matrix (row * columns + col).  col is a multiple of 4.  The gate is
+// applied here only with AUX; the persistent kernels gate their 16-bit outputs after rounding
+// instead, 16 bytes at a time (gate16), which selects the same values.
+// The bias does not change while the kernel runs: read through the constant address space, its
+// loads may be moved and merged across the output stores.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(4))) f32x4 *const_f4;
+__device__ __forceinline__ void act4(int act, float (&v)[4])
 {
-    if (tl.bias) {
-        const float4 b = *reinterpret_cast<const float4 *>(tl.bias + col);
-        v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
-    }
-    if (tl.act == SDROP_ACT_RELU) {
+    if (act == SDROP_ACT_RELU) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = v[e] < 0.f ? 0.f : v[e];
-    } else if (tl.act == SDROP_ACT_GELU_TANH) {
+    } else if (act == SDROP_ACT_GELU_TANH) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float x = v[e];
@@ -191,13 +190,36 @@ __device__ __forceinline__ void tail4(const Tail &tl, float (&v)[4], int64_t col
             v[e] = x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));
         }
     }
-    if (tl.aux) {
-        using E = typename In<T>::out16;
-        typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
-        const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = static_cast<float>(x[e]) > 0.f ? v[e] : 0.f;
+}
+template <class T, bool AUX>
+__device__ __forceinline__ void tail4(const Tail &tl, float (&v)[4], int64_t col, int64_t elem)
+{
+    if (tl.bias) {
+        const f32x4 b = *(const_f4)(uintptr_t)(tl.bias + col);
+        v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
     }
+    act4(tl.act, v);
+    if constexpr (AUX) {
+        if (tl.aux) {
+            using E = typename In<T>::out16;
+            typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
+            const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = static_cast<float>(x[e]) > 0.f ? v[e] : 0.f;
+        }
+    }
+}
+// Eight 16-bit outputs and the eight gate values at the same place of the gate matrix.
+template <class T>
+__device__ __forceinline__ uint4 gate16(uint4 out, uint4 gate)
+{
+    using E = typename In<T>::out16;
+    typedef __attribute__((__vector_size__(8 * sizeof(E)))) E e8;
+    e8 o = __builtin_bit_cast(e8, out);
+    const e8 g = __builtin_bit_cast(e8, gate);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = static_cast<float>(g[e]) > 0.f ? o[e] : static_cast<E>(0.f);
+    return __builtin_bit_cast(uint4, o);
 }
 
 // Slot swizzle of an LDS operand row: a 3-bit value XORed into the chunk index.
@@ -437,7 +459,7 @@ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 
 
 // SPEC: the workgroup has NW more wavefronts (one more per SIMD) that do nothing but issue the
 // direct loads, so that a load instruction held up by the memory pipeline never holds up MFMAs.
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED, bool SPEC>
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED, bool SPEC, bool TAIL>
 __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(GemmParams P)
 {
     constexpr int NW = WM * WN, NT = NW * 64 * (SPEC ? 2 : 1);   // computing wavefronts; threads
@@ -877,17 +899,17 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         char *reg = smem + wave * REGION;
         const float scale = P.scale;
         const Tail tl = make_tail(P);
+        {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int row = mi * 32 + (lane & 31), col = ni * 32 + q * 8 + (lane >> 5) * 4;
-                    float v[4] = {acc[mi][ni][4 * q] * scale, acc[mi][ni][4 * q + 1] * scale,
-                                  acc[mi][ni][4 * q + 2] * scale, acc[mi][ni][4 * q + 3] * scale};
-                    if constexpr (OP != DW) {
-                        if (tl.on) {
+                    for (int q = 0; q < 4; ++q) {
+                        const int row = mi * 32 + (lane & 31), col = ni * 32 + q * 8 + (lane >> 5) * 4;
+                        float v[4] = {acc[mi][ni][4 * q] * scale, acc[mi][ni][4 * q + 1] * scale,
+                                      acc[mi][ni][4 * q + 2] * scale, acc[mi][ni][4 * q + 3] * scale};
+                        if constexpr (TAIL && OP != DW) {
                             const int cl = wn * WTN + col;          // column within the tile
                             bool ok;
                             int64_t gcol;
@@ -902,18 +924,18 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
                                 ok = cl < c_lim;                    // c_lim is a multiple of 8
                                 gcol = out_col0[0] + cl;
                             }
-                            if (ok) tail4<T>(tl, v, gcol, (out_row0 + wm * WTM + row) * (ldc / ESZ) + gcol);
+                            if (ok) tail4<T, true>(tl, v, gcol, (out_row0 + wm * WTM + row) * (ldc / ESZ) + gcol);
+                        }
+                        char *dst = reg + row * RS + col * ESZ;
+                        if constexpr (ESZ == 4) {
+                            *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                        } else {
+                            typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
+                            const out4 o = {static_cast<OutT>(v[0]), static_cast<OutT>(v[1]), static_cast<OutT>(v[2]), static_cast<OutT>(v[3])};
+                            *reinterpret_cast<out4 *>(dst) = o;
                         }
                     }
-                    char *dst = reg + row * RS + col * ESZ;
-                    if constexpr (ESZ == 4) {
-                        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-                        typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
-                        const out4 o = {static_cast<OutT>(v[0]), static_cast<OutT>(v[1]), static_cast<OutT>(v[2]), static_cast<OutT>(v[3])};
-                        *reinterpret_cast<out4 *>(dst) = o;
-                    }
-                }
+        }
         constexpr int CH = ROWB / 16, RPI = 64 / CH;         // 16-byte pieces per row; rows per store instruction
         static_assert(CH <= 64 && 64 % CH == 0 && WTM % RPI == 0, "sub-tile rows must tile a wavefront");
 #pragma unroll
@@ -1013,12 +1035,45 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
     // rows then spread over all banks, and a 16-byte read finds its two halves in one 16-byte
     // piece, exchanged when r is odd.  dst(mi, nj) is the address of row 0 of the 32 x 128-byte
     // piece (mi, nj) of the wavefront's sub-tile, or null if that piece is not to be written.
-    // With a tail (tl.on), dst also reports the global column of the piece's first column.
-    template <class F> __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
+    // With a tail, dst also reports the global column of the piece's first column.
+    //
+    // The tail's operands (bias values, and for 16-bit outputs the gate values, which lie where
+    // the outputs go) are requested by tail_prefetch, called with the same dst before the tile's
+    // last slice: their latency then hides behind that slice's MFMAs instead of adding to the
+    // epilogue, which nothing overlaps.
+    uint4 gate_r[MI * NJ][4];
+    f32x4 bias_r[NJ][NIP * 4];
+    template <class F> __device__ __forceinline__ void tail_prefetch(int64_t ldc, const Tail &tl, F &&dst)
+    {
+        const int lane = threadIdx.x & 63;
+        const int whalf = lane >> 5, rrow = lane >> 3, rch = lane & 7;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int nj = 0; nj < NJ; ++nj) {
+                int64_t gcol0 = 0;
+                char *const out = dst(mi, nj, gcol0);
+                if (!out) continue;                        // uniform
+                if (mi == 0 && tl.bias) {
+#pragma unroll
+                    for (int i = 0; i < NIP * 4; ++i)
+                        bias_r[nj][i] = *(const_f4)(uintptr_t)(tl.bias + gcol0 + (i >> 2) * 32 + 8 * (i & 3) + 4 * whalf);
+                }
+                if constexpr (ESZ == 2) {
+                    if (tl.aux) {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it)
+                            gate_r[mi * NJ + nj][it] = *reinterpret_cast<const uint4 *>(tl.aux + (out - tl.c0) + (int64_t)(it * 8 + rrow) * ldc + rch * 16);
+                    }
+                }
+            }
+    }
+    template <bool TAIL, class F> __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
     {
         const int lane = threadIdx.x & 63;
         const int wrow = lane & 31, whalf = lane >> 5;
         const int rrow = lane >> 3, rch = lane & 7;
+        const bool gate_rows = TAIL && ESZ == 2 && tl.aux != nullptr;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -1032,9 +1087,24 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                     for (int q = 0; q < 4; ++q) {
                         const f32x16 &a = acc[mi][nj * NIP + nl];
                         float v[4] = {a[4 * q] * scale, a[4 * q + 1] * scale, a[4 * q + 2] * scale, a[4 * q + 3] * scale};
-                        if (tl.on) {
-                            const int c = nl * 32 + 8 * q + 4 * whalf;       // column within the piece
-                            tail4<T>(tl, v, gcol0 + c, (out - tl.c0) / ESZ + wrow * (ldc / ESZ) + c);
+                        if constexpr (TAIL) {
+                            if (tl.bias) {
+                                const f32x4 bv = bias_r[nj][nl * 4 + q];
+                                v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
+                            }
+                            act4(tl.act, v);
+                            if constexpr (ESZ == 4) {
+                                if (tl.aux) {
+                                    // fp32 outputs: the gate matrix has 16-bit elements, read in the accumulator's layout
+                                    using E = typename In<T>::out16;
+                                    typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
+                                    const int c = 8 * q + 4 * whalf;             // column within the piece
+                                    const int64_t elem = (out - tl.c0) / ESZ + wrow * (ldc / ESZ) + c;
+                                    const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) v[e] = static_cast<float>(x[e]) > 0.f ? v[e] : 0.f;
+                                }
+                            }
                         }
                         const float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
                         if constexpr (ESZ == 4) {
@@ -1057,6 +1127,9 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                     } else {
                         const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
                         v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
+                        if constexpr (TAIL) {
+                            if (gate_rows) v = gate16<T>(v, gate_r[mi * NJ + nj][it]);
+                        }
                     }
                     store_out(out + (int64_t)row * ldc + rch * 16, v);
                 }
@@ -1084,7 +1157,7 @@ constexpr int waitcnt_vm_only(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (
 // part of slice g+1 has landed; the loaders issue slice g+2 (into the stage of slice g-1) after
 // barrier g-1.  One more barrier, before the first slice, publishes slice 0.  Both roles derive
 // the number of slices from the same mask lists, so they execute the same number of barriers.
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN>
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
 {
     static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
@@ -1280,24 +1353,24 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
             __builtin_amdgcn_s_barrier();                     // slice 0 is in place
             cw.first(stage_ptr(0));
         }
+        const int line = t % per_line;
+        const int nt = line / P.splits, part = line % P.splits;
+        char *c_tile;
+        if constexpr (OP == FWD) c_tile = P.C + (int64_t)ord * P.BM * ldc + (int64_t)nt * TN * ESZ;
+        else c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)ord * P.BK * ldc + (int64_t)nt * TN * ESZ;
+        c_tile += (int64_t)(wm * WTM) * ldc + (int64_t)(wn * WTN) * ESZ;
+        auto dst = [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
+            gcol0 = (int64_t)nt * TN + wn * WTN + nj * (128 / ESZ);
+            return c_tile + (int64_t)(mi * 32) * ldc + nj * 128;
+        };
         for (int s = 0; s < nsteps; ++s) {
             cw.slice(stage_ptr(st0), stage_ptr(st1));
             const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
             if (s == 0) GEMM_TICKW(k * 4 + 1);
         }
+        if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
         GEMM_TICKW(k * 4 + 2);
-        {
-            const int line = t % per_line;
-            const int nt = line / P.splits, part = line % P.splits;
-            char *c_tile;
-            if constexpr (OP == FWD) c_tile = P.C + (int64_t)ord * P.BM * ldc + (int64_t)nt * TN * ESZ;
-            else c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)ord * P.BK * ldc + (int64_t)nt * TN * ESZ;
-            c_tile += (int64_t)(wm * WTM) * ldc + (int64_t)(wn * WTN) * ESZ;
-            cw.store(reg, scale, ldc, tl, [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
-                gcol0 = (int64_t)nt * TN + wn * WTN + nj * (128 / ESZ);
-                return c_tile + (int64_t)(mi * 32) * ldc + nj * 128;
-            });
-        }
+        cw.template store<TAIL>(reg, scale, ldc, tl, dst);
         GEMM_TICKW(k * 4 + 3);
         cur = n1; n1 = n2; n2 = n3;
     }
@@ -1324,7 +1397,7 @@ __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 // Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; the computing
 // wavefronts test a batch of them per tile (bits fetched before the tile's slices, used after
 // its stores) and finish what is left after their last tile.
-template <class T, class OutT, int TM, int TN, int WM, int WN>
+template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
 {
     constexpr int NW = WM * WN;
@@ -1546,12 +1619,8 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
                 __builtin_amdgcn_s_barrier();           // slice 0 is in place
                 cw.first(stage_ptr(0));
             }
-            for (int s = 0; s < nsteps; ++s) {
-                cw.slice(stage_ptr(st0), stage_ptr(st1));
-                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
-            }
             char *const c_rows = P.C + ((int64_t)row * P.BM + wm * WTM) * ldc;
-            cw.store(reg, scale, ldc, tl, [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
+            auto dst = [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
                 const int col_t = wn * WTN + nj * (128 / ESZ);         // first column of the piece, in the tile
                 const int g = col_t >> 6;
                 if (g >= chunks_valid) return nullptr;
@@ -1559,7 +1628,13 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
                 const int64_t col0 = (int64_t)col * P.BK + (g & cmask) * 64 + (col_t & 63);
                 gcol0 = col0;
                 return c_rows + (int64_t)(mi * 32) * ldc + col0 * ESZ;
-            });
+            };
+            for (int s = 0; s < nsteps; ++s) {
+                cw.slice(stage_ptr(st0), stage_ptr(st1));
+                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+            }
+            if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
+            cw.template store<TAIL>(reg, scale, ldc, tl, dst);
             if (zc > 0) { fill_batch(z_done, zc, zword, bitpos); z_done += zc; }
             a += nb;
         }
@@ -1577,13 +1652,29 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
 // WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
 int cu_count();
 
+// Kernels with the element-wise tail are separate instantiations, so that eq. (1)-(3) proper run
+// exactly the code they would without it.
+inline bool has_tail(const GemmParams &P) { return P.bias != nullptr || P.aux != nullptr || P.act != 0; }
+
+template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
+int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok);
+
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
 int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok = true)
 {
+    if constexpr (OP != DW) {
+        if (has_tail(P)) return launch_t<true, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
+    }
+    return launch_t<false, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
+}
+
+template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
+int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok)
+{
     constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
     constexpr bool SPEC = TM >= 128;     // loader wavefronts for the one-workgroup-per-CU tiles
-    auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false, SPEC>;
-    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WMR, WNR, true, false>;
+    auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false, SPEC, TAIL>;
+    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WMR, WNR, true, false, TAIL>;
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_full),
@@ -1599,7 +1690,7 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool 
         if (!ragged && persistent_ok) {
             // persistent form: three operand stages plus 4 KiB of output staging per computing wavefront
             constexpr int P_LDS = 3 * (TM + TN) * TK * 2 + WM * WN * 4096;
-            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN>;
+            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TAIL>;
             static int pers_ok = -1;    // per instantiation: does the device grant that much LDS?
             if (pers_ok < 0) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_pers),
@@ -1627,11 +1718,21 @@ int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool 
 }
 
 // Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
+template <class T, class OutT, int TN, bool TAIL>
+int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
+
 template <class T, class OutT, int TN>
 int launch_dx_persistent(const GemmParams &P, hipStream_t stream)
 {
+    if (has_tail(P)) return launch_dx_persistent_t<T, OutT, TN, true>(P, stream);
+    return launch_dx_persistent_t<T, OutT, TN, false>(P, stream);
+}
+
+template <class T, class OutT, int TN, bool TAIL>
+int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
+{
     constexpr int P_LDS = 3 * (128 + TN) * TK * 2 + 4 * 4096;
-    auto k = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2>;
+    auto k = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2, TAIL>;
     static int ok = -1;     // per instantiation: does the device grant that much LDS?
     if (ok < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);

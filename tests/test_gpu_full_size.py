@@ -11,6 +11,7 @@ import pytest
 import torch
 
 from oracle import sdrop_oracle as orc
+from oracle import sparse_block_oracle as sb
 from paper_2411_01238_amd import sdrop
 from paper_2411_01238_amd.workloads import WORKLOADS, make_inputs
 from _util import f64, assert_close, assert_bf16_rounding_of
@@ -121,3 +122,44 @@ def test_mlp_four_layers_chained():
         assert_close(gather(grads[l], r, c), orc.bwd_dx_at(dYd, Wd, keeps[l], w.BM, w.BK, p, r, c), "chain layer %d dX" % l)
         r, c = _positions(rng, w.K, w.N, 48, w.BK, 256)
         assert_close(gather(dWs[l], r, c), orc.bwd_dw_at(Xd, dYd, keeps[l], w.BM, w.BK, p, r, c), "chain layer %d dW" % l)
+
+
+def test_sparse_block_operators_full_size_sampled():
+    # the producing layer with bias + ReLU, and eq. (2) with the ReLU gate, at 4096^3: the oracle's
+    # sampled eq. (2) values (s = 1 for the producer) go through its own tail, position by position
+    w = WORKLOADS["square4096"]
+    p = 0.5
+    print("full-size case sparse block operators", flush=True)
+    X, W, dY = make_inputs(w)
+    m = sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, w.mask_seed, 0)
+    keep = orc.mask(w.MB, w.KB, p, w.mask_seed, 0)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(4242)
+    b0 = torch.randn(w.K, generator=g, dtype=torch.float32) * 8.0
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    Xd, Wd, dYd, b0d = f64(X), f64(W), f64(dY), f64(b0)
+    rng = np.random.default_rng(77)
+    r, c = _positions(rng, w.M, w.K, 400, w.BM, w.BK)
+    kept = keep[r // w.BM, c // w.BK].astype(bool)
+
+    def gather(t):
+        return t[torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()].cpu().to(torch.float64).numpy()
+
+    for act in (sdrop.ACT_RELU, sdrop.ACT_GELU_TANH):
+        z = orc.bwd_dx_at(dYd, Wd, keep, w.BM, w.BK, 0.0, r, c)          # H W0^T on kept blocks, s = 1
+        ref = np.where(kept, sb.act(z + b0d[c], act), 0.0)
+        o32 = sdrop.sdrop_producer(dYg, Wg, b0.cuda(), m, act=act, out_dtype=torch.float32)
+        o16 = sdrop.sdrop_producer(dYg, Wg, b0.cuda(), m, act=act)
+        torch.cuda.synchronize()
+        assert_close(gather(o32), ref, "producer act %d fp32 out (sampled)" % act)
+        assert torch.equal(o16, o32.to(torch.bfloat16))
+        assert_bf16_rounding_of(gather(o16), ref, "producer act %d bf16 out (sampled)" % act)
+        nz = (o16.view(w.MB, w.BM, w.KB, w.BK) != 0).any(dim=3).any(dim=1)
+        assert torch.equal(nz, torch.from_numpy(keep.astype(bool)).cuda())
+    ref = np.where(kept & (Xd[r, c] > 0.0), orc.bwd_dx_at(dYd, Wd, keep, w.BM, w.BK, p, r, c), 0.0)
+    o32 = sdrop.sdrop_bwd_dx_ex(dYg, Wg, m, relu_mask=Xg, out_dtype=torch.float32)
+    plain = sdrop.sdrop_bwd_dx(dYg, Wg, m, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_close(gather(o32), ref, "gated dX fp32 out (sampled)")
+    # whole-output property: the gated result is the plain one where the gate is open, +0 elsewhere
+    assert torch.equal(o32, torch.where(Xg > 0, plain, torch.zeros_like(plain)))
