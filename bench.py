@@ -22,7 +22,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_DENSE_TFLOPS = 2500.0     # MI355X published dense bf16/fp16 MFMA peak
 # Bytes per launch that crossed L2 -> fabric, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a known 1 GiB
 # copy (profiles/bench_square4096_p0.5_hbm_traffic.md), workload square4096 at p = 0.5
-MEASURED_TRAFFIC_BYTES = {"square4096": {"fwd": 235.7e6, "dx": 316.9e6, "dw": 238.6e6}}
+MEASURED_TRAFFIC_BYTES = {"square4096": {"fwd": 235.7e6, "bwd": 555.5e6}}
 HEADLINE_P = 0.5
 
 
@@ -83,12 +83,10 @@ def main():
         sdrop.sdrop_fwd(s["X"], s["W"], mask, out=s["Y"])
         if events is not None:
             events[2].record()
-        sdrop.sdrop_bwd_dx(s["dY"], s["W"], mask, out=s["dX"])
+        # eq. (2) and eq. (3) in one call: one launch where the shapes allow it, else two
+        sdrop.sdrop_bwd(s["dY"], s["W"], s["X"], mask, out_dx=s["dX"], out_dw=s["dW"], ws=ws)
         if events is not None:
             events[3].record()
-        sdrop.sdrop_bwd_dw(s["X"], s["dY"], mask, out=s["dW"], ws=ws)
-        if events is not None:
-            events[4].record()
 
     def nnz_of(p, seed):
         sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, seed, 0, out=mask)
@@ -106,11 +104,11 @@ def main():
         return (time.perf_counter() - t0) / steps * 1e3     # ms per step
 
     def per_kernel(p, steps, n_sets, seed=w.mask_seed):
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
         for i in range(steps):
             step(sets[i % n_sets], p, seed, evs[i])
         torch.cuda.synchronize()
-        names = ("mask", "fwd", "dx", "dw")
+        names = ("mask", "fwd", "bwd")
         return {n: sum(e[k].elapsed_time(e[k + 1]) for e in evs) / steps for k, n in enumerate(names)}
 
     flops_per_block = 3 * 2.0 * w.BM * w.BK * w.N
@@ -133,6 +131,21 @@ def main():
     value = nnz * flops_per_block / (ms * 1e-3) / 1e12
     ms_warm = timed(HEADLINE_P, args.steps, args.warmup, 1)
     kern = per_kernel(HEADLINE_P, args.steps, 3)
+
+    # for reference: eq. (2) and eq. (3) launched on their own (the same kernels, two launches)
+    def separate(steps, n_sets):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        for i in range(steps):
+            s = sets[i % n_sets]
+            evs[i][0].record()
+            sdrop.sdrop_bwd_dx(s["dY"], s["W"], mask, out=s["dX"])
+            evs[i][1].record()
+            sdrop.sdrop_bwd_dw(s["X"], s["dY"], mask, out=s["dW"], ws=ws)
+            evs[i][2].record()
+        torch.cuda.synchronize()
+        return {n: sum(e[k].elapsed_time(e[k + 1]) for e in evs) / steps for k, n in enumerate(("dx", "dw"))}
+    nnz_of(HEADLINE_P, w.mask_seed)
+    kern_sep = separate(args.steps, 3)
 
     # ---- sweep over p (fewer steps each), speed-up against the library's own dense run ----
     sweep = {}
@@ -213,21 +226,23 @@ def main():
         block["three_sparse_plus_three_vendor_dense_ms"] = round(ms_warm + vendor["sum_ms"], 5)
 
     # ---- roofline of the dominant kernel (largest average duration among the three GEMMs) ----
-    dom = max(("fwd", "dx", "dw"), key=lambda n: kern[n])
-    flops_launch = 2.0 * nnz * w.BM * w.BK * w.N       # algorithmic flops of one GEMM launch
+    dom = max(("fwd", "bwd"), key=lambda n: kern[n])
+    flops_gemm = 2.0 * nnz * w.BM * w.BK * w.N         # algorithmic flops of one of the three products
+    flops_launch = flops_gemm * (2 if dom == "bwd" else 1)     # the backward launch holds eq. (2) and eq. (3)
     achieved = flops_launch / (kern[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "sdrop_" + {"fwd": "fwd", "dx": "bwd_dx", "dw": "bwd_dw"}[dom],
+    roofline = {"bound": "mfma", "kernel": {"fwd": "sdrop_fwd", "bwd": "sdrop_bwd (eq. 2 and eq. 3)"}[dom],
                 "achieved": round(achieved, 3), "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_DENSE_TFLOPS, 5),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
-                "avg_launch_ms": {k: round(v, 5) for k, v in kern.items()}}
+                "avg_launch_ms": {k: round(v, 5) for k, v in kern.items()},
+                "separate_launch_ms": {k: round(v, 5) for k, v in kern_sep.items()}}
 
     out = {
         "metric": "effective TFLOP/s fwd+bwd (kept blocks) & speedup vs dense GEMM at p in {0.1,0.3,0.5}",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "%s: M=K=N=%d %s, block %dx%d, p=%.1f (mask + fwd + dX + dW per step), "
+        "config": {"workload": "%s: M=K=N=%d %s, block %dx%d, p=%.1f (mask + fwd + dX + dW per step; dX and dW by one sdrop_bwd call), "
                                "%s outputs, 3 rotating buffer sets" % (w.name, w.M, w.dtype, w.BM, w.BK, HEADLINE_P, w.dtype),
                    "kept_blocks": nnz, "blocks": w.MB * w.KB},
         "frac_of_bf16_peak": round(value / PEAK_BF16_DENSE_TFLOPS, 5),

@@ -67,9 +67,11 @@ enum { SDROP_OP_FWD = 0, SDROP_OP_BWD_DX = 1, SDROP_OP_BWD_DW = 2 };
  *   SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU  sdrop_bwd_dx with tiles of several kept blocks uses its
  *       persistent kernel when it expects at least this many tiles per CU (default 16; 0 = whenever
  *       the shape allows it)
- * Returns SDROP_EINVAL for an unknown knob or a negative value.
+ *   SDROP_TUNE_BWD_FUSED  1 (default): sdrop_bwd computes both gradients in one launch where the
+ *       shapes allow it; 0: always as the two separate launches
+ * Returns SDROP_EINVAL for an unknown knob or a value outside its range.
  */
-enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0 };
+enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0, SDROP_TUNE_BWD_FUSED = 1 };
 int sdrop_set_tuning(int knob, int value);
 
 /* Text for an error code (static storage). */
@@ -207,6 +209,21 @@ int sdrop_bwd_dx(const void *dY, const void *W, const void *mask, void *dX,
 int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
                  int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * eq. (2) and eq. (3) in one call: both gradients of the layer, which share dY and the mask and
+ * do not depend on each other.  Results are bit-identical to sdrop_bwd_dx followed by
+ * sdrop_bwd_dw with the same arguments.  With 128 x 128 blocks and N a multiple of 256 (and
+ * where sdrop_bwd_dx would use its persistent kernel) one launch holds the workgroups of both
+ * products: those of eq. (3) start on the CUs as those of eq. (2) leave them, with no launch
+ * boundary and no idle tail in between; otherwise the two are launched in turn.
+ *   dY[M,N], W[K,N], X[M,K] inputs;  dX[M,K], dW[K,N] outputs, both of type `out_dtype`
+ *   ws, ws_bytes  as for sdrop_bwd_dw (sdrop_workspace_bytes(SDROP_OP_BWD_DW, ...))
+ * All arguments are checked before anything is enqueued.
+ */
+int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,
+              int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+              int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Sparse operators for the layers around the dropout (Section 4.3, closing remark: the layer

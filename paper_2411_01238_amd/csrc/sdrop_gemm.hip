@@ -1157,8 +1157,10 @@ constexpr int waitcnt_vm_only(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (
 // part of slice g+1 has landed; the loaders issue slice g+2 (into the stage of slice g-1) after
 // barrier g-1.  One more barrier, before the first slice, publishes slice 0.  Both roles derive
 // the number of slices from the same mask lists, so they execute the same number of barriers.
+// (The body is a device function of the workgroup's index w among G, so that one launch can hold
+// the workgroups of two operations; see bwd_fused_kernel.)
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
-__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
+__device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const int G, const int w)
 {
     static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
     constexpr int NW = WM * WN;
@@ -1181,7 +1183,6 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
     const bool loader = wave_all >= NW;
     const int wave = loader ? wave_all - NW : wave_all;
     const int wm = wave / WN, wn = wave % WN;
-    const int G = gridDim.x, w = blockIdx.x;
     const int total = P.total_tiles;
     const int BLK = (OP == FWD) ? P.BK : P.BM;            // extent of a mask block along the reduction
     const int sub_shift = (BLK == 128), sub_mask = (1 << sub_shift) - 1;
@@ -1376,6 +1377,12 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmPara
     }
 }
 
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
+{
+    gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
+}
+
 // a[i] for a uniform index i in 0..3, as selects (keeps everything in scalar registers)
 __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 {
@@ -1398,7 +1405,7 @@ __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 // wavefronts test a batch of them per tile (bits fetched before the tile's slices, used after
 // its stores) and finish what is left after their last tile.
 template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
-__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
+__device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, const int G, const int w)
 {
     constexpr int NW = WM * WN;
     static_assert(NW == 4 && TM == 128, "one computing and one loading wavefront per SIMD, 128-row tiles");
@@ -1421,7 +1428,6 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
     const bool loader = wave_all >= NW;
     const int wave = loader ? wave_all - NW : wave_all;
     const int wm = wave / WN, wn = wave % WN;
-    const int G = gridDim.x, w = blockIdx.x;
     const int GB = TN / P.BK;                          // kept blocks per group: 1, 2 or 4
     const int cshift = (P.BK == 128), cmask = (1 << cshift) - 1;   // 64-column chunks per block
     const int nnz = H->nnz;
@@ -1649,6 +1655,27 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
     }
 }
 
+template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
+{
+    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
+}
+
+// Both gradients of the layer in one launch (eq. 2 and eq. 3 share dY and the mask and do not
+// depend on each other): workgroups [0, g_dx) are the persistent dX kernel, the rest the persistent
+// dW kernel.  One workgroup fits a CU, so the dW workgroups start one by one on the CUs that the dX
+// workgroups leave: no launch boundary (about 5 us of idle chip between dependent launches) and no
+// idle tail between the two.  The dX workgroups come first, so dX workgroup w is workgroup w of
+// the launch and runs on XCD w % 8, which its schedule assumes; the dW schedule assumes nothing.
+template <class T, class OutDX, class OutDW, int TN_DX>
+__global__ __launch_bounds__(512) void bwd_fused_kernel(GemmParams Pdx, GemmParams Pdw, int g_dx)
+{
+    if ((int)blockIdx.x < g_dx)
+        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, false>(Pdx, g_dx, (int)blockIdx.x);
+    else
+        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
+}
+
 // WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
 int cu_count();
 
@@ -1814,6 +1841,33 @@ int cu_count()
 // groups of kept blocks per CU from which dX tiles of several blocks use the persistent kernel
 int g_dx_persistent_groups_per_cu = 16;
 
+// dX: width of the tiles, and whether the persistent kernel computes them.
+// Every kept block costs the same, so the launch runs in ceil(tiles / CUs) rounds of
+// equal tiles.  A 256-wide tile moves a quarter less data per flop than two 128-wide
+// ones (a 128-wide tile was measured at 0.6 of the time of a wide one); take whichever shape is expected
+// to finish first for the expected number of kept blocks, (1-p) MB KB.
+// The persistent kernel deals out groups of TN/BK list entries and cuts a group where the block
+// row changes inside it; with few groups per workgroup one such extra tile is a whole round
+// (4096^3, a tenth dropped: 147 us against 111 us), so it is used for single-block tiles
+// (no cuts) and where a workgroup gets many groups (65536 x 4096 x 1024: 485 against 515 us).
+struct DxPlan { int TN; bool persistent; };
+DxPlan dx_plan(const GemmParams &P)
+{
+    const double kept = (1.0 - P.p) * (double)P.MB * (double)P.KB;
+    const int ncu = cu_count();
+    auto rounds = [&](int tn) {
+        const int g = tn / P.BK;
+        // groups of g kept blocks per block row; a random row leaves (g-1)/2g of a group unfilled
+        const double tiles = kept / g + (P.p > 0.0 ? P.MB * (g - 1) / (2.0 * g) : 0.0);
+        return (double)((int64_t)((tiles + ncu - 1) / ncu));
+    };
+    DxPlan plan;
+    plan.TN = (rounds(128) * 0.6 < rounds(256)) ? 128 : 256;
+    const int G_ = plan.TN / P.BK;
+    plan.persistent = P.BM == 128 && P.N % TK == 0 && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu);
+    return plan;
+}
+
 // Tile shapes: the tile edge that lies along the mask must equal the mask's block
 // (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
 // 256/BK kept blocks of one block row into a 256-wide tile.
@@ -1838,29 +1892,13 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         const double slices = (1.0 - P.p) * P.MB / P.splits * (P.BM / 64);
         return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream, slices >= 16.0);
     } else {
-        // Every kept block costs the same, so the launch runs in ceil(tiles / CUs) rounds of
-        // equal tiles.  A 256-wide tile moves a quarter less data per flop than two 128-wide
-        // ones (a 128-wide tile was measured at 0.6 of the time of a wide one); take whichever shape is expected
-        // to finish first for the expected number of kept blocks, (1-p) MB KB.
-        const double kept = (1.0 - P.p) * (double)P.MB * (double)P.KB;
-        const int ncu = cu_count();
-        auto rounds = [&](int tn) {
-            const int g = tn / P.BK;
-            // groups of g kept blocks per block row; a random row leaves (g-1)/2g of a group unfilled
-            const double tiles = kept / g + (P.p > 0.0 ? P.MB * (g - 1) / (2.0 * g) : 0.0);
-            return (double)((int64_t)((tiles + ncu - 1) / ncu));
-        };
-        const int TNsel = (rounds(128) * 0.6 < rounds(256)) ? 128 : 256;
-        const int G_ = TNsel / P.BK;
+        const DxPlan plan = dx_plan(P);
+        const int TNsel = plan.TN, G_ = TNsel / P.BK;
         P.n_tiles = (P.KB + G_ - 1) / G_;
         // one kept block per tile: a workgroup per block position, rounded up to whole sets of 8 XCDs
         const int grid = G_ == 1 ? (P.MB * P.KB + 7) / 8 * 8 : P.MB * P.n_tiles;
         const bool ragged = P.N % TK != 0;
-        // The persistent kernel deals out groups of G_ list entries and cuts a group where the block
-        // row changes inside it; with few groups per workgroup one such extra tile is a whole round
-        // (4096^3, a tenth dropped: 147 us against 111 us), so it is used for single-block tiles
-        // (no cuts) and where a workgroup gets many groups (65536 x 4096 x 1024: 485 against 515 us).
-        if (P.BM == 128 && !ragged && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu)) {
+        if (plan.persistent) {
             const int rc = TNsel == 256 ? launch_dx_persistent<T, OutT, 256>(P, stream) : launch_dx_persistent<T, OutT, 128>(P, stream);
             if (rc != -1) return rc;      // -1: the device does not grant the LDS; use the per-tile kernels
         }
@@ -1871,6 +1909,46 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         if (P.BM == 128) return launch<DX, T, OutT, 128, 128, 2, 2>(P, grid, ragged, stream);
         return launch<DX, T, OutT, 64, 128, 1, 4>(P, grid, ragged, stream);
     }
+}
+
+// 32-bit tile numbers must do (no operand that fits the device's memory comes near this)
+bool tile_count_ok(int64_t N, const sdrop_mask_layout_t &L)
+{
+    const int64_t n_tiles = (N + 255) / 256, lines = L.MB > L.KB ? L.MB : L.KB;
+    return lines * n_tiles * 16 <= INT32_MAX;
+}
+
+GemmParams base_params(const void *a, const void *b, const void *mask, void *out,
+                       int64_t M, int64_t K, int64_t N, int BM, int BK, double p, const sdrop_mask_layout_t &L)
+{
+    GemmParams P;
+    P.A = static_cast<const char *>(a);
+    P.B = static_cast<const char *>(b);
+    P.C = static_cast<char *>(out);
+    P.mv = make_view(mask, L);
+    P.M = M; P.K = K; P.N = N; P.BM = BM; P.BK = BK;
+    P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
+    P.n_tiles = 0;
+    P.splits = 1;
+    P.total_tiles = 0;
+    P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
+    P.bias = nullptr; P.aux = nullptr; P.act = SDROP_ACT_NONE;
+    P.p = p;
+    return P;
+}
+
+// sums the fp32 planes of a split DW into the output (second pass)
+int launch_reduce(const void *ws, void *out, int64_t n, int splits, float scale, int dtype, int out_dtype, hipStream_t st)
+{
+    const unsigned grid = (unsigned)((n / 4 + 255) / 256);
+    const float *part = static_cast<const float *>(ws);
+    if (out_dtype == SDROP_F32)
+        hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, splits, scale);
+    else if (dtype == SDROP_F16)
+        hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, splits, scale);
+    else
+        hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, splits, scale);
+    return hip_status(hipGetLastError());
 }
 
 template <int OP>
@@ -1892,30 +1970,14 @@ int run(const void *a, const void *b, const void *mask, void *out,
     if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
     sdrop_mask_layout_t L;
     sdrop_mask_layout(M, K, BM, BK, &L);
-    {
-        // tile numbers are 32-bit (no operand that fits the device's memory comes near this)
-        const int64_t n_tiles = (N + 255) / 256, lines = L.MB > L.KB ? L.MB : L.KB;
-        if (lines * n_tiles * 16 > INT32_MAX) return SDROP_ESHAPE;
-    }
-    GemmParams P;
-    P.A = static_cast<const char *>(a);
-    P.B = static_cast<const char *>(b);
-    P.C = static_cast<char *>(out);
-    P.mv = make_view(mask, L);
-    P.M = M; P.K = K; P.N = N; P.BM = BM; P.BK = BK;
-    P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
-    P.n_tiles = 0;
-    P.splits = 1;
-    P.total_tiles = 0;
-    P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
-    P.bias = nullptr; P.aux = nullptr; P.act = SDROP_ACT_NONE;
+    if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
+    GemmParams P = base_params(a, b, mask, out, M, K, N, BM, BK, p, L);
     if (epi) {
         if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
         P.bias = epi->bias;
         P.aux = static_cast<const char *>(epi->relu_mask);
         P.act = epi->act;
     }
-    P.p = p;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if constexpr (OP == DW) {
         P.splits = dw_splits(M, N, BM, BK, K);
@@ -1926,16 +1988,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
             P.scale = 1.0f;
             const int rc1 = (dtype == SDROP_F16) ? dispatch_tile<OP, F16, float>(P, st) : dispatch_tile<OP, BF16, float>(P, st);
             if (rc1 != SDROP_OK) return rc1;
-            const int64_t n = K * N;
-            const unsigned grid = (unsigned)((n / 4 + 255) / 256);
-            const float *part = static_cast<const float *>(ws);
-            if (out_dtype == SDROP_F32)
-                hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, P.splits, scale);
-            else if (dtype == SDROP_F16)
-                hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, P.splits, scale);
-            else
-                hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, P.splits, scale);
-            return hip_status(hipGetLastError());
+            return launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st);
         }
     }
     if (dtype == SDROP_F16) {
@@ -1944,6 +1997,86 @@ int run(const void *a, const void *b, const void *mask, void *out,
     }
     if (out_dtype == SDROP_F32) return dispatch_tile<OP, BF16, float>(P, st);
     return dispatch_tile<OP, BF16, __bf16>(P, st);
+}
+
+// both gradients in one launch where bwd_fused_kernel applies (128 x 128 blocks, N a multiple of 256,
+// dX on its persistent kernel); anything else is the two calls in turn
+int g_bwd_fused = 1;
+
+template <class T, class OutDX, class OutDW, int TN_DX>
+int launch_bwd_fused(const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
+{
+    constexpr int LDS_DX = 3 * (128 + TN_DX) * TK * 2 + 4 * 4096, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
+    constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
+    auto k = bwd_fused_kernel<T, OutDX, OutDW, TN_DX>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    const int ncu = cu_count();
+    const int64_t positions = (int64_t)Pdx.MB * Pdx.KB;
+    const int g_dx = (int)(positions < ncu ? positions : ncu);
+    const int g_dw = Pdw.total_tiles < ncu ? Pdw.total_tiles : ncu;
+    hipLaunchKernelGGL(k, dim3((unsigned)(g_dx + g_dw)), dim3(512), P_LDS, stream, Pdx, Pdw, g_dx);
+    return hip_status(hipGetLastError());
+}
+
+template <class T, class OutDX, class OutDW>
+int launch_bwd_fused_tn(int TN, const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
+{
+    if (TN == 256) return launch_bwd_fused<T, OutDX, OutDW, 256>(Pdx, Pdw, stream);
+    return launch_bwd_fused<T, OutDX, OutDW, 128>(Pdx, Pdw, stream);
+}
+
+int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void *dx, void *dw,
+            int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+            int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    // every argument check of both calls before anything is enqueued
+    int rc = check_gemm_args(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype);
+    if (rc == SDROP_OK) rc = check_gemm_args(x, dy, mask, dw, M, K, N, BM, BK, p, dtype, out_dtype);
+    if (rc != SDROP_OK) return rc;
+    const size_t ws_need = sdrop_workspace_bytes(SDROP_OP_BWD_DW, M, K, N, BM, BK, dtype, out_dtype);
+    if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
+    sdrop_mask_layout_t L;
+    sdrop_mask_layout(M, K, BM, BK, &L);
+    if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    GemmParams Pdx = base_params(dy, w, mask, dx, M, K, N, BM, BK, p, L);
+    const DxPlan plan = dx_plan(Pdx);
+    if (g_bwd_fused && BM == 128 && BK == 128 && N % 256 == 0 && plan.persistent) {
+        const int G_ = plan.TN / BK;
+        Pdx.n_tiles = (Pdx.KB + G_ - 1) / G_;
+        GemmParams Pdw = base_params(x, dy, mask, dw, M, K, N, BM, BK, p, L);
+        Pdw.splits = dw_splits(M, N, BM, BK, K);
+        Pdw.n_tiles = (int)(N / 256);
+        Pdw.total_tiles = Pdw.KB * Pdw.n_tiles * Pdw.splits;
+        const float scale = Pdw.scale;
+        const bool split = Pdw.splits > 1;
+        if (split) { Pdw.C = static_cast<char *>(ws); Pdw.scale = 1.0f; }
+        const bool f16 = dtype == SDROP_F16, o32 = out_dtype == SDROP_F32;
+        int rf;
+        if (f16) {
+            if (o32) rf = launch_bwd_fused_tn<F16, float, float>(plan.TN, Pdx, Pdw, st);
+            else if (split) rf = launch_bwd_fused_tn<F16, _Float16, float>(plan.TN, Pdx, Pdw, st);
+            else rf = launch_bwd_fused_tn<F16, _Float16, _Float16>(plan.TN, Pdx, Pdw, st);
+        } else {
+            if (o32) rf = launch_bwd_fused_tn<BF16, float, float>(plan.TN, Pdx, Pdw, st);
+            else if (split) rf = launch_bwd_fused_tn<BF16, __bf16, float>(plan.TN, Pdx, Pdw, st);
+            else rf = launch_bwd_fused_tn<BF16, __bf16, __bf16>(plan.TN, Pdx, Pdw, st);
+        }
+        if (rf != -1) {     // -1: the device does not grant the LDS; fall through to the two calls
+            if (rf != SDROP_OK || !split) return rf;
+            return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st);
+        }
+    }
+    rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream);
+    if (rc != SDROP_OK) return rc;
+    return run<DW>(x, dy, mask, dw, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
 }
 
 }  // namespace
@@ -1982,6 +2115,10 @@ extern "C" {
 
 int sdrop_set_tuning(int knob, int value)
 {
+    if (knob == SDROP_TUNE_BWD_FUSED && (value == 0 || value == 1)) {
+        sdrop::g_bwd_fused = value;
+        return SDROP_OK;
+    }
     if (knob == SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU && value >= 0) {
         sdrop::g_dx_persistent_groups_per_cu = value;
         return SDROP_OK;
@@ -2018,6 +2155,13 @@ int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
 {
     return sdrop::run<sdrop::DW>(X, dY, mask, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
+}
+
+int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,
+              int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+              int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return sdrop::run_bwd(dY, W, X, mask, dX, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
 }
 
 int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,

@@ -24,7 +24,7 @@ MASK_NNZ_OFFSET = 36
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
            "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw",
-           "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer")
+           "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer")
 
 SCALE_DROPOUT, SCALE_ONE = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU_TANH = 0, 1, 2
@@ -90,6 +90,8 @@ def lib():
             f = getattr(L, name)
             f.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp, ctypes.POINTER(Epilogue)]
             f.restype = ci
+        L.sdrop_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
+        L.sdrop_bwd.restype = ci
         L.sdrop_producer.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, ci, vp]
         L.sdrop_producer.restype = ci
         _lib = L
@@ -97,6 +99,7 @@ def lib():
 
 
 TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0
+TUNE_BWD_FUSED = 1
 
 
 def set_tuning(knob, value):
@@ -284,6 +287,37 @@ def sdrop_bwd_dw(X, dY, mask, out_dtype=None, out=None, ws=None):
     if M2 != M or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dw")
     return _gemm("sdrop_bwd_dw", OP_BWD_DW, X, dY, mask, (K, N), M, K, N, out_dtype, out, ws)
+
+
+def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None):
+    """eq. (2) and eq. (3) in one call (one launch where the shapes allow it): returns (dX, dW)."""
+    M, N = dY.shape
+    K, N2 = W.shape
+    if N2 != N or tuple(X.shape) != (M, K) or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_bwd")
+    dtype = dY.dtype
+    if W.dtype != dtype or X.dtype != dtype:
+        raise ValueError("operands must have the same dtype")
+    out_dtype = dtype if out_dtype is None else out_dtype
+    if dtype not in (torch.float16, torch.bfloat16) or out_dtype not in _DTYPES:
+        raise SdropError(EDTYPE, "sdrop_bwd")
+    outs = []
+    for o, shape in ((out_dx, (M, K)), (out_dw, (K, N))):
+        if o is None:
+            o = torch.empty(shape, dtype=out_dtype, device=dY.device)
+        elif tuple(o.shape) != shape or o.dtype != out_dtype:
+            raise ValueError("an output has the wrong shape or dtype")
+        outs.append(o)
+    need = workspace_bytes(OP_BWD_DW, M, K, N, mask.BM, mask.BK, dtype, out_dtype)
+    if ws is None and need:
+        ws = torch.empty(need, dtype=torch.uint8, device=dY.device)
+    ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
+    ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    rc = lib().sdrop_bwd(_dev(dY, "dY"), _dev(W, "W"), _dev(X, "X"), _dev(mask.buf, "mask"),
+                         _dev(outs[0], "dX"), _dev(outs[1], "dW"), M, K, N, mask.BM, mask.BK, mask.p,
+                         _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream())
+    _check(rc, "sdrop_bwd")
+    return outs[0], outs[1]
 
 
 def sdrop_fwd_ex(X, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,

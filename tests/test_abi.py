@@ -37,6 +37,10 @@ def test_tuning_knobs_reject_bad_arguments():
     assert L.sdrop_set_tuning(99, 1) == sdrop.EINVAL
     assert L.sdrop_set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, -1) == sdrop.EINVAL
     assert L.sdrop_set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, 2) == sdrop.EINVAL
+    assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, -1) == sdrop.EINVAL
+    assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, 0) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, 1) == sdrop.OK
 
 
 def test_mask_layout_regions_do_not_overlap():
@@ -100,6 +104,31 @@ def test_host_side_argument_errors_return_before_any_launch():
         assert call(a10=sdrop.F32) == sdrop.EDTYPE
         assert call(a11=sdrop.BF16) == sdrop.EDTYPE   # out_dtype must be the input type or fp32
         assert call(a1=ctypes.c_void_p(addr + 8)) == sdrop.EALIGN
+
+
+def test_fused_backward_checks_both_products_before_any_launch():
+    L = sdrop.lib()
+    buf = ctypes.create_string_buffer(1 << 16)
+    addr = (ctypes.addressof(buf) + 15) // 16 * 16
+    p = ctypes.c_void_p(addr)
+    null = ctypes.c_void_p(0)
+    ok = (p, p, p, p, p, p, 2048, 256, 264, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return L.sdrop_bwd(*a)
+    for i in range(6):
+        assert call(**{"a%d" % i: null}) == sdrop.EINVAL
+        assert call(**{"a%d" % i: ctypes.c_void_p(addr + 8)}) == sdrop.EALIGN
+    assert call(a11=1.5) == sdrop.EINVAL
+    assert call(a6=2047) == sdrop.ESHAPE
+    assert call(a8=250) == sdrop.ESHAPE
+    assert call(a12=sdrop.F32) == sdrop.EDTYPE
+    # few output tiles and long columns: the weight gradient is split, so a workspace is required
+    assert L.sdrop_workspace_bytes(sdrop.OP_BWD_DW, 2048, 256, 264, 64, 64, sdrop.F16, sdrop.F16) > 0
+    assert call() == sdrop.EWORKSPACE
 
 
 def test_tail_arguments_are_checked_on_the_host():
