@@ -23,8 +23,11 @@ class _SparseDropMatmul(torch.autograd.Function):
     def backward(ctx, dy):
         x, w = ctx.saved_tensors
         dy = dy.contiguous()
-        dx = sdrop.sdrop_bwd_dx(dy, w, ctx.mask) if ctx.needs_input_grad[0] else None
-        dw = sdrop.sdrop_bwd_dw(x, dy, ctx.mask) if ctx.needs_input_grad[1] else None
+        if ctx.needs_input_grad[0] and ctx.needs_input_grad[1]:
+            dx, dw = sdrop.sdrop_bwd(dy, w, x, ctx.mask)      # both gradients, one launch where the shapes allow it
+        else:
+            dx = sdrop.sdrop_bwd_dx(dy, w, ctx.mask) if ctx.needs_input_grad[0] else None
+            dw = sdrop.sdrop_bwd_dw(x, dy, ctx.mask) if ctx.needs_input_grad[1] else None
         return dx, dw, None, None, None, None, None
 
 
