@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from oracle import sdrop_oracle as orc
+from oracle import sparse_block_oracle as sb
 from paper_2411_01238_amd import sdrop
 from paper_2411_01238_amd.workloads import make_custom
 from _util import f64, assert_close
@@ -52,3 +53,18 @@ def test_random_shape(M, K, N, BM, BK, dtype, p, seed):
     torch.cuda.synchronize()
     for a16, a32 in ((Y16, Y), (dX16, dX), (dW16, dW)):
         assert torch.equal(a16, a32.to(a16.dtype)), tag + ": 16-bit output is not the rounding of the fp32 output"
+    # both gradients in one call are the two calls, bit for bit, whichever way they are launched
+    bx, bw = sdrop.sdrop_bwd(dYg, Wg, Xg, m)
+    assert torch.equal(bx, dX16) and torch.equal(bw, dW16), tag + ": sdrop_bwd differs from the separate calls"
+    # one tail per case on eq. (1) and eq. (2), chosen by the seed: every kernel form meets every tail over the sample
+    act = (sdrop.ACT_NONE, sdrop.ACT_RELU, sdrop.ACT_GELU_TANH)[seed % 3]
+    one = bool(seed % 2)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(9000 + seed)
+    bN, bK = torch.randn(N, generator=g), torch.randn(K, generator=g)
+    kw = dict(scale_mode=sdrop.SCALE_ONE if one else sdrop.SCALE_DROPOUT, act=act, out_dtype=torch.float32)
+    Yt = sdrop.sdrop_fwd_ex(Xg, Wg, m, bias=bN.cuda(), relu_mask=dYg, **kw)
+    dXt = sdrop.sdrop_bwd_dx_ex(dYg, Wg, m, bias=bK.cuda(), relu_mask=Xg, **kw)
+    torch.cuda.synchronize()
+    assert_close(f64(Yt), sb.fwd_tail(Xd, Wd, keep, BM, BK, p, one, f64(bN), act, dYd), tag + " Y with tail")
+    assert_close(f64(dXt), sb.bwd_dx_tail(dYd, Wd, keep, BM, BK, p, one, f64(bK), act, Xd), tag + " dX with tail")
