@@ -1313,24 +1313,24 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     // ---------------- computing wavefronts ----------------
     // Look-ups two tiles ahead (order[] of tile k+2, list bounds of tile k+1), as vector loads:
     // they are waited for with the vector-memory counter, which the main loop never waits on.
-    struct CMeta { int t, ord, len; };
-    auto c_level1 = [&](int k) __attribute__((always_inline)) -> CMeta {
-        CMeta m;
-        m.t = tile_of(k);
-        m.ord = order[rank_of(m.t)];
-        m.len = 0;
-        return m;
-    };
-    auto c_level2 = [&](CMeta &m) __attribute__((always_inline)) {
-        const int o = uni(m.ord);
-        const int cnt = ptr[o + 1] - ptr[o];
+    // Every look-up is turned into a scalar right after a tile's slices, BEFORE the tile's stores:
+    // the counter is in order, so a wait placed after the stores (the top of the next iteration)
+    // would also wait until those stores have drained to memory.
+    auto c_order = [&](int k) __attribute__((always_inline)) -> int { return order[rank_of(tile_of(k))]; };
+    auto c_count = [&](int o) __attribute__((always_inline)) -> int { return ptr[o + 1] - ptr[o]; };
+    auto c_len = [&](int k, int cnt) __attribute__((always_inline)) -> int {
+        const int tk = tile_of(k);
         int lo;
-        m.len = part_of(m.t < total ? m.t : total - 1, cnt, lo);
+        return part_of(tk < total ? tk : total - 1, cnt, lo);
     };
-    CMeta cur, n1, n2;
-    cur = c_level1(0); c_level2(cur);
-    n1 = c_level1(1);
-    n2 = c_level1(2);
+    // scalars: this tile (ord0, len0), the next one's block row / column (ord1);
+    // in flight: the next tile's kept count (cnt1_v), order[] of the tile after it (ord2_v)
+    int ord0 = uni(c_order(0));
+    int len0 = uni(c_len(0, c_count(ord0)));
+    int ord1 = uni(c_order(1));
+    int ord2_v = c_order(2);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+    int ord2 = uni(ord2_v);
 
     Compute<T, OutT, A_TR, B_TR, TM, TN, WM, WN> cw;
     cw.wm = wm; cw.wn = wn;
@@ -1341,12 +1341,13 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     char *const reg = staging + wave * STAGING;
 
     for (int k = 0;; ++k) {
-        if (cur.t >= total) break;
-        const int t = cur.t, ord = uni(cur.ord), nsteps = uni(cur.len) << sub_shift;
+        const int t = tile_of(k);
+        if (t >= total) break;
+        const int ord = ord0, nsteps = len0 << sub_shift;
         GEMM_TICKW(k * 4);
-        // look-ups for the tiles after this one (n1.ord was requested a whole tile ago)
-        c_level2(n1);
-        CMeta n3 = c_level1(k + 3);
+        // requests for the tiles after this one; consumed after this tile's slices
+        const int cnt1_v = c_count(ord1);
+        const int ord3_v = c_order(k + 3);
 
         cw.zero();
         if (nsteps > 0 && !started) {
@@ -1369,11 +1370,14 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
             if (s == 0) GEMM_TICKW(k * 4 + 1);
         }
+        // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+        len0 = uni(c_len(k + 1, cnt1_v));
+        ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
         if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
         GEMM_TICKW(k * 4 + 2);
         cw.template store<TAIL>(reg, scale, ldc, tl, dst);
         GEMM_TICKW(k * 4 + 3);
-        cur = n1; n1 = n2; n2 = n3;
     }
 }
 
@@ -1578,9 +1582,12 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
         bitpos = zj & 63;
         return P.mv.bits[(int64_t)zi * H->words_per_row + (zj >> 6)];
     };
-    auto fill_batch = [&](int z0, int cnt, uint64_t word, int bitpos) __attribute__((always_inline)) {
+    // which of the positions z0 .. z0 + cnt - 1 are dropped, one bit per lane's position
+    auto dropped_of = [&](int z0, int cnt, uint64_t word, int bitpos) __attribute__((always_inline)) -> uint64_t {
         const bool dropped = lane < cnt && (w + G * (z0 + lane)) < total_pos && !((word >> bitpos) & 1);
-        uint64_t todo = __ballot(dropped);
+        return __ballot(dropped);
+    };
+    auto fill_batch = [&](int z0, uint64_t todo) __attribute__((always_inline)) {
         while (todo) {
             const int l = __builtin_ctzll(todo);
             todo &= todo - 1;
@@ -1600,13 +1607,20 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     const Tail tl = make_tail(P);
     char *const reg = staging + wave * STAGING;
 
+    // Every look-up (the next group's entries, the keep bits of the next zero-fill batch) is turned
+    // into scalars right after a tile's slices, BEFORE the tile's stores: the vector-memory counter is
+    // in order, so a wait placed after the stores would also wait until they have drained to memory
+    // (measured: 2.4 us per tile on 65536 x 4096 x 1024).
     Group nxt = c_load_group(0);
-    for (int k = 0; nxt.u >= 0; ++k) {
-        int gr[4], gc[4];
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+    int gr[4], gc[4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) { gr[b] = uni(nxt.r[b]); gc[b] = uni(nxt.c[b]); }
-        const int gn = nxt.n;
-        nxt = c_load_group(k + 1);                      // requested a whole group ahead of its use
+    for (int b = 0; b < 4; ++b) { gr[b] = uni(nxt.r[b]); gc[b] = uni(nxt.c[b]); }
+    int gn = nxt.n, gu = nxt.u;
+    int tick_no = 0;        // timing builds only: tiles done by this workgroup
+    for (int k = 0; gu >= 0; ++k) {
+        nxt = c_load_group(k + 1);                      // in flight during this group's tiles
+        int ngr[4] = {0, 0, 0, 0}, ngc[4] = {0, 0, 0, 0};
         int a = 0;
         while (a < gn) {
             const int row = sel4(gr, a);
@@ -1635,22 +1649,35 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
                 gcol0 = col0;
                 return c_rows + (int64_t)(mi * 32) * ldc + col0 * ESZ;
             };
+            GEMM_TICKW(tick_no * 4);
             for (int s = 0; s < nsteps; ++s) {
                 cw.slice(stage_ptr(st0), stage_ptr(st1));
                 const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
             }
+            GEMM_TICKW(tick_no * 4 + 1);
+            // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) { ngr[b] = uni(nxt.r[b]); ngc[b] = uni(nxt.c[b]); }
+            const uint64_t todo = zc > 0 ? dropped_of(z_done, zc, zword, bitpos) : 0;
             if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
             cw.template store<TAIL>(reg, scale, ldc, tl, dst);
-            if (zc > 0) { fill_batch(z_done, zc, zword, bitpos); z_done += zc; }
+            GEMM_TICKW(tick_no * 4 + 2);
+            if (zc > 0) { fill_batch(z_done, todo); z_done += zc; }
+            GEMM_TICKW(tick_no * 4 + 3);
+            ++tick_no;
             a += nb;
         }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) { gr[b] = ngr[b]; gc[b] = ngc[b]; }
+        gn = nxt.n; gu = nxt.u;
     }
     // what is left of the zero fill (all of it for a workgroup without tiles)
     while (z_done < nz) {
         const int zc = nz - z_done < 64 ? nz - z_done : 64;
         int bitpos = 0;
         const uint64_t zword = fetch_bits(z_done, zc, bitpos);
-        fill_batch(z_done, zc, zword, bitpos);
+        fill_batch(z_done, dropped_of(z_done, zc, zword, bitpos));
         z_done += zc;
     }
 }
