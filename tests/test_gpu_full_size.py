@@ -62,7 +62,12 @@ def _sampled_parity(w, p, layer=0, n=400, n_dw=96):
     check("Y", lambda **k: sdrop.sdrop_fwd(Xg, Wg, m, **k), orc.fwd_at, Xd, Wd, w.M, w.N, w.BM, 256, n)
     dX32, dX16 = check("dX", lambda **k: sdrop.sdrop_bwd_dx(dYg, Wg, m, **k), orc.bwd_dx_at, dYd, Wd,
                        w.M, w.K, w.BM, w.BK, n)
-    check("dW", lambda **k: sdrop.sdrop_bwd_dw(Xg, dYg, m, **k), orc.bwd_dw_at, Xd, dYd, w.K, w.N, w.BK, 256, n_dw)
+    dW32, dW16 = check("dW", lambda **k: sdrop.sdrop_bwd_dw(Xg, dYg, m, **k), orc.bwd_dw_at, Xd, dYd, w.K, w.N, w.BK, 256, n_dw)
+    # both gradients in one call (one launch where the shapes allow it) are the two calls, bit for bit
+    bx, bw = sdrop.sdrop_bwd(dYg, Wg, Xg, m)
+    torch.cuda.synchronize()
+    assert torch.equal(bx, dX16) and torch.equal(bw, dW16), tag + ": sdrop_bwd differs from the separate calls"
+    del bx, bw, dW32, dW16
 
     # whole-output property: per block, dX is all +0 exactly where the block is dropped
     keep_t = torch.from_numpy(keep.astype(bool)).cuda()
