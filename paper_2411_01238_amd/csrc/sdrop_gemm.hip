@@ -1405,9 +1405,9 @@ __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 // chunk, so that the tiles an XCD has in flight at one time are neighbours in the list.
 // Both roles read the same list entries and derive the same tiles from them.
 //
-// Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; the computing
-// wavefronts test a batch of them per tile (bits fetched before the tile's slices, used after
-// its stores) and finish what is left after their last tile.
+// Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; its loader
+// wavefronts write them a kilobyte per slice of the stream, beside the direct loads, and finish
+// what is left when the stream has ended.
 template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
 __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, const int G, const int w)
 {
@@ -1525,24 +1525,73 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
             return true;
         };
 
+        // Zero fill of the dropped blocks, by the loaders: the workgroup owns positions w, w + G, ...
+        // (z-th: w + G z).  One step per slice of the stream: either test the next position's keep
+        // bit (its word was requested a step earlier, as a scalar load through the constant address
+        // space) or write this wavefront's next kilobyte of the dropped block in hand (a block is
+        // TM rows of BK elements; the four loaders share its 16-byte pieces).  The computing
+        // wavefronts never stop for it.  The stores go out before the step's direct loads, so the
+        // wait that follows those loads still means "the slice issued one step ago has landed".
+        typedef const __attribute__((address_space(4))) uint64_t *const_u64;
+        const const_u64 k_bits = (const_u64)(uintptr_t)P.mv.bits;
+        const int total_pos = P.MB * P.KB;
+        const int nz = w < total_pos ? (total_pos - w + G - 1) / G : 0;
+        const int wpr = H->words_per_row;
+        const int row_chunks = P.BK * ESZ / 16;                      // 16-byte pieces per row of a block
+        const int per_wave = TM * row_chunks / (NW * 64);           // store instructions per wavefront and block
+        int zpos = 0;                    // next position to test
+        int zprog = 0;                   // store instructions already issued for the block in hand
+        char *zblock = nullptr;          // the dropped block in hand, or null
+        uint64_t zword = 0;              // keep bits around position zpos (valid when zpos < nz)
+        auto request_word = [&]() __attribute__((always_inline)) {
+            if (zpos < nz) {
+                const int pz = w + G * zpos;
+                zword = k_bits[(int64_t)(pz / P.KB) * wpr + ((pz % P.KB) >> 6)];
+            }
+        };
+        request_word();
+        // true while there is zero fill left
+        auto zero_step = [&]() __attribute__((always_inline)) -> bool {
+            if (zblock) {
+                const int c = (zprog * NW + wave) * 64 + lane;
+                store_out(zblock + (c / row_chunks) * ldc + (c % row_chunks) * 16, make_uint4(0, 0, 0, 0));
+                if (++zprog == per_wave) zblock = nullptr;
+                return true;
+            }
+            if (zpos >= nz) return false;
+            const int pz = w + G * zpos;
+            const int zi = pz / P.KB, zj = pz % P.KB;
+            if (!((zword >> (zj & 63)) & 1)) {
+                zblock = P.C + (int64_t)zi * P.BM * ldc + (int64_t)zj * P.BK * ESZ;
+                zprog = 0;
+            }
+            ++zpos;
+            request_word();
+            return true;
+        };
+
         int issued = 0, st_issue = 0;
         for (int i = 0; i < AHEAD; ++i)
             if (issue_next(st_issue)) { ++issued; st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1; }
-        if (issued == 0) return;
-        if (issued == AHEAD) __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
-        else __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
-        __builtin_amdgcn_s_barrier();
-        for (int g = 0; g < issued; ++g) {
-            const bool more = issue_next(st_issue);
-            if (more) {
-                ++issued;
-                st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1;
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
-            } else {
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
-            }
+        if (issued > 0) {
+            if (issued == AHEAD) __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+            else __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
             __builtin_amdgcn_s_barrier();
+            for (int g = 0; g < issued; ++g) {
+                zero_step();
+                const bool more = issue_next(st_issue);
+                if (more) {
+                    ++issued;
+                    st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1;
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+                } else {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+                }
+                __builtin_amdgcn_s_barrier();
+            }
         }
+        // what the stream left of the zero fill (all of it for a workgroup without tiles)
+        while (zero_step()) { }
         return;
     }
 
@@ -1560,45 +1609,6 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
         }
         return g;
     };
-    // zero fill: this workgroup's positions are w + G z, z in [0, nz)
-    const int total_pos = P.MB * P.KB;
-    const int nz = w < total_pos ? (total_pos - w + G - 1) / G : 0;
-    int my_groups = 0;
-    {
-        const int first = x * per_chunk;
-        const int avail = ngroups - first < per_chunk ? ngroups - first : per_chunk;   // groups in chunk x
-        my_groups = avail > r ? (avail - r + wx - 1) / wx : 0;
-    }
-    int quota = my_groups > 0 ? (nz + my_groups - 1) / my_groups : 0;
-    if (quota > 64) quota = 64;
-    int z_done = 0;
-    const int row_chunks = P.BK * ESZ / 16;
-    // lane l: is position z0 + l (l < cnt) of this workgroup dropped?  (word fetched here, tested later)
-    auto fetch_bits = [&](int z0, int cnt, int &bitpos) __attribute__((always_inline)) -> uint64_t {
-        const int z = z0 + (lane < cnt ? lane : 0);
-        const int pz = w + G * z;
-        const int pc = pz < total_pos ? pz : 0;
-        const int zi = pc / P.KB, zj = pc % P.KB;
-        bitpos = zj & 63;
-        return P.mv.bits[(int64_t)zi * H->words_per_row + (zj >> 6)];
-    };
-    // which of the positions z0 .. z0 + cnt - 1 are dropped, one bit per lane's position
-    auto dropped_of = [&](int z0, int cnt, uint64_t word, int bitpos) __attribute__((always_inline)) -> uint64_t {
-        const bool dropped = lane < cnt && (w + G * (z0 + lane)) < total_pos && !((word >> bitpos) & 1);
-        return __ballot(dropped);
-    };
-    auto fill_batch = [&](int z0, uint64_t todo) __attribute__((always_inline)) {
-        while (todo) {
-            const int l = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const int pz = w + G * (z0 + l);
-            const int zi = pz / P.KB, zj = pz % P.KB;
-            char *z = P.C + (int64_t)zi * P.BM * ldc + (int64_t)zj * P.BK * ESZ;
-            for (int c = threadIdx.x; c < TM * row_chunks; c += NW * 64)
-                store_out(z + (c / row_chunks) * ldc + (c % row_chunks) * 16, make_uint4(0, 0, 0, 0));
-        }
-    };
-
     Compute<T, OutT, false, false, TM, TN, WM, WN> cw;
     cw.wm = wm; cw.wn = wn;
     int st0 = 0, st1 = 1, st2 = 2;
@@ -1607,7 +1617,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     const Tail tl = make_tail(P);
     char *const reg = staging + wave * STAGING;
 
-    // Every look-up (the next group's entries, the keep bits of the next zero-fill batch) is turned
+    // Every look-up (the next group's entries) is turned
     // into scalars right after a tile's slices, BEFORE the tile's stores: the vector-memory counter is
     // in order, so a wait placed after the stores would also wait until they have drained to memory
     // (measured: 2.4 us per tile on 65536 x 4096 x 1024).
@@ -1627,11 +1637,6 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
             int nb = 1;
             while (a + nb < gn && sel4(gr, a + nb) == row) ++nb;
             const int chunks_valid = nb << cshift;
-            // bits of the next batch of this workgroup's positions
-            const int zc = nz - z_done < quota ? nz - z_done : quota;
-            int bitpos = 0;
-            uint64_t zword = 0;
-            if (zc > 0) zword = fetch_bits(z_done, zc, bitpos);
 
             cw.zero();
             if (!started) {
@@ -1659,11 +1664,9 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
 #pragma unroll
             for (int b = 0; b < 4; ++b) { ngr[b] = uni(nxt.r[b]); ngc[b] = uni(nxt.c[b]); }
-            const uint64_t todo = zc > 0 ? dropped_of(z_done, zc, zword, bitpos) : 0;
             if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
             cw.template store<TAIL>(reg, scale, ldc, tl, dst);
             GEMM_TICKW(tick_no * 4 + 2);
-            if (zc > 0) { fill_batch(z_done, todo); z_done += zc; }
             GEMM_TICKW(tick_no * 4 + 3);
             ++tick_no;
             a += nb;
@@ -1671,14 +1674,6 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
 #pragma unroll
         for (int b = 0; b < 4; ++b) { gr[b] = ngr[b]; gc[b] = ngc[b]; }
         gn = nxt.n; gu = nxt.u;
-    }
-    // what is left of the zero fill (all of it for a workgroup without tiles)
-    while (z_done < nz) {
-        const int zc = nz - z_done < 64 ? nz - z_done : 64;
-        int bitpos = 0;
-        const uint64_t zword = fetch_bits(z_done, zc, bitpos);
-        fill_batch(z_done, dropped_of(z_done, zc, zword, bitpos));
-        z_done += zc;
     }
 }
 
