@@ -65,13 +65,15 @@ enum { SDROP_OP_FWD = 0, SDROP_OP_BWD_DX = 1, SDROP_OP_BWD_DW = 2 };
  * Host-side tuning knobs (process-wide; not thread-safe against concurrent GEMM calls).  They change
  * which kernel a call uses, never its result.
  *   SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU  sdrop_bwd_dx with tiles of several kept blocks uses its
- *       persistent kernel when it expects at least this many tiles per CU (default 16; 0 = whenever
+ *       persistent kernel when it expects at least this many tiles per CU (default 8; 0 = whenever
  *       the shape allows it)
+ *   SDROP_TUNE_DX_TILE_WIDTH  columns of sdrop_bwd_dx's output tiles: 0 (default) chosen per call
+ *       from the expected number of kept blocks, 128 or 256 forced
  *   SDROP_TUNE_BWD_FUSED  1 (default): sdrop_bwd computes both gradients in one launch where the
  *       shapes allow it; 0: always as the two separate launches
  * Returns SDROP_EINVAL for an unknown knob or a value outside its range.
  */
-enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0, SDROP_TUNE_BWD_FUSED = 1 };
+enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0, SDROP_TUNE_BWD_FUSED = 1, SDROP_TUNE_DX_TILE_WIDTH = 2 };
 int sdrop_set_tuning(int knob, int value);
 
 /* Text for an error code (static storage). */

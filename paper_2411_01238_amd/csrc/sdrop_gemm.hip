@@ -1861,7 +1861,7 @@ int cu_count()
 }
 
 // groups of kept blocks per CU from which dX tiles of several blocks use the persistent kernel
-int g_dx_persistent_groups_per_cu = 16;
+int g_dx_persistent_groups_per_cu = 8;
 
 // dX: width of the tiles, and whether the persistent kernel computes them.
 // Every kept block costs the same, so the launch runs in ceil(tiles / CUs) rounds of
@@ -1869,9 +1869,13 @@ int g_dx_persistent_groups_per_cu = 16;
 // ones (a 128-wide tile was measured at 0.6 of the time of a wide one); take whichever shape is expected
 // to finish first for the expected number of kept blocks, (1-p) MB KB.
 // The persistent kernel deals out groups of TN/BK list entries and cuts a group where the block
-// row changes inside it; with few groups per workgroup one such extra tile is a whole round
-// (4096^3, a tenth dropped: 147 us against 111 us), so it is used for single-block tiles
-// (no cuts) and where a workgroup gets many groups (65536 x 4096 x 1024: 485 against 515 us).
+// row changes inside it; with few groups per workgroup one such extra tile is a whole round, so it
+// is used for single-block tiles (no cuts) and where a workgroup gets at least 8 groups.  Measured,
+// persistent against per-tile: 1.8 groups per CU (4096^3, a tenth dropped) 134 against 103 us;
+// 3 (16384 x 3072 x 768, 64-wide blocks, half dropped) 61 against 56; 5.6 (8192 x 8192 x 2048, 0.3
+// dropped) 215 against 190; 9.6 (65536 x 4096 x 1024, 0.7 dropped) 235 against 270; 22 (the same,
+// 0.3 dropped) 410 against 417.
+int g_dx_tile_width = 0;    // 0: chosen per call; 128 or 256: forced (benchmarks and tests)
 struct DxPlan { int TN; bool persistent; };
 DxPlan dx_plan(const GemmParams &P)
 {
@@ -1885,6 +1889,7 @@ DxPlan dx_plan(const GemmParams &P)
     };
     DxPlan plan;
     plan.TN = (rounds(128) * 0.6 < rounds(256)) ? 128 : 256;
+    if (g_dx_tile_width == 128 || g_dx_tile_width == 256) plan.TN = g_dx_tile_width;
     const int G_ = plan.TN / P.BK;
     plan.persistent = P.BM == 128 && P.N % TK == 0 && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu);
     return plan;
@@ -2137,6 +2142,10 @@ extern "C" {
 
 int sdrop_set_tuning(int knob, int value)
 {
+    if (knob == SDROP_TUNE_DX_TILE_WIDTH && (value == 0 || value == 128 || value == 256)) {
+        sdrop::g_dx_tile_width = value;
+        return SDROP_OK;
+    }
     if (knob == SDROP_TUNE_BWD_FUSED && (value == 0 || value == 1)) {
         sdrop::g_bwd_fused = value;
         return SDROP_OK;

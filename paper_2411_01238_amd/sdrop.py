@@ -99,7 +99,9 @@ def lib():
 
 
 TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0
+DX_PERSISTENT_GROUPS_PER_CU_DEFAULT = 8
 TUNE_BWD_FUSED = 1
+TUNE_DX_TILE_WIDTH = 2
 
 
 def set_tuning(knob, value):

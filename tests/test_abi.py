@@ -36,7 +36,10 @@ def test_tuning_knobs_reject_bad_arguments():
     L = sdrop.lib()
     assert L.sdrop_set_tuning(99, 1) == sdrop.EINVAL
     assert L.sdrop_set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, -1) == sdrop.EINVAL
-    assert L.sdrop_set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_TILE_WIDTH, 64) == sdrop.EINVAL
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_TILE_WIDTH, 256) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_TILE_WIDTH, 0) == sdrop.OK
     assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, 2) == sdrop.EINVAL
     assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, -1) == sdrop.EINVAL
     assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, 0) == sdrop.OK

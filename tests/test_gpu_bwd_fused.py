@@ -55,7 +55,7 @@ def test_both_gradients_in_one_call(M, K, N, BM, BK, dtype, p, seed, force):
                     assert_bf16_rounding_of(f64(dw), ref_dw, tag + " dW")
     finally:
         sdrop.set_tuning(sdrop.TUNE_BWD_FUSED, 1)
-        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16)
+        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT)
 
 
 def test_everything_dropped_and_outputs_given():

@@ -126,7 +126,38 @@ def test_dx_persistent_kernel_with_several_blocks_per_tile(M, K, N, BM, BK, dtyp
     try:
         _full_parity(X, W, dY, BM, BK, p, seed, 0, "dx-persistent(%d,%d,%d,%dx%d,%s)" % (M, K, N, BM, BK, dtype))
     finally:
-        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16)
+        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT)
+
+
+@pytest.mark.parametrize("M,K,N,BM,BK,dtype,p,seed", [
+    (1024, 1024, 256, 128, 128, "bf16", 0.4, 41),   # width 256: two kept blocks per tile; width 128: one
+    (512, 1024, 192, 128, 64, "f16", 0.6, 42),      # width 256: four 64-column blocks per tile; width 128: two
+    (384, 512, 136, 64, 64, "bf16", 0.3, 43),       # 64-row blocks, ragged reduction: per-tile kernels only
+])
+def test_dx_every_tile_width_and_kernel_form(M, K, N, BM, BK, dtype, p, seed):
+    # the host normally picks the width of dX's tiles and the kernel form from the expected number of
+    # kept blocks; here every combination is forced and must give the same dX, bit for bit
+    print("gemm dx widths", M, K, N, BM, BK, dtype, p, seed, flush=True)
+    X, W, dY = make_custom(M, K, N, dtype, seed=seed)
+    m = sdrop.sdrop_mask(M, K, BM, BK, p, seed, 0)
+    keep = orc.mask(M // BM, K // BK, p, seed, 0)
+    ref = orc.bwd_dx(f64(dY), f64(W), keep, BM, BK, p)
+    outs = []
+    try:
+        for width in (0, 128, 256):
+            for knob in (sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT, 0):
+                sdrop.set_tuning(sdrop.TUNE_DX_TILE_WIDTH, width)
+                sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, knob)
+                o = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=torch.float32)
+                torch.cuda.synchronize()
+                assert_close(f64(o), ref, "dX width %d knob %d" % (width, knob))
+                outs.append(o)
+    finally:
+        sdrop.set_tuning(sdrop.TUNE_DX_TILE_WIDTH, 0)
+        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT)
+    # a tile's reduction order does not depend on its width or on the kernel form
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
 
 
 def test_retilings_of_one_logical_mask_give_the_same_products():
@@ -254,4 +285,4 @@ def test_structured_masks_on_a_grid_larger_than_the_chip(force_groups):
             p = 1.0 - float(keep.mean())              # the scale that goes with this kept fraction; any p would do
             _full_parity(X, W, dY, B, B, p, 0, 0, name, keep=keep)
     finally:
-        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16)
+        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT)

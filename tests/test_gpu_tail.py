@@ -132,7 +132,7 @@ def test_tails_in_the_persistent_dx_kernel_with_several_blocks_per_tile():
             o16 = sdrop.sdrop_bwd_dx_ex(dY.cuda(), W.cuda(), m, act=act, bias=bK.cuda(), relu_mask=X.cuda())
             _check(o32, o16, ref, X.dtype, "forced persistent dx act %d" % act)
     finally:
-        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, 16)
+        sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT)
 
 
 def test_gate_never_reads_dropped_blocks_and_no_tail_is_the_plain_call():
