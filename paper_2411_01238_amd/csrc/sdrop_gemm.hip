@@ -10,6 +10,10 @@
 // gemm_persistent_kernel / gemm_persistent_dx_kernel: one workgroup per CU walks a sequence of
 // tiles as one stream of slices, so that the next tile's operands arrive while the current one is
 // still multiplied and stored; the host picks between them per call (dispatch_tile).
+// bwd_fused_kernel holds the persistent dX and dW workgroups of one layer in a single launch
+// (sdrop_bwd).  Kernels with an element-wise tail (bias, activation, ReLU gate: the sparse
+// operators around the dropout of Section 4.3's closing remark) are separate instantiations
+// of the same templates, so eq. (1)-(3) proper run the code they would without that feature.
 //
 // Each workgroup owns one TM x TN output tile and steps through its reduction in slices of
 // TK = 64 that rotate through LDS stages (three for 128-row tiles, one workgroup per CU; two for
