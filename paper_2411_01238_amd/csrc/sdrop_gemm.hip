@@ -463,8 +463,10 @@ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 
 
 // SPEC: the workgroup has NW more wavefronts (one more per SIMD) that do nothing but issue the
 // direct loads, so that a load instruction held up by the memory pipeline never holds up MFMAs.
+// (The body is a device function of the tile number, so that one launch can hold the workgroups
+// of two operations; see bwd_fused_tile_kernel.)
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED, bool SPEC, bool TAIL>
-__global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(GemmParams P)
+__device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bid)
 {
     constexpr int NW = WM * WN, NT = NW * 64 * (SPEC ? 2 : 1);   // computing wavefronts; threads
     static_assert(NW == 4 || (NW == 8 && !RAGGED), "4 wavefronts (8 only without the register path)");
@@ -517,7 +519,7 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
     int out_col0[NGRP_MAX] = {0, 0, 0, 0};
 
     if constexpr (OP == FWD) {
-        const int t = blockIdx.x;
+        const int t = bid;
         const int rank = t / P.n_tiles, nt = t % P.n_tiles;
         const int i = uni(P.mv.row_order[rank]);
         const int rp = uni(P.mv.row_ptr[i]);
@@ -533,8 +535,8 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         out_col0[0] = nt * TN;
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
     } else if constexpr (OP == DW) {
-        // blockIdx.x = (rank of block column j in the schedule, N tile, part of the list)
-        const int t = blockIdx.x;
+        // bid = (rank of block column j in the schedule, N tile, part of the list)
+        const int t = bid;
         const int per_col = P.n_tiles * P.splits;
         const int j = uni(P.mv.col_order[t / per_col]);
         const int nt = (t % per_col) / P.splits, part = t % P.splits;
@@ -567,7 +569,7 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         // cannot be proven unaliased and would lose its scalar form.
         if (G_ == 1) {
             // One kept block per tile.  Two duties per workgroup.  (1) Zero fill: block position
-            // blockIdx.x, if it is dropped.  (2) Compute: kept block e of the mask's locally ordered list
+            // bid, if it is dropped.  (2) Compute: kept block e of the mask's locally ordered list
             // (groups of 8 block rows, column by column), where the hardware's round-robin placement
             // of workgroups on the 8 XCDs is undone: workgroup b runs on XCD b % 8 and takes
             // e = (b % 8) * ceil(nnz / 8) + b / 8.  Every XCD so gets the same number of tiles (its CUs
@@ -576,7 +578,7 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
             // cover about 8 block rows x 8 block columns, so that each dY and W tile it fetches from
             // HBM serves several of them (measured at 4096^3, half kept, operands not in the Infinity
             // Cache: 78 us against 86-100 us in row-major order).
-            const int b = blockIdx.x;
+            const int b = bid;
             const int nnz = H->nnz;
             const int per_xcd = (nnz + 7) >> 3;
             const int e = (b & 7) * per_xcd + (b >> 3);
@@ -593,11 +595,11 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
             if (b < total && !((zword >> (zj & 63)) & 1)) zero_block(zi, zj);
             blocks_valid = computes ? 1 : 0;
         } else {
-            // blockIdx.x = q * MB + i.  The workgroup computes the kept blocks of ranks
+            // bid = q * MB + i.  The workgroup computes the kept blocks of ranks
             // [q*G, q*G+G) of block row i as one TM x (G*BK) tile, and zero-fills the block
             // positions [q*G, q*G+G) of row i that are dropped.
-            i = blockIdx.x % P.MB;
-            const int q = blockIdx.x / P.MB;
+            i = bid % P.MB;
+            const int q = bid / P.MB;
             const int rp = uni(P.mv.row_ptr[i]);
             const int cnt = uni(P.mv.row_ptr[i + 1]) - rp;
             blocks_valid = cnt - q * G_ < G_ ? cnt - q * G_ : G_;
@@ -961,6 +963,12 @@ __global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(Gem
         }
         GEMM_TICK(4);
     }
+}
+
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool RAGGED, bool SPEC, bool TAIL>
+__global__ __launch_bounds__(WM * WN * 64 * (SPEC ? 2 : 1)) void gemm_kernel(GemmParams P)
+{
+    gemm_tile_body<OP, T, OutT, TM, TN, WM, WN, RAGGED, SPEC, TAIL>(P, (int)blockIdx.x);
 }
 
 // The computing side of a persistent kernel: one wavefront's accumulators and operand registers,
@@ -1702,6 +1710,18 @@ __global__ __launch_bounds__(512) void bwd_fused_kernel(GemmParams Pdx, GemmPara
         gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
 }
 
+// The same where dX runs one workgroup per tile (tiles of two kept blocks that are too few per CU
+// for the persistent kernel): workgroups [0, n_dx) are those tiles, in the order of the separate
+// launch, the rest the persistent dW kernel.
+template <class T, class OutDX, class OutDW>
+__global__ __launch_bounds__(512) void bwd_fused_tile_kernel(GemmParams Pdx, GemmParams Pdw, int n_dx)
+{
+    if ((int)blockIdx.x < n_dx)
+        gemm_tile_body<DX, T, OutDX, 128, 256, 2, 2, false, true, false>(Pdx, (int)blockIdx.x);
+    else
+        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - n_dx, (int)blockIdx.x - n_dx);
+}
+
 // WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
 int cu_count();
 
@@ -2030,8 +2050,8 @@ int run(const void *a, const void *b, const void *mask, void *out,
     return dispatch_tile<OP, BF16, __bf16>(P, st);
 }
 
-// both gradients in one launch where bwd_fused_kernel applies (128 x 128 blocks, N a multiple of 256,
-// dX on its persistent kernel); anything else is the two calls in turn
+// both gradients in one launch where bwd_fused_kernel or bwd_fused_tile_kernel applies (128 x 128
+// blocks, N a multiple of 256); anything else is the two calls in turn
 int g_bwd_fused = 1;
 
 template <class T, class OutDX, class OutDW, int TN_DX>
@@ -2052,6 +2072,25 @@ int launch_bwd_fused(const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t s
     const int g_dx = (int)(positions < ncu ? positions : ncu);
     const int g_dw = Pdw.total_tiles < ncu ? Pdw.total_tiles : ncu;
     hipLaunchKernelGGL(k, dim3((unsigned)(g_dx + g_dw)), dim3(512), P_LDS, stream, Pdx, Pdw, g_dx);
+    return hip_status(hipGetLastError());
+}
+
+template <class T, class OutDX, class OutDW>
+int launch_bwd_fused_tile(const GemmParams &Pdx, const GemmParams &Pdw, int n_dx, hipStream_t stream)
+{
+    constexpr int LDS_DX = 3 * (128 + 256) * TK * 2, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
+    constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
+    auto k = bwd_fused_tile_kernel<T, OutDX, OutDW>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    const int ncu = cu_count();
+    const int g_dw = Pdw.total_tiles < ncu ? Pdw.total_tiles : ncu;
+    hipLaunchKernelGGL(k, dim3((unsigned)(n_dx + g_dw)), dim3(512), P_LDS, stream, Pdx, Pdw, n_dx);
     return hip_status(hipGetLastError());
 }
 
@@ -2079,9 +2118,12 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
 
     GemmParams Pdx = base_params(dy, w, mask, dx, M, K, N, BM, BK, p, L);
     const DxPlan plan = dx_plan(Pdx);
-    if (g_bwd_fused && BM == 128 && BK == 128 && N % 256 == 0 && plan.persistent) {
+    // dX as one workgroup per tile of two kept blocks (never with one block per tile: that form is persistent)
+    const bool tile_form = !plan.persistent && plan.TN == 256;
+    if (g_bwd_fused && BM == 128 && BK == 128 && N % 256 == 0 && (plan.persistent || tile_form)) {
         const int G_ = plan.TN / BK;
         Pdx.n_tiles = (Pdx.KB + G_ - 1) / G_;
+        const int n_dx = Pdx.MB * Pdx.n_tiles;           // the per-tile launch's grid: (group of the row, block row)
         GemmParams Pdw = base_params(x, dy, mask, dw, M, K, N, BM, BK, p, L);
         Pdw.splits = dw_splits(M, N, BM, BK, K);
         Pdw.n_tiles = (int)(N / 256);
@@ -2091,7 +2133,17 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
         if (split) { Pdw.C = static_cast<char *>(ws); Pdw.scale = 1.0f; }
         const bool f16 = dtype == SDROP_F16, o32 = out_dtype == SDROP_F32;
         int rf;
-        if (f16) {
+        if (tile_form) {
+            if (f16) {
+                if (o32) rf = launch_bwd_fused_tile<F16, float, float>(Pdx, Pdw, n_dx, st);
+                else if (split) rf = launch_bwd_fused_tile<F16, _Float16, float>(Pdx, Pdw, n_dx, st);
+                else rf = launch_bwd_fused_tile<F16, _Float16, _Float16>(Pdx, Pdw, n_dx, st);
+            } else {
+                if (o32) rf = launch_bwd_fused_tile<BF16, float, float>(Pdx, Pdw, n_dx, st);
+                else if (split) rf = launch_bwd_fused_tile<BF16, __bf16, float>(Pdx, Pdw, n_dx, st);
+                else rf = launch_bwd_fused_tile<BF16, __bf16, __bf16>(Pdx, Pdw, n_dx, st);
+            }
+        } else if (f16) {
             if (o32) rf = launch_bwd_fused_tn<F16, float, float>(plan.TN, Pdx, Pdw, st);
             else if (split) rf = launch_bwd_fused_tn<F16, _Float16, float>(plan.TN, Pdx, Pdw, st);
             else rf = launch_bwd_fused_tn<F16, _Float16, _Float16>(plan.TN, Pdx, Pdw, st);

@@ -16,7 +16,9 @@ CASES = [
     # M, K, N, BM, BK, dtype, p, seed, dX kernel forced persistent
     (1024, 512, 512, 128, 128, "bf16", 0.5, 1, False),    # one launch: one kept block per dX tile, 8 dW tiles
     (1536, 256, 512, 128, 128, "f16", 0.3, 2, False),     # one launch; the dW part writes split fp32 planes, a summing pass follows
-    (2560, 2560, 256, 128, 128, "bf16", 0.1, 3, True),    # one launch: dX tiles of two kept blocks
+    (2560, 2560, 256, 128, 128, "bf16", 0.1, 3, True),    # one launch: dX tiles of two kept blocks, persistent form
+    (2560, 2560, 256, 128, 128, "f16", 0.1, 13, False),   # one launch: dX tiles of two kept blocks, a workgroup per tile
+    (1536, 1536, 512, 128, 128, "bf16", 0.0, 14, False),  # the same with nothing dropped and a split dW
     (4096, 1024, 256, 128, 128, "f16", 0.7, 4, False),    # one launch: more dX workgroups than kept blocks
     (512, 768, 328, 128, 128, "bf16", 0.3, 5, False),     # ragged N: two launches
     (384, 512, 256, 64, 64, "f16", 0.5, 6, False),        # 64 x 64 blocks: two launches
