@@ -152,3 +152,29 @@ def test_gate_never_reads_dropped_blocks_and_no_tail_is_the_plain_call():
                             (sdrop.sdrop_bwd_dx_ex, sdrop.sdrop_bwd_dx, (dY.cuda(), W.cuda())),
                             (sdrop.sdrop_bwd_dw_ex, sdrop.sdrop_bwd_dw, (X.cuda(), dY.cuda()))):
         assert torch.equal(ex(*args, m), plain(*args, m))
+
+
+@pytest.mark.parametrize("BM,BK,N", [(128, 128, 256), (64, 64, 136)])     # persistent kernels; per-tile kernels with ragged edges
+def test_tails_with_everything_dropped_and_nothing_dropped(BM, BK, N):
+    M, K = 4 * BM, 6 * BK
+    print("tail p=0 / p=1", BM, BK, N, flush=True)
+    X, W, dY = make_custom(M, K, N, "bf16", seed=77)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    bN, bK = _bias(N, 1).cuda(), _bias(K, 2).cuda()
+    # everything dropped: a bias is not added where there is no block; eq. (1) sees an empty X, so only the tail is left
+    m = sdrop.sdrop_mask(M, K, BM, BK, 1.0, 0, 0)
+    none = np.zeros((M // BM, K // BK), dtype=np.uint8)
+    for o in (sdrop.sdrop_producer(dYg, Wg, bK, m, act=sdrop.ACT_GELU_TANH),
+              sdrop.sdrop_bwd_dx_ex(dYg, Wg, m, bias=bK, act=sdrop.ACT_RELU, relu_mask=Xg)):
+        assert torch.count_nonzero(o).item() == 0 and not torch.signbit(o).any().item()
+    y = sdrop.sdrop_fwd_ex(Xg, Wg, m, bias=bN, act=sdrop.ACT_RELU, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    ref = sb.fwd_tail(f64(X), f64(W), none, BM, BK, 1.0, False, f64(bN.cpu()), sdrop.ACT_RELU)
+    assert np.array_equal(f64(y), np.broadcast_to(np.maximum(f64(bN.cpu()), 0.0), (M, N))) and np.array_equal(f64(y), ref)
+    # nothing dropped: the producer is a dense layer with bias and activation
+    m = sdrop.sdrop_mask(M, K, BM, BK, 0.0, 0, 0)
+    allk = np.ones((M // BM, K // BK), dtype=np.uint8)
+    o = sdrop.sdrop_producer(dYg, Wg, bK, m, act=sdrop.ACT_RELU, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_close(f64(o), np.maximum(f64(dY) @ f64(W).T + f64(bK.cpu()), 0.0), "dense producer")
+    assert_close(f64(o), sb.producer(f64(dY), f64(W), f64(bK.cpu()), allk, BM, BK, sdrop.ACT_RELU), "dense producer vs oracle")
