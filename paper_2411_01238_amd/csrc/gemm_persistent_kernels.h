@@ -1,0 +1,763 @@
+// The persistent forms of the three block-sparse GEMMs and the launches that hold both gradients (included by
+// sdrop_gemm.hip only; the design notes are at the top of that file).
+#ifndef SDROP_GEMM_PERSISTENT_KERNELS_H
+#define SDROP_GEMM_PERSISTENT_KERNELS_H
+#include "gemm_tile_kernel.h"
+
+namespace sdrop {
+namespace {
+
+// The computing side of a persistent kernel: one wavefront's accumulators and operand registers,
+// the MFMA schedule of one slice, and the epilogue.
+template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int WN> struct Compute {
+    static constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
+    static constexpr int A_BYTES = TM * TK * 2;
+    static constexpr int NM = MI * NI, NOPS = MI + NI;
+    // operand reads requested per MFMA (at least what fits the group)
+    static constexpr int RPM_MIN = ceil_div(NOPS, NM >= 4 ? NM - 2 : NM), RPM = 2 > RPM_MIN ? 2 : RPM_MIN;
+    static constexpr int ESZ = (int)sizeof(OutT);
+    static constexpr int STAGING = 32 * 128;         // output staging per wavefront: 32 rows of 128 bytes
+    static constexpr int NIP = 128 / (32 * ESZ);     // 32-column accumulator blocks per 128-byte row
+    static constexpr int NJ = NI / NIP;              // 128-byte column groups of the wavefront's sub-tile
+    static_assert(NI % NIP == 0, "a wavefront's columns must fill whole 128-byte rows");
+
+    typename In<T>::vec fa[2][MI], fb[2][NI];
+    f32x16 acc[MI][NI];
+    int wm, wn;
+
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+    }
+    // operands of the first quarter of the slice in stage `st`
+    __device__ __forceinline__ void first(const char *st)
+    {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) fa[0][mi] = read_frag<T, A_TR, TM>(st, wm * WTM + mi * 32, 0);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) fb[0][ni] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + ni * 32, 0);
+    }
+    // One slice: 4 quarters of NM MFMAs.  On entry the first quarter's operands are in flight to
+    // register set 0; each MFMA is followed by up to RPM operand reads for the next quarter, in the
+    // order that quarter's MFMAs (A index major) first use them: A0, B0 .. B(NI-1), A1 .. A(MI-1).
+    // After the first MFMAs of the last quarter comes the slice's barrier (every wavefront is done
+    // reading `cur`; the slice in `nx1` has landed), then the first operands of `nx1`.
+    __device__ __forceinline__ void slice(const char *cur, const char *nx1)
+    {
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<4>([&](auto gi) __attribute__((always_inline)) {
+            constexpr int g = decltype(gi)::value;
+            constexpr int NB = (g == 3 && NM >= 4) ? 2 : 0;   // MFMAs of the last quarter that precede the barrier
+            static_for<NM>([&](auto ci) __attribute__((always_inline)) {
+                constexpr int c = decltype(ci)::value;
+                constexpr int mi = c / NI, ni = c % NI, cb = g & 1, nb = (g + 1) & 1;
+                if constexpr (g == 3 && c == NB) {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
+                    __builtin_amdgcn_s_barrier();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[mi][ni] = In<T>::mfma(fb[cb][ni], fa[cb][mi], acc[mi][ni]);
+                constexpr int r0 = c < NB ? 0 : (c - NB) * RPM < NOPS ? (c - NB) * RPM : NOPS;
+                constexpr int r1 = c < NB ? 0 : (c - NB + 1) * RPM < NOPS ? (c - NB + 1) * RPM : NOPS;
+                static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
+                    constexpr int r = r0 + decltype(ri)::value;
+                    const char *st = g < 3 ? cur : nx1;
+                    constexpr int kk = g < 3 ? g + 1 : 0;
+                    if constexpr (r == 0) fa[nb][0] = read_frag<T, A_TR, TM>(st, wm * WTM, kk);
+                    else if constexpr (r <= NI) fb[nb][r - 1] = read_frag<T, B_TR, TN>(st + A_BYTES, wn * WTN + (r - 1) * 32, kk);
+                    else fa[nb][r - NI] = read_frag<T, A_TR, TM>(st, wm * WTM + (r - NI) * 32, kk);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    }
+    // Epilogue: scale in fp32, round once, park 32 rows x 128 bytes at a time in this wavefront's
+    // own piece of LDS (`reg`) and write them out as whole 128-byte lines.  The MFMAs took the
+    // operands swapped, so accumulator register 4q+e of lane l is row l%32, column 8q + 4(l/32) + e
+    // of its 32x32 block.  8-byte slot u of row r lies at slot u ^ (r & 15): the 8-byte writes of 32
+    // rows then spread over all banks, and a 16-byte read finds its two halves in one 16-byte
+    // piece, exchanged when r is odd.  dst(mi, nj) is the address of row 0 of the 32 x 128-byte
+    // piece (mi, nj) of the wavefront's sub-tile, or null if that piece is not to be written.
+    // With a tail, dst also reports the global column of the piece's first column.
+    //
+    // The tail's operands (bias values, and for 16-bit outputs the gate values, which lie where
+    // the outputs go) are requested by tail_prefetch, called with the same dst before the tile's
+    // last slice: their latency then hides behind that slice's MFMAs instead of adding to the
+    // epilogue, which nothing overlaps.
+    uint4 gate_r[MI * NJ][4];
+    f32x4 bias_r[NJ][NIP * 4];
+    template <class F> __device__ __forceinline__ void tail_prefetch(int64_t ldc, const Tail &tl, F &&dst)
+    {
+        const int lane = threadIdx.x & 63;
+        const int whalf = lane >> 5, rrow = lane >> 3, rch = lane & 7;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int nj = 0; nj < NJ; ++nj) {
+                int64_t gcol0 = 0;
+                char *const out = dst(mi, nj, gcol0);
+                if (!out) continue;                        // uniform
+                if (mi == 0 && tl.bias) {
+#pragma unroll
+                    for (int i = 0; i < NIP * 4; ++i)
+                        bias_r[nj][i] = *(const_f4)(uintptr_t)(tl.bias + gcol0 + (i >> 2) * 32 + 8 * (i & 3) + 4 * whalf);
+                }
+                if constexpr (ESZ == 2) {
+                    if (tl.aux) {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it)
+                            gate_r[mi * NJ + nj][it] = *reinterpret_cast<const uint4 *>(tl.aux + (out - tl.c0) + (int64_t)(it * 8 + rrow) * ldc + rch * 16);
+                    }
+                }
+            }
+    }
+    template <bool TAIL, class F> __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
+    {
+        const int lane = threadIdx.x & 63;
+        const int wrow = lane & 31, whalf = lane >> 5;
+        const int rrow = lane >> 3, rch = lane & 7;
+        const bool gate_rows = TAIL && ESZ == 2 && tl.aux != nullptr;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int nj = 0; nj < NJ; ++nj) {
+                int64_t gcol0 = 0;
+                char *const out = dst(mi, nj, gcol0);
+                if (!out) continue;                        // uniform
+#pragma unroll
+                for (int nl = 0; nl < NIP; ++nl)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16 &a = acc[mi][nj * NIP + nl];
+                        float v[4] = {a[4 * q] * scale, a[4 * q + 1] * scale, a[4 * q + 2] * scale, a[4 * q + 3] * scale};
+                        if constexpr (TAIL) {
+                            if (tl.bias) {
+                                const f32x4 bv = bias_r[nj][nl * 4 + q];
+                                v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
+                            }
+                            act4(tl.act, v);
+                            if constexpr (ESZ == 4) {
+                                if (tl.aux) {
+                                    // fp32 outputs: the gate matrix has 16-bit elements, read in the accumulator's layout
+                                    using E = typename In<T>::out16;
+                                    typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
+                                    const int c = 8 * q + 4 * whalf;             // column within the piece
+                                    const int64_t elem = (out - tl.c0) / ESZ + wrow * (ldc / ESZ) + c;
+                                    const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) v[e] = static_cast<float>(x[e]) > 0.f ? v[e] : 0.f;
+                                }
+                            }
+                        }
+                        const float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
+                        if constexpr (ESZ == 4) {
+                            // 16 bytes per lane: 16-byte slot 2q + half, exchanged as a whole with (row & 7)
+                            const int slot = (2 * q + whalf) ^ (wrow & 7);
+                            *reinterpret_cast<float4 *>(reg + wrow * 128 + slot * 16) = make_float4(v0, v1, v2, v3);
+                        } else {
+                            typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
+                            const out4 o = {static_cast<OutT>(v0), static_cast<OutT>(v1), static_cast<OutT>(v2), static_cast<OutT>(v3)};
+                            const int slot8 = (nl * 8 + 2 * q + whalf) ^ (wrow & 15);
+                            *reinterpret_cast<out4 *>(reg + wrow * 128 + slot8 * 8) = o;
+                        }
+                    }
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = it * 8 + rrow;
+                    uint4 v;
+                    if constexpr (ESZ == 4) {
+                        v = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
+                    } else {
+                        const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
+                        v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
+                        if constexpr (TAIL) {
+                            if (gate_rows) v = gate16<T>(v, gate_r[mi * NJ + nj][it]);
+                        }
+                    }
+                    store_out(out + (int64_t)row * ldc + rch * 16, v);
+                }
+            }
+    }
+};
+
+// s_waitcnt immediate that waits only for vector-memory operations (at most `vm` outstanding).
+constexpr int waitcnt_vm_only(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// FWD and DW for 128-row tiles without ragged edges, as a persistent kernel: one workgroup per
+// CU walks a fixed sequence of tiles, and the slices of consecutive tiles form ONE stream
+// through the three LDS stages.  The four loader wavefronts run two slices ahead of the four
+// computing wavefronts across tile boundaries, so the first operands of the next tile arrive
+// while the current tile is still being multiplied and stored; what the per-tile launch pays
+// for every tile (index look-ups, the latency of the first loads: about 4 us, against 25 us of
+// MFMAs per tile at 4096^3 with half the blocks kept) is paid once per workgroup.
+//
+// Tile sequence of workgroup w of G: tiles are numbered in the mask's schedule order (heaviest
+// block rows / columns first), and round k takes tile k*G + w (k even) or k*G + G-1-w (k odd),
+// so a workgroup that drew a heavy tile in one round draws a light one in the next.
+//
+// Synchronisation: slice g of the workgroup's stream lives in stage g % 3.  Barrier g is passed
+// by the computing wavefronts when they have read all of slice g, and by the loaders when their
+// part of slice g+1 has landed; the loaders issue slice g+2 (into the stage of slice g-1) after
+// barrier g-1.  One more barrier, before the first slice, publishes slice 0.  Both roles derive
+// the number of slices from the same mask lists, so they execute the same number of barriers.
+// (The body is a device function of the workgroup's index w among G, so that one launch can hold
+// the workgroups of two operations; see bwd_fused_kernel.)
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+__device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const int G, const int w)
+{
+    static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
+    constexpr int NW = WM * WN;
+    static_assert(NW == 4, "one computing and one loading wavefront per SIMD");
+    constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
+    constexpr bool A_KMAJ = (OP == FWD), A_TR = !A_KMAJ, B_TR = true;
+    constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int STAGES = 3, AHEAD = 2;
+    constexpr int ESZ = (int)sizeof(OutT);
+    constexpr int STAGING = 32 * 128;           // per computing wavefront: 32 rows of 128 bytes
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *const staging = smem + STAGES * STAGE_BYTES;
+
+    const MaskHeader *H = P.mv.hdr;
+    if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = wave_all >= NW;
+    const int wave = loader ? wave_all - NW : wave_all;
+    const int wm = wave / WN, wn = wave % WN;
+    const int total = P.total_tiles;
+    const int BLK = (OP == FWD) ? P.BK : P.BM;            // extent of a mask block along the reduction
+    const int sub_shift = (BLK == 128), sub_mask = (1 << sub_shift) - 1;
+    const int64_t lda = P.K * 2, ldb = P.N * 2, ldc = P.N * (int64_t)ESZ;
+    const int32_t *const order = (OP == FWD) ? P.mv.row_order : P.mv.col_order;
+    const int32_t *const ptr = (OP == FWD) ? P.mv.row_ptr : P.mv.col_ptr;
+    const int32_t *const lists = (OP == FWD) ? P.mv.col_idx : P.mv.row_idx;
+    const int per_line = P.n_tiles * P.splits;            // tiles per block row / column
+
+    // tile number of round k (may be >= total: the sequence has ended)
+    auto tile_of = [&](int k) __attribute__((always_inline)) -> int { return k * G + ((k & 1) ? G - 1 - w : w); };
+    // position in the schedule order; clamped so that look-ahead beyond the end stays in bounds
+    auto rank_of = [&](int t) __attribute__((always_inline)) -> int { return (t < total ? t : total - 1) / per_line; };
+    // the part of a kept list of `cnt` entries that tile t reduces: [lo, lo + len)
+    auto part_of = [&](int t, int cnt, int &lo) __attribute__((always_inline)) -> int {
+        if (P.splits == 1) { lo = 0; return cnt; }
+        const int part = t % P.splits;
+        lo = (int)((int64_t)cnt * part / P.splits);
+        return (int)((int64_t)cnt * (part + 1) / P.splits) - lo;
+    };
+    auto stage_ptr = [&](int st) __attribute__((always_inline)) -> char * { return smem + st * STAGE_BYTES; };
+
+    if (loader) {
+        // ---------------- loaders: the stream of slices ----------------
+        using DmaA = typename std::conditional<A_KMAJ, DmaK<TM, 1, NW>, DmaT<TM, NW>>::type;
+        using DmaB = DmaT<TN, NW>;
+        DmaA da;
+        DmaB db;
+        da.init(lda, wave);
+        db.init(ldb, wave);
+        constexpr int NDMA_A = TM / (8 * NW), NDMA_B = TN / (8 * NW), NDMA = NDMA_A + NDMA_B;
+
+        // Look-ups run three tiles ahead of the tile being issued, one level of indirection per
+        // tile, so that no load waits for the one before it: order[] of tile k+3, the list bounds
+        // of tile k+2, the first two list entries of tile k+1.
+        // The mask lists do not change while the kernel runs: read through the constant address
+        // space they keep the scalar load form also after a barrier (which otherwise counts as a
+        // possible write to anything in global memory).
+        typedef const __attribute__((address_space(4))) int32_t *const_i32;
+        const const_i32 k_order = (const_i32)(uintptr_t)order, k_ptr = (const_i32)(uintptr_t)ptr;
+        const const_i32 k_lists = (const_i32)(uintptr_t)lists;
+        struct Meta { int t, ord, start, len, e0, e1; };
+        auto level1 = [&](int k) __attribute__((always_inline)) -> Meta {
+            Meta m;
+            m.t = tile_of(k);
+            m.ord = k_order[rank_of(m.t)];
+            m.start = m.len = m.e0 = m.e1 = 0;
+            return m;
+        };
+        auto level2 = [&](Meta &m) __attribute__((always_inline)) {
+            const int p0 = k_ptr[m.ord], cnt = k_ptr[m.ord + 1] - p0;
+            int lo;
+            m.len = part_of(m.t < total ? m.t : total - 1, cnt, lo);
+            m.start = p0 + lo;
+        };
+        auto entry = [&](const Meta &m, int e) __attribute__((always_inline)) -> int {
+            const int ec = e < m.len ? e : m.len - 1;
+            return k_lists[ec < 0 ? 0 : m.start + ec];
+        };
+        auto level3 = [&](Meta &m) __attribute__((always_inline)) { m.e0 = entry(m, 0); m.e1 = entry(m, 1); };
+
+        Meta cur, n1, n2, n3;
+        n1 = level1(0); level2(n1); level3(n1);
+        n2 = level1(1); level2(n2);
+        n3 = level1(2);
+        int k = -1;                      // round of the tile being issued
+        int s = 0, nsteps = 0;           // next slice of that tile; its number of slices
+        int e_cur = 0, e_nxt = 0;        // list entries of slice s and of the block after it
+        const char *a_tile = nullptr, *b_tile = nullptr;
+        bool ended = false;
+
+        // issues the next slice of the stream into stage `st`; false when the stream has ended
+        auto issue_next = [&](int st) __attribute__((always_inline)) -> bool {
+            while (s == nsteps) {
+                if (ended) return false;
+                ++k;
+                cur = n1;
+                if (cur.t >= total) { ended = true; return false; }
+                n1 = n2; level3(n1);
+                n2 = n3; level2(n2);
+                n3 = level1(k + 3);
+                s = 0;
+                nsteps = cur.len << sub_shift;
+                e_cur = cur.e0; e_nxt = cur.e1;
+                const int line = cur.t % per_line;
+                const int nt = line / P.splits;
+                if constexpr (OP == FWD) a_tile = P.A + (int64_t)cur.ord * P.BM * lda;
+                else a_tile = P.A + (int64_t)cur.ord * P.BK * 2;
+                b_tile = P.B + (int64_t)nt * TN * 2;
+            }
+            const int64_t off = (int64_t)e_cur * BLK + (int64_t)(s & sub_mask) * TK;
+            const char *const sa[1] = {a_tile + off * (OP == FWD ? 2 : lda)};
+            const char *const sb[1] = {b_tile + off * ldb};
+            char *stp = stage_ptr(st);
+#pragma unroll
+            for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+#pragma unroll
+            for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+            ++s;
+            if ((s & sub_mask) == 0) {
+                e_cur = e_nxt;
+                e_nxt = entry(cur, (s >> sub_shift) + 1);
+            }
+            return true;
+        };
+
+        int issued = 0, st_issue = 0;
+        for (int i = 0; i < AHEAD; ++i)
+            if (issue_next(st_issue)) { ++issued; st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1; }
+        if (issued == 0) return;         // no slice at all: the computing wavefronts meet no barrier either
+        if (issued == AHEAD) __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+        __builtin_amdgcn_s_barrier();    // slice 0 is in place
+        for (int g = 0; g < issued; ++g) {
+            const bool more = issue_next(st_issue);
+            if (more) {
+                ++issued;
+                st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1;
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));      // all but the slice just issued: g+1 is in
+            } else {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+            }
+            __builtin_amdgcn_s_barrier();
+        }
+        return;
+    }
+
+    // ---------------- computing wavefronts ----------------
+    // Look-ups two tiles ahead (order[] of tile k+2, list bounds of tile k+1), as vector loads:
+    // they are waited for with the vector-memory counter, which the main loop never waits on.
+    // Every look-up is turned into a scalar right after a tile's slices, BEFORE the tile's stores:
+    // the counter is in order, so a wait placed after the stores (the top of the next iteration)
+    // would also wait until those stores have drained to memory.
+    auto c_order = [&](int k) __attribute__((always_inline)) -> int { return order[rank_of(tile_of(k))]; };
+    auto c_count = [&](int o) __attribute__((always_inline)) -> int { return ptr[o + 1] - ptr[o]; };
+    auto c_len = [&](int k, int cnt) __attribute__((always_inline)) -> int {
+        const int tk = tile_of(k);
+        int lo;
+        return part_of(tk < total ? tk : total - 1, cnt, lo);
+    };
+    // scalars: this tile (ord0, len0), the next one's block row / column (ord1);
+    // in flight: the next tile's kept count (cnt1_v), order[] of the tile after it (ord2_v)
+    int ord0 = uni(c_order(0));
+    int len0 = uni(c_len(0, c_count(ord0)));
+    int ord1 = uni(c_order(1));
+    int ord2_v = c_order(2);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+    int ord2 = uni(ord2_v);
+
+    Compute<T, OutT, A_TR, B_TR, TM, TN, WM, WN> cw;
+    cw.wm = wm; cw.wn = wn;
+    int st0 = 0, st1 = 1, st2 = 2;       // stages of the stream's slices g, g+1, g+2
+    bool started = false;
+    const float scale = P.scale;
+    const Tail tl = make_tail(P);
+    char *const reg = staging + wave * STAGING;
+
+    for (int k = 0;; ++k) {
+        const int t = tile_of(k);
+        if (t >= total) break;
+        const int ord = ord0, nsteps = len0 << sub_shift;
+        GEMM_TICKW(k * 4);
+        // requests for the tiles after this one; consumed after this tile's slices
+        const int cnt1_v = c_count(ord1);
+        const int ord3_v = c_order(k + 3);
+
+        cw.zero();
+        if (nsteps > 0 && !started) {
+            started = true;
+            __builtin_amdgcn_s_barrier();                     // slice 0 is in place
+            cw.first(stage_ptr(0));
+        }
+        const int line = t % per_line;
+        const int nt = line / P.splits, part = line % P.splits;
+        char *c_tile;
+        if constexpr (OP == FWD) c_tile = P.C + (int64_t)ord * P.BM * ldc + (int64_t)nt * TN * ESZ;
+        else c_tile = P.C + (int64_t)part * P.K * ldc + (int64_t)ord * P.BK * ldc + (int64_t)nt * TN * ESZ;
+        c_tile += (int64_t)(wm * WTM) * ldc + (int64_t)(wn * WTN) * ESZ;
+        auto dst = [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
+            gcol0 = (int64_t)nt * TN + wn * WTN + nj * (128 / ESZ);
+            return c_tile + (int64_t)(mi * 32) * ldc + nj * 128;
+        };
+        for (int s = 0; s < nsteps; ++s) {
+            cw.slice(stage_ptr(st0), stage_ptr(st1));
+            const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+            if (s == 0) GEMM_TICKW(k * 4 + 1);
+        }
+        // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+        len0 = uni(c_len(k + 1, cnt1_v));
+        ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
+        if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
+        GEMM_TICKW(k * 4 + 2);
+        cw.template store<TAIL>(reg, scale, ldc, tl, dst);
+        GEMM_TICKW(k * 4 + 3);
+    }
+}
+
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
+{
+    gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
+}
+
+// a[i] for a uniform index i in 0..3, as selects (keeps everything in scalar registers)
+__device__ __forceinline__ int sel4(const int (&a)[4], int i)
+{
+    return i == 0 ? a[0] : i == 1 ? a[1] : i == 2 ? a[2] : a[3];
+}
+
+// dX for 128-row tiles without a ragged reduction tail, as a persistent kernel (same stream of
+// slices, stages and barrier protocol as gemm_persistent_kernel; every tile reduces over all of N,
+// so every tile has the same number of slices).
+//
+// Work units are groups of G = TN / BK consecutive entries of a kept-block list: the locally
+// ordered one for G = 1, the row-major one for G > 1 (consecutive entries then share the block
+// row).  A group whose entries lie in one block row is one tile; where the row changes inside a
+// group it is cut into one tile per run of equal rows.  The groups are dealt out in equal
+// contiguous chunks to the XCDs (workgroup w runs on XCD w mod 8) and round-robin inside a
+// chunk, so that the tiles an XCD has in flight at one time are neighbours in the list.
+// Both roles read the same list entries and derive the same tiles from them.
+//
+// Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; its loader
+// wavefronts write them a kilobyte per slice of the stream, beside the direct loads, and finish
+// what is left when the stream has ended.
+template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+__device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, const int G, const int w)
+{
+    constexpr int NW = WM * WN;
+    static_assert(NW == 4 && TM == 128, "one computing and one loading wavefront per SIMD, 128-row tiles");
+    constexpr int WTM = TM / WM, WTN = TN / WN;
+    constexpr int DXG = TN / 64;                      // 64-column chunks of a tile
+    static_assert(DXG <= 4, "tile too wide");
+    constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int STAGES = 3, AHEAD = 2;
+    constexpr int ESZ = (int)sizeof(OutT);
+    constexpr int STAGING = 32 * 128;
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *const staging = smem + STAGES * STAGE_BYTES;
+
+    const MaskHeader *H = P.mv.hdr;
+    if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = wave_all >= NW;
+    const int wave = loader ? wave_all - NW : wave_all;
+    const int wm = wave / WN, wn = wave % WN;
+    const int GB = TN / P.BK;                          // kept blocks per group: 1, 2 or 4
+    const int cshift = (P.BK == 128), cmask = (1 << cshift) - 1;   // 64-column chunks per block
+    const int nnz = H->nnz;
+    const int ngroups = (nnz + GB - 1) / GB;
+    const int nsteps = (int)(P.N / TK);
+    const int64_t lda = P.N * 2, ldb = P.N * 2, ldc = P.K * (int64_t)ESZ;
+    const int32_t *const rows = GB == 1 ? P.mv.loc_row : P.mv.blk_row;
+    const int32_t *const cols = GB == 1 ? P.mv.loc_col : P.mv.col_idx;
+    // this workgroup's groups: chunk x of the list, local indices r, r + wx, r + 2 wx, ...
+    const int nx = G < 8 ? G : 8;
+    const int x = w % nx, r = w / nx;
+    const int wx = (G - x + nx - 1) / nx;              // workgroups that share chunk x
+    const int per_chunk = (ngroups + nx - 1) / nx;
+    // group of round k, or -1 when the workgroup has no more
+    auto group_of = [&](int k) __attribute__((always_inline)) -> int {
+        const int lr = r + k * wx;
+        const int u = x * per_chunk + lr;
+        return (lr < per_chunk && u < ngroups) ? u : -1;
+    };
+    auto stage_ptr = [&](int st) __attribute__((always_inline)) -> char * { return smem + st * STAGE_BYTES; };
+    struct Group { int u, n; int r[4], c[4]; };        // list entries [u GB, u GB + n)
+
+    if (loader) {
+        DmaK<TM, 1, NW> da;
+        DmaK<TN, DXG, NW> db;
+        da.init(lda, wave);
+        db.init(ldb, wave);
+        constexpr int NDMA_A = TM / (8 * NW), NDMA_B = TN / (8 * NW), NDMA = NDMA_A + NDMA_B;
+        typedef const __attribute__((address_space(4))) int32_t *const_i32;   // see gemm_persistent_kernel
+        const const_i32 k_rows = (const_i32)(uintptr_t)rows, k_cols = (const_i32)(uintptr_t)cols;
+        auto load_group = [&](int k) __attribute__((always_inline)) -> Group {
+            Group g;
+            g.u = group_of(k);
+            const int e0 = (g.u < 0 ? 0 : g.u) * GB;
+            g.n = g.u < 0 ? 0 : (nnz - e0 < GB ? nnz - e0 : GB);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int e = e0 + (b < g.n ? b : 0);   // always a valid entry (the lists hold at least one slot)
+                g.r[b] = k_rows[e < nnz ? e : 0];
+                g.c[b] = k_cols[e < nnz ? e : 0];
+            }
+            return g;
+        };
+        Group cur, nxt;
+        cur.u = -1; cur.n = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) cur.r[b] = cur.c[b] = 0;
+        nxt = load_group(0);
+        int k = -1, a = 0;                              // round of `cur`; next unused entry of `cur`
+        int s = nsteps;                                 // next slice of the tile being issued
+        const char *a_tile = nullptr;
+        const char *bgrp[DXG];
+#pragma unroll
+        for (int g = 0; g < DXG; ++g) bgrp[g] = nullptr;
+        bool ended = false;
+
+        auto issue_next = [&](int st) __attribute__((always_inline)) -> bool {
+            if (s == nsteps) {
+                if (ended) return false;
+                if (a >= cur.n) {
+                    ++k;
+                    cur = nxt;
+                    if (cur.u < 0) { ended = true; return false; }
+                    nxt = load_group(k + 1);
+                    a = 0;
+                }
+                const int row = sel4(cur.r, a);
+                int nb = 1;
+                while (a + nb < cur.n && sel4(cur.r, a + nb) == row) ++nb;
+                a_tile = P.A + (int64_t)row * P.BM * lda;
+#pragma unroll
+                for (int g = 0; g < DXG; ++g) {
+                    const int bb = g >> cshift;         // a missing block repeats the last one
+                    const int col = sel4(cur.c, a + (bb < nb ? bb : nb - 1));
+                    bgrp[g] = P.B + ((int64_t)col * P.BK + (g & cmask) * 64) * ldb;
+                }
+                a += nb;
+                s = 0;
+            }
+            const int64_t off = (int64_t)s * TK * 2;
+            const char *const sa[1] = {a_tile + off};
+            const char *sb[DXG];
+#pragma unroll
+            for (int g = 0; g < DXG; ++g) sb[g] = bgrp[g] + off;
+            char *stp = stage_ptr(st);
+#pragma unroll
+            for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+#pragma unroll
+            for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+            ++s;
+            return true;
+        };
+
+        // Zero fill of the dropped blocks, by the loaders: the workgroup owns positions w, w + G, ...
+        // (z-th: w + G z).  One step per slice of the stream: either test the next position's keep
+        // bit (its word was requested a step earlier, as a scalar load through the constant address
+        // space) or write this wavefront's next kilobyte of the dropped block in hand (a block is
+        // TM rows of BK elements; the four loaders share its 16-byte pieces).  The computing
+        // wavefronts never stop for it.  The stores go out before the step's direct loads, so the
+        // wait that follows those loads still means "the slice issued one step ago has landed".
+        typedef const __attribute__((address_space(4))) uint64_t *const_u64;
+        const const_u64 k_bits = (const_u64)(uintptr_t)P.mv.bits;
+        const int total_pos = P.MB * P.KB;
+        const int nz = w < total_pos ? (total_pos - w + G - 1) / G : 0;
+        const int wpr = H->words_per_row;
+        const int row_chunks = P.BK * ESZ / 16;                      // 16-byte pieces per row of a block
+        const int per_wave = TM * row_chunks / (NW * 64);           // store instructions per wavefront and block
+        int zpos = 0;                    // next position to test
+        int zprog = 0;                   // store instructions already issued for the block in hand
+        char *zblock = nullptr;          // the dropped block in hand, or null
+        uint64_t zword = 0;              // keep bits around position zpos (valid when zpos < nz)
+        auto request_word = [&]() __attribute__((always_inline)) {
+            if (zpos < nz) {
+                const int pz = w + G * zpos;
+                zword = k_bits[(int64_t)(pz / P.KB) * wpr + ((pz % P.KB) >> 6)];
+            }
+        };
+        request_word();
+        // true while there is zero fill left
+        auto zero_step = [&]() __attribute__((always_inline)) -> bool {
+            if (zblock) {
+                const int c = (zprog * NW + wave) * 64 + lane;
+                store_out(zblock + (c / row_chunks) * ldc + (c % row_chunks) * 16, make_uint4(0, 0, 0, 0));
+                if (++zprog == per_wave) zblock = nullptr;
+                return true;
+            }
+            if (zpos >= nz) return false;
+            const int pz = w + G * zpos;
+            const int zi = pz / P.KB, zj = pz % P.KB;
+            if (!((zword >> (zj & 63)) & 1)) {
+                zblock = P.C + (int64_t)zi * P.BM * ldc + (int64_t)zj * P.BK * ESZ;
+                zprog = 0;
+            }
+            ++zpos;
+            request_word();
+            return true;
+        };
+
+        int issued = 0, st_issue = 0;
+        for (int i = 0; i < AHEAD; ++i)
+            if (issue_next(st_issue)) { ++issued; st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1; }
+        if (issued > 0) {
+            if (issued == AHEAD) __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+            else __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+            __builtin_amdgcn_s_barrier();
+            for (int g = 0; g < issued; ++g) {
+                zero_step();
+                const bool more = issue_next(st_issue);
+                if (more) {
+                    ++issued;
+                    st_issue = st_issue == STAGES - 1 ? 0 : st_issue + 1;
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(NDMA));
+                } else {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+                }
+                __builtin_amdgcn_s_barrier();
+            }
+        }
+        // what the stream left of the zero fill (all of it for a workgroup without tiles)
+        while (zero_step()) { }
+        return;
+    }
+
+    // ---------------- computing wavefronts ----------------
+    auto c_load_group = [&](int k) __attribute__((always_inline)) -> Group {
+        Group g;
+        g.u = group_of(k);
+        const int e0 = (g.u < 0 ? 0 : g.u) * GB;
+        g.n = g.u < 0 ? 0 : (nnz - e0 < GB ? nnz - e0 : GB);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int e = e0 + (b < g.n ? b : 0);
+            g.r[b] = rows[e < nnz ? e : 0];
+            g.c[b] = cols[e < nnz ? e : 0];
+        }
+        return g;
+    };
+    Compute<T, OutT, false, false, TM, TN, WM, WN> cw;
+    cw.wm = wm; cw.wn = wn;
+    int st0 = 0, st1 = 1, st2 = 2;
+    bool started = false;
+    const float scale = P.scale;
+    const Tail tl = make_tail(P);
+    char *const reg = staging + wave * STAGING;
+
+    // Every look-up (the next group's entries) is turned
+    // into scalars right after a tile's slices, BEFORE the tile's stores: the vector-memory counter is
+    // in order, so a wait placed after the stores would also wait until they have drained to memory
+    // (measured: 2.4 us per tile on 65536 x 4096 x 1024).
+    Group nxt = c_load_group(0);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+    int gr[4], gc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) { gr[b] = uni(nxt.r[b]); gc[b] = uni(nxt.c[b]); }
+    int gn = nxt.n, gu = nxt.u;
+    int tick_no = 0;        // timing builds only: tiles done by this workgroup
+    for (int k = 0; gu >= 0; ++k) {
+        nxt = c_load_group(k + 1);                      // in flight during this group's tiles
+        int ngr[4] = {0, 0, 0, 0}, ngc[4] = {0, 0, 0, 0};
+        int a = 0;
+        while (a < gn) {
+            const int row = sel4(gr, a);
+            int nb = 1;
+            while (a + nb < gn && sel4(gr, a + nb) == row) ++nb;
+            const int chunks_valid = nb << cshift;
+
+            cw.zero();
+            if (!started) {
+                started = true;
+                __builtin_amdgcn_s_barrier();           // slice 0 is in place
+                cw.first(stage_ptr(0));
+            }
+            char *const c_rows = P.C + ((int64_t)row * P.BM + wm * WTM) * ldc;
+            auto dst = [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
+                const int col_t = wn * WTN + nj * (128 / ESZ);         // first column of the piece, in the tile
+                const int g = col_t >> 6;
+                if (g >= chunks_valid) return nullptr;
+                const int col = sel4(gc, a + (g >> cshift));
+                const int64_t col0 = (int64_t)col * P.BK + (g & cmask) * 64 + (col_t & 63);
+                gcol0 = col0;
+                return c_rows + (int64_t)(mi * 32) * ldc + col0 * ESZ;
+            };
+            GEMM_TICKW(tick_no * 4);
+            for (int s = 0; s < nsteps; ++s) {
+                cw.slice(stage_ptr(st0), stage_ptr(st1));
+                const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+            }
+            GEMM_TICKW(tick_no * 4 + 1);
+            // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) { ngr[b] = uni(nxt.r[b]); ngc[b] = uni(nxt.c[b]); }
+            if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
+            cw.template store<TAIL>(reg, scale, ldc, tl, dst);
+            GEMM_TICKW(tick_no * 4 + 2);
+            GEMM_TICKW(tick_no * 4 + 3);
+            ++tick_no;
+            a += nb;
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) { gr[b] = ngr[b]; gc[b] = ngc[b]; }
+        gn = nxt.n; gu = nxt.u;
+    }
+}
+
+template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+__global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
+{
+    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
+}
+
+// Both gradients of the layer in one launch (eq. 2 and eq. 3 share dY and the mask and do not
+// depend on each other): workgroups [0, g_dx) are the persistent dX kernel, the rest the persistent
+// dW kernel.  One workgroup fits a CU, so the dW workgroups start one by one on the CUs that the dX
+// workgroups leave: no launch boundary (about 5 us of idle chip between dependent launches) and no
+// idle tail between the two.  The dX workgroups come first, so dX workgroup w is workgroup w of
+// the launch and runs on XCD w % 8, which its schedule assumes; the dW schedule assumes nothing.
+template <class T, class OutDX, class OutDW, int TN_DX>
+__global__ __launch_bounds__(512) void bwd_fused_kernel(GemmParams Pdx, GemmParams Pdw, int g_dx)
+{
+    if ((int)blockIdx.x < g_dx)
+        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, false>(Pdx, g_dx, (int)blockIdx.x);
+    else
+        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
+}
+
+// The same where dX runs one workgroup per tile (tiles of two kept blocks that are too few per CU
+// for the persistent kernel): workgroups [0, n_dx) are those tiles, in the order of the separate
+// launch, the rest the persistent dW kernel.
+template <class T, class OutDX, class OutDW>
+__global__ __launch_bounds__(512) void bwd_fused_tile_kernel(GemmParams Pdx, GemmParams Pdw, int n_dx)
+{
+    if ((int)blockIdx.x < n_dx)
+        gemm_tile_body<DX, T, OutDX, 128, 256, 2, 2, false, true, false>(Pdx, (int)blockIdx.x);
+    else
+        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - n_dx, (int)blockIdx.x - n_dx);
+}
+
+}  // namespace
+}  // namespace sdrop
+#endif
