@@ -242,13 +242,20 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  *   act         SDROP_ACT_NONE, SDROP_ACT_RELU (max(v,0)), SDROP_ACT_GELU_TANH
  *               (0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))), the "tanh" form of GELU)
  *   bias        device, fp32[number of output columns], 16-byte aligned, or NULL
- *   relu_mask   device, a matrix of type `dtype` with the output's shape, 16-byte aligned, or
- *               NULL: where it is not > 0 the output is +-0 (the backward of a ReLU, given
- *               the ReLU's output).  Its dropped blocks are never read.
+ *   relu_mask   device, a matrix of type `dtype` with the output's shape (and the output's
+ *               leading dimension), 16-byte aligned, or NULL: where it is not > 0 the output is
+ *               +-0 (the backward of a ReLU, given the ReLU's output).  Its dropped blocks are
+ *               never read.
+ *   ld_a, ld_b, ld_out   leading dimensions, in elements, of the first matrix argument, the
+ *               second one and the output (row r starts r * ld elements after the pointer);
+ *               0 = contiguous.  A leading dimension must be at least the number of columns, a
+ *               multiple of 8 and at most 2^24, else SDROP_ESHAPE.  This is how a column range
+ *               of a wider matrix (a slice of a fused QKV or gate/up projection, a padded buffer)
+ *               is passed without a copy.  sdrop_bwd_dw_ex takes them too.
  *
  * sdrop_fwd_ex / sdrop_bwd_dx_ex / sdrop_bwd_dw_ex are sdrop_fwd / sdrop_bwd_dx / sdrop_bwd_dw
- * with such a tail (epi = NULL: exactly those).  sdrop_bwd_dw_ex takes scale_mode only and
- * returns SDROP_EINVAL for anything else; bad enum values give SDROP_EINVAL, a misaligned bias
+ * with such a tail (epi = NULL: exactly those).  sdrop_bwd_dw_ex takes scale_mode and the leading
+ * dimensions only and returns SDROP_EINVAL for a bias, an activation or a relu_mask; bad enum values give SDROP_EINVAL, a misaligned bias
  * or relu_mask SDROP_EALIGN.  Dropped blocks of sdrop_bwd_dx_ex's output are +0 whatever the tail.
  */
 enum { SDROP_SCALE_DROPOUT = 0, SDROP_SCALE_ONE = 1 };
@@ -259,6 +266,7 @@ typedef struct sdrop_epilogue {
     int32_t act;
     const float *bias;
     const void *relu_mask;
+    int64_t ld_a, ld_b, ld_out;
 } sdrop_epilogue_t;
 
 int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,

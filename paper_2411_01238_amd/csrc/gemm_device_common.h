@@ -80,6 +80,7 @@ struct GemmParams {
     char *C;            // FWD: Y   DX: dX  DW: dW
     MaskView mv;
     int64_t M, K, N;
+    int64_t lda, ldb, ldc;   // bytes between consecutive rows of A, B and C (contiguous: columns * element size)
     int32_t BM, BK, MB, KB;
     int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
     int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)

@@ -234,7 +234,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     const int total = P.total_tiles;
     const int BLK = (OP == FWD) ? P.BK : P.BM;            // extent of a mask block along the reduction
     const int sub_shift = (BLK == 128), sub_mask = (1 << sub_shift) - 1;
-    const int64_t lda = P.K * 2, ldb = P.N * 2, ldc = P.N * (int64_t)ESZ;
+    const int64_t lda = P.lda, ldb = P.ldb, ldc = P.ldc;
     const int32_t *const order = (OP == FWD) ? P.mv.row_order : P.mv.col_order;
     const int32_t *const ptr = (OP == FWD) ? P.mv.row_ptr : P.mv.col_ptr;
     const int32_t *const lists = (OP == FWD) ? P.mv.col_idx : P.mv.row_idx;
@@ -485,7 +485,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     const int nnz = H->nnz;
     const int ngroups = (nnz + GB - 1) / GB;
     const int nsteps = (int)(P.N / TK);
-    const int64_t lda = P.N * 2, ldb = P.N * 2, ldc = P.K * (int64_t)ESZ;
+    const int64_t lda = P.lda, ldb = P.ldb, ldc = P.ldc;
     const int32_t *const rows = GB == 1 ? P.mv.loc_row : P.mv.blk_row;
     const int32_t *const cols = GB == 1 ? P.mv.loc_col : P.mv.col_idx;
     // this workgroup's groups: chunk x of the list, local indices r, r + wx, r + 2 wx, ...

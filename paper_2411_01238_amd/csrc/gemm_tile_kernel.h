@@ -73,7 +73,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
         list_len = uni(P.mv.row_ptr[i + 1]) - rp;
         sub_shift = (P.BK == 128);
         nsteps = list_len << sub_shift;
-        lda = P.K * esz; ldb = P.N * esz; ldc = P.N * (int64_t)sizeof(OutT);
+        lda = P.lda; ldb = P.ldb; ldc = P.ldc;
         a_tile = P.A + (int64_t)i * P.BM * lda;
         b_tile = P.B + (int64_t)nt * TN * esz;
         c_tile = P.C + (int64_t)i * P.BM * ldc + (int64_t)nt * TN * sizeof(OutT);
@@ -93,7 +93,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
         list_len = hi - lo;
         sub_shift = (P.BM == 128);
         nsteps = list_len << sub_shift;
-        lda = P.K * esz; ldb = P.N * esz; ldc = P.N * (int64_t)sizeof(OutT);
+        lda = P.lda; ldb = P.ldb; ldc = P.ldc;
         a_tile = P.A + (int64_t)j * P.BK * esz;
         b_tile = P.B + (int64_t)nt * TN * esz;
         // with a split list, part `part` writes its own K x N plane of partial sums
@@ -101,7 +101,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
         { const int64_t left = P.N - (int64_t)nt * TN; c_lim = left < TN ? (int)left : TN; }
     } else {
         const int G_ = TN / P.BK;                     // kept blocks gathered into one tile
-        lda = P.N * esz; ldb = P.N * esz; ldc = P.K * (int64_t)sizeof(OutT);
+        lda = P.lda; ldb = P.ldb; ldc = P.ldc;
         const int cshift = (P.BK == 128);             // 64-column chunks per block, log2
         const int row_chunks = P.BK * (int)sizeof(OutT) / 16;
         auto zero_block = [&](int zi, int zj) __attribute__((always_inline)) {

@@ -162,10 +162,12 @@ int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
 
 // out[e] = scale * sum_c part[c][e], rounded once (the second pass of a split DW)
 template <class OutT>
-__global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, OutT *out, int64_t n, int splits, float scale)
+__global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, OutT *out_base, int64_t n, int splits, float scale,
+                                                           int64_t ncols, int64_t ld)
 {
     const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= n) return;
+    OutT *const out = out_base + (e / ncols) * (ld - ncols);       // row e / ncols of an output with `ld` elements per row (4 | ncols)
     float4 acc = *reinterpret_cast<const float4 *>(part + e);
     for (int c = 1; c < splits; ++c) {
         const float4 v = *reinterpret_cast<const float4 *>(part + (int64_t)c * n + e);
@@ -307,8 +309,8 @@ bool tile_count_ok(int64_t N, const sdrop_mask_layout_t &L)
     return lines * n_tiles * 16 <= INT32_MAX;
 }
 
-GemmParams base_params(const void *a, const void *b, const void *mask, void *out,
-                       int64_t M, int64_t K, int64_t N, int BM, int BK, double p, const sdrop_mask_layout_t &L)
+GemmParams base_params(int op, const void *a, const void *b, const void *mask, void *out,
+                       int64_t M, int64_t K, int64_t N, int BM, int BK, double p, int out_dtype, const sdrop_mask_layout_t &L)
 {
     GemmParams P;
     P.A = static_cast<const char *>(a);
@@ -316,6 +318,14 @@ GemmParams base_params(const void *a, const void *b, const void *mask, void *out
     P.C = static_cast<char *>(out);
     P.mv = make_view(mask, L);
     P.M = M; P.K = K; P.N = N; P.BM = BM; P.BK = BK;
+    {
+        // contiguous operands: A is X[M,K] (FWD, DW) or dY[M,N] (DX); B is W[K,N] (FWD, DX) or dY[M,N] (DW);
+        // C is Y[M,N], dX[M,K] or dW[K,N]
+        const int64_t esz_out = out_dtype == SDROP_F32 ? 4 : 2;
+        P.lda = (op == DX ? N : K) * 2;
+        P.ldb = N * 2;
+        P.ldc = (op == DX ? K : N) * esz_out;
+    }
     P.MB = (int32_t)L.MB; P.KB = (int32_t)L.KB;
     P.n_tiles = 0;
     P.splits = 1;
@@ -327,16 +337,17 @@ GemmParams base_params(const void *a, const void *b, const void *mask, void *out
 }
 
 // sums the fp32 planes of a split DW into the output (second pass)
-int launch_reduce(const void *ws, void *out, int64_t n, int splits, float scale, int dtype, int out_dtype, hipStream_t st)
+int launch_reduce(const void *ws, void *out, int64_t n, int splits, float scale, int dtype, int out_dtype, hipStream_t st,
+                  int64_t ncols, int64_t ld)
 {
     const unsigned grid = (unsigned)((n / 4 + 255) / 256);
     const float *part = static_cast<const float *>(ws);
     if (out_dtype == SDROP_F32)
-        hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, splits, scale);
+        hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, splits, scale, ncols, ld);
     else if (dtype == SDROP_F16)
-        hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, splits, scale);
+        hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, splits, scale, ncols, ld);
     else
-        hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, splits, scale);
+        hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, splits, scale, ncols, ld);
     return hip_status(hipGetLastError());
 }
 
@@ -354,14 +365,22 @@ int run(const void *a, const void *b, const void *mask, void *out,
         // the gradient of the weights takes a scale only
         if (OP == DW && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask)) return SDROP_EINVAL;
         if ((reinterpret_cast<uintptr_t>(epi->bias) | reinterpret_cast<uintptr_t>(epi->relu_mask)) % 16) return SDROP_EALIGN;
+        // leading dimensions: 0 = contiguous; else at least the row length, rows 16-byte aligned, lane offsets 32-bit
+        const int64_t cols_a = OP == DX ? N : K, cols_b = N, cols_c = OP == DX ? K : N;
+        const int64_t lds[3] = {epi->ld_a, epi->ld_b, epi->ld_out}, cols[3] = {cols_a, cols_b, cols_c};
+        for (int i = 0; i < 3; ++i)
+            if (lds[i] != 0 && (lds[i] < cols[i] || lds[i] % 8 || lds[i] > (int64_t(1) << 24))) return SDROP_ESHAPE;
     }
     const size_t ws_need = sdrop_workspace_bytes(OP, M, K, N, BM, BK, dtype, out_dtype);
     if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
     sdrop_mask_layout_t L;
     sdrop_mask_layout(M, K, BM, BK, &L);
     if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
-    GemmParams P = base_params(a, b, mask, out, M, K, N, BM, BK, p, L);
+    GemmParams P = base_params(OP, a, b, mask, out, M, K, N, BM, BK, p, out_dtype, L);
     if (epi) {
+        if (epi->ld_a) P.lda = epi->ld_a * 2;
+        if (epi->ld_b) P.ldb = epi->ld_b * 2;
+        if (epi->ld_out) P.ldc = epi->ld_out * (out_dtype == SDROP_F32 ? 4 : 2);
         if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
         P.bias = epi->bias;
         P.aux = static_cast<const char *>(epi->relu_mask);
@@ -373,11 +392,13 @@ int run(const void *a, const void *b, const void *mask, void *out,
         if (P.splits > 1) {
             // first pass: unscaled fp32 partial planes into the workspace; second pass: sum, scale, round
             const float scale = P.scale;
+            const int64_t ld_out = P.ldc / (out_dtype == SDROP_F32 ? 4 : 2);
             P.C = static_cast<char *>(ws);
+            P.ldc = N * 4;            // the planes of partial sums are contiguous fp32
             P.scale = 1.0f;
             const int rc1 = (dtype == SDROP_F16) ? dispatch_tile<OP, F16, float>(P, st) : dispatch_tile<OP, BF16, float>(P, st);
             if (rc1 != SDROP_OK) return rc1;
-            return launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st);
+            return launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out);
         }
     }
     if (dtype == SDROP_F16) {
@@ -454,7 +475,7 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
     if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    GemmParams Pdx = base_params(dy, w, mask, dx, M, K, N, BM, BK, p, L);
+    GemmParams Pdx = base_params(DX, dy, w, mask, dx, M, K, N, BM, BK, p, out_dtype, L);
     const DxPlan plan = dx_plan(Pdx);
     // dX as one workgroup per tile of two kept blocks (never with one block per tile: that form is persistent)
     const bool tile_form = !plan.persistent && plan.TN == 256;
@@ -462,13 +483,13 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
         const int G_ = plan.TN / BK;
         Pdx.n_tiles = (Pdx.KB + G_ - 1) / G_;
         const int n_dx = Pdx.MB * Pdx.n_tiles;           // the per-tile launch's grid: (group of the row, block row)
-        GemmParams Pdw = base_params(x, dy, mask, dw, M, K, N, BM, BK, p, L);
+        GemmParams Pdw = base_params(DW, x, dy, mask, dw, M, K, N, BM, BK, p, out_dtype, L);
         Pdw.splits = dw_splits(M, N, BM, BK, K);
         Pdw.n_tiles = (int)(N / 256);
         Pdw.total_tiles = Pdw.KB * Pdw.n_tiles * Pdw.splits;
         const float scale = Pdw.scale;
         const bool split = Pdw.splits > 1;
-        if (split) { Pdw.C = static_cast<char *>(ws); Pdw.scale = 1.0f; }
+        if (split) { Pdw.C = static_cast<char *>(ws); Pdw.ldc = N * 4; Pdw.scale = 1.0f; }
         const bool f16 = dtype == SDROP_F16, o32 = out_dtype == SDROP_F32;
         int rf;
         if (tile_form) {
@@ -492,7 +513,7 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
         }
         if (rf != -1) {     // -1: the device does not grant the LDS; fall through to the two calls
             if (rf != SDROP_OK || !split) return rf;
-            return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st);
+            return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, N);
         }
     }
     rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream);
@@ -622,6 +643,7 @@ int sdrop_producer(const void *H, const void *W0, const float *bias, const void 
     epi.act = act;
     epi.bias = bias;
     epi.relu_mask = nullptr;
+    epi.ld_a = epi.ld_b = epi.ld_out = 0;
     return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi);
 }
 

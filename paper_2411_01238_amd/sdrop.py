@@ -48,7 +48,8 @@ class MaskLayout(ctypes.Structure):
 class Epilogue(ctypes.Structure):
     """sdrop_epilogue_t of the header."""
     _fields_ = [("scale_mode", ctypes.c_int32), ("act", ctypes.c_int32),
-                ("bias", ctypes.c_void_p), ("relu_mask", ctypes.c_void_p)]
+                ("bias", ctypes.c_void_p), ("relu_mask", ctypes.c_void_p),
+                ("ld_a", ctypes.c_int64), ("ld_b", ctypes.c_int64), ("ld_out", ctypes.c_int64)]
 
 
 _lib = None
@@ -125,6 +126,16 @@ def _dev(t, name):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
         raise ValueError("%s must be a contiguous GPU tensor" % name)
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _mat(t, name):
+    """Device pointer and leading dimension (elements) of a 2-D GPU tensor whose rows are contiguous:
+    a contiguous matrix or a column range of a wider one."""
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dim() == 2 and (t.shape[1] == 1 or t.stride(1) == 1)
+            and (t.shape[0] == 1 or t.stride(0) >= t.shape[1])):
+        raise ValueError("%s must be a 2-D GPU tensor with contiguous rows" % name)
+    ld = t.stride(0) if t.shape[0] > 1 else t.shape[1]
+    return ctypes.c_void_p(t.data_ptr()), int(ld)
 
 
 def mask_layout(M, K, BM, BK):
@@ -221,12 +232,11 @@ def workspace_bytes(op, M, K, N, BM, BK, dtype, out_dtype):
 
 
 def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype):
-    """Marshals the tail arguments into the C struct (None when there is no tail)."""
-    if scale_mode == SCALE_DROPOUT and act == ACT_NONE and bias is None and relu_mask is None:
-        return None
+    """Marshals the tail arguments into the C struct (leading dimensions are filled in by _gemm)."""
     e = Epilogue()
     e.scale_mode, e.act = int(scale_mode), int(act)
     e.bias = e.relu_mask = None
+    e.ld_a = e.ld_b = e.ld_out = 0
     if bias is not None:
         if bias.dtype != torch.float32 or tuple(bias.shape) != (ncols,):
             raise ValueError("bias must be fp32 with one value per output column")
@@ -234,7 +244,8 @@ def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype):
     if relu_mask is not None:
         if relu_mask.dtype != dtype or tuple(relu_mask.shape) != tuple(out_shape):
             raise ValueError("relu_mask must have the operands' dtype and the output's shape")
-        e.relu_mask = _dev(relu_mask, "relu_mask").value
+        ptr, e.relu_mask_ld = _mat(relu_mask, "relu_mask")
+        e.relu_mask = ptr.value
     return e
 
 
@@ -254,10 +265,20 @@ def _gemm(name, op, a, b, mask, out_shape, M, K, N, out_dtype, out, ws, epi=None
         ws = torch.empty(need, dtype=torch.uint8, device=a.device)
     ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
     ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
-    args = (_dev(a, "a"), _dev(b, "b"), _dev(mask.buf, "mask"), _dev(out, "out"),
+    (pa, lda), (pb, ldb), (po, ldo) = _mat(a, "a"), _mat(b, "b"), _mat(out, "out")
+    args = (pa, pb, _dev(mask.buf, "mask"), po,
             M, K, N, mask.BM, mask.BK, mask.p, _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream())
-    if name.endswith("_ex"):
-        rc = getattr(lib(), name)(*args, ctypes.byref(epi) if epi is not None else None)
+    strided = (lda, ldb, ldo) != (a.shape[1], b.shape[1], out.shape[1])
+    if epi is not None and getattr(epi, "relu_mask_ld", ldo) != ldo:
+        raise ValueError("relu_mask must have the output's leading dimension")
+    if name.endswith("_ex") or strided:
+        # row-strided operands go through the _ex entry point of the same operation
+        if epi is None:
+            epi = _epilogue(SCALE_DROPOUT, ACT_NONE, None, None, 0, out_shape, dtype)
+        if strided:
+            epi.ld_a, epi.ld_b, epi.ld_out = lda, ldb, ldo
+        ex = name if name.endswith("_ex") else name + "_ex"
+        rc = getattr(lib(), ex)(*args, ctypes.byref(epi))
     else:
         rc = getattr(lib(), name)(*args)
     _check(rc, name)

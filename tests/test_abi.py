@@ -157,7 +157,16 @@ def test_tail_arguments_are_checked_on_the_host():
         f = getattr(L, name)
         assert f(*base, epi(bias=addr + 4)) == sdrop.EALIGN
         assert f(*base, epi(relu_mask=addr + 8)) == sdrop.EALIGN
-    # the gradient of the weights takes a scale only
+    # leading dimensions: at least the row length, a multiple of 8
+    def epi_ld(a=0, b=0, o=0):
+        e = sdrop.Epilogue()
+        e.scale_mode, e.act, e.bias, e.relu_mask, e.ld_a, e.ld_b, e.ld_out = 0, 0, None, None, a, b, o
+        return ctypes.byref(e)
+    for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex"):
+        f = getattr(L, name)
+        for kw in (dict(a=8), dict(b=248), dict(o=16), dict(a=16384 + 4), dict(b=1 << 25)):
+            assert f(*base, epi_ld(**kw)) == sdrop.ESHAPE, (name, kw)
+    # the gradient of the weights takes a scale and leading dimensions only
     f = L.sdrop_bwd_dw_ex
     assert f(*base, epi(act=sdrop.ACT_RELU)) == sdrop.EINVAL
     assert f(*base, epi(bias=addr)) == sdrop.EINVAL
