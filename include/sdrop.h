@@ -240,7 +240,8 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  *   scale_mode  SDROP_SCALE_DROPOUT: scale = 1/(1-p), as in eq. (1)-(3)
  *               SDROP_SCALE_ONE:     scale = 1 (a masked product that is not a dropout's output)
  *   act         SDROP_ACT_NONE, SDROP_ACT_RELU (max(v,0)), SDROP_ACT_GELU_TANH
- *               (0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))), the "tanh" form of GELU)
+ *               (0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))), the "tanh" form of GELU),
+ *               SDROP_ACT_GELU_ERF (0.5 v (1 + erf(v / sqrt 2)), the exact form)
  *   bias        device, fp32[number of output columns], 16-byte aligned, or NULL
  *   relu_mask   device, a matrix of type `dtype` with the output's shape (and the output's
  *               leading dimension), 16-byte aligned, or NULL: where it is not > 0 the output is
@@ -259,7 +260,7 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  * or relu_mask SDROP_EALIGN.  Dropped blocks of sdrop_bwd_dx_ex's output are +0 whatever the tail.
  */
 enum { SDROP_SCALE_DROPOUT = 0, SDROP_SCALE_ONE = 1 };
-enum { SDROP_ACT_NONE = 0, SDROP_ACT_RELU = 1, SDROP_ACT_GELU_TANH = 2 };
+enum { SDROP_ACT_NONE = 0, SDROP_ACT_RELU = 1, SDROP_ACT_GELU_TANH = 2, SDROP_ACT_GELU_ERF = 3 };
 
 typedef struct sdrop_epilogue {
     int32_t scale_mode;

@@ -17,7 +17,7 @@ multiplied in, nothing is skipped or reordered.
 """
 import numpy as np
 
-ACT_NONE, ACT_RELU, ACT_GELU_TANH = 0, 1, 2
+ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF = 0, 1, 2, 3
 
 
 def expand(keep, BM, BK):
@@ -33,7 +33,8 @@ def scale_of(p, scale_one=False):
 
 
 def act(v, kind):
-    """ReLU, or GELU in its tanh form 0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3)))."""
+    """ReLU, GELU in its tanh form 0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))), or GELU itself,
+    0.5 v (1 + erf(v / sqrt 2)) = v Phi(v)."""
     v = np.asarray(v, dtype=np.float64)
     if kind == ACT_NONE:
         return v
@@ -41,6 +42,9 @@ def act(v, kind):
         return np.where(v > 0.0, v, 0.0)
     if kind == ACT_GELU_TANH:
         return 0.5 * v * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (v + 0.044715 * v ** 3)))
+    if kind == ACT_GELU_ERF:
+        from scipy.special import erf          # the error function itself is a library primitive
+        return 0.5 * v * (1.0 + erf(v / np.sqrt(2.0)))
     raise ValueError("unknown activation")
 
 

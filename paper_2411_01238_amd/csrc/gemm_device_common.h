@@ -109,7 +109,8 @@ __device__ __forceinline__ void store_out(char *p, uint4 v)
 // the dropout as well):  out = [aux > 0] act(scale * acc + bias[column]).
 //   bias  fp32, one value per output column
 //   act   SDROP_ACT_RELU: max(v, 0);  SDROP_ACT_GELU_TANH: v / (1 + exp(-2 c (v + 0.044715 v^3))),
-//         c = sqrt(2/pi), which is 0.5 v (1 + tanh(c (v + 0.044715 v^3)))
+//         c = sqrt(2/pi), which is 0.5 v (1 + tanh(c (v + 0.044715 v^3)));
+//         SDROP_ACT_GELU_ERF: 0.5 v (1 + erf(v / sqrt 2))
 //   aux   matrix of the operands' type and the output's shape; where it is not > 0 the output
 //         is 0 (the backward of a ReLU whose output was kept)
 struct Tail {
@@ -144,6 +145,9 @@ __device__ __forceinline__ void act4(int act, float (&v)[4])
             const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
             v[e] = x * __builtin_amdgcn_rcpf(1.f + __expf(-2.f * u));
         }
+    } else if (act == SDROP_ACT_GELU_ERF) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = 0.5f * v[e] * (1.f + erff(v[e] * 0.7071067811865476f));
     }
 }
 template <class T, bool AUX>

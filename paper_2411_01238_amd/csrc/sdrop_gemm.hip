@@ -361,7 +361,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
     if (rc != SDROP_OK) return rc;
     if (epi) {
         if (epi->scale_mode != SDROP_SCALE_DROPOUT && epi->scale_mode != SDROP_SCALE_ONE) return SDROP_EINVAL;
-        if (epi->act != SDROP_ACT_NONE && epi->act != SDROP_ACT_RELU && epi->act != SDROP_ACT_GELU_TANH) return SDROP_EINVAL;
+        if (epi->act < SDROP_ACT_NONE || epi->act > SDROP_ACT_GELU_ERF) return SDROP_EINVAL;
         // the gradient of the weights takes a scale only
         if (OP == DW && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask)) return SDROP_EINVAL;
         if ((reinterpret_cast<uintptr_t>(epi->bias) | reinterpret_cast<uintptr_t>(epi->relu_mask)) % 16) return SDROP_EALIGN;

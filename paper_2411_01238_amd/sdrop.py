@@ -27,7 +27,7 @@ EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_
            "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer")
 
 SCALE_DROPOUT, SCALE_ONE = 0, 1
-ACT_NONE, ACT_RELU, ACT_GELU_TANH = 0, 1, 2
+ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF = 0, 1, 2, 3
 
 _DTYPES = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 

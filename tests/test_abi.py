@@ -151,7 +151,7 @@ def test_tail_arguments_are_checked_on_the_host():
         f = getattr(L, name)
         assert f(*base[:3], null, *base[4:], epi()) == sdrop.EINVAL          # the plain checks still apply
         assert f(*base, epi(scale_mode=2)) == sdrop.EINVAL
-        assert f(*base, epi(act=3)) == sdrop.EINVAL
+        assert f(*base, epi(act=4)) == sdrop.EINVAL
         assert f(*base, epi(act=-1)) == sdrop.EINVAL
     for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex"):
         f = getattr(L, name)

@@ -53,7 +53,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("M,K,N,BM,BK,dtype,p,seed", CASES)
-@pytest.mark.parametrize("act", [sdrop.ACT_NONE, sdrop.ACT_RELU, sdrop.ACT_GELU_TANH])
+@pytest.mark.parametrize("act", [sdrop.ACT_NONE, sdrop.ACT_RELU, sdrop.ACT_GELU_TANH, sdrop.ACT_GELU_ERF])
 def test_fwd_and_dx_tails(M, K, N, BM, BK, dtype, p, seed, act):
     print("tail", M, K, N, BM, BK, dtype, p, seed, act, flush=True)
     X, W, dY = make_custom(M, K, N, dtype, seed=seed)
@@ -103,7 +103,7 @@ def test_dw_with_scale_one_and_producer(M, K, N, BM, BK, dtype, p, seed):
         _check(o32, o16, ref, X.dtype, "dw_ex" + tag + " mode %d" % scale_mode)
     # the producing layer: H[M,N0] = dY's role, W0[K,N0] = W's role, one bias value per column of X
     b0 = _bias(K, seed + 90)
-    for act in (sdrop.ACT_NONE, sdrop.ACT_RELU, sdrop.ACT_GELU_TANH):
+    for act in (sdrop.ACT_NONE, sdrop.ACT_RELU, sdrop.ACT_GELU_TANH, sdrop.ACT_GELU_ERF):
         ref = sb.producer(dYd, Wd, f64(b0), keep, BM, BK, act)
         o32 = sdrop.sdrop_producer(dYg, Wg, b0.cuda(), m, act=act, out_dtype=torch.float32)
         o16 = sdrop.sdrop_producer(dYg, Wg, b0.cuda(), m, act=act)

@@ -37,12 +37,12 @@ def _torch_block(H, W0, b0, W, keep, BM, BK, p, kind):
     Ht, W0t, b0t, Wt = t(H), t(W0), t(b0), t(W)
     m = torch.tensor(keep, dtype=torch.float64).repeat_interleave(BM, 0).repeat_interleave(BK, 1)
     Z = torch.nn.functional.linear(Ht, W0t, b0t)
-    A = torch.relu(Z) if kind == sb.ACT_RELU else torch.nn.functional.gelu(Z, approximate="tanh")
+    A = torch.relu(Z) if kind == sb.ACT_RELU else torch.nn.functional.gelu(Z, approximate="tanh" if kind == sb.ACT_GELU_TANH else "none")
     Y = (A * m) @ Wt / (1.0 - p)
     return Ht, W0t, b0t, Wt, A * m, Y
 
 
-@pytest.mark.parametrize("kind", [sb.ACT_RELU, sb.ACT_GELU_TANH])
+@pytest.mark.parametrize("kind", [sb.ACT_RELU, sb.ACT_GELU_TANH, sb.ACT_GELU_ERF])
 def test_forward_matches_library_ops(kind):
     H, W0, b0, W, dY, keep, BM, BK, p = _case(seed=3)
     X, Y = sb.block_forward(H, W0, b0, W, keep, BM, BK, p, kind)
@@ -147,3 +147,13 @@ def test_everything_dropped_or_kept():
     allk = np.ones_like(keep)
     np.testing.assert_allclose(sb.producer(H, W0, b0, allk, BM, BK, sb.ACT_RELU), np.maximum(H @ W0.T + b0, 0.0), rtol=1e-13)
     assert sb.scale_of(1.0) == 0.0 and sb.scale_of(0.0) == 1.0 and sb.scale_of(0.75) == 4.0 and sb.scale_of(0.75, True) == 1.0
+
+
+def test_gelu_erf_is_v_times_the_normal_cdf():
+    from scipy.stats import norm
+    v = np.linspace(-7.0, 7.0, 281)
+    g = sb.act(v, sb.ACT_GELU_ERF)
+    np.testing.assert_allclose(g, v * norm.cdf(v), rtol=1e-12, atol=1e-15)          # another library's route to Phi
+    np.testing.assert_allclose(g, torch.nn.functional.gelu(torch.tensor(v)).numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(g - sb.act(-v, sb.ACT_GELU_ERF), v, rtol=0, atol=1e-14)
+    assert sb.act(np.array([0.0]), sb.ACT_GELU_ERF)[0] == 0.0
