@@ -223,8 +223,14 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char *const staging = smem + STAGES * STAGE_BYTES;
 
+    GEMM_TICKW(12);
+    // A kernel handed a mask built for another problem writes nothing.  The header is tested after
+    // the first look-ups have been issued (they are addressed by the tile number alone and stay
+    // inside the mask object whatever it holds), so that it costs no round trip of its own.
     const MaskHeader *H = P.mv.hdr;
-    if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+    auto mask_ok = [&]() __attribute__((always_inline)) -> bool {
+        return H->magic == kMaskMagic && H->M == P.M && H->K == P.K && H->BM == P.BM && H->BK == P.BK;
+    };
 
     const int lane = threadIdx.x & 63;
     const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -293,9 +299,11 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         auto level3 = [&](Meta &m) __attribute__((always_inline)) { m.e0 = entry(m, 0); m.e1 = entry(m, 1); };
 
         Meta cur, n1, n2, n3;
-        n1 = level1(0); level2(n1); level3(n1);
-        n2 = level1(1); level2(n2);
-        n3 = level1(2);
+        n1 = level1(0); n2 = level1(1); n3 = level1(2);
+        if (!mask_ok()) return;
+        GEMM_TICKW(13);
+        level2(n1); level3(n1);
+        level2(n2);
         int k = -1;                      // round of the tile being issued
         int s = 0, nsteps = 0;           // next slice of that tile; its number of slices
         int e_cur = 0, e_nxt = 0;        // list entries of slice s and of the block after it
@@ -373,10 +381,12 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     };
     // scalars: this tile (ord0, len0), the next one's block row / column (ord1);
     // in flight: the next tile's kept count (cnt1_v), order[] of the tile after it (ord2_v)
-    int ord0 = uni(c_order(0));
+    const int ord0_v = c_order(0), ord1_v = c_order(1), ord2_v = c_order(2);
+    if (!mask_ok()) return;
+    GEMM_TICKW(13);
+    int ord0 = uni(ord0_v);
     int len0 = uni(c_len(0, c_count(ord0)));
-    int ord1 = uni(c_order(1));
-    int ord2_v = c_order(2);
+    int ord1 = uni(ord1_v);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
     int ord2 = uni(ord2_v);
 
@@ -472,8 +482,10 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char *const staging = smem + STAGES * STAGE_BYTES;
 
+    GEMM_TICKW(12);
     const MaskHeader *H = P.mv.hdr;
     if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+    GEMM_TICKW(13);
 
     const int lane = threadIdx.x & 63;
     const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

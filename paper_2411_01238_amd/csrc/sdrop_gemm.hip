@@ -163,8 +163,11 @@ int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
 // out[e] = scale * sum_c part[c][e], rounded once (the second pass of a split DW)
 template <class OutT>
 __global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, OutT *out_base, int64_t n, int splits, float scale,
-                                                           int64_t ncols, int64_t ld)
+                                                           int64_t ncols, int64_t ld, const MaskHeader *H,
+                                                           int64_t M, int64_t K, int BM, int BK)
 {
+    // like the first pass, write nothing when the mask was built for another problem (the planes are then unwritten)
+    if (H->magic != kMaskMagic || H->M != M || H->K != K || H->BM != BM || H->BK != BK) return;
     const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= n) return;
     OutT *const out = out_base + (e / ncols) * (ld - ncols);       // row e / ncols of an output with `ld` elements per row (4 | ncols)
@@ -338,16 +341,19 @@ GemmParams base_params(int op, const void *a, const void *b, const void *mask, v
 
 // sums the fp32 planes of a split DW into the output (second pass)
 int launch_reduce(const void *ws, void *out, int64_t n, int splits, float scale, int dtype, int out_dtype, hipStream_t st,
-                  int64_t ncols, int64_t ld)
+                  int64_t ncols, int64_t ld, const GemmParams &P)
 {
+    const MaskHeader *H = P.mv.hdr;
+    const int64_t M = P.M, K = P.K;
+    const int BM = P.BM, BK = P.BK;
     const unsigned grid = (unsigned)((n / 4 + 255) / 256);
     const float *part = static_cast<const float *>(ws);
     if (out_dtype == SDROP_F32)
-        hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, splits, scale, ncols, ld);
+        hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK);
     else if (dtype == SDROP_F16)
-        hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, splits, scale, ncols, ld);
+        hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK);
     else
-        hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, splits, scale, ncols, ld);
+        hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK);
     return hip_status(hipGetLastError());
 }
 
@@ -398,7 +404,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
             P.scale = 1.0f;
             const int rc1 = (dtype == SDROP_F16) ? dispatch_tile<OP, F16, float>(P, st) : dispatch_tile<OP, BF16, float>(P, st);
             if (rc1 != SDROP_OK) return rc1;
-            return launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out);
+            return launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out, P);
         }
     }
     if (dtype == SDROP_F16) {
@@ -513,7 +519,7 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
         }
         if (rf != -1) {     // -1: the device does not grant the LDS; fall through to the two calls
             if (rf != SDROP_OK || !split) return rf;
-            return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, N);
+            return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, N, Pdw);
         }
     }
     rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream);

@@ -286,3 +286,32 @@ def test_structured_masks_on_a_grid_larger_than_the_chip(force_groups):
             _full_parity(X, W, dY, B, B, p, 0, 0, name, keep=keep)
     finally:
         sdrop.set_tuning(sdrop.TUNE_DX_PERSISTENT_GROUPS_PER_CU, sdrop.DX_PERSISTENT_GROUPS_PER_CU_DEFAULT)
+
+
+@pytest.mark.parametrize("M,K,N", [(512, 768, 256), (512, 768, 136), (2048, 256, 512)])
+def test_mask_built_for_another_problem_writes_nothing(M, K, N):
+    # every kernel compares the mask object's header with the call's shape before it trusts a list entry:
+    # persistent kernels and the one-launch backward; per-tile kernels; dW as split parts with its summing pass
+    import ctypes
+    B = 128
+    print("gemm foreign mask", M, K, N, flush=True)
+    X, W, dY = make_custom(M, K, N, "bf16", seed=5)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    other = sdrop.sdrop_mask(K, M, B, B, 0.5, 1, 0)           # the transposed problem: same size, different header
+    buf = torch.zeros(2 * other.buf.numel(), dtype=torch.uint8, device="cuda")
+    buf[:other.buf.numel()] = other.buf
+    ws = torch.zeros(max(16, sdrop.workspace_bytes(sdrop.OP_BWD_DW, M, K, N, B, B, X.dtype, X.dtype)), dtype=torch.uint8, device="cuda")
+    L = sdrop.lib()
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    outs = {n: torch.full(s, 3.0, dtype=torch.bfloat16, device="cuda") for n, s in (("Y", (M, N)), ("dX", (M, K)), ("dW", (K, N)))}
+    common = (M, K, N, B, B, 0.5, sdrop.BF16, sdrop.BF16, ws.data_ptr(), ws.numel(), st)
+    assert L.sdrop_fwd(Xg.data_ptr(), Wg.data_ptr(), buf.data_ptr(), outs["Y"].data_ptr(), *common) == sdrop.OK
+    assert L.sdrop_bwd_dx(dYg.data_ptr(), Wg.data_ptr(), buf.data_ptr(), outs["dX"].data_ptr(), *common) == sdrop.OK
+    assert L.sdrop_bwd_dw(Xg.data_ptr(), dYg.data_ptr(), buf.data_ptr(), outs["dW"].data_ptr(), *common) == sdrop.OK
+    torch.cuda.synchronize()
+    for n, o in outs.items():
+        assert torch.all(o == 3.0).item(), n + " was written with a foreign mask"
+    assert L.sdrop_bwd(dYg.data_ptr(), Wg.data_ptr(), Xg.data_ptr(), buf.data_ptr(), outs["dX"].data_ptr(), outs["dW"].data_ptr(), *common) == sdrop.OK
+    torch.cuda.synchronize()
+    for n in ("dX", "dW"):
+        assert torch.all(outs[n] == 3.0).item(), n + " was written by sdrop_bwd with a foreign mask"
