@@ -247,6 +247,10 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  *               leading dimension), 16-byte aligned, or NULL: where it is not > 0 the output is
  *               +-0 (the backward of a ReLU, given the ReLU's output).  Its dropped blocks are
  *               never read.
+ *   gate_mode   what relu_mask does.  SDROP_GATE_RELU (0): as above.  SDROP_GATE_GELU_TANH /
+ *               SDROP_GATE_GELU_ERF: the output is multiplied by the derivative of that GELU at
+ *               relu_mask, which then holds the GELU's INPUT (the backward of a GELU; the second
+ *               output of sdrop_producer is that input)
  *   ld_a, ld_b, ld_out   leading dimensions, in elements, of the first matrix argument, the
  *               second one and the output (row r starts r * ld elements after the pointer);
  *               0 = contiguous.  A leading dimension must be at least the number of columns, a
@@ -261,6 +265,7 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  */
 enum { SDROP_SCALE_DROPOUT = 0, SDROP_SCALE_ONE = 1 };
 enum { SDROP_ACT_NONE = 0, SDROP_ACT_RELU = 1, SDROP_ACT_GELU_TANH = 2, SDROP_ACT_GELU_ERF = 3 };
+enum { SDROP_GATE_RELU = 0, SDROP_GATE_GELU_TANH = 1, SDROP_GATE_GELU_ERF = 2 };
 
 typedef struct sdrop_epilogue {
     int32_t scale_mode;
@@ -268,6 +273,7 @@ typedef struct sdrop_epilogue {
     const float *bias;
     const void *relu_mask;
     int64_t ld_a, ld_b, ld_out;
+    int32_t gate_mode;
 } sdrop_epilogue_t;
 
 int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,
@@ -287,19 +293,23 @@ int sdrop_bwd_dw_ex(const void *X, const void *dY, const void *mask, void *dW,
  * The layer before the dropout as an output-sparse product: only the blocks of X that the
  * dropout keeps are computed; dropped blocks are written as +0.
  *
- *     X[M,K] = m' . act(H W0^T + b0)
+ *     X[M,K] = m' . act(H W0^T + b0)          Z[M,K] = m' . (H W0^T + b0)   (optional)
  *
  *   H[M,N0]   input of type `dtype`
  *   W0[K,N0]  the producing layer's weight, one ROW per output feature (the [out, in] layout)
  *   bias      device fp32[K] or NULL;  act as above;  mask over X[M,K] in BM x BK blocks
+ *   Z         NULL, or a second output of X's shape and type that receives the value before the
+ *             activation on the kept blocks (what the backward of a GELU needs); its dropped
+ *             blocks are NOT written (nothing reads them)
  *   p         used only to choose tile shapes (the product is not scaled)
  * It is sdrop_bwd_dx_ex(H, W0, ...) with SDROP_SCALE_ONE: the same kernels.  Its backward uses
  * the other two (dZ = the gradient at the pre-activation, zero on dropped blocks):
  *     dH[M,N0]  = (dZ . m') W0      sdrop_fwd_ex(dZ, W0, mask, dH, M, K, N0, ..., SDROP_SCALE_ONE)
  *     dW0[K,N0] = (dZ . m')^T H     sdrop_bwd_dw_ex(dZ, H, mask, dW0, M, K, N0, ..., SDROP_SCALE_ONE)
- * and, for act = ReLU, dZ itself comes from sdrop_bwd_dx_ex(dY, W, ..., relu_mask = X).
+ * and dZ itself comes from sdrop_bwd_dx_ex(dY, W, ...) with relu_mask = X for act = ReLU, or with
+ * relu_mask = Z and the matching gate_mode for a GELU.
  */
-int sdrop_producer(const void *H, const void *W0, const float *bias, const void *mask, void *X,
+int sdrop_producer(const void *H, const void *W0, const float *bias, const void *mask, void *X, void *Z,
                    int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
                    int dtype, int out_dtype, void *stream);
 

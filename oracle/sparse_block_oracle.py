@@ -48,32 +48,63 @@ def act(v, kind):
     raise ValueError("unknown activation")
 
 
-def tail(v, bias=None, kind=ACT_NONE, relu_mask=None):
-    """[relu_mask > 0] act(v + bias[column])."""
+GATE_RELU, GATE_GELU_TANH, GATE_GELU_ERF = 0, 1, 2
+
+
+def act_grad(z, kind):
+    """Derivative of act(., kind) at z.
+
+    ReLU: [z > 0].  tanh-GELU g = 0.5 z (1 + t), t = tanh(u), u = c (z + a z^3):
+    g' = 0.5 (1 + t) + 0.5 z (1 - t^2) c (1 + 3 a z^2).  GELU g = z Phi(z): g' = Phi(z) + z phi(z)."""
+    z = np.asarray(z, dtype=np.float64)
+    if kind == ACT_NONE:
+        return np.ones_like(z)
+    if kind == ACT_RELU:
+        return (z > 0.0).astype(np.float64)
+    if kind == ACT_GELU_TANH:
+        c, a = np.sqrt(2.0 / np.pi), 0.044715
+        t = np.tanh(c * (z + a * z ** 3))
+        return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * c * (1.0 + 3.0 * a * z * z)
+    if kind == ACT_GELU_ERF:
+        from scipy.special import erf
+        return 0.5 * (1.0 + erf(z / np.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi)
+    raise ValueError("unknown activation")
+
+
+def gate(v, g, gate_mode):
+    """v gated by g: zero where g <= 0 (ReLU), or times the GELU's derivative at g."""
+    g = np.asarray(g, dtype=np.float64)
+    if gate_mode == GATE_RELU:
+        return np.where(g > 0.0, v, 0.0)
+    return v * act_grad(g, ACT_GELU_TANH if gate_mode == GATE_GELU_TANH else ACT_GELU_ERF)
+
+
+def tail(v, bias=None, kind=ACT_NONE, relu_mask=None, gate_mode=GATE_RELU):
+    """gate(act(v + bias[column]), relu_mask)."""
     v = np.asarray(v, dtype=np.float64)
     if bias is not None:
         v = v + np.asarray(bias, dtype=np.float64)[None, :]
     v = act(v, kind)
     if relu_mask is not None:
-        v = np.where(np.asarray(relu_mask, dtype=np.float64) > 0.0, v, 0.0)
+        v = gate(v, relu_mask, gate_mode)
     return v
 
 
-def fwd_tail(X, W, keep, BM, BK, p, scale_one=False, bias=None, kind=ACT_NONE, relu_mask=None):
+def fwd_tail(X, W, keep, BM, BK, p, scale_one=False, bias=None, kind=ACT_NONE, relu_mask=None, gate_mode=GATE_RELU):
     """eq. (1) followed by the tail: [relu_mask > 0] act(s (X . m) W + bias)."""
     X = np.asarray(X, dtype=np.float64)
     m = expand(keep, BM, BK)
     # dropped blocks of X may hold anything (NaN included): they are excluded, not multiplied by 0
     Xm = np.where(m > 0.0, X, 0.0)
-    return tail(scale_of(p, scale_one) * (Xm @ np.asarray(W, dtype=np.float64)), bias, kind, relu_mask)
+    return tail(scale_of(p, scale_one) * (Xm @ np.asarray(W, dtype=np.float64)), bias, kind, relu_mask, gate_mode)
 
 
-def bwd_dx_tail(dY, W, keep, BM, BK, p, scale_one=False, bias=None, kind=ACT_NONE, relu_mask=None):
+def bwd_dx_tail(dY, W, keep, BM, BK, p, scale_one=False, bias=None, kind=ACT_NONE, relu_mask=None, gate_mode=GATE_RELU):
     """eq. (2) with the tail on the kept blocks: m . [relu_mask > 0] act(s dY W^T + bias)."""
     m = expand(keep, BM, BK)
     full = scale_of(p, scale_one) * (np.asarray(dY, dtype=np.float64) @ np.asarray(W, dtype=np.float64).T)
     rm = None if relu_mask is None else np.where(m > 0.0, np.asarray(relu_mask, dtype=np.float64), 0.0)
-    return np.where(m > 0.0, tail(full, bias, kind, rm), 0.0)
+    return np.where(m > 0.0, tail(full, bias, kind, rm, gate_mode), 0.0)
 
 
 def bwd_dw_scaled(X, dY, keep, BM, BK, p, scale_one=False):
@@ -89,6 +120,11 @@ def producer(H, W0, b0, keep, BM, BK, kind=ACT_NONE):
     return expand(keep, BM, BK) * tail(Z, b0, kind)
 
 
+def producer_preact(H, W0, b0, keep, BM, BK):
+    """m . (H W0^T + b0): the producing layer's value before the activation, on the kept blocks."""
+    return producer(H, W0, b0, keep, BM, BK, ACT_NONE)
+
+
 def block_forward(H, W0, b0, W, keep, BM, BK, p, kind=ACT_RELU):
     """Returns (X, Y) of the block defined at the top."""
     X = producer(H, W0, b0, keep, BM, BK, kind)
@@ -96,11 +132,11 @@ def block_forward(H, W0, b0, W, keep, BM, BK, p, kind=ACT_RELU):
     return X, Y
 
 
-def block_backward(H, W0, b0, W, keep, BM, BK, p, dY):
-    """Gradients of sum(Y . dY) for the block with act = ReLU, by the chain rule:
+def block_backward(H, W0, b0, W, keep, BM, BK, p, dY, kind=ACT_RELU):
+    """Gradients of sum(Y . dY) for the block, by the chain rule:
 
         dX  = s (dY W^T) . m            eq. (2)
-        dZ  = dX . [Z > 0]              ReLU
+        dZ  = dX . act'(Z)              [Z > 0] for ReLU
         dW  = s X^T dY                  eq. (3)
         dH  = dZ W0,   dW0 = dZ^T H,   db0 = column sums of dZ
 
@@ -113,7 +149,7 @@ def block_backward(H, W0, b0, W, keep, BM, BK, p, dY):
     m = expand(keep, BM, BK)
     s = scale_of(p)
     Z = H @ W0.T + (0.0 if b0 is None else np.asarray(b0, dtype=np.float64)[None, :])
-    X = m * np.where(Z > 0.0, Z, 0.0)
+    X = m * act(Z, kind)
     dX = s * (dY @ W.T) * m
-    dZ = dX * (Z > 0.0)
+    dZ = dX * act_grad(Z, kind)
     return {"dH": dZ @ W0, "dW0": dZ.T @ H, "db0": dZ.sum(axis=0), "dW": s * (X.T @ dY), "dZ": dZ, "Z": Z}

@@ -39,37 +39,48 @@ def sparsedrop_matmul(x, w, p, BM=128, BK=128, seed=0, rng_stream=0):
     return _SparseDropMatmul.apply(x, w, float(p), int(BM), int(BK), int(seed), int(rng_stream))
 
 
-class _SparseReluBlock(torch.autograd.Function):
-    """Linear -> ReLU -> SparseDrop -> Linear with every GEMM sparse (Section 4.3, closing remark).
+_ACTS = {"relu": (sdrop.ACT_RELU, sdrop.GATE_RELU), "gelu_tanh": (sdrop.ACT_GELU_TANH, sdrop.GATE_GELU_TANH),
+         "gelu": (sdrop.ACT_GELU_ERF, sdrop.GATE_GELU_ERF)}
 
-    forward   X = m' . relu(H W0^T + b0)        sdrop_producer (dropped blocks never computed)
+
+class _SparseActBlock(torch.autograd.Function):
+    """Linear -> activation -> SparseDrop -> Linear with every GEMM sparse (Section 4.3, closing remark).
+
+    forward   X = m' . act(H W0^T + b0)          sdrop_producer (dropped blocks never computed;
+                                                 for a GELU it also keeps Z = H W0^T + b0 on the kept blocks)
               Y = s X W                          eq. (1)
-    backward  dZ  = s (dY W^T) . m' . [X > 0]    eq. (2) with the ReLU gate in its tail
+    backward  dZ  = s (dY W^T) . m' . act'(Z)    eq. (2) with the gate in its tail ([X > 0] for ReLU)
               dW  = s X^T dY                     eq. (3)
               dH  = dZ W0, dW0 = dZ^T H          eq. (1) / eq. (3) at scale 1 on the block-sparse dZ
               db0 = column sums of dZ            (a torch reduction: no GEMM)
     """
 
     @staticmethod
-    def forward(ctx, h, w0, b0, w, p, BM, BK, seed, rng_stream):
+    def forward(ctx, h, w0, b0, w, p, BM, BK, seed, rng_stream, act):
         M, K = h.shape[0], w0.shape[0]
+        act_id, gate_id = _ACTS[act]
         m = sdrop.sdrop_mask(M, K, BM, BK, p, seed, rng_stream)
-        x = sdrop.sdrop_producer(h, w0, b0, m, act=sdrop.ACT_RELU)
+        if act == "relu":
+            x = sdrop.sdrop_producer(h, w0, b0, m, act=act_id)
+            gate = x                    # [X > 0] is [Z > 0] on the kept blocks
+        else:
+            x, gate = sdrop.sdrop_producer(h, w0, b0, m, act=act_id, preact=True)
         y = sdrop.sdrop_fwd(x, w, m)
-        ctx.save_for_backward(h, w0, w, x)
+        ctx.save_for_backward(h, w0, w, x, gate)
         ctx.mask = m
         ctx.has_bias = b0 is not None
+        ctx.gate_id = gate_id
         return y
 
     @staticmethod
     def backward(ctx, dy):
-        h, w0, w, x = ctx.saved_tensors
+        h, w0, w, x, gate = ctx.saved_tensors
         m = ctx.mask
         dy = dy.contiguous()
         need_h, need_w0, need_b0, need_w = ctx.needs_input_grad[:4]
         dz = dh = dw0 = db0 = dw = None
         if need_h or need_w0 or (need_b0 and ctx.has_bias):
-            dz = sdrop.sdrop_bwd_dx_ex(dy, w, m, relu_mask=x)
+            dz = sdrop.sdrop_bwd_dx_ex(dy, w, m, relu_mask=gate, gate_mode=ctx.gate_id)
         if need_h:
             dh = sdrop.sdrop_fwd_ex(dz, w0, m, scale_mode=sdrop.SCALE_ONE)
         if need_w0:
@@ -78,16 +89,22 @@ class _SparseReluBlock(torch.autograd.Function):
             db0 = dz.sum(dim=0, dtype=torch.float32)
         if need_w:
             dw = sdrop.sdrop_bwd_dw(x, dy, m)
-        return dh, dw0, db0, dw, None, None, None, None, None
+        return dh, dw0, db0, dw, None, None, None, None, None, None
 
 
-def sparse_relu_block(h, w0, b0, w, p, BM=128, BK=128, seed=0, rng_stream=0):
-    """y = s (m' . relu(h w0^T + b0)) w with a fresh block mask m' over the hidden activation.
+def sparse_act_block(h, w0, b0, w, p, act="relu", BM=128, BK=128, seed=0, rng_stream=0):
+    """y = s (m' . act(h w0^T + b0)) w with a fresh block mask m' over the hidden activation.
 
     h [M, N0], w0 [K, N0] (one row per hidden feature), b0 fp32 [K] or None, w [K, N]: contiguous
     fp16 / bf16 GPU tensors; M % BM == 0, K % BK == 0, N0 % 8 == 0, N % 8 == 0.
+    act: "relu", "gelu" (the exact form) or "gelu_tanh".
     """
-    return _SparseReluBlock.apply(h, w0, b0, w, float(p), int(BM), int(BK), int(seed), int(rng_stream))
+    return _SparseActBlock.apply(h, w0, b0, w, float(p), int(BM), int(BK), int(seed), int(rng_stream), act)
+
+
+def sparse_relu_block(h, w0, b0, w, p, BM=128, BK=128, seed=0, rng_stream=0):
+    """sparse_act_block with a ReLU."""
+    return sparse_act_block(h, w0, b0, w, p, "relu", BM, BK, seed, rng_stream)
 
 
 class SparseDropLinear(torch.nn.Module):

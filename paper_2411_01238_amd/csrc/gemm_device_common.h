@@ -90,6 +90,8 @@ struct GemmParams {
     const float *bias;
     const char *aux;
     int32_t act;
+    int32_t gate_mode;  // how aux gates the output (SDROP_GATE_*)
+    char *C2;           // DX only: second output, the value before the activation (same shape, type and stride as C), or null
     double p;           // host only: dropout probability, for choosing tile shapes
 };
 
@@ -111,18 +113,28 @@ __device__ __forceinline__ void store_out(char *p, uint4 v)
 //   act   SDROP_ACT_RELU: max(v, 0);  SDROP_ACT_GELU_TANH: v / (1 + exp(-2 c (v + 0.044715 v^3))),
 //         c = sqrt(2/pi), which is 0.5 v (1 + tanh(c (v + 0.044715 v^3)));
 //         SDROP_ACT_GELU_ERF: 0.5 v (1 + erf(v / sqrt 2))
-//   aux   matrix of the operands' type and the output's shape; where it is not > 0 the output
-//         is 0 (the backward of a ReLU whose output was kept)
+//   aux   matrix of the operands' type and the output's shape.  SDROP_GATE_RELU: where it is not > 0
+//         the output is 0 (the backward of a ReLU, given the ReLU's output or input).
+//         SDROP_GATE_GELU_TANH / SDROP_GATE_GELU_ERF: the output is multiplied by the derivative of
+//         that GELU at aux (the backward of a GELU, given its input).
 struct Tail {
     const float *bias;
     const char *aux;
     const char *c0;     // the output's origin
     int act;
+    int gate_mode;
 };
 __device__ __forceinline__ Tail make_tail(const GemmParams &P)
 {
     Tail t;
-    t.bias = P.bias; t.aux = P.aux; t.c0 = P.C; t.act = P.act;
+    t.bias = P.bias; t.aux = P.aux; t.c0 = P.C; t.act = P.act; t.gate_mode = P.gate_mode;
+    return t;
+}
+// The tail that writes the second output of the producing layer: bias, no activation, no gate.
+__device__ __forceinline__ Tail make_tail_preact(const GemmParams &P)
+{
+    Tail t;
+    t.bias = P.bias; t.aux = nullptr; t.c0 = P.C2; t.act = SDROP_ACT_NONE; t.gate_mode = SDROP_GATE_RELU;
     return t;
 }
 // v: four consecutive columns of one output row, starting at global column `col`; `elem` is the
@@ -150,6 +162,30 @@ __device__ __forceinline__ void act4(int act, float (&v)[4])
         for (int e = 0; e < 4; ++e) v[e] = 0.5f * v[e] * (1.f + erff(v[e] * 0.7071067811865476f));
     }
 }
+// v[e] gated by x[e] (see Tail)
+__device__ __forceinline__ void gate4(int gate_mode, float (&v)[4], const float (&x)[4])
+{
+    if (gate_mode == SDROP_GATE_RELU) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = x[e] > 0.f ? v[e] : 0.f;
+    } else if (gate_mode == SDROP_GATE_GELU_TANH) {
+        // g = 0.5 x (1 + t), t = tanh(u), u = c (x + a x^3):  g' = 0.5 (1 + t) + 0.5 x (1 - t^2) c (1 + 3 a x^2)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float z = x[e];
+            const float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+            const float t = 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + __expf(2.f * u));
+            v[e] *= 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * 0.7978845608028654f * (1.f + 0.134145f * z * z);
+        }
+    } else {
+        // g = x Phi(x):  g' = Phi(x) + x phi(x)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float z = x[e];
+            v[e] *= 0.5f * (1.f + erff(z * 0.7071067811865476f)) + z * 0.3989422804014327f * __expf(-0.5f * z * z);
+        }
+    }
+}
 template <class T, bool AUX>
 __device__ __forceinline__ void tail4(const Tail &tl, float (&v)[4], int64_t col, int64_t elem)
 {
@@ -163,8 +199,8 @@ __device__ __forceinline__ void tail4(const Tail &tl, float (&v)[4], int64_t col
             using E = typename In<T>::out16;
             typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
             const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = static_cast<float>(x[e]) > 0.f ? v[e] : 0.f;
+            const float xf[4] = {static_cast<float>(x[0]), static_cast<float>(x[1]), static_cast<float>(x[2]), static_cast<float>(x[3])};
+            gate4(tl.gate_mode, v, xf);
         }
     }
 }

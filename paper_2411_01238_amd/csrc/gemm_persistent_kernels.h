@@ -108,7 +108,7 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                         bias_r[nj][i] = *(const_f4)(uintptr_t)(tl.bias + gcol0 + (i >> 2) * 32 + 8 * (i & 3) + 4 * whalf);
                 }
                 if constexpr (ESZ == 2) {
-                    if (tl.aux) {
+                    if (tl.aux && tl.gate_mode == SDROP_GATE_RELU) {
 #pragma unroll
                         for (int it = 0; it < 4; ++it)
                             gate_r[mi * NJ + nj][it] = *reinterpret_cast<const uint4 *>(tl.aux + (out - tl.c0) + (int64_t)(it * 8 + rrow) * ldc + rch * 16);
@@ -121,7 +121,8 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
         const int lane = threadIdx.x & 63;
         const int wrow = lane & 31, whalf = lane >> 5;
         const int rrow = lane >> 3, rch = lane & 7;
-        const bool gate_rows = TAIL && ESZ == 2 && tl.aux != nullptr;
+        // 16-bit outputs under a ReLU gate are gated after rounding, on whole rows; everything else in the accumulator's layout
+        const bool gate_rows = TAIL && ESZ == 2 && tl.aux != nullptr && tl.gate_mode == SDROP_GATE_RELU;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -141,17 +142,15 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                                 v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
                             }
                             act4(tl.act, v);
-                            if constexpr (ESZ == 4) {
-                                if (tl.aux) {
-                                    // fp32 outputs: the gate matrix has 16-bit elements, read in the accumulator's layout
-                                    using E = typename In<T>::out16;
-                                    typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
-                                    const int c = 8 * q + 4 * whalf;             // column within the piece
-                                    const int64_t elem = (out - tl.c0) / ESZ + wrow * (ldc / ESZ) + c;
-                                    const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
-#pragma unroll
-                                    for (int e = 0; e < 4; ++e) v[e] = static_cast<float>(x[e]) > 0.f ? v[e] : 0.f;
-                                }
+                            if (tl.aux && !gate_rows) {
+                                // the gate matrix has 16-bit elements, read here in the accumulator's layout
+                                using E = typename In<T>::out16;
+                                typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
+                                const int c = nl * 32 + 8 * q + 4 * whalf;   // column within the piece
+                                const int64_t elem = (out - tl.c0) / ESZ + wrow * (ldc / ESZ) + c;
+                                const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
+                                const float xf[4] = {static_cast<float>(x[0]), static_cast<float>(x[1]), static_cast<float>(x[2]), static_cast<float>(x[3])};
+                                gate4(tl.gate_mode, v, xf);
                             }
                         }
                         const float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
@@ -724,7 +723,20 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
 #pragma unroll
             for (int b = 0; b < 4; ++b) { ngr[b] = uni(nxt.r[b]); ngc[b] = uni(nxt.c[b]); }
-            if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
+            if constexpr (TAIL) {
+                if (P.C2) {
+                    // the producing layer's value before the activation, to the second output
+                    const Tail tz = make_tail_preact(P);
+                    const int64_t delta = P.C2 - P.C;
+                    auto dst2 = [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
+                        char *const o = dst(mi, nj, gcol0);
+                        return o ? o + delta : nullptr;
+                    };
+                    cw.tail_prefetch(ldc, tz, dst2);
+                    cw.template store<TAIL>(reg, scale, ldc, tz, dst2);
+                }
+                cw.tail_prefetch(ldc, tl, dst);
+            }
             cw.template store<TAIL>(reg, scale, ldc, tl, dst);
             GEMM_TICKW(tick_no * 4 + 2);
             GEMM_TICKW(tick_no * 4 + 3);

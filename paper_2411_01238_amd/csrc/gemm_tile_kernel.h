@@ -450,8 +450,8 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
         if (loader) return;
         char *reg = smem + wave * REGION;
         const float scale = P.scale;
-        const Tail tl = make_tail(P);
-        {
+        // parks the sub-tile in LDS with tail tl applied and writes it out `delta` bytes from its place in C
+        auto emit = [&](const Tail &tl, int64_t delta) __attribute__((always_inline)) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -487,7 +487,6 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
                             *reinterpret_cast<out4 *>(dst) = o;
                         }
                     }
-        }
         constexpr int CH = ROWB / 16, RPI = 64 / CH;         // 16-byte pieces per row; rows per store instruction
         static_assert(CH <= 64 && 64 % CH == 0 && WTM % RPI == 0, "sub-tile rows must tile a wavefront");
 #pragma unroll
@@ -505,8 +504,14 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
                 for (int gg = 1; gg < DXG; ++gg) cbase = (g == gg) ? cgrp[gg] : cbase;
                 col &= 63;
             }
-            if (ok) store_out(cbase + (int64_t)(wm * WTM + row) * ldc + col * ESZ, v);
+            if (ok) store_out(cbase + delta + (int64_t)(wm * WTM + row) * ldc + col * ESZ, v);
         }
+        };
+        if constexpr (TAIL && OP == DX) {
+            // the producing layer's value before the activation, to the second output
+            if (P.C2) emit(make_tail_preact(P), P.C2 - P.C);
+        }
+        emit(make_tail(P), 0);
         GEMM_TICK(4);
     }
 }

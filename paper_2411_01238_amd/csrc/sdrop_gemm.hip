@@ -65,7 +65,7 @@ int cu_count();
 
 // Kernels with the element-wise tail are separate instantiations, so that eq. (1)-(3) proper run
 // exactly the code they would without it.
-inline bool has_tail(const GemmParams &P) { return P.bias != nullptr || P.aux != nullptr || P.act != 0; }
+inline bool has_tail(const GemmParams &P) { return P.bias != nullptr || P.aux != nullptr || P.act != 0 || P.C2 != nullptr; }
 
 template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
 int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok);
@@ -335,6 +335,7 @@ GemmParams base_params(int op, const void *a, const void *b, const void *mask, v
     P.total_tiles = 0;
     P.scale = (p < 1.0) ? (float)(1.0 / (1.0 - p)) : 0.0f;
     P.bias = nullptr; P.aux = nullptr; P.act = SDROP_ACT_NONE;
+    P.gate_mode = SDROP_GATE_RELU; P.C2 = nullptr;
     P.p = p;
     return P;
 }
@@ -361,13 +362,14 @@ template <int OP>
 int run(const void *a, const void *b, const void *mask, void *out,
         int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
         int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
-        const sdrop_epilogue_t *epi = nullptr)
+        const sdrop_epilogue_t *epi = nullptr, void *out2 = nullptr)
 {
     const int rc = check_gemm_args(a, b, mask, out, M, K, N, BM, BK, p, dtype, out_dtype);
     if (rc != SDROP_OK) return rc;
     if (epi) {
         if (epi->scale_mode != SDROP_SCALE_DROPOUT && epi->scale_mode != SDROP_SCALE_ONE) return SDROP_EINVAL;
         if (epi->act < SDROP_ACT_NONE || epi->act > SDROP_ACT_GELU_ERF) return SDROP_EINVAL;
+        if (epi->gate_mode < SDROP_GATE_RELU || epi->gate_mode > SDROP_GATE_GELU_ERF) return SDROP_EINVAL;
         // the gradient of the weights takes a scale only
         if (OP == DW && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask)) return SDROP_EINVAL;
         if ((reinterpret_cast<uintptr_t>(epi->bias) | reinterpret_cast<uintptr_t>(epi->relu_mask)) % 16) return SDROP_EALIGN;
@@ -391,6 +393,11 @@ int run(const void *a, const void *b, const void *mask, void *out,
         P.bias = epi->bias;
         P.aux = static_cast<const char *>(epi->relu_mask);
         P.act = epi->act;
+        P.gate_mode = epi->gate_mode;
+    }
+    if (out2) {
+        if (reinterpret_cast<uintptr_t>(out2) % 16) return SDROP_EALIGN;
+        P.C2 = static_cast<char *>(out2);
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if constexpr (OP == DW) {
@@ -640,7 +647,7 @@ int sdrop_bwd_dw_ex(const void *X, const void *dY, const void *mask, void *dW,
     return sdrop::run<sdrop::DW>(X, dY, mask, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, epi);
 }
 
-int sdrop_producer(const void *H, const void *W0, const float *bias, const void *mask, void *X,
+int sdrop_producer(const void *H, const void *W0, const float *bias, const void *mask, void *X, void *Z,
                    int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
                    int dtype, int out_dtype, void *stream)
 {
@@ -650,7 +657,8 @@ int sdrop_producer(const void *H, const void *W0, const float *bias, const void 
     epi.bias = bias;
     epi.relu_mask = nullptr;
     epi.ld_a = epi.ld_b = epi.ld_out = 0;
-    return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi);
+    epi.gate_mode = SDROP_GATE_RELU;
+    return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi, Z);
 }
 
 }  // extern "C"

@@ -28,6 +28,7 @@ EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_
 
 SCALE_DROPOUT, SCALE_ONE = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF = 0, 1, 2, 3
+GATE_RELU, GATE_GELU_TANH, GATE_GELU_ERF = 0, 1, 2
 
 _DTYPES = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 
@@ -49,7 +50,8 @@ class Epilogue(ctypes.Structure):
     """sdrop_epilogue_t of the header."""
     _fields_ = [("scale_mode", ctypes.c_int32), ("act", ctypes.c_int32),
                 ("bias", ctypes.c_void_p), ("relu_mask", ctypes.c_void_p),
-                ("ld_a", ctypes.c_int64), ("ld_b", ctypes.c_int64), ("ld_out", ctypes.c_int64)]
+                ("ld_a", ctypes.c_int64), ("ld_b", ctypes.c_int64), ("ld_out", ctypes.c_int64),
+                ("gate_mode", ctypes.c_int32)]
 
 
 _lib = None
@@ -93,7 +95,7 @@ def lib():
             f.restype = ci
         L.sdrop_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
         L.sdrop_bwd.restype = ci
-        L.sdrop_producer.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, ci, vp]
+        L.sdrop_producer.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, ci, vp]
         L.sdrop_producer.restype = ci
         _lib = L
     return _lib
@@ -231,10 +233,10 @@ def workspace_bytes(op, M, K, N, BM, BK, dtype, out_dtype):
     return v
 
 
-def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype):
+def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype, gate_mode=GATE_RELU):
     """Marshals the tail arguments into the C struct (leading dimensions are filled in by _gemm)."""
     e = Epilogue()
-    e.scale_mode, e.act = int(scale_mode), int(act)
+    e.scale_mode, e.act, e.gate_mode = int(scale_mode), int(act), int(gate_mode)
     e.bias = e.relu_mask = None
     e.ld_a = e.ld_b = e.ld_out = 0
     if bias is not None:
@@ -344,24 +346,24 @@ def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None)
 
 
 def sdrop_fwd_ex(X, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
-                 out_dtype=None, out=None, ws=None):
+                 out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU):
     """eq. (1) with an element-wise tail: Y = [relu_mask > 0] act(scale (X . m') W + bias)."""
     M, K = X.shape
     K2, N = W.shape
     if K2 != K or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_fwd_ex")
-    epi = _epilogue(scale_mode, act, bias, relu_mask, N, (M, N), X.dtype)
+    epi = _epilogue(scale_mode, act, bias, relu_mask, N, (M, N), X.dtype, gate_mode)
     return _gemm("sdrop_fwd_ex", OP_FWD, X, W, mask, (M, N), M, K, N, out_dtype, out, ws, epi)
 
 
 def sdrop_bwd_dx_ex(dY, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
-                    out_dtype=None, out=None, ws=None):
+                    out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU):
     """eq. (2) with an element-wise tail on the kept blocks; dropped blocks are +0."""
     M, N = dY.shape
     K, N2 = W.shape
     if N2 != N or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dx_ex")
-    epi = _epilogue(scale_mode, act, bias, relu_mask, K, (M, K), dY.dtype)
+    epi = _epilogue(scale_mode, act, bias, relu_mask, K, (M, K), dY.dtype, gate_mode)
     return _gemm("sdrop_bwd_dx_ex", OP_BWD_DX, dY, W, mask, (M, K), M, K, N, out_dtype, out, ws, epi)
 
 
@@ -375,8 +377,12 @@ def sdrop_bwd_dw_ex(X, dY, mask, scale_mode=SCALE_DROPOUT, out_dtype=None, out=N
     return _gemm("sdrop_bwd_dw_ex", OP_BWD_DW, X, dY, mask, (K, N), M, K, N, out_dtype, out, ws, epi)
 
 
-def sdrop_producer(H, W0, bias, mask, act=ACT_NONE, out_dtype=None, out=None):
-    """The layer before the dropout, output-sparse: X = m' . act(H W0^T + bias), W0 is [K, N0]."""
+def sdrop_producer(H, W0, bias, mask, act=ACT_NONE, out_dtype=None, out=None, preact=None):
+    """The layer before the dropout, output-sparse: X = m' . act(H W0^T + bias), W0 is [K, N0].
+
+    preact: None, or a tensor of X's shape and type that receives H W0^T + bias on the kept blocks
+    (its dropped blocks are left as they are); True allocates one (zero-filled).  With it the call
+    returns (X, preact)."""
     M, N0 = H.shape
     K, N02 = W0.shape
     if N02 != N0 or (M, K) != (mask.M, mask.K):
@@ -393,9 +399,15 @@ def sdrop_producer(H, W0, bias, mask, act=ACT_NONE, out_dtype=None, out=None):
         raise SdropError(EDTYPE, "sdrop_producer")
     if bias is not None and (bias.dtype != torch.float32 or tuple(bias.shape) != (K,)):
         raise ValueError("bias must be fp32 with one value per output column")
+    if preact is True:
+        preact = torch.zeros((M, K), dtype=out_dtype, device=H.device)
+    if preact is not None and (tuple(preact.shape) != (M, K) or preact.dtype != out_dtype):
+        raise ValueError("preact has the wrong shape or dtype")
     rc = lib().sdrop_producer(_dev(H, "H"), _dev(W0, "W0"),
                               _dev(bias, "bias") if bias is not None else ctypes.c_void_p(0),
-                              _dev(mask.buf, "mask"), _dev(out, "out"), M, N0, K, mask.BM, mask.BK, mask.p,
+                              _dev(mask.buf, "mask"), _dev(out, "out"),
+                              _dev(preact, "preact") if preact is not None else ctypes.c_void_p(0),
+                              M, N0, K, mask.BM, mask.BK, mask.p,
                               int(act), _DTYPES[dtype], _DTYPES[out_dtype], _stream())
     _check(rc, "sdrop_producer")
-    return out
+    return out if preact is None else (out, preact)

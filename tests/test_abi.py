@@ -153,6 +153,9 @@ def test_tail_arguments_are_checked_on_the_host():
         assert f(*base, epi(scale_mode=2)) == sdrop.EINVAL
         assert f(*base, epi(act=4)) == sdrop.EINVAL
         assert f(*base, epi(act=-1)) == sdrop.EINVAL
+        e = sdrop.Epilogue()
+        e.gate_mode = 3
+        assert f(*base, ctypes.byref(e)) == sdrop.EINVAL
     for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex"):
         f = getattr(L, name)
         assert f(*base, epi(bias=addr + 4)) == sdrop.EALIGN
@@ -173,11 +176,12 @@ def test_tail_arguments_are_checked_on_the_host():
     assert f(*base, epi(relu_mask=addr)) == sdrop.EINVAL
     # the producer: same checks as eq. (2), plus the activation
     g = L.sdrop_producer
-    ok = (p, p, null, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.ACT_RELU, sdrop.F16, sdrop.F16, null)
-    assert g(*ok[:11], 7, *ok[12:]) == sdrop.EINVAL
+    ok = (p, p, null, p, p, null, 256, 256, 256, 64, 64, 0.5, sdrop.ACT_RELU, sdrop.F16, sdrop.F16, null)
+    assert g(*ok[:12], 7, *ok[13:]) == sdrop.EINVAL
     assert g(null, *ok[1:]) == sdrop.EINVAL
-    assert g(*ok[:5], 250, *ok[6:]) == sdrop.ESHAPE
+    assert g(*ok[:6], 250, *ok[7:]) == sdrop.ESHAPE
     assert g(*ok[:2], ctypes.c_void_p(addr + 4), *ok[3:]) == sdrop.EALIGN
+    assert g(*ok[:5], ctypes.c_void_p(addr + 8), *ok[6:]) == sdrop.EALIGN      # the second output
 
 
 def test_workspace_size_is_a_whole_number_of_fp32_planes():

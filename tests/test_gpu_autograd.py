@@ -6,7 +6,7 @@ import torch
 
 from oracle import sdrop_oracle as orc
 from oracle import sparse_block_oracle as sb
-from paper_2411_01238_amd.autograd import sparsedrop_matmul, SparseDropLinear, sparse_relu_block
+from paper_2411_01238_amd.autograd import sparsedrop_matmul, SparseDropLinear, sparse_relu_block, sparse_act_block
 from paper_2411_01238_amd.workloads import make_custom
 from _util import f64, assert_close
 
@@ -49,7 +49,8 @@ def test_module_train_and_eval():
     assert layer.weight.grad is not None and layer.bias.grad is not None
 
 
-def test_sparse_relu_block_matches_oracle_forward_and_gradients():
+@pytest.mark.parametrize("act,kind", [("relu", sb.ACT_RELU), ("gelu", sb.ACT_GELU_ERF), ("gelu_tanh", sb.ACT_GELU_TANH)])
+def test_sparse_block_matches_oracle_forward_and_gradients(act, kind):
     # Linear -> ReLU -> SparseDrop -> Linear with all six GEMMs sparse, against the chain rule
     # written out in float64.  The GPU keeps the hidden activation in 16 bits and gates the backward
     # on it; the oracle gates on its own float64 pre-activation: the two can differ only where that
@@ -63,18 +64,20 @@ def test_sparse_relu_block_matches_oracle_forward_and_gradients():
     b0 = torch.randn(K, generator=g) * 0.5
     W = (torch.randn(K, N, generator=g) / K ** 0.5).to(torch.bfloat16)
     dY = torch.randn(M, N, generator=g).to(torch.bfloat16)
-    print("autograd sparse relu block", flush=True)
+    print("autograd sparse block", act, flush=True)
     h = H.cuda().requires_grad_(True)
     w0 = W0.cuda().requires_grad_(True)
     b = b0.cuda().requires_grad_(True)
     w = W.cuda().requires_grad_(True)
-    y = sparse_relu_block(h, w0, b, w, p, BM, BK, seed, stream)
+    y = sparse_act_block(h, w0, b, w, p, act, BM, BK, seed, stream)
+    if act == "relu":
+        assert torch.equal(y, sparse_relu_block(h, w0, b, w, p, BM, BK, seed, stream))
     y.backward(dY.cuda())
     torch.cuda.synchronize()
     keep = orc.mask(M // BM, K // BK, p, seed, stream)
     Hd, W0d, b0d, Wd, dYd = f64(H), f64(W0), f64(b0), f64(W), f64(dY)
-    _, Yref = sb.block_forward(Hd, W0d, b0d, Wd, keep, BM, BK, p, sb.ACT_RELU)
-    gref = sb.block_backward(Hd, W0d, b0d, Wd, keep, BM, BK, p, dYd)
+    _, Yref = sb.block_forward(Hd, W0d, b0d, Wd, keep, BM, BK, p, kind)
+    gref = sb.block_backward(Hd, W0d, b0d, Wd, keep, BM, BK, p, dYd, kind)
     # two 16-bit roundings on the way (X, then Y or a gradient): 2^-9 relative each in bf16
     tol = dict(rel_fro=6e-3, max_abs=3e-2)
     assert_close(f64(y.detach()), Yref, "block Y", **tol)

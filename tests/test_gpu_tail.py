@@ -178,3 +178,40 @@ def test_tails_with_everything_dropped_and_nothing_dropped(BM, BK, N):
     torch.cuda.synchronize()
     assert_close(f64(o), np.maximum(f64(dY) @ f64(W).T + f64(bK.cpu()), 0.0), "dense producer")
     assert_close(f64(o), sb.producer(f64(dY), f64(W), f64(bK.cpu()), allk, BM, BK, sdrop.ACT_RELU), "dense producer vs oracle")
+
+
+@pytest.mark.parametrize("M,K,N,BM,BK,dtype,p,seed", CASES[:5])
+def test_gelu_gates_and_preactivation_output(M, K, N, BM, BK, dtype, p, seed):
+    print("tail gelu gates", M, K, N, BM, BK, dtype, p, seed, flush=True)
+    X, W, dY = make_custom(M, K, N, dtype, seed=seed)
+    m = sdrop.sdrop_mask(M, K, BM, BK, p, seed, 0)
+    keep = orc.mask(M // BM, K // BK, p, seed, 0)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    Xd, Wd, dYd = f64(X), f64(W), f64(dY)
+    tag = "(%d,%d,%d,%dx%d,%s)" % (M, K, N, BM, BK, dtype)
+    # eq. (2) times the GELU's derivative at a saved pre-activation (X stands in for it: values ~ N(0,1))
+    for mode in (sdrop.GATE_GELU_TANH, sdrop.GATE_GELU_ERF):
+        ref = sb.bwd_dx_tail(dYd, Wd, keep, BM, BK, p, relu_mask=Xd, gate_mode=mode)
+        o32 = sdrop.sdrop_bwd_dx_ex(dYg, Wg, m, relu_mask=Xg, gate_mode=mode, out_dtype=torch.float32)
+        o16 = sdrop.sdrop_bwd_dx_ex(dYg, Wg, m, relu_mask=Xg, gate_mode=mode)
+        _check(o32, o16, ref, X.dtype, "gelu-gated dX" + tag + " mode %d" % mode)
+        ref = sb.fwd_tail(Xd, Wd, keep, BM, BK, p, relu_mask=dYd, gate_mode=mode)
+        o32 = sdrop.sdrop_fwd_ex(Xg, Wg, m, relu_mask=dYg, gate_mode=mode, out_dtype=torch.float32)
+        _check(o32, sdrop.sdrop_fwd_ex(Xg, Wg, m, relu_mask=dYg, gate_mode=mode), ref, X.dtype, "gelu-gated Y" + tag + " mode %d" % mode)
+    # the producing layer with its second output: the value before the activation, on the kept blocks only
+    b0 = _bias(K, seed + 90)
+    kept = _expand(keep, BM, BK)
+    for out_dtype in (torch.float32, None):
+        z = torch.full((M, K), 5.0, dtype=out_dtype or X.dtype, device="cuda")
+        x, z2 = sdrop.sdrop_producer(dYg, Wg, b0.cuda(), m, act=sdrop.ACT_GELU_ERF, out_dtype=out_dtype, preact=z)
+        torch.cuda.synchronize()
+        assert z2 is z
+        assert torch.equal(x, sdrop.sdrop_producer(dYg, Wg, b0.cuda(), m, act=sdrop.ACT_GELU_ERF, out_dtype=out_dtype))
+        zr = sb.producer_preact(dYd, Wd, f64(b0), keep, BM, BK)
+        zd = f64(z)
+        assert np.all(zd[~kept] == 5.0), "pre-activation output wrote a dropped block"
+        if out_dtype == torch.float32 or X.dtype == torch.float16:
+            got = np.where(kept, zd, 0.0)
+            assert_close(got, zr, "producer pre-activation" + tag)
+        else:
+            assert_bf16_rounding_of(np.where(kept, zd, 0.0), zr, "producer pre-activation bf16" + tag)

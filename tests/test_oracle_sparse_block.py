@@ -51,10 +51,11 @@ def test_forward_matches_library_ops(kind):
     np.testing.assert_allclose(Y, Yt.detach().numpy(), rtol=1e-12, atol=1e-12)
 
 
-def test_backward_matches_automatic_differentiation():
+@pytest.mark.parametrize("kind", [sb.ACT_RELU, sb.ACT_GELU_TANH, sb.ACT_GELU_ERF])
+def test_backward_matches_automatic_differentiation(kind):
     H, W0, b0, W, dY, keep, BM, BK, p = _case(seed=5)
-    g = sb.block_backward(H, W0, b0, W, keep, BM, BK, p, dY)
-    Ht, W0t, b0t, Wt, _, Yt = _torch_block(H, W0, b0, W, keep, BM, BK, p, sb.ACT_RELU)
+    g = sb.block_backward(H, W0, b0, W, keep, BM, BK, p, dY, kind)
+    Ht, W0t, b0t, Wt, _, Yt = _torch_block(H, W0, b0, W, keep, BM, BK, p, kind)
     (Yt * torch.tensor(dY)).sum().backward()
     np.testing.assert_allclose(g["dH"], Ht.grad.numpy(), rtol=1e-11, atol=1e-11)
     np.testing.assert_allclose(g["dW0"], W0t.grad.numpy(), rtol=1e-11, atol=1e-11)
@@ -157,3 +158,25 @@ def test_gelu_erf_is_v_times_the_normal_cdf():
     np.testing.assert_allclose(g, torch.nn.functional.gelu(torch.tensor(v)).numpy(), rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(g - sb.act(-v, sb.ACT_GELU_ERF), v, rtol=0, atol=1e-14)
     assert sb.act(np.array([0.0]), sb.ACT_GELU_ERF)[0] == 0.0
+
+
+@pytest.mark.parametrize("kind", [sb.ACT_RELU, sb.ACT_GELU_TANH, sb.ACT_GELU_ERF])
+def test_activation_derivative_by_central_differences(kind):
+    z = np.linspace(-5.0, 5.0, 401) + 0.0123            # keeps clear of the ReLU's kink at 0
+    h = 1e-6
+    fd = (sb.act(z + h, kind) - sb.act(z - h, kind)) / (2 * h)
+    np.testing.assert_allclose(sb.act_grad(z, kind), fd, rtol=0, atol=2e-9)
+
+
+@pytest.mark.parametrize("kind,mode", [(sb.ACT_GELU_TANH, sb.GATE_GELU_TANH), (sb.ACT_GELU_ERF, sb.GATE_GELU_ERF)])
+def test_gelu_backward_pieces_are_the_three_products(kind, mode):
+    """dZ of a GELU block is eq. (2) gated by the GELU's derivative at the saved pre-activation."""
+    H, W0, b0, W, dY, keep, BM, BK, p = _case(seed=17)
+    g = sb.block_backward(H, W0, b0, W, keep, BM, BK, p, dY, kind)
+    Zk = sb.producer_preact(H, W0, b0, keep, BM, BK)
+    m = np.repeat(np.repeat(keep, BM, 0), BK, 1)
+    np.testing.assert_allclose(Zk, np.where(m > 0, g["Z"], 0.0), rtol=1e-12, atol=1e-12)
+    dZ = sb.bwd_dx_tail(dY, W, keep, BM, BK, p, relu_mask=Zk, gate_mode=mode)
+    np.testing.assert_allclose(dZ, g["dZ"], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(sb.fwd_tail(dZ, W0, keep, BM, BK, p, scale_one=True), g["dH"], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(sb.bwd_dw_scaled(dZ, H, keep, BM, BK, p, scale_one=True), g["dW0"], rtol=1e-12, atol=1e-12)
