@@ -215,10 +215,10 @@ int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
 /*
  * eq. (2) and eq. (3) in one call: both gradients of the layer, which share dY and the mask and
  * do not depend on each other.  Results are bit-identical to sdrop_bwd_dx followed by
- * sdrop_bwd_dw with the same arguments.  With 128 x 128 blocks and N a multiple of 256 one
- * launch holds the workgroups of both products: those of eq. (3) start on the CUs as those of
- * eq. (2) leave them, with no launch boundary and no idle tail in between; otherwise the two
- * are launched in turn.
+ * sdrop_bwd_dw with the same arguments.  With 128 x 128 blocks (or 64 x 64 blocks and short
+ * kept lists) and N a multiple of 256 one launch holds the workgroups of both products: those
+ * of eq. (3) start on the CUs as those of eq. (2) leave them, with no launch boundary and no
+ * idle tail in between; otherwise the two are launched in turn.
  *   dY[M,N], W[K,N], X[M,K] inputs;  dX[M,K], dW[K,N] outputs, both of type `out_dtype`
  *   ws, ws_bytes  as for sdrop_bwd_dw (sdrop_workspace_bytes(SDROP_OP_BWD_DW, ...))
  * All arguments are checked before anything is enqueued.

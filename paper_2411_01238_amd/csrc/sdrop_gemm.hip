@@ -60,6 +60,18 @@
 namespace sdrop {
 namespace {
 
+// Both gradients in one launch for 64 x 64 blocks with short kept lists, where dX and dW both run one
+// workgroup per tile (four wavefronts, several workgroups per CU): workgroups [0, n_dx) are dX's tiles,
+// the rest dW's, each in the order of its separate launch.
+template <class T, class OutDX, class OutDW, int TN_DX>
+__global__ __launch_bounds__(256) void bwd_fused_tile64_kernel(GemmParams Pdx, GemmParams Pdw, int n_dx)
+{
+    if ((int)blockIdx.x < n_dx)
+        gemm_tile_body<DX, T, OutDX, 64, TN_DX, 1, 4, false, false, false>(Pdx, (int)blockIdx.x);
+    else
+        gemm_tile_body<DW, T, OutDW, 64, 256, 1, 4, false, false, false>(Pdw, (int)blockIdx.x - n_dx);
+}
+
 // WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
 int cu_count();
 
@@ -262,6 +274,9 @@ DxPlan dx_plan(const GemmParams &P)
     return plan;
 }
 
+// dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on (see dispatch_tile)
+bool dw64_persistent(const GemmParams &P) { return (1.0 - P.p) * P.MB / P.splits * (P.BM / 64) >= 16.0; }
+
 // Tile shapes: the tile edge that lies along the mask must equal the mask's block
 // (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
 // 256/BK kept blocks of one block row into a 256-wide tile.
@@ -283,8 +298,7 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         // overlaps; with short kept lists (a few slices per tile) three co-resident workgroups of the
         // per-tile kernel do better (8192 x 1024 x 1024, 64 x 64 blocks, half kept, 16 parts:
         // 26.5 against 29.5 us; 16384 x 3072 x 768, a tenth dropped, 4 parts: 121 against 101 us)
-        const double slices = (1.0 - P.p) * P.MB / P.splits * (P.BM / 64);
-        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream, slices >= 16.0);
+        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream, dw64_persistent(P));
     } else {
         const DxPlan plan = dx_plan(P);
         const int TNsel = plan.TN, G_ = TNsel / P.BK;
@@ -473,6 +487,38 @@ int launch_bwd_fused_tn(int TN, const GemmParams &Pdx, const GemmParams &Pdw, hi
     return launch_bwd_fused<T, OutDX, OutDW, 128>(Pdx, Pdw, stream);
 }
 
+template <class T, class OutDX, class OutDW, int TN_DX>
+int launch_bwd_fused_tile64(const GemmParams &Pdx, const GemmParams &Pdw, int n_dx, int n_dw, hipStream_t stream)
+{
+    constexpr int P_LDS = stages_for(64, 256) * (64 + 256) * TK * 2;      // the larger of the two bodies' needs
+    static_assert(stages_for(64, TN_DX) * (64 + TN_DX) * TK * 2 <= P_LDS, "dX's stages must fit");
+    auto k = bwd_fused_tile64_kernel<T, OutDX, OutDW, TN_DX>;
+    static int ok = -1;
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    hipLaunchKernelGGL(k, dim3((unsigned)(n_dx + n_dw)), dim3(256), P_LDS, stream, Pdx, Pdw, n_dx);
+    return hip_status(hipGetLastError());
+}
+
+// calls f(operand tag, dX's output type, dW's output type) for the call's types; a split dW writes fp32 planes
+template <class F>
+int with_bwd_types(int dtype, int out_dtype, bool split, F &&f)
+{
+    const bool o32 = out_dtype == SDROP_F32;
+    if (dtype == SDROP_F16) {
+        if (o32) return f(F16{}, float{}, float{});
+        if (split) return f(F16{}, _Float16{}, float{});
+        return f(F16{}, _Float16{}, _Float16{});
+    }
+    if (o32) return f(BF16{}, float{}, float{});
+    if (split) return f(BF16{}, __bf16{}, float{});
+    return f(BF16{}, __bf16{}, __bf16{});
+}
+
 int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void *dx, void *dw,
             int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
             int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
@@ -489,41 +535,36 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     GemmParams Pdx = base_params(DX, dy, w, mask, dx, M, K, N, BM, BK, p, out_dtype, L);
+    GemmParams Pdw = base_params(DW, x, dy, mask, dw, M, K, N, BM, BK, p, out_dtype, L);
     const DxPlan plan = dx_plan(Pdx);
-    // dX as one workgroup per tile of two kept blocks (never with one block per tile: that form is persistent)
-    const bool tile_form = !plan.persistent && plan.TN == 256;
-    if (g_bwd_fused && BM == 128 && BK == 128 && N % 256 == 0 && (plan.persistent || tile_form)) {
+    Pdw.splits = dw_splits(M, N, BM, BK, K);
+    // Which single launch applies, if any (all need N to be a multiple of 256, so that neither product has a ragged edge):
+    //   persistent dX + persistent dW                      128 x 128 blocks, dX on its persistent kernel
+    //   dX a workgroup per tile of two blocks + persistent dW   128 x 128 blocks otherwise
+    //   both a workgroup per tile                          64 x 64 blocks, dW with short kept lists
+    enum { kNone, kPersistent, kTile128, kTile64 } form = kNone;
+    if (g_bwd_fused && N % 256 == 0) {
+        if (BM == 128 && BK == 128) form = plan.persistent ? kPersistent : (plan.TN == 256 ? kTile128 : kNone);
+        else if (BM == 64 && BK == 64 && !dw64_persistent(Pdw)) form = kTile64;
+    }
+    if (form != kNone) {
         const int G_ = plan.TN / BK;
         Pdx.n_tiles = (Pdx.KB + G_ - 1) / G_;
         const int n_dx = Pdx.MB * Pdx.n_tiles;           // the per-tile launch's grid: (group of the row, block row)
-        GemmParams Pdw = base_params(DW, x, dy, mask, dw, M, K, N, BM, BK, p, out_dtype, L);
-        Pdw.splits = dw_splits(M, N, BM, BK, K);
         Pdw.n_tiles = (int)(N / 256);
         Pdw.total_tiles = Pdw.KB * Pdw.n_tiles * Pdw.splits;
         const float scale = Pdw.scale;
         const bool split = Pdw.splits > 1;
         if (split) { Pdw.C = static_cast<char *>(ws); Pdw.ldc = N * 4; Pdw.scale = 1.0f; }
-        const bool f16 = dtype == SDROP_F16, o32 = out_dtype == SDROP_F32;
-        int rf;
-        if (tile_form) {
-            if (f16) {
-                if (o32) rf = launch_bwd_fused_tile<F16, float, float>(Pdx, Pdw, n_dx, st);
-                else if (split) rf = launch_bwd_fused_tile<F16, _Float16, float>(Pdx, Pdw, n_dx, st);
-                else rf = launch_bwd_fused_tile<F16, _Float16, _Float16>(Pdx, Pdw, n_dx, st);
-            } else {
-                if (o32) rf = launch_bwd_fused_tile<BF16, float, float>(Pdx, Pdw, n_dx, st);
-                else if (split) rf = launch_bwd_fused_tile<BF16, __bf16, float>(Pdx, Pdw, n_dx, st);
-                else rf = launch_bwd_fused_tile<BF16, __bf16, __bf16>(Pdx, Pdw, n_dx, st);
-            }
-        } else if (f16) {
-            if (o32) rf = launch_bwd_fused_tn<F16, float, float>(plan.TN, Pdx, Pdw, st);
-            else if (split) rf = launch_bwd_fused_tn<F16, _Float16, float>(plan.TN, Pdx, Pdw, st);
-            else rf = launch_bwd_fused_tn<F16, _Float16, _Float16>(plan.TN, Pdx, Pdw, st);
-        } else {
-            if (o32) rf = launch_bwd_fused_tn<BF16, float, float>(plan.TN, Pdx, Pdw, st);
-            else if (split) rf = launch_bwd_fused_tn<BF16, __bf16, float>(plan.TN, Pdx, Pdw, st);
-            else rf = launch_bwd_fused_tn<BF16, __bf16, __bf16>(plan.TN, Pdx, Pdw, st);
-        }
+        const int rf = with_bwd_types(dtype, out_dtype, split, [&](auto t, auto odx, auto odw) -> int {
+            using T = decltype(t);
+            using ODX = decltype(odx);
+            using ODW = decltype(odw);
+            if (form == kPersistent) return launch_bwd_fused_tn<T, ODX, ODW>(plan.TN, Pdx, Pdw, st);
+            if (form == kTile128) return launch_bwd_fused_tile<T, ODX, ODW>(Pdx, Pdw, n_dx, st);
+            if (plan.TN == 256) return launch_bwd_fused_tile64<T, ODX, ODW, 256>(Pdx, Pdw, n_dx, Pdw.total_tiles, st);
+            return launch_bwd_fused_tile64<T, ODX, ODW, 128>(Pdx, Pdw, n_dx, Pdw.total_tiles, st);
+        });
         if (rf != -1) {     // -1: the device does not grant the LDS; fall through to the two calls
             if (rf != SDROP_OK || !split) return rf;
             return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, N, Pdw);

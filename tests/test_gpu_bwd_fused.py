@@ -21,7 +21,10 @@ CASES = [
     (1536, 1536, 512, 128, 128, "bf16", 0.0, 14, False),  # the same with nothing dropped and a split dW
     (4096, 1024, 256, 128, 128, "f16", 0.7, 4, False),    # one launch: more dX workgroups than kept blocks
     (512, 768, 328, 128, 128, "bf16", 0.3, 5, False),     # ragged N: two launches
-    (384, 512, 256, 64, 64, "f16", 0.5, 6, False),        # 64 x 64 blocks: two launches
+    (384, 512, 256, 64, 64, "f16", 0.5, 6, False),        # 64 x 64 blocks, short kept lists: one launch, both a workgroup per tile
+    (2048, 512, 256, 64, 64, "bf16", 0.3, 16, False),     # the same with dW split into parts and summed
+    (4096, 256, 256, 64, 64, "bf16", 0.0, 17, False),     # 64 x 64 blocks, long kept lists (persistent dW): two launches
+    (384, 512, 328, 64, 64, "f16", 0.5, 18, False),       # 64 x 64 blocks, ragged N: two launches
     (512, 512, 256, 128, 64, "bf16", 0.4, 7, False),      # 128 x 64 blocks: two launches
     (128, 128, 256, 128, 128, "bf16", 0.0, 8, False),     # a single block
 ]
@@ -72,3 +75,22 @@ def test_everything_dropped_and_outputs_given():
     assert a is dx and b is dw
     for o in (dx, dw):
         assert torch.count_nonzero(o).item() == 0 and not torch.signbit(o).any().item()
+
+
+@pytest.mark.parametrize("width", [128, 256])
+def test_one_launch_for_64_blocks_with_either_dx_tile_width(width):
+    M, K, N, B, p, seed = 1024, 768, 512, 64, 0.4, 21
+    print("bwd fused 64-blocks width", width, flush=True)
+    X, W, dY = make_custom(M, K, N, "bf16", seed=seed)
+    m = sdrop.sdrop_mask(M, K, B, B, p, seed, 0)
+    keep = orc.mask(M // B, K // B, p, seed, 0)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    sdrop.set_tuning(sdrop.TUNE_DX_TILE_WIDTH, width)
+    try:
+        dx, dw = sdrop.sdrop_bwd(dYg, Wg, Xg, m, out_dtype=torch.float32)
+        assert torch.equal(dx, sdrop.sdrop_bwd_dx(dYg, Wg, m, out_dtype=torch.float32))
+        assert torch.equal(dw, sdrop.sdrop_bwd_dw(Xg, dYg, m, out_dtype=torch.float32))
+    finally:
+        sdrop.set_tuning(sdrop.TUNE_DX_TILE_WIDTH, 0)
+    assert_close(f64(dx), orc.bwd_dx(f64(dY), f64(W), keep, B, B, p), "dX 64-blocks width %d" % width)
+    assert_close(f64(dw), orc.bwd_dw(f64(X), f64(dY), keep, B, B, p), "dW 64-blocks width %d" % width)
