@@ -120,7 +120,14 @@ def _check(code, what):
         raise SdropError(code, what)
 
 
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream():
+    """The current HIP stream of the current device, as a pointer."""
+    if _raw_stream is not None:
+        # one C call instead of building a torch.cuda.Stream object (a third of a call's host time)
+        return ctypes.c_void_p(_raw_stream(torch.cuda.current_device()))
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
