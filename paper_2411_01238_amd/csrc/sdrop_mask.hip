@@ -66,7 +66,8 @@ __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint3
 // and split_k times along K; without it this is i * KB + j.
 __device__ __forceinline__ uint64_t logical_block(const MaskParams &P, int64_t i, int j)
 {
-    return (uint64_t)(i / P.split_m) * (uint64_t)P.KBL + (uint64_t)(j / P.split_k);
+    // block rows and columns are below 2^31: 32-bit divisions (a 64-bit one costs several times as much)
+    return (uint64_t)((uint32_t)i / (uint32_t)P.split_m) * (uint64_t)P.KBL + (uint64_t)((uint32_t)j / (uint32_t)P.split_k);
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
@@ -138,10 +139,14 @@ __device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t
 // [row_ptr[8g], row_ptr[8g + 8)); inside it a block's place is the number of kept blocks of the
 // group in earlier columns (a prefix sum over the lanes) plus those above it in its own column.
 // `bits` and `row_ptr` may be in LDS or in global memory written earlier by this workgroup.
-__device__ void local_order(const uint64_t *bits, const int32_t *row_ptr, const MaskParams &P)
+// The groups are shared by wavefronts [wave0, wave0 + nw) of the workgroup; the others return at once.
+__device__ void local_order(const uint64_t *bits, const int32_t *row_ptr, const MaskParams &P,
+                            int wave0 = 0, int nw = kMaskWaves)
 {
     const int lane = lane_id();
-    for (int i0 = wave_id() * 8; i0 < P.MB; i0 += kMaskWaves * 8) {
+    const int me = wave_id() - wave0;
+    if (me < 0 || me >= nw) return;
+    for (int i0 = me * 8; i0 < P.MB; i0 += nw * 8) {
         const int nr = P.MB - i0 < 8 ? P.MB - i0 : 8;
         int pos = row_ptr[i0];
         for (int w = 0; w < P.wpr; ++w) {
@@ -355,6 +360,28 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
     }
     if (threadIdx.x < 2) s_max[threadIdx.x] = 0;
     if constexpr (DRAW) {
+        if (P.wpr == 1 && P.KB <= 32) {
+            // narrow grids: a wavefront draws R = 64 / (KB rounded up to a power of two) block rows at
+            // a time, so that no lane idles through the ten Philox rounds; the ballot holds R row words
+            int kbp = 1;
+            while (kbp < P.KB) kbp <<= 1;
+            const int R = 64 / kbp, sub = lane / kbp, j = lane & (kbp - 1);
+            for (int g = wave; g * R < P.MB; g += kMaskWaves) {
+                const int i = g * R + sub;
+                bool keep = false;
+                if (i < P.MB && j < P.KB) {
+                    const uint64_t b = logical_block(P, i, j);
+                    const uint32_t r = philox_word0((uint32_t)b, (uint32_t)(b >> 32), P.ctr2, P.ctr3, P.key0, P.key1);
+                    keep = (uint64_t)r >= P.threshold;
+                }
+                const uint64_t all = __ballot(keep);
+                if (j == 0 && i < P.MB) {
+                    const uint64_t word = (all >> (sub * kbp)) & ((uint64_t(1) << kbp) - 1);
+                    s_bits[i] = word;
+                    P.bits[i] = word;
+                }
+            }
+        } else
         for (int g = wave; g < nwords; g += kMaskWaves) {
             const int i = g / P.wpr, w = g % P.wpr, j = w * 64 + lane;
             bool keep = false;
@@ -434,7 +461,15 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
     // -- phase 3: the lists --
     for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
     for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = s_col_ptr[j];
-    for (int i = wave; i < P.MB; i += kMaskWaves) {
+    // The three kinds of lists do not depend on each other.  With few groups of 8 block rows (a small
+    // grid) the locally ordered list would keep only that many wavefronts busy, on top of their share
+    // of the other lists: those groups then get wavefronts of their own, the last ones, and the row
+    // and column lists are shared by the rest.
+    const int ngroups = (P.MB + 7) / 8;
+    const int nlo = ngroups < kMaskWaves / 2 ? ngroups : 0;       // wavefronts that only build the locally ordered list
+    const int nls = kMaskWaves - nlo;                              // wavefronts that build the row and column lists
+    if (nlo > 0) local_order(s_bits, s_row_ptr, P, nls, nlo);
+    for (int i = wave; i < P.MB && wave < nls; i += nls) {
         int pos = s_row_ptr[i];
         for (int w = 0; w < P.wpr; ++w) {
             const uint64_t word = s_bits[i * P.wpr + w];
@@ -447,9 +482,9 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         }
     }
     MASK_TICK(4);
-    local_order(s_bits, s_row_ptr, P);
+    if (nlo == 0) local_order(s_bits, s_row_ptr, P);
     MASK_TICK(5);
-    for (int j = wave; j < P.KB; j += kMaskWaves) {
+    for (int j = wave; j < P.KB && wave < nls; j += nls) {
         int pos = s_col_ptr[j];
         for (int i0 = 0; i0 < P.MB; i0 += 64) {
             const int i = i0 + lane;

@@ -56,6 +56,12 @@ def test_mask_matches_oracle_on_every_workload(name, p, layer):
     (64 * 2100, 64 * 2, 64, 64, 0.5, 6, 1),      # MB > 2048: the list builder that works in global memory
     (128 * 3, 64 * 2100, 128, 64, 0.25, 7, 2),   # KB > 2048: 33 words per row
     (128 * 64, 128 * 1, 128, 128, 0.5, 8, 0),    # a single block column
+    # narrow grids drawn by the list kernel itself, several block rows per wavefront and ballot
+    (64 * 7, 64 * 20, 64, 64, 0.5, 9, 0),        # KB = 20 (two rows per ballot), odd number of rows
+    (128 * 13, 128 * 5, 128, 128, 0.3, 10, 1),   # KB = 5 (eight rows per ballot), 13 rows
+    (64 * 33, 64 * 32, 64, 64, 0.6, 11, 2),      # KB = 32 exactly, 33 rows
+    (64 * 50, 64 * 1, 64, 64, 0.5, 12, 3),       # KB = 1: 64 rows per ballot
+    (128 * 2, 128 * 17, 128, 128, 0.4, 13, 4),   # KB = 17 rounds up to 32
 ])
 def test_mask_edge_shapes(M, K, BM, BK, p, seed, stream):
     print("mask edge", M, K, BM, BK, p, seed, stream, flush=True)
