@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsdrop.so")
-SOURCES = ["sdrop_mask.hip", "sdrop_gemm.hip"]
+SOURCES = ["sdrop_mask.hip", "sdrop_gemm.hip", "sdrop_gemm_f16.hip", "sdrop_gemm_bf16.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

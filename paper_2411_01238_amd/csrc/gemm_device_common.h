@@ -1,4 +1,4 @@
-// Device-side building blocks of libsdrop's GEMM kernels (included by sdrop_gemm.hip only): operand types and the MFMA
+// Device-side building blocks of libsdrop's GEMM kernels (included by the GEMM translation units only): operand types and the MFMA
 // wrapper, kernel parameters, the non-temporal output store, the element-wise tail, the LDS swizzle, the direct-load
 // engines (HBM -> LDS), the register path for ragged edges, operand reads from LDS, scheduling helpers.
 #ifndef SDROP_GEMM_DEVICE_COMMON_H
@@ -10,6 +10,33 @@
 #include <utility>
 
 namespace sdrop {
+
+// What the translation units of the GEMMs share by name (everything else here is per translation unit).
+struct F16 {};      // operand type tags
+struct BF16 {};
+enum Op { FWD = 0, DX = 1, DW = 2 };
+
+struct GemmParams {
+    const char *A;      // FWD: X   DX: dY  DW: X
+    const char *B;      // FWD: W   DX: W   DW: dY
+    char *C;            // FWD: Y   DX: dX  DW: dW
+    MaskView mv;
+    int64_t M, K, N;
+    int64_t lda, ldb, ldc;   // bytes between consecutive rows of A, B and C (contiguous: columns * element size)
+    int32_t BM, BK, MB, KB;
+    int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
+    int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)
+    int32_t total_tiles; // persistent kernels: tiles of the whole launch
+    float scale;
+    // optional element-wise tail of FWD and DX (see Tail below); all null / 0 for eq. (1)-(3) proper
+    const float *bias;
+    const char *aux;
+    int32_t act;
+    int32_t gate_mode;  // how aux gates the output (SDROP_GATE_*)
+    char *C2;           // DX only: second output, the value before the activation (same shape, type and stride as C), or null
+    double p;           // host only: dropout probability, for choosing tile shapes
+};
+
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
@@ -18,9 +45,6 @@ typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-struct F16 {};
-struct BF16 {};
 
 template <class T> struct In;
 template <> struct In<F16> {
@@ -58,8 +82,6 @@ constexpr int kThreads = 256;    // 4 wavefronts per workgroup
 // two for tiles of 64 rows, so that two or three workgroups share a CU (measured faster there).
 constexpr int stages_for(int tm, int tn) { return (void)tn, tm <= 64 ? 2 : 3; }
 
-enum Op { FWD = 0, DX = 1, DW = 2 };
-
 // A value that is the same in every lane, told to the compiler (it then lives in a scalar register
 // and everything derived from it is scalar arithmetic).
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -74,26 +96,6 @@ __device__ long long g_ticks[16384 * 16];
 #define GEMM_TICKW(n) do { } while (0)
 #endif
 
-struct GemmParams {
-    const char *A;      // FWD: X   DX: dY  DW: X
-    const char *B;      // FWD: W   DX: W   DW: dY
-    char *C;            // FWD: Y   DX: dX  DW: dW
-    MaskView mv;
-    int64_t M, K, N;
-    int64_t lda, ldb, ldc;   // bytes between consecutive rows of A, B and C (contiguous: columns * element size)
-    int32_t BM, BK, MB, KB;
-    int32_t n_tiles;    // FWD/DW: TN-wide tiles along N.  DX: groups of kept blocks per block row
-    int32_t splits;     // DW: parts the kept-row list of a block column is cut into (1 = no split)
-    int32_t total_tiles; // persistent kernels: tiles of the whole launch
-    float scale;
-    // optional element-wise tail of FWD and DX (see Tail below); all null / 0 for eq. (1)-(3) proper
-    const float *bias;
-    const char *aux;
-    int32_t act;
-    int32_t gate_mode;  // how aux gates the output (SDROP_GATE_*)
-    char *C2;           // DX only: second output, the value before the activation (same shape, type and stride as C), or null
-    double p;           // host only: dropout probability, for choosing tile shapes
-};
 
 // 16 bytes of output, as a non-temporal store.  Outputs are written once and not read again by the
 // kernel that writes them; stored this way they neither displace operand tiles from the L2s and

@@ -1,0 +1,39 @@
+// Host-side declarations shared by the GEMM translation units: the launch heuristics and knobs (defined in
+// sdrop_gemm.hip) and the two entry functions that each typed translation unit (sdrop_gemm_f16.hip,
+// sdrop_gemm_bf16.hip) instantiates for its operand type.  The kernels are compiled per operand type in
+// separate files so that they build in parallel.
+#ifndef SDROP_GEMM_HOST_H
+#define SDROP_GEMM_HOST_H
+#include "gemm_device_common.h"
+
+namespace sdrop {
+
+int cu_count();
+
+// Kernels with the element-wise tail are separate instantiations, so that eq. (1)-(3) proper run
+// exactly the code they would without it.
+inline bool has_tail(const GemmParams &P) { return P.bias != nullptr || P.aux != nullptr || P.act != 0 || P.C2 != nullptr; }
+
+// dX: width of the tiles, and whether the persistent kernel computes them (see sdrop_gemm.hip)
+struct DxPlan { int TN; bool persistent; };
+DxPlan dx_plan(const GemmParams &P);
+// dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on
+bool dw64_persistent(const GemmParams &P);
+
+// which single launch sdrop_bwd uses (see run_bwd)
+enum BwdForm { kBwdNone = 0, kBwdPersistent, kBwdTile128, kBwdTile64 };
+
+// One of the three products for operands of type T: picks tile shapes and kernel form, launches.
+// o32: fp32 output instead of the operands' type.
+template <class T> int dispatch_typed(int op, bool o32, GemmParams &P, hipStream_t stream);
+// Both gradients in one launch, in the given form; dw_f32: dW's launch writes fp32 planes (a split reduction).
+// Returns -1 when the device does not grant the LDS the launch needs.
+template <class T> int bwd_fused_typed(int form, int TN, bool o32, bool dw_f32, const GemmParams &Pdx, const GemmParams &Pdw,
+                                       int n_dx, hipStream_t stream);
+extern template int dispatch_typed<F16>(int, bool, GemmParams &, hipStream_t);
+extern template int dispatch_typed<BF16>(int, bool, GemmParams &, hipStream_t);
+extern template int bwd_fused_typed<F16>(int, int, bool, bool, const GemmParams &, const GemmParams &, int, hipStream_t);
+extern template int bwd_fused_typed<BF16>(int, int, bool, bool, const GemmParams &, const GemmParams &, int, hipStream_t);
+
+}  // namespace sdrop
+#endif

@@ -1,0 +1,241 @@
+// Launch logic of the GEMM kernels for one operand type (included by the typed translation units only).
+#ifndef SDROP_GEMM_LAUNCH_H
+#define SDROP_GEMM_LAUNCH_H
+#include "gemm_host.h"
+#include "gemm_tile_kernel.h"
+#include "gemm_persistent_kernels.h"
+
+namespace sdrop {
+namespace {
+
+// WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
+
+
+template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
+int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok);
+
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
+int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok = true)
+{
+    if constexpr (OP != DW) {
+        if (has_tail(P)) return launch_t<true, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
+    }
+    return launch_t<false, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
+}
+
+template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
+int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok)
+{
+    constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
+    constexpr bool SPEC = TM >= 128;     // loader wavefronts for the one-workgroup-per-CU tiles
+    auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false, SPEC, TAIL>;
+    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WMR, WNR, true, false, TAIL>;
+    static bool attr_set = false;   // per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_full),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_ragged),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return hip_status(e);
+        attr_set = true;
+    }
+    if (grid <= 0) return SDROP_OK;
+    if constexpr (OP != DX) {
+        if (!ragged && persistent_ok) {
+            // persistent form: three operand stages plus 4 KiB of output staging per computing wavefront
+            constexpr int P_LDS = 3 * (TM + TN) * TK * 2 + WM * WN * 4096;
+            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TAIL>;
+            static int pers_ok = -1;    // per instantiation: does the device grant that much LDS?
+            if (pers_ok < 0) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_pers),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+                pers_ok = (e == hipSuccess);
+                if (!pers_ok) (void)hipGetLastError();
+            }
+#ifdef SDROP_GEMM_TIMING
+            const bool pers_off = getenv("SDROP_NO_PERSIST") != nullptr;
+#else
+            const bool pers_off = false;
+#endif
+            if (pers_ok && !pers_off) {
+                GemmParams Q = P;
+                Q.total_tiles = grid;
+                const int ncu = cu_count();
+                hipLaunchKernelGGL(k_pers, dim3(grid < ncu ? grid : ncu), dim3(WM * WN * 128), P_LDS, stream, Q);
+                return hip_status(hipGetLastError());
+            }
+        }
+    }
+    if (ragged) hipLaunchKernelGGL(k_ragged, dim3(grid), dim3(WMR * WNR * 64), LDS_BYTES, stream, P);
+    else hipLaunchKernelGGL(k_full, dim3(grid), dim3(WM * WN * 64 * (SPEC ? 2 : 1)), LDS_BYTES, stream, P);
+    return hip_status(hipGetLastError());
+}
+
+// Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
+template <class T, class OutT, int TN, bool TAIL>
+int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
+
+template <class T, class OutT, int TN>
+int launch_dx_persistent(const GemmParams &P, hipStream_t stream)
+{
+    if (has_tail(P)) return launch_dx_persistent_t<T, OutT, TN, true>(P, stream);
+    return launch_dx_persistent_t<T, OutT, TN, false>(P, stream);
+}
+
+template <class T, class OutT, int TN, bool TAIL>
+int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
+{
+    constexpr int P_LDS = 3 * (128 + TN) * TK * 2 + 4 * 4096;
+    auto k = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2, TAIL>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+#ifdef SDROP_GEMM_TIMING
+    if (getenv("SDROP_NO_PERSIST")) return -1;
+#endif
+    if (!ok) return -1;
+    const int64_t positions = (int64_t)P.MB * P.KB;
+    const int ncu = cu_count();
+    hipLaunchKernelGGL(k, dim3((unsigned)(positions < ncu ? positions : ncu)), dim3(512), P_LDS, stream, P);
+    return hip_status(hipGetLastError());
+}
+
+// Tile shapes: the tile edge that lies along the mask must equal the mask's block
+// (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
+// 256/BK kept blocks of one block row into a 256-wide tile.
+template <int OP, class T, class OutT>
+int dispatch_tile(GemmParams &P, hipStream_t stream)
+{
+    if constexpr (OP == FWD) {
+        P.n_tiles = (int)((P.N + 255) / 256);
+        const int grid = P.MB * P.n_tiles;
+        const bool ragged = P.N % 256 != 0;
+        if (P.BM == 128) return launch<FWD, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
+        return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
+    } else if constexpr (OP == DW) {
+        P.n_tiles = (int)((P.N + 255) / 256);
+        const int grid = P.KB * P.n_tiles * P.splits;
+        const bool ragged = P.N % 256 != 0;
+        if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
+        // 64-row tiles: the persistent kernel runs one workgroup per CU, whose epilogue nothing
+        // overlaps; with short kept lists (a few slices per tile) three co-resident workgroups of the
+        // per-tile kernel do better (8192 x 1024 x 1024, 64 x 64 blocks, half kept, 16 parts:
+        // 26.5 against 29.5 us; 16384 x 3072 x 768, a tenth dropped, 4 parts: 121 against 101 us)
+        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream, dw64_persistent(P));
+    } else {
+        const DxPlan plan = dx_plan(P);
+        const int TNsel = plan.TN, G_ = TNsel / P.BK;
+        P.n_tiles = (P.KB + G_ - 1) / G_;
+        // one kept block per tile: a workgroup per block position, rounded up to whole sets of 8 XCDs
+        const int grid = G_ == 1 ? (P.MB * P.KB + 7) / 8 * 8 : P.MB * P.n_tiles;
+        const bool ragged = P.N % TK != 0;
+        if (plan.persistent) {
+            const int rc = TNsel == 256 ? launch_dx_persistent<T, OutT, 256>(P, stream) : launch_dx_persistent<T, OutT, 128>(P, stream);
+            if (rc != -1) return rc;      // -1: the device does not grant the LDS; use the per-tile kernels
+        }
+        if (TNsel == 256) {
+            if (P.BM == 128) return launch<DX, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
+            return launch<DX, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
+        }
+        if (P.BM == 128) return launch<DX, T, OutT, 128, 128, 2, 2>(P, grid, ragged, stream);
+        return launch<DX, T, OutT, 64, 128, 1, 4>(P, grid, ragged, stream);
+    }
+}
+
+template <class T, class OutDX, class OutDW, int TN_DX>
+int launch_bwd_fused(const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
+{
+    constexpr int LDS_DX = 3 * (128 + TN_DX) * TK * 2 + 4 * 4096, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
+    constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
+    auto k = bwd_fused_kernel<T, OutDX, OutDW, TN_DX>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    const int ncu = cu_count();
+    const int64_t positions = (int64_t)Pdx.MB * Pdx.KB;
+    const int g_dx = (int)(positions < ncu ? positions : ncu);
+    const int g_dw = Pdw.total_tiles < ncu ? Pdw.total_tiles : ncu;
+    hipLaunchKernelGGL(k, dim3((unsigned)(g_dx + g_dw)), dim3(512), P_LDS, stream, Pdx, Pdw, g_dx);
+    return hip_status(hipGetLastError());
+}
+
+template <class T, class OutDX, class OutDW>
+int launch_bwd_fused_tile(const GemmParams &Pdx, const GemmParams &Pdw, int n_dx, hipStream_t stream)
+{
+    constexpr int LDS_DX = 3 * (128 + 256) * TK * 2, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
+    constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
+    auto k = bwd_fused_tile_kernel<T, OutDX, OutDW>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    const int ncu = cu_count();
+    const int g_dw = Pdw.total_tiles < ncu ? Pdw.total_tiles : ncu;
+    hipLaunchKernelGGL(k, dim3((unsigned)(n_dx + g_dw)), dim3(512), P_LDS, stream, Pdx, Pdw, n_dx);
+    return hip_status(hipGetLastError());
+}
+
+template <class T, class OutDX, class OutDW>
+int launch_bwd_fused_tn(int TN, const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
+{
+    if (TN == 256) return launch_bwd_fused<T, OutDX, OutDW, 256>(Pdx, Pdw, stream);
+    return launch_bwd_fused<T, OutDX, OutDW, 128>(Pdx, Pdw, stream);
+}
+
+template <class T, class OutDX, class OutDW, int TN_DX>
+int launch_bwd_fused_tile64(const GemmParams &Pdx, const GemmParams &Pdw, int n_dx, int n_dw, hipStream_t stream)
+{
+    constexpr int P_LDS = stages_for(64, 256) * (64 + 256) * TK * 2;      // the larger of the two bodies' needs
+    static_assert(stages_for(64, TN_DX) * (64 + TN_DX) * TK * 2 <= P_LDS, "dX's stages must fit");
+    auto k = bwd_fused_tile64_kernel<T, OutDX, OutDW, TN_DX>;
+    static int ok = -1;
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    hipLaunchKernelGGL(k, dim3((unsigned)(n_dx + n_dw)), dim3(256), P_LDS, stream, Pdx, Pdw, n_dx);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+template <class T> int dispatch_typed(int op, bool o32, GemmParams &P, hipStream_t stream)
+{
+    using O16 = typename In<T>::out16;
+    if (op == FWD) return o32 ? dispatch_tile<FWD, T, float>(P, stream) : dispatch_tile<FWD, T, O16>(P, stream);
+    if (op == DX) return o32 ? dispatch_tile<DX, T, float>(P, stream) : dispatch_tile<DX, T, O16>(P, stream);
+    return o32 ? dispatch_tile<DW, T, float>(P, stream) : dispatch_tile<DW, T, O16>(P, stream);
+}
+
+template <class T> int bwd_fused_typed(int form, int TN, bool o32, bool dw_f32, const GemmParams &Pdx, const GemmParams &Pdw,
+                                       int n_dx, hipStream_t stream)
+{
+    using O16 = typename In<T>::out16;
+    auto go = [&](auto odx, auto odw) -> int {
+        using ODX = decltype(odx);
+        using ODW = decltype(odw);
+        if (form == kBwdPersistent) return launch_bwd_fused_tn<T, ODX, ODW>(TN, Pdx, Pdw, stream);
+        if (form == kBwdTile128) return launch_bwd_fused_tile<T, ODX, ODW>(Pdx, Pdw, n_dx, stream);
+        if (TN == 256) return launch_bwd_fused_tile64<T, ODX, ODW, 256>(Pdx, Pdw, n_dx, Pdw.total_tiles, stream);
+        return launch_bwd_fused_tile64<T, ODX, ODW, 128>(Pdx, Pdw, n_dx, Pdw.total_tiles, stream);
+    };
+    if (o32) return go(float{}, float{});
+    if (dw_f32) return go(O16{}, float{});
+    return go(O16{}, O16{});
+}
+
+}  // namespace sdrop
+#endif

@@ -1,5 +1,5 @@
 // The persistent forms of the three block-sparse GEMMs and the launches that hold both gradients (included by
-// sdrop_gemm.hip only; the design notes are at the top of that file).
+// the typed GEMM translation units only; the design notes are at the top of that file).
 #ifndef SDROP_GEMM_PERSISTENT_KERNELS_H
 #define SDROP_GEMM_PERSISTENT_KERNELS_H
 #include "gemm_tile_kernel.h"
@@ -780,6 +780,18 @@ __global__ __launch_bounds__(512) void bwd_fused_tile_kernel(GemmParams Pdx, Gem
         gemm_tile_body<DX, T, OutDX, 128, 256, 2, 2, false, true, false>(Pdx, (int)blockIdx.x);
     else
         gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - n_dx, (int)blockIdx.x - n_dx);
+}
+
+// Both gradients in one launch for 64 x 64 blocks with short kept lists, where dX and dW both run one
+// workgroup per tile (four wavefronts, several workgroups per CU): workgroups [0, n_dx) are dX's tiles,
+// the rest dW's, each in the order of its separate launch.
+template <class T, class OutDX, class OutDW, int TN_DX>
+__global__ __launch_bounds__(256) void bwd_fused_tile64_kernel(GemmParams Pdx, GemmParams Pdw, int n_dx)
+{
+    if ((int)blockIdx.x < n_dx)
+        gemm_tile_body<DX, T, OutDX, 64, TN_DX, 1, 4, false, false, false>(Pdx, (int)blockIdx.x);
+    else
+        gemm_tile_body<DW, T, OutDW, 64, 256, 1, 4, false, false, false>(Pdw, (int)blockIdx.x - n_dx);
 }
 
 }  // namespace

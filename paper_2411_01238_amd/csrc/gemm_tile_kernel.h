@@ -1,4 +1,4 @@
-// The one-launch-per-tile form of the three block-sparse GEMMs (included by sdrop_gemm.hip only; the design notes are
+// The one-launch-per-tile form of the three block-sparse GEMMs (included by the typed GEMM translation units only; the design notes are
 // at the top of that file).
 #ifndef SDROP_GEMM_TILE_KERNEL_H
 #define SDROP_GEMM_TILE_KERNEL_H

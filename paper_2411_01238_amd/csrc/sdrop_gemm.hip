@@ -53,125 +53,11 @@
 // On this chip the loop is limited by power, not by issue slots: the shader clock, read in the
 // loop, is ~2.0 GHz with the MFMAs alone, ~1.55 GHz once the operand reads from LDS are added
 // and ~1.4 GHz with the loads as well, at 84 % MFMA duty (1214 clocks per slice against 1024).
-#include "gemm_device_common.h"
-#include "gemm_tile_kernel.h"
-#include "gemm_persistent_kernels.h"
+#include "gemm_host.h"
 
 namespace sdrop {
-namespace {
 
-// Both gradients in one launch for 64 x 64 blocks with short kept lists, where dX and dW both run one
-// workgroup per tile (four wavefronts, several workgroups per CU): workgroups [0, n_dx) are dX's tiles,
-// the rest dW's, each in the order of its separate launch.
-template <class T, class OutDX, class OutDW, int TN_DX>
-__global__ __launch_bounds__(256) void bwd_fused_tile64_kernel(GemmParams Pdx, GemmParams Pdw, int n_dx)
-{
-    if ((int)blockIdx.x < n_dx)
-        gemm_tile_body<DX, T, OutDX, 64, TN_DX, 1, 4, false, false, false>(Pdx, (int)blockIdx.x);
-    else
-        gemm_tile_body<DW, T, OutDW, 64, 256, 1, 4, false, false, false>(Pdw, (int)blockIdx.x - n_dx);
-}
-
-// WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
-int cu_count();
-
-// Kernels with the element-wise tail are separate instantiations, so that eq. (1)-(3) proper run
-// exactly the code they would without it.
-inline bool has_tail(const GemmParams &P) { return P.bias != nullptr || P.aux != nullptr || P.act != 0 || P.C2 != nullptr; }
-
-template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
-int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok);
-
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
-int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok = true)
-{
-    if constexpr (OP != DW) {
-        if (has_tail(P)) return launch_t<true, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
-    }
-    return launch_t<false, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
-}
-
-template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
-int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok)
-{
-    constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
-    constexpr bool SPEC = TM >= 128;     // loader wavefronts for the one-workgroup-per-CU tiles
-    auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false, SPEC, TAIL>;
-    auto k_ragged = gemm_kernel<OP, T, OutT, TM, TN, WMR, WNR, true, false, TAIL>;
-    static bool attr_set = false;   // per instantiation
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_full),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_ragged),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return hip_status(e);
-        attr_set = true;
-    }
-    if (grid <= 0) return SDROP_OK;
-    if constexpr (OP != DX) {
-        if (!ragged && persistent_ok) {
-            // persistent form: three operand stages plus 4 KiB of output staging per computing wavefront
-            constexpr int P_LDS = 3 * (TM + TN) * TK * 2 + WM * WN * 4096;
-            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TAIL>;
-            static int pers_ok = -1;    // per instantiation: does the device grant that much LDS?
-            if (pers_ok < 0) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_pers),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
-                pers_ok = (e == hipSuccess);
-                if (!pers_ok) (void)hipGetLastError();
-            }
-#ifdef SDROP_GEMM_TIMING
-            const bool pers_off = getenv("SDROP_NO_PERSIST") != nullptr;
-#else
-            const bool pers_off = false;
-#endif
-            if (pers_ok && !pers_off) {
-                GemmParams Q = P;
-                Q.total_tiles = grid;
-                const int ncu = cu_count();
-                hipLaunchKernelGGL(k_pers, dim3(grid < ncu ? grid : ncu), dim3(WM * WN * 128), P_LDS, stream, Q);
-                return hip_status(hipGetLastError());
-            }
-        }
-    }
-    if (ragged) hipLaunchKernelGGL(k_ragged, dim3(grid), dim3(WMR * WNR * 64), LDS_BYTES, stream, P);
-    else hipLaunchKernelGGL(k_full, dim3(grid), dim3(WM * WN * 64 * (SPEC ? 2 : 1)), LDS_BYTES, stream, P);
-    return hip_status(hipGetLastError());
-}
-
-// Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
-template <class T, class OutT, int TN, bool TAIL>
-int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
-
-template <class T, class OutT, int TN>
-int launch_dx_persistent(const GemmParams &P, hipStream_t stream)
-{
-    if (has_tail(P)) return launch_dx_persistent_t<T, OutT, TN, true>(P, stream);
-    return launch_dx_persistent_t<T, OutT, TN, false>(P, stream);
-}
-
-template <class T, class OutT, int TN, bool TAIL>
-int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
-{
-    constexpr int P_LDS = 3 * (128 + TN) * TK * 2 + 4 * 4096;
-    auto k = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2, TAIL>;
-    static int ok = -1;     // per instantiation: does the device grant that much LDS?
-    if (ok < 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
-        ok = (e == hipSuccess);
-        if (!ok) (void)hipGetLastError();
-    }
-#ifdef SDROP_GEMM_TIMING
-    if (getenv("SDROP_NO_PERSIST")) return -1;
-#endif
-    if (!ok) return -1;
-    const int64_t positions = (int64_t)P.MB * P.KB;
-    const int ncu = cu_count();
-    hipLaunchKernelGGL(k, dim3((unsigned)(positions < ncu ? positions : ncu)), dim3(512), P_LDS, stream, P);
-    return hip_status(hipGetLastError());
-}
-
+// ---- launch heuristics and knobs (shared with the typed translation units through gemm_host.h) ----
 // out[e] = scale * sum_c part[c][e], rounded once (the second pass of a split DW)
 template <class OutT>
 __global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, OutT *out_base, int64_t n, int splits, float scale,
@@ -255,7 +141,6 @@ int g_dx_persistent_groups_per_cu = 8;
 // dropped) 215 against 190; 9.6 (65536 x 4096 x 1024, 0.7 dropped) 235 against 270; 22 (the same,
 // 0.3 dropped) 410 against 417.
 int g_dx_tile_width = 0;    // 0: chosen per call; 128 or 256: forced (benchmarks and tests)
-struct DxPlan { int TN; bool persistent; };
 DxPlan dx_plan(const GemmParams &P)
 {
     const double kept = (1.0 - P.p) * (double)P.MB * (double)P.KB;
@@ -277,47 +162,7 @@ DxPlan dx_plan(const GemmParams &P)
 // dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on (see dispatch_tile)
 bool dw64_persistent(const GemmParams &P) { return (1.0 - P.p) * P.MB / P.splits * (P.BM / 64) >= 16.0; }
 
-// Tile shapes: the tile edge that lies along the mask must equal the mask's block
-// (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
-// 256/BK kept blocks of one block row into a 256-wide tile.
-template <int OP, class T, class OutT>
-int dispatch_tile(GemmParams &P, hipStream_t stream)
-{
-    if constexpr (OP == FWD) {
-        P.n_tiles = (int)((P.N + 255) / 256);
-        const int grid = P.MB * P.n_tiles;
-        const bool ragged = P.N % 256 != 0;
-        if (P.BM == 128) return launch<FWD, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
-        return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
-    } else if constexpr (OP == DW) {
-        P.n_tiles = (int)((P.N + 255) / 256);
-        const int grid = P.KB * P.n_tiles * P.splits;
-        const bool ragged = P.N % 256 != 0;
-        if (P.BK == 128) return launch<DW, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
-        // 64-row tiles: the persistent kernel runs one workgroup per CU, whose epilogue nothing
-        // overlaps; with short kept lists (a few slices per tile) three co-resident workgroups of the
-        // per-tile kernel do better (8192 x 1024 x 1024, 64 x 64 blocks, half kept, 16 parts:
-        // 26.5 against 29.5 us; 16384 x 3072 x 768, a tenth dropped, 4 parts: 121 against 101 us)
-        return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream, dw64_persistent(P));
-    } else {
-        const DxPlan plan = dx_plan(P);
-        const int TNsel = plan.TN, G_ = TNsel / P.BK;
-        P.n_tiles = (P.KB + G_ - 1) / G_;
-        // one kept block per tile: a workgroup per block position, rounded up to whole sets of 8 XCDs
-        const int grid = G_ == 1 ? (P.MB * P.KB + 7) / 8 * 8 : P.MB * P.n_tiles;
-        const bool ragged = P.N % TK != 0;
-        if (plan.persistent) {
-            const int rc = TNsel == 256 ? launch_dx_persistent<T, OutT, 256>(P, stream) : launch_dx_persistent<T, OutT, 128>(P, stream);
-            if (rc != -1) return rc;      // -1: the device does not grant the LDS; use the per-tile kernels
-        }
-        if (TNsel == 256) {
-            if (P.BM == 128) return launch<DX, T, OutT, 128, 256, 2, 2>(P, grid, ragged, stream);
-            return launch<DX, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
-        }
-        if (P.BM == 128) return launch<DX, T, OutT, 128, 128, 2, 2>(P, grid, ragged, stream);
-        return launch<DX, T, OutT, 64, 128, 1, 4>(P, grid, ragged, stream);
-    }
-}
+namespace {
 
 // 32-bit tile numbers must do (no operand that fits the device's memory comes near this)
 bool tile_count_ok(int64_t N, const sdrop_mask_layout_t &L)
@@ -423,101 +268,18 @@ int run(const void *a, const void *b, const void *mask, void *out,
             P.C = static_cast<char *>(ws);
             P.ldc = N * 4;            // the planes of partial sums are contiguous fp32
             P.scale = 1.0f;
-            const int rc1 = (dtype == SDROP_F16) ? dispatch_tile<OP, F16, float>(P, st) : dispatch_tile<OP, BF16, float>(P, st);
+            const int rc1 = (dtype == SDROP_F16) ? dispatch_typed<F16>(OP, true, P, st) : dispatch_typed<BF16>(OP, true, P, st);
             if (rc1 != SDROP_OK) return rc1;
             return launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out, P);
         }
     }
-    if (dtype == SDROP_F16) {
-        if (out_dtype == SDROP_F32) return dispatch_tile<OP, F16, float>(P, st);
-        return dispatch_tile<OP, F16, _Float16>(P, st);
-    }
-    if (out_dtype == SDROP_F32) return dispatch_tile<OP, BF16, float>(P, st);
-    return dispatch_tile<OP, BF16, __bf16>(P, st);
+    const bool o32 = out_dtype == SDROP_F32;
+    return dtype == SDROP_F16 ? dispatch_typed<F16>(OP, o32, P, st) : dispatch_typed<BF16>(OP, o32, P, st);
 }
 
 // both gradients in one launch where bwd_fused_kernel or bwd_fused_tile_kernel applies (128 x 128
 // blocks, N a multiple of 256); anything else is the two calls in turn
 int g_bwd_fused = 1;
-
-template <class T, class OutDX, class OutDW, int TN_DX>
-int launch_bwd_fused(const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
-{
-    constexpr int LDS_DX = 3 * (128 + TN_DX) * TK * 2 + 4 * 4096, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
-    constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
-    auto k = bwd_fused_kernel<T, OutDX, OutDW, TN_DX>;
-    static int ok = -1;     // per instantiation: does the device grant that much LDS?
-    if (ok < 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
-        ok = (e == hipSuccess);
-        if (!ok) (void)hipGetLastError();
-    }
-    if (!ok) return -1;
-    const int ncu = cu_count();
-    const int64_t positions = (int64_t)Pdx.MB * Pdx.KB;
-    const int g_dx = (int)(positions < ncu ? positions : ncu);
-    const int g_dw = Pdw.total_tiles < ncu ? Pdw.total_tiles : ncu;
-    hipLaunchKernelGGL(k, dim3((unsigned)(g_dx + g_dw)), dim3(512), P_LDS, stream, Pdx, Pdw, g_dx);
-    return hip_status(hipGetLastError());
-}
-
-template <class T, class OutDX, class OutDW>
-int launch_bwd_fused_tile(const GemmParams &Pdx, const GemmParams &Pdw, int n_dx, hipStream_t stream)
-{
-    constexpr int LDS_DX = 3 * (128 + 256) * TK * 2, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
-    constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
-    auto k = bwd_fused_tile_kernel<T, OutDX, OutDW>;
-    static int ok = -1;     // per instantiation: does the device grant that much LDS?
-    if (ok < 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
-        ok = (e == hipSuccess);
-        if (!ok) (void)hipGetLastError();
-    }
-    if (!ok) return -1;
-    const int ncu = cu_count();
-    const int g_dw = Pdw.total_tiles < ncu ? Pdw.total_tiles : ncu;
-    hipLaunchKernelGGL(k, dim3((unsigned)(n_dx + g_dw)), dim3(512), P_LDS, stream, Pdx, Pdw, n_dx);
-    return hip_status(hipGetLastError());
-}
-
-template <class T, class OutDX, class OutDW>
-int launch_bwd_fused_tn(int TN, const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
-{
-    if (TN == 256) return launch_bwd_fused<T, OutDX, OutDW, 256>(Pdx, Pdw, stream);
-    return launch_bwd_fused<T, OutDX, OutDW, 128>(Pdx, Pdw, stream);
-}
-
-template <class T, class OutDX, class OutDW, int TN_DX>
-int launch_bwd_fused_tile64(const GemmParams &Pdx, const GemmParams &Pdw, int n_dx, int n_dw, hipStream_t stream)
-{
-    constexpr int P_LDS = stages_for(64, 256) * (64 + 256) * TK * 2;      // the larger of the two bodies' needs
-    static_assert(stages_for(64, TN_DX) * (64 + TN_DX) * TK * 2 <= P_LDS, "dX's stages must fit");
-    auto k = bwd_fused_tile64_kernel<T, OutDX, OutDW, TN_DX>;
-    static int ok = -1;
-    if (ok < 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
-        ok = (e == hipSuccess);
-        if (!ok) (void)hipGetLastError();
-    }
-    if (!ok) return -1;
-    hipLaunchKernelGGL(k, dim3((unsigned)(n_dx + n_dw)), dim3(256), P_LDS, stream, Pdx, Pdw, n_dx);
-    return hip_status(hipGetLastError());
-}
-
-// calls f(operand tag, dX's output type, dW's output type) for the call's types; a split dW writes fp32 planes
-template <class F>
-int with_bwd_types(int dtype, int out_dtype, bool split, F &&f)
-{
-    const bool o32 = out_dtype == SDROP_F32;
-    if (dtype == SDROP_F16) {
-        if (o32) return f(F16{}, float{}, float{});
-        if (split) return f(F16{}, _Float16{}, float{});
-        return f(F16{}, _Float16{}, _Float16{});
-    }
-    if (o32) return f(BF16{}, float{}, float{});
-    if (split) return f(BF16{}, __bf16{}, float{});
-    return f(BF16{}, __bf16{}, __bf16{});
-}
 
 int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void *dx, void *dw,
             int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
@@ -542,12 +304,12 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
     //   persistent dX + persistent dW                      128 x 128 blocks, dX on its persistent kernel
     //   dX a workgroup per tile of two blocks + persistent dW   128 x 128 blocks otherwise
     //   both a workgroup per tile                          64 x 64 blocks, dW with short kept lists
-    enum { kNone, kPersistent, kTile128, kTile64 } form = kNone;
+    int form = kBwdNone;
     if (g_bwd_fused && N % 256 == 0) {
-        if (BM == 128 && BK == 128) form = plan.persistent ? kPersistent : (plan.TN == 256 ? kTile128 : kNone);
-        else if (BM == 64 && BK == 64 && !dw64_persistent(Pdw)) form = kTile64;
+        if (BM == 128 && BK == 128) form = plan.persistent ? kBwdPersistent : (plan.TN == 256 ? kBwdTile128 : kBwdNone);
+        else if (BM == 64 && BK == 64 && !dw64_persistent(Pdw)) form = kBwdTile64;
     }
-    if (form != kNone) {
+    if (form != kBwdNone) {
         const int G_ = plan.TN / BK;
         Pdx.n_tiles = (Pdx.KB + G_ - 1) / G_;
         const int n_dx = Pdx.MB * Pdx.n_tiles;           // the per-tile launch's grid: (group of the row, block row)
@@ -556,15 +318,9 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
         const float scale = Pdw.scale;
         const bool split = Pdw.splits > 1;
         if (split) { Pdw.C = static_cast<char *>(ws); Pdw.ldc = N * 4; Pdw.scale = 1.0f; }
-        const int rf = with_bwd_types(dtype, out_dtype, split, [&](auto t, auto odx, auto odw) -> int {
-            using T = decltype(t);
-            using ODX = decltype(odx);
-            using ODW = decltype(odw);
-            if (form == kPersistent) return launch_bwd_fused_tn<T, ODX, ODW>(plan.TN, Pdx, Pdw, st);
-            if (form == kTile128) return launch_bwd_fused_tile<T, ODX, ODW>(Pdx, Pdw, n_dx, st);
-            if (plan.TN == 256) return launch_bwd_fused_tile64<T, ODX, ODW, 256>(Pdx, Pdw, n_dx, Pdw.total_tiles, st);
-            return launch_bwd_fused_tile64<T, ODX, ODW, 128>(Pdx, Pdw, n_dx, Pdw.total_tiles, st);
-        });
+        const bool o32 = out_dtype == SDROP_F32;
+        const int rf = dtype == SDROP_F16 ? bwd_fused_typed<F16>(form, plan.TN, o32, split, Pdx, Pdw, n_dx, st)
+                                          : bwd_fused_typed<BF16>(form, plan.TN, o32, split, Pdx, Pdw, n_dx, st);
         if (rf != -1) {     // -1: the device does not grant the LDS; fall through to the two calls
             if (rf != SDROP_OK || !split) return rf;
             return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, N, Pdw);
@@ -601,6 +357,15 @@ int check_gemm_args(const void *a, const void *b, const void *mask, void *out,
 }  // namespace sdrop
 
 #ifdef SDROP_GEMM_TIMING
+// Timing builds are a single translation unit (the time stamps live in one device array): compile this
+// file alone with -DSDROP_GEMM_TIMING and leave the typed files out.
+#include "gemm_launch.h"
+namespace sdrop {
+template int dispatch_typed<F16>(int, bool, GemmParams &, hipStream_t);
+template int dispatch_typed<BF16>(int, bool, GemmParams &, hipStream_t);
+template int bwd_fused_typed<F16>(int, int, bool, bool, const GemmParams &, const GemmParams &, int, hipStream_t);
+template int bwd_fused_typed<BF16>(int, int, bool, bool, const GemmParams &, const GemmParams &, int, hipStream_t);
+}  // namespace sdrop
 extern "C" int sdrop_debug_ticks(long long *host, int n)
 {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(sdrop::g_ticks), sizeof(long long) * n);
