@@ -114,6 +114,14 @@ def bwd_dw_scaled(X, dY, keep, BM, BK, p, scale_one=False):
     return scale_of(p, scale_one) * (Xm.T @ np.asarray(dY, dtype=np.float64))
 
 
+def bias_grad(dZ, keep, BM, BK):
+    """db0 of the block: column sums of dZ over the kept blocks, db0[k] = sum_r (dZ . m)[r, k]
+    (b0 enters Z = H W0^T + b0 once per row, and only the kept blocks of Z reach the output)."""
+    m = expand(keep, BM, BK)
+    # dropped blocks of dZ may hold anything: excluded, not multiplied by 0
+    return np.where(m > 0.0, np.asarray(dZ, dtype=np.float64), 0.0).sum(axis=0)
+
+
 def producer(H, W0, b0, keep, BM, BK, kind=ACT_NONE):
     """X = m . act(H W0^T + b0), W0 is [K, N0]."""
     Z = np.asarray(H, dtype=np.float64) @ np.asarray(W0, dtype=np.float64).T
@@ -152,4 +160,4 @@ def block_backward(H, W0, b0, W, keep, BM, BK, p, dY, kind=ACT_RELU):
     X = m * act(Z, kind)
     dX = s * (dY @ W.T) * m
     dZ = dX * act_grad(Z, kind)
-    return {"dH": dZ @ W0, "dW0": dZ.T @ H, "db0": dZ.sum(axis=0), "dW": s * (X.T @ dY), "dZ": dZ, "Z": Z}
+    return {"dH": dZ @ W0, "dW0": dZ.T @ H, "db0": bias_grad(dZ, keep, BM, BK), "dW": s * (X.T @ dY), "dZ": dZ, "Z": Z}

@@ -180,3 +180,34 @@ def test_gelu_backward_pieces_are_the_three_products(kind, mode):
     np.testing.assert_allclose(dZ, g["dZ"], rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(sb.fwd_tail(dZ, W0, keep, BM, BK, p, scale_one=True), g["dH"], rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(sb.bwd_dw_scaled(dZ, H, keep, BM, BK, p, scale_one=True), g["dW0"], rtol=1e-12, atol=1e-12)
+
+
+def test_bias_gradient_counts_kept_rows_and_ignores_dropped_blocks():
+    # dZ = 1 everywhere: column k sums to BM times the number of kept blocks in its block column
+    MB, KB, BM, BK = 5, 3, 4, 2
+    keep = orc.mask(MB, KB, 0.5, 3, 0)
+    assert 0 < keep.sum() < keep.size
+    got = sb.bias_grad(np.ones((MB * BM, KB * BK)), keep, BM, BK)
+    np.testing.assert_array_equal(got, np.repeat(keep.sum(axis=0) * BM, BK))
+    # scalar loops over a random dZ whose dropped blocks hold NaN
+    dZ = _rand((MB * BM, KB * BK), 8)
+    want = np.zeros(KB * BK)
+    for r in range(MB * BM):
+        for k in range(KB * BK):
+            if keep[r // BM, k // BK]:
+                want[k] += dZ[r, k]
+            else:
+                dZ[r, k] = np.nan
+    np.testing.assert_allclose(sb.bias_grad(dZ, keep, BM, BK), want, rtol=1e-13, atol=1e-13)
+
+
+def test_bias_gradient_is_the_blocks_derivative_by_central_differences():
+    H, W0, b0, W, dY, keep, BM, BK, p = _case(seed=21)
+    g = sb.block_backward(H, W0, b0, W, keep, BM, BK, p, dY, sb.ACT_GELU_ERF)
+    np.testing.assert_allclose(g["db0"], sb.bias_grad(g["dZ"], keep, BM, BK), rtol=0, atol=0)
+    eps = 1e-6
+    for k in range(b0.size):
+        e = np.zeros_like(b0); e[k] = eps
+        lp = (sb.block_forward(H, W0, b0 + e, W, keep, BM, BK, p, sb.ACT_GELU_ERF)[1] * dY).sum()
+        lm = (sb.block_forward(H, W0, b0 - e, W, keep, BM, BK, p, sb.ACT_GELU_ERF)[1] * dY).sum()
+        assert abs((lp - lm) / (2 * eps) - g["db0"][k]) <= 1e-6 * max(1.0, abs(g["db0"][k])), k
