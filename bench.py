@@ -214,8 +214,12 @@ def main():
             "dh_fwd_scale1": lambda: sdrop.sdrop_fwd_ex(dz, s0["W"], mask, scale_mode=sdrop.SCALE_ONE, out=dh),
             "dw0_dw_scale1": lambda: sdrop.sdrop_bwd_dw_ex(dz, s0["dY"], mask, scale_mode=sdrop.SCALE_ONE, out=dw0, ws=ws),
         }
+        gemms = list(parts.values())
+        db0 = torch.empty(w.K, dtype=torch.float32, device="cuda")
+        ws_bg = torch.empty(max(sdrop.bias_grad_workspace_bytes(w.M, w.K, w.BM, w.BK), 16), dtype=torch.uint8, device="cuda")
+        parts["db0_bias_grad"] = lambda: sdrop.sdrop_bias_grad(dz, mask, out=db0, ws=ws_bg)
         def whole():
-            for f in parts.values():
+            for f in gemms:
                 f()
         block = {k: round(_t(f), 5) for k, f in parts.items()}
         block["plain_dx"] = round(_t(lambda: sdrop.sdrop_bwd_dx(s0["dY"], s0["W"], mask, out=dz)), 5)

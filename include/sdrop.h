@@ -313,6 +313,28 @@ int sdrop_producer(const void *H, const void *W0, const float *bias, const void 
                    int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
                    int dtype, int out_dtype, void *stream);
 
+/*
+ * Gradient of that layer's bias (the block of Section 4.3's closing remark, as above):
+ *
+ *     db[k] = sum over rows r of (dZ . m')[r, k]
+ *
+ * the column sums of dZ over the kept blocks; dropped blocks of dZ are not read.
+ *
+ *   dZ[M,K]   input of type `dtype` (fp16 / bf16), rows ld_dz elements apart (0 = K; else >= K, a
+ *             multiple of 8)
+ *   mask      the block mask over [M,K], as for the products
+ *   db        device fp32[K], 16-byte aligned; every element is written (0 for a block column with
+ *             no kept block)
+ *   ws, ws_bytes  device workspace of at least sdrop_bias_grad_workspace_bytes(M, K, BM, BK) bytes
+ *             (fp32 rows [parts][K] that a second launch adds in a fixed order: the result does not
+ *             depend on scheduling); a function of the shape and of the device's CU count only
+ * Sums are accumulated in fp32, in the kept list's order.  Errors as for the products; a mask
+ * object built for another problem makes the kernels write nothing.
+ */
+size_t sdrop_bias_grad_workspace_bytes(int64_t M, int64_t K, int BM, int BK);
+int sdrop_bias_grad(const void *dZ, const void *mask, float *db, int64_t M, int64_t K, int BM, int BK,
+                    int dtype, int64_t ld_dz, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,7 +52,7 @@ class _SparseActBlock(torch.autograd.Function):
     backward  dZ  = s (dY W^T) . m' . act'(Z)    eq. (2) with the gate in its tail ([X > 0] for ReLU)
               dW  = s X^T dY                     eq. (3)
               dH  = dZ W0, dW0 = dZ^T H          eq. (1) / eq. (3) at scale 1 on the block-sparse dZ
-              db0 = column sums of dZ            (a torch reduction: no GEMM)
+              db0 = column sums of dZ            sdrop_bias_grad (kept blocks only)
     """
 
     @staticmethod
@@ -86,7 +86,7 @@ class _SparseActBlock(torch.autograd.Function):
         if need_w0:
             dw0 = sdrop.sdrop_bwd_dw_ex(dz, h, m, scale_mode=sdrop.SCALE_ONE)
         if need_b0 and ctx.has_bias:
-            db0 = dz.sum(dim=0, dtype=torch.float32)
+            db0 = sdrop.sdrop_bias_grad(dz, m)
         if need_w:
             dw = sdrop.sdrop_bwd_dw(x, dy, m)
         return dh, dw0, db0, dw, None, None, None, None, None, None

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsdrop.so")
-SOURCES = ["sdrop_mask.hip", "sdrop_gemm.hip", "sdrop_gemm_f16.hip", "sdrop_gemm_bf16.hip"]
+SOURCES = ["sdrop_mask.hip", "sdrop_bias_grad.hip", "sdrop_gemm.hip", "sdrop_gemm_f16.hip", "sdrop_gemm_bf16.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -37,7 +37,7 @@ def _compile(src):
 
 def build(verbose=True):
     """Compiles every HIP source and links libsdrop.so; always rebuilds."""
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.check_call(cmd)

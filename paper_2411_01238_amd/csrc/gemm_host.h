@@ -8,8 +8,6 @@
 
 namespace sdrop {
 
-int cu_count();
-
 // Kernels with the element-wise tail are separate instantiations, so that eq. (1)-(3) proper run
 // exactly the code they would without it.
 inline bool has_tail(const GemmParams &P) { return P.bias != nullptr || P.aux != nullptr || P.act != 0 || P.C2 != nullptr; }

@@ -61,4 +61,7 @@ int hip_status(hipError_t e);
 
 inline bool block_size_ok(int b) { return b == 64 || b == 128; }
 
+// Compute units of the current device (256 when the query fails).
+int cu_count();
+
 }  // namespace sdrop

@@ -24,7 +24,8 @@ MASK_NNZ_OFFSET = 36
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
            "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw",
-           "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer")
+           "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer",
+           "sdrop_bias_grad_workspace_bytes", "sdrop_bias_grad")
 
 SCALE_DROPOUT, SCALE_ONE = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF = 0, 1, 2, 3
@@ -97,6 +98,10 @@ def lib():
         L.sdrop_bwd.restype = ci
         L.sdrop_producer.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, ci, vp]
         L.sdrop_producer.restype = ci
+        L.sdrop_bias_grad_workspace_bytes.argtypes = [i64, i64, ci, ci]
+        L.sdrop_bias_grad_workspace_bytes.restype = sz
+        L.sdrop_bias_grad.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, i64, vp, sz, vp]
+        L.sdrop_bias_grad.restype = ci
         _lib = L
     return _lib
 
@@ -418,3 +423,31 @@ def sdrop_producer(H, W0, bias, mask, act=ACT_NONE, out_dtype=None, out=None, pr
                               int(act), _DTYPES[dtype], _DTYPES[out_dtype], _stream())
     _check(rc, "sdrop_producer")
     return out if preact is None else (out, preact)
+
+
+def bias_grad_workspace_bytes(M, K, BM, BK):
+    return int(lib().sdrop_bias_grad_workspace_bytes(M, K, BM, BK))
+
+
+def sdrop_bias_grad(dZ, mask, out=None, ws=None):
+    """db[k] = sum_r (dZ . m')[r, k], fp32 [K]: the bias gradient of the layer before the dropout
+    (Section 4.3, closing remark); dZ [M, K] fp16 / bf16 with contiguous rows (a leading dimension is allowed)."""
+    M, K = dZ.shape
+    if (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_bias_grad")
+    if dZ.dtype not in (torch.float16, torch.bfloat16):
+        raise SdropError(EDTYPE, "sdrop_bias_grad")
+    if out is None:
+        out = torch.empty(K, dtype=torch.float32, device=dZ.device)
+    elif tuple(out.shape) != (K,) or out.dtype != torch.float32:
+        raise ValueError("out must be fp32 with one value per column")
+    need = bias_grad_workspace_bytes(M, K, mask.BM, mask.BK)
+    if ws is None and need:
+        ws = torch.empty(need, dtype=torch.uint8, device=dZ.device)
+    ptr, ld = _mat(dZ, "dZ")
+    rc = lib().sdrop_bias_grad(ptr, _dev(mask.buf, "mask"), _dev(out, "out"), M, K, mask.BM, mask.BK,
+                               _DTYPES[dZ.dtype], ld,
+                               ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0),
+                               ws.numel() * ws.element_size() if ws is not None else 0, _stream())
+    _check(rc, "sdrop_bias_grad")
+    return out

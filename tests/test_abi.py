@@ -201,3 +201,30 @@ def test_workspace_size_is_a_whole_number_of_fp32_planes():
             assert parts == 0
         assert parts <= max((M // BM) // 4, 1) or parts == 0
     assert L.sdrop_workspace_bytes(sdrop.OP_BWD_DW, 100, 256, 256, 64, 64, sdrop.BF16, sdrop.BF16) == 0   # bad shape
+
+
+def test_bias_gradient_arguments_are_checked_on_the_host():
+    L = sdrop.lib()
+    buf = ctypes.create_string_buffer(1 << 16)   # host memory: never dereferenced by these calls
+    addr = (ctypes.addressof(buf) + 15) // 16 * 16
+    p, null = ctypes.c_void_p(addr), ctypes.c_void_p(0)
+    ok = (p, p, p, 65536, 1024, 128, 128, sdrop.BF16, 0, null, 0, null)
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return L.sdrop_bias_grad(*a)
+    assert call(a0=null) == sdrop.EINVAL and call(a1=null) == sdrop.EINVAL and call(a2=null) == sdrop.EINVAL
+    assert call(a3=65500) == sdrop.ESHAPE and call(a5=32) == sdrop.ESHAPE
+    assert call(a7=sdrop.F32) == sdrop.EDTYPE
+    assert call(a2=ctypes.c_void_p(addr + 4)) == sdrop.EALIGN
+    assert call(a8=1000) == sdrop.ESHAPE and call(a8=1028) == sdrop.ESHAPE     # shorter than a row; not a multiple of 8
+    # 512 block rows, 8 block columns: the lists are cut into parts, whose fp32 rows need a workspace
+    need = L.sdrop_bias_grad_workspace_bytes(65536, 1024, 128, 128)
+    assert need > 0 and need % (1024 * 4) == 0 and need // (1024 * 4) <= 64
+    assert call() == sdrop.EWORKSPACE
+    assert call(a9=ctypes.c_void_p(addr + 4), a10=need) == sdrop.EWORKSPACE
+    # at most one part per block row; none for a bad shape
+    assert L.sdrop_bias_grad_workspace_bytes(128, 1024, 128, 128) == 0
+    assert L.sdrop_bias_grad_workspace_bytes(100, 1024, 128, 128) == 0
