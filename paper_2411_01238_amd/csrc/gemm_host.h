@@ -12,6 +12,27 @@ namespace sdrop {
 // exactly the code they would without it.
 inline bool has_tail(const GemmParams &P) { return P.bias != nullptr || P.aux != nullptr || P.act != 0 || P.C2 != nullptr; }
 
+// The persistent kernels are compiled once per kind of tail: the common ones each have a form that
+// holds that tail's code only (see Compute::store), everything else runs the generic form.
+enum TailMode {
+    kTailNone = 0,        // eq. (1)-(3) proper
+    kTailLight,           // bias and/or ReLU (or neither, with a second output), no gate
+    kTailReluGate,        // ReLU gate, no activation (bias allowed)
+    kTailGeluErf,         // GELU (erf form), no gate
+    kTailGeluErfGate,     // that GELU's derivative as the gate, no activation
+    kTailGeneric          // anything else (the tanh form, an activation together with a gate)
+};
+inline int tail_mode(const GemmParams &P)
+{
+    if (!has_tail(P)) return kTailNone;
+    if (P.aux == nullptr) {
+        if (P.act == SDROP_ACT_NONE || P.act == SDROP_ACT_RELU) return kTailLight;
+        return P.act == SDROP_ACT_GELU_ERF ? kTailGeluErf : kTailGeneric;
+    }
+    if (P.act != SDROP_ACT_NONE) return kTailGeneric;
+    return P.gate_mode == SDROP_GATE_RELU ? kTailReluGate : P.gate_mode == SDROP_GATE_GELU_ERF ? kTailGeluErfGate : kTailGeneric;
+}
+
 // dX: width of the tiles, and whether the persistent kernel computes them (see sdrop_gemm.hip)
 struct DxPlan { int TN; bool persistent; };
 DxPlan dx_plan(const GemmParams &P);

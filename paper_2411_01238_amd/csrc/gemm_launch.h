@@ -11,21 +11,32 @@ namespace {
 // WM x WN: wavefront grid of the kernel without ragged edges; WMR x WNR (4 wavefronts): with.
 
 
-template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
+template <int TMODE, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
 int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok);
 
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
 int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok = true)
 {
     if constexpr (OP != DW) {
-        if (has_tail(P)) return launch_t<true, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
+        switch (tail_mode(P)) {
+        case kTailNone: break;
+#define SDROP_TAIL_CASE(m) case m: return launch_t<m, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok)
+        SDROP_TAIL_CASE(kTailLight);
+        SDROP_TAIL_CASE(kTailReluGate);
+        SDROP_TAIL_CASE(kTailGeluErf);
+        SDROP_TAIL_CASE(kTailGeluErfGate);
+        default: SDROP_TAIL_CASE(kTailGeneric);
+#undef SDROP_TAIL_CASE
+        }
     }
-    return launch_t<false, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
+    return launch_t<kTailNone, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok);
 }
 
-template <bool TAIL, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
+// TMODE picks the persistent kernel's form; the kernels that run one workgroup per tile have one form with a tail.
+template <int TMODE, int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR, int WNR>
 int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok)
 {
+    constexpr bool TAIL = TMODE != kTailNone;
     constexpr int LDS_BYTES = stages_for(TM, TN) * (TM + TN) * TK * 2;
     constexpr bool SPEC = TM >= 128;     // loader wavefronts for the one-workgroup-per-CU tiles
     auto k_full = gemm_kernel<OP, T, OutT, TM, TN, WM, WN, false, SPEC, TAIL>;
@@ -45,7 +56,7 @@ int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, boo
         if (!ragged && persistent_ok) {
             // persistent form: three operand stages plus 4 KiB of output staging per computing wavefront
             constexpr int P_LDS = 3 * (TM + TN) * TK * 2 + WM * WN * 4096;
-            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TAIL>;
+            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TMODE>;
             static int pers_ok = -1;    // per instantiation: does the device grant that much LDS?
             if (pers_ok < 0) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_pers),
@@ -73,17 +84,23 @@ int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, boo
 }
 
 // Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
-template <class T, class OutT, int TN, bool TAIL>
+template <class T, class OutT, int TN, int TAIL>
 int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
 
 template <class T, class OutT, int TN>
 int launch_dx_persistent(const GemmParams &P, hipStream_t stream)
 {
-    if (has_tail(P)) return launch_dx_persistent_t<T, OutT, TN, true>(P, stream);
-    return launch_dx_persistent_t<T, OutT, TN, false>(P, stream);
+    switch (tail_mode(P)) {
+    case kTailNone: return launch_dx_persistent_t<T, OutT, TN, kTailNone>(P, stream);
+    case kTailLight: return launch_dx_persistent_t<T, OutT, TN, kTailLight>(P, stream);
+    case kTailReluGate: return launch_dx_persistent_t<T, OutT, TN, kTailReluGate>(P, stream);
+    case kTailGeluErf: return launch_dx_persistent_t<T, OutT, TN, kTailGeluErf>(P, stream);
+    case kTailGeluErfGate: return launch_dx_persistent_t<T, OutT, TN, kTailGeluErfGate>(P, stream);
+    default: return launch_dx_persistent_t<T, OutT, TN, kTailGeneric>(P, stream);
+    }
 }
 
-template <class T, class OutT, int TN, bool TAIL>
+template <class T, class OutT, int TN, int TAIL>
 int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
 {
     constexpr int P_LDS = 3 * (128 + TN) * TK * 2 + 4 * 4096;

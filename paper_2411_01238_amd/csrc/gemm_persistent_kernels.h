@@ -85,20 +85,20 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
     // piece (mi, nj) of the wavefront's sub-tile, or null if that piece is not to be written.
     // With a tail, dst also reports the global column of the piece's first column.
     //
-    // The tail's operands (bias values, and for 16-bit outputs the gate values, which lie where
-    // the outputs go) are requested by tail_prefetch, called with the same dst before the tile's
-    // last slice: their latency then hides behind that slice's MFMAs instead of adding to the
-    // epilogue, which nothing overlaps.
+    // The tail's operands (bias values, and for 16-bit outputs under a ReLU gate the gate values, which
+    // lie where the outputs go) are requested by tail_prefetch for a range of pieces, ahead of the
+    // store of that range (see finish): one wait for all of them instead of one per piece.
     uint4 gate_r[MI * NJ][4];
     f32x4 bias_r[NJ][NIP * 4];
-    template <class F> __device__ __forceinline__ void tail_prefetch(int64_t ldc, const Tail &tl, F &&dst)
+    template <int MI0 = 0, int MI1 = MI, int NJ0 = 0, int NJ1 = NJ, class F>
+    __device__ __forceinline__ void tail_prefetch(int64_t ldc, const Tail &tl, F &&dst)
     {
         const int lane = threadIdx.x & 63;
         const int whalf = lane >> 5, rrow = lane >> 3, rch = lane & 7;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int mi = MI0; mi < MI1; ++mi)
 #pragma unroll
-            for (int nj = 0; nj < NJ; ++nj) {
+            for (int nj = NJ0; nj < NJ1; ++nj) {
                 int64_t gcol0 = 0;
                 char *const out = dst(mi, nj, gcol0);
                 if (!out) continue;                        // uniform
@@ -116,17 +116,28 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                 }
             }
     }
-    template <bool TAIL, class F> __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
+    // MODE: which tail this instance is compiled for (TailMode; the host picks the kernel by it).  The
+    // generic form carries every activation and every gate's derivative in each of its 16 to 32
+    // unrolled steps, ~200 KB of code of which a tile runs a few KB scattered over all of it: a ReLU
+    // then cost 25 us per 128 x 256 tile, mostly instruction fetch.  The common tails have forms of
+    // their own that hold one mode's code only.
+    template <int MODE, int MI0 = 0, int MI1 = MI, int NJ0 = 0, int NJ1 = NJ, class F>
+    __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
     {
+        constexpr bool TAIL = MODE != kTailNone;
         const int lane = threadIdx.x & 63;
         const int wrow = lane & 31, whalf = lane >> 5;
         const int rrow = lane >> 3, rch = lane & 7;
         // 16-bit outputs under a ReLU gate are gated after rounding, on whole rows; everything else in the accumulator's layout
-        const bool gate_rows = TAIL && ESZ == 2 && tl.aux != nullptr && tl.gate_mode == SDROP_GATE_RELU;
+        const bool gate_rows = MODE == kTailReluGate ? ESZ == 2
+                             : MODE == kTailGeneric ? (ESZ == 2 && tl.aux != nullptr && tl.gate_mode == SDROP_GATE_RELU) : false;
+        const bool gate_acc = MODE == kTailReluGate ? ESZ == 4 : MODE == kTailGeluErfGate ? true
+                            : MODE == kTailGeneric ? (tl.aux != nullptr && !gate_rows) : false;
+        const int gate_mode = MODE == kTailGeneric ? tl.gate_mode : MODE == kTailGeluErfGate ? SDROP_GATE_GELU_ERF : SDROP_GATE_RELU;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int mi = MI0; mi < MI1; ++mi)
 #pragma unroll
-            for (int nj = 0; nj < NJ; ++nj) {
+            for (int nj = NJ0; nj < NJ1; ++nj) {
                 int64_t gcol0 = 0;
                 char *const out = dst(mi, nj, gcol0);
                 if (!out) continue;                        // uniform
@@ -141,8 +152,14 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                                 const f32x4 bv = bias_r[nj][nl * 4 + q];
                                 v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
                             }
-                            act4(tl.act, v);
-                            if (tl.aux && !gate_rows) {
+                            if constexpr (MODE == kTailLight) {
+                                if (tl.act == SDROP_ACT_RELU) act4(SDROP_ACT_RELU, v);       // no activation, or a ReLU
+                            } else if constexpr (MODE == kTailGeluErf) {
+                                act4(SDROP_ACT_GELU_ERF, v);
+                            } else if constexpr (MODE == kTailGeneric) {
+                                act4(tl.act, v);
+                            }
+                            if (gate_acc) {
                                 // the gate matrix has 16-bit elements, read here in the accumulator's layout
                                 using E = typename In<T>::out16;
                                 typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
@@ -150,7 +167,7 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                                 const int64_t elem = (out - tl.c0) / ESZ + wrow * (ldc / ESZ) + c;
                                 const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
                                 const float xf[4] = {static_cast<float>(x[0]), static_cast<float>(x[1]), static_cast<float>(x[2]), static_cast<float>(x[3])};
-                                gate4(tl.gate_mode, v, xf);
+                                gate4(gate_mode, v, xf);
                             }
                         }
                         const float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
@@ -182,6 +199,31 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                 }
             }
     }
+    // The epilogue of one tile.  With a tail, the sub-tile goes out in two halves (of its column groups,
+    // else of its row blocks when it is one group wide and four blocks tall), each half requesting its
+    // own tail operands first: the accumulators and the operands of a whole 64 x 128 or 128 x 64 sub-tile
+    // together do not fit the register file, those of a half do.
+    template <int MODE, class F> __device__ __forceinline__ void finish(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
+    {
+        if constexpr (MODE == kTailNone) {
+            store<kTailNone>(reg, scale, ldc, tl, dst);
+        } else if constexpr (NJ >= 2) {
+            constexpr int H = NJ / 2;
+            tail_prefetch<0, MI, 0, H>(ldc, tl, dst);
+            store<MODE, 0, MI, 0, H>(reg, scale, ldc, tl, dst);
+            tail_prefetch<0, MI, H, NJ>(ldc, tl, dst);
+            store<MODE, 0, MI, H, NJ>(reg, scale, ldc, tl, dst);
+        } else if constexpr (MI >= 4) {
+            constexpr int H = MI / 2;
+            tail_prefetch<0, H, 0, NJ>(ldc, tl, dst);
+            store<MODE, 0, H, 0, NJ>(reg, scale, ldc, tl, dst);
+            tail_prefetch<H, MI, 0, NJ>(ldc, tl, dst);
+            store<MODE, H, MI, 0, NJ>(reg, scale, ldc, tl, dst);
+        } else {
+            tail_prefetch(ldc, tl, dst);
+            store<MODE>(reg, scale, ldc, tl, dst);
+        }
+    }
 };
 
 // s_waitcnt immediate that waits only for vector-memory operations (at most `vm` outstanding).
@@ -206,7 +248,7 @@ constexpr int waitcnt_vm_only(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (
 // the number of slices from the same mask lists, so they execute the same number of barriers.
 // (The body is a device function of the workgroup's index w among G, so that one launch can hold
 // the workgroups of two operations; see bwd_fused_kernel.)
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
 __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const int G, const int w)
 {
     static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
@@ -431,14 +473,13 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
         len0 = uni(c_len(k + 1, cnt1_v));
         ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
-        if constexpr (TAIL) cw.tail_prefetch(ldc, tl, dst);
         GEMM_TICKW(k * 4 + 2);
-        cw.template store<TAIL>(reg, scale, ldc, tl, dst);
+        cw.template finish<TAIL>(reg, scale, ldc, tl, dst);
         GEMM_TICKW(k * 4 + 3);
     }
 }
 
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
 {
     gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
@@ -465,7 +506,7 @@ __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 // Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; its loader
 // wavefronts write them a kilobyte per slice of the stream, beside the direct loads, and finish
 // what is left when the stream has ended.
-template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
 __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, const int G, const int w)
 {
     constexpr int NW = WM * WN;
@@ -723,7 +764,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
 #pragma unroll
             for (int b = 0; b < 4; ++b) { ngr[b] = uni(nxt.r[b]); ngc[b] = uni(nxt.c[b]); }
-            if constexpr (TAIL) {
+            if constexpr (TAIL != kTailNone) {
                 if (P.C2) {
                     // the producing layer's value before the activation, to the second output
                     const Tail tz = make_tail_preact(P);
@@ -732,12 +773,10 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
                         char *const o = dst(mi, nj, gcol0);
                         return o ? o + delta : nullptr;
                     };
-                    cw.tail_prefetch(ldc, tz, dst2);
-                    cw.template store<TAIL>(reg, scale, ldc, tz, dst2);
+                    cw.template finish<kTailLight>(reg, scale, ldc, tz, dst2);     // bias only
                 }
-                cw.tail_prefetch(ldc, tl, dst);
             }
-            cw.template store<TAIL>(reg, scale, ldc, tl, dst);
+            cw.template finish<TAIL>(reg, scale, ldc, tl, dst);
             GEMM_TICKW(tick_no * 4 + 2);
             GEMM_TICKW(tick_no * 4 + 3);
             ++tick_no;
@@ -749,7 +788,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     }
 }
 
-template <class T, class OutT, int TM, int TN, int WM, int WN, bool TAIL>
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
 {
     gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
@@ -765,9 +804,9 @@ template <class T, class OutDX, class OutDW, int TN_DX>
 __global__ __launch_bounds__(512) void bwd_fused_kernel(GemmParams Pdx, GemmParams Pdw, int g_dx)
 {
     if ((int)blockIdx.x < g_dx)
-        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, false>(Pdx, g_dx, (int)blockIdx.x);
+        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, kTailNone>(Pdx, g_dx, (int)blockIdx.x);
     else
-        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
+        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, kTailNone>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
 }
 
 // The same where dX runs one workgroup per tile (tiles of two kept blocks that are too few per CU
@@ -779,7 +818,7 @@ __global__ __launch_bounds__(512) void bwd_fused_tile_kernel(GemmParams Pdx, Gem
     if ((int)blockIdx.x < n_dx)
         gemm_tile_body<DX, T, OutDX, 128, 256, 2, 2, false, true, false>(Pdx, (int)blockIdx.x);
     else
-        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, false>(Pdw, (int)gridDim.x - n_dx, (int)blockIdx.x - n_dx);
+        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, kTailNone>(Pdw, (int)gridDim.x - n_dx, (int)blockIdx.x - n_dx);
 }
 
 // Both gradients in one launch for 64 x 64 blocks with short kept lists, where dX and dW both run one

@@ -66,8 +66,17 @@ __global__ __launch_bounds__(256) void colsum_reduce_kernel(const float *part, f
     if (!header_matches(H, M, K, BM, BK)) return;
     const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k >= K) return;
-    float t = part[k];
-    for (int c = 1; c < parts; ++c) t += part[(int64_t)c * K + k];
+    // eight loads in flight, added in order
+    float t = 0.f;
+    int c = 0;
+    for (; c + 8 <= parts; c += 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = part[(int64_t)(c + i) * K + k];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t += v[i];
+    }
+    for (; c < parts; ++c) t += part[(int64_t)c * K + k];
     db[k] = t;
 }
 
