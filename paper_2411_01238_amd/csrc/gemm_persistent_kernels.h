@@ -85,16 +85,16 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
     // piece (mi, nj) of the wavefront's sub-tile, or null if that piece is not to be written.
     // With a tail, dst also reports the global column of the piece's first column.
     //
-    // The tail's operands (bias values, and for 16-bit outputs under a ReLU gate the gate values, which
-    // lie where the outputs go) are requested by tail_prefetch for a range of pieces, ahead of the
-    // store of that range (see finish): one wait for all of them instead of one per piece.
-    uint4 gate_r[MI * NJ][4];
+    // The bias values of a range of pieces are requested by tail_prefetch ahead of the store of that
+    // range (see finish): one wait for all of them instead of one per piece.  For 16-bit outputs under
+    // a ReLU gate the gate values lie where the outputs go; store requests them a piece ahead.
+    uint4 gate_q[MI * NJ][4];
     f32x4 bias_r[NJ][NIP * 4];
     template <int MI0 = 0, int MI1 = MI, int NJ0 = 0, int NJ1 = NJ, class F>
     __device__ __forceinline__ void tail_prefetch(int64_t ldc, const Tail &tl, F &&dst)
     {
         const int lane = threadIdx.x & 63;
-        const int whalf = lane >> 5, rrow = lane >> 3, rch = lane & 7;
+        const int whalf = lane >> 5;
 #pragma unroll
         for (int mi = MI0; mi < MI1; ++mi)
 #pragma unroll
@@ -107,14 +107,19 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                     for (int i = 0; i < NIP * 4; ++i)
                         bias_r[nj][i] = *(const_f4)(uintptr_t)(tl.bias + gcol0 + (i >> 2) * 32 + 8 * (i & 3) + 4 * whalf);
                 }
-                if constexpr (ESZ == 2) {
-                    if (tl.aux && tl.gate_mode == SDROP_GATE_RELU) {
-#pragma unroll
-                        for (int it = 0; it < 4; ++it)
-                            gate_r[mi * NJ + nj][it] = *reinterpret_cast<const uint4 *>(tl.aux + (out - tl.c0) + (int64_t)(it * 8 + rrow) * ldc + rch * 16);
-                    }
-                }
             }
+    }
+    // The gate values of one 32 x 128-byte piece, in the layout its rows are written in.
+    template <class F> __device__ __forceinline__ void gate_load(int mi, int nj, uint4 (&g)[4], int64_t ldc, const Tail &tl, F &&dst)
+    {
+        const int lane = threadIdx.x & 63;
+        const int rrow = lane >> 3, rch = lane & 7;
+        int64_t gcol0 = 0;
+        char *const out = dst(mi, nj, gcol0);
+        if (!out) return;                                  // uniform
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            g[it] = *reinterpret_cast<const uint4 *>(tl.aux + (out - tl.c0) + (int64_t)(it * 8 + rrow) * ldc + rch * 16);
     }
     // MODE: which tail this instance is compiled for (TailMode; the host picks the kernel by it).  The
     // generic form carries every activation and every gate's derivative in each of its 16 to 32
@@ -134,10 +139,27 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
         const bool gate_acc = MODE == kTailReluGate ? ESZ == 4 : MODE == kTailGeluErfGate ? true
                             : MODE == kTailGeneric ? (tl.aux != nullptr && !gate_rows) : false;
         const int gate_mode = MODE == kTailGeneric ? tl.gate_mode : MODE == kTailGeluErfGate ? SDROP_GATE_GELU_ERF : SDROP_GATE_RELU;
+        // The gate values of a piece are requested AHEAD pieces before it is written.  With 128
+        // accumulator registers (a 64 x 128 sub-tile) that is one piece: the values of a whole
+        // sub-tile next to its accumulators do not fit the register file (measured on tiles with a
+        // 1024-long reduction: 672 -> 619 us).  Smaller sub-tiles request all of them up front
+        // (one piece ahead measured 73 -> 79 us at 4096^3).
+        constexpr int NJW = NJ1 - NJ0, NP = (MI1 - MI0) * NJW;
+        constexpr int AHEAD = MI * NI * 16 >= 128 ? 1 : NP;
+        if constexpr (TAIL && ESZ == 2) {
+            if (gate_rows) {
 #pragma unroll
-        for (int mi = MI0; mi < MI1; ++mi)
+                for (int q = 0; q < AHEAD && q < NP; ++q) gate_load(MI0 + q / NJW, NJ0 + q % NJW, gate_q[q], ldc, tl, dst);
+            }
+        }
 #pragma unroll
-            for (int nj = NJ0; nj < NJ1; ++nj) {
+        for (int pc = 0; pc < NP; ++pc) {
+            {
+                const int mi = MI0 + pc / NJW, nj = NJ0 + pc % NJW;
+                if constexpr (TAIL && ESZ == 2) {
+                    if (gate_rows && pc + AHEAD < NP)
+                        gate_load(MI0 + (pc + AHEAD) / NJW, NJ0 + (pc + AHEAD) % NJW, gate_q[pc + AHEAD], ldc, tl, dst);
+                }
                 int64_t gcol0 = 0;
                 char *const out = dst(mi, nj, gcol0);
                 if (!out) continue;                        // uniform
@@ -192,12 +214,13 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                         const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
                         v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
                         if constexpr (TAIL) {
-                            if (gate_rows) v = gate16<T>(v, gate_r[mi * NJ + nj][it]);
+                            if (gate_rows) v = gate16<T>(v, gate_q[pc][it]);
                         }
                     }
                     store_out(out + (int64_t)row * ldc + rch * 16, v);
                 }
             }
+        }
     }
     // The epilogue of one tile.  With a tail, the sub-tile goes out in two halves (of its column groups,
     // else of its row blocks when it is one group wide and four blocks tall), each half requesting its
