@@ -127,6 +127,27 @@ int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
 template <int OP, class T, class OutT>
 int dispatch_tile(GemmParams &P, hipStream_t stream)
 {
+    if constexpr (OP != DX) {
+        // N is not a multiple of the 256-wide tile: only the last tile column is ragged, but a launch is
+        // one kernel, and the kernel with bounds checks is the slow one (4096^3 with N = 4104: fwd 158 us
+        // against 66 us at N = 4096).  With at least a chip's worth of whole tiles the output columns are
+        // cut in two, [0, N - N % 256) for the fast kernels and the rest for the checked one, which the
+        // leading dimensions make a matter of pointers: operands and outputs keep their strides.
+        const int64_t n_full = P.N / 256 * 256;
+        if (P.N % 256 != 0 && n_full > 0 && (int64_t)(OP == FWD ? P.MB : P.KB * P.splits) * (n_full / 256) >= cu_count()) {
+            GemmParams Q = P;
+            Q.N = n_full;
+            const int rc = dispatch_tile<OP, T, OutT>(Q, stream);
+            if (rc != SDROP_OK) return rc;
+            Q = P;
+            Q.N = P.N - n_full;
+            Q.B += n_full * 2;
+            Q.C += n_full * (int64_t)sizeof(OutT);
+            if (Q.bias) Q.bias += n_full;
+            if (Q.aux) Q.aux += n_full * 2;
+            return dispatch_tile<OP, T, OutT>(Q, stream);
+        }
+    }
     if constexpr (OP == FWD) {
         P.n_tiles = (int)((P.N + 255) / 256);
         const int grid = P.MB * P.n_tiles;
