@@ -139,9 +139,8 @@ __device__ __forceinline__ Tail make_tail_preact(const GemmParams &P)
     t.bias = P.bias; t.aux = nullptr; t.c0 = P.C2; t.act = SDROP_ACT_NONE; t.gate_mode = SDROP_GATE_RELU;
     return t;
 }
-// v: four consecutive columns of one output row, starting at global column `col`; `elem` is the
-// index of v[0] in the output matrix (row * columns + col).  col is a multiple of 4.  The gate is
-// applied here only with AUX; the persistent kernels gate their 16-bit outputs after rounding
+// act4 / gate4 work on four consecutive columns of one output row (a register quad of the
+// accumulator).  The persistent kernels gate their 16-bit outputs under a ReLU gate after rounding
 // instead, 16 bytes at a time (gate16), which selects the same values.
 // The bias does not change while the kernel runs: read through the constant address space, its
 // loads may be moved and merged across the output stores.
@@ -202,24 +201,6 @@ __device__ __forceinline__ void gate4(int gate_mode, float (&v)[4], const float 
             float gauss;                                   // exp(-z^2 / 2), shared by both terms
             const float cdf = 0.5f * (1.f + erf_rsqrt2(z, gauss));
             v[e] *= cdf + z * 0.3989422804014327f * gauss;
-        }
-    }
-}
-template <class T, bool AUX>
-__device__ __forceinline__ void tail4(const Tail &tl, float (&v)[4], int64_t col, int64_t elem)
-{
-    if (tl.bias) {
-        const f32x4 b = *(const_f4)(uintptr_t)(tl.bias + col);
-        v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
-    }
-    act4(tl.act, v);
-    if constexpr (AUX) {
-        if (tl.aux) {
-            using E = typename In<T>::out16;
-            typedef __attribute__((__vector_size__(4 * sizeof(E)))) E e4;
-            const e4 x = *reinterpret_cast<const e4 *>(tl.aux + elem * (int64_t)sizeof(E));
-            const float xf[4] = {static_cast<float>(x[0]), static_cast<float>(x[1]), static_cast<float>(x[2]), static_cast<float>(x[3])};
-            gate4(tl.gate_mode, v, xf);
         }
     }
 }

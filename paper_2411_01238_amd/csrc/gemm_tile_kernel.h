@@ -450,33 +450,88 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
         if (loader) return;
         char *reg = smem + wave * REGION;
         const float scale = P.scale;
-        // parks the sub-tile in LDS with tail tl applied and writes it out `delta` bytes from its place in C
-        auto emit = [&](const Tail &tl, int64_t delta) __attribute__((always_inline)) {
+        // Parks the sub-tile in LDS with tail tl applied and writes it out `delta` bytes from its place in C.
+        // mode_c (a TailMode constant) says which tail this copy of the code is for: a copy holds one
+        // activation's or one gate's arithmetic only, and the tail's operands are requested in batches
+        // ahead of their arithmetic instead of one load, one wait per register quad.
+        auto emit_mode = [&](auto mode_c, const Tail &tl, int64_t delta) __attribute__((always_inline)) {
+            constexpr int MODE = decltype(mode_c)::value;
+            constexpr bool TL = TAIL && OP != DW && MODE != kTailNone;
+            // global column of register quad (ni, q) of this lane; false if it lies outside the output
+            auto quad_col = [&](int ni, int q, int64_t &gcol) __attribute__((always_inline)) -> bool {
+                const int cl = wn * WTN + ni * 32 + q * 8 + (lane >> 5) * 4;          // column within the tile
+                if constexpr (OP == DX) {
+                    const int g = cl >> 6;
+                    int c0 = out_col0[0];
+#pragma unroll
+                    for (int gg = 1; gg < DXG; ++gg) c0 = (g == gg) ? out_col0[gg] : c0;
+                    gcol = c0 + (cl & 63);
+                    return g < chunks_valid;
+                } else {
+                    gcol = out_col0[0] + cl;
+                    return cl < c_lim;                      // c_lim is a multiple of 8
+                }
+            };
+            using E16 = typename In<T>::out16;
+            typedef __attribute__((__vector_size__(4 * sizeof(E16)))) E16 e16x4;
+            // Batch of the tail's operand requests: the register quads of NB 32-column blocks of one
+            // 32-row block.  A wavefront with 128 accumulator registers takes one block at a time
+            // (all four at once measured 182 -> 204 us on its ragged dX kernel), smaller ones all.
+            constexpr int NB = MI * NI * 16 >= 128 ? 1 : NI;
+            const bool has_bias = TL && tl.bias != nullptr;
+            const bool gated = MODE == kTailReluGate || MODE == kTailGeluErfGate || (MODE == kTailGeneric && tl.aux != nullptr);
+            const int gate_mode = MODE == kTailGeneric ? tl.gate_mode : MODE == kTailGeluErfGate ? SDROP_GATE_GELU_ERF : SDROP_GATE_RELU;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
+            for (int nb = 0; nb < NI; nb += NB) {
+                const int row = mi * 32 + (lane & 31);
+                f32x4 bias_v[NB * 4];
+                e16x4 gate_v[NB * 4];
+                if constexpr (TL) {
+                    if (has_bias) {
+#pragma unroll
+                        for (int i = 0; i < NB * 4; ++i) {
+                            int64_t gcol;
+                            const bool ok = quad_col(nb + (i >> 2), i & 3, gcol);
+                            bias_v[i] = ok ? *(const_f4)(uintptr_t)(tl.bias + gcol) : f32x4{0.f, 0.f, 0.f, 0.f};
+                        }
+                    }
+                    if (gated) {
+#pragma unroll
+                        for (int i = 0; i < NB * 4; ++i) {
+                            int64_t gcol;
+                            const bool ok = quad_col(nb + (i >> 2), i & 3, gcol);
+                            const int64_t elem = (out_row0 + wm * WTM + row) * (ldc / ESZ) + gcol;
+                            gate_v[i] = ok ? *reinterpret_cast<const e16x4 *>(tl.aux + elem * (int64_t)sizeof(E16)) : e16x4{};
+                        }
+                    }
+                }
+#pragma unroll
+                for (int ni = nb; ni < nb + NB; ++ni)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const int row = mi * 32 + (lane & 31), col = ni * 32 + q * 8 + (lane >> 5) * 4;
+                        const int col = ni * 32 + q * 8 + (lane >> 5) * 4;
                         float v[4] = {acc[mi][ni][4 * q] * scale, acc[mi][ni][4 * q + 1] * scale,
                                       acc[mi][ni][4 * q + 2] * scale, acc[mi][ni][4 * q + 3] * scale};
-                        if constexpr (TAIL && OP != DW) {
-                            const int cl = wn * WTN + col;          // column within the tile
-                            bool ok;
-                            int64_t gcol;
-                            if constexpr (OP == DX) {
-                                const int g = cl >> 6;
-                                ok = g < chunks_valid;
-                                int c0 = out_col0[0];
-#pragma unroll
-                                for (int gg = 1; gg < DXG; ++gg) c0 = (g == gg) ? out_col0[gg] : c0;
-                                gcol = c0 + (cl & 63);
-                            } else {
-                                ok = cl < c_lim;                    // c_lim is a multiple of 8
-                                gcol = out_col0[0] + cl;
+                        if constexpr (TL) {
+                            // (lanes outside the output compute on zeros; their values are not stored)
+                            if (has_bias) {
+                                const f32x4 b = bias_v[(ni - nb) * 4 + q];
+                                v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
                             }
-                            if (ok) tail4<T, true>(tl, v, gcol, (out_row0 + wm * WTM + row) * (ldc / ESZ) + gcol);
+                            if constexpr (MODE == kTailLight) {
+                                if (tl.act == SDROP_ACT_RELU) act4(SDROP_ACT_RELU, v);
+                            } else if constexpr (MODE == kTailGeluErf) {
+                                act4(SDROP_ACT_GELU_ERF, v);
+                            } else if constexpr (MODE == kTailGeneric) {
+                                act4(tl.act, v);
+                            }
+                            if (gated) {
+                                const e16x4 x = gate_v[(ni - nb) * 4 + q];
+                                const float xf[4] = {static_cast<float>(x[0]), static_cast<float>(x[1]), static_cast<float>(x[2]), static_cast<float>(x[3])};
+                                gate4(gate_mode, v, xf);
+                            }
                         }
                         char *dst = reg + row * RS + col * ESZ;
                         if constexpr (ESZ == 4) {
@@ -487,6 +542,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
                             *reinterpret_cast<out4 *>(dst) = o;
                         }
                     }
+            }
         constexpr int CH = ROWB / 16, RPI = 64 / CH;         // 16-byte pieces per row; rows per store instruction
         static_assert(CH <= 64 && 64 % CH == 0 && WTM % RPI == 0, "sub-tile rows must tile a wavefront");
 #pragma unroll
@@ -507,9 +563,25 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
             if (ok) store_out(cbase + delta + (int64_t)(wm * WTM + row) * ldc + col * ESZ, v);
         }
         };
+        // the tail's kind is branched on once (uniform), here at the end of the kernel
+        auto emit = [&](const Tail &tl, int64_t delta) __attribute__((always_inline)) {
+            if constexpr (!(TAIL && OP != DW)) {
+                emit_mode(std::integral_constant<int, kTailNone>{}, tl, delta);
+            } else if (tl.aux == nullptr) {
+                if (tl.act == SDROP_ACT_NONE || tl.act == SDROP_ACT_RELU) emit_mode(std::integral_constant<int, kTailLight>{}, tl, delta);
+                else if (tl.act == SDROP_ACT_GELU_ERF) emit_mode(std::integral_constant<int, kTailGeluErf>{}, tl, delta);
+                else emit_mode(std::integral_constant<int, kTailGeneric>{}, tl, delta);
+            } else if (tl.act == SDROP_ACT_NONE && tl.gate_mode == SDROP_GATE_RELU) {
+                emit_mode(std::integral_constant<int, kTailReluGate>{}, tl, delta);
+            } else if (tl.act == SDROP_ACT_NONE && tl.gate_mode == SDROP_GATE_GELU_ERF) {
+                emit_mode(std::integral_constant<int, kTailGeluErfGate>{}, tl, delta);
+            } else {
+                emit_mode(std::integral_constant<int, kTailGeneric>{}, tl, delta);
+            }
+        };
         if constexpr (TAIL && OP == DX) {
             // the producing layer's value before the activation, to the second output
-            if (P.C2) emit(make_tail_preact(P), P.C2 - P.C);
+            if (P.C2) emit_mode(std::integral_constant<int, kTailLight>{}, make_tail_preact(P), P.C2 - P.C);
         }
         emit(make_tail(P), 0);
         GEMM_TICK(4);
