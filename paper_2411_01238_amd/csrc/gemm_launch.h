@@ -17,7 +17,12 @@ int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, boo
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int WMR = WM, int WNR = WN>
 int launch(const GemmParams &P, int grid, bool ragged, hipStream_t stream, bool persistent_ok = true)
 {
-    if constexpr (OP != DW) {
+    // dW takes no tail, and dX with a tail runs on 128-wide tiles only (dx_plan)
+    constexpr bool kHasTailForms = OP == FWD || (OP == DX && TN == 128);
+    if constexpr (!kHasTailForms) {
+        if (has_tail(P)) return SDROP_EINVAL;
+    }
+    if constexpr (kHasTailForms) {
         switch (tail_mode(P)) {
         case kTailNone: break;
 #define SDROP_TAIL_CASE(m) case m: return launch_t<m, OP, T, OutT, TM, TN, WM, WN, WMR, WNR>(P, grid, ragged, stream, persistent_ok)
@@ -90,14 +95,19 @@ int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
 template <class T, class OutT, int TN>
 int launch_dx_persistent(const GemmParams &P, hipStream_t stream)
 {
-    switch (tail_mode(P)) {
-    case kTailNone: return launch_dx_persistent_t<T, OutT, TN, kTailNone>(P, stream);
-    case kTailLight: return launch_dx_persistent_t<T, OutT, TN, kTailLight>(P, stream);
-    case kTailReluGate: return launch_dx_persistent_t<T, OutT, TN, kTailReluGate>(P, stream);
-    case kTailGeluErf: return launch_dx_persistent_t<T, OutT, TN, kTailGeluErf>(P, stream);
-    case kTailGeluErfGate: return launch_dx_persistent_t<T, OutT, TN, kTailGeluErfGate>(P, stream);
-    default: return launch_dx_persistent_t<T, OutT, TN, kTailGeneric>(P, stream);
+    if constexpr (TN == 128) {
+        switch (tail_mode(P)) {
+        case kTailNone: break;
+        case kTailLight: return launch_dx_persistent_t<T, OutT, TN, kTailLight>(P, stream);
+        case kTailReluGate: return launch_dx_persistent_t<T, OutT, TN, kTailReluGate>(P, stream);
+        case kTailGeluErf: return launch_dx_persistent_t<T, OutT, TN, kTailGeluErf>(P, stream);
+        case kTailGeluErfGate: return launch_dx_persistent_t<T, OutT, TN, kTailGeluErfGate>(P, stream);
+        default: return launch_dx_persistent_t<T, OutT, TN, kTailGeneric>(P, stream);
+        }
+    } else {
+        if (has_tail(P)) return SDROP_EINVAL;       // dX with a tail runs on 128-wide tiles only (dx_plan)
     }
+    return launch_dx_persistent_t<T, OutT, TN, kTailNone>(P, stream);
 }
 
 template <class T, class OutT, int TN, int TAIL>

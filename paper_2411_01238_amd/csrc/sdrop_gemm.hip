@@ -153,13 +153,14 @@ DxPlan dx_plan(const GemmParams &P)
     };
     DxPlan plan;
     plan.TN = (rounds(128) * 0.6 < rounds(256)) ? 128 : 256;
+    if (g_dx_tile_width == 128 || g_dx_tile_width == 256) plan.TN = g_dx_tile_width;
     // With a tail the epilogue is the longer the wider the tile, nothing overlaps it, and a 64 x 128
     // sub-tile's accumulators leave the tail's operands no registers: 128-wide tiles (65536 x 4096 x
     // 1024, 128-wide blocks, half dropped: producer with bias and ReLU 528 against 377 us, ReLU-gated dX
     // 615 against 439, GELU forms 735 against 460-490; 32768 x 4096 x 512, 64-wide blocks: 213 against
     // 142, 227 against 163, 300-310 against 190-200; no difference where the per-tile kernels run).
+    // (Whatever the knob says: the 256-wide kernels are not compiled with a tail.)
     if (has_tail(P)) plan.TN = 128;
-    if (g_dx_tile_width == 128 || g_dx_tile_width == 256) plan.TN = g_dx_tile_width;
     const int G_ = plan.TN / P.BK;
     plan.persistent = P.BM == 128 && P.N % TK == 0 && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu);
     return plan;
