@@ -222,6 +222,8 @@ def main(argv=None):
     ap.add_argument("--model", default="all", choices=tuple(MODELS) + ("all",))
     ap.add_argument("--p", type=float, nargs="+", default=[0.0, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7])
     ap.add_argument("--dtype", default="bf16", choices=("bf16", "f16"))
+    ap.add_argument("--batch-scale", type=int, default=1,
+                    help="multiply the paper's batch sizes (1024 / 64 / 32) by this: larger batches are bound by the GPU, not the host")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     a = ap.parse_args(argv)
@@ -229,11 +231,11 @@ def main(argv=None):
         raise SystemExit("model_step needs a GPU: the substituted layers run in libsdrop's kernels only")
     dtype = torch.bfloat16 if a.dtype == "bf16" else torch.float16
     for name in (tuple(MODELS) if a.model == "all" else (a.model,)):
-        batch = synthetic_batch(name, dtype=dtype)
+        batch = synthetic_batch(name, dtype=dtype, batch={"mlp": 1024, "vit": 64, "gpt": 32}[name] * a.batch_scale)
         ms = time_step(MODELS[name]("dense", 0.0, dtype=dtype), batch, a.steps, a.warmup)
-        print(json.dumps({"model": name, "layer": "dense", "p": None, "ms_fwd_bwd": round(ms, 4)}), flush=True)
+        print(json.dumps({"model": name, "batch": batch[0].shape[0], "layer": "dense", "p": None, "ms_fwd_bwd": round(ms, 4)}), flush=True)
         for p in a.p:
-            row = {"model": name, "p": p}
+            row = {"model": name, "batch": batch[0].shape[0], "p": p}
             for kind in ("dropout_dense", "sparsedrop"):
                 row[kind + "_ms_fwd_bwd"] = round(time_step(MODELS[name](kind, p, dtype=dtype), batch, a.steps, a.warmup), 4)
             row["speedup"] = round(row["dropout_dense_ms_fwd_bwd"] / row["sparsedrop_ms_fwd_bwd"], 3)
