@@ -242,6 +242,9 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  *   act         SDROP_ACT_NONE, SDROP_ACT_RELU (max(v,0)), SDROP_ACT_GELU_TANH
  *               (0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))), the "tanh" form of GELU),
  *               SDROP_ACT_GELU_ERF (0.5 v (1 + erf(v / sqrt 2)), the exact form)
+ *               (erf is evaluated in fp32 by a rational approximation whose absolute error is
+ *               below 1e-6, exp and tanh by the hardware's fast forms: far inside the rounding of
+ *               a 16-bit output)
  *   bias        device, fp32[number of output columns], 16-byte aligned, or NULL
  *   relu_mask   device, a matrix of type `dtype` with the output's shape (and the output's
  *               leading dimension), 16-byte aligned, or NULL: where it is not > 0 the output is
