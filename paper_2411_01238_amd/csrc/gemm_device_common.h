@@ -253,23 +253,34 @@ template <int ROWS, int NGRP, int NW> struct DmaK {
     static constexpr int PER_WAVE = ROWS / PASS_ROWS, GROUP_ROWS = ROWS / NGRP;
     static_assert(GROUP_ROWS % PASS_ROWS == 0 && ROWS % PASS_ROWS == 0, "row groups must cover whole passes");
     uint32_t voff_even, voff_odd;
-    int wave;
+    int wave, chunk_even;                                 // chunk_even: the 16-byte chunk this lane fetches in even passes
     __device__ __forceinline__ void init(int64_t ld_bytes, int w)
     {
         const int lane = threadIdx.x & 63;
         wave = w;
         const int r0 = 8 * wave + (lane >> 3);
         const uint32_t row_off = (uint32_t)r0 * (uint32_t)ld_bytes;
-        voff_even = row_off + (((lane & 7) ^ swz(r0)) << 4);
-        voff_odd = row_off + (((lane & 7) ^ swz(r0) ^ 4) << 4);
+        chunk_even = (lane & 7) ^ swz(r0);
+        voff_even = row_off + (chunk_even << 4);
+        voff_odd = row_off + ((chunk_even ^ 4) << 4);
     }
-    // pass i of this wavefront
-    __device__ __forceinline__ void issue(const char *const (&base)[NGRP], int64_t ld_bytes, char *lds, int i) const
+    // pass i of this wavefront.  nch < 8: the slice is the ragged last one of the reduction and holds
+    // only nch valid 16-byte chunks per row; lanes whose chunk lies beyond fetch nothing and clear
+    // their 16 bytes of LDS instead (the caller waits for those LDS writes before it publishes the slice).
+    __device__ __forceinline__ void issue(const char *const (&base)[NGRP], int64_t ld_bytes, char *lds, int i, int nch = 8) const
     {
         const int g = (PASS_ROWS * i) / GROUP_ROWS;       // uniform: pass i covers rows PASS_ROWS*i ..
         const char *sbase = base[g] + (int64_t)(PASS_ROWS * i - g * GROUP_ROWS) * ld_bytes;
         // bit 5 of the row (the only bit of a pass offset that swz() sees) picks the lane offset
-        dma16(sbase, ((PASS_ROWS * i) & 32) ? voff_odd : voff_even, lds + (wave + NW * i) * 1024);
+        const bool odd = ((PASS_ROWS * i) & 32) != 0;
+        char *const dst = lds + (wave + NW * i) * 1024;
+        if (nch == 8) {
+            dma16(sbase, odd ? voff_odd : voff_even, dst);
+        } else {
+            const int lane = threadIdx.x & 63;
+            if ((odd ? chunk_even ^ 4 : chunk_even) < nch) dma16(sbase, odd ? voff_odd : voff_even, dst);
+            else *reinterpret_cast<uint4 *>(dst + lane * 16) = make_uint4(0, 0, 0, 0);
+        }
     }
 };
 

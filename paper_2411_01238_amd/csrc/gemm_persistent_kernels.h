@@ -251,6 +251,8 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
 
 // s_waitcnt immediate that waits only for vector-memory operations (at most `vm` outstanding).
 constexpr int waitcnt_vm_only(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (15 << 8); }
+// s_waitcnt immediate that waits only for LDS / scalar-memory operations (lgkmcnt = 0).
+constexpr int waitcnt_lgkm0_only() { return 15 | (3 << 14) | (7 << 4) | (0 << 8); }
 
 // FWD and DW for 128-row tiles without ragged edges, as a persistent kernel: one workgroup per
 // CU walks a fixed sequence of tiles, and the slices of consecutive tiles form ONE stream
@@ -559,7 +561,10 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     const int cshift = (P.BK == 128), cmask = (1 << cshift) - 1;   // 64-column chunks per block
     const int nnz = H->nnz;
     const int ngroups = (nnz + GB - 1) / GB;
-    const int nsteps = (int)(P.N / TK);
+    // slices of the reduction; when N is not a multiple of the slice the last one is ragged: the loaders
+    // clear what lies beyond N in LDS (see DmaK::issue), the computing wavefronts see a full slice
+    const int nsteps = (int)((P.N + TK - 1) / TK);
+    const int last_chunks = (int)(P.N % TK) / 8;       // valid 16-byte chunks of a ragged last slice, 0 if none
     const int64_t lda = P.lda, ldb = P.ldb, ldc = P.ldc;
     const int32_t *const rows = GB == 1 ? P.mv.loc_row : P.mv.blk_row;
     const int32_t *const cols = GB == 1 ? P.mv.loc_col : P.mv.col_idx;
@@ -640,10 +645,20 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
 #pragma unroll
             for (int g = 0; g < DXG; ++g) sb[g] = bgrp[g] + off;
             char *stp = stage_ptr(st);
+            if (last_chunks != 0 && s == nsteps - 1) {
 #pragma unroll
-            for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+                for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j, last_chunks);
 #pragma unroll
-            for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+                for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j, last_chunks);
+                // the cleared chunks are ordinary LDS writes: done before this wavefront goes on to
+                // the barrier that publishes the slice (which waits for the direct loads only)
+                __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0_only());
+            } else {
+#pragma unroll
+                for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+#pragma unroll
+                for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+            }
             ++s;
             return true;
         };

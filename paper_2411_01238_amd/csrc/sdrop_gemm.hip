@@ -162,7 +162,7 @@ DxPlan dx_plan(const GemmParams &P)
     // (Whatever the knob says: the 256-wide kernels are not compiled with a tail.)
     if (has_tail(P)) plan.TN = 128;
     const int G_ = plan.TN / P.BK;
-    plan.persistent = P.BM == 128 && P.N % TK == 0 && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu);
+    plan.persistent = P.BM == 128 && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu);
     return plan;
 }
 

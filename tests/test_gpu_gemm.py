@@ -133,6 +133,9 @@ def test_dx_persistent_kernel_with_several_blocks_per_tile(M, K, N, BM, BK, dtyp
     (1024, 1024, 256, 128, 128, "bf16", 0.4, 41),   # width 256: two kept blocks per tile; width 128: one
     (512, 1024, 192, 128, 64, "f16", 0.6, 42),      # width 256: four 64-column blocks per tile; width 128: two
     (384, 512, 136, 64, 64, "bf16", 0.3, 43),       # 64-row blocks, ragged reduction: per-tile kernels only
+    (1024, 1024, 264, 128, 128, "bf16", 0.4, 44),   # ragged reduction (one valid 16-byte chunk in the last slice): the
+                                                    # persistent kernel's loaders clear the rest of that slice in LDS
+    (512, 1024, 184, 128, 64, "f16", 0.5, 45),      # the same with seven valid chunks and 64-column blocks
 ])
 def test_dx_every_tile_width_and_kernel_form(M, K, N, BM, BK, dtype, p, seed):
     # the host normally picks the width of dX's tiles and the kernel form from the expected number of
