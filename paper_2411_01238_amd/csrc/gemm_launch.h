@@ -114,13 +114,18 @@ template <class T, class OutT, int TN, int TAIL>
 int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
 {
     constexpr int P_LDS = 3 * (128 + TN) * TK * 2 + 4 * 4096;
-    auto k = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2, TAIL>;
+    // two forms: N a multiple of the 64-wide slice, or with a ragged last slice
+    auto k_whole = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2, TAIL, false>;
+    auto k_ragged = gemm_persistent_dx_kernel<T, OutT, 128, TN, 2, 2, TAIL, true>;
     static int ok = -1;     // per instantiation: does the device grant that much LDS?
     if (ok < 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_whole), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_ragged), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
         ok = (e == hipSuccess);
         if (!ok) (void)hipGetLastError();
     }
+    auto k = P.N % TK == 0 ? k_whole : k_ragged;
 #ifdef SDROP_GEMM_TIMING
     if (getenv("SDROP_NO_PERSIST")) return -1;
 #endif

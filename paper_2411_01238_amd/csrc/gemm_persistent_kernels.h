@@ -531,7 +531,7 @@ __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 // Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; its loader
 // wavefronts write them a kilobyte per slice of the stream, beside the direct loads, and finish
 // what is left when the stream has ended.
-template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false>
 __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, const int G, const int w)
 {
     constexpr int NW = WM * WN;
@@ -563,8 +563,9 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     const int ngroups = (nnz + GB - 1) / GB;
     // slices of the reduction; when N is not a multiple of the slice the last one is ragged: the loaders
     // clear what lies beyond N in LDS (see DmaK::issue), the computing wavefronts see a full slice
-    const int nsteps = (int)((P.N + TK - 1) / TK);
-    const int last_chunks = (int)(P.N % TK) / 8;       // valid 16-byte chunks of a ragged last slice, 0 if none
+    // (RAGN: a form of its own, because the extra case in the loaders cost the whole-slice form 5 %)
+    const int nsteps = RAGN ? (int)((P.N + TK - 1) / TK) : (int)(P.N / TK);
+    const int last_chunks = RAGN ? (int)(P.N % TK) / 8 : 0;       // valid 16-byte chunks of a ragged last slice, 0 if none
     const int64_t lda = P.lda, ldb = P.ldb, ldc = P.ldc;
     const int32_t *const rows = GB == 1 ? P.mv.loc_row : P.mv.blk_row;
     const int32_t *const cols = GB == 1 ? P.mv.loc_col : P.mv.col_idx;
@@ -645,15 +646,20 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
 #pragma unroll
             for (int g = 0; g < DXG; ++g) sb[g] = bgrp[g] + off;
             char *stp = stage_ptr(st);
-            if (last_chunks != 0 && s == nsteps - 1) {
+            bool whole = true;
+            if constexpr (RAGN) {
+                if (last_chunks != 0 && s == nsteps - 1) {
+                    whole = false;
 #pragma unroll
-                for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j, last_chunks);
+                    for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j, last_chunks);
 #pragma unroll
-                for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j, last_chunks);
-                // the cleared chunks are ordinary LDS writes: done before this wavefront goes on to
-                // the barrier that publishes the slice (which waits for the direct loads only)
-                __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0_only());
-            } else {
+                    for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j, last_chunks);
+                    // the cleared chunks are ordinary LDS writes: done before this wavefront goes on to
+                    // the barrier that publishes the slice (which waits for the direct loads only)
+                    __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0_only());
+                }
+            }
+            if (whole) {
 #pragma unroll
                 for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
 #pragma unroll
@@ -826,10 +832,10 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     }
 }
 
-template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
 {
-    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
+    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL, RAGN>(P, gridDim.x, blockIdx.x);
 }
 
 // Both gradients of the layer in one launch (eq. 2 and eq. 3 share dY and the mask and do not
