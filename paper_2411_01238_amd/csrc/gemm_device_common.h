@@ -303,7 +303,7 @@ template <int ROWS, int NW> struct DmaT {
     static_assert(ROWS % (8 * NW) == 0, "every wavefront issues whole instructions");
     static_assert(ROWS == 64 || ROWS == 128 || ROWS == 256, "unsupported tile edge");
     uint32_t voff;
-    int wave;
+    int wave, chunk;                                         // chunk: the 16-byte chunk of the row this lane fetches
     __device__ __forceinline__ void init(int64_t ld_bytes, int w)
     {
         const int lane = threadIdx.x & 63;
@@ -311,12 +311,17 @@ template <int ROWS, int NW> struct DmaT {
         const int kl = (lane * 16) / ROW_BYTES;              // row within the instruction
         const int cpos = ((lane * 16) % ROW_BYTES) >> 4;     // 16-byte slot within the row
         const int k0 = RPI * wave + kl;
-        voff = (uint32_t)kl * (uint32_t)ld_bytes + ((cpos ^ swz_t<ROWS>(k0)) << 4);
+        chunk = cpos ^ swz_t<ROWS>(k0);
+        voff = (uint32_t)kl * (uint32_t)ld_bytes + (chunk << 4);
     }
-    __device__ __forceinline__ void issue(const char *const (&base)[1], int64_t ld_bytes, char *lds, int i) const
+    // nch < ROWS / 8: the tile hangs over the end of the rows (the last tile column of a ragged N)
+    // and only its first nch >= 1 chunks per row exist: the other lanes fetch nothing, and their
+    // LDS columns keep whatever they held (columns beyond N, which no one stores).
+    __device__ __forceinline__ void issue(const char *const (&base)[1], int64_t ld_bytes, char *lds, int i, int nch = ROWS / 8) const
     {
         const int I = wave + NW * i;
-        dma16(base[0] + (int64_t)(RPI * I) * ld_bytes, voff, lds + I * 1024);
+        if (nch == ROWS / 8) dma16(base[0] + (int64_t)(RPI * I) * ld_bytes, voff, lds + I * 1024);
+        else if (chunk < nch) dma16(base[0] + (int64_t)(RPI * I) * ld_bytes, voff, lds + I * 1024);
     }
 };
 

@@ -58,17 +58,23 @@ int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, boo
     }
     if (grid <= 0) return SDROP_OK;
     if constexpr (OP != DX) {
-        if (!ragged && persistent_ok) {
+        // the persistent form also has a variant for a ragged last tile column, without a tail
+        if ((!ragged || !TAIL) && persistent_ok) {
             // persistent form: three operand stages plus 4 KiB of output staging per computing wavefront
             constexpr int P_LDS = 3 * (TM + TN) * TK * 2 + WM * WN * 4096;
-            auto k_pers = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TMODE>;
+            auto k_whole = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TMODE, false>;
+            auto k_edge = gemm_persistent_kernel<OP, T, OutT, TM, TN, WM, WN, TMODE, !TAIL>;    // (the same kernel when there is a tail)
             static int pers_ok = -1;    // per instantiation: does the device grant that much LDS?
             if (pers_ok < 0) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_pers),
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_whole),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+                if (e == hipSuccess)
+                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_edge),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
                 pers_ok = (e == hipSuccess);
                 if (!pers_ok) (void)hipGetLastError();
             }
+            auto k_pers = ragged ? k_edge : k_whole;
 #ifdef SDROP_GEMM_TIMING
             const bool pers_off = getenv("SDROP_NO_PERSIST") != nullptr;
 #else
@@ -149,7 +155,9 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         // cut in two, [0, N - N % 256) for the fast kernels and the rest for the checked one, which the
         // leading dimensions make a matter of pointers: operands and outputs keep their strides.
         const int64_t n_full = P.N / 256 * 256;
-        if (P.N % 256 != 0 && n_full > 0 && (int64_t)(OP == FWD ? P.MB : P.KB * P.splits) * (n_full / 256) >= cu_count()) {
+        // (Without a tail the persistent kernels take the ragged column themselves, where they apply.)
+        const bool one_launch = !has_tail(P) && (OP == FWD || P.BK == 128 || dw64_persistent(P));
+        if (!one_launch && P.N % 256 != 0 && n_full > 0 && (int64_t)(OP == FWD ? P.MB : P.KB * P.splits) * (n_full / 256) >= cu_count()) {
             GemmParams Q = P;
             Q.N = n_full;
             const int rc = dispatch_tile<OP, T, OutT>(Q, stream);

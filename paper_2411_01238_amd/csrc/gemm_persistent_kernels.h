@@ -126,7 +126,11 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
     // unrolled steps, ~200 KB of code of which a tile runs a few KB scattered over all of it: a ReLU
     // then cost 25 us per 128 x 256 tile, mostly instruction fetch.  The common tails have forms of
     // their own that hold one mode's code only.
-    template <int MODE, int MI0 = 0, int MI1 = MI, int NJ0 = 0, int NJ1 = NJ, class F>
+    // RAGN: the tile may hang over the last column of the output (N not a multiple of the tile);
+    // pieces that lie beyond column `ncols` are skipped and the piece that straddles it is written
+    // only up to it (N is a multiple of 8, so whole 16-byte chunks).
+    int64_t ncols;
+    template <int MODE, int MI0 = 0, int MI1 = MI, int NJ0 = 0, int NJ1 = NJ, bool RAGN = false, class F>
     __device__ __forceinline__ void store(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
     {
         constexpr bool TAIL = MODE != kTailNone;
@@ -163,6 +167,8 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                 int64_t gcol0 = 0;
                 char *const out = dst(mi, nj, gcol0);
                 if (!out) continue;                        // uniform
+                const int vch = RAGN ? (int)((ncols - gcol0) * ESZ / 16) : 8;      // valid 16-byte chunks of the piece's rows
+                if (RAGN && vch <= 0) continue;            // uniform
 #pragma unroll
                 for (int nl = 0; nl < NIP; ++nl)
 #pragma unroll
@@ -217,7 +223,7 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                             if (gate_rows) v = gate16<T>(v, gate_q[pc][it]);
                         }
                     }
-                    store_out(out + (int64_t)row * ldc + rch * 16, v);
+                    if (!RAGN || rch < vch) store_out(out + (int64_t)row * ldc + rch * 16, v);
                 }
             }
         }
@@ -226,10 +232,11 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
     // else of its row blocks when it is one group wide and four blocks tall), each half requesting its
     // own tail operands first: the accumulators and the operands of a whole 64 x 128 or 128 x 64 sub-tile
     // together do not fit the register file, those of a half do.
-    template <int MODE, class F> __device__ __forceinline__ void finish(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
+    template <int MODE, bool RAGN = false, class F> __device__ __forceinline__ void finish(char *reg, float scale, int64_t ldc, const Tail &tl, F &&dst)
     {
+        static_assert(!RAGN || MODE == kTailNone, "tiles that hang over the output's edge have no tail forms");
         if constexpr (MODE == kTailNone) {
-            store<kTailNone>(reg, scale, ldc, tl, dst);
+            store<kTailNone, 0, MI, 0, NJ, RAGN>(reg, scale, ldc, tl, dst);
         } else if constexpr (NJ >= 2) {
             constexpr int H = NJ / 2;
             tail_prefetch<0, MI, 0, H>(ldc, tl, dst);
@@ -273,7 +280,7 @@ constexpr int waitcnt_lgkm0_only() { return 15 | (3 << 14) | (7 << 4) | (0 << 8)
 // the number of slices from the same mask lists, so they execute the same number of barriers.
 // (The body is a device function of the workgroup's index w among G, so that one launch can hold
 // the workgroups of two operations; see bwd_fused_kernel.)
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false>
 __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const int G, const int w)
 {
     static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
@@ -374,6 +381,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         int s = 0, nsteps = 0;           // next slice of that tile; its number of slices
         int e_cur = 0, e_nxt = 0;        // list entries of slice s and of the block after it
         const char *a_tile = nullptr, *b_tile = nullptr;
+        int b_chunks = TN / 8;           // RAGN: 16-byte chunks of B's rows that exist in this tile column
         bool ended = false;
 
         // issues the next slice of the stream into stage `st`; false when the stream has ended
@@ -394,6 +402,10 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
                 if constexpr (OP == FWD) a_tile = P.A + (int64_t)cur.ord * P.BM * lda;
                 else a_tile = P.A + (int64_t)cur.ord * P.BK * 2;
                 b_tile = P.B + (int64_t)nt * TN * 2;
+                if constexpr (RAGN) {
+                    const int64_t left = P.N - (int64_t)nt * TN;
+                    b_chunks = left < TN ? (int)(left / 8) : TN / 8;
+                }
             }
             const int64_t off = (int64_t)e_cur * BLK + (int64_t)(s & sub_mask) * TK;
             const char *const sa[1] = {a_tile + off * (OP == FWD ? 2 : lda)};
@@ -401,8 +413,13 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             char *stp = stage_ptr(st);
 #pragma unroll
             for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+            if constexpr (RAGN) {
 #pragma unroll
-            for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+                for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j, b_chunks);
+            } else {
+#pragma unroll
+                for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+            }
             ++s;
             if ((s & sub_mask) == 0) {
                 e_cur = e_nxt;
@@ -458,6 +475,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
 
     Compute<T, OutT, A_TR, B_TR, TM, TN, WM, WN> cw;
     cw.wm = wm; cw.wn = wn;
+    cw.ncols = P.N;
     int st0 = 0, st1 = 1, st2 = 2;       // stages of the stream's slices g, g+1, g+2
     bool started = false;
     const float scale = P.scale;
@@ -499,15 +517,15 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         len0 = uni(c_len(k + 1, cnt1_v));
         ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
         GEMM_TICKW(k * 4 + 2);
-        cw.template finish<TAIL>(reg, scale, ldc, tl, dst);
+        cw.template finish<TAIL, RAGN>(reg, scale, ldc, tl, dst);
         GEMM_TICKW(k * 4 + 3);
     }
 }
 
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL>
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
 {
-    gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL>(P, gridDim.x, blockIdx.x);
+    gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL, RAGN>(P, gridDim.x, blockIdx.x);
 }
 
 // a[i] for a uniform index i in 0..3, as selects (keeps everything in scalar registers)

@@ -1,7 +1,9 @@
 """eq. (1) and eq. (3) of arxiv 2411.01238 (Section 3.1) when N is not a multiple of the 256-wide
-tile and the problem has at least a chip's worth of whole tiles: the library then issues the whole
-tile columns and the ragged rest as two launches.  Parity against the float64 oracle as for every
-other shape, the tail's operands (bias, gate) included, which move with the columns."""
+tile and the problem has at least a chip's worth of whole tiles.  Without a tail the persistent
+kernels take the ragged tile column themselves (their loaders fetch only the chunks that exist,
+their epilogue stops at N); with a tail the library issues the whole tile columns and the ragged
+rest as two launches.  Parity against the float64 oracle as for every other shape, the tail's
+operands (bias, gate) included, which move with the columns."""
 import numpy as np
 import pytest
 import torch
@@ -29,7 +31,7 @@ def test_products_with_whole_and_ragged_tile_columns(M, K, N, BM, BK, dtype, p, 
     td = torch.float16 if dtype == "f16" else torch.bfloat16
     parts = max(sdrop.workspace_bytes(sdrop.OP_BWD_DW, M, K, N, BM, BK, td, td) // (K * N * 4), 1)
     whole = N // 256
-    # the shape must take the two-launch path for at least one of the two products
+    # large enough for many tiles per workgroup in at least one of the two products
     assert (M // BM) * whole >= CUS or (K // BK) * parts * whole >= CUS
     X, W, dY = make_custom(M, K, N, dtype, seed=seed)
     _full_parity(X, W, dY, BM, BK, p, seed, 0, "ragged-split(%d,%d,%d,%dx%d,%s)" % (M, K, N, BM, BK, dtype))
