@@ -6,6 +6,11 @@ import torch
 # to the largest reference magnitude, for fp32-accumulated results
 REL_FRO = 1e-3
 MAX_ABS = 5e-3
+# regression gate for fp32 outputs of eq. (1)-(3): a length-n fp32 sum of exact 16-bit products, added in
+# groups of 16, errs by about 2^-24 * sqrt(n / 16) of the result (2e-6 for the longest reduction of the
+# workloads, n = 46000; measured 1e-7 to 1e-6).  1e-5 is above all of that and far below what a 16-bit
+# accumulation (1e-3), a lost slice of a reduction or a wrong tile would cost.
+TIGHT = 1e-5
 
 
 def f64(t):
@@ -28,6 +33,14 @@ def assert_close(got, ref, what, rel_fro=REL_FRO, max_abs=MAX_ABS):
     fro, mabs = errors(got, ref)
     assert fro <= rel_fro, "%s: relative Frobenius error %.3e > %.1e" % (what, fro, rel_fro)
     assert mabs <= max_abs, "%s: max-abs error %.3e of max|ref| > %.1e" % (what, mabs, max_abs)
+    return fro, mabs
+
+
+def assert_tight(got, ref, what, tol=TIGHT):
+    """The regression gate for fp32 outputs (see TIGHT): both error measures at most tol."""
+    fro, mabs = errors(got, ref)
+    assert fro <= tol and mabs <= tol, "%s: rel-Frobenius %.3e / max-abs %.3e of max|ref| above the regression gate %.0e" % (
+        what, fro, mabs, tol)
     return fro, mabs
 
 

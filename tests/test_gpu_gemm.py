@@ -15,7 +15,7 @@ import torch
 from oracle import sdrop_oracle as orc
 from paper_2411_01238_amd import sdrop
 from paper_2411_01238_amd.workloads import WORKLOADS, make_inputs, make_custom
-from _util import f64, assert_close, assert_bf16_rounding_of
+from _util import f64, assert_close, assert_bf16_rounding_of, assert_tight
 
 pytestmark = pytest.mark.gpu
 
@@ -56,6 +56,7 @@ def _full_parity(X, W, dY, BM, BK, p, seed, stream, tag, keep=None):
     outs32 = _run_all(X, W, dY, m, torch.float32)
     for name, o, ref in zip(("Y", "dX", "dW"), outs32, refs):
         assert_close(f64(o), ref, "%s %s fp32 out" % (tag, name))
+        assert_tight(f64(o), ref, "%s %s fp32 out" % (tag, name))
     outs16 = _run_all(X, W, dY, m, None)
     _check_16bit_outputs(outs16, outs32, refs, X.dtype, tag)
     # dropped blocks of dX are +0 exactly, in both output types
