@@ -213,6 +213,24 @@ int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * sdrop_bwd_dw for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and
+ * result (bit for bit) as sdrop_bwd_dw, without `ws`: the fp32 planes of a split reduction go to
+ * SDROP_STATIC_SCRATCH_BYTES (128 MiB) of device memory that is part of the library's code object
+ * (one copy per GPU, held from the library's load on that GPU to the end of the process).  The
+ * call allocates and frees nothing.
+ *   - SDROP_EWORKSPACE when sdrop_workspace_bytes(SDROP_OP_BWD_DW, ...) exceeds
+ *     SDROP_STATIC_SCRATCH_BYTES (nothing is enqueued); all five workloads of the benchmark fit.
+ *   - Every call on a GPU uses that GPU's one copy, which keeps the previous call's contents (a
+ *     call overwrites all it reads, nothing needs clearing).  Two calls that overlap in time on
+ *     one GPU (different streams, or threads) race on it: serialise them.
+ */
+#define SDROP_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
+int sdrop_bwd_dw_static(const void *X, const void *dY, const void *mask, void *dW,
+                        int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                        int dtype, int out_dtype, void *stream);
+
+/*
  * eq. (2) and eq. (3) in one call: both gradients of the layer, which share dY and the mask and
  * do not depend on each other.  Results are bit-identical to sdrop_bwd_dx followed by
  * sdrop_bwd_dw with the same arguments.  With 128 x 128 blocks (or 64 x 64 blocks and short

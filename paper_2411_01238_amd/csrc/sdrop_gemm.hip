@@ -54,6 +54,7 @@
 // loop, is ~2.0 GHz with the MFMAs alone, ~1.55 GHz once the operand reads from LDS are added
 // and ~1.4 GHz with the loads as well, at 84 % MFMA duty (1214 clocks per slice against 1024).
 #include "gemm_host.h"
+#include <atomic>
 
 namespace sdrop {
 
@@ -361,6 +362,30 @@ int check_gemm_args(const void *a, const void *b, const void *mask, void *out,
     return SDROP_OK;
 }
 
+// ---- device memory that belongs to the library: the planes of a split dW for sdrop_bwd_dw_static ----
+// One copy per GPU, part of the code object's zero-initialised data, there from the moment the library
+// is loaded on a device until the process ends.  In host code the array's name is only a handle: its
+// device address is asked for once per device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = SDROP_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// The current device's copy of `scratch`, or null with the HIP error recorded.
+void *static_scratch()
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    if (e != hipSuccess) { hip_status(e); return nullptr; }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { hip_status(e != hipSuccess ? e : hipErrorInvalidSymbol); return nullptr; }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);     // every thread that asks gets the same address
+    return p;
+}
+
 }  // namespace sdrop
 
 #ifdef SDROP_GEMM_TIMING
@@ -427,6 +452,23 @@ int sdrop_bwd_dw(const void *X, const void *dY, const void *mask, void *dW,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
 {
     return sdrop::run<sdrop::DW>(X, dY, mask, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
+}
+
+int sdrop_bwd_dw_static(const void *X, const void *dY, const void *mask, void *dW,
+                        int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                        int dtype, int out_dtype, void *stream)
+{
+    // argument errors first, as in sdrop_bwd_dw; then the size against the library's own memory
+    const int rc = sdrop::check_gemm_args(X, dY, mask, dW, M, K, N, BM, BK, p, dtype, out_dtype);
+    if (rc != SDROP_OK) return rc;
+    const size_t need = sdrop_workspace_bytes(SDROP_OP_BWD_DW, M, K, N, BM, BK, dtype, out_dtype);
+    if (need > sdrop::kStaticScratchBytes) return SDROP_EWORKSPACE;
+    void *ws = nullptr;
+    if (need) {
+        ws = sdrop::static_scratch();
+        if (!ws) return SDROP_EHIP;
+    }
+    return sdrop::run<sdrop::DW>(X, dY, mask, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, need, stream);
 }
 
 int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,

@@ -23,7 +23,7 @@ MASK_NNZ_OFFSET = 36
 
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
-           "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw",
+           "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
            "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer",
            "sdrop_bias_grad_workspace_bytes", "sdrop_bias_grad")
 
@@ -90,6 +90,8 @@ def lib():
             f = getattr(L, name)
             f.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
             f.restype = ci
+        L.sdrop_bwd_dw_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp]
+        L.sdrop_bwd_dw_static.restype = ci
         for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex"):
             f = getattr(L, name)
             f.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp, ctypes.POINTER(Epilogue)]
@@ -324,6 +326,28 @@ def sdrop_bwd_dw(X, dY, mask, out_dtype=None, out=None, ws=None):
     if M2 != M or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dw")
     return _gemm("sdrop_bwd_dw", OP_BWD_DW, X, dY, mask, (K, N), M, K, N, out_dtype, out, ws)
+
+
+STATIC_SCRATCH_BYTES = 128 << 20
+
+
+def sdrop_bwd_dw_static(X, dY, mask, out, out_dtype=None):
+    """eq. (3) through the entry point that allocates nothing: the caller passes the output, the planes of a
+    split reduction live in the library's own device memory (at most STATIC_SCRATCH_BYTES)."""
+    M, K = X.shape
+    M2, N = dY.shape
+    if M2 != M or (M, K) != (mask.M, mask.K):
+        raise SdropError(ESHAPE, "sdrop_bwd_dw_static")
+    dtype = X.dtype
+    out_dtype = dtype if out_dtype is None else out_dtype
+    if dY.dtype != dtype or tuple(out.shape) != (K, N) or out.dtype != out_dtype:
+        raise ValueError("operands / output have the wrong shape or dtype")
+    if dtype not in (torch.float16, torch.bfloat16) or out_dtype not in _DTYPES:
+        raise SdropError(EDTYPE, "sdrop_bwd_dw_static")
+    rc = lib().sdrop_bwd_dw_static(_dev(X, "X"), _dev(dY, "dY"), _dev(mask.buf, "mask"), _dev(out, "dW"),
+                                   M, K, N, mask.BM, mask.BK, mask.p, _DTYPES[dtype], _DTYPES[out_dtype], _stream())
+    _check(rc, "sdrop_bwd_dw_static")
+    return out
 
 
 def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None):
