@@ -20,10 +20,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_DENSE_TFLOPS = 2500.0     # MI355X published dense bf16/fp16 MFMA peak
-# Bytes per launch that crossed L2 -> fabric, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a known 1 GiB
-# copy (profiles/bench_square4096_p0.5_hbm_traffic.md), workload square4096 at p = 0.5
-MEASURED_TRAFFIC_BYTES = {"square4096": {"fwd": 235.7e6, "bwd": 555.5e6}}
-HEADLINE_P = 0.5
+# What the matrix cores of this chip were measured to sustain under its power limit (profiles/probe_clock_mfma_lds_loads.md):
+# bf16 MFMAs issued back to back hold 1.56 GHz = 1640 TFLOP/s; with the operand reads from LDS that feed them, 1390
+MFMA_ONLY_CEILING_TFLOPS = 1640.0
+MFMA_WITH_LDS_READS_CEILING_TFLOPS = 1390.0
+# Bytes per launch that crossed L2 -> fabric: rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier run of this
+# benchmark's launches, scaled by a known 1 GiB copy.  Constants from the tracked counter summaries named
+# here, NOT measured by this run (counters need the profiler).
+TRAFFIC_BYTES = {
+    ("square4096", 0.5): {"fwd": 235.7e6, "bwd": 555.5e6, "source": "profiles/bench_square4096_p0.5_hbm_traffic.md"},
+}
+
+
+def headline_p(w):
+    """The dropout rate the headline is quoted at: 0.5 where the workload is run at it, else the workload's own rate."""
+    return 0.5 if 0.5 in w.ps else w.ps[-1]
 
 
 def _sets(w, n_sets, torch):
@@ -69,6 +80,7 @@ def main():
     # three buffer sets (576 MiB at 4096^3) rotate so that a step's operands are not left in
     # the 256 MiB Infinity Cache by the step before; a single-set (warm) figure is given too
     sets = _sets(w, 3, torch)
+    HEADLINE_P = headline_p(w)
     mask = sdrop.Mask(w.M, w.K, w.BM, w.BK, HEADLINE_P)
     td = w.torch_dtype
     ws_need = sdrop.workspace_bytes(sdrop.OP_BWD_DW, w.M, w.K, w.N, w.BM, w.BK, td, td)
@@ -124,7 +136,9 @@ def main():
 
     # ---- headline: p = 0.5, rotating buffer sets ----
     nnz = nnz_of(HEADLINE_P, w.mask_seed)
-    # settle first (untimed, not part of --warmup): the first ~100 steps after start-up run about 10 %
+    # the same measurement straight after start-up, reported beside the headline
+    ms_cold = timed(HEADLINE_P, args.steps, args.warmup, 3)
+    # settle (untimed, not part of --warmup): the first ~100 steps after start-up run about 10 %
     # slower than the steady state (first touches of the buffers, clocks ramping)
     timed(HEADLINE_P, 150, 0, 3)
     ms = timed(HEADLINE_P, args.steps, args.warmup, 3)
@@ -148,19 +162,34 @@ def main():
     kern_sep = separate(args.steps, 3)
 
     # ---- sweep over p (fewer steps each), speed-up against the library's own dense run ----
+    # The points are visited in shuffled order, in several rounds (every round visits every p), and a
+    # point's time is the mean over its rounds: drift of the clocks during the sweep then spreads over all
+    # points instead of reading as scaling.  p = 0 (the library's own dense run) is always a point.
     sweep = {}
     if not args.no_sweep:
-        k_sweep = max(10, args.steps // 2)
-        ms_dense = timed(0.0, k_sweep, 3, 3)
-        for p in w.ps:
+        import random
+        rounds = 3
+        k_sweep = max(4, args.steps // (2 * rounds))
+        points = sorted(set(w.ps) | {0.0})
+        acc = {p: [] for p in points}
+        rnd = random.Random(20241128)
+        for _ in range(rounds):
+            order = points[:]
+            rnd.shuffle(order)
+            for p in order:
+                acc[p].append(timed(p, k_sweep, 3, 3))
+        ms_dense = sum(acc[0.0]) / rounds
+        for p in points:
             n_p = nnz_of(p, w.mask_seed)
-            ms_p = ms if p == HEADLINE_P else (ms_dense if p == 0.0 else timed(p, k_sweep, 3, 3))
+            ms_p = sum(acc[p]) / rounds
             sweep["%.1f" % p] = {
                 "ms_per_step": round(ms_p, 5), "kept_fraction": round(n_p / (w.MB * w.KB), 5),
                 "eff_tflops": round(n_p * flops_per_block / (ms_p * 1e-3) / 1e12, 3),
                 "speedup_vs_own_dense": round(ms_dense / ms_p, 4),
                 "ideal_speedup": round(w.MB * w.KB / max(n_p, 1), 4),
+                "ms_per_round": [round(t, 5) for t in acc[p]],
             }
+        sweep_order = "shuffled, %d rounds of %d steps per point, mean over rounds" % (rounds, k_sweep)
 
     # ---- how linear is t(p) in the kept fraction f?  least squares t = a + b f over the sweep ----
     linearity = None
@@ -234,10 +263,20 @@ def main():
     flops_gemm = 2.0 * nnz * w.BM * w.BK * w.N         # algorithmic flops of one of the three products
     flops_launch = flops_gemm * (2 if dom == "bwd" else 1)     # the backward launch holds eq. (2) and eq. (3)
     achieved = flops_launch / (kern[dom] * 1e-3) / 1e12
+    traffic = TRAFFIC_BYTES.get((w.name, HEADLINE_P), {})
     roofline = {"bound": "mfma", "kernel": {"fwd": "sdrop_fwd", "bwd": "sdrop_bwd (eq. 2 and eq. 3)"}[dom],
                 "achieved": round(achieved, 3), "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_DENSE_TFLOPS, 5),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
+                "traffic": traffic.get(dom),
+                "traffic_source": ("%s (an earlier profiled run of the same launches, not this run)" % traffic["source"]) if traffic else None,
+                "algorithmic_bytes": algorithmic_bytes(w, nnz, dom),
+                "traffic_over_algorithmic": round(traffic[dom] / algorithmic_bytes(w, nnz, dom), 3) if traffic.get(dom) else None,
+                "duration_is": "HIP events on the launch stream around each launch of the timed steps (includes the dispatch "
+                               "latency between dependent launches); profiles/ holds the rocprofv3 kernel trace of the same command",
+                "frac_of_measured_mfma_ceiling": {
+                    "mfma_only_1640_tflops": round(achieved / MFMA_ONLY_CEILING_TFLOPS, 5),
+                    "mfma_with_lds_operand_reads_1390_tflops": round(achieved / MFMA_WITH_LDS_READS_CEILING_TFLOPS, 5),
+                    "source": "profiles/probe_clock_mfma_lds_loads.md"},
                 "avg_launch_ms": {k: round(v, 5) for k, v in kern.items()},
                 "separate_launch_ms": {k: round(v, 5) for k, v in kern_sep.items()}}
 
@@ -246,13 +285,15 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "%s: M=K=N=%d %s, block %dx%d, p=%.1f (mask + fwd + dX + dW per step; dX and dW by one sdrop_bwd call), "
-                               "%s outputs, 3 rotating buffer sets" % (w.name, w.M, w.dtype, w.BM, w.BK, HEADLINE_P, w.dtype),
+        "config": {"workload": "%s: M=%d K=%d N=%d %s, block %dx%d, p=%.1f (mask + fwd + dX + dW per step; dX and dW by one sdrop_bwd call), "
+                               "%s outputs, 3 rotating buffer sets" % (w.name, w.M, w.K, w.N, w.dtype, w.BM, w.BK, HEADLINE_P, w.dtype),
                    "kept_blocks": nnz, "blocks": w.MB * w.KB},
         "frac_of_bf16_peak": round(value / PEAK_BF16_DENSE_TFLOPS, 5),
         "ms_per_step_warm_single_set": round(ms_warm, 5),
         "untimed_settle_steps_before_warmup": 150,
+        "ms_per_step_before_settle": round(ms_cold, 5),
         "sweep": sweep,
+        "sweep_order": sweep_order if sweep else None,
         "linearity": linearity,
         "vendor_dense_gemm_ms_single_set": vendor,
         "sparse_relu_block_ms_single_set": block,
@@ -262,6 +303,16 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, HEADLINE_P)
     print(json.dumps(out))
+
+
+def algorithmic_bytes(w, nnz, launch):
+    """Minimum HBM bytes of a launch: kept blocks of X, all of W, dY and the outputs, each once."""
+    e = 2
+    f = nnz / float(w.MB * w.KB)
+    fwd = f * w.M * w.K * e + w.K * w.N * e + w.M * w.N * e
+    dx = w.M * w.N * e + w.K * w.N * e + w.M * w.K * e
+    dw = f * w.M * w.K * e + w.M * w.N * e + w.K * w.N * e
+    return fwd if launch == "fwd" else dx + dw
 
 
 def cpu_baseline(w, p, rows=None):

@@ -168,6 +168,16 @@ int sdrop_mask_from_bits(void *mask, size_t mask_bytes, int64_t M, int64_t K, in
                          const uint64_t *bits, void *stream);
 
 /*
+ * Reads a mask object back: the packed keep bits of Section 3.4 (uint64[MB][words_per_row], as laid out
+ * above) into HOST memory `bits_host` of `n_words` words, and the number of kept blocks into
+ * `*nnz_host` (either may be NULL, not both).  This is the one entry point that synchronises: it waits
+ * for `stream`, so the object as written by the work enqueued before the call is what is read.
+ * SDROP_EINVAL if the buffer does not hold a mask object (nothing is written to the outputs);
+ * SDROP_EWORKSPACE if n_words is less than MB * words_per_row of the object (nnz is still delivered).
+ */
+int sdrop_mask_bits(const void *mask, uint64_t *bits_host, size_t n_words, int64_t *nnz_host, void *stream);
+
+/*
  * Bytes of device workspace an operation needs for these arguments (may be 0).  Only
  * sdrop_bwd_dw uses one: when K/BK * ceil(N/256) output tiles are too few to fill the chip,
  * the reduction over M is cut into `splits` parts that write fp32 planes [splits][K][N] to
@@ -184,7 +194,10 @@ size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, in
  *
  *   X[M,K], W[K,N]  inputs of type `dtype`;  Y[M,N] output of type `out_dtype`
  *   mask            object written by sdrop_mask / sdrop_mask_from_bits with the same
- *                   (M, K, BM, BK); a kernel that finds a different header writes nothing
+ *                   (M, K, BM, BK), in a buffer of at least sdrop_mask_bytes(M, K, BM, BK) bytes
+ *                   for THIS call's shape (the kernels address the lists by the call's shape before
+ *                   they have compared the header); a kernel that finds a different header writes
+ *                   nothing
  *   p               the dropout probability the scale s is derived from
  *   ws, ws_bytes    device workspace of at least sdrop_workspace_bytes(SDROP_OP_FWD, ...)
  *                   bytes (ws may be NULL when that is 0)

@@ -87,14 +87,6 @@ constexpr int stages_for(int tm, int tn) { return (void)tn, tm <= 64 ? 2 : 3; }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 
-#ifdef SDROP_GEMM_TIMING   // development aid: per-workgroup phase timestamps
-__device__ long long g_ticks[16384 * 16];
-#define GEMM_TICK(n) do { if (threadIdx.x == 0 && blockIdx.x < 16384) { g_ticks[blockIdx.x * 16 + (n)] = wall_clock64(); g_ticks[blockIdx.x * 16 + 8 + (n)] = clock64(); } } while (0)
-#define GEMM_TICKW(n) do { if (threadIdx.x == 0 && blockIdx.x < 16384 && (n) < 16) g_ticks[blockIdx.x * 16 + (n)] = wall_clock64(); } while (0)
-#else
-#define GEMM_TICK(n) do { } while (0)
-#define GEMM_TICKW(n) do { } while (0)
-#endif
 
 
 // 16 bytes of output, as a non-temporal store.  Outputs are written once and not read again by the

@@ -75,12 +75,7 @@ int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, boo
                 if (!pers_ok) (void)hipGetLastError();
             }
             auto k_pers = ragged ? k_edge : k_whole;
-#ifdef SDROP_GEMM_TIMING
-            const bool pers_off = getenv("SDROP_NO_PERSIST") != nullptr;
-#else
-            const bool pers_off = false;
-#endif
-            if (pers_ok && !pers_off) {
+            if (pers_ok) {
                 GemmParams Q = P;
                 Q.total_tiles = grid;
                 const int ncu = cu_count();
@@ -132,9 +127,6 @@ int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
         if (!ok) (void)hipGetLastError();
     }
     auto k = P.N % TK == 0 ? k_whole : k_ragged;
-#ifdef SDROP_GEMM_TIMING
-    if (getenv("SDROP_NO_PERSIST")) return -1;
-#endif
     if (!ok) return -1;
     const int64_t positions = (int64_t)P.MB * P.KB;
     const int ncu = cu_count();

@@ -296,7 +296,6 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char *const staging = smem + STAGES * STAGE_BYTES;
 
-    GEMM_TICKW(12);
     // A kernel handed a mask built for another problem writes nothing.  The header is tested after
     // the first look-ups have been issued (they are addressed by the tile number alone and stay
     // inside the mask object whatever it holds), so that it costs no round trip of its own.
@@ -374,7 +373,6 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         Meta cur, n1, n2, n3;
         n1 = level1(0); n2 = level1(1); n3 = level1(2);
         if (!mask_ok()) return;
-        GEMM_TICKW(13);
         level2(n1); level3(n1);
         level2(n2);
         int k = -1;                      // round of the tile being issued
@@ -466,7 +464,6 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     // in flight: the next tile's kept count (cnt1_v), order[] of the tile after it (ord2_v)
     const int ord0_v = c_order(0), ord1_v = c_order(1), ord2_v = c_order(2);
     if (!mask_ok()) return;
-    GEMM_TICKW(13);
     int ord0 = uni(ord0_v);
     int len0 = uni(c_len(0, c_count(ord0)));
     int ord1 = uni(ord1_v);
@@ -486,7 +483,6 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         const int t = tile_of(k);
         if (t >= total) break;
         const int ord = ord0, nsteps = len0 << sub_shift;
-        GEMM_TICKW(k * 4);
         // requests for the tiles after this one; consumed after this tile's slices
         const int cnt1_v = c_count(ord1);
         const int ord3_v = c_order(k + 3);
@@ -510,15 +506,12 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         for (int s = 0; s < nsteps; ++s) {
             cw.slice(stage_ptr(st0), stage_ptr(st1));
             const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
-            if (s == 0) GEMM_TICKW(k * 4 + 1);
         }
         // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
         len0 = uni(c_len(k + 1, cnt1_v));
         ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
-        GEMM_TICKW(k * 4 + 2);
         cw.template finish<TAIL, RAGN>(reg, scale, ldc, tl, dst);
-        GEMM_TICKW(k * 4 + 3);
     }
 }
 
@@ -565,10 +558,8 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char *const staging = smem + STAGES * STAGE_BYTES;
 
-    GEMM_TICKW(12);
     const MaskHeader *H = P.mv.hdr;
     if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
-    GEMM_TICKW(13);
 
     const int lane = threadIdx.x & 63;
     const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -789,7 +780,6 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
 #pragma unroll
     for (int b = 0; b < 4; ++b) { gr[b] = uni(nxt.r[b]); gc[b] = uni(nxt.c[b]); }
     int gn = nxt.n, gu = nxt.u;
-    int tick_no = 0;        // timing builds only: tiles done by this workgroup
     for (int k = 0; gu >= 0; ++k) {
         nxt = c_load_group(k + 1);                      // in flight during this group's tiles
         int ngr[4] = {0, 0, 0, 0}, ngc[4] = {0, 0, 0, 0};
@@ -816,12 +806,10 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
                 gcol0 = col0;
                 return c_rows + (int64_t)(mi * 32) * ldc + col0 * ESZ;
             };
-            GEMM_TICKW(tick_no * 4);
             for (int s = 0; s < nsteps; ++s) {
                 cw.slice(stage_ptr(st0), stage_ptr(st1));
                 const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
             }
-            GEMM_TICKW(tick_no * 4 + 1);
             // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
 #pragma unroll
@@ -839,9 +827,6 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
                 }
             }
             cw.template finish<TAIL>(reg, scale, ldc, tl, dst);
-            GEMM_TICKW(tick_no * 4 + 2);
-            GEMM_TICKW(tick_no * 4 + 3);
-            ++tick_no;
             a += nb;
         }
 #pragma unroll

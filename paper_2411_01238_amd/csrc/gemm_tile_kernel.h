@@ -34,7 +34,6 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    GEMM_TICK(0);
     // a kernel handed a mask built for another problem writes nothing
     const MaskHeader *H = P.mv.hdr;
     if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
@@ -192,7 +191,6 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    GEMM_TICK(1);
     if (nsteps > 0) {
         using SliceA = Slice<A_KMAJ, TM, RAGGED && OP == DX>;
         using SliceB = Slice<B_KMAJ, TN, RAGGED, DXG>;
@@ -311,7 +309,6 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
         constexpr int NFR = MI * (A_TR ? 2 : 1) + NI * (B_TR ? 2 : 1);              // LDS reads per operand set
 
         int st0 = 0, st1 = 1, st2 = 2;      // stages of slices s, s+1, s+2
-        GEMM_TICK(2);
         if (!loader) read_frags(0, stage_ptr(0), 0);
 
         if (loader) {
@@ -439,7 +436,6 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
     // is four consecutive columns.  A wavefront parks its WTM x WTN sub-tile in its own piece of
     // LDS (rows padded by one quad against bank conflicts) and writes it out 16 bytes per lane,
     // so that a store instruction covers full 128-byte lines instead of 32 scattered pieces.
-    GEMM_TICK(3);
     {
         constexpr int ESZ = (int)sizeof(OutT);
         constexpr int ROWB = WTN * ESZ, RS = ROWB + 4 * ESZ, REGION = WTM * RS;
@@ -584,7 +580,6 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
             if (P.C2) emit_mode(std::integral_constant<int, kTailLight>{}, make_tail_preact(P), P.C2 - P.C);
         }
         emit(make_tail(P), 0);
-        GEMM_TICK(4);
     }
 }
 

@@ -96,9 +96,6 @@ int dw_splits(int64_t M, int64_t N, int BM, int BK, int64_t K)
     const int64_t tiles = (K / BK) * ((N + 255) / 256);
     const int64_t ncu = cu_count();
     if (tiles >= ncu) return 1;
-#ifdef SDROP_GEMM_TIMING
-    if (getenv("SDROP_DW_SPLITS")) return atoi(getenv("SDROP_DW_SPLITS"));
-#endif
     int64_t max_parts = (M / BM) / 4;                      // keep at least ~4 row blocks per part
     if (max_parts > 16) max_parts = 16;
     const double len = (double)(M / 64), sum_cost = (double)K * (double)N / 0.86e6;
@@ -388,21 +385,6 @@ void *static_scratch()
 
 }  // namespace sdrop
 
-#ifdef SDROP_GEMM_TIMING
-// Timing builds are a single translation unit (the time stamps live in one device array): compile this
-// file alone with -DSDROP_GEMM_TIMING and leave the typed files out.
-#include "gemm_launch.h"
-namespace sdrop {
-template int dispatch_typed<F16>(int, bool, GemmParams &, hipStream_t);
-template int dispatch_typed<BF16>(int, bool, GemmParams &, hipStream_t);
-template int bwd_fused_typed<F16>(int, int, bool, bool, const GemmParams &, const GemmParams &, int, hipStream_t);
-template int bwd_fused_typed<BF16>(int, int, bool, bool, const GemmParams &, const GemmParams &, int, hipStream_t);
-}  // namespace sdrop
-extern "C" int sdrop_debug_ticks(long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(sdrop::g_ticks), sizeof(long long) * n);
-}
-#endif
 
 extern "C" {
 

@@ -43,24 +43,6 @@ struct MaskParams {
     uint64_t threshold;              // floor(p * 2^32)
 };
 
-// Philox4x32-10 (Salmon et al., SC'11); returns output word 0.
-__device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                                 uint32_t k0, uint32_t k1)
-{
-    constexpr uint32_t MUL0 = 0xD2511F53u, MUL1 = 0xCD9E8D57u;
-    constexpr uint32_t BUMP0 = 0x9E3779B9u, BUMP1 = 0xBB67AE85u;
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(MUL0, c0), lo0 = MUL0 * c0;
-        const uint32_t hi1 = __umulhi(MUL1, c2), lo1 = MUL1 * c2;
-        const uint32_t n0 = hi1 ^ c1 ^ k0;
-        const uint32_t n2 = hi0 ^ c3 ^ k1;
-        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
-        k0 += BUMP0; k1 += BUMP1;   // the bump after the last round is unused
-    }
-    return c0;
-}
-
 // Number of the logical block that decides block (i, j): with block splitting (Section 3.3) the
 // logical grid is (MB / split_m) x KBL and every logical entry is repeated split_m times along M
 // and split_k times along K; without it this is i * KB + j.
@@ -190,11 +172,6 @@ __global__ __launch_bounds__(256) void mask_draw_kernel(MaskParams P)
 }
 
 // Limits of the variant that keeps the bits and both pointer arrays in LDS between phases.
-#ifdef SDROP_MASK_TIMING
-#define MASK_TICK(n) do { if (threadIdx.x == 0) ticks[n] = wall_clock64(); } while (0)
-#else
-#define MASK_TICK(n) do { } while (0)
-#endif
 constexpr int kLdsWords = 2048;   // MB * words_per_row
 constexpr int kLdsPtrs = 2048;    // MB, KB
 
@@ -213,10 +190,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     uint64_t *const bits = IN_LDS ? s_bits : P.bits;
     int32_t *const row_ptr = IN_LDS ? s_row_ptr : P.row_ptr;
     int32_t *const col_ptr = IN_LDS ? s_col_ptr : P.col_ptr;
-#ifdef SDROP_MASK_TIMING
-    long long ticks[12] = {0};
-#endif
-    MASK_TICK(0);
 
     // -- rows: fetch the packed words (drawn by mask_draw_kernel, or given by the caller with
     //    possibly dirty padding bits), count per row --
@@ -230,7 +203,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
         if (IN_LDS || P.given_bits) P.bits[g] = word;
     }
     __syncthreads();
-    MASK_TICK(1);
     for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
         int cnt = 0;
         for (int w = 0; w < P.wpr; ++w) cnt += __popcll(bits[(int64_t)i * P.wpr + w]);
@@ -239,7 +211,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     if (threadIdx.x == 0) row_ptr[0] = 0;
     __syncthreads();
     block_inclusive_scan(row_ptr + 1, P.MB, wave_tot);
-    MASK_TICK(2);
     if (IN_LDS)
         for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = row_ptr[i];
 
@@ -259,7 +230,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
 
     local_order(bits, row_ptr, P);
 
-    MASK_TICK(3);
     // -- columns: lane <-> block row --
     for (int j = wave; j < P.KB; j += kMaskWaves) {
         int cnt = 0;
@@ -272,9 +242,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     }
     if (threadIdx.x == 0) col_ptr[0] = 0;
     __syncthreads();
-    MASK_TICK(4);
     block_inclusive_scan(col_ptr + 1, P.KB, wave_tot);
-    MASK_TICK(5);
     if (IN_LDS)
         for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = col_ptr[j];
     for (int j = wave; j < P.KB; j += kMaskWaves) {
@@ -289,12 +257,9 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
     }
 
     // -- schedules: heavy rows / columns first --
-    MASK_TICK(6);
     __shared__ int32_t s_first[2];
     descending_order(row_ptr, P.MB, P.KB, P.row_order, bins, wave_tot, &s_first[0]);
-    MASK_TICK(7);
     descending_order(col_ptr, P.KB, P.MB, P.col_order, bins, wave_tot, &s_first[1]);
-    MASK_TICK(8);
 
     if (threadIdx.x == 0) {
         MaskHeader h = {};
@@ -304,9 +269,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
         h.magic = kMaskMagic;
         h.max_row_cnt = s_first[0];
         h.max_col_cnt = s_first[1];
-#ifdef SDROP_MASK_TIMING
-        for (int n = 0; n < 9; ++n) h.pad_[2 + n] = (int32_t)(ticks[n] - ticks[0]);
-#endif
         *P.hdr = h;
     }
 }
@@ -347,10 +309,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
     __shared__ int32_t s_max[2];
     const int lane = lane_id(), wave = wave_id();
     const int nwords = P.MB * P.wpr;
-#ifdef SDROP_MASK_TIMING
-    long long ticks[12] = {0};
-#endif
-    MASK_TICK(0);
 
     // -- phase 0: the packed words into LDS (drawn here, drawn by mask_draw_kernel, or given) --
     for (int j = threadIdx.x; j < kSmallN; j += kMaskThreads) {
@@ -404,7 +362,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         }
     }
     __syncthreads();
-    MASK_TICK(1);
 
     // -- phase 1: kept counts per block row and per block column --
     for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) {
@@ -421,7 +378,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         if (w * 64 + lane < P.KB && c) atomicAdd(&s_ccnt[w * 64 + lane], c);
     }
     __syncthreads();
-    MASK_TICK(2);
 
     // -- phase 2: pointers (one wavefront each) and schedules.  rank = number of entries with a larger
     //    count, ties by index: with the key count * 1024 + (1023 - index) that is the number of larger
@@ -456,7 +412,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         }
     }
     __syncthreads();
-    MASK_TICK(3);
 
     // -- phase 3: the lists --
     for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
@@ -481,9 +436,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
             pos += __popcll(word);
         }
     }
-    MASK_TICK(4);
     if (nlo == 0) local_order(s_bits, s_row_ptr, P);
-    MASK_TICK(5);
     for (int j = wave; j < P.KB && wave < nls; j += nls) {
         int pos = s_col_ptr[j];
         for (int i0 = 0; i0 < P.MB; i0 += 64) {
@@ -502,10 +455,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         h.magic = kMaskMagic;
         h.max_row_cnt = s_max[0];
         h.max_col_cnt = s_max[1];
-#ifdef SDROP_MASK_TIMING
-        ticks[6] = wall_clock64();
-        for (int n = 0; n < 9; ++n) h.pad_[2 + n] = (int32_t)(ticks[n] - ticks[0]);
-#endif
         *P.hdr = h;
     }
 }
@@ -640,6 +589,28 @@ int sdrop_mask_from_bits(void *mask, size_t mask_bytes, int64_t M, int64_t K, in
 {
     if (!bits) return SDROP_EINVAL;
     return sdrop::launch_mask(mask, mask_bytes, M, K, BM, BK, 0.0, 0, 0, bits, stream);
+}
+
+int sdrop_mask_bits(const void *mask, uint64_t *bits_host, size_t n_words, int64_t *nnz_host, void *stream)
+{
+    if (!mask || (!bits_host && !nnz_host)) return SDROP_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the header first (it says how many words there are), then the words: two copies, each waited for
+    sdrop::MaskHeader h;
+    hipError_t e = hipMemcpyAsync(&h, mask, sizeof(h), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return sdrop::hip_status(e);
+    if (h.magic != sdrop::kMaskMagic || h.MB <= 0 || h.words_per_row <= 0) return SDROP_EINVAL;
+    if (nnz_host) *nnz_host = h.nnz;
+    if (bits_host) {
+        const size_t words = (size_t)h.MB * (size_t)h.words_per_row;
+        if (n_words < words) return SDROP_EWORKSPACE;
+        e = hipMemcpyAsync(bits_host, static_cast<const char *>(mask) + sizeof(sdrop::MaskHeader), words * sizeof(uint64_t),
+                           hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return sdrop::hip_status(e);
+    }
+    return SDROP_OK;
 }
 
 }  // extern "C"

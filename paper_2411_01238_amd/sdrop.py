@@ -22,7 +22,7 @@ OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
 MASK_NNZ_OFFSET = 36
 
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
-           "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_workspace_bytes",
+           "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_mask_bits", "sdrop_workspace_bytes",
            "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
            "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer",
            "sdrop_bias_grad_workspace_bytes", "sdrop_bias_grad")
@@ -84,6 +84,8 @@ def lib():
         L.sdrop_mask_split.restype = ci
         L.sdrop_mask_from_bits.argtypes = [vp, sz, i64, i64, ci, ci, vp, vp]
         L.sdrop_mask_from_bits.restype = ci
+        L.sdrop_mask_bits.argtypes = [vp, vp, sz, vp, vp]
+        L.sdrop_mask_bits.restype = ci
         L.sdrop_workspace_bytes.argtypes = [ci, i64, i64, i64, ci, ci, ci, ci]
         L.sdrop_workspace_bytes.restype = sz
         for name in ("sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw"):
@@ -208,9 +210,30 @@ class Mask:
         }
 
 
+def _mask_out(out, M, K, BM, BK, p):
+    """A new Mask, or `out` after checking that it was made for this shape (a reused object's buffer
+    and Python fields must agree with what the library is about to write into it)."""
+    if out is None:
+        return Mask(M, K, BM, BK, p)
+    if (out.M, out.K, out.BM, out.BK) != (M, K, BM, BK):
+        raise SdropError(ESHAPE, "mask object passed as out= was made for another shape")
+    return out
+
+
+def mask_bits_host(mask):
+    """(keep bits as a numpy uint64 array [MB, words_per_row], nnz) of a Mask, through sdrop_mask_bits
+    (synchronises with the current stream)."""
+    import numpy as np
+    words = np.zeros((mask.MB, int(mask.layout.words_per_row)), dtype=np.uint64)
+    nnz = ctypes.c_int64(-1)
+    _check(lib().sdrop_mask_bits(_dev(mask.buf, "mask"), words.ctypes.data_as(ctypes.c_void_p), words.size,
+                                 ctypes.byref(nnz), _stream()), "sdrop_mask_bits")
+    return words, int(nnz.value)
+
+
 def sdrop_mask(M, K, BM, BK, p, seed, rng_stream=0, out=None):
     """Draws the block mask of Section 3.2 on the device; returns a Mask."""
-    m = out if out is not None else Mask(M, K, BM, BK, p)
+    m = _mask_out(out, M, K, BM, BK, p)
     m.p = float(p)
     _check(lib().sdrop_mask(_dev(m.buf, "mask"), m.buf.numel(), M, K, BM, BK, float(p),
                             int(seed), int(rng_stream), _stream()), "sdrop_mask")
@@ -219,7 +242,7 @@ def sdrop_mask(M, K, BM, BK, p, seed, rng_stream=0, out=None):
 
 def sdrop_mask_split(M, K, BM, BK, split_m, split_k, p, seed, rng_stream=0, out=None):
     """Block splitting (Section 3.3): logical blocks of (split_m BM) x (split_k BK), retiled to BM x BK."""
-    m = out if out is not None else Mask(M, K, BM, BK, p)
+    m = _mask_out(out, M, K, BM, BK, p)
     m.p = float(p)
     _check(lib().sdrop_mask_split(_dev(m.buf, "mask"), m.buf.numel(), M, K, BM, BK, int(split_m), int(split_k),
                                   float(p), int(seed), int(rng_stream), _stream()), "sdrop_mask_split")
@@ -228,7 +251,7 @@ def sdrop_mask_split(M, K, BM, BK, split_m, split_k, p, seed, rng_stream=0, out=
 
 def sdrop_mask_from_bits(M, K, BM, BK, p, bits, out=None):
     """Mask object from given keep bits: int64/uint64 GPU tensor [MB, words_per_row]."""
-    m = out if out is not None else Mask(M, K, BM, BK, p)
+    m = _mask_out(out, M, K, BM, BK, p)
     m.p = float(p)
     _check(lib().sdrop_mask_from_bits(_dev(m.buf, "mask"), m.buf.numel(), M, K, BM, BK,
                                       _dev(bits, "bits"), _stream()), "sdrop_mask_from_bits")

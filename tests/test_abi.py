@@ -109,6 +109,15 @@ def test_host_side_argument_errors_return_before_any_launch():
         assert call(a1=ctypes.c_void_p(addr + 8)) == sdrop.EALIGN
 
 
+def test_mask_bits_rejects_null_arguments_on_the_host():
+    import ctypes
+    L = sdrop.lib()
+    buf = (ctypes.c_uint64 * 4)()
+    assert L.sdrop_mask_bits(None, buf, 4, None, None) == sdrop.EINVAL
+    # neither output asked for (the mask pointer is never dereferenced on the host)
+    assert L.sdrop_mask_bits(ctypes.c_void_p(4096), None, 0, None, None) == sdrop.EINVAL
+
+
 def test_fused_backward_checks_both_products_before_any_launch():
     L = sdrop.lib()
     buf = ctypes.create_string_buffer(1 << 16)

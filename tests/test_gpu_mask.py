@@ -108,3 +108,43 @@ def test_mask_from_bits():
     none = torch.zeros((4, 1), dtype=torch.int64, device="cuda")
     m = sdrop.sdrop_mask_from_bits(256, 256, 64, 64, 0.5, none)
     _check_mask(m, np.zeros((4, 4), dtype=np.uint8))
+
+
+def test_mask_bits_reads_the_object_back_through_the_c_abi():
+    # sdrop_mask_bits, called raw: host buffers, the one call that waits for the stream
+    import ctypes
+    L = sdrop.lib()
+    vp = ctypes.c_void_p
+    for (M, K, BM, BK, p, seed) in ((4096, 4096, 128, 128, 0.5, 0), (576, 64 * 70, 64, 64, 0.3, 5)):
+        m = sdrop.sdrop_mask(M, K, BM, BK, p, seed, 2)          # enqueued only: the call below must wait for it
+        keep = orc.mask(M // BM, K // BK, p, seed, 2)
+        want = orc.pack_bits(keep)
+        words = np.full(want.shape, 0xDEADBEEF, dtype=np.uint64)
+        nnz = ctypes.c_int64(-1)
+        rc = L.sdrop_mask_bits(vp(m.buf.data_ptr()), words.ctypes.data_as(vp), words.size, ctypes.byref(nnz), sdrop._stream())
+        assert rc == sdrop.OK
+        assert np.array_equal(words, want) and nnz.value == int(keep.sum())
+        # nnz alone; bits alone
+        nnz2 = ctypes.c_int64(-1)
+        assert L.sdrop_mask_bits(vp(m.buf.data_ptr()), None, 0, ctypes.byref(nnz2), sdrop._stream()) == sdrop.OK
+        assert nnz2.value == nnz.value
+        # too few words: refused, the bits untouched
+        short = np.full(want.size - 1, 7, dtype=np.uint64)
+        assert L.sdrop_mask_bits(vp(m.buf.data_ptr()), short.ctypes.data_as(vp), short.size, None, sdrop._stream()) == sdrop.EWORKSPACE
+        assert np.all(short == 7)
+        got, n = sdrop.mask_bits_host(m)
+        assert np.array_equal(got, want) and n == nnz.value
+    # a buffer that holds no mask object
+    junk = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    w1 = np.zeros(4, dtype=np.uint64)
+    assert L.sdrop_mask_bits(vp(junk.data_ptr()), w1.ctypes.data_as(vp), 4, None, sdrop._stream()) == sdrop.EINVAL
+    assert L.sdrop_mask_bits(None, w1.ctypes.data_as(vp), 4, None, None) == sdrop.EINVAL
+    assert L.sdrop_mask_bits(vp(junk.data_ptr()), None, 0, None, None) == sdrop.EINVAL
+
+
+def test_reusing_a_mask_object_for_another_shape_is_refused_by_the_binding():
+    m = sdrop.sdrop_mask(512, 512, 128, 128, 0.5, 0, 0)
+    with pytest.raises(sdrop.SdropError):
+        sdrop.sdrop_mask(512, 512, 64, 64, 0.5, 0, 0, out=m)
+    with pytest.raises(sdrop.SdropError):
+        sdrop.sdrop_mask_split(1024, 512, 128, 128, 2, 1, 0.5, 0, 0, out=m)
