@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="square4096")
+    ap.add_argument("--p", type=float, default=None, help="dropout rate of the headline (default: 0.5 where the workload is run at it, else the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -80,7 +81,7 @@ def main():
     # three buffer sets (576 MiB at 4096^3) rotate so that a step's operands are not left in
     # the 256 MiB Infinity Cache by the step before; a single-set (warm) figure is given too
     sets = _sets(w, 3, torch)
-    HEADLINE_P = headline_p(w)
+    HEADLINE_P = headline_p(w) if args.p is None else args.p
     mask = sdrop.Mask(w.M, w.K, w.BM, w.BK, HEADLINE_P)
     td = w.torch_dtype
     ws_need = sdrop.workspace_bytes(sdrop.OP_BWD_DW, w.M, w.K, w.N, w.BM, w.BK, td, td)
@@ -89,16 +90,15 @@ def main():
     def step(s, p, seed, events=None):
         if events is not None:
             events[0].record()
-        sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, seed, 0, out=mask)
+        # the mask and eq. (1) in one call: one launch where the block grid is small enough for every
+        # workgroup to draw it (the mask object for the backward comes out of the same launch), else two
+        sdrop.sdrop_fwd_seeded(s["X"], s["W"], w.BM, w.BK, p, seed, 0, mask=mask, out=s["Y"])
         if events is not None:
             events[1].record()
-        sdrop.sdrop_fwd(s["X"], s["W"], mask, out=s["Y"])
-        if events is not None:
-            events[2].record()
         # eq. (2) and eq. (3) in one call: one launch where the shapes allow it, else two
         sdrop.sdrop_bwd(s["dY"], s["W"], s["X"], mask, out_dx=s["dX"], out_dw=s["dW"], ws=ws)
         if events is not None:
-            events[3].record()
+            events[2].record()
 
     def nnz_of(p, seed):
         sdrop.sdrop_mask(w.M, w.K, w.BM, w.BK, p, seed, 0, out=mask)
@@ -116,11 +116,11 @@ def main():
         return (time.perf_counter() - t0) / steps * 1e3     # ms per step
 
     def per_kernel(p, steps, n_sets, seed=w.mask_seed):
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
         for i in range(steps):
             step(sets[i % n_sets], p, seed, evs[i])
         torch.cuda.synchronize()
-        names = ("mask", "fwd", "bwd")
+        names = ("fwd", "bwd")          # "fwd" is the call that also draws the mask
         return {n: sum(e[k].elapsed_time(e[k + 1]) for e in evs) / steps for k, n in enumerate(names)}
 
     flops_per_block = 3 * 2.0 * w.BM * w.BK * w.N
@@ -160,6 +160,10 @@ def main():
         return {n: sum(e[k].elapsed_time(e[k + 1]) for e in evs) / steps for k, n in enumerate(("dx", "dw"))}
     nnz_of(HEADLINE_P, w.mask_seed)
     kern_sep = separate(args.steps, 3)
+    # and the step with the mask as a launch of its own (sdrop_mask, sdrop_fwd, sdrop_bwd)
+    sdrop.set_tuning(sdrop.TUNE_FWD_SEEDED, 0)
+    ms_mask_launch = timed(HEADLINE_P, args.steps, args.warmup, 3)
+    sdrop.set_tuning(sdrop.TUNE_FWD_SEEDED, 1)
 
     # ---- sweep over p (fewer steps each), speed-up against the library's own dense run ----
     # The points are visited in shuffled order, in several rounds (every round visits every p), and a
@@ -264,7 +268,7 @@ def main():
     flops_launch = flops_gemm * (2 if dom == "bwd" else 1)     # the backward launch holds eq. (2) and eq. (3)
     achieved = flops_launch / (kern[dom] * 1e-3) / 1e12
     traffic = TRAFFIC_BYTES.get((w.name, HEADLINE_P), {})
-    roofline = {"bound": "mfma", "kernel": {"fwd": "sdrop_fwd", "bwd": "sdrop_bwd (eq. 2 and eq. 3)"}[dom],
+    roofline = {"bound": "mfma", "kernel": {"fwd": "sdrop_fwd_seeded (mask and eq. 1)", "bwd": "sdrop_bwd (eq. 2 and eq. 3)"}[dom],
                 "achieved": round(achieved, 3), "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_DENSE_TFLOPS, 5),
                 "traffic": traffic.get(dom),
@@ -285,13 +289,14 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "%s: M=%d K=%d N=%d %s, block %dx%d, p=%.1f (mask + fwd + dX + dW per step; dX and dW by one sdrop_bwd call), "
+        "config": {"workload": "%s: M=%d K=%d N=%d %s, block %dx%d, p=%.1f (mask + fwd + dX + dW per step; mask and fwd by one sdrop_fwd_seeded call, dX and dW by one sdrop_bwd call), "
                                "%s outputs, 3 rotating buffer sets" % (w.name, w.M, w.K, w.N, w.dtype, w.BM, w.BK, HEADLINE_P, w.dtype),
                    "kept_blocks": nnz, "blocks": w.MB * w.KB},
         "frac_of_bf16_peak": round(value / PEAK_BF16_DENSE_TFLOPS, 5),
         "ms_per_step_warm_single_set": round(ms_warm, 5),
         "untimed_settle_steps_before_warmup": 150,
         "ms_per_step_before_settle": round(ms_cold, 5),
+        "ms_per_step_with_mask_as_its_own_launch": round(ms_mask_launch, 5),
         "sweep": sweep,
         "sweep_order": sweep_order if sweep else None,
         "linearity": linearity,

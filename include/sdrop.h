@@ -71,9 +71,12 @@ enum { SDROP_OP_FWD = 0, SDROP_OP_BWD_DX = 1, SDROP_OP_BWD_DW = 2 };
  *       from the expected number of kept blocks, 128 or 256 forced
  *   SDROP_TUNE_BWD_FUSED  1 (default): sdrop_bwd computes both gradients in one launch where the
  *       shapes allow it; 0: always as the two separate launches
+ *   SDROP_TUNE_FWD_SEEDED  1 (default): sdrop_fwd_seeded draws the mask inside the forward kernel where the
+ *       block grid allows it; 0: always as sdrop_mask followed by sdrop_fwd
  * Returns SDROP_EINVAL for an unknown knob or a value outside its range.
  */
-enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0, SDROP_TUNE_BWD_FUSED = 1, SDROP_TUNE_DX_TILE_WIDTH = 2 };
+enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0, SDROP_TUNE_BWD_FUSED = 1, SDROP_TUNE_DX_TILE_WIDTH = 2,
+       SDROP_TUNE_FWD_SEEDED = 3 };
 int sdrop_set_tuning(int knob, int value);
 
 /* Text for an error code (static storage). */
@@ -205,6 +208,21 @@ size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, in
 int sdrop_fwd(const void *X, const void *W, const void *mask, void *Y,
               int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
               int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The mask of a step and eq. (1) in one call: draws m' exactly as sdrop_mask(mask, ..., p, seed, rng_stream) does,
+ * writes the same mask object to `mask` (for the backward calls of the step) and computes Y = s (X . m') W, all
+ * bit-identical to sdrop_mask followed by sdrop_fwd.  The paper found mask generation to dominate small layers
+ * (Section 3.4); here the mask kernel and the launch boundary behind it are what is left of that, and for block
+ * grids of at most 128 rows x 64 columns (M/BM * (K/BK rounded up to a power of two) <= 4096) this call removes
+ * both: one launch, in which every workgroup draws the grid itself (the generator is counter-based) and the
+ * workgroups share the writing of the mask object.  Larger grids run the two launches in turn.
+ *   mask, mask_bytes  device buffer of at least sdrop_mask_bytes(M, K, BM, BK) bytes: OUTPUT
+ *   other arguments as for sdrop_mask and sdrop_fwd; no workspace is needed
+ */
+int sdrop_fwd_seeded(const void *X, const void *W, void *mask, size_t mask_bytes, void *Y,
+                     int64_t M, int64_t K, int64_t N, int BM, int BK, double p, uint64_t seed, uint64_t rng_stream,
+                     int dtype, int out_dtype, void *stream);
 
 /*
  * eq. (2): dX[M,K] = s (dY W^T) . m'.  Only kept output blocks are computed

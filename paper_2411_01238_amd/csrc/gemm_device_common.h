@@ -35,6 +35,10 @@ struct GemmParams {
     int32_t gate_mode;  // how aux gates the output (SDROP_GATE_*)
     char *C2;           // DX only: second output, the value before the activation (same shape, type and stride as C), or null
     double p;           // host only: dropout probability, for choosing tile shapes
+    // the forward kernel that draws its own mask (SeededGrid): the generator's key (seed) and stream words, and the
+    // keep threshold floor(p 2^32)
+    uint32_t key0, key1, ctr2, ctr3;
+    uint64_t threshold;
 };
 
 namespace {

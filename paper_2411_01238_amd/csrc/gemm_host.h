@@ -49,6 +49,11 @@ template <class T> int dispatch_typed(int op, bool o32, GemmParams &P, hipStream
 // Returns -1 when the device does not grant the LDS the launch needs.
 template <class T> int bwd_fused_typed(int form, int TN, bool o32, bool dw_f32, const GemmParams &Pdx, const GemmParams &Pdw,
                                        int n_dx, hipStream_t stream);
+// The forward product by the kernel that draws its own mask and writes the mask object (see gemm_seeded_grid.h).
+// Returns -1 when the device does not grant the LDS the launch needs.
+template <class T> int fwd_seeded_typed(bool o32, const GemmParams &P, hipStream_t stream);
+extern template int fwd_seeded_typed<F16>(bool, const GemmParams &, hipStream_t);
+extern template int fwd_seeded_typed<BF16>(bool, const GemmParams &, hipStream_t);
 extern template int dispatch_typed<F16>(int, bool, GemmParams &, hipStream_t);
 extern template int dispatch_typed<BF16>(int, bool, GemmParams &, hipStream_t);
 extern template int bwd_fused_typed<F16>(int, int, bool, bool, const GemmParams &, const GemmParams &, int, hipStream_t);

@@ -89,6 +89,33 @@ int launch_t(const GemmParams &P, int grid, bool ragged, hipStream_t stream, boo
     return hip_status(hipGetLastError());
 }
 
+// The forward kernel that draws its own mask and writes the mask object (block grids of at most 128 x 64; whole
+// tiles or a ragged last tile column).  Returns -1 when the device does not grant the LDS.
+template <class T, class OutT, int TM>
+int launch_fwd_seeded(const GemmParams &P, hipStream_t stream)
+{
+    constexpr int P_LDS = 3 * (TM + 256) * TK * 2 + 4 * 4096;
+    auto k_whole = fwd_seeded_kernel<T, OutT, TM, false>;
+    auto k_edge = fwd_seeded_kernel<T, OutT, TM, true>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_whole), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_edge), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    GemmParams Q = P;
+    Q.n_tiles = (int)((P.N + 255) / 256);
+    Q.splits = 1;
+    Q.total_tiles = Q.MB * Q.n_tiles;
+    const int ncu = cu_count();
+    auto k = P.N % 256 != 0 ? k_edge : k_whole;
+    hipLaunchKernelGGL(k, dim3((unsigned)(Q.total_tiles < ncu ? Q.total_tiles : ncu)), dim3(512), P_LDS, stream, Q);
+    return hip_status(hipGetLastError());
+}
+
 // Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
 template <class T, class OutT, int TN, int TAIL>
 int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
@@ -271,6 +298,13 @@ template <class T> int dispatch_typed(int op, bool o32, GemmParams &P, hipStream
     if (op == FWD) return o32 ? dispatch_tile<FWD, T, float>(P, stream) : dispatch_tile<FWD, T, O16>(P, stream);
     if (op == DX) return o32 ? dispatch_tile<DX, T, float>(P, stream) : dispatch_tile<DX, T, O16>(P, stream);
     return o32 ? dispatch_tile<DW, T, float>(P, stream) : dispatch_tile<DW, T, O16>(P, stream);
+}
+
+template <class T> int fwd_seeded_typed(bool o32, const GemmParams &P, hipStream_t stream)
+{
+    using O16 = typename In<T>::out16;
+    if (P.BM == 128) return o32 ? launch_fwd_seeded<T, float, 128>(P, stream) : launch_fwd_seeded<T, O16, 128>(P, stream);
+    return o32 ? launch_fwd_seeded<T, float, 64>(P, stream) : launch_fwd_seeded<T, O16, 64>(P, stream);
 }
 
 template <class T> int bwd_fused_typed(int form, int TN, bool o32, bool dw_f32, const GemmParams &Pdx, const GemmParams &Pdw,

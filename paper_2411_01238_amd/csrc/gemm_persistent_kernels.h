@@ -3,6 +3,7 @@
 #ifndef SDROP_GEMM_PERSISTENT_KERNELS_H
 #define SDROP_GEMM_PERSISTENT_KERNELS_H
 #include "gemm_tile_kernel.h"
+#include "gemm_seeded_grid.h"
 
 namespace sdrop {
 namespace {
@@ -280,10 +281,16 @@ constexpr int waitcnt_lgkm0_only() { return 15 | (3 << 14) | (7 << 4) | (0 << 8)
 // the number of slices from the same mask lists, so they execute the same number of barriers.
 // (The body is a device function of the workgroup's index w among G, so that one launch can hold
 // the workgroups of two operations; see bwd_fused_kernel.)
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false>
+//
+// SEEDED (the forward only): there is no mask object to read.  Every workgroup draws the block grid itself and keeps
+// it in registers (SeededGrid), so a tile's block row and its kept columns come from a few scalar instructions
+// instead of three dependent look-ups, and the computing wavefronts write the mask object for the backward kernels,
+// a small piece each, before they meet their first barrier.
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false, bool SEEDED = false>
 __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const int G, const int w)
 {
     static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
+    static_assert(!SEEDED || OP == FWD, "only the forward kernel draws its own mask");
     constexpr int NW = WM * WN;
     static_assert(NW == 4, "one computing and one loading wavefront per SIMD");
     constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
@@ -317,6 +324,9 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     const int32_t *const ptr = (OP == FWD) ? P.mv.row_ptr : P.mv.col_ptr;
     const int32_t *const lists = (OP == FWD) ? P.mv.col_idx : P.mv.row_idx;
     const int per_line = P.n_tiles * P.splits;            // tiles per block row / column
+
+    SeededGrid sg;
+    if constexpr (SEEDED) sg.draw(P, reinterpret_cast<uint64_t *>(staging));     // all eight wavefronts; two barriers inside
 
     // tile number of round k (may be >= total: the sequence has ended)
     auto tile_of = [&](int k) __attribute__((always_inline)) -> int { return k * G + ((k & 1) ? G - 1 - w : w); };
@@ -371,10 +381,14 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         auto level3 = [&](Meta &m) __attribute__((always_inline)) { m.e0 = entry(m, 0); m.e1 = entry(m, 1); };
 
         Meta cur, n1, n2, n3;
-        n1 = level1(0); n2 = level1(1); n3 = level1(2);
-        if (!mask_ok()) return;
-        level2(n1); level3(n1);
-        level2(n2);
+        if constexpr (!SEEDED) {
+            n1 = level1(0); n2 = level1(1); n3 = level1(2);
+            if (!mask_ok()) return;
+            level2(n1); level3(n1);
+            level2(n2);
+        }
+        uint64_t w_rem = 0;              // SEEDED: kept columns of the current block row that are still to come
+        int nt_cur = 0, ord_cur = 0;
         int k = -1;                      // round of the tile being issued
         int s = 0, nsteps = 0;           // next slice of that tile; its number of slices
         int e_cur = 0, e_nxt = 0;        // list entries of slice s and of the block after it
@@ -387,18 +401,31 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             while (s == nsteps) {
                 if (ended) return false;
                 ++k;
-                cur = n1;
-                if (cur.t >= total) { ended = true; return false; }
-                n1 = n2; level3(n1);
-                n2 = n3; level2(n2);
-                n3 = level1(k + 3);
-                s = 0;
-                nsteps = cur.len << sub_shift;
-                e_cur = cur.e0; e_nxt = cur.e1;
-                const int line = cur.t % per_line;
-                const int nt = line / P.splits;
-                if constexpr (OP == FWD) a_tile = P.A + (int64_t)cur.ord * P.BM * lda;
-                else a_tile = P.A + (int64_t)cur.ord * P.BK * 2;
+                if constexpr (SEEDED) {
+                    const int t = tile_of(k);
+                    if (t >= total) { ended = true; return false; }
+                    ord_cur = sg.row_of_rank(t / per_line);
+                    nt_cur = t % per_line;
+                    const uint64_t word = sg.row_word(ord_cur);
+                    s = 0;
+                    nsteps = (int)__popcll(word) << sub_shift;
+                    e_cur = word ? (int)__builtin_ctzll(word) : 0;
+                    w_rem = word & (word - 1);
+                } else {
+                    cur = n1;
+                    if (cur.t >= total) { ended = true; return false; }
+                    n1 = n2; level3(n1);
+                    n2 = n3; level2(n2);
+                    n3 = level1(k + 3);
+                    s = 0;
+                    nsteps = cur.len << sub_shift;
+                    e_cur = cur.e0; e_nxt = cur.e1;
+                    ord_cur = cur.ord;
+                    nt_cur = (cur.t % per_line) / P.splits;
+                }
+                const int nt = nt_cur;
+                if constexpr (OP == FWD) a_tile = P.A + (int64_t)ord_cur * P.BM * lda;
+                else a_tile = P.A + (int64_t)ord_cur * P.BK * 2;
                 b_tile = P.B + (int64_t)nt * TN * 2;
                 if constexpr (RAGN) {
                     const int64_t left = P.N - (int64_t)nt * TN;
@@ -420,8 +447,13 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             }
             ++s;
             if ((s & sub_mask) == 0) {
-                e_cur = e_nxt;
-                e_nxt = entry(cur, (s >> sub_shift) + 1);
+                if constexpr (SEEDED) {
+                    e_cur = w_rem ? (int)__builtin_ctzll(w_rem) : 0;
+                    w_rem &= w_rem - 1;
+                } else {
+                    e_cur = e_nxt;
+                    e_nxt = entry(cur, (s >> sub_shift) + 1);
+                }
             }
             return true;
         };
@@ -462,13 +494,19 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     };
     // scalars: this tile (ord0, len0), the next one's block row / column (ord1);
     // in flight: the next tile's kept count (cnt1_v), order[] of the tile after it (ord2_v)
-    const int ord0_v = c_order(0), ord1_v = c_order(1), ord2_v = c_order(2);
-    if (!mask_ok()) return;
-    int ord0 = uni(ord0_v);
-    int len0 = uni(c_len(0, c_count(ord0)));
-    int ord1 = uni(ord1_v);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
-    int ord2 = uni(ord2_v);
+    int ord0 = 0, len0 = 0, ord1 = 0, ord2 = 0;
+    if constexpr (SEEDED) {
+        // this wavefront's pieces of the mask object, while the first operands are on their way
+        sg.write_pieces(P, w * NW + wave, G * NW);
+    } else {
+        const int ord0_v = c_order(0), ord1_v = c_order(1), ord2_v = c_order(2);
+        if (!mask_ok()) return;
+        ord0 = uni(ord0_v);
+        len0 = uni(c_len(0, c_count(ord0)));
+        ord1 = uni(ord1_v);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+        ord2 = uni(ord2_v);
+    }
 
     Compute<T, OutT, A_TR, B_TR, TM, TN, WM, WN> cw;
     cw.wm = wm; cw.wn = wn;
@@ -482,10 +520,16 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     for (int k = 0;; ++k) {
         const int t = tile_of(k);
         if (t >= total) break;
+        int cnt1_v = 0, ord3_v = 0;
+        if constexpr (SEEDED) {
+            ord0 = sg.row_of_rank(t / per_line);
+            len0 = (int)__popcll(sg.row_word(ord0));
+        } else {
+            // requests for the tiles after this one; consumed after this tile's slices
+            cnt1_v = c_count(ord1);
+            ord3_v = c_order(k + 3);
+        }
         const int ord = ord0, nsteps = len0 << sub_shift;
-        // requests for the tiles after this one; consumed after this tile's slices
-        const int cnt1_v = c_count(ord1);
-        const int ord3_v = c_order(k + 3);
 
         cw.zero();
         if (nsteps > 0 && !started) {
@@ -507,10 +551,12 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             cw.slice(stage_ptr(st0), stage_ptr(st1));
             const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
         }
-        // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
-        len0 = uni(c_len(k + 1, cnt1_v));
-        ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
+        if constexpr (!SEEDED) {
+            // the look-ups have had the whole tile to arrive and no store is in flight: this wait is free
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+            len0 = uni(c_len(k + 1, cnt1_v));
+            ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
+        }
         cw.template finish<TAIL, RAGN>(reg, scale, ldc, tl, dst);
     }
 }
@@ -519,6 +565,13 @@ template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL,
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
 {
     gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL, RAGN>(P, gridDim.x, blockIdx.x);
+}
+
+// The forward kernel that draws its own mask and writes the mask object as well (see SEEDED above).
+template <class T, class OutT, int TM, bool RAGN>
+__global__ __launch_bounds__(512) void fwd_seeded_kernel(GemmParams P)
+{
+    gemm_persistent_body<FWD, T, OutT, TM, 256, 1, 4, kTailNone, RAGN, true>(P, gridDim.x, blockIdx.x);
 }
 
 // a[i] for a uniform index i in 0..3, as selects (keeps everything in scalar registers)

@@ -1,0 +1,236 @@
+// The block mask of a small grid, drawn inside a GEMM kernel and held in registers (included by the GEMM translation
+// units only).
+//
+// The paper found mask generation to dominate the run time of small layers (Section 3.4).  Here the mask kernel of a
+// step and the launch boundary behind it cost about 15 us, a tenth of a 4096^3 step and a fifth of an 8192 x 1024 x 1024
+// one.  For block grids of at most 128 rows and 64 columns every workgroup of the forward kernel therefore draws the
+// whole mask itself: the generator is counter-based, a block's keep flag depends on (seed, stream, block number, p)
+// only, so every workgroup arrives at the same bits without talking to anyone.  A block row's flags are one 64-bit
+// word; lane l of every wavefront keeps the words of rows l and l + 64, and everything the forward kernel looks up in a
+// mask object (the heaviest-first order of the rows, a row's kept columns) is computed from those registers:
+// no dependent chain of global loads at the start of the kernel.  The mask object that the backward kernels read is
+// written by the same launch, cut into small independent pieces that the computing wavefronts of all workgroups share
+// while they wait for their first operands.
+#ifndef SDROP_GEMM_SEEDED_GRID_H
+#define SDROP_GEMM_SEEDED_GRID_H
+#include "gemm_device_common.h"
+
+namespace sdrop {
+namespace {
+
+constexpr int kSeededMaxRows = 128, kSeededMaxCols = 64;
+
+__device__ __forceinline__ int wave_incl_scan(int v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(v, d, 64);
+        if (lane >= d) v += up;
+    }
+    return v;
+}
+__device__ __forceinline__ int wave_sum(int v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+__device__ __forceinline__ uint64_t lanes_below_mask() { return (uint64_t(1) << (threadIdx.x & 63)) - 1; }
+
+struct SeededGrid {
+    uint64_t rw[2];     // keep bits of block rows lane and lane + 64 (0 for rows that do not exist)
+    int cnt[2];         // kept blocks of those rows
+    int rank[2];        // their place in the heaviest-first order (more kept blocks first, ties: lower row first)
+    int MB, KB;
+
+    // keep bits of block row i (uniform)
+    __device__ __forceinline__ uint64_t row_word(int i) const
+    {
+        const uint64_t v = i < 64 ? rw[0] : rw[1];
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, i & 63);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), i & 63);
+        return ((uint64_t)hi << 32) | lo;
+    }
+    // the block row at place q of the heaviest-first order (uniform q < MB)
+    __device__ __forceinline__ int row_of_rank(int q) const
+    {
+        const uint64_t b0 = __ballot(rank[0] == q);
+        if (b0) return (int)__builtin_ctzll(b0);
+        const uint64_t b1 = __ballot(rank[1] == q);
+        return b1 ? 64 + (int)__builtin_ctzll(b1) : 0;
+    }
+
+    // Draws the grid: every wavefront of the workgroup takes its share of the rows (a wavefront draws 64 / (KB
+    // rounded up to a power of two) rows per ballot, so that no lane idles through the Philox rounds), the row words
+    // meet in `s_words` (LDS, room for MB words, free for this use until the second barrier below), and every
+    // wavefront reads all of them back.  Called by all wavefronts of the workgroup.
+    __device__ __forceinline__ void draw(const GemmParams &P, uint64_t *s_words)
+    {
+        const int lane = threadIdx.x & 63;
+        const int wave = uni((int)(threadIdx.x >> 6)), nwaves = (int)(blockDim.x >> 6);
+        MB = P.MB; KB = P.KB;
+        int kshift = 0;
+        while ((1 << kshift) < KB) ++kshift;
+        const int kbp = 1 << kshift, R = 64 >> kshift, sub = lane >> kshift, j = lane & (kbp - 1);
+        for (int b = wave; b * R < MB; b += nwaves) {
+            const int i = b * R + sub;
+            bool keep = false;
+            if (i < MB && j < KB) {
+                const uint32_t blk = (uint32_t)(i * KB + j);        // the block number b = i KB + j of the generator's counter
+                keep = (uint64_t)philox_word0(blk, 0u, P.ctr2, P.ctr3, P.key0, P.key1) >= P.threshold;
+            }
+            const uint64_t all = __ballot(keep);
+            if (j == 0 && i < MB) s_words[i] = kbp == 64 ? all : ((all >> (sub * kbp)) & ((uint64_t(1) << kbp) - 1));
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int i = lane + 64 * r;
+            rw[r] = i < MB ? s_words[i] : 0;
+            cnt[r] = (int)__popcll(rw[r]);
+        }
+        __syncthreads();            // from here on the LDS is the kernel's again
+        // rank = number of rows with a larger key; the key count * 1024 + (1023 - row) is the one the mask kernel sorts by
+        int key[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) key[r] = lane + 64 * r < MB ? cnt[r] * 1024 + (1023 - (lane + 64 * r)) : -1;
+        rank[0] = rank[1] = 0;
+        for (int q = 0; q < MB && q < 64; ++q) {
+            const int kq = __builtin_amdgcn_readlane(key[0], q);
+            rank[0] += kq > key[0]; rank[1] += kq > key[1];
+        }
+        for (int q = 64; q < MB; ++q) {
+            const int kq = __builtin_amdgcn_readlane(key[1], q - 64);
+            rank[0] += kq > key[0]; rank[1] += kq > key[1];
+        }
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+            if (lane + 64 * r >= MB) rank[r] = 1 << 20;
+    }
+
+    // ---- the mask object, in pieces ----
+    // Piece numbers: 0 = header, bits, col_ptr, col_order; 1 = row_ptr, row_order; then one per block row (its part of
+    // col_idx / blk_row), one per block column (its part of row_idx), one per group of 8 block rows (its part of
+    // loc_row / loc_col).  Every piece is computed from the registers alone and writes a part of the object that no
+    // other piece writes; the result is what sdrop_mask builds (same lists, same tie-breaking).
+    __device__ __forceinline__ int pieces() const { return 2 + MB + KB + (MB + 7) / 8; }
+
+    // exclusive prefix sums of the rows' kept counts, for this lane's two rows; total = number of kept blocks
+    __device__ __forceinline__ void row_starts(int (&start)[2], int &total) const
+    {
+        const int i0 = wave_incl_scan(cnt[0]);
+        const int t0 = __builtin_amdgcn_readlane(i0, 63);
+        const int i1 = wave_incl_scan(cnt[1]) + t0;
+        start[0] = i0 - cnt[0];
+        start[1] = i1 - cnt[1];
+        total = __builtin_amdgcn_readlane(i1, 63);
+    }
+    __device__ __forceinline__ int start_of_row(const int (&start)[2], int i) const
+    {
+        return __builtin_amdgcn_readlane(i < 64 ? start[0] : start[1], i & 63);
+    }
+
+    __device__ __forceinline__ void write_piece(const GemmParams &P, int piece) const
+    {
+        const int lane = threadIdx.x & 63;
+        const MaskView &mv = P.mv;
+        // the object is this launch's output although the GEMM parameters describe it as an input
+        int32_t *const row_ptr = const_cast<int32_t *>(mv.row_ptr), *const col_idx = const_cast<int32_t *>(mv.col_idx);
+        int32_t *const blk_row = const_cast<int32_t *>(mv.blk_row), *const col_ptr = const_cast<int32_t *>(mv.col_ptr);
+        int32_t *const row_idx = const_cast<int32_t *>(mv.row_idx), *const row_order = const_cast<int32_t *>(mv.row_order);
+        int32_t *const col_order = const_cast<int32_t *>(mv.col_order);
+        int32_t *const loc_row = const_cast<int32_t *>(mv.loc_row), *const loc_col = const_cast<int32_t *>(mv.loc_col);
+        if (piece == 0) {
+            // kept count of block column `lane`: one pass over the rows
+            int ccnt = 0;
+            for (int i = 0; i < MB; ++i) ccnt += (int)((row_word(i) >> lane) & 1);
+            if (lane >= KB) ccnt = 0;
+            const int incl = wave_incl_scan(ccnt);
+            if (lane < KB) col_ptr[lane] = incl - ccnt;
+            const int total = __builtin_amdgcn_readlane(incl, 63);
+            if (lane == 0) col_ptr[KB] = total;
+            const int key = lane < KB ? ccnt * 1024 + (1023 - lane) : -1;
+            int crank = 0;
+            for (int q = 0; q < KB; ++q) crank += __builtin_amdgcn_readlane(key, q) > key;
+            if (lane < KB) col_order[crank] = lane;
+            const uint64_t first_col = __ballot(lane < KB && crank == 0), first_row = __ballot(rank[0] == 0);
+            const int max_col = __builtin_amdgcn_readlane(ccnt, first_col ? (int)__builtin_ctzll(first_col) : 0);
+            const uint64_t first_row1 = __ballot(rank[1] == 0);
+            const int max_row = first_row ? __builtin_amdgcn_readlane(cnt[0], (int)__builtin_ctzll(first_row))
+                                          : __builtin_amdgcn_readlane(cnt[1], first_row1 ? (int)__builtin_ctzll(first_row1) : 0);
+            uint64_t *const bits = const_cast<uint64_t *>(mv.bits);
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+                if (lane + 64 * r < MB) bits[lane + 64 * r] = rw[r];
+            if (lane == 0) {
+                MaskHeader h = {};
+                h.M = P.M; h.K = P.K; h.BM = P.BM; h.BK = P.BK; h.MB = MB; h.KB = KB;
+                h.words_per_row = 1;
+                h.nnz = total;
+                h.magic = kMaskMagic;
+                h.max_row_cnt = max_row;
+                h.max_col_cnt = max_col;
+                *const_cast<MaskHeader *>(mv.hdr) = h;
+            }
+            return;
+        }
+        int start[2], total;
+        row_starts(start, total);
+        if (piece == 1) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+                if (lane + 64 * r < MB) { row_ptr[lane + 64 * r] = start[r]; row_order[rank[r]] = lane + 64 * r; }
+            if (lane == 0) row_ptr[MB] = total;
+            return;
+        }
+        piece -= 2;
+        if (piece < MB) {
+            // block row `piece`: lane <-> block column
+            const uint64_t word = row_word(piece);
+            const int base = start_of_row(start, piece);     // read from another lane: outside the divergent branch
+            if ((word >> lane) & 1) {
+                const int at = base + (int)__popcll(word & lanes_below_mask());
+                col_idx[at] = lane;
+                blk_row[at] = piece;
+            }
+            return;
+        }
+        piece -= MB;
+        if (piece < KB) {
+            // block column `piece`: lane <-> block row; the ballots are the column's keep bits
+            const int j = piece;
+            const uint64_t c0 = __ballot((rw[0] >> j) & 1), c1 = __ballot((rw[1] >> j) & 1);
+            const uint64_t below = (uint64_t(1) << j) - 1;
+            const int base = wave_sum((int)__popcll(rw[0] & below) + (int)__popcll(rw[1] & below));   // kept blocks in earlier columns
+            if ((rw[0] >> j) & 1) row_idx[base + (int)__popcll(c0 & lanes_below_mask())] = lane;
+            if ((rw[1] >> j) & 1) row_idx[base + (int)__popcll(c0) + (int)__popcll(c1 & lanes_below_mask())] = lane + 64;
+            return;
+        }
+        piece -= KB;
+        {
+            // group `piece` of 8 block rows, sorted by (column, row): lane <-> block column
+            const int i0 = piece * 8, nr = MB - i0 < 8 ? MB - i0 : 8;
+            int mine = 0, c = 0;
+            for (int r = 0; r < nr; ++r) {
+                const int bit = (int)((row_word(i0 + r) >> lane) & 1);
+                mine |= bit << r;
+                c += bit;
+            }
+            int at = start_of_row(start, i0) + wave_incl_scan(c) - c;
+            for (int r = 0; r < nr; ++r)
+                if ((mine >> r) & 1) { loc_row[at] = i0 + r; loc_col[at] = lane; ++at; }
+        }
+    }
+
+    // wavefront `slot` of `nslots` writes pieces slot, slot + nslots, ...
+    __device__ __forceinline__ void write_pieces(const GemmParams &P, int slot, int nslots) const
+    {
+        const int n = pieces();
+        for (int piece = slot; piece < n; piece += nslots) write_piece(P, piece);
+    }
+};
+
+}  // namespace
+}  // namespace sdrop
+#endif

@@ -55,6 +55,7 @@
 // and ~1.4 GHz with the loads as well, at 84 % MFMA duty (1214 clocks per slice against 1024).
 #include "gemm_host.h"
 #include <atomic>
+#include <math.h>
 
 namespace sdrop {
 
@@ -201,6 +202,8 @@ GemmParams base_params(int op, const void *a, const void *b, const void *mask, v
     P.bias = nullptr; P.aux = nullptr; P.act = SDROP_ACT_NONE;
     P.gate_mode = SDROP_GATE_RELU; P.C2 = nullptr;
     P.p = p;
+    P.key0 = P.key1 = P.ctr2 = P.ctr3 = 0;
+    P.threshold = 0;
     return P;
 }
 
@@ -280,6 +283,45 @@ int run(const void *a, const void *b, const void *mask, void *out,
     }
     const bool o32 = out_dtype == SDROP_F32;
     return dtype == SDROP_F16 ? dispatch_typed<F16>(OP, o32, P, st) : dispatch_typed<BF16>(OP, o32, P, st);
+}
+
+// The mask and the forward product in one launch (fwd_seeded_kernel) where the block grid is small enough for every
+// workgroup to draw it: at most 128 block rows and 64 block columns, and at most 64 ballots of draws per workgroup
+// (8 per wavefront, about a microsecond).  Anything else is sdrop_mask followed by sdrop_fwd.
+int g_fwd_seeded = 1;
+
+bool fwd_seeded_applies(const sdrop_mask_layout_t &L)
+{
+    if (!g_fwd_seeded || L.MB > 128 || L.KB > 64) return false;
+    int64_t kbp = 1;
+    while (kbp < L.KB) kbp <<= 1;
+    return L.MB * kbp <= 4096;
+}
+
+int run_fwd_seeded(const void *x, const void *w, void *mask, size_t mask_bytes, void *y,
+                   int64_t M, int64_t K, int64_t N, int BM, int BK, double p, uint64_t seed, uint64_t rng_stream,
+                   int dtype, int out_dtype, void *stream)
+{
+    // every argument check of both calls before anything is enqueued
+    const int rc = check_gemm_args(x, w, mask, y, M, K, N, BM, BK, p, dtype, out_dtype);
+    if (rc != SDROP_OK) return rc;
+    sdrop_mask_layout_t L;
+    sdrop_mask_layout(M, K, BM, BK, &L);
+    if (mask_bytes < L.total_bytes) return SDROP_EWORKSPACE;
+    if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
+    if (fwd_seeded_applies(L)) {
+        GemmParams P = base_params(FWD, x, w, mask, y, M, K, N, BM, BK, p, out_dtype, L);
+        P.key0 = (uint32_t)seed; P.key1 = (uint32_t)(seed >> 32);
+        P.ctr2 = (uint32_t)rng_stream; P.ctr3 = (uint32_t)(rng_stream >> 32);
+        P.threshold = (uint64_t)floor(p * 4294967296.0);
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        const bool o32 = out_dtype == SDROP_F32;
+        const int rs = dtype == SDROP_F16 ? fwd_seeded_typed<F16>(o32, P, st) : fwd_seeded_typed<BF16>(o32, P, st);
+        if (rs != -1) return rs;        // -1: the device does not grant the LDS; fall through to the two calls
+    }
+    const int rm = sdrop_mask(mask, mask_bytes, M, K, BM, BK, p, seed, rng_stream, stream);
+    if (rm != SDROP_OK) return rm;
+    return run<FWD>(x, w, mask, y, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream);
 }
 
 // both gradients in one launch where bwd_fused_kernel or bwd_fused_tile_kernel applies (128 x 128
@@ -398,6 +440,10 @@ int sdrop_set_tuning(int knob, int value)
         sdrop::g_bwd_fused = value;
         return SDROP_OK;
     }
+    if (knob == SDROP_TUNE_FWD_SEEDED && (value == 0 || value == 1)) {
+        sdrop::g_fwd_seeded = value;
+        return SDROP_OK;
+    }
     if (knob == SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU && value >= 0) {
         sdrop::g_dx_persistent_groups_per_cu = value;
         return SDROP_OK;
@@ -420,6 +466,13 @@ int sdrop_fwd(const void *X, const void *W, const void *mask, void *Y,
               int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
 {
     return sdrop::run<sdrop::FWD>(X, W, mask, Y, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
+}
+
+int sdrop_fwd_seeded(const void *X, const void *W, void *mask, size_t mask_bytes, void *Y,
+                     int64_t M, int64_t K, int64_t N, int BM, int BK, double p, uint64_t seed, uint64_t rng_stream,
+                     int dtype, int out_dtype, void *stream)
+{
+    return sdrop::run_fwd_seeded(X, W, mask, mask_bytes, Y, M, K, N, BM, BK, p, seed, rng_stream, dtype, out_dtype, stream);
 }
 
 int sdrop_bwd_dx(const void *dY, const void *W, const void *mask, void *dX,

@@ -23,7 +23,7 @@ MASK_NNZ_OFFSET = 36
 
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_mask_bits", "sdrop_workspace_bytes",
-           "sdrop_fwd", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
+           "sdrop_fwd", "sdrop_fwd_seeded", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
            "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer",
            "sdrop_bias_grad_workspace_bytes", "sdrop_bias_grad")
 
@@ -92,6 +92,8 @@ def lib():
             f = getattr(L, name)
             f.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
             f.restype = ci
+        L.sdrop_fwd_seeded.argtypes = [vp, vp, vp, sz, vp, i64, i64, i64, ci, ci, dbl, u64, u64, ci, ci, vp]
+        L.sdrop_fwd_seeded.restype = ci
         L.sdrop_bwd_dw_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp]
         L.sdrop_bwd_dw_static.restype = ci
         for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex"):
@@ -114,6 +116,7 @@ TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0
 DX_PERSISTENT_GROUPS_PER_CU_DEFAULT = 8
 TUNE_BWD_FUSED = 1
 TUNE_DX_TILE_WIDTH = 2
+TUNE_FWD_SEEDED = 3
 
 
 def set_tuning(knob, value):
@@ -331,6 +334,32 @@ def sdrop_fwd(X, W, mask, out_dtype=None, out=None, ws=None):
     if K2 != K or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_fwd")
     return _gemm("sdrop_fwd", OP_FWD, X, W, mask, (M, N), M, K, N, out_dtype, out, ws)
+
+
+def sdrop_fwd_seeded(X, W, BM, BK, p, seed, rng_stream=0, mask=None, out_dtype=None, out=None):
+    """The step's mask and eq. (1) in one call (one launch for small block grids): returns (Y, Mask).
+    The Mask is the object sdrop_mask would have written; the backward calls of the step take it."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K:
+        raise SdropError(ESHAPE, "sdrop_fwd_seeded")
+    dtype = X.dtype
+    if W.dtype != dtype:
+        raise ValueError("operands must have the same dtype")
+    out_dtype = dtype if out_dtype is None else out_dtype
+    if dtype not in (torch.float16, torch.bfloat16) or out_dtype not in _DTYPES:
+        raise SdropError(EDTYPE, "sdrop_fwd_seeded")
+    m = _mask_out(mask, M, K, BM, BK, p)
+    m.p = float(p)
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=X.device)
+    elif tuple(out.shape) != (M, N) or out.dtype != out_dtype:
+        raise ValueError("out has the wrong shape or dtype")
+    rc = lib().sdrop_fwd_seeded(_dev(X, "X"), _dev(W, "W"), _dev(m.buf, "mask"), m.buf.numel(), _dev(out, "Y"),
+                                M, K, N, BM, BK, float(p), int(seed), int(rng_stream),
+                                _DTYPES[dtype], _DTYPES[out_dtype], _stream())
+    _check(rc, "sdrop_fwd_seeded")
+    return out, m
 
 
 def sdrop_bwd_dx(dY, W, mask, out_dtype=None, out=None, ws=None):
