@@ -326,7 +326,10 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     const int per_line = P.n_tiles * P.splits;            // tiles per block row / column
 
     SeededGrid sg;
-    if constexpr (SEEDED) sg.draw(P, reinterpret_cast<uint64_t *>(staging));     // all eight wavefronts; two barriers inside
+    // all eight wavefronts; two barriers inside.  The third stage is free for it: the loaders fill it only after the
+    // stream's first barrier, which the computing wavefronts join after they have read the order back
+    static_assert(SeededGrid::kLdsBytes <= STAGE_BYTES, "the draw's scratch must fit a stage");
+    if constexpr (SEEDED) sg.draw(P, smem + 2 * STAGE_BYTES);
 
     // tile number of round k (may be >= total: the sequence has ended)
     auto tile_of = [&](int k) __attribute__((always_inline)) -> int { return k * G + ((k & 1) ? G - 1 - w : w); };
@@ -523,7 +526,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
         int cnt1_v = 0, ord3_v = 0;
         if constexpr (SEEDED) {
             ord0 = sg.row_of_rank(t / per_line);
-            len0 = (int)__popcll(sg.row_word(ord0));
+            len0 = sg.row_count(ord0);
         } else {
             // requests for the tiles after this one; consumed after this tile's slices
             cnt1_v = c_count(ord1);

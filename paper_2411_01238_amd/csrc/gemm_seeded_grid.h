@@ -20,29 +20,36 @@ namespace {
 
 constexpr int kSeededMaxRows = 128, kSeededMaxCols = 64;
 
-__device__ __forceinline__ int wave_incl_scan(int v)
+// number of set bits of `mask` that belong to lanes below this one
+__device__ __forceinline__ int below_count(uint64_t mask)
 {
-    const int lane = threadIdx.x & 63;
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+// Sum of v (0 <= v < 2^BITS) over the lanes below this one, and over all lanes, without LDS traffic or shuffles: one
+// ballot per bit of v, whose set bits are counted below the lane and altogether.
+template <int BITS> __device__ __forceinline__ int excl_prefix(int v, int &total)
+{
+    int pre = 0;
+    total = 0;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int up = __shfl_up(v, d, 64);
-        if (lane >= d) v += up;
+    for (int b = 0; b < BITS; ++b) {
+        const uint64_t m = __ballot((v >> b) & 1);
+        pre += below_count(m) << b;
+        total += (int)__popcll(m) << b;
     }
-    return v;
+    return pre;
 }
-__device__ __forceinline__ int wave_sum(int v)
-{
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
-}
-__device__ __forceinline__ uint64_t lanes_below_mask() { return (uint64_t(1) << (threadIdx.x & 63)) - 1; }
 
 struct SeededGrid {
     uint64_t rw[2];     // keep bits of block rows lane and lane + 64 (0 for rows that do not exist)
     int cnt[2];         // kept blocks of those rows
-    int rank[2];        // their place in the heaviest-first order (more kept blocks first, ties: lower row first)
+    int ord[2];         // the block rows at places lane and lane + 64 of the heaviest-first order (more kept blocks
+                        // first, ties: lower row first)
+    int ccnt;           // kept blocks of block column `lane` (0 for columns that do not exist)
     int MB, KB;
+
+    // LDS the draw needs: the row words, the order, the column counts
+    static constexpr int kLdsBytes = kSeededMaxRows * 8 + kSeededMaxRows * 4 + kSeededMaxCols * 4;
 
     // keep bits of block row i (uniform)
     __device__ __forceinline__ uint64_t row_word(int i) const
@@ -52,21 +59,21 @@ struct SeededGrid {
         const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), i & 63);
         return ((uint64_t)hi << 32) | lo;
     }
+    __device__ __forceinline__ int row_count(int i) const { return __builtin_amdgcn_readlane(i < 64 ? cnt[0] : cnt[1], i & 63); }
     // the block row at place q of the heaviest-first order (uniform q < MB)
-    __device__ __forceinline__ int row_of_rank(int q) const
-    {
-        const uint64_t b0 = __ballot(rank[0] == q);
-        if (b0) return (int)__builtin_ctzll(b0);
-        const uint64_t b1 = __ballot(rank[1] == q);
-        return b1 ? 64 + (int)__builtin_ctzll(b1) : 0;
-    }
+    __device__ __forceinline__ int row_of_rank(int q) const { return __builtin_amdgcn_readlane(q < 64 ? ord[0] : ord[1], q & 63); }
 
-    // Draws the grid: every wavefront of the workgroup takes its share of the rows (a wavefront draws 64 / (KB
-    // rounded up to a power of two) rows per ballot, so that no lane idles through the Philox rounds), the row words
-    // meet in `s_words` (LDS, room for MB words, free for this use until the second barrier below), and every
-    // wavefront reads all of them back.  Called by all wavefronts of the workgroup.
-    __device__ __forceinline__ void draw(const GemmParams &P, uint64_t *s_words)
+    // Draws the grid.  Every wavefront of the workgroup takes its share of the rows (a wavefront draws 64 / (KB
+    // rounded up to a power of two) rows per ballot, so that no lane idles through the Philox rounds) and the row
+    // words meet in LDS; every wavefront reads all of them back, ranks its share of the rows (rank = number of
+    // rows with a larger key, two ballots per row; the key count * 1024 + (1023 - row) is the one the mask kernel
+    // sorts by) and the order meets in LDS the same way.  `lds` (kLdsBytes) must stay untouched by anyone else
+    // until every wavefront has passed one more barrier after this call.  Called by all wavefronts of the workgroup.
+    __device__ __forceinline__ void draw(const GemmParams &P, char *lds)
     {
+        uint64_t *const s_words = reinterpret_cast<uint64_t *>(lds);
+        int32_t *const s_order = reinterpret_cast<int32_t *>(lds + kSeededMaxRows * 8);
+        int32_t *const s_ccnt = s_order + kSeededMaxRows;
         const int lane = threadIdx.x & 63;
         const int wave = uni((int)(threadIdx.x >> 6)), nwaves = (int)(blockDim.x >> 6);
         MB = P.MB; KB = P.KB;
@@ -84,29 +91,28 @@ struct SeededGrid {
             if (j == 0 && i < MB) s_words[i] = kbp == 64 ? all : ((all >> (sub * kbp)) & ((uint64_t(1) << kbp) - 1));
         }
         __syncthreads();
+        int key[2];
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int i = lane + 64 * r;
             rw[r] = i < MB ? s_words[i] : 0;
             cnt[r] = (int)__popcll(rw[r]);
+            key[r] = i < MB ? cnt[r] * 1024 + (1023 - i) : -1;
         }
-        __syncthreads();            // from here on the LDS is the kernel's again
-        // rank = number of rows with a larger key; the key count * 1024 + (1023 - row) is the one the mask kernel sorts by
-        int key[2];
+        for (int i = wave; i < MB; i += nwaves) {
+            const int ki = __builtin_amdgcn_readlane(i < 64 ? key[0] : key[1], i & 63);
+            const int rank = (int)__popcll(__ballot(key[0] > ki)) + (int)__popcll(__ballot(key[1] > ki));
+            if (lane == 0) s_order[rank] = i;
+        }
+        // kept counts of the block columns, shared the same way: a column's keep bits are a ballot over the rows
+        for (int jc = wave; jc < KB; jc += nwaves) {
+            const int c = (int)__popcll(__ballot((rw[0] >> jc) & 1)) + (int)__popcll(__ballot((rw[1] >> jc) & 1));
+            if (lane == 0) s_ccnt[jc] = c;
+        }
+        __syncthreads();
 #pragma unroll
-        for (int r = 0; r < 2; ++r) key[r] = lane + 64 * r < MB ? cnt[r] * 1024 + (1023 - (lane + 64 * r)) : -1;
-        rank[0] = rank[1] = 0;
-        for (int q = 0; q < MB && q < 64; ++q) {
-            const int kq = __builtin_amdgcn_readlane(key[0], q);
-            rank[0] += kq > key[0]; rank[1] += kq > key[1];
-        }
-        for (int q = 64; q < MB; ++q) {
-            const int kq = __builtin_amdgcn_readlane(key[1], q - 64);
-            rank[0] += kq > key[0]; rank[1] += kq > key[1];
-        }
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-            if (lane + 64 * r >= MB) rank[r] = 1 << 20;
+        for (int r = 0; r < 2; ++r) ord[r] = lane + 64 * r < MB ? s_order[lane + 64 * r] : 0;
+        ccnt = lane < KB ? s_ccnt[lane] : 0;
     }
 
     // ---- the mask object, in pieces ----
@@ -119,12 +125,12 @@ struct SeededGrid {
     // exclusive prefix sums of the rows' kept counts, for this lane's two rows; total = number of kept blocks
     __device__ __forceinline__ void row_starts(int (&start)[2], int &total) const
     {
-        const int i0 = wave_incl_scan(cnt[0]);
-        const int t0 = __builtin_amdgcn_readlane(i0, 63);
-        const int i1 = wave_incl_scan(cnt[1]) + t0;
-        start[0] = i0 - cnt[0];
-        start[1] = i1 - cnt[1];
-        total = __builtin_amdgcn_readlane(i1, 63);
+        int t0, t1;
+        start[0] = excl_prefix<7>(cnt[0], t0);
+        start[1] = t0;
+        t1 = 0;
+        if (MB > 64) start[1] += excl_prefix<7>(cnt[1], t1);        // uniform branch
+        total = t0 + t1;
     }
     __device__ __forceinline__ int start_of_row(const int (&start)[2], int i) const
     {
@@ -142,23 +148,17 @@ struct SeededGrid {
         int32_t *const col_order = const_cast<int32_t *>(mv.col_order);
         int32_t *const loc_row = const_cast<int32_t *>(mv.loc_row), *const loc_col = const_cast<int32_t *>(mv.loc_col);
         if (piece == 0) {
-            // kept count of block column `lane`: one pass over the rows
-            int ccnt = 0;
-            for (int i = 0; i < MB; ++i) ccnt += (int)((row_word(i) >> lane) & 1);
-            if (lane >= KB) ccnt = 0;
-            const int incl = wave_incl_scan(ccnt);
-            if (lane < KB) col_ptr[lane] = incl - ccnt;
-            const int total = __builtin_amdgcn_readlane(incl, 63);
+            int total;
+            const int cstart = excl_prefix<8>(ccnt, total);
+            if (lane < KB) col_ptr[lane] = cstart;
             if (lane == 0) col_ptr[KB] = total;
             const int key = lane < KB ? ccnt * 1024 + (1023 - lane) : -1;
             int crank = 0;
             for (int q = 0; q < KB; ++q) crank += __builtin_amdgcn_readlane(key, q) > key;
             if (lane < KB) col_order[crank] = lane;
-            const uint64_t first_col = __ballot(lane < KB && crank == 0), first_row = __ballot(rank[0] == 0);
+            const uint64_t first_col = __ballot(lane < KB && crank == 0);
             const int max_col = __builtin_amdgcn_readlane(ccnt, first_col ? (int)__builtin_ctzll(first_col) : 0);
-            const uint64_t first_row1 = __ballot(rank[1] == 0);
-            const int max_row = first_row ? __builtin_amdgcn_readlane(cnt[0], (int)__builtin_ctzll(first_row))
-                                          : __builtin_amdgcn_readlane(cnt[1], first_row1 ? (int)__builtin_ctzll(first_row1) : 0);
+            const int max_row = row_count(row_of_rank(0));
             uint64_t *const bits = const_cast<uint64_t *>(mv.bits);
 #pragma unroll
             for (int r = 0; r < 2; ++r)
@@ -180,7 +180,7 @@ struct SeededGrid {
         if (piece == 1) {
 #pragma unroll
             for (int r = 0; r < 2; ++r)
-                if (lane + 64 * r < MB) { row_ptr[lane + 64 * r] = start[r]; row_order[rank[r]] = lane + 64 * r; }
+                if (lane + 64 * r < MB) { row_ptr[lane + 64 * r] = start[r]; row_order[lane + 64 * r] = ord[r]; }
             if (lane == 0) row_ptr[MB] = total;
             return;
         }
@@ -190,7 +190,7 @@ struct SeededGrid {
             const uint64_t word = row_word(piece);
             const int base = start_of_row(start, piece);     // read from another lane: outside the divergent branch
             if ((word >> lane) & 1) {
-                const int at = base + (int)__popcll(word & lanes_below_mask());
+                const int at = base + (int)below_count(word);
                 col_idx[at] = lane;
                 blk_row[at] = piece;
             }
@@ -201,10 +201,10 @@ struct SeededGrid {
             // block column `piece`: lane <-> block row; the ballots are the column's keep bits
             const int j = piece;
             const uint64_t c0 = __ballot((rw[0] >> j) & 1), c1 = __ballot((rw[1] >> j) & 1);
-            const uint64_t below = (uint64_t(1) << j) - 1;
-            const int base = wave_sum((int)__popcll(rw[0] & below) + (int)__popcll(rw[1] & below));   // kept blocks in earlier columns
-            if ((rw[0] >> j) & 1) row_idx[base + (int)__popcll(c0 & lanes_below_mask())] = lane;
-            if ((rw[1] >> j) & 1) row_idx[base + (int)__popcll(c0) + (int)__popcll(c1 & lanes_below_mask())] = lane + 64;
+            int base;                                         // kept blocks in earlier columns: those columns' counts, summed
+            (void)excl_prefix<8>(lane < j ? ccnt : 0, base);
+            if ((rw[0] >> j) & 1) row_idx[base + below_count(c0)] = lane;
+            if ((rw[1] >> j) & 1) row_idx[base + (int)__popcll(c0) + below_count(c1)] = lane + 64;
             return;
         }
         piece -= KB;
@@ -217,7 +217,8 @@ struct SeededGrid {
                 mine |= bit << r;
                 c += bit;
             }
-            int at = start_of_row(start, i0) + wave_incl_scan(c) - c;
+            int in_group;
+            int at = start_of_row(start, i0) + excl_prefix<4>(c, in_group);
             for (int r = 0; r < nr; ++r)
                 if ((mine >> r) & 1) { loc_row[at] = i0 + r; loc_col[at] = lane; ++at; }
         }

@@ -55,15 +55,16 @@ inline MaskView make_view(const void *mask, const sdrop_mask_layout_t &L)
 __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                  uint32_t k0, uint32_t k1)
 {
-    constexpr uint32_t MUL0 = 0xD2511F53u, MUL1 = 0xCD9E8D57u;
+    // the two 32 x 32 -> 64-bit products of a round, each as ONE 64-bit multiply (a multiply-add instruction that
+    // delivers both halves; written as separate high and low products the round costs four multiplies)
+    constexpr uint64_t MUL0 = 0xD2511F53u, MUL1 = 0xCD9E8D57u;
     constexpr uint32_t BUMP0 = 0x9E3779B9u, BUMP1 = 0xBB67AE85u;
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(MUL0, c0), lo0 = MUL0 * c0;
-        const uint32_t hi1 = __umulhi(MUL1, c2), lo1 = MUL1 * c2;
-        const uint32_t n0 = hi1 ^ c1 ^ k0;
-        const uint32_t n2 = hi0 ^ c3 ^ k1;
-        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        const uint64_t p0 = MUL0 * (uint64_t)c0, p1 = MUL1 * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c0 = n0; c1 = (uint32_t)p1; c2 = n2; c3 = (uint32_t)p0;
         k0 += BUMP0; k1 += BUMP1;   // the bump after the last round is unused
     }
     return c0;
