@@ -166,6 +166,24 @@ def bwd_dw(X, dY, keep, BM, BK, p):
     return _gemm("sdo_bwd_dw", X, dY, keep, M, K, N, BM, BK, p, (K, N))
 
 
+# The same three products for a weight stored as Wt[N,K], one row per output feature (the [out, in] layout
+# of common frameworks; Section 3.1 writes W in R^{K x N}, so Wt is its transpose).  Defined through the
+# functions above on an explicit transposed copy: W[k][n] = Wt[n][k].
+def fwd_wt(X, Wt, keep, BM, BK, p):
+    """eq. (1) with W given as Wt[N,K]: Y = (X . m') Wt^T / (1-p)."""
+    return fwd(X, np.ascontiguousarray(np.asarray(Wt, dtype=np.float64).T), keep, BM, BK, p)
+
+
+def bwd_dx_wt(dY, Wt, keep, BM, BK, p):
+    """eq. (2) with W given as Wt[N,K]: dX = (dY Wt) . m' / (1-p)."""
+    return bwd_dx(dY, np.ascontiguousarray(np.asarray(Wt, dtype=np.float64).T), keep, BM, BK, p)
+
+
+def bwd_dw_wt(X, dY, keep, BM, BK, p):
+    """eq. (3) with the gradient delivered in the weight's [N,K] layout: dWt = dY^T (X . m') / (1-p)."""
+    return np.ascontiguousarray(bwd_dw(X, dY, keep, BM, BK, p).T)
+
+
 def _gemm_at(name, A, B, keep, M, K, N, BM, BK, p, rows, cols):
     A = _f64(A)
     B = _f64(B)

@@ -204,3 +204,33 @@ def test_retiled_mask_gives_the_products_of_the_logical_mask():
         for g, r in zip(got, ref):
             # the same elements are kept; only the grouping of the sums may differ
             assert np.allclose(g, r, rtol=1e-13, atol=1e-13), (sm, sk)
+
+
+def test_weight_in_out_in_layout_by_index_loops_and_einsum():
+    # Wt[N,K] is the transpose of Section 3.1's W[K,N].  Pins: scalar index loops on a tiny case (a missing or
+    # doubled transpose, or a gradient left in [K,N], fails them), einsum with an element mask on non-square
+    # and on square shapes (square shapes pass every shape check with the wrong orientation).
+    rng = np.random.default_rng(5)
+    for (M, K, N, BM, BK) in ((4, 6, 3, 2, 3), (6, 4, 4, 3, 2), (4, 4, 4, 2, 2)):
+        X, Wt, dY = rng.standard_normal((M, K)), rng.standard_normal((N, K)), rng.standard_normal((M, N))
+        keep = (rng.random((M // BM, K // BK)) < 0.6).astype(np.uint8)
+        keep[0, 0] = 1
+        p = 0.25
+        s = 1.0 / (1.0 - p)
+        el = np.repeat(np.repeat(keep, BM, axis=0), BK, axis=1).astype(np.float64)
+        Y, dX, dWt = orc.fwd_wt(X, Wt, keep, BM, BK, p), orc.bwd_dx_wt(dY, Wt, keep, BM, BK, p), orc.bwd_dw_wt(X, dY, keep, BM, BK, p)
+        assert Y.shape == (M, N) and dX.shape == (M, K) and dWt.shape == (N, K)
+        for r in range(M):
+            for n in range(N):
+                assert abs(Y[r, n] - s * sum(X[r, k] * el[r, k] * Wt[n, k] for k in range(K))) < 1e-12
+            for k in range(K):
+                assert abs(dX[r, k] - s * el[r, k] * sum(dY[r, n] * Wt[n, k] for n in range(N))) < 1e-12
+        for n in range(N):
+            for k in range(K):
+                assert abs(dWt[n, k] - s * sum(dY[r, n] * X[r, k] * el[r, k] for r in range(M))) < 1e-12
+        assert np.allclose(Y, s * np.einsum("mk,nk->mn", X * el, Wt), atol=1e-12)
+        assert np.allclose(dX, s * el * np.einsum("mn,nk->mk", dY, Wt), atol=1e-12)
+        assert np.allclose(dWt, s * np.einsum("mn,mk->nk", dY, X * el), atol=1e-12)
+        # and against the [K,N] functions on the transposed weight
+        assert np.array_equal(Y, orc.fwd(X, np.ascontiguousarray(Wt.T), keep, BM, BK, p))
+        assert np.array_equal(dWt.T, orc.bwd_dw(X, dY, keep, BM, BK, p))
