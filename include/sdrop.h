@@ -214,8 +214,7 @@ int sdrop_fwd(const void *X, const void *W, const void *mask, void *Y,
  * writes the same mask object to `mask` (for the backward calls of the step) and computes Y = s (X . m') W, all
  * bit-identical to sdrop_mask followed by sdrop_fwd.  The paper found mask generation to dominate small layers
  * (Section 3.4); here the mask kernel and the launch boundary behind it are what is left of that, and for block
- * grids of at most 128 rows x 64 columns (M/BM * (K/BK rounded up to a power of two) <= 4096) this call removes
- * both: one launch, in which every workgroup draws the grid itself (the generator is counter-based) and the
+ * grids of at most 128 rows x 64 columns this call removes both: one launch, in which every workgroup draws the grid itself (the generator is counter-based) and the
  * workgroups share the writing of the mask object.  Larger grids run the two launches in turn.
  *   mask, mask_bytes  device buffer of at least sdrop_mask_bytes(M, K, BM, BK) bytes: OUTPUT
  *   other arguments as for sdrop_mask and sdrop_fwd; no workspace is needed
@@ -277,6 +276,16 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
               int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * sdrop_bwd for row-strided matrices: the leading dimensions, in elements, of dY[M,N], W[K,N], X[M,K], dX[M,K] and
+ * dW[K,N] (0 = contiguous; else at least the number of columns, a multiple of 8, at most 2^24, else SDROP_ESHAPE).
+ * Same launches and results as sdrop_bwd on contiguous copies; nothing outside the column ranges is written.
+ */
+int sdrop_bwd_ex(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,
+                 int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                 int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                 int64_t ld_dy, int64_t ld_w, int64_t ld_x, int64_t ld_dx, int64_t ld_dw);
+
+/*
  * Sparse operators for the layers around the dropout (Section 4.3, closing remark: the layer
  * directly before the dropout can use sparse operators as well).  None of this is part of
  * eq. (1)-(3); it is what lets a block  H -> act(H W0^T + b0) -> SparseDrop -> . W  run without
@@ -318,6 +327,12 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
 enum { SDROP_SCALE_DROPOUT = 0, SDROP_SCALE_ONE = 1 };
 enum { SDROP_ACT_NONE = 0, SDROP_ACT_RELU = 1, SDROP_ACT_GELU_TANH = 2, SDROP_ACT_GELU_ERF = 3 };
 enum { SDROP_GATE_RELU = 0, SDROP_GATE_GELU_TANH = 1, SDROP_GATE_GELU_ERF = 2 };
+/* Layout of the weight of eq. (1)-(3).  SDROP_W_KN: W[K,N] as Section 3.1 writes it.  SDROP_W_NK: Wt[N,K], one row
+ * per output feature (the [out, in] layout of common frameworks): sdrop_fwd_ex and sdrop_bwd_dx_ex then take Wt as
+ * their second operand (ld_b >= K), sdrop_bwd_dw_ex delivers the gradient as dWt[N,K] (ld_out >= K).  The kernels walk
+ * W by rows of K, so such a weight is transposed into the workspace by a pass of its own before the product (and the
+ * gradient after it): sdrop_workspace_bytes_ex gives the larger workspace these calls need. */
+enum { SDROP_W_KN = 0, SDROP_W_NK = 1 };
 
 typedef struct sdrop_epilogue {
     int32_t scale_mode;
@@ -326,7 +341,12 @@ typedef struct sdrop_epilogue {
     const void *relu_mask;
     int64_t ld_a, ld_b, ld_out;
     int32_t gate_mode;
+    int32_t w_layout;
 } sdrop_epilogue_t;
+
+/* sdrop_workspace_bytes for an _ex call with this tail (epi may be NULL: then exactly sdrop_workspace_bytes). */
+size_t sdrop_workspace_bytes_ex(int op, int64_t M, int64_t K, int64_t N, int BM, int BK,
+                                int dtype, int out_dtype, const sdrop_epilogue_t *epi);
 
 int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,
                  int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
@@ -364,6 +384,11 @@ int sdrop_bwd_dw_ex(const void *X, const void *dY, const void *mask, void *dW,
 int sdrop_producer(const void *H, const void *W0, const float *bias, const void *mask, void *X, void *Z,
                    int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
                    int dtype, int out_dtype, void *stream);
+
+/* sdrop_producer for row-strided matrices: leading dimensions of H[M,N0], W0[K,N0] and of X (and Z) [M,K], as above. */
+int sdrop_producer_ex(const void *H, const void *W0, const float *bias, const void *mask, void *X, void *Z,
+                      int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
+                      int dtype, int out_dtype, void *stream, int64_t ld_h, int64_t ld_w0, int64_t ld_out);
 
 /*
  * Gradient of that layer's bias (the block of Section 4.3's closing remark, as above):

@@ -80,6 +80,49 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, Ou
     out[e + 2] = static_cast<OutT>(acc.z * scale); out[e + 3] = static_cast<OutT>(acc.w * scale);
 }
 
+// dst[c][r] = src[r][c] for a rows x cols matrix of 2- or 4-byte elements (rows of src ld_src elements apart, rows of dst
+// ld_dst apart): 64 x 64 tiles through LDS, so that both the reads and the writes cover whole 128-byte (or longer) runs.
+// Used where a weight comes, or its gradient goes, in the [N,K] layout (see run()).
+template <class E>
+__global__ __launch_bounds__(256) void transpose_kernel(const E *src, E *dst, int64_t rows, int64_t cols, int64_t ld_src, int64_t ld_dst)
+{
+    __shared__ E tile[64][65];
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4)
+        if (r0 + r < rows && c0 + tx < cols) tile[r][tx] = src[(r0 + r) * ld_src + c0 + tx];
+    __syncthreads();
+    for (int c = ty; c < 64; c += 4)
+        if (c0 + c < cols && r0 + tx < rows) dst[(c0 + c) * ld_dst + r0 + tx] = tile[tx][c];
+}
+
+int launch_transpose(const void *src, void *dst, int64_t rows, int64_t cols, int64_t ld_src, int64_t ld_dst, int esz, hipStream_t st)
+{
+    const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
+    if (esz == 4)
+        hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, st, static_cast<const uint32_t *>(src), static_cast<uint32_t *>(dst), rows, cols, ld_src, ld_dst);
+    else
+        hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, st, static_cast<const uint16_t *>(src), static_cast<uint16_t *>(dst), rows, cols, ld_src, ld_dst);
+    return hip_status(hipGetLastError());
+}
+
+int dw_splits(int64_t M, int64_t N, int BM, int BK, int64_t K);
+
+// Workspace of one product: the fp32 planes of a split dW first, then (weight in the [N,K] layout) a K x N matrix: the
+// transposed weight for FWD / DX (operand type), the gradient before its transposition for DW (output type).
+size_t ws_planes_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, int BK)
+{
+    if (op != SDROP_OP_BWD_DW) return 0;
+    const int splits = dw_splits(M, N, BM, BK, K);
+    return splits > 1 ? (size_t)splits * (size_t)K * (size_t)N * sizeof(float) : 0;
+}
+size_t ws_total_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, int BK, int out_dtype, bool w_nk)
+{
+    size_t need = ws_planes_bytes(op, M, K, N, BM, BK);
+    if (w_nk) need += (size_t)K * (size_t)N * (op == SDROP_OP_BWD_DW && out_dtype == SDROP_F32 ? 4 : 2);
+    return need;
+}
+
 // Parts the reduction of DW is cut into.  DW has only KB * ceil(N/256) output tiles; when
 // that is fewer than the chip has CUs, each block column's kept-row list is cut into parts
 // computed by different workgroups into fp32 planes that a second pass sums in a fixed
@@ -237,36 +280,55 @@ int run(const void *a, const void *b, const void *mask, void *out,
         if (epi->scale_mode != SDROP_SCALE_DROPOUT && epi->scale_mode != SDROP_SCALE_ONE) return SDROP_EINVAL;
         if (epi->act < SDROP_ACT_NONE || epi->act > SDROP_ACT_GELU_ERF) return SDROP_EINVAL;
         if (epi->gate_mode < SDROP_GATE_RELU || epi->gate_mode > SDROP_GATE_GELU_ERF) return SDROP_EINVAL;
+        if (epi->w_layout != SDROP_W_KN && epi->w_layout != SDROP_W_NK) return SDROP_EINVAL;
         // the gradient of the weights takes a scale only
         if (OP == DW && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask)) return SDROP_EINVAL;
         if ((reinterpret_cast<uintptr_t>(epi->bias) | reinterpret_cast<uintptr_t>(epi->relu_mask)) % 16) return SDROP_EALIGN;
         // leading dimensions: 0 = contiguous; else at least the row length, rows 16-byte aligned, lane offsets 32-bit
-        const int64_t cols_a = OP == DX ? N : K, cols_b = N, cols_c = OP == DX ? K : N;
+        const bool nk = epi->w_layout == SDROP_W_NK;        // the weight (FWD, DX: second operand; DW: the output) as [N,K]
+        const int64_t cols_a = OP == DX ? N : K, cols_b = (nk && OP != DW) ? K : N, cols_c = OP == DX ? K : (nk && OP == DW) ? K : N;
         const int64_t lds[3] = {epi->ld_a, epi->ld_b, epi->ld_out}, cols[3] = {cols_a, cols_b, cols_c};
         for (int i = 0; i < 3; ++i)
             if (lds[i] != 0 && (lds[i] < cols[i] || lds[i] % 8 || lds[i] > (int64_t(1) << 24))) return SDROP_ESHAPE;
     }
-    const size_t ws_need = sdrop_workspace_bytes(OP, M, K, N, BM, BK, dtype, out_dtype);
+    if (out2 && reinterpret_cast<uintptr_t>(out2) % 16) return SDROP_EALIGN;
+    const bool w_nk = epi && epi->w_layout == SDROP_W_NK;
+    const size_t ws_planes = ws_planes_bytes(OP, M, K, N, BM, BK);
+    const size_t ws_need = ws_total_bytes(OP, M, K, N, BM, BK, out_dtype, w_nk);
     if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
     sdrop_mask_layout_t L;
     sdrop_mask_layout(M, K, BM, BK, &L);
     if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // A weight in the [N,K] layout: the kernels read W as [K,N] (eq. 1 walks its row blocks, eq. 2 its rows), so the
+    // weight is transposed into the workspace first (one pass over K N elements; at 4096 x 4096 about 15 us beside a
+    // product of 60), and eq. 3 writes its [K,N] result there and transposes it into the output afterwards.
+    char *const ws_kn = static_cast<char *>(ws) + ws_planes;       // the K x N matrix behind the planes
+    const int64_t esz_out = out_dtype == SDROP_F32 ? 4 : 2;
+    void *final_out = out;
+    int64_t final_ld = 0;
+    if (w_nk) {
+        if constexpr (OP == DW) {
+            final_ld = epi->ld_out ? epi->ld_out : K;
+            out = ws_kn;
+        } else {
+            const int rt = launch_transpose(b, ws_kn, N, K, epi->ld_b ? epi->ld_b : K, N, 2, st);
+            if (rt != SDROP_OK) return rt;
+            b = ws_kn;
+        }
+    }
     GemmParams P = base_params(OP, a, b, mask, out, M, K, N, BM, BK, p, out_dtype, L);
     if (epi) {
         if (epi->ld_a) P.lda = epi->ld_a * 2;
-        if (epi->ld_b) P.ldb = epi->ld_b * 2;
-        if (epi->ld_out) P.ldc = epi->ld_out * (out_dtype == SDROP_F32 ? 4 : 2);
+        if (epi->ld_b && !(w_nk && OP != DW)) P.ldb = epi->ld_b * 2;
+        if (epi->ld_out && !(w_nk && OP == DW)) P.ldc = epi->ld_out * (out_dtype == SDROP_F32 ? 4 : 2);
         if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
         P.bias = epi->bias;
         P.aux = static_cast<const char *>(epi->relu_mask);
         P.act = epi->act;
         P.gate_mode = epi->gate_mode;
     }
-    if (out2) {
-        if (reinterpret_cast<uintptr_t>(out2) % 16) return SDROP_EALIGN;
-        P.C2 = static_cast<char *>(out2);
-    }
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (out2) P.C2 = static_cast<char *>(out2);
     if constexpr (OP == DW) {
         P.splits = dw_splits(M, N, BM, BK, K);
         if (P.splits > 1) {
@@ -278,24 +340,25 @@ int run(const void *a, const void *b, const void *mask, void *out,
             P.scale = 1.0f;
             const int rc1 = (dtype == SDROP_F16) ? dispatch_typed<F16>(OP, true, P, st) : dispatch_typed<BF16>(OP, true, P, st);
             if (rc1 != SDROP_OK) return rc1;
-            return launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out, P);
+            const int rc2 = launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out, P);
+            if (rc2 != SDROP_OK || !w_nk) return rc2;
+            return launch_transpose(out, final_out, K, N, N, final_ld, (int)esz_out, st);
         }
     }
     const bool o32 = out_dtype == SDROP_F32;
-    return dtype == SDROP_F16 ? dispatch_typed<F16>(OP, o32, P, st) : dispatch_typed<BF16>(OP, o32, P, st);
+    const int rcg = dtype == SDROP_F16 ? dispatch_typed<F16>(OP, o32, P, st) : dispatch_typed<BF16>(OP, o32, P, st);
+    if (rcg != SDROP_OK || !(w_nk && OP == DW)) return rcg;
+    return launch_transpose(out, final_out, K, N, N, final_ld, (int)esz_out, st);
 }
 
 // The mask and the forward product in one launch (fwd_seeded_kernel) where the block grid is small enough for every
-// workgroup to draw it: at most 128 block rows and 64 block columns, and at most 64 ballots of draws per workgroup
-// (8 per wavefront, about a microsecond).  Anything else is sdrop_mask followed by sdrop_fwd.
+// workgroup to draw it and keep it in registers: at most 128 block rows and 64 block columns (a workgroup draws 512
+// blocks in 0.11 us, so the largest such grid costs it under 2 us).  Anything else is sdrop_mask followed by sdrop_fwd.
 int g_fwd_seeded = 1;
 
 bool fwd_seeded_applies(const sdrop_mask_layout_t &L)
 {
-    if (!g_fwd_seeded || L.MB > 128 || L.KB > 64) return false;
-    int64_t kbp = 1;
-    while (kbp < L.KB) kbp <<= 1;
-    return L.MB * kbp <= 4096;
+    return g_fwd_seeded && L.MB <= 128 && L.KB <= 64;
 }
 
 int run_fwd_seeded(const void *x, const void *w, void *mask, size_t mask_bytes, void *y,
@@ -328,14 +391,22 @@ int run_fwd_seeded(const void *x, const void *w, void *mask, size_t mask_bytes, 
 // blocks, N a multiple of 256); anything else is the two calls in turn
 int g_bwd_fused = 1;
 
+// ld: null (contiguous), or the leading dimensions of dY, W, X, dX, dW in elements (0 = contiguous)
 int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void *dx, void *dw,
             int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
-            int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
+            int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream, const int64_t *ld = nullptr)
 {
     // every argument check of both calls before anything is enqueued
     int rc = check_gemm_args(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype);
     if (rc == SDROP_OK) rc = check_gemm_args(x, dy, mask, dw, M, K, N, BM, BK, p, dtype, out_dtype);
     if (rc != SDROP_OK) return rc;
+    int64_t lds[5] = {N, N, K, K, N};                    // dY[M,N], W[K,N], X[M,K], dX[M,K], dW[K,N]
+    if (ld) {
+        for (int i = 0; i < 5; ++i) {
+            if (ld[i] != 0 && (ld[i] < lds[i] || ld[i] % 8 || ld[i] > (int64_t(1) << 24))) return SDROP_ESHAPE;
+            if (ld[i]) lds[i] = ld[i];
+        }
+    }
     const size_t ws_need = sdrop_workspace_bytes(SDROP_OP_BWD_DW, M, K, N, BM, BK, dtype, out_dtype);
     if (ws_bytes < ws_need || (ws_need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
     sdrop_mask_layout_t L;
@@ -345,6 +416,11 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
 
     GemmParams Pdx = base_params(DX, dy, w, mask, dx, M, K, N, BM, BK, p, out_dtype, L);
     GemmParams Pdw = base_params(DW, x, dy, mask, dw, M, K, N, BM, BK, p, out_dtype, L);
+    {
+        const int64_t esz_out = out_dtype == SDROP_F32 ? 4 : 2;
+        Pdx.lda = lds[0] * 2; Pdx.ldb = lds[1] * 2; Pdx.ldc = lds[3] * esz_out;
+        Pdw.lda = lds[2] * 2; Pdw.ldb = lds[0] * 2; Pdw.ldc = lds[4] * esz_out;
+    }
     const DxPlan plan = dx_plan(Pdx);
     Pdw.splits = dw_splits(M, N, BM, BK, K);
     // Which single launch applies, if any (all need N to be a multiple of 256, so that neither product has a ragged edge):
@@ -370,12 +446,17 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
                                           : bwd_fused_typed<BF16>(form, plan.TN, o32, split, Pdx, Pdw, n_dx, st);
         if (rf != -1) {     // -1: the device does not grant the LDS; fall through to the two calls
             if (rf != SDROP_OK || !split) return rf;
-            return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, N, Pdw);
+            return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, lds[4], Pdw);
         }
     }
-    rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream);
+    sdrop_epilogue_t e;
+    e.scale_mode = SDROP_SCALE_DROPOUT; e.act = SDROP_ACT_NONE; e.bias = nullptr; e.relu_mask = nullptr;
+    e.gate_mode = SDROP_GATE_RELU; e.w_layout = SDROP_W_KN;
+    e.ld_a = lds[0]; e.ld_b = lds[1]; e.ld_out = lds[3];
+    rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, ld ? &e : nullptr);
     if (rc != SDROP_OK) return rc;
-    return run<DW>(x, dy, mask, dw, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
+    e.ld_a = lds[2]; e.ld_b = lds[0]; e.ld_out = lds[4];
+    return run<DW>(x, dy, mask, dw, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, ld ? &e : nullptr);
 }
 
 }  // namespace
@@ -457,8 +538,16 @@ size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, in
     (void)dtype; (void)out_dtype;
     if (op != SDROP_OP_BWD_DW) return 0;
     if (M <= 0 || K <= 0 || N <= 0 || !sdrop::block_size_ok(BM) || !sdrop::block_size_ok(BK) || M % BM || K % BK) return 0;
-    const int splits = sdrop::dw_splits(M, N, BM, BK, K);
-    return splits > 1 ? (size_t)splits * (size_t)K * (size_t)N * sizeof(float) : 0;
+    return sdrop::ws_planes_bytes(op, M, K, N, BM, BK);
+}
+
+size_t sdrop_workspace_bytes_ex(int op, int64_t M, int64_t K, int64_t N, int BM, int BK,
+                                int dtype, int out_dtype, const sdrop_epilogue_t *epi)
+{
+    (void)dtype;
+    if (op != SDROP_OP_FWD && op != SDROP_OP_BWD_DX && op != SDROP_OP_BWD_DW) return 0;
+    if (M <= 0 || K <= 0 || N <= 0 || !sdrop::block_size_ok(BM) || !sdrop::block_size_ok(BK) || M % BM || K % BK) return 0;
+    return sdrop::ws_total_bytes(op, M, K, N, BM, BK, out_dtype, epi && epi->w_layout == SDROP_W_NK);
 }
 
 int sdrop_fwd(const void *X, const void *W, const void *mask, void *Y,
@@ -513,6 +602,15 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
     return sdrop::run_bwd(dY, W, X, mask, dX, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream);
 }
 
+int sdrop_bwd_ex(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,
+                 int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
+                 int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                 int64_t ld_dy, int64_t ld_w, int64_t ld_x, int64_t ld_dx, int64_t ld_dw)
+{
+    const int64_t ld[5] = {ld_dy, ld_w, ld_x, ld_dx, ld_dw};
+    return sdrop::run_bwd(dY, W, X, mask, dX, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, ld);
+}
+
 int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,
                  int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
@@ -548,6 +646,22 @@ int sdrop_producer(const void *H, const void *W0, const float *bias, const void 
     epi.relu_mask = nullptr;
     epi.ld_a = epi.ld_b = epi.ld_out = 0;
     epi.gate_mode = SDROP_GATE_RELU;
+    epi.w_layout = SDROP_W_KN;
+    return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi, Z);
+}
+
+int sdrop_producer_ex(const void *H, const void *W0, const float *bias, const void *mask, void *X, void *Z,
+                      int64_t M, int64_t N0, int64_t K, int BM, int BK, double p, int act,
+                      int dtype, int out_dtype, void *stream, int64_t ld_h, int64_t ld_w0, int64_t ld_out)
+{
+    sdrop_epilogue_t epi;
+    epi.scale_mode = SDROP_SCALE_ONE;
+    epi.act = act;
+    epi.bias = bias;
+    epi.relu_mask = nullptr;
+    epi.ld_a = ld_h; epi.ld_b = ld_w0; epi.ld_out = ld_out;
+    epi.gate_mode = SDROP_GATE_RELU;
+    epi.w_layout = SDROP_W_KN;
     return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi, Z);
 }
 

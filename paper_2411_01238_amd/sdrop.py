@@ -24,12 +24,14 @@ MASK_NNZ_OFFSET = 36
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_mask_bits", "sdrop_workspace_bytes",
            "sdrop_fwd", "sdrop_fwd_seeded", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
-           "sdrop_bwd", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_producer",
+           "sdrop_bwd", "sdrop_bwd_ex", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_workspace_bytes_ex",
+           "sdrop_producer", "sdrop_producer_ex",
            "sdrop_bias_grad_workspace_bytes", "sdrop_bias_grad")
 
 SCALE_DROPOUT, SCALE_ONE = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF = 0, 1, 2, 3
 GATE_RELU, GATE_GELU_TANH, GATE_GELU_ERF = 0, 1, 2
+W_KN, W_NK = 0, 1
 
 _DTYPES = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 
@@ -52,7 +54,7 @@ class Epilogue(ctypes.Structure):
     _fields_ = [("scale_mode", ctypes.c_int32), ("act", ctypes.c_int32),
                 ("bias", ctypes.c_void_p), ("relu_mask", ctypes.c_void_p),
                 ("ld_a", ctypes.c_int64), ("ld_b", ctypes.c_int64), ("ld_out", ctypes.c_int64),
-                ("gate_mode", ctypes.c_int32)]
+                ("gate_mode", ctypes.c_int32), ("w_layout", ctypes.c_int32)]
 
 
 _lib = None
@@ -102,6 +104,12 @@ def lib():
             f.restype = ci
         L.sdrop_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
         L.sdrop_bwd.restype = ci
+        L.sdrop_bwd_ex.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp, i64, i64, i64, i64, i64]
+        L.sdrop_bwd_ex.restype = ci
+        L.sdrop_workspace_bytes_ex.argtypes = [ci, i64, i64, i64, ci, ci, ci, ci, ctypes.POINTER(Epilogue)]
+        L.sdrop_workspace_bytes_ex.restype = sz
+        L.sdrop_producer_ex.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, ci, vp, i64, i64, i64]
+        L.sdrop_producer_ex.restype = ci
         L.sdrop_producer.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, ci, vp]
         L.sdrop_producer.restype = ci
         L.sdrop_bias_grad_workspace_bytes.argtypes = [i64, i64, ci, ci]
@@ -273,10 +281,10 @@ def workspace_bytes(op, M, K, N, BM, BK, dtype, out_dtype):
     return v
 
 
-def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype, gate_mode=GATE_RELU):
+def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype, gate_mode=GATE_RELU, w_layout=W_KN):
     """Marshals the tail arguments into the C struct (leading dimensions are filled in by _gemm)."""
     e = Epilogue()
-    e.scale_mode, e.act, e.gate_mode = int(scale_mode), int(act), int(gate_mode)
+    e.scale_mode, e.act, e.gate_mode, e.w_layout = int(scale_mode), int(act), int(gate_mode), int(w_layout)
     e.bias = e.relu_mask = None
     e.ld_a = e.ld_b = e.ld_out = 0
     if bias is not None:
@@ -302,7 +310,10 @@ def _gemm(name, op, a, b, mask, out_shape, M, K, N, out_dtype, out, ws, epi=None
         raise ValueError("out has the wrong shape or dtype")
     if dtype not in (torch.float16, torch.bfloat16) or out_dtype not in _DTYPES:
         raise SdropError(EDTYPE, name)
-    need = workspace_bytes(op, M, K, N, mask.BM, mask.BK, dtype, out_dtype)
+    if epi is not None and epi.w_layout != W_KN:
+        need = int(lib().sdrop_workspace_bytes_ex(op, M, K, N, mask.BM, mask.BK, _DTYPES[dtype], _DTYPES[out_dtype], ctypes.byref(epi)))
+    else:
+        need = workspace_bytes(op, M, K, N, mask.BM, mask.BK, dtype, out_dtype)
     if ws is None and need:
         ws = torch.empty(need, dtype=torch.uint8, device=a.device)
     ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
@@ -426,43 +437,53 @@ def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None)
         ws = torch.empty(need, dtype=torch.uint8, device=dY.device)
     ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
     ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
-    rc = lib().sdrop_bwd(_dev(dY, "dY"), _dev(W, "W"), _dev(X, "X"), _dev(mask.buf, "mask"),
-                         _dev(outs[0], "dX"), _dev(outs[1], "dW"), M, K, N, mask.BM, mask.BK, mask.p,
-                         _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream())
+    mats = [_mat(t, n) for t, n in ((dY, "dY"), (W, "W"), (X, "X"), (outs[0], "dX"), (outs[1], "dW"))]
+    ptrs = [m[0] for m in mats]
+    lds = [m[1] for m in mats]
+    if lds == [N, N, K, K, N]:
+        rc = lib().sdrop_bwd(ptrs[0], ptrs[1], ptrs[2], _dev(mask.buf, "mask"), ptrs[3], ptrs[4], M, K, N, mask.BM, mask.BK, mask.p,
+                             _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream())
+    else:
+        # row-strided operands or outputs (column ranges of wider matrices)
+        rc = lib().sdrop_bwd_ex(ptrs[0], ptrs[1], ptrs[2], _dev(mask.buf, "mask"), ptrs[3], ptrs[4], M, K, N, mask.BM, mask.BK, mask.p,
+                                _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream(), *lds)
     _check(rc, "sdrop_bwd")
     return outs[0], outs[1]
 
 
 def sdrop_fwd_ex(X, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
-                 out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU):
-    """eq. (1) with an element-wise tail: Y = [relu_mask > 0] act(scale (X . m') W + bias)."""
+                 out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU, w_layout=W_KN):
+    """eq. (1) with an element-wise tail: Y = [relu_mask > 0] act(scale (X . m') W + bias).
+    w_layout=W_NK: W is given as [N, K] (one row per output feature)."""
     M, K = X.shape
-    K2, N = W.shape
+    K2, N = W.shape if w_layout == W_KN else (W.shape[1], W.shape[0])
     if K2 != K or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_fwd_ex")
-    epi = _epilogue(scale_mode, act, bias, relu_mask, N, (M, N), X.dtype, gate_mode)
+    epi = _epilogue(scale_mode, act, bias, relu_mask, N, (M, N), X.dtype, gate_mode, w_layout)
     return _gemm("sdrop_fwd_ex", OP_FWD, X, W, mask, (M, N), M, K, N, out_dtype, out, ws, epi)
 
 
 def sdrop_bwd_dx_ex(dY, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
-                    out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU):
-    """eq. (2) with an element-wise tail on the kept blocks; dropped blocks are +0."""
+                    out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU, w_layout=W_KN):
+    """eq. (2) with an element-wise tail on the kept blocks; dropped blocks are +0.
+    w_layout=W_NK: W is given as [N, K]."""
     M, N = dY.shape
-    K, N2 = W.shape
+    K, N2 = W.shape if w_layout == W_KN else (W.shape[1], W.shape[0])
     if N2 != N or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dx_ex")
-    epi = _epilogue(scale_mode, act, bias, relu_mask, K, (M, K), dY.dtype, gate_mode)
+    epi = _epilogue(scale_mode, act, bias, relu_mask, K, (M, K), dY.dtype, gate_mode, w_layout)
     return _gemm("sdrop_bwd_dx_ex", OP_BWD_DX, dY, W, mask, (M, K), M, K, N, out_dtype, out, ws, epi)
 
 
-def sdrop_bwd_dw_ex(X, dY, mask, scale_mode=SCALE_DROPOUT, out_dtype=None, out=None, ws=None):
-    """eq. (3) with the scale chosen by scale_mode."""
+def sdrop_bwd_dw_ex(X, dY, mask, scale_mode=SCALE_DROPOUT, out_dtype=None, out=None, ws=None, w_layout=W_KN):
+    """eq. (3) with the scale chosen by scale_mode.  w_layout=W_NK: the gradient comes as [N, K]."""
     M, K = X.shape
     M2, N = dY.shape
     if M2 != M or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dw_ex")
-    epi = _epilogue(scale_mode, ACT_NONE, None, None, N, (K, N), X.dtype)
-    return _gemm("sdrop_bwd_dw_ex", OP_BWD_DW, X, dY, mask, (K, N), M, K, N, out_dtype, out, ws, epi)
+    out_shape = (K, N) if w_layout == W_KN else (N, K)
+    epi = _epilogue(scale_mode, ACT_NONE, None, None, N, out_shape, X.dtype, w_layout=w_layout)
+    return _gemm("sdrop_bwd_dw_ex", OP_BWD_DW, X, dY, mask, out_shape, M, K, N, out_dtype, out, ws, epi)
 
 
 def sdrop_producer(H, W0, bias, mask, act=ACT_NONE, out_dtype=None, out=None, preact=None):
@@ -491,12 +512,18 @@ def sdrop_producer(H, W0, bias, mask, act=ACT_NONE, out_dtype=None, out=None, pr
         preact = torch.zeros((M, K), dtype=out_dtype, device=H.device)
     if preact is not None and (tuple(preact.shape) != (M, K) or preact.dtype != out_dtype):
         raise ValueError("preact has the wrong shape or dtype")
-    rc = lib().sdrop_producer(_dev(H, "H"), _dev(W0, "W0"),
-                              _dev(bias, "bias") if bias is not None else ctypes.c_void_p(0),
-                              _dev(mask.buf, "mask"), _dev(out, "out"),
-                              _dev(preact, "preact") if preact is not None else ctypes.c_void_p(0),
-                              M, N0, K, mask.BM, mask.BK, mask.p,
-                              int(act), _DTYPES[dtype], _DTYPES[out_dtype], _stream())
+    (ph, ldh), (pw, ldw), (po, ldo) = _mat(H, "H"), _mat(W0, "W0"), _mat(out, "out")
+    pz = ctypes.c_void_p(0)
+    if preact is not None:
+        pz, ldz = _mat(preact, "preact")
+        if ldz != ldo:
+            raise ValueError("preact must have the output's leading dimension")
+    args = (ph, pw, _dev(bias, "bias") if bias is not None else ctypes.c_void_p(0), _dev(mask.buf, "mask"), po, pz,
+            M, N0, K, mask.BM, mask.BK, mask.p, int(act), _DTYPES[dtype], _DTYPES[out_dtype], _stream())
+    if (ldh, ldw, ldo) == (N0, N0, K):
+        rc = lib().sdrop_producer(*args)
+    else:
+        rc = lib().sdrop_producer_ex(*args, ldh, ldw, ldo)
     _check(rc, "sdrop_producer")
     return out if preact is None else (out, preact)
 

@@ -237,3 +237,43 @@ def test_bias_gradient_arguments_are_checked_on_the_host():
     # at most one part per block row; none for a bad shape
     assert L.sdrop_bias_grad_workspace_bytes(128, 1024, 128, 128) == 0
     assert L.sdrop_bias_grad_workspace_bytes(100, 1024, 128, 128) == 0
+
+
+def test_new_entry_points_check_their_arguments_on_the_host():
+    L = sdrop.lib()
+    buf = ctypes.create_string_buffer(1 << 16)
+    addr = (ctypes.addressof(buf) + 15) // 16 * 16
+    p = ctypes.c_void_p(addr)
+    null = ctypes.c_void_p(0)
+    # sdrop_bwd_ex: leading dimensions of dY, W, X, dX, dW
+    ok = (p, p, p, p, p, p, 2048, 256, 264, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, 0) == sdrop.EWORKSPACE          # as sdrop_bwd: the split needs a workspace
+    assert L.sdrop_bwd_ex(*ok, 256, 0, 0, 0, 0) == sdrop.ESHAPE            # dY has 264 columns
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 260, 0, 0) == sdrop.ESHAPE            # not a multiple of 8
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, (1 << 24) + 8) == sdrop.ESHAPE
+    # sdrop_producer_ex
+    okp = (p, p, null, p, p, null, 256, 256, 256, 64, 64, 0.5, sdrop.ACT_RELU, sdrop.F16, sdrop.F16, null)
+    assert L.sdrop_producer_ex(*okp, 128, 0, 0) == sdrop.ESHAPE
+    assert L.sdrop_producer_ex(*okp, 0, 0, 260) == sdrop.ESHAPE
+    # the weight's layout: bad enum, the larger workspace
+    e = sdrop.Epilogue()
+    e.scale_mode, e.act, e.gate_mode, e.w_layout = 0, 0, 0, 7
+    okf = (p, p, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)
+    assert L.sdrop_fwd_ex(*okf, ctypes.byref(e)) == sdrop.EINVAL
+    e.w_layout = sdrop.W_NK
+    assert L.sdrop_fwd_ex(*okf, ctypes.byref(e)) == sdrop.EWORKSPACE
+    assert L.sdrop_workspace_bytes_ex(sdrop.OP_FWD, 256, 256, 512, 64, 64, sdrop.F16, sdrop.F16, ctypes.byref(e)) == 256 * 512 * 2
+    assert L.sdrop_workspace_bytes_ex(sdrop.OP_BWD_DX, 256, 256, 512, 64, 64, sdrop.F16, sdrop.F32, ctypes.byref(e)) == 256 * 512 * 2
+    planes = L.sdrop_workspace_bytes(sdrop.OP_BWD_DW, 2048, 256, 264, 64, 64, sdrop.F16, sdrop.F32)
+    assert L.sdrop_workspace_bytes_ex(sdrop.OP_BWD_DW, 2048, 256, 264, 64, 64, sdrop.F16, sdrop.F32, ctypes.byref(e)) == planes + 256 * 264 * 4
+    assert L.sdrop_workspace_bytes_ex(sdrop.OP_BWD_DW, 2048, 256, 264, 64, 64, sdrop.F16, sdrop.F32, None) == planes
+    # sdrop_fwd_seeded
+    oks = (p, p, p, 1 << 16, p, 256, 256, 256, 64, 64, 0.5, 1, 2, sdrop.F16, sdrop.F16, null)
+    assert L.sdrop_fwd_seeded(*(oks[:2] + (null,) + oks[3:])) == sdrop.EINVAL
+    assert L.sdrop_fwd_seeded(*(oks[:3] + (64,) + oks[4:])) == sdrop.EWORKSPACE
+    assert L.sdrop_fwd_seeded(*(oks[:10] + (1.5,) + oks[11:])) == sdrop.EINVAL
+    assert L.sdrop_fwd_seeded(*(oks[:7] + (250,) + oks[8:])) == sdrop.ESHAPE
+    # sdrop_bwd_dw_static: argument errors as sdrop_bwd_dw
+    okd = (p, p, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null)
+    assert L.sdrop_bwd_dw_static(*((null,) + okd[1:])) == sdrop.EINVAL
+    assert L.sdrop_bwd_dw_static(*(okd[:6] + (250,) + okd[7:])) == sdrop.ESHAPE

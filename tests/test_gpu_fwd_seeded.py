@@ -99,9 +99,10 @@ def test_seeded_forward_on_the_workloads(name, p, layer):
           out_dtypes=(None,))
 
 
-def test_grids_too_large_for_one_workgroup_take_the_two_launches():
-    # 128 x 48 blocks (the FFN workload's grid) and a 256-row grid: same results through the fallback
-    for (M, K, N, BM, BK) in ((16384, 3072, 256, 128, 64), (16384, 512, 256, 64, 128)):
+def test_largest_grid_and_grids_beyond_it():
+    # 128 x 48 blocks (the FFN workload's grid, one launch); 128 x 64 (the largest a workgroup draws); a 256-row grid
+    # and a 65-column grid (the two launches in turn): the same results
+    for (M, K, N, BM, BK) in ((16384, 3072, 256, 128, 64), (8192, 4096, 256, 64, 64), (16384, 512, 256, 64, 128), (512, 8320, 256, 128, 128)):
         X, W, _ = make_custom(M, K, N, "bf16", seed=21)
         _case(X, W, BM, BK, 0.3, 11, 0, "fallback %dx%dx%d" % (M, K, N), oracle_product=False, out_dtypes=(None,))
 
