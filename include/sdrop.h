@@ -312,6 +312,9 @@ int sdrop_bwd_ex(const void *dY, const void *W, const void *X, const void *mask,
  *               SDROP_GATE_GELU_ERF: the output is multiplied by the derivative of that GELU at
  *               relu_mask, which then holds the GELU's INPUT (the backward of a GELU; the second
  *               output of sdrop_producer is that input)
+ *   kept_fraction   0, or the share of kept blocks the caller expects the mask to have, in (0,1].  Used only to choose
+ *               tile shapes and kernel forms (never the result): the library plans by 1 - p, which a mask built by
+ *               sdrop_mask_from_bits from the caller's own bits need not have.  Outside [0,1]: SDROP_EINVAL.
  *   ld_a, ld_b, ld_out   leading dimensions, in elements, of the first matrix argument, the
  *               second one and the output (row r starts r * ld elements after the pointer);
  *               0 = contiguous.  A leading dimension must be at least the number of columns, a
@@ -342,6 +345,7 @@ typedef struct sdrop_epilogue {
     int64_t ld_a, ld_b, ld_out;
     int32_t gate_mode;
     int32_t w_layout;
+    double kept_fraction;
 } sdrop_epilogue_t;
 
 /* sdrop_workspace_bytes for an _ex call with this tail (epi may be NULL: then exactly sdrop_workspace_bytes). */

@@ -281,6 +281,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
         if (epi->act < SDROP_ACT_NONE || epi->act > SDROP_ACT_GELU_ERF) return SDROP_EINVAL;
         if (epi->gate_mode < SDROP_GATE_RELU || epi->gate_mode > SDROP_GATE_GELU_ERF) return SDROP_EINVAL;
         if (epi->w_layout != SDROP_W_KN && epi->w_layout != SDROP_W_NK) return SDROP_EINVAL;
+        if (!(epi->kept_fraction >= 0.0 && epi->kept_fraction <= 1.0)) return SDROP_EINVAL;
         // the gradient of the weights takes a scale only
         if (OP == DW && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask)) return SDROP_EINVAL;
         if ((reinterpret_cast<uintptr_t>(epi->bias) | reinterpret_cast<uintptr_t>(epi->relu_mask)) % 16) return SDROP_EALIGN;
@@ -323,6 +324,9 @@ int run(const void *a, const void *b, const void *mask, void *out,
         if (epi->ld_b && !(w_nk && OP != DW)) P.ldb = epi->ld_b * 2;
         if (epi->ld_out && !(w_nk && OP == DW)) P.ldc = epi->ld_out * (out_dtype == SDROP_F32 ? 4 : 2);
         if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
+        // the kernel choice goes by the expected share of kept blocks: the caller's figure where given (a mask built
+        // from the caller's own bits need not have the density 1 - p), else 1 - p
+        if (epi->kept_fraction > 0.0) P.p = 1.0 - (epi->kept_fraction < 1.0 ? epi->kept_fraction : 1.0);
         P.bias = epi->bias;
         P.aux = static_cast<const char *>(epi->relu_mask);
         P.act = epi->act;
@@ -451,7 +455,7 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
     }
     sdrop_epilogue_t e;
     e.scale_mode = SDROP_SCALE_DROPOUT; e.act = SDROP_ACT_NONE; e.bias = nullptr; e.relu_mask = nullptr;
-    e.gate_mode = SDROP_GATE_RELU; e.w_layout = SDROP_W_KN;
+    e.gate_mode = SDROP_GATE_RELU; e.w_layout = SDROP_W_KN; e.kept_fraction = 0.0;
     e.ld_a = lds[0]; e.ld_b = lds[1]; e.ld_out = lds[3];
     rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, ld ? &e : nullptr);
     if (rc != SDROP_OK) return rc;
@@ -647,6 +651,7 @@ int sdrop_producer(const void *H, const void *W0, const float *bias, const void 
     epi.ld_a = epi.ld_b = epi.ld_out = 0;
     epi.gate_mode = SDROP_GATE_RELU;
     epi.w_layout = SDROP_W_KN;
+    epi.kept_fraction = 0.0;
     return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi, Z);
 }
 
@@ -662,6 +667,7 @@ int sdrop_producer_ex(const void *H, const void *W0, const float *bias, const vo
     epi.ld_a = ld_h; epi.ld_b = ld_w0; epi.ld_out = ld_out;
     epi.gate_mode = SDROP_GATE_RELU;
     epi.w_layout = SDROP_W_KN;
+    epi.kept_fraction = 0.0;
     return sdrop::run<sdrop::DX>(H, W0, mask, X, M, K, N0, BM, BK, p, dtype, out_dtype, nullptr, 0, stream, &epi, Z);
 }
 

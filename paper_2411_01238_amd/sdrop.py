@@ -54,7 +54,7 @@ class Epilogue(ctypes.Structure):
     _fields_ = [("scale_mode", ctypes.c_int32), ("act", ctypes.c_int32),
                 ("bias", ctypes.c_void_p), ("relu_mask", ctypes.c_void_p),
                 ("ld_a", ctypes.c_int64), ("ld_b", ctypes.c_int64), ("ld_out", ctypes.c_int64),
-                ("gate_mode", ctypes.c_int32), ("w_layout", ctypes.c_int32)]
+                ("gate_mode", ctypes.c_int32), ("w_layout", ctypes.c_int32), ("kept_fraction", ctypes.c_double)]
 
 
 _lib = None
@@ -281,10 +281,11 @@ def workspace_bytes(op, M, K, N, BM, BK, dtype, out_dtype):
     return v
 
 
-def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype, gate_mode=GATE_RELU, w_layout=W_KN):
+def _epilogue(scale_mode, act, bias, relu_mask, ncols, out_shape, dtype, gate_mode=GATE_RELU, w_layout=W_KN, kept_fraction=0.0):
     """Marshals the tail arguments into the C struct (leading dimensions are filled in by _gemm)."""
     e = Epilogue()
     e.scale_mode, e.act, e.gate_mode, e.w_layout = int(scale_mode), int(act), int(gate_mode), int(w_layout)
+    e.kept_fraction = float(kept_fraction)
     e.bias = e.relu_mask = None
     e.ld_a = e.ld_b = e.ld_out = 0
     if bias is not None:
@@ -452,37 +453,37 @@ def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None)
 
 
 def sdrop_fwd_ex(X, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
-                 out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU, w_layout=W_KN):
+                 out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU, w_layout=W_KN, kept_fraction=0.0):
     """eq. (1) with an element-wise tail: Y = [relu_mask > 0] act(scale (X . m') W + bias).
     w_layout=W_NK: W is given as [N, K] (one row per output feature)."""
     M, K = X.shape
     K2, N = W.shape if w_layout == W_KN else (W.shape[1], W.shape[0])
     if K2 != K or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_fwd_ex")
-    epi = _epilogue(scale_mode, act, bias, relu_mask, N, (M, N), X.dtype, gate_mode, w_layout)
+    epi = _epilogue(scale_mode, act, bias, relu_mask, N, (M, N), X.dtype, gate_mode, w_layout, kept_fraction)
     return _gemm("sdrop_fwd_ex", OP_FWD, X, W, mask, (M, N), M, K, N, out_dtype, out, ws, epi)
 
 
 def sdrop_bwd_dx_ex(dY, W, mask, scale_mode=SCALE_DROPOUT, act=ACT_NONE, bias=None, relu_mask=None,
-                    out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU, w_layout=W_KN):
+                    out_dtype=None, out=None, ws=None, gate_mode=GATE_RELU, w_layout=W_KN, kept_fraction=0.0):
     """eq. (2) with an element-wise tail on the kept blocks; dropped blocks are +0.
     w_layout=W_NK: W is given as [N, K]."""
     M, N = dY.shape
     K, N2 = W.shape if w_layout == W_KN else (W.shape[1], W.shape[0])
     if N2 != N or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dx_ex")
-    epi = _epilogue(scale_mode, act, bias, relu_mask, K, (M, K), dY.dtype, gate_mode, w_layout)
+    epi = _epilogue(scale_mode, act, bias, relu_mask, K, (M, K), dY.dtype, gate_mode, w_layout, kept_fraction)
     return _gemm("sdrop_bwd_dx_ex", OP_BWD_DX, dY, W, mask, (M, K), M, K, N, out_dtype, out, ws, epi)
 
 
-def sdrop_bwd_dw_ex(X, dY, mask, scale_mode=SCALE_DROPOUT, out_dtype=None, out=None, ws=None, w_layout=W_KN):
+def sdrop_bwd_dw_ex(X, dY, mask, scale_mode=SCALE_DROPOUT, out_dtype=None, out=None, ws=None, w_layout=W_KN, kept_fraction=0.0):
     """eq. (3) with the scale chosen by scale_mode.  w_layout=W_NK: the gradient comes as [N, K]."""
     M, K = X.shape
     M2, N = dY.shape
     if M2 != M or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd_dw_ex")
     out_shape = (K, N) if w_layout == W_KN else (N, K)
-    epi = _epilogue(scale_mode, ACT_NONE, None, None, N, out_shape, X.dtype, w_layout=w_layout)
+    epi = _epilogue(scale_mode, ACT_NONE, None, None, N, out_shape, X.dtype, w_layout=w_layout, kept_fraction=kept_fraction)
     return _gemm("sdrop_bwd_dw_ex", OP_BWD_DW, X, dY, mask, out_shape, M, K, N, out_dtype, out, ws, epi)
 
 

@@ -260,7 +260,9 @@ def test_new_entry_points_check_their_arguments_on_the_host():
     e.scale_mode, e.act, e.gate_mode, e.w_layout = 0, 0, 0, 7
     okf = (p, p, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)
     assert L.sdrop_fwd_ex(*okf, ctypes.byref(e)) == sdrop.EINVAL
-    e.w_layout = sdrop.W_NK
+    e.w_layout, e.kept_fraction = sdrop.W_KN, 1.5
+    assert L.sdrop_fwd_ex(*okf, ctypes.byref(e)) == sdrop.EINVAL
+    e.w_layout, e.kept_fraction = sdrop.W_NK, 0.25
     assert L.sdrop_fwd_ex(*okf, ctypes.byref(e)) == sdrop.EWORKSPACE
     assert L.sdrop_workspace_bytes_ex(sdrop.OP_FWD, 256, 256, 512, 64, 64, sdrop.F16, sdrop.F16, ctypes.byref(e)) == 256 * 512 * 2
     assert L.sdrop_workspace_bytes_ex(sdrop.OP_BWD_DX, 256, 256, 512, 64, 64, sdrop.F16, sdrop.F32, ctypes.byref(e)) == 256 * 512 * 2

@@ -215,3 +215,31 @@ def test_gelu_gates_and_preactivation_output(M, K, N, BM, BK, dtype, p, seed):
             assert_close(got, zr, "producer pre-activation" + tag)
         else:
             assert_bf16_rounding_of(np.where(kept, zd, 0.0), zr, "producer pre-activation bf16" + tag)
+
+
+def test_kept_fraction_hint_changes_the_plan_not_the_result():
+    # a mask built from the caller's bits with a density far from 1 - p: with and without the planning hint the
+    # products are the oracle's, and equal to each other bit for bit
+    M, K, N, BM, BK, p = 4096, 2048, 512, 128, 128, 0.5
+    print("kept_fraction hint", flush=True)
+    X, W, dY = make_custom(M, K, N, "bf16", seed=41)
+    rng = np.random.default_rng(41)
+    keep = (rng.random((M // BM, K // BK)) < 0.06).astype(np.uint8)       # 6 % kept although p says 50 %
+    keep[0, 0] = 1
+    bits = torch.from_numpy(orc.pack_bits(keep).view(np.int64)).cuda()
+    m = sdrop.sdrop_mask_from_bits(M, K, BM, BK, p, bits)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    frac = float(keep.mean())
+    for od in (torch.float32, torch.bfloat16):
+        plain = (sdrop.sdrop_fwd(Xg, Wg, m, out_dtype=od), sdrop.sdrop_bwd_dx(dYg, Wg, m, out_dtype=od),
+                 sdrop.sdrop_bwd_dw(Xg, dYg, m, out_dtype=od))
+        hinted = (sdrop.sdrop_fwd_ex(Xg, Wg, m, out_dtype=od, kept_fraction=frac),
+                  sdrop.sdrop_bwd_dx_ex(dYg, Wg, m, out_dtype=od, kept_fraction=frac),
+                  sdrop.sdrop_bwd_dw_ex(Xg, dYg, m, out_dtype=od, kept_fraction=frac))
+        torch.cuda.synchronize()
+        for a, b in zip(plain, hinted):
+            assert torch.equal(a, b)
+        if od == torch.float32:
+            assert_close(f64(hinted[0]), orc.fwd(f64(X), f64(W), keep, BM, BK, p), "hinted Y")
+            assert_close(f64(hinted[1]), orc.bwd_dx(f64(dY), f64(W), keep, BM, BK, p), "hinted dX")
+            assert_close(f64(hinted[2]), orc.bwd_dw(f64(X), f64(dY), keep, BM, BK, p), "hinted dW")
