@@ -79,6 +79,18 @@ enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0, SDROP_TUNE_BWD_FUSED = 1, SDR
        SDROP_TUNE_FWD_SEEDED = 3 };
 int sdrop_set_tuning(int knob, int value);
 
+/*
+ * What the kernels have found wrong since the status word was last cleared.  Calls only enqueue work, so a condition
+ * that only the device can see cannot come back as a return code: a kernel that is handed a mask object that does
+ * not belong to its call (another shape or block size, not a mask object at all, or a mask drawn with a dropout
+ * probability other than the call's p) writes nothing and sets SDROP_STATUS_MASK_MISMATCH in a status word that
+ * lives in device memory (one per GPU).  sdrop_status copies that word to *flags_host, clears it if `clear` is
+ * non-zero, and waits for `stream` (so work enqueued on it before the call has reported).  SDROP_EINVAL for a null
+ * pointer.
+ */
+#define SDROP_STATUS_MASK_MISMATCH 1
+int sdrop_status(int *flags_host, int clear, void *stream);
+
 /* Text for an error code (static storage). */
 const char *sdrop_strerror(int code);
 
@@ -90,7 +102,9 @@ int sdrop_last_hip_error(void);
  * buffer of `total_bytes`; all offsets are in bytes from its start.  With
  * MB = M/BM, KB = K/BK and nnz = number of kept blocks:
  *
- *   header   at 0 (256 bytes): int64 M, K; int32 BM, BK, MB, KB, words_per_row, nnz; ...
+ *   header   at 0 (256 bytes): int64 M, K; int32 BM, BK, MB, KB, words_per_row, nnz; ...; for a mask that was
+ *            drawn also the p, seed and rng_stream it was drawn with (the kernels compare that p with the p of
+ *            the call that uses the mask)
  *            (nnz is the int32 at byte offset SDROP_MASK_NNZ_OFFSET)
  *   bits     uint64[MB][words_per_row]: block (i,j) is bit j%64 of word j/64 of
  *            row i, 1 = kept, unused high bits zero (the 64-bit packing of Section 3.4)
@@ -201,7 +215,10 @@ size_t sdrop_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int BM, in
  *                   for THIS call's shape (the kernels address the lists by the call's shape before
  *                   they have compared the header); a kernel that finds a different header writes
  *                   nothing
- *   p               the dropout probability the scale s is derived from
+ *   p               the dropout probability the scale s is derived from; for a mask made by sdrop_mask /
+ *                   sdrop_mask_split / sdrop_fwd_seeded it must be the p the mask was drawn with (a kernel
+ *                   that finds another p in the object treats it like a mask of another problem: it writes
+ *                   nothing, see sdrop_status); a mask built from the caller's bits goes with any p
  *   ws, ws_bytes    device workspace of at least sdrop_workspace_bytes(SDROP_OP_FWD, ...)
  *                   bytes (ws may be NULL when that is 0)
  */

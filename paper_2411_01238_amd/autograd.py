@@ -13,8 +13,8 @@ from . import sdrop
 class _SparseDropMatmul(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, w, p, BM, BK, seed, rng_stream):
-        m = sdrop.sdrop_mask(x.shape[0], x.shape[1], BM, BK, p, seed, rng_stream)
-        y = sdrop.sdrop_fwd(x, w, m)
+        # the mask and eq. (1) in one call (one launch for block grids up to 128 x 64); m serves the backward
+        y, m = sdrop.sdrop_fwd_seeded(x, w, BM, BK, p, seed, rng_stream)
         ctx.save_for_backward(x, w)
         ctx.mask = m
         return y

@@ -39,6 +39,8 @@ struct GemmParams {
     // keep threshold floor(p 2^32)
     uint32_t key0, key1, ctr2, ctr3;
     uint64_t threshold;
+    double p_call;      // the dropout probability of the call (compared with the one a drawn mask records)
+    int *status;        // the library's status word on this device, or null
 };
 
 namespace {

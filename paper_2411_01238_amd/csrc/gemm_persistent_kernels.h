@@ -308,7 +308,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     // inside the mask object whatever it holds), so that it costs no round trip of its own.
     const MaskHeader *H = P.mv.hdr;
     auto mask_ok = [&]() __attribute__((always_inline)) -> bool {
-        return H->magic == kMaskMagic && H->M == P.M && H->K == P.K && H->BM == P.BM && H->BK == P.BK;
+        return mask_header_ok(H, P.M, P.K, P.BM, P.BK, true, P.p_call, P.status);
     };
 
     const int lane = threadIdx.x & 63;
@@ -615,7 +615,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     char *const staging = smem + STAGES * STAGE_BYTES;
 
     const MaskHeader *H = P.mv.hdr;
-    if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+    if (!mask_header_ok(H, P.M, P.K, P.BM, P.BK, true, P.p_call, P.status)) return;
 
     const int lane = threadIdx.x & 63;
     const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

@@ -171,6 +171,10 @@ struct SeededGrid {
                 h.magic = kMaskMagic;
                 h.max_row_cnt = max_row;
                 h.max_col_cnt = max_col;
+                h.flags = kMaskDrawn;
+                h.p = P.p_call;
+                h.seed = ((uint64_t)P.key1 << 32) | P.key0;
+                h.rng_stream = ((uint64_t)P.ctr3 << 32) | P.ctr2;
                 *const_cast<MaskHeader *>(mv.hdr) = h;
             }
             return;

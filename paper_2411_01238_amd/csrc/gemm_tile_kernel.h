@@ -36,7 +36,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &P, const int bi
 
     // a kernel handed a mask built for another problem writes nothing
     const MaskHeader *H = P.mv.hdr;
-    if (H->magic != kMaskMagic || H->M != P.M || H->K != P.K || H->BM != P.BM || H->BK != P.BK) return;
+    if (!mask_header_ok(H, P.M, P.K, P.BM, P.BK, true, P.p_call, P.status)) return;
 
     constexpr int esz = 2;
     const int lane = threadIdx.x & 63;

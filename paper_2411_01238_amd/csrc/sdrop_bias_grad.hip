@@ -19,9 +19,10 @@ namespace {
 
 template <class T> struct Vec8 { typedef __attribute__((__vector_size__(8 * sizeof(T)))) T type; };
 
-__device__ __forceinline__ bool header_matches(const MaskHeader *H, int64_t M, int64_t K, int BM, int BK)
+// (the sums carry no scale, so the mask's dropout probability is not compared)
+__device__ __forceinline__ bool header_matches(const MaskHeader *H, int64_t M, int64_t K, int BM, int BK, int *status)
 {
-    return H->magic == kMaskMagic && H->M == M && H->K == K && H->BM == BM && H->BK == BK;
+    return mask_header_ok(H, M, K, BM, BK, false, 0.0, status);
 }
 
 // out[part][k], k in block column kb: sum of dZ[r][k] over the rows r of the kept blocks number
@@ -29,10 +30,10 @@ __device__ __forceinline__ bool header_matches(const MaskHeader *H, int64_t M, i
 template <class T, int BK>
 __global__ __launch_bounds__(256) void colsum_parts_kernel(const T *dz, int64_t ld, const MaskHeader *H, const int32_t *col_ptr,
                                                            const int32_t *row_idx, float *out, int parts,
-                                                           int64_t M, int64_t K, int BM)
+                                                           int64_t M, int64_t K, int BM, int *status)
 {
     // like the GEMMs: write nothing when the mask was built for another problem
-    if (!header_matches(H, M, K, BM, BK)) return;
+    if (!header_matches(H, M, K, BM, BK, status)) return;
     constexpr int L = BK / 8;         // threads per row (8 elements = 16 bytes each)
     constexpr int R = 256 / L;        // rows per step; divides 64, so it divides BM
     __shared__ float red[R][BK];
@@ -61,9 +62,9 @@ __global__ __launch_bounds__(256) void colsum_parts_kernel(const T *dz, int64_t 
 
 // db[k] = part[0][k] + part[1][k] + ... in that order
 __global__ __launch_bounds__(256) void colsum_reduce_kernel(const float *part, float *db, int parts, const MaskHeader *H,
-                                                            int64_t M, int64_t K, int BM, int BK)
+                                                            int64_t M, int64_t K, int BM, int BK, int *status)
 {
-    if (!header_matches(H, M, K, BM, BK)) return;
+    if (!header_matches(H, M, K, BM, BK, status)) return;
     const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k >= K) return;
     // eight loads in flight, added in order
@@ -98,9 +99,9 @@ void launch_parts(const void *dz, int64_t ld, const MaskView &V, float *out, int
     const dim3 grid((unsigned)((K / BK) * parts)), block(256);
     const T *src = static_cast<const T *>(dz);
     if (BK == 64)
-        hipLaunchKernelGGL((colsum_parts_kernel<T, 64>), grid, block, 0, st, src, ld, V.hdr, V.col_ptr, V.row_idx, out, parts, M, K, BM);
+        hipLaunchKernelGGL((colsum_parts_kernel<T, 64>), grid, block, 0, st, src, ld, V.hdr, V.col_ptr, V.row_idx, out, parts, M, K, BM, device_status_word());
     else
-        hipLaunchKernelGGL((colsum_parts_kernel<T, 128>), grid, block, 0, st, src, ld, V.hdr, V.col_ptr, V.row_idx, out, parts, M, K, BM);
+        hipLaunchKernelGGL((colsum_parts_kernel<T, 128>), grid, block, 0, st, src, ld, V.hdr, V.col_ptr, V.row_idx, out, parts, M, K, BM, device_status_word());
 }
 
 int check_shape(int64_t M, int64_t K, int BM, int BK)
@@ -148,7 +149,7 @@ int sdrop_bias_grad(const void *dZ, const void *mask, float *db, int64_t M, int6
     int rs = hip_status(hipGetLastError());
     if (rs != SDROP_OK || parts == 1) return rs;
     hipLaunchKernelGGL(colsum_reduce_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const float *>(ws), db, parts, V.hdr, M, K, BM, BK);
+                       static_cast<const float *>(ws), db, parts, V.hdr, M, K, BM, BK, device_status_word());
     return hip_status(hipGetLastError());
 }
 

@@ -64,10 +64,10 @@ namespace sdrop {
 template <class OutT>
 __global__ __launch_bounds__(256) void reduce_parts_kernel(const float *part, OutT *out_base, int64_t n, int splits, float scale,
                                                            int64_t ncols, int64_t ld, const MaskHeader *H,
-                                                           int64_t M, int64_t K, int BM, int BK)
+                                                           int64_t M, int64_t K, int BM, int BK, double p_call, int *status)
 {
     // like the first pass, write nothing when the mask was built for another problem (the planes are then unwritten)
-    if (H->magic != kMaskMagic || H->M != M || H->K != K || H->BM != BM || H->BK != BK) return;
+    if (!mask_header_ok(H, M, K, BM, BK, true, p_call, status)) return;
     const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= n) return;
     OutT *const out = out_base + (e / ncols) * (ld - ncols);       // row e / ncols of an output with `ld` elements per row (4 | ncols)
@@ -247,6 +247,8 @@ GemmParams base_params(int op, const void *a, const void *b, const void *mask, v
     P.p = p;
     P.key0 = P.key1 = P.ctr2 = P.ctr3 = 0;
     P.threshold = 0;
+    P.p_call = p;
+    P.status = device_status_word();
     return P;
 }
 
@@ -257,14 +259,16 @@ int launch_reduce(const void *ws, void *out, int64_t n, int splits, float scale,
     const MaskHeader *H = P.mv.hdr;
     const int64_t M = P.M, K = P.K;
     const int BM = P.BM, BK = P.BK;
+    const double p_call = P.p_call;
+    int *const status = P.status;
     const unsigned grid = (unsigned)((n / 4 + 255) / 256);
     const float *part = static_cast<const float *>(ws);
     if (out_dtype == SDROP_F32)
-        hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK);
+        hipLaunchKernelGGL(reduce_parts_kernel<float>, dim3(grid), dim3(256), 0, st, part, static_cast<float *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK, p_call, status);
     else if (dtype == SDROP_F16)
-        hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK);
+        hipLaunchKernelGGL(reduce_parts_kernel<_Float16>, dim3(grid), dim3(256), 0, st, part, static_cast<_Float16 *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK, p_call, status);
     else
-        hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK);
+        hipLaunchKernelGGL(reduce_parts_kernel<__bf16>, dim3(grid), dim3(256), 0, st, part, static_cast<__bf16 *>(out), n, splits, scale, ncols, ld, H, M, K, BM, BK, p_call, status);
     return hip_status(hipGetLastError());
 }
 
@@ -495,6 +499,23 @@ constexpr int kMaxDevices = 64;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 static std::atomic<void *> g_scratch_ptr[kMaxDevices];
 
+// The status word: kernels that find a mask object that does not belong to their call record it here (one word per
+// GPU, part of the code object like `scratch`; its device address is looked up once per device).
+static __device__ int status_word;
+static std::atomic<int *> g_status_ptr[kMaxDevices];
+
+int *device_status_word()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    int *p = g_status_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *v = nullptr;
+    if (hipGetSymbolAddress(&v, HIP_SYMBOL(status_word)) != hipSuccess || !v) { (void)hipGetLastError(); return nullptr; }
+    g_status_ptr[dev].store(static_cast<int *>(v), std::memory_order_release);
+    return static_cast<int *>(v);
+}
+
 // The current device's copy of `scratch`, or null with the HIP error recorded.
 void *static_scratch()
 {
@@ -514,6 +535,18 @@ void *static_scratch()
 
 
 extern "C" {
+
+int sdrop_status(int *flags_host, int clear, void *stream)
+{
+    if (!flags_host) return SDROP_EINVAL;
+    int *const word = sdrop::device_status_word();
+    if (!word) return SDROP_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(flags_host, word, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && clear) e = hipMemsetAsync(word, 0, sizeof(int), st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    return sdrop::hip_status(e);
+}
 
 int sdrop_set_tuning(int knob, int value)
 {

@@ -17,12 +17,29 @@ struct MaskHeader {
     uint32_t magic;          // 40
     int32_t max_row_cnt;     // 44
     int32_t max_col_cnt;     // 48
-    int32_t pad_[51];
+    uint32_t flags;          // 52: kMaskDrawn when the mask was drawn (p, seed, rng_stream below say how)
+    double p;                // 56: the dropout probability the mask was drawn with (0 when built from given bits)
+    uint64_t seed;           // 64
+    uint64_t rng_stream;     // 72
+    int32_t pad_[44];
 };
 static_assert(sizeof(MaskHeader) == 256, "mask header is 256 bytes");
 static_assert(offsetof(MaskHeader, nnz) == SDROP_MASK_NNZ_OFFSET, "nnz offset is part of the ABI");
 
 constexpr uint32_t kMaskMagic = 0x5344524Fu;  // "SDRO"
+constexpr uint32_t kMaskDrawn = 1u;           // MaskHeader::flags
+
+// Does the mask object belong to this call?  Same shape and blocks, and, for a mask that was drawn, the dropout
+// probability the call derives its scale from is the one the mask was drawn with.  A kernel that finds a mismatch
+// writes nothing; one of its threads records it in the library's status word (see sdrop_status) when there is one.
+__device__ __forceinline__ bool mask_header_ok(const MaskHeader *H, int64_t M, int64_t K, int BM, int BK,
+                                               bool check_p, double p_call, int *status)
+{
+    bool ok = H->magic == kMaskMagic && H->M == M && H->K == K && H->BM == BM && H->BK == BK;
+    if (ok && check_p && (H->flags & kMaskDrawn) && H->p != p_call) ok = false;
+    if (!ok && status && blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, SDROP_STATUS_MASK_MISMATCH);
+    return ok;
+}
 
 // Device-side view of a mask object.
 struct MaskView {
@@ -82,5 +99,8 @@ inline bool block_size_ok(int b) { return b == 64 || b == 128; }
 
 // Compute units of the current device (256 when the query fails).
 int cu_count();
+
+// The current device's status word (device address), or null when it cannot be had.
+int *device_status_word();
 
 }  // namespace sdrop

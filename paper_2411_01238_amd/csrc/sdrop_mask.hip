@@ -41,6 +41,8 @@ struct MaskParams {
     int32_t split_m, split_k, KBL;   // block splitting: logical block = split_m x split_k blocks; logical columns
     uint32_t key0, key1, ctr2, ctr3; // seed and rng_stream split in 32-bit words
     uint64_t threshold;              // floor(p * 2^32)
+    double p;                        // as given (recorded in the header)
+    uint64_t seed, rng_stream;
 };
 
 // Number of the logical block that decides block (i, j): with block splitting (Section 3.3) the
@@ -269,6 +271,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_kernel(MaskParams P)
         h.magic = kMaskMagic;
         h.max_row_cnt = s_first[0];
         h.max_col_cnt = s_first[1];
+        if (!P.given_bits) { h.flags = kMaskDrawn; h.p = P.p; h.seed = P.seed; h.rng_stream = P.rng_stream; }
         *P.hdr = h;
     }
 }
@@ -455,6 +458,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         h.magic = kMaskMagic;
         h.max_row_cnt = s_max[0];
         h.max_col_cnt = s_max[1];
+        if (!P.given_bits) { h.flags = kMaskDrawn; h.p = P.p; h.seed = P.seed; h.rng_stream = P.rng_stream; }
         *P.hdr = h;
     }
 }
@@ -497,6 +501,7 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     P.key0 = static_cast<uint32_t>(seed); P.key1 = static_cast<uint32_t>(seed >> 32);
     P.ctr2 = static_cast<uint32_t>(rng_stream); P.ctr3 = static_cast<uint32_t>(rng_stream >> 32);
     P.threshold = static_cast<uint64_t>(floor(p * 4294967296.0));
+    P.p = p; P.seed = seed; P.rng_stream = rng_stream;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t words = L.MB * L.words_per_row;
     const bool small = L.MB <= kSmallN && L.KB <= kSmallN && words <= kLdsWords;

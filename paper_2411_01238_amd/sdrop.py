@@ -21,7 +21,7 @@ F16, BF16, F32 = 0, 1, 2
 OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
 MASK_NNZ_OFFSET = 36
 
-EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
+EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_status", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_mask_bits", "sdrop_workspace_bytes",
            "sdrop_fwd", "sdrop_fwd_seeded", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
            "sdrop_bwd", "sdrop_bwd_ex", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_workspace_bytes_ex",
@@ -74,6 +74,8 @@ def lib():
         L.sdrop_strerror.restype = ctypes.c_char_p
         L.sdrop_last_hip_error.argtypes = []
         L.sdrop_last_hip_error.restype = ci
+        L.sdrop_status.argtypes = [ctypes.POINTER(ci), ci, vp]
+        L.sdrop_status.restype = ci
         L.sdrop_set_tuning.argtypes = [ci, ci]
         L.sdrop_set_tuning.restype = ci
         L.sdrop_mask_layout.argtypes = [i64, i64, ci, ci, ctypes.POINTER(MaskLayout)]
@@ -129,6 +131,16 @@ TUNE_FWD_SEEDED = 3
 
 def set_tuning(knob, value):
     _check(lib().sdrop_set_tuning(int(knob), int(value)), "sdrop_set_tuning")
+
+
+STATUS_MASK_MISMATCH = 1
+
+
+def status(clear=True):
+    """The library's device-side status word on the current GPU (see sdrop_status): waits for the current stream."""
+    v = ctypes.c_int(0)
+    _check(lib().sdrop_status(ctypes.byref(v), 1 if clear else 0, _stream()), "sdrop_status")
+    return int(v.value)
 
 
 def strerror(code):

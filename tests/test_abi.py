@@ -275,6 +275,7 @@ def test_new_entry_points_check_their_arguments_on_the_host():
     assert L.sdrop_fwd_seeded(*(oks[:3] + (64,) + oks[4:])) == sdrop.EWORKSPACE
     assert L.sdrop_fwd_seeded(*(oks[:10] + (1.5,) + oks[11:])) == sdrop.EINVAL
     assert L.sdrop_fwd_seeded(*(oks[:7] + (250,) + oks[8:])) == sdrop.ESHAPE
+    assert L.sdrop_status(None, 0, None) == sdrop.EINVAL
     # sdrop_bwd_dw_static: argument errors as sdrop_bwd_dw
     okd = (p, p, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null)
     assert L.sdrop_bwd_dw_static(*((null,) + okd[1:])) == sdrop.EINVAL

@@ -250,6 +250,47 @@ def test_mask_for_another_problem_writes_nothing():
     assert torch.all(out == 7.0)
 
 
+def test_status_word_reports_what_only_the_device_can_see():
+    # a mask of another problem, and a drawn mask used with another dropout probability: the call returns OK (it only
+    # enqueues), the kernels write nothing, and the status word says so; a mask built from bits goes with any p
+    M, K, N, BM, BK = 1024, 512, 256, 128, 128
+    X, W, dY = make_custom(M, K, N, "bf16", seed=17)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    sdrop.status(clear=True)
+    m = sdrop.sdrop_mask(M, K, BM, BK, 0.5, 3, 1)
+    good = sdrop.sdrop_fwd(Xg, Wg, m)
+    assert sdrop.status(clear=True) == 0
+    hdr = m.buf[:256].cpu().numpy()
+    assert hdr[56:64].view(np.float64)[0] == 0.5 and hdr[64:72].view(np.uint64)[0] == 3 and hdr[72:80].view(np.uint64)[0] == 1
+    # another p for the same object: every product refuses
+    m.p = 0.25
+    outs = {"Y": torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda"),
+            "dX": torch.full((M, K), 7.0, dtype=torch.bfloat16, device="cuda"),
+            "dW": torch.full((K, N), 7.0, dtype=torch.bfloat16, device="cuda")}
+    sdrop.sdrop_fwd(Xg, Wg, m, out=outs["Y"])
+    assert sdrop.status(clear=False) == sdrop.STATUS_MASK_MISMATCH
+    assert sdrop.status(clear=True) == sdrop.STATUS_MASK_MISMATCH
+    assert sdrop.status(clear=True) == 0
+    sdrop.sdrop_bwd(dYg, Wg, Xg, m, out_dx=outs["dX"], out_dw=outs["dW"])
+    assert sdrop.status(clear=True) == sdrop.STATUS_MASK_MISMATCH
+    for n, o in outs.items():
+        assert torch.all(o == 7.0).item(), n + " was written with a mask drawn for another p"
+    m.p = 0.5
+    assert torch.equal(sdrop.sdrop_fwd(Xg, Wg, m), good) and sdrop.status() == 0
+    # a mask from the caller's bits carries no p: any p is taken, the scale follows the call
+    keep = orc.mask(M // BM, K // BK, 0.5, 3, 1)
+    bits = torch.from_numpy(orc.pack_bits(keep).view(np.int64)).cuda()
+    mb = sdrop.sdrop_mask_from_bits(M, K, BM, BK, 0.25, bits)
+    y = sdrop.sdrop_fwd(Xg, Wg, mb, out_dtype=torch.float32)
+    assert sdrop.status() == 0
+    assert_close(f64(y), orc.fwd(f64(X), f64(W), keep, BM, BK, 0.25), "mask from bits with its own p")
+    # a foreign mask
+    wrong = sdrop.sdrop_mask(M, K, 64, 64, 0.5, 0, 0)
+    wrong.BM = wrong.BK = 128
+    sdrop.sdrop_fwd(Xg, Wg, wrong, out=outs["Y"])
+    assert sdrop.status() == sdrop.STATUS_MASK_MISMATCH and torch.all(outs["Y"] == 7.0).item()
+
+
 def test_binding_reports_errors():
     X, W, dY = make_custom(256, 256, 64, "f16", seed=16)
     m = sdrop.sdrop_mask(256, 256, 64, 64, 0.5, 0, 0)
