@@ -124,13 +124,14 @@ __device__ void descending_order(const int32_t *ptr, int n, int max_cnt, int32_t
 // group in earlier columns (a prefix sum over the lanes) plus those above it in its own column.
 // `bits` and `row_ptr` may be in LDS or in global memory written earlier by this workgroup.
 // The groups are shared by wavefronts [wave0, wave0 + nw) of the workgroup; the others return at once.
+// With several workgroups (wg of nwg) the groups are dealt out over the wavefronts of all of them.
 __device__ void local_order(const uint64_t *bits, const int32_t *row_ptr, const MaskParams &P,
-                            int wave0 = 0, int nw = kMaskWaves)
+                            int wave0 = 0, int nw = kMaskWaves, int wg = 0, int nwg = 1)
 {
     const int lane = lane_id();
     const int me = wave_id() - wave0;
     if (me < 0 || me >= nw) return;
-    for (int i0 = me * 8; i0 < P.MB; i0 += nw * 8) {
+    for (int i0 = (wg * nw + me) * 8; i0 < P.MB; i0 += nwg * nw * 8) {
         const int nr = P.MB - i0 < 8 ? P.MB - i0 : 8;
         int pos = row_ptr[i0];
         for (int w = 0; w < P.wpr; ++w) {
@@ -302,9 +303,15 @@ __device__ __forceinline__ void wave_scan(const int32_t *cnt, int32_t *ptr, int 
     if (lane == 63) ptr[n] = incl;
 }
 
+// Launched as one workgroup or as several.  Several: every workgroup builds the same bits, counts and pointers in its
+// own LDS (the draw is counter-based, so no workgroup needs another's result) and the lists, the part whose store
+// count grows with the grid, are shared out wavefront by wavefront over all workgroups; workgroup 0 alone writes the
+// bits, the pointer arrays, the schedules and the header.  For 512 x 32 blocks (57 k list entries, one CU's store
+// rate was what the single workgroup spent its time on) mask_draw_kernel + this kernel took 5 + 31 us.
 template <bool DRAW>
 __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
 {
+    const bool first_wg = blockIdx.x == 0;
     __shared__ uint64_t s_bits[kLdsWords];
     __shared__ __attribute__((aligned(16))) int32_t s_rcnt[kSmallN], s_ccnt[kSmallN];
     __shared__ __attribute__((aligned(16))) int32_t s_rkey[kSmallN], s_ckey[kSmallN];   // sort keys, see phase 2
@@ -339,7 +346,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
                 if (j == 0 && i < P.MB) {
                     const uint64_t word = (all >> (sub * kbp)) & ((uint64_t(1) << kbp) - 1);
                     s_bits[i] = word;
-                    P.bits[i] = word;
+                    if (first_wg) P.bits[i] = word;
                 }
             }
         } else
@@ -352,7 +359,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
                 keep = (uint64_t)r >= P.threshold;
             }
             const uint64_t word = __ballot(keep);
-            if (lane == 0) { s_bits[g] = word; P.bits[g] = word; }
+            if (lane == 0) { s_bits[g] = word; if (first_wg) P.bits[g] = word; }
         }
     } else {
         const uint64_t *src_bits = P.given_bits ? P.given_bits : P.bits;
@@ -361,7 +368,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
             uint64_t word = src_bits[g];
             if (valid < 64) word &= (uint64_t(1) << valid) - 1;
             s_bits[g] = word;
-            P.bits[g] = word;
+            if (first_wg) P.bits[g] = word;
         }
     }
     __syncthreads();
@@ -400,34 +407,44 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         }
         return rank;
     };
+    // (with several workgroups the rows and columns to rank are dealt out over all of them: ranking is quadratic,
+    // 512 rows took one workgroup 5 us)
     constexpr int kHalf = kMaskThreads / 2;
+    const int rank_stride = (int)gridDim.x * kHalf;
     if (threadIdx.x < kHalf) {
-        for (int i = threadIdx.x; i < P.MB; i += kHalf) {
+        for (int i = (int)blockIdx.x * kHalf + threadIdx.x; i < P.MB; i += rank_stride) {
             const int rank = rank_of(s_rkey, P.MB, s_rkey[i]);
             P.row_order[rank] = i;
-            if (rank == 0) s_max[0] = s_rcnt[i];
         }
     } else {
-        for (int j = threadIdx.x - kHalf; j < P.KB; j += kHalf) {
+        for (int j = (int)blockIdx.x * kHalf + threadIdx.x - kHalf; j < P.KB; j += rank_stride) {
             const int rank = rank_of(s_ckey, P.KB, s_ckey[j]);
             P.col_order[rank] = j;
-            if (rank == 0) s_max[1] = s_ccnt[j];
         }
+    }
+    // the largest counts, for the header (workgroup 0 writes it)
+    if (first_wg) {
+        for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) atomicMax(&s_max[0], s_rcnt[i]);
+        for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) atomicMax(&s_max[1], s_ccnt[j]);
     }
     __syncthreads();
 
     // -- phase 3: the lists --
-    for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
-    for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = s_col_ptr[j];
-    // The three kinds of lists do not depend on each other.  With few groups of 8 block rows (a small
-    // grid) the locally ordered list would keep only that many wavefronts busy, on top of their share
-    // of the other lists: those groups then get wavefronts of their own, the last ones, and the row
-    // and column lists are shared by the rest.
+    if (first_wg) {
+        for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
+        for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = s_col_ptr[j];
+    }
+    // The three kinds of lists do not depend on each other.  One workgroup: with few groups of 8 block rows (a small
+    // grid) the locally ordered list would keep only that many wavefronts busy, on top of their share of the other
+    // lists: those groups then get wavefronts of their own, the last ones, and the row and column lists are shared
+    // by the rest.  Several workgroups: every kind is dealt out over all wavefronts of the launch.
+    const int nwg = (int)gridDim.x;
     const int ngroups = (P.MB + 7) / 8;
-    const int nlo = ngroups < kMaskWaves / 2 ? ngroups : 0;       // wavefronts that only build the locally ordered list
-    const int nls = kMaskWaves - nlo;                              // wavefronts that build the row and column lists
+    const int nlo = (nwg == 1 && ngroups < kMaskWaves / 2) ? ngroups : 0;   // wavefronts that only build the locally ordered list
+    const int nls = kMaskWaves - nlo;                              // wavefronts (per workgroup) that build the row and column lists
+    const int gw = (int)blockIdx.x * nls + wave, ngw = nwg * nls;  // this wavefront among those of the whole launch
     if (nlo > 0) local_order(s_bits, s_row_ptr, P, nls, nlo);
-    for (int i = wave; i < P.MB && wave < nls; i += nls) {
+    for (int i = gw; i < P.MB && wave < nls; i += ngw) {
         int pos = s_row_ptr[i];
         for (int w = 0; w < P.wpr; ++w) {
             const uint64_t word = s_bits[i * P.wpr + w];
@@ -439,8 +456,8 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
             pos += __popcll(word);
         }
     }
-    if (nlo == 0) local_order(s_bits, s_row_ptr, P);
-    for (int j = wave; j < P.KB && wave < nls; j += nls) {
+    if (nlo == 0) local_order(s_bits, s_row_ptr, P, 0, kMaskWaves, (int)blockIdx.x, nwg);
+    for (int j = gw; j < P.KB && wave < nls; j += ngw) {
         int pos = s_col_ptr[j];
         for (int i0 = 0; i0 < P.MB; i0 += 64) {
             const int i = i0 + lane;
@@ -450,6 +467,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
             pos += __popcll(word);
         }
     }
+    if (!first_wg) return;
     if (threadIdx.x == 0) {
         MaskHeader h = {};
         h.M = P.M; h.K = P.K; h.BM = P.BM; h.BK = P.BK; h.MB = P.MB; h.KB = P.KB;
@@ -505,15 +523,20 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t words = L.MB * L.words_per_row;
     const bool small = L.MB <= kSmallN && L.KB <= kSmallN && words <= kLdsWords;
-    const bool fused_draw = small && !given_bits && words <= 64;     // a launch costs more than 4 draws per wavefront
+    // Small grids (and that is all five workloads') are drawn by the workgroups that build the lists: one launch.
+    // The lists are shared out over several workgroups when there are many of them (about 32 list pieces, i.e. block
+    // rows, block columns and groups of 8 block rows, per workgroup).
+    const bool fused_draw = small && !given_bits;
+    const int64_t pieces = L.MB + L.KB + (L.MB + 7) / 8;
+    const unsigned n_wg = !small || words <= 64 ? 1u : (unsigned)(pieces / 32 < 1 ? 1 : pieces / 32 > 64 ? 64 : pieces / 32);
     if (!given_bits && !fused_draw) {
         hipLaunchKernelGGL(mask_draw_kernel, dim3((unsigned)((words + 3) / 4)), dim3(256), 0, st, P);
         const int rc2 = hip_status(hipGetLastError());
         if (rc2 != SDROP_OK) return rc2;
     }
     if (small) {
-        if (fused_draw) hipLaunchKernelGGL(mask_small_kernel<true>, dim3(1), dim3(kMaskThreads), 0, st, P);
-        else hipLaunchKernelGGL(mask_small_kernel<false>, dim3(1), dim3(kMaskThreads), 0, st, P);
+        if (fused_draw) hipLaunchKernelGGL(mask_small_kernel<true>, dim3(n_wg), dim3(kMaskThreads), 0, st, P);
+        else hipLaunchKernelGGL(mask_small_kernel<false>, dim3(n_wg), dim3(kMaskThreads), 0, st, P);
         return hip_status(hipGetLastError());
     }
     const bool in_lds = L.MB * L.words_per_row <= kLdsWords && L.MB <= kLdsPtrs && L.KB <= kLdsPtrs;
