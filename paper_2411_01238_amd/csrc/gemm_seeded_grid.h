@@ -84,7 +84,7 @@ struct SeededGrid {
             const int i = b * R + sub;
             bool keep = false;
             if (i < MB && j < KB) {
-                const uint32_t blk = (uint32_t)(i * KB + j);        // the block number b = i KB + j of the generator's counter
+                const uint32_t blk = __umul24((uint32_t)i, (uint32_t)KB) + (uint32_t)j;   // the block number b = i KB + j of the generator's counter
                 keep = (uint64_t)philox_word0(blk, 0u, P.ctr2, P.ctr3, P.key0, P.key1) >= P.threshold;
             }
             const uint64_t all = __ballot(keep);

@@ -50,6 +50,9 @@ struct MaskParams {
 // and split_k times along K; without it this is i * KB + j.
 __device__ __forceinline__ uint64_t logical_block(const MaskParams &P, int64_t i, int j)
 {
+    // without splitting: i * KB + j, below 2^26 (see sdrop_mask_layout), both factors below 2^24: one full-rate multiply
+    // (the divisions below cost as much as half the generator's rounds)
+    if (P.split_m == 1 && P.split_k == 1) return (uint64_t)(__umul24((uint32_t)i, (uint32_t)P.KB) + (uint32_t)j);
     // block rows and columns are below 2^31: 32-bit divisions (a 64-bit one costs several times as much)
     return (uint64_t)((uint32_t)i / (uint32_t)P.split_m) * (uint64_t)P.KBL + (uint64_t)((uint32_t)j / (uint32_t)P.split_k);
 }
@@ -423,9 +426,18 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         }
     }
     // the largest counts, for the header (workgroup 0 writes it)
+    // (a maximum per wavefront first: atomics of many lanes on one LDS word are served one by one)
     if (first_wg) {
-        for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) atomicMax(&s_max[0], s_rcnt[i]);
-        for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) atomicMax(&s_max[1], s_ccnt[j]);
+        int mr = 0, mc = 0;
+        for (int i = threadIdx.x; i < P.MB; i += kMaskThreads) mr = s_rcnt[i] > mr ? s_rcnt[i] : mr;
+        for (int j = threadIdx.x; j < P.KB; j += kMaskThreads) mc = s_ccnt[j] > mc ? s_ccnt[j] : mc;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const int orr = __shfl_xor(mr, d, 64), oc = __shfl_xor(mc, d, 64);
+            mr = orr > mr ? orr : mr;
+            mc = oc > mc ? oc : mc;
+        }
+        if (lane == 0) { atomicMax(&s_max[0], mr); atomicMax(&s_max[1], mc); }
     }
     __syncthreads();
 
