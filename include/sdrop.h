@@ -73,10 +73,14 @@ enum { SDROP_OP_FWD = 0, SDROP_OP_BWD_DX = 1, SDROP_OP_BWD_DW = 2 };
  *       shapes allow it; 0: always as the two separate launches
  *   SDROP_TUNE_FWD_SEEDED  1 (default): sdrop_fwd_seeded draws the mask inside the forward kernel where the
  *       block grid allows it; 0: always as sdrop_mask followed by sdrop_fwd
+ *   SDROP_TUNE_DW64_PERSISTENT_SLICES  sdrop_bwd_dw with 64-row tiles (BK = 64) uses its persistent kernel
+ *       when it expects at least this many reduction slices per tile (default 16; 0 = always)
+ *   SDROP_TUNE_DX_PAIRS  sdrop_bwd_dx / sdrop_bwd with 128 x 128 blocks on grids of at most 128 x 64 blocks: tiles
+ *       of two kept blocks from the mask's pair list; 0 (default) chosen per call, 1 wherever it applies, 2 never
  * Returns SDROP_EINVAL for an unknown knob or a value outside its range.
  */
 enum { SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU = 0, SDROP_TUNE_BWD_FUSED = 1, SDROP_TUNE_DX_TILE_WIDTH = 2,
-       SDROP_TUNE_FWD_SEEDED = 3 };
+       SDROP_TUNE_FWD_SEEDED = 3, SDROP_TUNE_DW64_PERSISTENT_SLICES = 4, SDROP_TUNE_DX_PAIRS = 5 };
 int sdrop_set_tuning(int knob, int value);
 
 /*
@@ -124,16 +128,24 @@ int sdrop_last_hip_error(void);
  *            this list share block rows AND block columns, which is the order eq. 2
  *            computes them in (tiles that run at the same time then share operand
  *            tiles in cache)
+ *   units    int32[n_units (room for MB*KB)], for grids of at most 128 x 64 blocks (n_units, the int32 at
+ *            byte offset SDROP_MASK_NUNITS_OFFSET of the header, is 0 for larger grids): the kept blocks
+ *            once more, as pairs that can share an output tile of eq. 2, and the few blocks left over.
+ *            An entry is kind << 30 | x << 16 | y << 8 | z with kind 0: blocks (x, y) and (x, z) of one
+ *            block row; kind 1: blocks (y, x) and (z, x) of one block column; kind 2: block (x, y) alone.
+ *            Every kept block is in exactly one entry.
  */
 typedef struct sdrop_mask_layout {
     size_t total_bytes;
     size_t off_bits, off_row_ptr, off_col_idx, off_blk_row;
     size_t off_col_ptr, off_row_idx, off_row_order, off_col_order;
     size_t off_loc_row, off_loc_col;
+    size_t off_units;
     int64_t MB, KB, words_per_row;
 } sdrop_mask_layout_t;
 
 #define SDROP_MASK_NNZ_OFFSET 36
+#define SDROP_MASK_NUNITS_OFFSET 80
 
 /* Fills *out for a mask over X[M,K] in BM x BK blocks.  SDROP_ESHAPE on a bad shape. */
 int sdrop_mask_layout(int64_t M, int64_t K, int BM, int BK, sdrop_mask_layout_t *out);

@@ -34,13 +34,15 @@ inline int tail_mode(const GemmParams &P)
 }
 
 // dX: width of the tiles, and whether the persistent kernel computes them (see sdrop_gemm.hip)
-struct DxPlan { int TN; bool persistent; };
+struct DxPlan { int TN; bool persistent; bool pairs; };
 DxPlan dx_plan(const GemmParams &P);
 // dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on
 bool dw64_persistent(const GemmParams &P);
 
 // which single launch sdrop_bwd uses (see run_bwd)
 enum BwdForm { kBwdNone = 0, kBwdPersistent, kBwdTile128, kBwdTile64 };
+// the tile width argument of bwd_fused_typed that stands for 256-wide tiles from the pair list
+constexpr int kTNPairs = 257;
 
 // One of the three products for operands of type T: picks tile shapes and kernel form, launches.
 // o32: fp32 output instead of the operands' type.

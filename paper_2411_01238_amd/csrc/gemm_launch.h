@@ -161,6 +161,25 @@ int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// Persistent dX over the mask's pair list (128 x 256 tiles of two kept blocks).
+template <class T, class OutT>
+int launch_dx_pairs(const GemmParams &P, hipStream_t stream)
+{
+    constexpr int P_LDS = 3 * (128 + 256) * TK * 2 + 4 * 4096;
+    auto k = gemm_persistent_dx_kernel<T, OutT, 128, 256, 2, 2, kTailNone, false, true>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    const int64_t positions = (int64_t)P.MB * P.KB;
+    const int ncu = cu_count();
+    hipLaunchKernelGGL(k, dim3((unsigned)(positions < ncu ? positions : ncu)), dim3(512), P_LDS, stream, P);
+    return hip_status(hipGetLastError());
+}
+
 // Tile shapes: the tile edge that lies along the mask must equal the mask's block
 // (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
 // 256/BK kept blocks of one block row into a 256-wide tile.
@@ -213,6 +232,11 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         // one kept block per tile: a workgroup per block position, rounded up to whole sets of 8 XCDs
         const int grid = G_ == 1 ? (P.MB * P.KB + 7) / 8 * 8 : P.MB * P.n_tiles;
         const bool ragged = P.N % TK != 0;
+        if (plan.pairs) {
+            const int rc = launch_dx_pairs<T, OutT>(P, stream);
+            if (rc != -1) return rc;
+            return SDROP_EHIP;            // (the plain 128 x 256 persistent form needs the same LDS)
+        }
         if (plan.persistent) {
             const int rc = TNsel == 256 ? launch_dx_persistent<T, OutT, 256>(P, stream) : launch_dx_persistent<T, OutT, 128>(P, stream);
             if (rc != -1) return rc;      // -1: the device does not grant the LDS; use the per-tile kernels
@@ -226,12 +250,12 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
     }
 }
 
-template <class T, class OutDX, class OutDW, int TN_DX>
+template <class T, class OutDX, class OutDW, int TN_DX, bool PAIRS = false>
 int launch_bwd_fused(const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
 {
     constexpr int LDS_DX = 3 * (128 + TN_DX) * TK * 2 + 4 * 4096, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
     constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
-    auto k = bwd_fused_kernel<T, OutDX, OutDW, TN_DX>;
+    auto k = bwd_fused_kernel<T, OutDX, OutDW, TN_DX, PAIRS>;
     static int ok = -1;     // per instantiation: does the device grant that much LDS?
     if (ok < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
@@ -269,6 +293,7 @@ int launch_bwd_fused_tile(const GemmParams &Pdx, const GemmParams &Pdw, int n_dx
 template <class T, class OutDX, class OutDW>
 int launch_bwd_fused_tn(int TN, const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
 {
+    if (TN == kTNPairs) return launch_bwd_fused<T, OutDX, OutDW, 256, true>(Pdx, Pdw, stream);
     if (TN == 256) return launch_bwd_fused<T, OutDX, OutDW, 256>(Pdx, Pdw, stream);
     return launch_bwd_fused<T, OutDX, OutDW, 128>(Pdx, Pdw, stream);
 }

@@ -48,7 +48,9 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
     // order that quarter's MFMAs (A index major) first use them: A0, B0 .. B(NI-1), A1 .. A(MI-1).
     // After the first MFMAs of the last quarter comes the slice's barrier (every wavefront is done
     // reading `cur`; the slice in `nx1` has landed), then the first operands of `nx1`.
-    __device__ __forceinline__ void slice(const char *cur, const char *nx1)
+    // SWAP: the MFMAs take the operands the other way round, which leaves the transposed 32 x 32 blocks in the
+    // accumulators (lane <-> tile column, registers <-> tile rows); store_t writes such a tile out transposed.
+    template <bool SWAP = false> __device__ __forceinline__ void slice(const char *cur, const char *nx1)
     {
         __builtin_amdgcn_sched_barrier(0);
         static_for<4>([&](auto gi) __attribute__((always_inline)) {
@@ -62,7 +64,8 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                     __builtin_amdgcn_s_barrier();
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                acc[mi][ni] = In<T>::mfma(fb[cb][ni], fa[cb][mi], acc[mi][ni]);
+                if constexpr (SWAP) acc[mi][ni] = In<T>::mfma(fa[cb][mi], fb[cb][ni], acc[mi][ni]);
+                else acc[mi][ni] = In<T>::mfma(fb[cb][ni], fa[cb][mi], acc[mi][ni]);
                 constexpr int r0 = c < NB ? 0 : (c - NB) * RPM < NOPS ? (c - NB) * RPM : NOPS;
                 constexpr int r1 = c < NB ? 0 : (c - NB + 1) * RPM < NOPS ? (c - NB + 1) * RPM : NOPS;
                 static_for<r1 - r0>([&](auto ri) __attribute__((always_inline)) {
@@ -228,6 +231,52 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                 }
             }
         }
+    }
+    // The epilogue of a tile whose slices ran with SWAP, written out transposed (no tail): accumulator block
+    // [mi][ni] holds, in the layout `store` expects, the 32 x 32 block (ni, mi) of the transposed sub-tile, so a
+    // 32-row x 128-byte piece (r, pj) of the transposed sub-tile is made of blocks [pj NIP + nl][r].
+    // dst_t(r, pj) is the address of its row 0, or null.
+    template <class F> __device__ __forceinline__ void store_t(char *reg, float scale, int64_t ldc, F &&dst_t)
+    {
+        static_assert(MI % NIP == 0, "a wavefront's rows must fill whole 128-byte rows of the transposed tile");
+        const int lane = threadIdx.x & 63;
+        const int wrow = lane & 31, whalf = lane >> 5;
+        const int rrow = lane >> 3, rch = lane & 7;
+#pragma unroll
+        for (int r = 0; r < NI; ++r)
+#pragma unroll
+            for (int pj = 0; pj < MI / NIP; ++pj) {
+                char *const out = dst_t(r, pj);
+                if (!out) continue;                        // uniform
+#pragma unroll
+                for (int nl = 0; nl < NIP; ++nl)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16 &a = acc[pj * NIP + nl][r];
+                        const float v0 = a[4 * q] * scale, v1 = a[4 * q + 1] * scale, v2 = a[4 * q + 2] * scale, v3 = a[4 * q + 3] * scale;
+                        if constexpr (ESZ == 4) {
+                            const int slot = (2 * q + whalf) ^ (wrow & 7);
+                            *reinterpret_cast<float4 *>(reg + wrow * 128 + slot * 16) = make_float4(v0, v1, v2, v3);
+                        } else {
+                            typedef __attribute__((__vector_size__(4 * sizeof(OutT)))) OutT out4;
+                            const out4 o = {static_cast<OutT>(v0), static_cast<OutT>(v1), static_cast<OutT>(v2), static_cast<OutT>(v3)};
+                            const int slot8 = (nl * 8 + 2 * q + whalf) ^ (wrow & 15);
+                            *reinterpret_cast<out4 *>(reg + wrow * 128 + slot8 * 8) = o;
+                        }
+                    }
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = it * 8 + rrow;
+                    uint4 v;
+                    if constexpr (ESZ == 4) {
+                        v = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
+                    } else {
+                        const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
+                        v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
+                    }
+                    store_out(out + (int64_t)row * ldc + rch * 16, v);
+                }
+            }
     }
     // The epilogue of one tile.  With a tail, the sub-tile goes out in two halves (of its column groups,
     // else of its row blocks when it is one group wide and four blocks tall), each half requesting its
@@ -598,11 +647,19 @@ __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 // Zero fill of the dropped blocks: workgroup w owns block positions w, w+G, ...; its loader
 // wavefronts write them a kilobyte per slice of the stream, beside the direct loads, and finish
 // what is left when the stream has ended.
-template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false>
+//
+// PAIRS (128 x 128 blocks, 256-wide tiles, no tail, whole slices, dY and W with the same row stride): the work
+// units are the entries of the mask's pair list instead.  A wide pair or a single block is a tile as above (two
+// block columns of one block row; the single block twice, written once).  A tall pair, blocks (i1, j) and
+// (i2, j), is computed as the transposed product: W's panel j takes dY's place as the 128-row operand, the two dY
+// panels are the 256-row operand, the MFMAs take their operands the other way round and the epilogue writes the
+// two 128 x 128 results transposed.
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false, bool PAIRS = false>
 __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, const int G, const int w)
 {
     constexpr int NW = WM * WN;
     static_assert(NW == 4 && TM == 128, "one computing and one loading wavefront per SIMD, 128-row tiles");
+    static_assert(!PAIRS || (TN == 256 && TAIL == kTailNone && !RAGN), "the pair list serves plain 128 x 256 tiles");
     constexpr int WTM = TM / WM, WTN = TN / WN;
     constexpr int DXG = TN / 64;                      // 64-column chunks of a tile
     static_assert(DXG <= 4, "tile too wide");
@@ -625,7 +682,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     const int GB = TN / P.BK;                          // kept blocks per group: 1, 2 or 4
     const int cshift = (P.BK == 128), cmask = (1 << cshift) - 1;   // 64-column chunks per block
     const int nnz = H->nnz;
-    const int ngroups = (nnz + GB - 1) / GB;
+    const int ngroups = PAIRS ? H->n_units : (nnz + GB - 1) / GB;
     // slices of the reduction; when N is not a multiple of the slice the last one is ragged: the loaders
     // clear what lies beyond N in LDS (see DmaK::issue), the computing wavefronts see a full slice
     // (RAGN: a form of its own, because the extra case in the loaders cost the whole-slice form 5 %)
@@ -656,9 +713,18 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
         constexpr int NDMA_A = TM / (8 * NW), NDMA_B = TN / (8 * NW), NDMA = NDMA_A + NDMA_B;
         typedef const __attribute__((address_space(4))) int32_t *const_i32;   // see gemm_persistent_kernel
         const const_i32 k_rows = (const_i32)(uintptr_t)rows, k_cols = (const_i32)(uintptr_t)cols;
+        const const_i32 k_units = (const_i32)(uintptr_t)P.mv.units;
         auto load_group = [&](int k) __attribute__((always_inline)) -> Group {
             Group g;
             g.u = group_of(k);
+            if constexpr (PAIRS) {
+                // one entry of the pair list (c[0]); entry 0 always lies inside the object
+                g.n = g.u < 0 ? 0 : 1;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) g.r[b] = g.c[b] = 0;
+                g.c[0] = k_units[g.u < 0 ? 0 : g.u];
+                return g;
+            }
             const int e0 = (g.u < 0 ? 0 : g.u) * GB;
             g.n = g.u < 0 ? 0 : (nnz - e0 < GB ? nnz - e0 : GB);
 #pragma unroll
@@ -692,6 +758,16 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
                     nxt = load_group(k + 1);
                     a = 0;
                 }
+                if constexpr (PAIRS) {
+                    const int ent = cur.c[0], kind = (ent >> 30) & 3, x = (ent >> 16) & 255, y = (ent >> 8) & 255, z = ent & 255;
+                    // (lda == ldb here, so either matrix can sit on either side)
+                    const char *const m128 = kind == kUnitTall ? P.B : P.A, *const m256 = kind == kUnitTall ? P.A : P.B;
+                    a_tile = m128 + (int64_t)x * 128 * lda;
+#pragma unroll
+                    for (int g = 0; g < DXG; ++g) bgrp[g] = m256 + ((int64_t)(g < 2 ? y : z) * 128 + (g & 1) * 64) * ldb;
+                    a = 1;
+                    s = 0;
+                } else {
                 const int row = sel4(cur.r, a);
                 int nb = 1;
                 while (a + nb < cur.n && sel4(cur.r, a + nb) == row) ++nb;
@@ -704,6 +780,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
                 }
                 a += nb;
                 s = 0;
+                }
             }
             const int64_t off = (int64_t)s * TK * 2;
             const char *const sa[1] = {a_tile + off};
@@ -808,6 +885,13 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     auto c_load_group = [&](int k) __attribute__((always_inline)) -> Group {
         Group g;
         g.u = group_of(k);
+        if constexpr (PAIRS) {
+            g.n = g.u < 0 ? 0 : 1;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) g.r[b] = g.c[b] = 0;
+            g.c[0] = P.mv.units[g.u < 0 ? 0 : g.u];
+            return g;
+        }
         const int e0 = (g.u < 0 ? 0 : g.u) * GB;
         g.n = g.u < 0 ? 0 : (nnz - e0 < GB ? nnz - e0 : GB);
 #pragma unroll
@@ -840,6 +924,51 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
         nxt = c_load_group(k + 1);                      // in flight during this group's tiles
         int ngr[4] = {0, 0, 0, 0}, ngc[4] = {0, 0, 0, 0};
         int a = 0;
+        if constexpr (PAIRS) {
+            // one unit = one tile
+            const int ent = gc[0], kind = (ent >> 30) & 3, x = (ent >> 16) & 255, y = (ent >> 8) & 255, z = ent & 255;
+            cw.zero();
+            if (!started) {
+                started = true;
+                __builtin_amdgcn_s_barrier();           // slice 0 is in place
+                cw.first(stage_ptr(0));
+            }
+            if (kind == kUnitTall) {
+                for (int s = 0; s < nsteps; ++s) {
+                    cw.template slice<true>(stage_ptr(st0), stage_ptr(st1));
+                    const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+                }
+            } else {
+                for (int s = 0; s < nsteps; ++s) {
+                    cw.slice(stage_ptr(st0), stage_ptr(st1));
+                    const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_only(0));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) { ngr[b] = uni(nxt.r[b]); ngc[b] = uni(nxt.c[b]); }
+            if (kind == kUnitTall) {
+                // sub-tile (wm, wn) of the tile [W panel x] x [dY panels y, z] is, transposed, rows [32 r, 32 r + 32)
+                // of block row (wn ? z : y) and columns [64 wm, 64 wm + 64) of block column x
+                char *const c_blk = P.C + ((int64_t)(wn ? z : y) * 128) * ldc + ((int64_t)x * 128 + wm * WTM) * ESZ;
+                auto dst_t = [&](int r, int pj) __attribute__((always_inline)) -> char * {
+                    return c_blk + (int64_t)(r * 32) * ldc + pj * 128;
+                };
+                cw.store_t(reg, scale, ldc, dst_t);
+            } else {
+                char *const c_rows = P.C + ((int64_t)x * 128 + wm * WTM) * ldc;
+                const int cols_valid = kind == kUnitSingle ? 128 : 256;
+                auto dst = [&](int mi, int nj, int64_t &gcol0) __attribute__((always_inline)) -> char * {
+                    const int col_t = wn * WTN + nj * (128 / ESZ);         // first column of the piece, in the tile
+                    if (col_t >= cols_valid) return nullptr;
+                    const int64_t col0 = (int64_t)(col_t < 128 ? y : z) * 128 + (col_t & 127);
+                    gcol0 = col0;
+                    return c_rows + (int64_t)(mi * 32) * ldc + col0 * ESZ;
+                };
+                cw.template finish<kTailNone>(reg, scale, ldc, tl, dst);
+            }
+            (void)a;
+        } else
         while (a < gn) {
             const int row = sel4(gr, a);
             int nb = 1;
@@ -891,10 +1020,10 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     }
 }
 
-template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN>
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN, bool PAIRS = false>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
 {
-    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL, RAGN>(P, gridDim.x, blockIdx.x);
+    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL, RAGN, PAIRS>(P, gridDim.x, blockIdx.x);
 }
 
 // Both gradients of the layer in one launch (eq. 2 and eq. 3 share dY and the mask and do not
@@ -903,11 +1032,11 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
 // workgroups leave: no launch boundary (about 5 us of idle chip between dependent launches) and no
 // idle tail between the two.  The dX workgroups come first, so dX workgroup w is workgroup w of
 // the launch and runs on XCD w % 8, which its schedule assumes; the dW schedule assumes nothing.
-template <class T, class OutDX, class OutDW, int TN_DX>
+template <class T, class OutDX, class OutDW, int TN_DX, bool PAIRS = false>
 __global__ __launch_bounds__(512) void bwd_fused_kernel(GemmParams Pdx, GemmParams Pdw, int g_dx)
 {
     if ((int)blockIdx.x < g_dx)
-        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, kTailNone>(Pdx, g_dx, (int)blockIdx.x);
+        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, kTailNone, false, PAIRS>(Pdx, g_dx, (int)blockIdx.x);
     else
         gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, kTailNone>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
 }

@@ -116,11 +116,11 @@ struct SeededGrid {
     }
 
     // ---- the mask object, in pieces ----
-    // Piece numbers: 0 = header, bits, col_ptr, col_order; 1 = row_ptr, row_order; then one per block row (its part of
-    // col_idx / blk_row), one per block column (its part of row_idx), one per group of 8 block rows (its part of
-    // loc_row / loc_col).  Every piece is computed from the registers alone and writes a part of the object that no
+    // Piece numbers: 0 = header, bits, col_ptr, col_order; 1 = row_ptr, row_order; 2 = the pair list and its length
+    // in the header; then one per block row (its part of col_idx / blk_row), one per block column (its part of
+    // row_idx), one per group of 8 block rows (its part of loc_row / loc_col).  Every piece is computed from the registers alone and writes a part of the object that no
     // other piece writes; the result is what sdrop_mask builds (same lists, same tie-breaking).
-    __device__ __forceinline__ int pieces() const { return 2 + MB + KB + (MB + 7) / 8; }
+    __device__ __forceinline__ int pieces() const { return 3 + MB + KB + (MB + 7) / 8; }
 
     // exclusive prefix sums of the rows' kept counts, for this lane's two rows; total = number of kept blocks
     __device__ __forceinline__ void row_starts(int (&start)[2], int &total) const
@@ -175,8 +175,20 @@ struct SeededGrid {
                 h.p = P.p_call;
                 h.seed = ((uint64_t)P.key1 << 32) | P.key0;
                 h.rng_stream = ((uint64_t)P.ctr3 << 32) | P.ctr2;
-                *const_cast<MaskHeader *>(mv.hdr) = h;
+                // everything but n_units, which piece 2 writes
+                const uint64_t *const src = reinterpret_cast<const uint64_t *>(&h);
+                uint64_t *const dst = reinterpret_cast<uint64_t *>(const_cast<MaskHeader *>(mv.hdr));
+                static_assert(offsetof(MaskHeader, n_units) == 80, "the header's eleventh 8 bytes hold n_units");
+#pragma unroll
+                for (int q = 0; q < 32; ++q)
+                    if (q != 10) dst[q] = src[q];
+                reinterpret_cast<int32_t *>(dst)[21] = 0;
             }
+            return;
+        }
+        if (piece == 2) {
+            const int n = build_units(rw[0], rw[1], MB, const_cast<int32_t *>(mv.units));
+            if (lane == 0) reinterpret_cast<int32_t *>(const_cast<MaskHeader *>(mv.hdr))[20] = n;
             return;
         }
         int start[2], total;
@@ -188,7 +200,7 @@ struct SeededGrid {
             if (lane == 0) row_ptr[MB] = total;
             return;
         }
-        piece -= 2;
+        piece -= 3;
         if (piece < MB) {
             // block row `piece`: lane <-> block column
             const uint64_t word = row_word(piece);

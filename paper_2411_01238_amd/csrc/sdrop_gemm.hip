@@ -183,6 +183,18 @@ int g_dx_persistent_groups_per_cu = 8;
 // dropped) 215 against 190; 9.6 (65536 x 4096 x 1024, 0.7 dropped) 235 against 270; 22 (the same,
 // 0.3 dropped) 410 against 417.
 int g_dx_tile_width = 0;    // 0: chosen per call; 128 or 256: forced (benchmarks and tests)
+// The pair list (see build_units): every unit is a 128 x 256 tile of two kept blocks, from the same block row or
+// the same block column, so no tile is cut and (almost) none is half empty: ceil(kept / 2) equal tiles, each
+// about 1.6 single-block tiles long.  Needs 128 x 128 blocks, a grid the list exists for, whole slices, no tail,
+// dY and W with the same row stride, and a drawn mask (a caller's own bits may pair badly: a diagonal has no pairs
+// at all and every unit would cost a tile of two).  Taken in place of single-block tiles where those would fill the
+// chip (at least 1.5 kept blocks per CU) and rows hold enough blocks to pair.  Measured at 4096^3 (dX alone /
+// sdrop_bwd, pairs against what the plan took before): half dropped, 511 blocks, 63 against 68 us / 123 against 130;
+// 0.7 dropped, 281 blocks, 49 against 47 / 89 against 87 (the chip is power bound, so single tiles on a chip that
+// is not full run at a higher clock: the second round of 25 tiles costs far less than the first of 256); at 0.3
+// dropped and below the plan takes 256-wide tiles of one block row, which the pair list equals (98 against 94 / 180
+// against 180).
+int g_dx_pairs = 0;         // 0: chosen per call; 1: wherever it applies; 2: never
 DxPlan dx_plan(const GemmParams &P)
 {
     const double kept = (1.0 - P.p) * (double)P.MB * (double)P.KB;
@@ -205,11 +217,22 @@ DxPlan dx_plan(const GemmParams &P)
     if (has_tail(P)) plan.TN = 128;
     const int G_ = plan.TN / P.BK;
     plan.persistent = P.BM == 128 && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu);
+    plan.pairs = false;
+    const bool pairs_apply = P.BM == 128 && P.BK == 128 && units_apply(P.MB, P.KB) && P.N % TK == 0 && !has_tail(P) &&
+                             P.lda == P.ldb && !P.kept_given && g_dx_tile_width == 0;
+    if (pairs_apply && g_dx_pairs != 2) {
+        if (g_dx_pairs == 1 || (plan.TN == 128 && plan.persistent && kept >= 1.5 * ncu && (1.0 - P.p) * P.KB >= 4.0)) {
+            plan.pairs = true;
+            plan.TN = 256;
+            plan.persistent = true;
+        }
+    }
     return plan;
 }
 
 // dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on (see dispatch_tile)
-bool dw64_persistent(const GemmParams &P) { return (1.0 - P.p) * P.MB / P.splits * (P.BM / 64) >= 16.0; }
+int g_dw64_persistent_slices = 16;
+bool dw64_persistent(const GemmParams &P) { return (1.0 - P.p) * P.MB / P.splits * (P.BM / 64) >= (double)g_dw64_persistent_slices; }
 
 namespace {
 
@@ -249,6 +272,7 @@ GemmParams base_params(int op, const void *a, const void *b, const void *mask, v
     P.threshold = 0;
     P.p_call = p;
     P.status = device_status_word();
+    P.kept_given = false;
     return P;
 }
 
@@ -330,7 +354,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
         if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
         // the kernel choice goes by the expected share of kept blocks: the caller's figure where given (a mask built
         // from the caller's own bits need not have the density 1 - p), else 1 - p
-        if (epi->kept_fraction > 0.0) P.p = 1.0 - (epi->kept_fraction < 1.0 ? epi->kept_fraction : 1.0);
+        if (epi->kept_fraction > 0.0) { P.p = 1.0 - (epi->kept_fraction < 1.0 ? epi->kept_fraction : 1.0); P.kept_given = true; }
         P.bias = epi->bias;
         P.aux = static_cast<const char *>(epi->relu_mask);
         P.act = epi->act;
@@ -450,8 +474,9 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
         const bool split = Pdw.splits > 1;
         if (split) { Pdw.C = static_cast<char *>(ws); Pdw.ldc = N * 4; Pdw.scale = 1.0f; }
         const bool o32 = out_dtype == SDROP_F32;
-        const int rf = dtype == SDROP_F16 ? bwd_fused_typed<F16>(form, plan.TN, o32, split, Pdx, Pdw, n_dx, st)
-                                          : bwd_fused_typed<BF16>(form, plan.TN, o32, split, Pdx, Pdw, n_dx, st);
+        const int tn = plan.pairs ? kTNPairs : plan.TN;
+        const int rf = dtype == SDROP_F16 ? bwd_fused_typed<F16>(form, tn, o32, split, Pdx, Pdw, n_dx, st)
+                                          : bwd_fused_typed<BF16>(form, tn, o32, split, Pdx, Pdw, n_dx, st);
         if (rf != -1) {     // -1: the device does not grant the LDS; fall through to the two calls
             if (rf != SDROP_OK || !split) return rf;
             return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, N, lds[4], Pdw);
@@ -560,6 +585,14 @@ int sdrop_set_tuning(int knob, int value)
     }
     if (knob == SDROP_TUNE_FWD_SEEDED && (value == 0 || value == 1)) {
         sdrop::g_fwd_seeded = value;
+        return SDROP_OK;
+    }
+    if (knob == SDROP_TUNE_DX_PAIRS && value >= 0 && value <= 2) {
+        sdrop::g_dx_pairs = value;
+        return SDROP_OK;
+    }
+    if (knob == SDROP_TUNE_DW64_PERSISTENT_SLICES && value >= 0) {
+        sdrop::g_dw64_persistent_slices = value;
         return SDROP_OK;
     }
     if (knob == SDROP_TUNE_DX_PERSISTENT_GROUPS_PER_CU && value >= 0) {

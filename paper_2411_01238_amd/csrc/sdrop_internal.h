@@ -21,7 +21,8 @@ struct MaskHeader {
     double p;                // 56: the dropout probability the mask was drawn with (0 when built from given bits)
     uint64_t seed;           // 64
     uint64_t rng_stream;     // 72
-    int32_t pad_[44];
+    int32_t n_units;         // 80: entries of the pair list (0 when the grid is too large for one)
+    int32_t pad_[43];
 };
 static_assert(sizeof(MaskHeader) == 256, "mask header is 256 bytes");
 static_assert(offsetof(MaskHeader, nnz) == SDROP_MASK_NNZ_OFFSET, "nnz offset is part of the ABI");
@@ -48,6 +49,7 @@ struct MaskView {
     const int32_t *row_ptr, *col_idx, *blk_row;
     const int32_t *col_ptr, *row_idx, *row_order, *col_order;
     const int32_t *loc_row, *loc_col;
+    const int32_t *units;
 };
 
 inline MaskView make_view(const void *mask, const sdrop_mask_layout_t &L)
@@ -65,6 +67,7 @@ inline MaskView make_view(const void *mask, const sdrop_mask_layout_t &L)
     v.col_order = reinterpret_cast<const int32_t *>(b + L.off_col_order);
     v.loc_row = reinterpret_cast<const int32_t *>(b + L.off_loc_row);
     v.loc_col = reinterpret_cast<const int32_t *>(b + L.off_loc_col);
+    v.units = reinterpret_cast<const int32_t *>(b + L.off_units);
     return v;
 }
 
@@ -85,6 +88,90 @@ __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint3
         k0 += BUMP0; k1 += BUMP1;   // the bump after the last round is unused
     }
     return c0;
+}
+
+// ---- The pair list: the kept blocks of a small grid (at most 128 x 64 blocks) as units of two ----
+// eq. (2) computes kept blocks only, and a 128 x 256 tile of two kept blocks costs about 1.6 single 128 x 128 tiles.
+// Two kept blocks can share a tile when they share the block row (a wide pair: one dY panel against two W panels)
+// or the block column (a tall pair: two dY panels against one W panel, computed as the transposed product).
+// The list partitions the kept blocks into such pairs and as few single blocks as it can:
+//   rows in ascending order; a row with an odd number of kept blocks gives one of them away: if it keeps a column
+//   in which an earlier row's block is still waiting, the lowest such column, and the two form a tall pair; else
+//   its own highest kept column, where the block waits.  The rest of a row pairs up left to right.  Blocks
+//   still waiting after the last row are singles.
+// Order of the list: the wide pairs row by row, the tall pairs in the order they were closed, the singles by column.
+// An entry is kind << 30 | x << 16 | y << 8 | z: wide (i, j1, j2), tall (j, i1, i2), single (i, j, j).
+constexpr int kUnitWide = 0, kUnitTall = 1, kUnitSingle = 2;
+constexpr int kUnitsMaxMB = 128, kUnitsMaxKB = 64;
+__host__ __device__ inline bool units_apply(int64_t MB, int64_t KB) { return MB <= kUnitsMaxMB && KB <= kUnitsMaxKB; }
+__device__ __forceinline__ int32_t unit_entry(int kind, int x, int y, int z) { return (int32_t)((uint32_t)kind << 30 | (uint32_t)x << 16 | (uint32_t)y << 8 | (uint32_t)z); }
+
+// Called by all 64 lanes of one wavefront; lane l passes the keep words of block rows l and l + 64 (0 beyond the
+// grid).  Writes the list and returns its length (the same value in every lane).
+__device__ inline int build_units(uint64_t rw0, uint64_t rw1, int MB, int32_t *units)
+{
+    const int lane = threadIdx.x & 63;
+    // where each row's wide pairs go: a row has floor(kept / 2) of them whichever block it gives away
+    const int np0 = __popcll(rw0) >> 1, np1 = __popcll(rw1) >> 1;
+    int inc0 = np0, inc1 = np1;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int u0 = __shfl_up(inc0, d, 64), u1 = __shfl_up(inc1, d, 64);
+        if (lane >= d) { inc0 += u0; inc1 += u1; }
+    }
+    const int tot0 = __shfl(inc0, 63, 64);
+    const int n_wide = tot0 + __shfl(inc1, 63, 64);
+    const int off0 = inc0 - np0, off1 = tot0 + inc1 - np1;
+    // the rows in turn (uniform: every lane follows the same chain; lane c remembers the row waiting in column c,
+    // lane i % 64 the column row i gave away)
+    const uint32_t lo0 = (uint32_t)rw0, hi0 = (uint32_t)(rw0 >> 32), lo1 = (uint32_t)rw1, hi1 = (uint32_t)(rw1 >> 32);
+    uint64_t waiting = 0;
+    int pend = 0, gave0 = -1, gave1 = -1, n_tall = 0;
+    for (int i = 0; i < MB; ++i) {
+        const int src = i & 63;
+        const uint32_t lo = i < 64 ? __builtin_amdgcn_readlane(lo0, src) : __builtin_amdgcn_readlane(lo1, src);
+        const uint32_t hi = i < 64 ? __builtin_amdgcn_readlane(hi0, src) : __builtin_amdgcn_readlane(hi1, src);
+        const uint64_t w = (uint64_t)hi << 32 | lo;
+        if (!(__popcll(w) & 1)) continue;
+        const uint64_t hit = w & waiting;
+        int c;
+        if (hit) {
+            c = __builtin_ctzll(hit);
+            const int i1 = __builtin_amdgcn_readlane(pend, c);
+            if (lane == 0) units[n_wide + n_tall] = unit_entry(kUnitTall, c, i1, i);
+            ++n_tall;
+            waiting ^= uint64_t(1) << c;
+        } else {
+            c = 63 - __builtin_clzll(w);
+            waiting |= uint64_t(1) << c;
+            if (lane == c) pend = i;
+        }
+        if (lane == src) { if (i < 64) gave0 = c; else gave1 = c; }
+    }
+    int n_single = 0;
+    while (waiting) {
+        const int c = __builtin_ctzll(waiting);
+        waiting &= waiting - 1;
+        const int i1 = __builtin_amdgcn_readlane(pend, c);
+        if (lane == 0) units[n_wide + n_tall + n_single] = unit_entry(kUnitSingle, i1, c, c);
+        ++n_single;
+    }
+    // every lane writes the wide pairs of its two rows
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint64_t w = h ? rw1 : rw0;
+        const int gave = h ? gave1 : gave0, i = lane + 64 * h;
+        int at = h ? off1 : off0;
+        if (gave >= 0) w &= ~(uint64_t(1) << gave);
+        while (w) {
+            const int j1 = __builtin_ctzll(w);
+            w &= w - 1;
+            const int j2 = __builtin_ctzll(w);
+            w &= w - 1;
+            units[at++] = unit_entry(kUnitWide, i, j1, j2);
+        }
+    }
+    return n_wide + n_tall + n_single;
 }
 
 // Host-side argument checks shared by the GEMM entry points.

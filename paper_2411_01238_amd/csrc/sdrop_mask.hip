@@ -34,7 +34,7 @@ constexpr int kMaxBins = 4096;   // histogram bins of the descending-count sort
 struct MaskParams {
     MaskHeader *hdr;
     uint64_t *bits;
-    int32_t *row_ptr, *col_idx, *blk_row, *col_ptr, *row_idx, *row_order, *col_order, *loc_row, *loc_col;
+    int32_t *row_ptr, *col_idx, *blk_row, *col_ptr, *row_idx, *row_order, *col_order, *loc_row, *loc_col, *units;
     const uint64_t *given_bits;      // non-null: take the bits from here instead of drawing
     int64_t M, K;
     int32_t BM, BK, MB, KB, wpr;
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
     __shared__ __attribute__((aligned(16))) int32_t s_rcnt[kSmallN], s_ccnt[kSmallN];
     __shared__ __attribute__((aligned(16))) int32_t s_rkey[kSmallN], s_ckey[kSmallN];   // sort keys, see phase 2
     __shared__ int32_t s_row_ptr[kSmallN + 1], s_col_ptr[kSmallN + 1];
-    __shared__ int32_t s_max[2];
+    __shared__ int32_t s_max[2], s_nunits;
     const int lane = lane_id(), wave = wave_id();
     const int nwords = P.MB * P.wpr;
 
@@ -445,6 +445,13 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
     if (first_wg) {
         for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
         for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = s_col_ptr[j];
+        // the pair list (grids of at most 128 x 64 blocks: a block row is one word), by the last wavefront
+        if (wave == kMaskWaves - 1) {
+            int n = 0;
+            if (units_apply(P.MB, P.KB))
+                n = build_units(lane < P.MB ? s_bits[lane] : 0, lane + 64 < P.MB ? s_bits[lane + 64] : 0, P.MB, P.units);
+            if (lane == 0) s_nunits = n;
+        }
     }
     // The three kinds of lists do not depend on each other.  One workgroup: with few groups of 8 block rows (a small
     // grid) the locally ordered list would keep only that many wavefronts busy, on top of their share of the other
@@ -480,6 +487,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         }
     }
     if (!first_wg) return;
+    __syncthreads();                                   // s_nunits
     if (threadIdx.x == 0) {
         MaskHeader h = {};
         h.M = P.M; h.K = P.K; h.BM = P.BM; h.BK = P.BK; h.MB = P.MB; h.KB = P.KB;
@@ -488,6 +496,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
         h.magic = kMaskMagic;
         h.max_row_cnt = s_max[0];
         h.max_col_cnt = s_max[1];
+        h.n_units = s_nunits;
         if (!P.given_bits) { h.flags = kMaskDrawn; h.p = P.p; h.seed = P.seed; h.rng_stream = P.rng_stream; }
         *P.hdr = h;
     }
@@ -523,6 +532,7 @@ int launch_mask(void *mask, size_t mask_bytes, int64_t M, int64_t K, int BM, int
     P.col_order = reinterpret_cast<int32_t *>(b + L.off_col_order);
     P.loc_row = reinterpret_cast<int32_t *>(b + L.off_loc_row);
     P.loc_col = reinterpret_cast<int32_t *>(b + L.off_loc_col);
+    P.units = reinterpret_cast<int32_t *>(b + L.off_units);
     P.given_bits = given_bits;
     P.M = M; P.K = K; P.BM = BM; P.BK = BK;
     P.MB = static_cast<int32_t>(L.MB); P.KB = static_cast<int32_t>(L.KB);
@@ -601,6 +611,7 @@ int sdrop_mask_layout(int64_t M, int64_t K, int BM, int BK, sdrop_mask_layout_t 
     out->off_col_order = off; off = sdrop::align_up(off + 4 * KB, 256);
     out->off_loc_row = off;   off = sdrop::align_up(off + 4 * nblk, 256);
     out->off_loc_col = off;   off = sdrop::align_up(off + 4 * nblk, 256);
+    out->off_units = off;     off = sdrop::align_up(off + 4 * nblk, 256);
     out->total_bytes = off;
     out->MB = MB; out->KB = KB; out->words_per_row = wpr;
     return SDROP_OK;

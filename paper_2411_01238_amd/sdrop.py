@@ -20,6 +20,7 @@ OK, EINVAL, ESHAPE, EDTYPE, EALIGN, EWORKSPACE, EHIP = range(7)
 F16, BF16, F32 = 0, 1, 2
 OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
 MASK_NNZ_OFFSET = 36
+MASK_NUNITS_OFFSET = 80
 
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_status", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_mask_bits", "sdrop_workspace_bytes",
@@ -45,7 +46,7 @@ class SdropError(RuntimeError):
 class MaskLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
                 ("total_bytes", "off_bits", "off_row_ptr", "off_col_idx", "off_blk_row",
-                 "off_col_ptr", "off_row_idx", "off_row_order", "off_col_order", "off_loc_row", "off_loc_col")] + \
+                 "off_col_ptr", "off_row_idx", "off_row_order", "off_col_order", "off_loc_row", "off_loc_col", "off_units")] + \
                [(n, ctypes.c_int64) for n in ("MB", "KB", "words_per_row")]
 
 
@@ -127,6 +128,8 @@ DX_PERSISTENT_GROUPS_PER_CU_DEFAULT = 8
 TUNE_BWD_FUSED = 1
 TUNE_DX_TILE_WIDTH = 2
 TUNE_FWD_SEEDED = 3
+TUNE_DW64_PERSISTENT_SLICES = 4
+TUNE_DX_PAIRS = 5
 
 
 def set_tuning(knob, value):
@@ -212,6 +215,10 @@ class Mask:
     def nnz(self):
         return int(self.buf[MASK_NNZ_OFFSET:MASK_NNZ_OFFSET + 4].view(torch.int32).item())
 
+    def n_units(self):
+        """Entries of the pair list (0 for grids it is not built for)."""
+        return int(self.buf[MASK_NUNITS_OFFSET:MASK_NUNITS_OFFSET + 4].view(torch.int32).item())
+
     def bits(self):
         L = self.layout
         n = self.MB * int(L.words_per_row)
@@ -230,6 +237,7 @@ class Mask:
             "col_order": self._i32(L.off_col_order, self.KB),
             "loc_row": self._i32(L.off_loc_row, nnz),
             "loc_col": self._i32(L.off_loc_col, nnz),
+            "units": self._i32(L.off_units, self.n_units()),
         }
 
 

@@ -76,3 +76,49 @@ def lists_from_keep(keep):
     return {"row_ptr": row_ptr, "col_idx": cols.astype(np.int32), "blk_row": rows.astype(np.int32),
             "col_ptr": col_ptr, "row_idx": ccols.astype(np.int32),
             "loc_row": rows[o].astype(np.int32), "loc_col": cols[o].astype(np.int32)}
+
+
+UNIT_WIDE, UNIT_TALL, UNIT_SINGLE = 0, 1, 2
+
+
+def units_from_keep(keep):
+    """The pair list of a mask object (grids of at most 128 x 64 blocks), by the rule the library documents:
+    rows in ascending order; a row with an odd number of kept blocks gives one away, the lowest column in which
+    an earlier row's block is still waiting (the two form a tall pair), else its own highest kept column, where
+    the block then waits; the rest of the row pairs up left to right; what still waits at the end is single.
+    Listed as wide pairs row by row, tall pairs in the order they were closed, singles by column.
+    Entries are (kind, x, y, z): wide (i, j1, j2), tall (j, i1, i2), single (i, j, j)."""
+    keep = np.asarray(keep, dtype=np.uint8)
+    MB, KB = keep.shape
+    wide, tall, waiting = [], [], {}
+    for i in range(MB):
+        cols = [int(j) for j in np.nonzero(keep[i])[0]]
+        if len(cols) % 2:
+            hits = [j for j in cols if j in waiting]
+            if hits:
+                c = hits[0]
+                tall.append((UNIT_TALL, c, waiting.pop(c), i))
+            else:
+                c = cols[-1]
+                waiting[c] = i
+            cols.remove(c)
+        wide += [(UNIT_WIDE, i, cols[t], cols[t + 1]) for t in range(0, len(cols), 2)]
+    single = [(UNIT_SINGLE, waiting[c], c, c) for c in sorted(waiting)]
+    return wide + tall + single
+
+
+def decode_units(entries):
+    return [((int(e) >> 30) & 3, (int(e) >> 16) & 255, (int(e) >> 8) & 255, int(e) & 255) for e in entries]
+
+
+def blocks_of_units(units):
+    """The kept blocks a pair list covers, as a list of (i, j) with repetitions kept."""
+    out = []
+    for kind, x, y, z in units:
+        if kind == UNIT_WIDE:
+            out += [(x, y), (x, z)]
+        elif kind == UNIT_TALL:
+            out += [(y, x), (z, x)]
+        else:
+            out.append((x, y))
+    return out

@@ -1,0 +1,186 @@
+"""GPU parity for eq. (2) of arxiv 2411.01238 (Section 3.1) computed on tiles of two kept blocks: the mask
+object's pair list (a schedule: any partition of the kept blocks into pairs that share a block row or a block
+column, and single blocks, is valid; the library documents the one it builds) and the kernels that walk it."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdrop_oracle as orc
+from paper_2411_01238_amd import sdrop
+from paper_2411_01238_amd.workloads import WORKLOADS, make_inputs
+from _util import (f64, assert_tight, assert_bf16_rounding_of, units_from_keep, decode_units, blocks_of_units,
+                   UNIT_WIDE, UNIT_TALL, UNIT_SINGLE)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _knobs_back():
+    yield
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 0)
+    sdrop.set_tuning(sdrop.TUNE_BWD_FUSED, 1)
+
+
+def _check_units(m, keep):
+    torch.cuda.synchronize()
+    MB, KB = keep.shape
+    got = decode_units(m.lists()["units"].cpu().numpy())
+    if MB > 128 or KB > 64:
+        assert m.n_units() == 0
+        return
+    # valid whatever rule built it: every kept block exactly once, pairs share a row or a column
+    for kind, x, y, z in got:
+        assert kind in (UNIT_WIDE, UNIT_TALL, UNIT_SINGLE)
+        if kind == UNIT_WIDE:
+            assert y < z
+        elif kind == UNIT_TALL:
+            assert y < z
+        else:
+            assert y == z
+    blocks = blocks_of_units(got)
+    kept = sorted((int(i), int(j)) for i, j in zip(*np.nonzero(keep)))
+    assert sorted(blocks) == kept
+    # and it is the documented list
+    assert got == units_from_keep(keep)
+
+
+GRIDS = [(32, 32), (8, 8), (128, 64), (127, 63), (65, 33), (1, 64), (128, 1), (3, 5), (64, 64), (100, 16)]
+
+
+@pytest.mark.parametrize("MB,KB", GRIDS)
+@pytest.mark.parametrize("p", [0.0, 0.3, 0.5, 0.9, 1.0])
+def test_pair_list_of_a_drawn_mask(MB, KB, p):
+    print("pair list of a drawn mask", MB, KB, p, flush=True)
+    m = sdrop.sdrop_mask(MB * 128, KB * 128, 128, 128, p, 11, 3)
+    _check_units(m, orc.mask(MB, KB, p, 11, 3))
+
+
+def test_pair_list_is_absent_on_larger_grids():
+    for MB, KB in ((129, 8), (8, 65), (512, 32)):
+        m = sdrop.sdrop_mask(MB * 64, KB * 64, 64, 64, 0.5, 0, 0)
+        _check_units(m, orc.mask(MB, KB, 0.5, 0, 0))
+
+
+def _mask_of(keep, p):
+    MB, KB = keep.shape
+    words = orc.pack_bits(keep).view(np.int64).reshape(MB, -1)
+    return sdrop.sdrop_mask_from_bits(MB * 128, KB * 128, 128, 128, p, torch.from_numpy(words.copy()).cuda())
+
+
+def _structured(kind, MB, KB):
+    keep = np.zeros((MB, KB), dtype=np.uint8)
+    if kind == "diagonal":
+        for i in range(MB):
+            keep[i, i % KB] = 1
+    elif kind == "one_column":
+        keep[:, KB // 2] = 1
+    elif kind == "one_row":
+        keep[MB // 2, :] = 1
+    elif kind == "all":
+        keep[:] = 1
+    elif kind == "checker":
+        keep[::2, ::2] = 1
+        keep[1::2, 1::2] = 1
+    elif kind == "odd_rows":       # every row holds three blocks: every row gives one away
+        for i in range(MB):
+            for t in range(3):
+                keep[i, (i * 5 + t * 3) % KB] = 1
+    return keep
+
+
+@pytest.mark.parametrize("kind", ["diagonal", "one_column", "one_row", "all", "checker", "odd_rows", "none"])
+def test_pair_list_of_given_bits(kind):
+    print("pair list of given bits", kind, flush=True)
+    keep = _structured(kind, 12, 10)
+    _check_units(_mask_of(keep, 0.5), keep)
+
+
+def _dx_case(M, K, N, p, dtype, keep=None, seed=5):
+    g = torch.Generator().manual_seed(seed)
+    dY = torch.randn((M, N), generator=g, dtype=torch.float64).to(dtype)
+    W = torch.randn((K, N), generator=g, dtype=torch.float64).to(dtype)
+    X = torch.randn((M, K), generator=g, dtype=torch.float64).to(dtype)
+    MB, KB = M // 128, K // 128
+    if keep is None:
+        keep = orc.mask(MB, KB, p, 21, 2)
+        m = sdrop.sdrop_mask(M, K, 128, 128, p, 21, 2)
+    else:
+        m = _mask_of(keep, p)
+    return dY, W, X, keep, m
+
+
+CASES = [
+    # M, K, N, p, dtype
+    (1024, 1024, 256, 0.5, torch.bfloat16),
+    (2048, 1024, 192, 0.3, torch.float16),       # three slices
+    (1024, 2048, 64, 0.7, torch.bfloat16),       # one slice
+    (128 * 20, 128 * 9, 320, 0.5, torch.bfloat16),
+    (128 * 9, 128 * 20, 128, 0.9, torch.float16),
+    (128 * 128, 128 * 4, 64, 0.5, torch.bfloat16),   # the tallest grid the list is built for
+    (128 * 4, 128 * 64, 64, 0.5, torch.float16),     # the widest
+    (1024, 1024, 256, 0.0, torch.bfloat16),
+    (1024, 1024, 256, 1.0, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("M,K,N,p,dtype", CASES)
+@pytest.mark.parametrize("out32", [True, False])
+def test_dx_on_pairs_matches_oracle(M, K, N, p, dtype, out32):
+    print("dX on pairs", M, K, N, p, dtype, out32, flush=True)
+    dY, W, X, keep, m = _dx_case(M, K, N, p, dtype)
+    ref = orc.bwd_dx(f64(dY), f64(W), keep, 128, 128, p)
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 1)
+    sdrop.status()                                     # (clears what an earlier test's foreign mask left)
+    od = torch.float32 if out32 else dtype
+    got = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=od)
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 2)
+    plain = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=od)
+    torch.cuda.synchronize()
+    assert sdrop.status() == 0
+    if out32:
+        assert_tight(f64(got), ref, "dX on pairs")
+    elif dtype == torch.bfloat16:
+        assert_bf16_rounding_of(f64(got), ref, "dX on pairs")
+    else:
+        assert_tight(f64(got), ref, "dX on pairs", tol=1e-3)
+    # same products summed in the same order, whichever tile a block is computed in
+    assert torch.equal(got, plain)
+
+
+@pytest.mark.parametrize("kind", ["diagonal", "one_column", "one_row", "all", "checker", "odd_rows", "none"])
+def test_dx_on_pairs_of_given_bits(kind):
+    print("dX on pairs of given bits", kind, flush=True)
+    keep = _structured(kind, 12, 10)
+    dY, W, X, keep, m = _dx_case(12 * 128, 10 * 128, 128, 0.5, torch.bfloat16, keep=keep)
+    ref = orc.bwd_dx(f64(dY), f64(W), keep, 128, 128, 0.5)
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 1)
+    got = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_tight(f64(got), ref, "dX on pairs, " + kind)
+
+
+@pytest.mark.parametrize("M,K,N,p,dtype", [(2048, 2048, 256, 0.5, torch.bfloat16), (128 * 20, 128 * 9, 512, 0.3, torch.float16)])
+def test_one_launch_backward_on_pairs(M, K, N, p, dtype):
+    print("sdrop_bwd on pairs", M, K, N, p, dtype, flush=True)
+    dY, W, X, keep, m = _dx_case(M, K, N, p, dtype)
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 1)
+    dX, dW = sdrop.sdrop_bwd(dY.cuda(), W.cuda(), X.cuda(), m, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_tight(f64(dX), orc.bwd_dx(f64(dY), f64(W), keep, 128, 128, p), "dX of sdrop_bwd on pairs")
+    assert_tight(f64(dW), orc.bwd_dw(f64(X), f64(dY), keep, 128, 128, p), "dW of sdrop_bwd on pairs")
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 2)
+    dX2, dW2 = sdrop.sdrop_bwd(dY.cuda(), W.cuda(), X.cuda(), m, out_dtype=torch.float32)
+    assert torch.equal(dX, dX2) and torch.equal(dW, dW2)
+
+
+def test_pairs_are_not_used_with_unequal_strides_or_a_stated_kept_share():
+    """Where the pair list does not apply the call runs as before (same result, no error)."""
+    dY, W, X, keep, m = _dx_case(1024, 1024, 256, 0.5, torch.bfloat16)
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 1)
+    ref = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=torch.float32)
+    wide = torch.zeros((1024, 512), dtype=torch.bfloat16, device="cuda")
+    wide[:, :256] = W.cuda()
+    got = sdrop.sdrop_bwd_dx_ex(dY.cuda(), wide[:, :256], m, out_dtype=torch.float32)
+    got2 = sdrop.sdrop_bwd_dx_ex(dY.cuda(), W.cuda(), m, out_dtype=torch.float32, kept_fraction=0.5)
+    torch.cuda.synchronize()
+    assert torch.equal(got, ref) and torch.equal(got2, ref)

@@ -18,7 +18,7 @@ from _util import f64, assert_close, assert_tight, lists_from_keep
 
 pytestmark = pytest.mark.gpu
 
-LISTS = ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx", "row_order", "col_order", "loc_row", "loc_col")
+LISTS = ("row_ptr", "col_idx", "blk_row", "col_ptr", "row_idx", "row_order", "col_order", "loc_row", "loc_col", "units")
 
 
 def _same_object(a, b, tag):
