@@ -35,7 +35,8 @@ inline int tail_mode(const GemmParams &P)
 
 // dX: width of the tiles, and whether the persistent kernel computes them (see sdrop_gemm.hip)
 struct DxPlan { int TN; bool persistent; bool pairs; };
-DxPlan dx_plan(const GemmParams &P);
+// fused: the plan is for sdrop_bwd's single launch, whose dW workgroups fill what dX's last round leaves idle
+DxPlan dx_plan(const GemmParams &P, bool fused = false);
 // dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on
 bool dw64_persistent(const GemmParams &P);
 

@@ -188,14 +188,16 @@ int g_dx_tile_width = 0;    // 0: chosen per call; 128 or 256: forced (benchmark
 // about 1.6 single-block tiles long.  Needs 128 x 128 blocks, a grid the list exists for, whole slices, no tail,
 // dY and W with the same row stride, and a drawn mask (a caller's own bits may pair badly: a diagonal has no pairs
 // at all and every unit would cost a tile of two).  Taken in place of single-block tiles where those would fill the
-// chip (at least 1.5 kept blocks per CU) and rows hold enough blocks to pair.  Measured at 4096^3 (dX alone /
+// chip (at least 1.5 kept blocks per CU) and rows hold enough blocks to pair: always in sdrop_bwd's single launch,
+// whose dW workgroups take the CUs that dX's last round leaves idle; on its own only where it is expected to finish
+// first.  Measured at 4096^3 (dX alone /
 // sdrop_bwd, pairs against what the plan took before): half dropped, 511 blocks, 63 against 68 us / 123 against 130;
 // 0.7 dropped, 281 blocks, 49 against 47 / 89 against 87 (the chip is power bound, so single tiles on a chip that
 // is not full run at a higher clock: the second round of 25 tiles costs far less than the first of 256); at 0.3
 // dropped and below the plan takes 256-wide tiles of one block row, which the pair list equals (98 against 94 / 180
 // against 180).
 int g_dx_pairs = 0;         // 0: chosen per call; 1: wherever it applies; 2: never
-DxPlan dx_plan(const GemmParams &P)
+DxPlan dx_plan(const GemmParams &P, bool fused)
 {
     const double kept = (1.0 - P.p) * (double)P.MB * (double)P.KB;
     const int ncu = cu_count();
@@ -221,7 +223,13 @@ DxPlan dx_plan(const GemmParams &P)
     const bool pairs_apply = P.BM == 128 && P.BK == 128 && units_apply(P.MB, P.KB) && P.N % TK == 0 && !has_tail(P) &&
                              P.lda == P.ldb && !P.kept_given && g_dx_tile_width == 0;
     if (pairs_apply && g_dx_pairs != 2) {
-        if (g_dx_pairs == 1 || (plan.TN == 128 && plan.persistent && kept >= 1.5 * ncu && (1.0 - P.p) * P.KB >= 4.0)) {
+        // in place of single-block tiles that would fill the chip; on its own also only where the tiles of two are
+        // expected to finish first (the kept count taken a standard deviation high: one tile more than the CUs can
+        // hold at once is a whole extra round), or where there are rounds enough for that not to matter
+        const double units_hi = kept / 2 + 2 + sqrt((double)P.MB * P.KB * P.p * (1.0 - P.p)) / 2;
+        const double rounds_pairs = (double)((int64_t)((units_hi + ncu - 1) / ncu));
+        const bool fills = plan.TN == 128 && plan.persistent && kept >= 1.5 * ncu && (1.0 - P.p) * P.KB >= 4.0;
+        if (g_dx_pairs == 1 || (fills && (fused || rounds_pairs >= 4 || rounds_pairs < rounds(128) * 0.6))) {
             plan.pairs = true;
             plan.TN = 256;
             plan.persistent = true;
@@ -453,7 +461,7 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
         Pdx.lda = lds[0] * 2; Pdx.ldb = lds[1] * 2; Pdx.ldc = lds[3] * esz_out;
         Pdw.lda = lds[2] * 2; Pdw.ldb = lds[0] * 2; Pdw.ldc = lds[4] * esz_out;
     }
-    const DxPlan plan = dx_plan(Pdx);
+    const DxPlan plan = dx_plan(Pdx, g_bwd_fused && N % 256 == 0 && BM == 128 && BK == 128);
     Pdw.splits = dw_splits(M, N, BM, BK, K);
     // Which single launch applies, if any (all need N to be a multiple of 256, so that neither product has a ragged edge):
     //   persistent dX + persistent dW                      128 x 128 blocks, dX on its persistent kernel
