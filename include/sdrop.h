@@ -128,8 +128,8 @@ int sdrop_last_hip_error(void);
  *            this list share block rows AND block columns, which is the order eq. 2
  *            computes them in (tiles that run at the same time then share operand
  *            tiles in cache)
- *   units    int32[n_units (room for MB*KB)], for grids of at most 128 x 64 blocks (n_units, the int32 at
- *            byte offset SDROP_MASK_NUNITS_OFFSET of the header, is 0 for larger grids): the kept blocks
+ *   units    int32[n_units (room for MB*KB)], for grids of at most 128 x 64 blocks of 128 x 128 (n_units, the
+ *            int32 at byte offset SDROP_MASK_NUNITS_OFFSET of the header, is 0 for other grids): the kept blocks
  *            once more, as pairs that can share an output tile of eq. 2, and the few blocks left over.
  *            An entry is kind << 30 | x << 16 | y << 8 | z with kind 0: blocks (x, y) and (x, z) of one
  *            block row; kind 1: blocks (y, x) and (z, x) of one block column; kind 2: block (x, y) alone.

@@ -187,7 +187,7 @@ struct SeededGrid {
             return;
         }
         if (piece == 2) {
-            const int n = build_units(rw[0], rw[1], MB, const_cast<int32_t *>(mv.units));
+            const int n = units_apply(MB, KB, P.BM, P.BK) ? build_units(rw[0], rw[1], MB, const_cast<int32_t *>(mv.units)) : 0;
             if (lane == 0) reinterpret_cast<int32_t *>(const_cast<MaskHeader *>(mv.hdr))[20] = n;
             return;
         }

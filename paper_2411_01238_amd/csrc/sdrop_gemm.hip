@@ -220,7 +220,7 @@ DxPlan dx_plan(const GemmParams &P, bool fused)
     const int G_ = plan.TN / P.BK;
     plan.persistent = P.BM == 128 && (G_ == 1 || kept / G_ >= (double)g_dx_persistent_groups_per_cu * ncu);
     plan.pairs = false;
-    const bool pairs_apply = P.BM == 128 && P.BK == 128 && units_apply(P.MB, P.KB) && P.N % TK == 0 && !has_tail(P) &&
+    const bool pairs_apply = units_apply(P.MB, P.KB, P.BM, P.BK) && P.N % TK == 0 && !has_tail(P) &&
                              P.lda == P.ldb && !P.kept_given && g_dx_tile_width == 0;
     if (pairs_apply && g_dx_pairs != 2) {
         // in place of single-block tiles that would fill the chip; on its own also only where the tiles of two are

@@ -90,7 +90,7 @@ __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint3
     return c0;
 }
 
-// ---- The pair list: the kept blocks of a small grid (at most 128 x 64 blocks) as units of two ----
+// ---- The pair list: the kept blocks of a small grid (at most 128 x 64 blocks of 128 x 128) as units of two ----
 // eq. (2) computes kept blocks only, and a 128 x 256 tile of two kept blocks costs about 1.6 single 128 x 128 tiles.
 // Two kept blocks can share a tile when they share the block row (a wide pair: one dY panel against two W panels)
 // or the block column (a tall pair: two dY panels against one W panel, computed as the transposed product).
@@ -103,7 +103,12 @@ __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint3
 // An entry is kind << 30 | x << 16 | y << 8 | z: wide (i, j1, j2), tall (j, i1, i2), single (i, j, j).
 constexpr int kUnitWide = 0, kUnitTall = 1, kUnitSingle = 2;
 constexpr int kUnitsMaxMB = 128, kUnitsMaxKB = 64;
-__host__ __device__ inline bool units_apply(int64_t MB, int64_t KB) { return MB <= kUnitsMaxMB && KB <= kUnitsMaxKB; }
+// (built for 128 x 128 blocks only, the one block size whose eq. 2 kernel walks it: on the 128 x 16 grid of 64 x 64
+// blocks of the MLP workload it cost the forward kernel that writes the mask object 5 of 23 us)
+__host__ __device__ inline bool units_apply(int64_t MB, int64_t KB, int BM, int BK)
+{
+    return MB <= kUnitsMaxMB && KB <= kUnitsMaxKB && BM == 128 && BK == 128;
+}
 __device__ __forceinline__ int32_t unit_entry(int kind, int x, int y, int z) { return (int32_t)((uint32_t)kind << 30 | (uint32_t)x << 16 | (uint32_t)y << 8 | (uint32_t)z); }
 
 // Called by all 64 lanes of one wavefront; lane l passes the keep words of block rows l and l + 64 (0 beyond the
@@ -112,50 +117,52 @@ __device__ inline int build_units(uint64_t rw0, uint64_t rw1, int MB, int32_t *u
 {
     const int lane = threadIdx.x & 63;
     // where each row's wide pairs go: a row has floor(kept / 2) of them whichever block it gives away
+    // (prefix sums over the lanes by ballots of the counts' six bits: no trips through the LDS crossbar)
     const int np0 = __popcll(rw0) >> 1, np1 = __popcll(rw1) >> 1;
-    int inc0 = np0, inc1 = np1;
+    const uint64_t below = (uint64_t(1) << lane) - 1;
+    int off0 = 0, off1 = 0, tot0 = 0, tot1 = 0;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int u0 = __shfl_up(inc0, d, 64), u1 = __shfl_up(inc1, d, 64);
-        if (lane >= d) { inc0 += u0; inc1 += u1; }
+    for (int b = 0; b < 6; ++b) {
+        const uint64_t m0 = __ballot((np0 >> b) & 1), m1 = __ballot((np1 >> b) & 1);
+        off0 += (int)__popcll(m0 & below) << b;
+        off1 += (int)__popcll(m1 & below) << b;
+        tot0 += (int)__popcll(m0) << b;
+        tot1 += (int)__popcll(m1) << b;
     }
-    const int tot0 = __shfl(inc0, 63, 64);
-    const int n_wide = tot0 + __shfl(inc1, 63, 64);
-    const int off0 = inc0 - np0, off1 = tot0 + inc1 - np1;
-    // the rows in turn (uniform: every lane follows the same chain; lane c remembers the row waiting in column c,
-    // lane i % 64 the column row i gave away)
+    off1 += tot0;
+    const int n_wide = tot0 + tot1;
+    // The rows with an odd count in turn (the others give nothing away).  Every lane follows the same chain, in
+    // scalar registers and without a branch inside a step (a step with branches took 0.14 us, 18 us for 128 rows):
+    // lane c remembers the row waiting in column c, lane i % 64 the column row i gave away, lane t the t-th tall pair.
     const uint32_t lo0 = (uint32_t)rw0, hi0 = (uint32_t)(rw0 >> 32), lo1 = (uint32_t)rw1, hi1 = (uint32_t)(rw1 >> 32);
     uint64_t waiting = 0;
     int pend = 0, gave0 = -1, gave1 = -1, n_tall = 0;
-    for (int i = 0; i < MB; ++i) {
-        const int src = i & 63;
-        const uint32_t lo = i < 64 ? __builtin_amdgcn_readlane(lo0, src) : __builtin_amdgcn_readlane(lo1, src);
-        const uint32_t hi = i < 64 ? __builtin_amdgcn_readlane(hi0, src) : __builtin_amdgcn_readlane(hi1, src);
-        const uint64_t w = (uint64_t)hi << 32 | lo;
-        if (!(__popcll(w) & 1)) continue;
-        const uint64_t hit = w & waiting;
-        int c;
-        if (hit) {
-            c = __builtin_ctzll(hit);
+    int32_t tall = 0;
+    auto chain = [&](uint64_t odd, uint32_t lo_v, uint32_t hi_v, int base, int &gave) __attribute__((always_inline)) {
+        while (odd) {
+            const int src = __builtin_ctzll(odd);
+            odd &= odd - 1;
+            // (the builtin returns a signed int: through uint32_t, or the low word's top bit would spread over the high word)
+            const uint64_t w = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(hi_v, src) << 32 | (uint32_t)__builtin_amdgcn_readlane(lo_v, src);
+            const uint64_t hit = w & waiting;
+            const bool has = hit != 0;                  // an earlier row's block waits in a column this row keeps
+            const int c = has ? __builtin_ctzll(hit) : 63 - __builtin_clzll(w);
             const int i1 = __builtin_amdgcn_readlane(pend, c);
-            if (lane == 0) units[n_wide + n_tall] = unit_entry(kUnitTall, c, i1, i);
-            ++n_tall;
-            waiting ^= uint64_t(1) << c;
-        } else {
-            c = 63 - __builtin_clzll(w);
-            waiting |= uint64_t(1) << c;
-            if (lane == c) pend = i;
+            tall = (has && lane == n_tall) ? unit_entry(kUnitTall, c, i1, base + src) : tall;
+            n_tall += has ? 1 : 0;
+            waiting ^= uint64_t(1) << c;                // taken out of the waiting set, or put into it
+            pend = (!has && lane == c) ? base + src : pend;
+            gave = lane == src ? c : gave;
         }
-        if (lane == src) { if (i < 64) gave0 = c; else gave1 = c; }
-    }
-    int n_single = 0;
-    while (waiting) {
-        const int c = __builtin_ctzll(waiting);
-        waiting &= waiting - 1;
-        const int i1 = __builtin_amdgcn_readlane(pend, c);
-        if (lane == 0) units[n_wide + n_tall + n_single] = unit_entry(kUnitSingle, i1, c, c);
-        ++n_single;
-    }
+    };
+    chain(__ballot(__popcll(rw0) & 1), lo0, hi0, 0, gave0);
+    chain(__ballot(__popcll(rw1) & 1), lo1, hi1, 64, gave1);
+    (void)MB;                                           // (rows beyond the grid hold no bits)
+    if (lane < n_tall) units[n_wide + lane] = tall;
+    // what still waits is single: lane <-> column
+    const int n_single = (int)__popcll(waiting);
+    if ((waiting >> lane) & 1)
+        units[n_wide + n_tall + (int)__popcll(waiting & ((uint64_t(1) << lane) - 1))] = unit_entry(kUnitSingle, pend, lane, lane);
     // every lane writes the wide pairs of its two rows
 #pragma unroll
     for (int h = 0; h < 2; ++h) {

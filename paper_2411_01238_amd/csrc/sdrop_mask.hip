@@ -445,13 +445,6 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
     if (first_wg) {
         for (int i = threadIdx.x; i <= P.MB; i += kMaskThreads) P.row_ptr[i] = s_row_ptr[i];
         for (int j = threadIdx.x; j <= P.KB; j += kMaskThreads) P.col_ptr[j] = s_col_ptr[j];
-        // the pair list (grids of at most 128 x 64 blocks: a block row is one word), by the last wavefront
-        if (wave == kMaskWaves - 1) {
-            int n = 0;
-            if (units_apply(P.MB, P.KB))
-                n = build_units(lane < P.MB ? s_bits[lane] : 0, lane + 64 < P.MB ? s_bits[lane + 64] : 0, P.MB, P.units);
-            if (lane == 0) s_nunits = n;
-        }
     }
     // The three kinds of lists do not depend on each other.  One workgroup: with few groups of 8 block rows (a small
     // grid) the locally ordered list would keep only that many wavefronts busy, on top of their share of the other
@@ -460,7 +453,16 @@ __global__ __launch_bounds__(kMaskThreads) void mask_small_kernel(MaskParams P)
     const int nwg = (int)gridDim.x;
     const int ngroups = (P.MB + 7) / 8;
     const int nlo = (nwg == 1 && ngroups < kMaskWaves / 2) ? ngroups : 0;   // wavefronts that only build the locally ordered list
-    const int nls = kMaskWaves - nlo;                              // wavefronts (per workgroup) that build the row and column lists
+    // The pair list (grids of at most 128 x 64 blocks of 128 x 128: a block row is one word) is one wavefront's work,
+    // the first workgroup's last; on a small grid that wavefront does nothing else.
+    const bool pairs_here = first_wg && units_apply(P.MB, P.KB, P.BM, P.BK);
+    const int npl = pairs_here && nlo > 0 ? 1 : 0;
+    const int nls = kMaskWaves - nlo - npl;                        // wavefronts (per workgroup) that build the row and column lists
+    if (first_wg && wave == kMaskWaves - 1) {
+        int n = 0;
+        if (pairs_here) n = build_units(lane < P.MB ? s_bits[lane] : 0, lane + 64 < P.MB ? s_bits[lane + 64] : 0, P.MB, P.units);
+        if (lane == 0) s_nunits = n;
+    }
     const int gw = (int)blockIdx.x * nls + wave, ngw = nwg * nls;  // this wavefront among those of the whole launch
     if (nlo > 0) local_order(s_bits, s_row_ptr, P, nls, nlo);
     for (int i = gw; i < P.MB && wave < nls; i += ngw) {

@@ -55,10 +55,19 @@ def test_pair_list_of_a_drawn_mask(MB, KB, p):
     _check_units(m, orc.mask(MB, KB, p, 11, 3))
 
 
-def test_pair_list_is_absent_on_larger_grids():
+def test_pair_list_is_absent_on_larger_grids_and_other_block_sizes():
     for MB, KB in ((129, 8), (8, 65), (512, 32)):
-        m = sdrop.sdrop_mask(MB * 64, KB * 64, 64, 64, 0.5, 0, 0)
+        m = sdrop.sdrop_mask(MB * 128, KB * 128, 128, 128, 0.5, 0, 0)
         _check_units(m, orc.mask(MB, KB, 0.5, 0, 0))
+    for BM, BK in ((64, 64), (128, 64), (64, 128)):
+        m = sdrop.sdrop_mask(16 * BM, 16 * BK, BM, BK, 0.5, 0, 0)
+        torch.cuda.synchronize()
+        assert m.n_units() == 0 and m.nnz() > 0
+        X = torch.randn((16 * BM, 16 * BK), device="cuda").to(torch.bfloat16)
+        W = torch.randn((16 * BK, 256), device="cuda").to(torch.bfloat16)
+        _, m2 = sdrop.sdrop_fwd_seeded(X, W, BM, BK, 0.5, 0, 0)
+        torch.cuda.synchronize()
+        assert m2.n_units() == 0 and torch.equal(m2.buf[:256], m.buf[:256])
 
 
 def _mask_of(keep, p):
