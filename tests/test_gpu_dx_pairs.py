@@ -193,3 +193,32 @@ def test_pairs_are_not_used_with_unequal_strides_or_a_stated_kept_share():
     got2 = sdrop.sdrop_bwd_dx_ex(dY.cuda(), W.cuda(), m, out_dtype=torch.float32, kept_fraction=0.5)
     torch.cuda.synchronize()
     assert torch.equal(got, ref) and torch.equal(got2, ref)
+
+
+@pytest.mark.parametrize("split_m,split_k", [(2, 2), (1, 2), (2, 1)])
+def test_pairs_on_a_retiled_mask(split_m, split_k):
+    """Block splitting (Section 3.3): the pair list of a mask whose logical blocks are larger than the kernel's."""
+    print("pairs on a retiled mask", split_m, split_k, flush=True)
+    M, K, N, p = 2048, 2048, 128, 0.5
+    keep = orc.mask_split(16, 16, split_m, split_k, p, 9, 1)
+    m = sdrop.sdrop_mask_split(M, K, 128, 128, split_m, split_k, p, 9, 1)
+    _check_units(m, keep)
+    g = torch.Generator().manual_seed(3)
+    dY = torch.randn((M, N), generator=g, dtype=torch.float64).to(torch.bfloat16)
+    W = torch.randn((K, N), generator=g, dtype=torch.float64).to(torch.bfloat16)
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 1)
+    got = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_tight(f64(got), orc.bwd_dx(f64(dY), f64(W), keep, 128, 128, p), "dX on pairs of a retiled mask")
+
+
+def test_a_single_kept_block():
+    keep = np.zeros((5, 7), dtype=np.uint8)
+    keep[3, 4] = 1
+    dY, W, X, keep, m = _dx_case(5 * 128, 7 * 128, 192, 0.5, torch.float16, keep=keep)
+    _check_units(m, keep)
+    sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 1)
+    got = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_tight(f64(got), orc.bwd_dx(f64(dY), f64(W), keep, 128, 128, 0.5), "dX of a single kept block")
+    assert m.n_units() == 1
