@@ -44,6 +44,11 @@ def test_tuning_knobs_reject_bad_arguments():
     assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, -1) == sdrop.EINVAL
     assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, 0) == sdrop.OK
     assert L.sdrop_set_tuning(sdrop.TUNE_BWD_FUSED, 1) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_PAIRS, 3) == sdrop.EINVAL
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_PAIRS, 2) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_DX_PAIRS, 0) == sdrop.OK
+    assert L.sdrop_set_tuning(sdrop.TUNE_DW64_PERSISTENT_SLICES, -1) == sdrop.EINVAL
+    assert L.sdrop_set_tuning(sdrop.TUNE_DW64_PERSISTENT_SLICES, 16) == sdrop.OK
 
 
 def test_mask_layout_regions_do_not_overlap():
@@ -55,7 +60,7 @@ def test_mask_layout_regions_do_not_overlap():
         regions = [(0, 256), (L.off_bits, 8 * MB * L.words_per_row), (L.off_row_ptr, 4 * (MB + 1)),
                    (L.off_col_idx, 4 * MB * KB), (L.off_blk_row, 4 * MB * KB), (L.off_col_ptr, 4 * (KB + 1)),
                    (L.off_row_idx, 4 * MB * KB), (L.off_row_order, 4 * MB), (L.off_col_order, 4 * KB),
-                   (L.off_loc_row, 4 * MB * KB), (L.off_loc_col, 4 * MB * KB)]
+                   (L.off_loc_row, 4 * MB * KB), (L.off_loc_col, 4 * MB * KB), (L.off_units, 4 * MB * KB)]
         end = 0
         for off, size in regions:
             assert off >= end and off % 16 == 0
