@@ -55,7 +55,14 @@ def _whole_parity(w, p, layer=0):
     is_bf16 = X.dtype == torch.bfloat16
 
     ref = orc.fwd(Xd, Wd, keep, w.BM, w.BK, p)
-    _check_product(tag, "Y", lambda **k: sdrop.sdrop_fwd(Xg, Wg, m, **k), ref, is_bf16)
+    Y32, Y16 = _check_product(tag, "Y", lambda **k: sdrop.sdrop_fwd(Xg, Wg, m, **k), ref, is_bf16)
+    # the call the benchmark's step makes (mask and eq. 1 in one launch where the grid allows it): the same Y bit
+    # for bit, and a mask object with the same header, bits and kept count
+    Ys, ms = sdrop.sdrop_fwd_seeded(Xg, Wg, w.BM, w.BK, p, w.mask_seed, layer)
+    torch.cuda.synchronize()
+    assert torch.equal(Ys, Y16), tag + ": sdrop_fwd_seeded differs from sdrop_mask + sdrop_fwd"
+    assert torch.equal(ms.buf[:256], m.buf[:256]) and torch.equal(ms.bits(), m.bits()), tag + ": mask objects differ"
+    del Y32, Y16, Ys
     ref = orc.bwd_dx(dYd, Wd, keep, w.BM, w.BK, p)
     dX32, dX16 = _check_product(tag, "dX", lambda **k: sdrop.sdrop_bwd_dx(dYg, Wg, m, **k), ref, is_bf16)
     ref = orc.bwd_dw(Xd, dYd, keep, w.BM, w.BK, p)
