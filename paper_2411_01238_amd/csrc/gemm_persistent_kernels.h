@@ -214,14 +214,22 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                             *reinterpret_cast<out4 *>(reg + wrow * 128 + slot8 * 8) = o;
                         }
                     }
+                // all four reads of the piece are requested before the first is used (left to itself the compiler
+                // waited for each one before it requested the next: four trips to LDS in a row per piece)
+                uint4 rv[4];
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
                     const int row = it * 8 + rrow;
-                    uint4 v;
-                    if constexpr (ESZ == 4) {
-                        v = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
-                    } else {
-                        const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
+                    if constexpr (ESZ == 4) rv[it] = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
+                    else rv[it] = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = it * 8 + rrow;
+                    uint4 v = rv[it];
+                    if constexpr (ESZ != 4) {
+                        const uint4 x = rv[it];
                         v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
                         if constexpr (TAIL) {
                             if (gate_rows) v = gate16<T>(v, gate_q[pc][it]);
@@ -264,16 +272,19 @@ template <class T, class OutT, bool A_TR, bool B_TR, int TM, int TN, int WM, int
                             *reinterpret_cast<out4 *>(reg + wrow * 128 + slot8 * 8) = o;
                         }
                     }
+                uint4 rv[4];                               // (all four reads first, as in store)
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
                     const int row = it * 8 + rrow;
-                    uint4 v;
-                    if constexpr (ESZ == 4) {
-                        v = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
-                    } else {
-                        const uint4 x = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
-                        v = (row & 1) ? make_uint4(x.z, x.w, x.x, x.y) : x;
-                    }
+                    if constexpr (ESZ == 4) rv[it] = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ (row & 7)) << 4));
+                    else rv[it] = *reinterpret_cast<const uint4 *>(reg + row * 128 + ((rch ^ ((row & 15) >> 1)) << 4));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = it * 8 + rrow;
+                    const uint4 x = rv[it];
+                    const uint4 v = (ESZ == 4 || !(row & 1)) ? x : make_uint4(x.z, x.w, x.x, x.y);
                     store_out(out + (int64_t)row * ldc + rch * 16, v);
                 }
             }
