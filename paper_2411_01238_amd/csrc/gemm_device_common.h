@@ -41,6 +41,7 @@ struct GemmParams {
     uint64_t threshold;
     double p_call;      // the dropout probability of the call (compared with the one a drawn mask records)
     int *status;        // the library's status word on this device, or null
+    bool w_nk;          // host side: the weight is [N,K] and the kernel reads it so (see w_nk_native in the launch code)
     bool kept_given;    // host side: the caller stated the kept share itself (a mask of its own bits, whose structure is unknown)
 };
 

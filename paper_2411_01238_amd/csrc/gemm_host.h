@@ -37,6 +37,8 @@ inline int tail_mode(const GemmParams &P)
 struct DxPlan { int TN; bool persistent; bool pairs; };
 // fused: the plan is for sdrop_bwd's single launch, whose dW workgroups fill what dX's last round leaves idle
 DxPlan dx_plan(const GemmParams &P, bool fused = false);
+// [N,K] weights: does the call's kernel read the array in place?
+bool w_nk_native(int op, int64_t N, int BM, int BK);
 // dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on
 bool dw64_persistent(const GemmParams &P);
 

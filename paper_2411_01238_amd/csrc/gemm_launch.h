@@ -116,6 +116,29 @@ int launch_fwd_seeded(const GemmParams &P, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// eq. (1) with the weight as [N,K], read in place (N a multiple of 256, no tail); SEEDED: the mask drawn in the
+// same launch.  Returns -1 when the device does not grant the LDS.
+template <class T, class OutT, int TM, bool SEEDED>
+int launch_fwd_nk(const GemmParams &P, hipStream_t stream)
+{
+    constexpr int P_LDS = 3 * (TM + 256) * TK * 2 + 4 * 4096;
+    auto k = fwd_nk_kernel<T, OutT, TM, SEEDED>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    GemmParams Q = P;
+    Q.n_tiles = (int)(P.N / 256);
+    Q.splits = 1;
+    Q.total_tiles = Q.MB * Q.n_tiles;
+    const int ncu = cu_count();
+    hipLaunchKernelGGL(k, dim3((unsigned)(Q.total_tiles < ncu ? Q.total_tiles : ncu)), dim3(512), P_LDS, stream, Q);
+    return hip_status(hipGetLastError());
+}
+
 // Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
 template <class T, class OutT, int TN, int TAIL>
 int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
@@ -210,6 +233,10 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         }
     }
     if constexpr (OP == FWD) {
+        if (P.w_nk) {
+            const int rc = P.BM == 128 ? launch_fwd_nk<T, OutT, 128, false>(P, stream) : launch_fwd_nk<T, OutT, 64, false>(P, stream);
+            return rc == -1 ? SDROP_EHIP : rc;       // (the [K,N] persistent form needs the same LDS)
+        }
         P.n_tiles = (int)((P.N + 255) / 256);
         const int grid = P.MB * P.n_tiles;
         const bool ragged = P.N % 256 != 0;

@@ -346,15 +346,21 @@ constexpr int waitcnt_lgkm0_only() { return 15 | (3 << 14) | (7 << 4) | (0 << 8)
 // it in registers (SeededGrid), so a tile's block row and its kept columns come from a few scalar instructions
 // instead of three dependent look-ups, and the computing wavefronts write the mask object for the backward kernels,
 // a small piece each, before they meet their first barrier.
-template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false, bool SEEDED = false>
+//
+// W_NK (the forward, whole tile columns, no tail): the weight is given as [N,K], one row per output column, so its
+// reduction index is the contiguous one like X's: the B tile of a slice is then 256 rows of W at the slice's column
+// offset, loaded and read in the row form that eq. (2) uses for both its operands.
+template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false, bool SEEDED = false,
+          bool W_NK = false>
 __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const int G, const int w)
 {
     static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
     static_assert(!SEEDED || OP == FWD, "only the forward kernel draws its own mask");
+    static_assert(!W_NK || (OP == FWD && !RAGN && TAIL == kTailNone), "[N,K] weights: the plain forward on whole tiles");
     constexpr int NW = WM * WN;
     static_assert(NW == 4, "one computing and one loading wavefront per SIMD");
     constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
-    constexpr bool A_KMAJ = (OP == FWD), A_TR = !A_KMAJ, B_TR = true;
+    constexpr bool A_KMAJ = (OP == FWD), A_TR = !A_KMAJ, B_TR = !W_NK;
     constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int STAGES = 3, AHEAD = 2;
     constexpr int ESZ = (int)sizeof(OutT);
@@ -407,7 +413,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     if (loader) {
         // ---------------- loaders: the stream of slices ----------------
         using DmaA = typename std::conditional<A_KMAJ, DmaK<TM, 1, NW>, DmaT<TM, NW>>::type;
-        using DmaB = DmaT<TN, NW>;
+        using DmaB = typename std::conditional<W_NK, DmaK<TN, 1, NW>, DmaT<TN, NW>>::type;
         DmaA da;
         DmaB db;
         da.init(lda, wave);
@@ -489,7 +495,8 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
                 const int nt = nt_cur;
                 if constexpr (OP == FWD) a_tile = P.A + (int64_t)ord_cur * P.BM * lda;
                 else a_tile = P.A + (int64_t)ord_cur * P.BK * 2;
-                b_tile = P.B + (int64_t)nt * TN * 2;
+                if constexpr (W_NK) b_tile = P.B + (int64_t)nt * TN * ldb;      // rows [nt TN, nt TN + TN) of W[N,K]
+                else b_tile = P.B + (int64_t)nt * TN * 2;
                 if constexpr (RAGN) {
                     const int64_t left = P.N - (int64_t)nt * TN;
                     b_chunks = left < TN ? (int)(left / 8) : TN / 8;
@@ -497,7 +504,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             }
             const int64_t off = (int64_t)e_cur * BLK + (int64_t)(s & sub_mask) * TK;
             const char *const sa[1] = {a_tile + off * (OP == FWD ? 2 : lda)};
-            const char *const sb[1] = {b_tile + off * ldb};
+            const char *const sb[1] = {W_NK ? b_tile + off * 2 : b_tile + off * ldb};
             char *stp = stage_ptr(st);
 #pragma unroll
             for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
@@ -628,6 +635,13 @@ template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL,
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
 {
     gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL, RAGN>(P, gridDim.x, blockIdx.x);
+}
+
+// eq. (1) with the weight as [N,K] (see W_NK above); with SEEDED it draws its own mask as well.
+template <class T, class OutT, int TM, bool SEEDED>
+__global__ __launch_bounds__(512) void fwd_nk_kernel(GemmParams P)
+{
+    gemm_persistent_body<FWD, T, OutT, TM, 256, 1, 4, kTailNone, false, SEEDED, true>(P, gridDim.x, blockIdx.x);
 }
 
 // The forward kernel that draws its own mask and writes the mask object as well (see SEEDED above).

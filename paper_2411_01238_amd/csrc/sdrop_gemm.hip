@@ -238,6 +238,15 @@ DxPlan dx_plan(const GemmParams &P, bool fused)
     return plan;
 }
 
+// Which calls read a weight given as [N,K] in place instead of through a transposed copy: eq. (1) on whole 256-wide
+// tile columns (its persistent kernel loads W's rows the way eq. 2 loads its operands).
+bool w_nk_native(int op, int64_t N, int BM, int BK)
+{
+    (void)BM; (void)BK;
+    if (op == FWD) return N % 256 == 0;
+    return false;
+}
+
 // dW with 64-row tiles: the persistent kernel from 16 expected slices per tile on (see dispatch_tile)
 int g_dw64_persistent_slices = 16;
 bool dw64_persistent(const GemmParams &P) { return (1.0 - P.p) * P.MB / P.splits * (P.BM / 64) >= (double)g_dw64_persistent_slices; }
@@ -281,6 +290,7 @@ GemmParams base_params(int op, const void *a, const void *b, const void *mask, v
     P.p_call = p;
     P.status = device_status_word();
     P.kept_given = false;
+    P.w_nk = false;
     return P;
 }
 
@@ -344,7 +354,10 @@ int run(const void *a, const void *b, const void *mask, void *out,
     const int64_t esz_out = out_dtype == SDROP_F32 ? 4 : 2;
     void *final_out = out;
     int64_t final_ld = 0;
-    if (w_nk) {
+    // ... unless the call is one whose kernel has a form that reads (writes) the [N,K] array in place
+    const bool has_tail_args = epi && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask);
+    const bool nk_native = w_nk && !out2 && !has_tail_args && w_nk_native(OP, N, BM, BK);
+    if (w_nk && !nk_native) {
         if constexpr (OP == DW) {
             final_ld = epi->ld_out ? epi->ld_out : K;
             out = ws_kn;
@@ -358,6 +371,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
     if (epi) {
         if (epi->ld_a) P.lda = epi->ld_a * 2;
         if (epi->ld_b && !(w_nk && OP != DW)) P.ldb = epi->ld_b * 2;
+        if (nk_native && OP != DW) { P.ldb = (epi->ld_b ? epi->ld_b : K) * 2; P.w_nk = true; }
         if (epi->ld_out && !(w_nk && OP == DW)) P.ldc = epi->ld_out * (out_dtype == SDROP_F32 ? 4 : 2);
         if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
         // the kernel choice goes by the expected share of kept blocks: the caller's figure where given (a mask built
@@ -381,13 +395,13 @@ int run(const void *a, const void *b, const void *mask, void *out,
             const int rc1 = (dtype == SDROP_F16) ? dispatch_typed<F16>(OP, true, P, st) : dispatch_typed<BF16>(OP, true, P, st);
             if (rc1 != SDROP_OK) return rc1;
             const int rc2 = launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out, P);
-            if (rc2 != SDROP_OK || !w_nk) return rc2;
+            if (rc2 != SDROP_OK || !(w_nk && !nk_native)) return rc2;
             return launch_transpose(out, final_out, K, N, N, final_ld, (int)esz_out, st);
         }
     }
     const bool o32 = out_dtype == SDROP_F32;
     const int rcg = dtype == SDROP_F16 ? dispatch_typed<F16>(OP, o32, P, st) : dispatch_typed<BF16>(OP, o32, P, st);
-    if (rcg != SDROP_OK || !(w_nk && OP == DW)) return rcg;
+    if (rcg != SDROP_OK || !(w_nk && !nk_native && OP == DW)) return rcg;
     return launch_transpose(out, final_out, K, N, N, final_ld, (int)esz_out, st);
 }
 

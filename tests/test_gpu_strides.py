@@ -148,6 +148,9 @@ def test_producer_with_leading_dimensions():
     (1024, 512, 512, 128, 128, "f16", 0.5, 2),     # square weight: a missing transposition would pass every shape check
     (2048, 256, 264, 64, 64, "bf16", 0.5, 3),      # dW as split parts + summing pass, then the transposition
     (1024, 1024, 256, 128, 64, "f16", 0.3, 4),
+    (1024, 1024, 512, 64, 64, "bf16", 0.5, 5),    # whole tile columns: the kernels that read and write [N,K] in place
+    (2048, 1024, 768, 128, 128, "bf16", 0.5, 6),
+    (2048, 2048, 256, 128, 128, "f16", 0.9, 7),
 ])
 def test_weight_in_out_in_layout(M, K, N, BM, BK, dtype, p, seed):
     # eq. (1)-(3) with the weight stored as Wt[N,K] (w_layout = W_NK), against the oracle's functions for that
