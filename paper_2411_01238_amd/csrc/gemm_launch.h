@@ -139,6 +139,27 @@ int launch_fwd_nk(const GemmParams &P, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// eq. (3) with the gradient written as [N,K] (128-row tiles, N a multiple of 256; P.splits parts).
+template <class T, class OutT>
+int launch_dw_nk(const GemmParams &P, hipStream_t stream)
+{
+    constexpr int P_LDS = 3 * (128 + 256) * TK * 2 + 4 * 4096;
+    auto k = dw_nk_kernel<T, OutT, 128>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    GemmParams Q = P;
+    Q.n_tiles = (int)(P.N / 256);
+    Q.total_tiles = Q.KB * Q.n_tiles * Q.splits;
+    const int ncu = cu_count();
+    hipLaunchKernelGGL(k, dim3((unsigned)(Q.total_tiles < ncu ? Q.total_tiles : ncu)), dim3(512), P_LDS, stream, Q);
+    return hip_status(hipGetLastError());
+}
+
 // Persistent dX: one workgroup per CU (fewer when there are fewer block positions than CUs).
 template <class T, class OutT, int TN, int TAIL>
 int launch_dx_persistent_t(const GemmParams &P, hipStream_t stream);
@@ -243,6 +264,10 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         if (P.BM == 128) return launch<FWD, T, OutT, 128, 256, 1, 4>(P, grid, ragged, stream);
         return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else if constexpr (OP == DW) {
+        if (P.w_nk) {
+            const int rc = launch_dw_nk<T, OutT>(P, stream);
+            return rc == -1 ? SDROP_EHIP : rc;
+        }
         P.n_tiles = (int)((P.N + 255) / 256);
         const int grid = P.KB * P.n_tiles * P.splits;
         const bool ragged = P.N % 256 != 0;

@@ -350,17 +350,22 @@ constexpr int waitcnt_lgkm0_only() { return 15 | (3 << 14) | (7 << 4) | (0 << 8)
 // W_NK (the forward, whole tile columns, no tail): the weight is given as [N,K], one row per output column, so its
 // reduction index is the contiguous one like X's: the B tile of a slice is then 256 rows of W at the slice's column
 // offset, loaded and read in the row form that eq. (2) uses for both its operands.
+// W_NK for eq. (3): the gradient goes out as [N,K].  Operands and loads are as ever; the MFMAs take their operands the
+// other way round, which leaves the transposed 32 x 32 blocks in the accumulators, and the epilogue writes the tile
+// transposed (Compute::store_t), into the output or into planes of partial sums laid out [N][K].
 template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false, bool SEEDED = false,
           bool W_NK = false>
 __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const int G, const int w)
 {
     static_assert(OP == FWD || OP == DW, "output-sparse dX is not handled here");
     static_assert(!SEEDED || OP == FWD, "only the forward kernel draws its own mask");
-    static_assert(!W_NK || (OP == FWD && !RAGN && TAIL == kTailNone), "[N,K] weights: the plain forward on whole tiles");
+    static_assert(!W_NK || (!RAGN && TAIL == kTailNone), "[N,K] weights: the plain products on whole tiles");
+    static_assert(!W_NK || OP == FWD || (TM / WM / 32) % (128 / (32 * (int)sizeof(OutT))) == 0, "the transposed tile's rows must fill 128-byte pieces");
     constexpr int NW = WM * WN;
     static_assert(NW == 4, "one computing and one loading wavefront per SIMD");
     constexpr int WTM = TM / WM, WTN = TN / WN, MI = WTM / 32, NI = WTN / 32;
-    constexpr bool A_KMAJ = (OP == FWD), A_TR = !A_KMAJ, B_TR = !W_NK;
+    constexpr bool A_KMAJ = (OP == FWD), A_TR = !A_KMAJ, B_TR = !(W_NK && OP == FWD);
+    constexpr bool OUT_T = W_NK && OP == DW;             // the output tile is written transposed
     constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int STAGES = 3, AHEAD = 2;
     constexpr int ESZ = (int)sizeof(OutT);
@@ -413,7 +418,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
     if (loader) {
         // ---------------- loaders: the stream of slices ----------------
         using DmaA = typename std::conditional<A_KMAJ, DmaK<TM, 1, NW>, DmaT<TM, NW>>::type;
-        using DmaB = typename std::conditional<W_NK, DmaK<TN, 1, NW>, DmaT<TN, NW>>::type;
+        using DmaB = typename std::conditional<W_NK && OP == FWD, DmaK<TN, 1, NW>, DmaT<TN, NW>>::type;
         DmaA da;
         DmaB db;
         da.init(lda, wave);
@@ -495,7 +500,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
                 const int nt = nt_cur;
                 if constexpr (OP == FWD) a_tile = P.A + (int64_t)ord_cur * P.BM * lda;
                 else a_tile = P.A + (int64_t)ord_cur * P.BK * 2;
-                if constexpr (W_NK) b_tile = P.B + (int64_t)nt * TN * ldb;      // rows [nt TN, nt TN + TN) of W[N,K]
+                if constexpr (W_NK && OP == FWD) b_tile = P.B + (int64_t)nt * TN * ldb;      // rows [nt TN, nt TN + TN) of W[N,K]
                 else b_tile = P.B + (int64_t)nt * TN * 2;
                 if constexpr (RAGN) {
                     const int64_t left = P.N - (int64_t)nt * TN;
@@ -504,7 +509,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             }
             const int64_t off = (int64_t)e_cur * BLK + (int64_t)(s & sub_mask) * TK;
             const char *const sa[1] = {a_tile + off * (OP == FWD ? 2 : lda)};
-            const char *const sb[1] = {W_NK ? b_tile + off * 2 : b_tile + off * ldb};
+            const char *const sb[1] = {(W_NK && OP == FWD) ? b_tile + off * 2 : b_tile + off * ldb};
             char *stp = stage_ptr(st);
 #pragma unroll
             for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
@@ -618,7 +623,7 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             return c_tile + (int64_t)(mi * 32) * ldc + nj * 128;
         };
         for (int s = 0; s < nsteps; ++s) {
-            cw.slice(stage_ptr(st0), stage_ptr(st1));
+            cw.template slice<OUT_T>(stage_ptr(st0), stage_ptr(st1));
             const int t0 = st0; st0 = st1; st1 = st2; st2 = t0;
         }
         if constexpr (!SEEDED) {
@@ -627,7 +632,18 @@ __device__ __forceinline__ void gemm_persistent_body(const GemmParams &P, const 
             len0 = uni(c_len(k + 1, cnt1_v));
             ord0 = ord1; ord1 = ord2; ord2 = uni(ord3_v);
         }
-        cw.template finish<TAIL, RAGN>(reg, scale, ldc, tl, dst);
+        if constexpr (OUT_T) {
+            // the wavefront's sub-tile, rows [ord BK + wm WTM, +WTM) x columns [nt TN + wn WTN, +WTN) of dW, is rows
+            // [nt TN + wn WTN, +WTN) x columns [ord BK + wm WTM, +WTM) of the [N,K] output (or of plane `part`)
+            char *const ct = P.C + (int64_t)part * P.N * ldc + ((int64_t)nt * TN + wn * WTN) * ldc
+                             + ((int64_t)ord * P.BK + wm * WTM) * ESZ;
+            auto dst_t = [&](int r, int pj) __attribute__((always_inline)) -> char * {
+                return ct + (int64_t)(r * 32) * ldc + pj * 128;
+            };
+            cw.store_t(reg, scale, ldc, dst_t);
+        } else {
+            cw.template finish<TAIL, RAGN>(reg, scale, ldc, tl, dst);
+        }
     }
 }
 
@@ -635,6 +651,13 @@ template <int OP, class T, class OutT, int TM, int TN, int WM, int WN, int TAIL,
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_kernel(GemmParams P)
 {
     gemm_persistent_body<OP, T, OutT, TM, TN, WM, WN, TAIL, RAGN>(P, gridDim.x, blockIdx.x);
+}
+
+// eq. (3) with the gradient written as [N,K] (see W_NK above).
+template <class T, class OutT, int TM>
+__global__ __launch_bounds__(512) void dw_nk_kernel(GemmParams P)
+{
+    gemm_persistent_body<DW, T, OutT, TM, 256, 1, 4, kTailNone, false, false, true>(P, gridDim.x, blockIdx.x);
 }
 
 // eq. (1) with the weight as [N,K] (see W_NK above); with SEEDED it draws its own mask as well.

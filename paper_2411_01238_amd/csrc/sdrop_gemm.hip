@@ -239,11 +239,13 @@ DxPlan dx_plan(const GemmParams &P, bool fused)
 }
 
 // Which calls read a weight given as [N,K] in place instead of through a transposed copy: eq. (1) on whole 256-wide
-// tile columns (its persistent kernel loads W's rows the way eq. 2 loads its operands).
+// tile columns (its persistent kernel loads W's rows the way eq. 2 loads its operands), and eq. (3) with 128-wide
+// blocks on whole tile columns (its persistent kernel writes its tiles transposed).
 bool w_nk_native(int op, int64_t N, int BM, int BK)
 {
-    (void)BM; (void)BK;
+    (void)BM;
     if (op == FWD) return N % 256 == 0;
+    if (op == DW) return N % 256 == 0 && BK == 128;       // (its persistent kernel's 128-row tiles, written transposed)
     return false;
 }
 
@@ -373,6 +375,7 @@ int run(const void *a, const void *b, const void *mask, void *out,
         if (epi->ld_b && !(w_nk && OP != DW)) P.ldb = epi->ld_b * 2;
         if (nk_native && OP != DW) { P.ldb = (epi->ld_b ? epi->ld_b : K) * 2; P.w_nk = true; }
         if (epi->ld_out && !(w_nk && OP == DW)) P.ldc = epi->ld_out * (out_dtype == SDROP_F32 ? 4 : 2);
+        if (nk_native && OP == DW) { P.ldc = (epi->ld_out ? epi->ld_out : K) * (out_dtype == SDROP_F32 ? 4 : 2); P.w_nk = true; }
         if (epi->scale_mode == SDROP_SCALE_ONE) P.scale = 1.0f;
         // the kernel choice goes by the expected share of kept blocks: the caller's figure where given (a mask built
         // from the caller's own bits need not have the density 1 - p), else 1 - p
@@ -390,11 +393,11 @@ int run(const void *a, const void *b, const void *mask, void *out,
             const float scale = P.scale;
             const int64_t ld_out = P.ldc / (out_dtype == SDROP_F32 ? 4 : 2);
             P.C = static_cast<char *>(ws);
-            P.ldc = N * 4;            // the planes of partial sums are contiguous fp32
+            P.ldc = (nk_native ? K : N) * 4;            // the planes of partial sums are contiguous fp32, [K][N] or [N][K]
             P.scale = 1.0f;
             const int rc1 = (dtype == SDROP_F16) ? dispatch_typed<F16>(OP, true, P, st) : dispatch_typed<BF16>(OP, true, P, st);
             if (rc1 != SDROP_OK) return rc1;
-            const int rc2 = launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, N, ld_out, P);
+            const int rc2 = launch_reduce(ws, out, K * N, P.splits, scale, dtype, out_dtype, st, nk_native ? K : N, ld_out, P);
             if (rc2 != SDROP_OK || !(w_nk && !nk_native)) return rc2;
             return launch_transpose(out, final_out, K, N, N, final_ld, (int)esz_out, st);
         }
