@@ -224,6 +224,25 @@ int launch_dx_pairs(const GemmParams &P, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// Persistent dX with the weight as [N,K], read in place (128 x 128 blocks, one per tile; N a multiple of 64).
+template <class T, class OutT>
+int launch_dx_nk(const GemmParams &P, hipStream_t stream)
+{
+    constexpr int P_LDS = 3 * (128 + 128) * TK * 2 + 4 * 4096;
+    auto k = gemm_persistent_dx_kernel<T, OutT, 128, 128, 2, 2, kTailNone, false, false, true>;
+    static int ok = -1;     // per instantiation: does the device grant that much LDS?
+    if (ok < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+        ok = (e == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    if (!ok) return -1;
+    const int64_t positions = (int64_t)P.MB * P.KB;
+    const int ncu = cu_count();
+    hipLaunchKernelGGL(k, dim3((unsigned)(positions < ncu ? positions : ncu)), dim3(512), P_LDS, stream, P);
+    return hip_status(hipGetLastError());
+}
+
 // Tile shapes: the tile edge that lies along the mask must equal the mask's block
 // (Section 3.2); the N edge is free (Section 3.3) and is 256 wide.  DX gathers
 // 256/BK kept blocks of one block row into a 256-wide tile.
@@ -278,6 +297,10 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         // 26.5 against 29.5 us; 16384 x 3072 x 768, a tenth dropped, 4 parts: 121 against 101 us)
         return launch<DW, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream, dw64_persistent(P));
     } else {
+        if (P.w_nk) {
+            const int rc = launch_dx_nk<T, OutT>(P, stream);
+            return rc == -1 ? SDROP_EHIP : rc;
+        }
         const DxPlan plan = dx_plan(P);
         const int TNsel = plan.TN, G_ = TNsel / P.BK;
         P.n_tiles = (P.KB + G_ - 1) / G_;

@@ -702,9 +702,14 @@ __device__ __forceinline__ int sel4(const int (&a)[4], int i)
 // (i2, j), is computed as the transposed product: W's panel j takes dY's place as the 128-row operand, the two dY
 // panels are the 256-row operand, the MFMAs take their operands the other way round and the epilogue writes the
 // two 128 x 128 results transposed.
-template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false, bool PAIRS = false>
+//
+// W_NK (one kept block of 128 x 128 per tile, no tail, whole slices): the weight is given as [N,K].  Its reduction
+// index is then the strided one, as in eq. (1): a slice of B is 64 rows of W at the block's column offset, loaded
+// and read in eq. 1's transposing form.
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN = false, bool PAIRS = false, bool W_NK = false>
 __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, const int G, const int w)
 {
+    static_assert(!W_NK || (TN == 128 && TAIL == kTailNone && !RAGN && !PAIRS), "[N,K] weights: plain single-block tiles");
     constexpr int NW = WM * WN;
     static_assert(NW == 4 && TM == 128, "one computing and one loading wavefront per SIMD, 128-row tiles");
     static_assert(!PAIRS || (TN == 256 && TAIL == kTailNone && !RAGN), "the pair list serves plain 128 x 256 tiles");
@@ -755,7 +760,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
 
     if (loader) {
         DmaK<TM, 1, NW> da;
-        DmaK<TN, DXG, NW> db;
+        typename std::conditional<W_NK, DmaT<TN, NW>, DmaK<TN, DXG, NW>>::type db;
         da.init(lda, wave);
         db.init(ldb, wave);
         constexpr int NDMA_A = TM / (8 * NW), NDMA_B = TN / (8 * NW), NDMA = NDMA_A + NDMA_B;
@@ -824,7 +829,8 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
                 for (int g = 0; g < DXG; ++g) {
                     const int bb = g >> cshift;         // a missing block repeats the last one
                     const int col = sel4(cur.c, a + (bb < nb ? bb : nb - 1));
-                    bgrp[g] = P.B + ((int64_t)col * P.BK + (g & cmask) * 64) * ldb;
+                    if constexpr (W_NK) bgrp[g] = P.B + (int64_t)col * P.BK * 2;      // columns of W[N,K] (one block per tile)
+                    else bgrp[g] = P.B + ((int64_t)col * P.BK + (g & cmask) * 64) * ldb;
                 }
                 a += nb;
                 s = 0;
@@ -852,8 +858,14 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
             if (whole) {
 #pragma unroll
                 for (int j = 0; j < NDMA_A; ++j) da.issue(sa, lda, stp, j);
+                if constexpr (W_NK) {
+                    const char *const sk[1] = {bgrp[0] + (int64_t)s * TK * ldb};      // rows [64 s, 64 s + 64) of W[N,K]
 #pragma unroll
-                for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+                    for (int j = 0; j < NDMA_B; ++j) db.issue(sk, ldb, stp + A_BYTES, j);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NDMA_B; ++j) db.issue(sb, ldb, stp + A_BYTES, j);
+                }
             }
             ++s;
             return true;
@@ -950,7 +962,7 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
         }
         return g;
     };
-    Compute<T, OutT, false, false, TM, TN, WM, WN> cw;
+    Compute<T, OutT, false, W_NK, TM, TN, WM, WN> cw;
     cw.wm = wm; cw.wn = wn;
     int st0 = 0, st1 = 1, st2 = 2;
     bool started = false;
@@ -1068,10 +1080,10 @@ __device__ __forceinline__ void gemm_persistent_dx_body(const GemmParams &P, con
     }
 }
 
-template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN, bool PAIRS = false>
+template <class T, class OutT, int TM, int TN, int WM, int WN, int TAIL, bool RAGN, bool PAIRS = false, bool W_NK = false>
 __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmParams P)
 {
-    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL, RAGN, PAIRS>(P, gridDim.x, blockIdx.x);
+    gemm_persistent_dx_body<T, OutT, TM, TN, WM, WN, TAIL, RAGN, PAIRS, W_NK>(P, gridDim.x, blockIdx.x);
 }
 
 // Both gradients of the layer in one launch (eq. 2 and eq. 3 share dY and the mask and do not

@@ -72,7 +72,13 @@ def _whole_parity(w, p, layer=0):
     bx, bw = sdrop.sdrop_bwd(dYg, Wg, Xg, m)
     torch.cuda.synchronize()
     assert torch.equal(bx, dX16) and torch.equal(bw, dW16), tag + ": sdrop_bwd differs from the separate calls"
-    del bx, bw, dW32, dW16
+    # the weight as [N,K] (read and written in place where the kernels have a form for it, else through a transposed
+    # copy): the same bits
+    Wt = Wg.t().contiguous()
+    assert torch.equal(sdrop.sdrop_fwd_ex(Xg, Wt, m, w_layout=sdrop.W_NK), sdrop.sdrop_fwd(Xg, Wg, m)), tag + ": Y with W as [N,K]"
+    assert torch.equal(sdrop.sdrop_bwd_dx_ex(dYg, Wt, m, w_layout=sdrop.W_NK), dX16), tag + ": dX with W as [N,K]"
+    assert torch.equal(sdrop.sdrop_bwd_dw_ex(Xg, dYg, m, w_layout=sdrop.W_NK), dW16.t().contiguous()), tag + ": dW as [N,K]"
+    del bx, bw, dW32, dW16, Wt
 
     # per block, dX is all +0 exactly where the oracle's mask drops the block
     keep_t = torch.from_numpy(keep.astype(bool)).cuda()
