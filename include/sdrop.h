@@ -361,9 +361,12 @@ enum { SDROP_ACT_NONE = 0, SDROP_ACT_RELU = 1, SDROP_ACT_GELU_TANH = 2, SDROP_AC
 enum { SDROP_GATE_RELU = 0, SDROP_GATE_GELU_TANH = 1, SDROP_GATE_GELU_ERF = 2 };
 /* Layout of the weight of eq. (1)-(3).  SDROP_W_KN: W[K,N] as Section 3.1 writes it.  SDROP_W_NK: Wt[N,K], one row
  * per output feature (the [out, in] layout of common frameworks): sdrop_fwd_ex and sdrop_bwd_dx_ex then take Wt as
- * their second operand (ld_b >= K), sdrop_bwd_dw_ex delivers the gradient as dWt[N,K] (ld_out >= K).  The kernels walk
- * W by rows of K, so such a weight is transposed into the workspace by a pass of its own before the product (and the
- * gradient after it): sdrop_workspace_bytes_ex gives the larger workspace these calls need. */
+ * their second operand (ld_b >= K), sdrop_bwd_dw_ex delivers the gradient as dWt[N,K] (ld_out >= K).  Without a tail
+ * the array is read (written) in place where the product's kernel has a form for it: eq. 1 when N is a multiple of
+ * 256; eq. 3 with BK = 128 when N is a multiple of 256; eq. 2 with 128 x 128 blocks when N is a multiple of 64 and the
+ * call would compute single kept blocks or pairs.  Every other call transposes the weight into the workspace by a pass
+ * of its own before the product (the gradient after it).  The results are the same bits either way, and
+ * sdrop_workspace_bytes_ex gives the (larger) workspace that covers both. */
 enum { SDROP_W_KN = 0, SDROP_W_NK = 1 };
 
 typedef struct sdrop_epilogue {

@@ -116,13 +116,13 @@ int launch_fwd_seeded(const GemmParams &P, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
-// eq. (1) with the weight as [N,K], read in place (N a multiple of 256, no tail); SEEDED: the mask drawn in the
-// same launch.  Returns -1 when the device does not grant the LDS.
-template <class T, class OutT, int TM, bool SEEDED>
+// eq. (1) with the weight as [N,K], read in place (N a multiple of 256, no tail).  Returns -1 when the device does
+// not grant the LDS.
+template <class T, class OutT, int TM>
 int launch_fwd_nk(const GemmParams &P, hipStream_t stream)
 {
     constexpr int P_LDS = 3 * (TM + 256) * TK * 2 + 4 * 4096;
-    auto k = fwd_nk_kernel<T, OutT, TM, SEEDED>;
+    auto k = fwd_nk_kernel<T, OutT, TM>;
     static int ok = -1;     // per instantiation: does the device grant that much LDS?
     if (ok < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
@@ -274,7 +274,7 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
     }
     if constexpr (OP == FWD) {
         if (P.w_nk) {
-            const int rc = P.BM == 128 ? launch_fwd_nk<T, OutT, 128, false>(P, stream) : launch_fwd_nk<T, OutT, 64, false>(P, stream);
+            const int rc = P.BM == 128 ? launch_fwd_nk<T, OutT, 128>(P, stream) : launch_fwd_nk<T, OutT, 64>(P, stream);
             return rc == -1 ? SDROP_EHIP : rc;       // (the [K,N] persistent form needs the same LDS)
         }
         P.n_tiles = (int)((P.N + 255) / 256);

@@ -80,7 +80,23 @@ def test_no_entry_point_writes_outside_its_buffers(M, K, N, BM, BK, dtype, out32
     dW2 = buf("dW of sdrop_bwd", K * N * esz).view((K, N), od)
     ws2 = buf("workspace of sdrop_bwd", max(need, 256)).body
     sdrop.sdrop_bwd(dY, W, X, m2, out_dtype=od, out_dx=dX2, out_dw=dW2, ws=ws2 if need else None)
+    # the same products with the weight as [N,K] (in place where the kernels have a form for it, else through the
+    # workspace), outputs and workspace guarded as well
+    Wt = W.t().contiguous()
+    import ctypes
+    code, ocode = sdrop._DTYPES[dtype], sdrop._DTYPES[od]
+    epi = sdrop._epilogue(sdrop.SCALE_DROPOUT, sdrop.ACT_NONE, None, None, N, (M, N), dtype, w_layout=sdrop.W_NK)
+    need_nk = max(sdrop.lib().sdrop_workspace_bytes_ex(op, M, K, N, BM, BK, code, ocode, ctypes.byref(epi))
+                  for op in (sdrop.OP_FWD, sdrop.OP_BWD_DX, sdrop.OP_BWD_DW))
+    ws3 = buf("workspace of the [N,K] calls", max(need_nk, 256)).body
+    Y3 = buf("Y, W as [N,K]", M * N * esz).view((M, N), od)
+    sdrop.sdrop_fwd_ex(X, Wt, m, out_dtype=od, out=Y3, ws=ws3, w_layout=sdrop.W_NK)
+    dX3 = buf("dX, W as [N,K]", M * K * esz).view((M, K), od)
+    sdrop.sdrop_bwd_dx_ex(dY, Wt, m, out_dtype=od, out=dX3, ws=ws3, w_layout=sdrop.W_NK)
+    dW3 = buf("dW as [N,K]", K * N * esz).view((N, K), od)
+    sdrop.sdrop_bwd_dw_ex(X, dY, m, out_dtype=od, out=dW3, ws=ws3, w_layout=sdrop.W_NK)
     torch.cuda.synchronize()
+    assert torch.equal(Y3, Y) and torch.equal(dX3, dX) and torch.equal(dW3, dW.t())
     assert sdrop.status() == 0
     for name, b in bufs.items():
         assert b.intact(), "%s: bytes outside the buffer were written" % name
