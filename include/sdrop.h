@@ -363,7 +363,8 @@ enum { SDROP_GATE_RELU = 0, SDROP_GATE_GELU_TANH = 1, SDROP_GATE_GELU_ERF = 2 };
  * per output feature (the [out, in] layout of common frameworks): sdrop_fwd_ex and sdrop_bwd_dx_ex then take Wt as
  * their second operand (ld_b >= K), sdrop_bwd_dw_ex delivers the gradient as dWt[N,K] (ld_out >= K).  Without a tail
  * the array is read (written) in place where the product's kernel has a form for it: eq. 1 when N is a multiple of
- * 256; eq. 3 with BK = 128 when N is a multiple of 256; eq. 2 with 128 x 128 blocks when N is a multiple of 64 and the
+ * 256; eq. 3 when N is a multiple of 256 (with BK = 64 only where its kept lists are long enough for the persistent
+ * kernel); eq. 2 with 128 x 128 blocks when N is a multiple of 64 and the
  * call would compute single kept blocks or pairs.  Every other call transposes the weight into the workspace by a pass
  * of its own before the product (the gradient after it).  The results are the same bits either way, and
  * sdrop_workspace_bytes_ex gives the (larger) workspace that covers both. */

@@ -139,12 +139,12 @@ int launch_fwd_nk(const GemmParams &P, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
-// eq. (3) with the gradient written as [N,K] (128-row tiles, N a multiple of 256; P.splits parts).
-template <class T, class OutT>
+// eq. (3) with the gradient written as [N,K] (tiles of TM = BK rows, N a multiple of 256; P.splits parts).
+template <class T, class OutT, int TM>
 int launch_dw_nk(const GemmParams &P, hipStream_t stream)
 {
-    constexpr int P_LDS = 3 * (128 + 256) * TK * 2 + 4 * 4096;
-    auto k = dw_nk_kernel<T, OutT, 128>;
+    constexpr int P_LDS = 3 * (TM + 256) * TK * 2 + 4 * 4096;
+    auto k = dw_nk_kernel<T, OutT, TM>;
     static int ok = -1;     // per instantiation: does the device grant that much LDS?
     if (ok < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
@@ -284,7 +284,7 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
         return launch<FWD, T, OutT, 64, 256, 1, 4>(P, grid, ragged, stream);
     } else if constexpr (OP == DW) {
         if (P.w_nk) {
-            const int rc = launch_dw_nk<T, OutT>(P, stream);
+            const int rc = P.BK == 128 ? launch_dw_nk<T, OutT, 128>(P, stream) : launch_dw_nk<T, OutT, 64>(P, stream);
             return rc == -1 ? SDROP_EHIP : rc;
         }
         P.n_tiles = (int)((P.N + 255) / 256);

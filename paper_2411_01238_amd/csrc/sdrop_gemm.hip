@@ -239,13 +239,13 @@ DxPlan dx_plan(const GemmParams &P, bool fused)
 }
 
 // Which calls read a weight given as [N,K] in place instead of through a transposed copy: eq. (1) on whole 256-wide
-// tile columns (its persistent kernel loads W's rows the way eq. 2 loads its operands), and eq. (3) with 128-wide
-// blocks on whole tile columns (its persistent kernel writes its tiles transposed), and eq. (2) with 128 x 128 blocks
+// tile columns (its persistent kernel loads W's rows the way eq. 2 loads its operands), and eq. (3) on whole tile
+// columns where it runs its persistent kernel (which writes its tiles transposed), and eq. (2) with 128 x 128 blocks
 // and whole slices (its persistent kernel on single-block tiles loads W's rows the way eq. 1 does).
 bool w_nk_native(int op, int64_t N, int BM, int BK)
 {
     if (op == FWD) return N % 256 == 0;
-    if (op == DW) return N % 256 == 0 && BK == 128;       // (its persistent kernel's 128-row tiles, written transposed)
+    if (op == DW) return N % 256 == 0;                    // (its persistent kernel's tiles, written transposed; see run)
     if (op == DX) return N % 64 == 0 && BM == 128 && BK == 128;     // (its persistent kernel, one kept block per tile)
     return false;
 }
@@ -360,6 +360,13 @@ int run(const void *a, const void *b, const void *mask, void *out,
     // ... unless the call is one whose kernel has a form that reads (writes) the [N,K] array in place
     const bool has_tail_args = epi && (epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask);
     bool nk_native = w_nk && !out2 && !has_tail_args && w_nk_native(OP, N, BM, BK);
+    if (OP == DW && nk_native && BK == 64) {
+        // 64-row tiles: only where the call takes the persistent kernel (see dw64_persistent)
+        GemmParams Q = base_params(OP, a, b, mask, out, M, K, N, BM, BK, p, out_dtype, L);
+        if (epi->kept_fraction > 0.0) Q.p = 1.0 - (epi->kept_fraction < 1.0 ? epi->kept_fraction : 1.0);
+        Q.splits = dw_splits(M, N, BM, BK, K);
+        nk_native = dw64_persistent(Q);
+    }
     if (OP == DX && nk_native) {
         // eq. 2's in-place form computes one kept block per tile.  Where the [K,N] plan would take 256-wide tiles of
         // one block row (many tiles per CU: 65536 x 4096 x 1024, 431 us through the transposed copy against 450 in
