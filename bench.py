@@ -28,11 +28,11 @@ MFMA_WITH_LDS_READS_CEILING_TFLOPS = 1390.0
 # benchmark's launches, scaled by a known 1 GiB copy.  Constants from the tracked counter summaries named
 # here, NOT measured by this run (counters need the profiler).
 TRAFFIC_BYTES = {
-    ("square4096", 0.5): {"fwd": 235.7e6, "bwd": 581.4e6, "source": "profiles/bench_square4096_p0.5.md"},
+    ("square4096", 0.5): {"fwd": 235.6e6, "bwd": 581.2e6, "source": "profiles/bench_square4096_p0.5.md"},
     ("mlp", 0.5): {"fwd": 58.2e6, "bwd": 127.9e6, "source": "profiles/bench_mlp_p0.5.md"},
-    ("mlp", 0.1): {"fwd": 85.1e6, "bwd": 135.7e6, "source": "profiles/bench_mlp_p0.1.md"},
-    ("ffn_down", 0.1): {"fwd": 373.0e6, "bwd": 663.1e6, "source": "profiles/bench_ffn_down_p0.1.md"},
-    ("skinny", 0.3): {"fwd": 1780.8e6, "bwd": 4918.8e6, "source": "profiles/bench_skinny_p0.3.md"},
+    ("mlp", 0.1): {"fwd": 85.1e6, "bwd": 135.6e6, "source": "profiles/bench_mlp_p0.1.md"},
+    ("ffn_down", 0.1): {"fwd": 372.9e6, "bwd": 671.7e6, "source": "profiles/bench_ffn_down_p0.1.md"},
+    ("skinny", 0.3): {"fwd": 1781.5e6, "bwd": 4891.2e6, "source": "profiles/bench_skinny_p0.3.md"},
 }
 
 
