@@ -222,3 +222,18 @@ def test_a_single_kept_block():
     torch.cuda.synchronize()
     assert_tight(f64(got), orc.bwd_dx(f64(dY), f64(W), keep, 128, 128, 0.5), "dX of a single kept block")
     assert m.n_units() == 1
+
+
+def test_pair_list_of_random_bits():
+    """Random grids and densities (rows of every parity, empty rows and columns, both words of a lane's two rows)."""
+    rng = np.random.default_rng(20241128)
+    for case in range(48):
+        MB = int(rng.integers(1, 129))
+        KB = int(rng.integers(1, 65))
+        density = float(rng.choice([0.05, 0.2, 0.5, 0.8, 0.97]))
+        keep = (rng.random((MB, KB)) < density).astype(np.uint8)
+        if case % 6 == 0:
+            keep[rng.integers(0, MB)] = 0                    # an empty row
+            keep[:, rng.integers(0, KB)] = 0                 # an empty column
+        print("pair list of random bits", case, MB, KB, density, flush=True)
+        _check_units(_mask_of(keep, 0.5), keep)
