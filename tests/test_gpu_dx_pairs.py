@@ -237,3 +237,19 @@ def test_pair_list_of_random_bits():
             keep[:, rng.integers(0, KB)] = 0                 # an empty column
         print("pair list of random bits", case, MB, KB, density, flush=True)
         _check_units(_mask_of(keep, 0.5), keep)
+
+
+def test_dx_on_pairs_of_random_bits():
+    rng = np.random.default_rng(7)
+    for case in range(8):
+        MB, KB = int(rng.integers(1, 21)), int(rng.integers(1, 21))
+        keep = (rng.random((MB, KB)) < float(rng.choice([0.2, 0.5, 0.9]))).astype(np.uint8)
+        print("dX on pairs of random bits", case, MB, KB, int(keep.sum()), flush=True)
+        dY, W, X, keep, m = _dx_case(MB * 128, KB * 128, 64, 0.5, torch.bfloat16, keep=keep, seed=case)
+        sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 1)
+        got = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=torch.float32)
+        sdrop.set_tuning(sdrop.TUNE_DX_PAIRS, 2)
+        plain = sdrop.sdrop_bwd_dx(dY.cuda(), W.cuda(), m, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert_tight(f64(got), orc.bwd_dx(f64(dY), f64(W), keep, 128, 128, 0.5), "dX on pairs of random bits %d" % case)
+        assert torch.equal(got, plain)
