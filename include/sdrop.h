@@ -308,11 +308,14 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  * sdrop_bwd for row-strided matrices: the leading dimensions, in elements, of dY[M,N], W[K,N], X[M,K], dX[M,K] and
  * dW[K,N] (0 = contiguous; else at least the number of columns, a multiple of 8, at most 2^24, else SDROP_ESHAPE).
  * Same launches and results as sdrop_bwd on contiguous copies; nothing outside the column ranges is written.
+ * w_layout = SDROP_W_NK: W is given and dW delivered as [N,K] (ld_w, ld_dw >= K); the call is then sdrop_bwd_dx_ex
+ * followed by sdrop_bwd_dw_ex with that layout (each in place where its kernel has a form for it), and the workspace
+ * is that of sdrop_bwd_dw_ex with that layout (sdrop_workspace_bytes_ex(SDROP_OP_BWD_DW, ...)).
  */
 int sdrop_bwd_ex(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,
                  int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
-                 int64_t ld_dy, int64_t ld_w, int64_t ld_x, int64_t ld_dx, int64_t ld_dw);
+                 int64_t ld_dy, int64_t ld_w, int64_t ld_x, int64_t ld_dx, int64_t ld_dw, int w_layout);
 
 /*
  * Sparse operators for the layers around the dropout (Section 4.3, closing remark: the layer
@@ -397,6 +400,19 @@ int sdrop_bwd_dw_ex(const void *X, const void *dY, const void *mask, void *dW,
                     int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
                     int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
                     const sdrop_epilogue_t *epi);
+
+/*
+ * sdrop_fwd_seeded for row-strided matrices and for a weight given as [N,K]: of `epi` only w_layout, ld_a (X), ld_b (W)
+ * and ld_out (Y) may be set (anything else: SDROP_EINVAL; epi = NULL: exactly sdrop_fwd_seeded).  ws, ws_bytes as for
+ * sdrop_fwd_ex with the same epi (sdrop_workspace_bytes_ex(SDROP_OP_FWD, ...): nothing for [K,N] weights).  The mask
+ * is drawn in the forward's launch on the same grids as in sdrop_fwd_seeded; an [N,K] weight is then read in place
+ * when N is a multiple of 256, else the call is sdrop_mask followed by sdrop_fwd_ex.  Same bits as those two calls.
+ */
+int sdrop_fwd_seeded_ex(const void *X, const void *W, void *mask, size_t mask_bytes, void *Y,
+                        int64_t M, int64_t K, int64_t N, int BM, int BK, double p, uint64_t seed, uint64_t rng_stream,
+                        int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                        const sdrop_epilogue_t *epi);
+
 
 /*
  * The layer before the dropout as an output-sparse product: only the blocks of X that the

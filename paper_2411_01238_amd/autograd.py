@@ -12,31 +12,36 @@ from . import sdrop
 
 class _SparseDropMatmul(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, w, p, BM, BK, seed, rng_stream):
+    def forward(ctx, x, w, p, BM, BK, seed, rng_stream, w_layout):
         # the mask and eq. (1) in one call (one launch for block grids up to 128 x 64); m serves the backward
-        y, m = sdrop.sdrop_fwd_seeded(x, w, BM, BK, p, seed, rng_stream)
+        y, m = sdrop.sdrop_fwd_seeded(x, w, BM, BK, p, seed, rng_stream, w_layout=w_layout)
         ctx.save_for_backward(x, w)
         ctx.mask = m
+        ctx.w_layout = w_layout
         return y
 
     @staticmethod
     def backward(ctx, dy):
         x, w = ctx.saved_tensors
         dy = dy.contiguous()
+        wl = ctx.w_layout
         if ctx.needs_input_grad[0] and ctx.needs_input_grad[1]:
-            dx, dw = sdrop.sdrop_bwd(dy, w, x, ctx.mask)      # both gradients, one launch where the shapes allow it
+            dx, dw = sdrop.sdrop_bwd(dy, w, x, ctx.mask, w_layout=wl)      # both gradients, one launch where the shapes allow it
         else:
-            dx = sdrop.sdrop_bwd_dx(dy, w, ctx.mask) if ctx.needs_input_grad[0] else None
-            dw = sdrop.sdrop_bwd_dw(x, dy, ctx.mask) if ctx.needs_input_grad[1] else None
-        return dx, dw, None, None, None, None, None
+            dx = sdrop.sdrop_bwd_dx_ex(dy, w, ctx.mask, w_layout=wl) if ctx.needs_input_grad[0] else None
+            dw = sdrop.sdrop_bwd_dw_ex(x, dy, ctx.mask, w_layout=wl) if ctx.needs_input_grad[1] else None
+        return dx, dw, None, None, None, None, None, None
 
 
-def sparsedrop_matmul(x, w, p, BM=128, BK=128, seed=0, rng_stream=0):
+def sparsedrop_matmul(x, w, p, BM=128, BK=128, seed=0, rng_stream=0, weight_layout="kn"):
     """y = (x . m') w / (1 - p) with a fresh block mask m' (Bernoulli(1-p) per BM x BK block of x).
 
-    x [M, K] and w [K, N] are contiguous fp16 / bf16 GPU tensors; M % BM == 0, K % BK == 0, N % 8 == 0.
+    x [M, K] and w [K, N] are fp16 / bf16 GPU tensors with contiguous rows; M % BM == 0, K % BK == 0, N % 8 == 0.
+    weight_layout="nk": w is [N, K], one row per output feature (the layout of torch.nn.Linear's weight), and so is
+    its gradient.
     """
-    return _SparseDropMatmul.apply(x, w, float(p), int(BM), int(BK), int(seed), int(rng_stream))
+    wl = {"kn": sdrop.W_KN, "nk": sdrop.W_NK}[weight_layout]
+    return _SparseDropMatmul.apply(x, w, float(p), int(BM), int(BK), int(seed), int(rng_stream), wl)
 
 
 _ACTS = {"relu": (sdrop.ACT_RELU, sdrop.GATE_RELU), "gelu_tanh": (sdrop.ACT_GELU_TANH, sdrop.GATE_GELU_TANH),
@@ -110,14 +115,20 @@ def sparse_relu_block(h, w0, b0, w, p, BM=128, BK=128, seed=0, rng_stream=0):
 class SparseDropLinear(torch.nn.Module):
     """Dropout(p) followed by Linear(K -> N), with the dropout block-structured and fused into the
     layer's three GEMMs (the layer substitution of Section 4).  The weight is stored [K, N] as in
-    Section 3.1.  In eval mode nothing is dropped (p = 0: all blocks kept, scale 1)."""
+    Section 3.1, or, with weight_layout="nk", [N, K] like torch.nn.Linear's (a state dict of such a layer then loads
+    as it is).  In eval mode nothing is dropped (p = 0: all blocks kept, scale 1)."""
 
     def __init__(self, in_features, out_features, p=0.5, BM=128, BK=128, bias=True, seed=0,
-                 dtype=torch.bfloat16, device="cuda"):
+                 dtype=torch.bfloat16, device="cuda", weight_layout="kn"):
         super().__init__()
         self.p, self.BM, self.BK, self.seed = float(p), int(BM), int(BK), int(seed)
+        if weight_layout not in ("kn", "nk"):
+            raise ValueError("weight_layout is 'kn' or 'nk'")
+        self.weight_layout = weight_layout
         w = torch.empty(in_features, out_features, dtype=torch.float32)
         torch.nn.init.kaiming_uniform_(w.t(), a=5 ** 0.5)
+        if weight_layout == "nk":
+            w = w.t().contiguous()
         self.weight = torch.nn.Parameter(w.to(dtype=dtype, device=device))
         self.bias = torch.nn.Parameter(torch.zeros(out_features, dtype=dtype, device=device)) if bias else None
         self.calls = 0          # the mask's rng_stream: a new mask every forward call
@@ -126,7 +137,7 @@ class SparseDropLinear(torch.nn.Module):
         lead = x.shape[:-1]
         x2 = x.reshape(-1, x.shape[-1]).contiguous()
         p = self.p if self.training else 0.0
-        y = sparsedrop_matmul(x2, self.weight, p, self.BM, self.BK, self.seed, self.calls)
+        y = sparsedrop_matmul(x2, self.weight, p, self.BM, self.BK, self.seed, self.calls, self.weight_layout)
         if self.training:
             self.calls += 1
         if self.bias is not None:

@@ -116,13 +116,13 @@ int launch_fwd_seeded(const GemmParams &P, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
-// eq. (1) with the weight as [N,K], read in place (N a multiple of 256, no tail).  Returns -1 when the device does
-// not grant the LDS.
-template <class T, class OutT, int TM>
+// eq. (1) with the weight as [N,K], read in place (N a multiple of 256, no tail); SEEDED: the mask drawn in the same
+// launch (block grids of at most 128 x 64).  Returns -1 when the device does not grant the LDS.
+template <class T, class OutT, int TM, bool SEEDED = false>
 int launch_fwd_nk(const GemmParams &P, hipStream_t stream)
 {
     constexpr int P_LDS = 3 * (TM + 256) * TK * 2 + 4 * 4096;
-    auto k = fwd_nk_kernel<T, OutT, TM>;
+    auto k = fwd_nk_kernel<T, OutT, TM, SEEDED>;
     static int ok = -1;     // per instantiation: does the device grant that much LDS?
     if (ok < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
@@ -403,6 +403,10 @@ template <class T> int dispatch_typed(int op, bool o32, GemmParams &P, hipStream
 template <class T> int fwd_seeded_typed(bool o32, const GemmParams &P, hipStream_t stream)
 {
     using O16 = typename In<T>::out16;
+    if (P.w_nk) {
+        if (P.BM == 128) return o32 ? launch_fwd_nk<T, float, 128, true>(P, stream) : launch_fwd_nk<T, O16, 128, true>(P, stream);
+        return o32 ? launch_fwd_nk<T, float, 64, true>(P, stream) : launch_fwd_nk<T, O16, 64, true>(P, stream);
+    }
     if (P.BM == 128) return o32 ? launch_fwd_seeded<T, float, 128>(P, stream) : launch_fwd_seeded<T, O16, 128>(P, stream);
     return o32 ? launch_fwd_seeded<T, float, 64>(P, stream) : launch_fwd_seeded<T, O16, 64>(P, stream);
 }

@@ -660,11 +660,11 @@ __global__ __launch_bounds__(512) void dw_nk_kernel(GemmParams P)
     gemm_persistent_body<DW, T, OutT, TM, 256, 1, 4, kTailNone, false, false, true>(P, gridDim.x, blockIdx.x);
 }
 
-// eq. (1) with the weight as [N,K] (see W_NK above).
-template <class T, class OutT, int TM>
+// eq. (1) with the weight as [N,K] (see W_NK above); SEEDED: it draws its own mask as well.
+template <class T, class OutT, int TM, bool SEEDED>
 __global__ __launch_bounds__(512) void fwd_nk_kernel(GemmParams P)
 {
-    gemm_persistent_body<FWD, T, OutT, TM, 256, 1, 4, kTailNone, false, false, true>(P, gridDim.x, blockIdx.x);
+    gemm_persistent_body<FWD, T, OutT, TM, 256, 1, 4, kTailNone, false, SEEDED, true>(P, gridDim.x, blockIdx.x);
 }
 
 // The forward kernel that draws its own mask and writes the mask object as well (see SEEDED above).

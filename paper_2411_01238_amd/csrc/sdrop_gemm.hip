@@ -448,9 +448,10 @@ bool fwd_seeded_applies(const sdrop_mask_layout_t &L)
     return g_fwd_seeded && L.MB <= 128 && L.KB <= 64;
 }
 
+// epi: null, or the weight layout and the leading dimensions of X, W and Y (nothing else of it may be set)
 int run_fwd_seeded(const void *x, const void *w, void *mask, size_t mask_bytes, void *y,
                    int64_t M, int64_t K, int64_t N, int BM, int BK, double p, uint64_t seed, uint64_t rng_stream,
-                   int dtype, int out_dtype, void *stream)
+                   int dtype, int out_dtype, void *stream, const sdrop_epilogue_t *epi = nullptr, void *ws = nullptr, size_t ws_bytes = 0)
 {
     // every argument check of both calls before anything is enqueued
     const int rc = check_gemm_args(x, w, mask, y, M, K, N, BM, BK, p, dtype, out_dtype);
@@ -459,8 +460,27 @@ int run_fwd_seeded(const void *x, const void *w, void *mask, size_t mask_bytes, 
     sdrop_mask_layout(M, K, BM, BK, &L);
     if (mask_bytes < L.total_bytes) return SDROP_EWORKSPACE;
     if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
-    if (fwd_seeded_applies(L)) {
+    const bool w_nk = epi && epi->w_layout == SDROP_W_NK;
+    if (epi) {
+        if (epi->w_layout != SDROP_W_KN && epi->w_layout != SDROP_W_NK) return SDROP_EINVAL;
+        if (epi->scale_mode != SDROP_SCALE_DROPOUT || epi->act != SDROP_ACT_NONE || epi->bias || epi->relu_mask ||
+            epi->kept_fraction != 0.0) return SDROP_EINVAL;
+        const int64_t lds[3] = {epi->ld_a, epi->ld_b, epi->ld_out}, cols[3] = {K, w_nk ? K : N, N};
+        for (int i = 0; i < 3; ++i)
+            if (lds[i] != 0 && (lds[i] < cols[i] || lds[i] % 8 || lds[i] > (int64_t(1) << 24))) return SDROP_ESHAPE;
+        // the workspace of sdrop_fwd_ex with the same layout (used where the [N,K] weight goes through a transposed copy)
+        const size_t need = ws_total_bytes(FWD, M, K, N, BM, BK, out_dtype, w_nk);
+        if (ws_bytes < need || (need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
+    }
+    if (fwd_seeded_applies(L) && (!w_nk || w_nk_native(FWD, N, BM, BK))) {
         GemmParams P = base_params(FWD, x, w, mask, y, M, K, N, BM, BK, p, out_dtype, L);
+        if (epi) {
+            if (epi->ld_a) P.lda = epi->ld_a * 2;
+            if (epi->ld_b) P.ldb = epi->ld_b * 2;
+            else if (w_nk) P.ldb = K * 2;
+            if (epi->ld_out) P.ldc = epi->ld_out * (out_dtype == SDROP_F32 ? 4 : 2);
+            P.w_nk = w_nk;
+        }
         P.key0 = (uint32_t)seed; P.key1 = (uint32_t)(seed >> 32);
         P.ctr2 = (uint32_t)rng_stream; P.ctr3 = (uint32_t)(rng_stream >> 32);
         P.threshold = (uint64_t)floor(p * 4294967296.0);
@@ -471,7 +491,7 @@ int run_fwd_seeded(const void *x, const void *w, void *mask, size_t mask_bytes, 
     }
     const int rm = sdrop_mask(mask, mask_bytes, M, K, BM, BK, p, seed, rng_stream, stream);
     if (rm != SDROP_OK) return rm;
-    return run<FWD>(x, w, mask, y, M, K, N, BM, BK, p, dtype, out_dtype, nullptr, 0, stream);
+    return run<FWD>(x, w, mask, y, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, epi);
 }
 
 // both gradients in one launch where bwd_fused_kernel or bwd_fused_tile_kernel applies (128 x 128
@@ -479,14 +499,36 @@ int run_fwd_seeded(const void *x, const void *w, void *mask, size_t mask_bytes, 
 int g_bwd_fused = 1;
 
 // ld: null (contiguous), or the leading dimensions of dY, W, X, dX, dW in elements (0 = contiguous)
+// w_layout = SDROP_W_NK: W is given, and dW wanted, as [N,K] (ld[1], ld[4] then count rows of K elements): the two
+// products are launched in turn, each in place where its kernel has a form for it (see run).
 int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void *dx, void *dw,
             int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
-            int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream, const int64_t *ld = nullptr)
+            int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream, const int64_t *ld = nullptr,
+            int w_layout = SDROP_W_KN)
 {
     // every argument check of both calls before anything is enqueued
     int rc = check_gemm_args(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype);
     if (rc == SDROP_OK) rc = check_gemm_args(x, dy, mask, dw, M, K, N, BM, BK, p, dtype, out_dtype);
     if (rc != SDROP_OK) return rc;
+    if (w_layout != SDROP_W_KN && w_layout != SDROP_W_NK) return SDROP_EINVAL;
+    if (w_layout == SDROP_W_NK) {
+        sdrop_epilogue_t e;
+        e.scale_mode = SDROP_SCALE_DROPOUT; e.act = SDROP_ACT_NONE; e.bias = nullptr; e.relu_mask = nullptr;
+        e.gate_mode = SDROP_GATE_RELU; e.w_layout = SDROP_W_NK; e.kept_fraction = 0.0;
+        // the workspace of the larger of the two calls (eq. 3's: its planes and the transposed copy), checked first
+        if (ld)
+            for (int i = 0; i < 5; ++i) {
+                const int64_t cols = (i == 0) ? N : K;     // dY has N columns; W[N,K], X, dX and dW[N,K] have K
+                if (ld[i] != 0 && (ld[i] < cols || ld[i] % 8 || ld[i] > (int64_t(1) << 24))) return SDROP_ESHAPE;
+            }
+        const size_t need = ws_total_bytes(DW, M, K, N, BM, BK, out_dtype, true);
+        if (ws_bytes < need || (need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
+        e.ld_a = ld ? ld[0] : 0; e.ld_b = ld ? ld[1] : 0; e.ld_out = ld ? ld[3] : 0;
+        rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, &e);
+        if (rc != SDROP_OK) return rc;
+        e.ld_a = ld ? ld[2] : 0; e.ld_b = ld ? ld[0] : 0; e.ld_out = ld ? ld[4] : 0;
+        return run<DW>(x, dy, mask, dw, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, &e);
+    }
     int64_t lds[5] = {N, N, K, K, N};                    // dY[M,N], W[K,N], X[M,K], dX[M,K], dW[K,N]
     if (ld) {
         for (int i = 0; i < 5; ++i) {
@@ -689,6 +731,14 @@ int sdrop_fwd_seeded(const void *X, const void *W, void *mask, size_t mask_bytes
     return sdrop::run_fwd_seeded(X, W, mask, mask_bytes, Y, M, K, N, BM, BK, p, seed, rng_stream, dtype, out_dtype, stream);
 }
 
+int sdrop_fwd_seeded_ex(const void *X, const void *W, void *mask, size_t mask_bytes, void *Y,
+                        int64_t M, int64_t K, int64_t N, int BM, int BK, double p, uint64_t seed, uint64_t rng_stream,
+                        int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream, const sdrop_epilogue_t *epi)
+{
+    return sdrop::run_fwd_seeded(X, W, mask, mask_bytes, Y, M, K, N, BM, BK, p, seed, rng_stream, dtype, out_dtype, stream,
+                                 epi, ws, ws_bytes);
+}
+
 int sdrop_bwd_dx(const void *dY, const void *W, const void *mask, void *dX,
                  int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream)
@@ -730,10 +780,10 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
 int sdrop_bwd_ex(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,
                  int64_t M, int64_t K, int64_t N, int BM, int BK, double p,
                  int dtype, int out_dtype, void *ws, size_t ws_bytes, void *stream,
-                 int64_t ld_dy, int64_t ld_w, int64_t ld_x, int64_t ld_dx, int64_t ld_dw)
+                 int64_t ld_dy, int64_t ld_w, int64_t ld_x, int64_t ld_dx, int64_t ld_dw, int w_layout)
 {
     const int64_t ld[5] = {ld_dy, ld_w, ld_x, ld_dx, ld_dw};
-    return sdrop::run_bwd(dY, W, X, mask, dX, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, ld);
+    return sdrop::run_bwd(dY, W, X, mask, dX, dW, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, ld, w_layout);
 }
 
 int sdrop_fwd_ex(const void *X, const void *W, const void *mask, void *Y,

@@ -24,7 +24,7 @@ MASK_NUNITS_OFFSET = 80
 
 EXPORTS = ("sdrop_strerror", "sdrop_last_hip_error", "sdrop_status", "sdrop_set_tuning", "sdrop_mask_layout", "sdrop_mask_bytes",
            "sdrop_mask", "sdrop_mask_split", "sdrop_mask_from_bits", "sdrop_mask_bits", "sdrop_workspace_bytes",
-           "sdrop_fwd", "sdrop_fwd_seeded", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
+           "sdrop_fwd", "sdrop_fwd_seeded", "sdrop_fwd_seeded_ex", "sdrop_bwd_dx", "sdrop_bwd_dw", "sdrop_bwd_dw_static",
            "sdrop_bwd", "sdrop_bwd_ex", "sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex", "sdrop_workspace_bytes_ex",
            "sdrop_producer", "sdrop_producer_ex",
            "sdrop_bias_grad_workspace_bytes", "sdrop_bias_grad")
@@ -99,6 +99,9 @@ def lib():
             f.restype = ci
         L.sdrop_fwd_seeded.argtypes = [vp, vp, vp, sz, vp, i64, i64, i64, ci, ci, dbl, u64, u64, ci, ci, vp]
         L.sdrop_fwd_seeded.restype = ci
+        L.sdrop_fwd_seeded_ex.argtypes = [vp, vp, vp, sz, vp, i64, i64, i64, ci, ci, dbl, u64, u64, ci, ci, vp, sz, vp,
+                                          ctypes.POINTER(Epilogue)]
+        L.sdrop_fwd_seeded_ex.restype = ci
         L.sdrop_bwd_dw_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp]
         L.sdrop_bwd_dw_static.restype = ci
         for name in ("sdrop_fwd_ex", "sdrop_bwd_dx_ex", "sdrop_bwd_dw_ex"):
@@ -107,7 +110,7 @@ def lib():
             f.restype = ci
         L.sdrop_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp]
         L.sdrop_bwd.restype = ci
-        L.sdrop_bwd_ex.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp, i64, i64, i64, i64, i64]
+        L.sdrop_bwd_ex.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, dbl, ci, ci, vp, sz, vp, i64, i64, i64, i64, i64, ci]
         L.sdrop_bwd_ex.restype = ci
         L.sdrop_workspace_bytes_ex.argtypes = [ci, i64, i64, i64, ci, ci, ci, ci, ctypes.POINTER(Epilogue)]
         L.sdrop_workspace_bytes_ex.restype = sz
@@ -368,11 +371,12 @@ def sdrop_fwd(X, W, mask, out_dtype=None, out=None, ws=None):
     return _gemm("sdrop_fwd", OP_FWD, X, W, mask, (M, N), M, K, N, out_dtype, out, ws)
 
 
-def sdrop_fwd_seeded(X, W, BM, BK, p, seed, rng_stream=0, mask=None, out_dtype=None, out=None):
+def sdrop_fwd_seeded(X, W, BM, BK, p, seed, rng_stream=0, mask=None, out_dtype=None, out=None, w_layout=W_KN, ws=None):
     """The step's mask and eq. (1) in one call (one launch for small block grids): returns (Y, Mask).
-    The Mask is the object sdrop_mask would have written; the backward calls of the step take it."""
+    The Mask is the object sdrop_mask would have written; the backward calls of the step take it.
+    w_layout=W_NK: W is given as [N, K].  Row-strided X, W or out (column ranges of wider matrices) are taken in place."""
     M, K = X.shape
-    K2, N = W.shape
+    K2, N = W.shape if w_layout == W_KN else (W.shape[1], W.shape[0])
     if K2 != K:
         raise SdropError(ESHAPE, "sdrop_fwd_seeded")
     dtype = X.dtype
@@ -387,9 +391,22 @@ def sdrop_fwd_seeded(X, W, BM, BK, p, seed, rng_stream=0, mask=None, out_dtype=N
         out = torch.empty((M, N), dtype=out_dtype, device=X.device)
     elif tuple(out.shape) != (M, N) or out.dtype != out_dtype:
         raise ValueError("out has the wrong shape or dtype")
-    rc = lib().sdrop_fwd_seeded(_dev(X, "X"), _dev(W, "W"), _dev(m.buf, "mask"), m.buf.numel(), _dev(out, "Y"),
-                                M, K, N, BM, BK, float(p), int(seed), int(rng_stream),
-                                _DTYPES[dtype], _DTYPES[out_dtype], _stream())
+    (xp, ldx), (wp, ldw), (yp, ldy) = _mat(X, "X"), _mat(W, "W"), _mat(out, "Y")
+    if w_layout == W_KN and (ldx, ldw, ldy) == (K, N, N):
+        rc = lib().sdrop_fwd_seeded(xp, wp, _dev(m.buf, "mask"), m.buf.numel(), yp,
+                                    M, K, N, BM, BK, float(p), int(seed), int(rng_stream),
+                                    _DTYPES[dtype], _DTYPES[out_dtype], _stream())
+    else:
+        e = _epilogue(SCALE_DROPOUT, ACT_NONE, None, None, N, (M, N), dtype, w_layout=w_layout)
+        e.ld_a, e.ld_b, e.ld_out = ldx, ldw, ldy
+        need = int(lib().sdrop_workspace_bytes_ex(OP_FWD, M, K, N, BM, BK, _DTYPES[dtype], _DTYPES[out_dtype], ctypes.byref(e)))
+        if ws is None and need:
+            ws = torch.empty(need, dtype=torch.uint8, device=X.device)
+        ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
+        ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+        rc = lib().sdrop_fwd_seeded_ex(xp, wp, _dev(m.buf, "mask"), m.buf.numel(), yp,
+                                       M, K, N, BM, BK, float(p), int(seed), int(rng_stream),
+                                       _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream(), ctypes.byref(e))
     _check(rc, "sdrop_fwd_seeded")
     return out, m
 
@@ -434,10 +451,11 @@ def sdrop_bwd_dw_static(X, dY, mask, out, out_dtype=None):
     return out
 
 
-def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None):
-    """eq. (2) and eq. (3) in one call (one launch where the shapes allow it): returns (dX, dW)."""
+def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None, w_layout=W_KN):
+    """eq. (2) and eq. (3) in one call (one launch where the shapes allow it): returns (dX, dW).
+    w_layout=W_NK: W is given, and dW returned, as [N, K]."""
     M, N = dY.shape
-    K, N2 = W.shape
+    K, N2 = W.shape if w_layout == W_KN else (W.shape[1], W.shape[0])
     if N2 != N or tuple(X.shape) != (M, K) or (M, K) != (mask.M, mask.K):
         raise SdropError(ESHAPE, "sdrop_bwd")
     dtype = dY.dtype
@@ -447,13 +465,17 @@ def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None)
     if dtype not in (torch.float16, torch.bfloat16) or out_dtype not in _DTYPES:
         raise SdropError(EDTYPE, "sdrop_bwd")
     outs = []
-    for o, shape in ((out_dx, (M, K)), (out_dw, (K, N))):
+    for o, shape in ((out_dx, (M, K)), (out_dw, (K, N) if w_layout == W_KN else (N, K))):
         if o is None:
             o = torch.empty(shape, dtype=out_dtype, device=dY.device)
         elif tuple(o.shape) != shape or o.dtype != out_dtype:
             raise ValueError("an output has the wrong shape or dtype")
         outs.append(o)
-    need = workspace_bytes(OP_BWD_DW, M, K, N, mask.BM, mask.BK, dtype, out_dtype)
+    if w_layout == W_KN:
+        need = workspace_bytes(OP_BWD_DW, M, K, N, mask.BM, mask.BK, dtype, out_dtype)
+    else:
+        e = _epilogue(SCALE_DROPOUT, ACT_NONE, None, None, N, (K, N), dtype, w_layout=w_layout)
+        need = int(lib().sdrop_workspace_bytes_ex(OP_BWD_DW, M, K, N, mask.BM, mask.BK, _DTYPES[dtype], _DTYPES[out_dtype], ctypes.byref(e)))
     if ws is None and need:
         ws = torch.empty(need, dtype=torch.uint8, device=dY.device)
     ws_ptr = ctypes.c_void_p(ws.data_ptr()) if ws is not None else ctypes.c_void_p(0)
@@ -461,13 +483,13 @@ def sdrop_bwd(dY, W, X, mask, out_dtype=None, out_dx=None, out_dw=None, ws=None)
     mats = [_mat(t, n) for t, n in ((dY, "dY"), (W, "W"), (X, "X"), (outs[0], "dX"), (outs[1], "dW"))]
     ptrs = [m[0] for m in mats]
     lds = [m[1] for m in mats]
-    if lds == [N, N, K, K, N]:
+    if w_layout == W_KN and lds == [N, N, K, K, N]:
         rc = lib().sdrop_bwd(ptrs[0], ptrs[1], ptrs[2], _dev(mask.buf, "mask"), ptrs[3], ptrs[4], M, K, N, mask.BM, mask.BK, mask.p,
                              _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream())
     else:
         # row-strided operands or outputs (column ranges of wider matrices)
         rc = lib().sdrop_bwd_ex(ptrs[0], ptrs[1], ptrs[2], _dev(mask.buf, "mask"), ptrs[3], ptrs[4], M, K, N, mask.BM, mask.BK, mask.p,
-                                _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream(), *lds)
+                                _DTYPES[dtype], _DTYPES[out_dtype], ws_ptr, ws_bytes, _stream(), *lds, int(w_layout))
     _check(rc, "sdrop_bwd")
     return outs[0], outs[1]
 

@@ -252,10 +252,13 @@ def test_new_entry_points_check_their_arguments_on_the_host():
     null = ctypes.c_void_p(0)
     # sdrop_bwd_ex: leading dimensions of dY, W, X, dX, dW
     ok = (p, p, p, p, p, p, 2048, 256, 264, 64, 64, 0.5, sdrop.F16, sdrop.F16, null, 0, null)
-    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, 0) == sdrop.EWORKSPACE          # as sdrop_bwd: the split needs a workspace
-    assert L.sdrop_bwd_ex(*ok, 256, 0, 0, 0, 0) == sdrop.ESHAPE            # dY has 264 columns
-    assert L.sdrop_bwd_ex(*ok, 0, 0, 260, 0, 0) == sdrop.ESHAPE            # not a multiple of 8
-    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, (1 << 24) + 8) == sdrop.ESHAPE
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, 0, sdrop.W_KN) == sdrop.EWORKSPACE          # as sdrop_bwd: the split needs a workspace
+    assert L.sdrop_bwd_ex(*ok, 256, 0, 0, 0, 0, sdrop.W_KN) == sdrop.ESHAPE            # dY has 264 columns
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 260, 0, 0, sdrop.W_KN) == sdrop.ESHAPE            # not a multiple of 8
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, (1 << 24) + 8, sdrop.W_KN) == sdrop.ESHAPE
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, 0, 5) == sdrop.EINVAL                       # no such layout
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, 0, sdrop.W_NK) == sdrop.EWORKSPACE
+    assert L.sdrop_bwd_ex(*ok, 0, 0, 0, 0, 128, sdrop.W_NK) == sdrop.ESHAPE            # dW[N,K] has 256 columns
     # sdrop_producer_ex
     okp = (p, p, null, p, p, null, 256, 256, 256, 64, 64, 0.5, sdrop.ACT_RELU, sdrop.F16, sdrop.F16, null)
     assert L.sdrop_producer_ex(*okp, 128, 0, 0) == sdrop.ESHAPE
@@ -280,6 +283,16 @@ def test_new_entry_points_check_their_arguments_on_the_host():
     assert L.sdrop_fwd_seeded(*(oks[:3] + (64,) + oks[4:])) == sdrop.EWORKSPACE
     assert L.sdrop_fwd_seeded(*(oks[:10] + (1.5,) + oks[11:])) == sdrop.EINVAL
     assert L.sdrop_fwd_seeded(*(oks[:7] + (250,) + oks[8:])) == sdrop.ESHAPE
+    # sdrop_fwd_seeded_ex: the layout and the leading dimensions only
+    okx = oks[:15] + (null, 0, null)
+    e2 = sdrop.Epilogue()
+    e2.scale_mode, e2.act, e2.gate_mode, e2.w_layout = 0, 0, 0, sdrop.W_NK
+    assert L.sdrop_fwd_seeded_ex(*okx, ctypes.byref(e2)) == sdrop.EWORKSPACE               # room for the transposed copy
+    e2.w_layout, e2.act = sdrop.W_KN, sdrop.ACT_RELU
+    assert L.sdrop_fwd_seeded_ex(*okx, ctypes.byref(e2)) == sdrop.EINVAL                   # no tail in this call
+    e2.act, e2.ld_a = sdrop.ACT_NONE, 128
+    assert L.sdrop_fwd_seeded_ex(*okx, ctypes.byref(e2)) == sdrop.ESHAPE                   # X has 256 columns
+    assert L.sdrop_fwd_seeded_ex(*(okx[:2] + (null,) + okx[3:]), None) == sdrop.EINVAL
     assert L.sdrop_status(None, 0, None) == sdrop.EINVAL
     # sdrop_bwd_dw_static: argument errors as sdrop_bwd_dw
     okd = (p, p, p, p, 256, 256, 256, 64, 64, 0.5, sdrop.F16, sdrop.F16, null)

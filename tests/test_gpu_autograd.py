@@ -28,6 +28,37 @@ def test_function_matches_oracle_forward_and_gradients():
     assert_close(f64(w.grad), orc.bwd_dw(Xd, dYd, keep, BM, BK, p), "autograd dW")
 
 
+@pytest.mark.parametrize("N", [256, 136])        # the weight read in place / through a transposed copy
+def test_function_with_the_weight_as_out_in(N):
+    M, K, BM, BK, p, seed, stream = 512, 384, 128, 128, 0.4, 5, 2
+    X, W, dY = make_custom(M, K, N, "bf16", seed=4)
+    x = X.cuda().requires_grad_(True)
+    wt = W.t().contiguous().cuda().requires_grad_(True)          # [N, K]
+    y = sparsedrop_matmul(x, wt, p, BM, BK, seed, stream, weight_layout="nk")
+    y.backward(dY.cuda())
+    x2 = X.cuda().requires_grad_(True)
+    w2 = W.cuda().requires_grad_(True)
+    y2 = sparsedrop_matmul(x2, w2, p, BM, BK, seed, stream)
+    y2.backward(dY.cuda())
+    torch.cuda.synchronize()
+    assert tuple(wt.grad.shape) == (N, K)
+    assert torch.equal(y, y2) and torch.equal(x.grad, x2.grad) and torch.equal(wt.grad, w2.grad.t())
+    keep = orc.mask(M // BM, K // BK, p, seed, stream)
+    ref = orc.bwd_dw_wt(f64(X), f64(dY), keep, BM, BK, p)
+    got = f64(wt.grad)
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -7 * np.max(np.abs(ref))          # a bf16 output: its rounding only
+
+
+def test_module_with_a_linear_layers_state():
+    lin = torch.nn.Linear(256, 384, bias=True).to(device="cuda", dtype=torch.bfloat16)
+    layer = SparseDropLinear(256, 384, p=0.5, BM=128, BK=128, bias=True, seed=1, weight_layout="nk")
+    layer.load_state_dict(lin.state_dict())              # same parameter names and shapes
+    layer.eval()
+    x = torch.randn(256, 256, device="cuda", dtype=torch.bfloat16)
+    ref = f64(x) @ f64(lin.weight.detach()).T + f64(lin.bias.detach())
+    assert_close(f64(layer(x).detach()), ref, "module in eval mode = the linear layer", rel_fro=5e-3, max_abs=2e-2)
+
+
 def test_module_train_and_eval():
     torch.manual_seed(0)
     layer = SparseDropLinear(256, 128, p=0.5, BM=64, BK=64, bias=True, seed=9, dtype=torch.float16)

@@ -185,6 +185,22 @@ def test_weight_in_out_in_layout(M, K, N, BM, BK, dtype, p, seed):
         sdrop.sdrop_bwd_dw_ex(Xg, dYg, m, out_dtype=out_dtype, out=out, w_layout=sdrop.W_NK)
         torch.cuda.synchronize()
         assert torch.equal(out, dWt) and _guards_ok(wide, 16, K)
+        # the calls that fuse steps, with the same layout: the mask drawn in the forward's launch, both gradients in one call
+        Ys, ms = sdrop.sdrop_fwd_seeded(Xg, Wtg, BM, BK, p, seed, 0, out_dtype=out_dtype, w_layout=sdrop.W_NK)
+        bx, bwt = sdrop.sdrop_bwd(dYg, Wtg, Xg, ms, out_dtype=out_dtype, w_layout=sdrop.W_NK)
+        torch.cuda.synchronize()
+        assert torch.equal(Ys, Y) and torch.equal(ms.buf[:256], m.buf[:256]) and torch.equal(ms.bits(), m.bits())
+        assert torch.equal(bx, dX) and torch.equal(bwt, dWt)
+        Ys2, _ = sdrop.sdrop_fwd_seeded(Xg, Wtv, BM, BK, p, seed, 0, out_dtype=out_dtype, w_layout=sdrop.W_NK)
+        wide, out = _inside(torch.empty((N, K), dtype=out_dtype), 16, 24, fill=False)
+        bx2, _ = sdrop.sdrop_bwd(dYg, Wtv, Xg, m, out_dtype=out_dtype, out_dw=out, w_layout=sdrop.W_NK)
+        torch.cuda.synchronize()
+        assert torch.equal(Ys2, Y) and torch.equal(bx2, dX) and torch.equal(out, dWt) and _guards_ok(wide, 16, K)
+        # and the seeded forward on a column range of a wider X with the [K,N] weight
+        _, Xv = _inside(X, 8, 8)
+        Ys3, _ = sdrop.sdrop_fwd_seeded(Xv, Wg, BM, BK, p, seed, 0, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        assert torch.equal(Ys3, Y)
     # a workspace sized for the [K,N] call is too small for the [N,K] one
     L = sdrop.lib()
     import ctypes
