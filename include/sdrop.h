@@ -308,8 +308,9 @@ int sdrop_bwd(const void *dY, const void *W, const void *X, const void *mask, vo
  * sdrop_bwd for row-strided matrices: the leading dimensions, in elements, of dY[M,N], W[K,N], X[M,K], dX[M,K] and
  * dW[K,N] (0 = contiguous; else at least the number of columns, a multiple of 8, at most 2^24, else SDROP_ESHAPE).
  * Same launches and results as sdrop_bwd on contiguous copies; nothing outside the column ranges is written.
- * w_layout = SDROP_W_NK: W is given and dW delivered as [N,K] (ld_w, ld_dw >= K); the call is then sdrop_bwd_dx_ex
- * followed by sdrop_bwd_dw_ex with that layout (each in place where its kernel has a form for it), and the workspace
+ * w_layout = SDROP_W_NK: W is given and dW delivered as [N,K] (ld_w, ld_dw >= K): one launch where both products
+ * read and write the arrays in place (128 x 128 blocks, N a multiple of 256, eq. 2 on single blocks), else
+ * sdrop_bwd_dx_ex followed by sdrop_bwd_dw_ex with that layout; the same bits as those two calls, and the workspace
  * is that of sdrop_bwd_dw_ex with that layout (sdrop_workspace_bytes_ex(SDROP_OP_BWD_DW, ...)).
  */
 int sdrop_bwd_ex(const void *dY, const void *W, const void *X, const void *mask, void *dX, void *dW,

@@ -46,6 +46,8 @@ bool dw64_persistent(const GemmParams &P);
 enum BwdForm { kBwdNone = 0, kBwdPersistent, kBwdTile128, kBwdTile64 };
 // the tile width argument of bwd_fused_typed that stands for 256-wide tiles from the pair list
 constexpr int kTNPairs = 257;
+// ... and the one for single-block tiles with the weight read, and its gradient written, as [N,K]
+constexpr int kTNNK = 129;
 
 // One of the three products for operands of type T: picks tile shapes and kernel form, launches.
 // o32: fp32 output instead of the operands' type.

@@ -325,12 +325,12 @@ int dispatch_tile(GemmParams &P, hipStream_t stream)
     }
 }
 
-template <class T, class OutDX, class OutDW, int TN_DX, bool PAIRS = false>
+template <class T, class OutDX, class OutDW, int TN_DX, bool PAIRS = false, bool W_NK = false>
 int launch_bwd_fused(const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
 {
     constexpr int LDS_DX = 3 * (128 + TN_DX) * TK * 2 + 4 * 4096, LDS_DW = 3 * (128 + 256) * TK * 2 + 4 * 4096;
     constexpr int P_LDS = LDS_DX > LDS_DW ? LDS_DX : LDS_DW;
-    auto k = bwd_fused_kernel<T, OutDX, OutDW, TN_DX, PAIRS>;
+    auto k = bwd_fused_kernel<T, OutDX, OutDW, TN_DX, PAIRS, W_NK>;
     static int ok = -1;     // per instantiation: does the device grant that much LDS?
     if (ok < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
@@ -369,6 +369,7 @@ template <class T, class OutDX, class OutDW>
 int launch_bwd_fused_tn(int TN, const GemmParams &Pdx, const GemmParams &Pdw, hipStream_t stream)
 {
     if (TN == kTNPairs) return launch_bwd_fused<T, OutDX, OutDW, 256, true>(Pdx, Pdw, stream);
+    if (TN == kTNNK) return launch_bwd_fused<T, OutDX, OutDW, 128, false, true>(Pdx, Pdw, stream);
     if (TN == 256) return launch_bwd_fused<T, OutDX, OutDW, 256>(Pdx, Pdw, stream);
     return launch_bwd_fused<T, OutDX, OutDW, 128>(Pdx, Pdw, stream);
 }

@@ -1092,13 +1092,14 @@ __global__ __launch_bounds__(WM * WN * 128) void gemm_persistent_dx_kernel(GemmP
 // workgroups leave: no launch boundary (about 5 us of idle chip between dependent launches) and no
 // idle tail between the two.  The dX workgroups come first, so dX workgroup w is workgroup w of
 // the launch and runs on XCD w % 8, which its schedule assumes; the dW schedule assumes nothing.
-template <class T, class OutDX, class OutDW, int TN_DX, bool PAIRS = false>
+// (W_NK: the weight is given and its gradient wanted as [N,K]; both bodies in their in-place forms.)
+template <class T, class OutDX, class OutDW, int TN_DX, bool PAIRS = false, bool W_NK = false>
 __global__ __launch_bounds__(512) void bwd_fused_kernel(GemmParams Pdx, GemmParams Pdw, int g_dx)
 {
     if ((int)blockIdx.x < g_dx)
-        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, kTailNone, false, PAIRS>(Pdx, g_dx, (int)blockIdx.x);
+        gemm_persistent_dx_body<T, OutDX, 128, TN_DX, 2, 2, kTailNone, false, PAIRS, W_NK>(Pdx, g_dx, (int)blockIdx.x);
     else
-        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, kTailNone>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
+        gemm_persistent_body<DW, T, OutDW, 128, 256, 1, 4, kTailNone, false, false, W_NK>(Pdw, (int)gridDim.x - g_dx, (int)blockIdx.x - g_dx);
 }
 
 // The same where dX runs one workgroup per tile (tiles of two kept blocks that are too few per CU

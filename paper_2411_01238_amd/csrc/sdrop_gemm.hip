@@ -523,6 +523,38 @@ int run_bwd(const void *dy, const void *w, const void *x, const void *mask, void
             }
         const size_t need = ws_total_bytes(DW, M, K, N, BM, BK, out_dtype, true);
         if (ws_bytes < need || (need && (!ws || reinterpret_cast<uintptr_t>(ws) % 16))) return SDROP_EWORKSPACE;
+        // One launch where both products have their in-place forms (128 x 128 blocks, whole tile columns, eq. 2 on
+        // single-block tiles or where its [K,N] plan takes the pair list): the persistent bodies as in bwd_fused_kernel.
+        if (g_bwd_fused && BM == 128 && BK == 128 && N % 256 == 0) {
+            sdrop_mask_layout_t L;
+            sdrop_mask_layout(M, K, BM, BK, &L);
+            if (!tile_count_ok(N, L)) return SDROP_ESHAPE;
+            GemmParams Pdx = base_params(DX, dy, w, mask, dx, M, K, N, BM, BK, p, out_dtype, L);
+            GemmParams Pdw = base_params(DW, x, dy, mask, dw, M, K, N, BM, BK, p, out_dtype, L);
+            const DxPlan plan = dx_plan(Pdx);
+            if (plan.TN == 128 || plan.pairs) {
+                const int64_t esz_out = out_dtype == SDROP_F32 ? 4 : 2;
+                const int64_t l0 = ld && ld[0] ? ld[0] : N, l1 = ld && ld[1] ? ld[1] : K, l2 = ld && ld[2] ? ld[2] : K;
+                const int64_t l3 = ld && ld[3] ? ld[3] : K, l4 = ld && ld[4] ? ld[4] : K;
+                Pdx.lda = l0 * 2; Pdx.ldb = l1 * 2; Pdx.ldc = l3 * esz_out;
+                Pdw.lda = l2 * 2; Pdw.ldb = l0 * 2; Pdw.ldc = l4 * esz_out;
+                Pdx.w_nk = Pdw.w_nk = true;
+                Pdw.splits = dw_splits(M, N, BM, BK, K);
+                Pdw.n_tiles = (int)(N / 256);
+                Pdw.total_tiles = Pdw.KB * Pdw.n_tiles * Pdw.splits;
+                const float scale = Pdw.scale;
+                const bool split = Pdw.splits > 1;
+                if (split) { Pdw.C = static_cast<char *>(ws); Pdw.ldc = K * 4; Pdw.scale = 1.0f; }
+                hipStream_t st = static_cast<hipStream_t>(stream);
+                const bool o32 = out_dtype == SDROP_F32;
+                const int rf = dtype == SDROP_F16 ? bwd_fused_typed<F16>(kBwdPersistent, kTNNK, o32, split, Pdx, Pdw, 0, st)
+                                                  : bwd_fused_typed<BF16>(kBwdPersistent, kTNNK, o32, split, Pdx, Pdw, 0, st);
+                if (rf != -1) {     // -1: the device does not grant the LDS; the two calls then
+                    if (rf != SDROP_OK || !split) return rf;
+                    return launch_reduce(ws, dw, K * N, Pdw.splits, scale, dtype, out_dtype, st, K, l4, Pdw);
+                }
+            }
+        }
         e.ld_a = ld ? ld[0] : 0; e.ld_b = ld ? ld[1] : 0; e.ld_out = ld ? ld[3] : 0;
         rc = run<DX>(dy, w, mask, dx, M, K, N, BM, BK, p, dtype, out_dtype, ws, ws_bytes, stream, &e);
         if (rc != SDROP_OK) return rc;
